@@ -1,0 +1,22 @@
+"""CPU oracle for the level-batched Child-Sum Tree-LSTM forward.
+
+TEST INFRASTRUCTURE ONLY.  Nothing here is part of the product: only the test
+suite, the smoke check and the benchmark's CPU-baseline leg may import it.  It
+shares no code with the HIP library and never imports it.
+
+Contents
+  schedule_oracle.py   heights / level buckets / permutation / child CSR, plus
+                       an independent brute-force height routine for tiny trees
+  treelstm_oracle.py   node-by-node postorder evaluation in fp64 (numpy)
+  treelstm_oracle.c    the same definition in plain C (fp64), one tree at a
+                       time; used where the numpy version is too slow
+  build.py             compiles the C file with gcc
+
+Pins (tests/test_oracle_*.py): brute-force heights, chain / star / perfect
+k-ary closed forms, stable-argsort CSR, leaf closed form, chain == library
+LSTM, star with U_f = 0 == library LSTM cell on summed child states, saturated
+forget gates select children by the sign of their own h, zero-weight closed
+form c = i*u*subtree_size, relabelling and forest-vs-single-tree invariance,
+numpy oracle vs C oracle.  Launch-count tables of the paper (Table 1, Table 2)
+need its dataset: parity unpinned, nothing here reproduces them.
+"""

@@ -1,0 +1,168 @@
+"""Schedule oracle: what the batching analysis must produce for a forest.
+
+The paper files every computation node in a table keyed by its depth in the
+computation graph; nodes of one depth are independent and run as one batch, and
+slots are visited in depth order (section 4.2, section 4.3).  For a tree
+evaluated bottom-up that depth is the node's HEIGHT: 0 for a leaf, otherwise
+1 + the largest height among its children.
+
+The paper does not fix an order inside a slot or among children.  The reading
+used here, needed for a bit-exact contract: ascending node id in both.
+
+Test infrastructure only; plain Python/numpy, no code shared with the GPU path.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+class ForestError(ValueError):
+    def __init__(self, kind: str, msg: str):
+        super().__init__(msg)
+        self.kind = kind   # "range" | "cycle"
+
+
+def validate(parent) -> None:
+    """Every parent is -1 or a node id other than the node itself, and walking
+    parents from any node reaches -1 within N steps."""
+    parent = np.asarray(parent)
+    n = parent.shape[0]
+    for v in range(n):
+        p = int(parent[v])
+        if p < -1 or p >= n or p == v:
+            raise ForestError("range", f"parent[{v}] = {p} is not a valid parent")
+    # state: 0 unknown, 1 on current walk, 2 known to reach a root
+    state = np.zeros(n, dtype=np.int8)
+    for v in range(n):
+        path = []
+        w = v
+        while w != -1 and state[w] == 0:
+            state[w] = 1
+            path.append(w)
+            w = int(parent[w])
+        if w != -1 and state[w] == 1:
+            raise ForestError("cycle", f"node {w} is its own ancestor")
+        for q in path:
+            state[q] = 2
+
+
+def children_lists(parent):
+    """children[j] = ids v with parent[v] == j, ascending."""
+    parent = np.asarray(parent)
+    n = parent.shape[0]
+    ch = [[] for _ in range(n)]
+    for v in range(n):          # ascending v => ascending lists
+        p = int(parent[v])
+        if p >= 0:
+            ch[p].append(v)
+    return ch
+
+
+def heights(parent) -> np.ndarray:
+    """height[v] = 0 for a leaf, else 1 + max over children (iterative postorder)."""
+    parent = np.asarray(parent)
+    n = parent.shape[0]
+    ch = children_lists(parent)
+    h = np.zeros(n, dtype=np.int32)
+    for r in range(n):
+        if parent[r] != -1:
+            continue
+        stack = [(r, 0)]
+        while stack:
+            v, i = stack.pop()
+            if i < len(ch[v]):
+                stack.append((v, i + 1))
+                stack.append((ch[v][i], 0))
+            else:
+                h[v] = 0 if not ch[v] else 1 + max(int(h[k]) for k in ch[v])
+    return h
+
+
+def heights_bruteforce(parent) -> np.ndarray:
+    """Independent twin: height[j] = the largest number of parent steps that
+    lead from some node v up to j.  O(N * depth); for tiny forests."""
+    parent = np.asarray(parent)
+    n = parent.shape[0]
+    h = np.zeros(n, dtype=np.int32)
+    for v in range(n):
+        steps = 0
+        w = int(parent[v])
+        while w != -1:
+            steps += 1
+            if steps > h[w]:
+                h[w] = steps
+            w = int(parent[w])
+    return h
+
+
+def schedule(parent) -> dict:
+    """Full schedule of a forest.
+
+    Returns a dict of int32 arrays:
+      height[N], level_ptr[L+1], perm[N] (position -> id, sorted by (height, id)),
+      inv_perm[N] (id -> position), child_ptr[N+1], child_idx[E]
+    and ints n_levels (L), n_edges (E = N - number of roots).
+    """
+    parent = np.asarray(parent)
+    n = parent.shape[0]
+    validate(parent)
+    ch = children_lists(parent)
+    child_ptr = np.zeros(n + 1, dtype=np.int32)
+    for j in range(n):
+        child_ptr[j + 1] = child_ptr[j] + len(ch[j])
+    child_idx = np.array([k for j in range(n) for k in ch[j]], dtype=np.int32)
+    h = heights(parent)
+    L = int(h.max()) + 1 if n else 0
+    order = sorted(range(n), key=lambda v: (int(h[v]), v))
+    perm = np.array(order, dtype=np.int32)
+    inv_perm = np.zeros(n, dtype=np.int32)
+    for pos, v in enumerate(order):
+        inv_perm[v] = pos
+    level_ptr = np.zeros(L + 1, dtype=np.int32)
+    for lvl in range(L + 1):
+        level_ptr[lvl] = int(np.count_nonzero(h < lvl))
+    return dict(height=h, level_ptr=level_ptr, perm=perm, inv_perm=inv_perm,
+                child_ptr=child_ptr, child_idx=child_idx,
+                n_levels=L, n_edges=int(child_ptr[n]))
+
+
+def schedule_fast(parent) -> dict:
+    """Same outputs as `schedule` for large forests, using numpy routines
+    (stable argsort, bincount) and a level-by-level height sweep.  Checked
+    against `schedule` in the CPU tests; used where `schedule` is too slow."""
+    parent = np.asarray(parent).astype(np.int64)
+    n = parent.shape[0]
+    if n == 0:
+        z = np.zeros(0, dtype=np.int32)
+        return dict(height=z, level_ptr=np.zeros(1, np.int32), perm=z, inv_perm=z,
+                    child_ptr=np.zeros(1, np.int32), child_idx=z, n_levels=0, n_edges=0)
+    if ((parent < -1) | (parent >= n) | (parent == np.arange(n))).any():
+        raise ForestError("range", "invalid parent")
+    nonroot = np.flatnonzero(parent >= 0)
+    cnt = np.bincount(parent[nonroot], minlength=n)
+    child_ptr = np.concatenate(([0], np.cumsum(cnt))).astype(np.int32)
+    child_idx = nonroot[np.argsort(parent[nonroot], kind="stable")].astype(np.int32)
+    # peel leaves upward: a node's height is final once all children reported
+    h = np.zeros(n, dtype=np.int64)
+    remaining = cnt.copy()
+    frontier = np.flatnonzero(cnt == 0)
+    done = 0
+    while frontier.size:
+        done += frontier.size
+        p = parent[frontier]
+        ok = p >= 0
+        p = p[ok]
+        np.maximum.at(h, p, h[frontier[ok]] + 1)
+        np.subtract.at(remaining, p, 1)
+        up = np.unique(p)
+        frontier = up[remaining[up] == 0]
+    if done != n:
+        raise ForestError("cycle", "some node never becomes ready: cycle")
+    L = int(h.max()) + 1
+    perm = np.lexsort((np.arange(n), h)).astype(np.int32)
+    inv_perm = np.empty(n, dtype=np.int32)
+    inv_perm[perm] = np.arange(n, dtype=np.int32)
+    level_ptr = np.concatenate(([0], np.cumsum(np.bincount(h, minlength=L)))).astype(np.int32)
+    return dict(height=h.astype(np.int32), level_ptr=level_ptr, perm=perm,
+                inv_perm=inv_perm, child_ptr=child_ptr, child_idx=child_idx,
+                n_levels=L, n_edges=int(child_ptr[n]))
