@@ -1,0 +1,153 @@
+/*
+ * jitdb - level-batched Child-Sum Tree-LSTM forward for MI355X (gfx950).
+ *
+ * C ABI of the data-parallel hot path of "Just-in-Time Dynamic-Batching"
+ * (arXiv 1904.07421).  The paper collects the computation graphs of a batch of
+ * samples, files every node in a look-up table by its depth in the computation
+ * graph (section 4.2), and then visits the table in depth order, running all
+ * nodes of one slot as a single batched launch: stack, execute, slice
+ * (section 4.3).  Here the samples are trees, the node type is one Tree-LSTM
+ * cell (section 3), and the two calls are the two halves of that method:
+ *
+ *   jitdb_schedule           the analysis: depth table, slot order, child lists
+ *   jitdb_treelstm_forward   the execution: one batched cell evaluation per depth
+ *
+ * Conventions
+ *   - Every function returns JITDB_OK (0) or a negative jitdb_status.  Nothing
+ *     throws, exits or prints.
+ *   - "dev" pointers are device (HBM) memory of the current HIP device, owned
+ *     by the caller; "host" pointers are ordinary host memory.  The library
+ *     allocates nothing: scratch comes from caller-supplied workspaces whose
+ *     sizes the *_workspace_bytes queries return.  Workspaces must be 256-byte
+ *     aligned.  Nothing is retained after a call returns except what was
+ *     written into caller buffers.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - A forest is ONE parent array over global node ids 0..N-1; parent -1 marks
+ *     a root.  Ids are arbitrary: parent[v] < v is NOT required and trees need
+ *     not be contiguous.
+ */
+#ifndef JITDB_H
+#define JITDB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    JITDB_OK = 0,
+    JITDB_E_NULL = -1,         /* a required pointer is NULL */
+    JITDB_E_BADARG = -2,       /* size, dimension, dtype or alignment out of range */
+    JITDB_E_PARENT_RANGE = -3, /* some parent[v] is < -1, >= N, or == v */
+    JITDB_E_CYCLE = -4,        /* some node never reaches a root */
+    JITDB_E_WORKSPACE = -5,    /* workspace smaller than the matching *_workspace_bytes */
+    JITDB_E_HIP = -6,          /* a HIP runtime call failed */
+    JITDB_E_SCHEDULE = -7      /* forward was handed a schedule that is not complete */
+} jitdb_status;
+
+typedef enum {
+    JITDB_F32 = 0,  /* x, W, U, h in fp32; fp32 MFMA */
+    JITDB_BF16 = 1  /* x, W, U, h in bfloat16; bf16 MFMA with fp32 accumulate; b, c in fp32 */
+} jitdb_dtype;
+
+/* Largest forest one call accepts (ids and offsets are int32 with headroom). */
+#define JITDB_MAX_NODES (1 << 28)
+
+/*
+ * The schedule of a forest: the paper's depth-keyed table (section 4.2),
+ * specialised to one node type, in flat arrays.
+ *
+ * "Depth" is the depth in the COMPUTATION graph: a node can run once all its
+ * inputs (its children) have run, so depth = height in the tree, 0 for leaves,
+ * 1 + max over children otherwise.  Nodes of equal height are independent and
+ * form one level batch.  The order inside a slot and among children, which the
+ * paper leaves open, is fixed as ascending node id so that the result is unique.
+ *
+ * The caller fills n_nodes and all pointers before jitdb_schedule; the call
+ * fills the arrays, n_levels and n_edges.
+ */
+typedef struct {
+    int64_t n_nodes;         /* in: N, 0 <= N <= JITDB_MAX_NODES */
+    int32_t *height;         /* dev [N]   out: height of every node */
+    int32_t *level_ptr;      /* dev [N+1] out: entries 0..n_levels valid; level l = positions
+                                          [level_ptr[l], level_ptr[l+1]) */
+    int32_t *perm;           /* dev [N]   out: position -> node id, sorted by (height, id) */
+    int32_t *inv_perm;       /* dev [N]   out: node id -> position */
+    int32_t *child_ptr;      /* dev [N+1] out: children of node j are child_idx[child_ptr[j] .. child_ptr[j+1]) */
+    int32_t *child_idx;      /* dev [N]   out: entries 0..n_edges valid, child ids ascending per parent */
+    int32_t *host_level_ptr; /* host [N+1] out: copy of level_ptr[0..n_levels]; the forward sizes
+                                          its per-level launches from it */
+    int32_t n_levels;        /* out: L = 1 + max height (0 if N == 0) */
+    int64_t n_edges;         /* out: E = N - number of roots */
+} jitdb_schedule_t;
+
+/* Bytes of device workspace jitdb_schedule needs for a forest of n_nodes (0 if n_nodes is invalid). */
+size_t jitdb_schedule_workspace_bytes(int64_t n_nodes);
+
+/*
+ * Analysis step (section 4.2: organise the nodes by depth; section 4.3: nodes
+ * that can be batched together share a slot).
+ *
+ *   parent  dev [N] int32, -1 = root.
+ *   s       in/out, see jitdb_schedule_t.
+ *
+ * Runs on `hip_stream` and synchronises that stream twice (to learn the number
+ * of levels, then to hand back level_ptr).  On JITDB_E_PARENT_RANGE or
+ * JITDB_E_CYCLE the output arrays hold unspecified values; no kernel reads or
+ * writes out of bounds for any input.  N == 0 succeeds with n_levels = 0.
+ * The schedule depends only on `parent` and may be reused for any number of
+ * forward calls (the paper's cached graph rewrite, section 4.3).
+ */
+int jitdb_schedule(const int32_t *parent, jitdb_schedule_t *s,
+                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Bytes of device workspace jitdb_treelstm_forward needs (0 if an argument is invalid). */
+size_t jitdb_treelstm_workspace_bytes(int64_t n_nodes, int64_t n_edges,
+                                      int32_t D, int32_t H, jitdb_dtype dtype);
+
+/*
+ * Execution step (section 4.3: per slot, stack the samples on the batch axis,
+ * run the common subgraph once, slice the outputs back), for the Child-Sum
+ * Tree-LSTM cell the paper analyses in section 3 (33 operators, 4 of which
+ * depend on the number of children).  For node j with children C(j):
+ *
+ *     hs  = sum_{k in C(j)} h_k
+ *     i   = sigmoid(W_i x_j + U_i hs + b_i)      o = sigmoid(W_o x_j + U_o hs + b_o)
+ *     u   = tanh   (W_u x_j + U_u hs + b_u)
+ *     f_k = sigmoid(W_f x_j + U_f h_k + b_f)     (one per child, from that child's h)
+ *     c_j = i*u + sum_k f_k*c_k                  h_j = o*tanh(c_j)
+ *
+ *   x      dev [N, D] row-major, row = node id.          dtype elements
+ *   W      dev [4H, D] row-major, gate rows i, o, u, f.  dtype elements
+ *   U      dev [4H, H] row-major, same gate order.       dtype elements
+ *   b      dev [4H] fp32 (both dtypes).
+ *   s      a schedule produced by jitdb_schedule for the same forest.
+ *   h_out  dev [N, H] row-major, row = node id.          dtype elements
+ *   c_out  dev [N, H] row-major, row = node id.          fp32 (both dtypes)
+ *
+ * D >= 1 with D % 4 == 0, H >= 1 (any H; rows are padded internally).  With
+ * JITDB_BF16, h is rounded to bfloat16 (nearest even) when stored and that
+ * rounded value feeds the parents; sums, gates and c stay fp32.
+ *
+ * Fully asynchronous on `hip_stream`: level sizes come from s->host_level_ptr,
+ * no device-to-host copy or synchronisation happens.  Levels run in order on
+ * that one stream.  N == 0 succeeds and launches nothing.
+ */
+int jitdb_treelstm_forward(const void *x, const void *W, const void *U, const float *b,
+                           int32_t D, int32_t H, jitdb_dtype dtype,
+                           const jitdb_schedule_t *s,
+                           void *h_out, float *c_out,
+                           void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Static, NUL-terminated description of a status code. */
+const char *jitdb_strerror(int code);
+
+/* Library version, "major.minor". */
+const char *jitdb_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* JITDB_H */

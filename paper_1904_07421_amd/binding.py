@@ -1,0 +1,203 @@
+"""ctypes binding of the C ABI in include/jitdb.h.
+
+PyTorch supplies device memory and the HIP stream; nothing is computed here.
+The shared library must have been built (paper_1904_07421_amd/build.py); if it
+is missing the binding builds it once, and if that fails every call raises.
+There is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libjitdb.so")
+
+JITDB_F32 = 0
+JITDB_BF16 = 1
+
+_c_i32p = ctypes.POINTER(ctypes.c_int32)
+
+
+class JitdbError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"jitdb error {code}: {msg}")
+        self.code = code
+
+
+class _ScheduleStruct(ctypes.Structure):
+    _fields_ = [
+        ("n_nodes", ctypes.c_int64),
+        ("height", ctypes.c_void_p),
+        ("level_ptr", ctypes.c_void_p),
+        ("perm", ctypes.c_void_p),
+        ("inv_perm", ctypes.c_void_p),
+        ("child_ptr", ctypes.c_void_p),
+        ("child_idx", ctypes.c_void_p),
+        ("host_level_ptr", ctypes.c_void_p),
+        ("n_levels", ctypes.c_int32),
+        ("n_edges", ctypes.c_int64),
+    ]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libjitdb.so (building it first only if no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from .build import build
+        build()
+    lib = ctypes.CDLL(_LIB_PATH)
+    lib.jitdb_schedule_workspace_bytes.restype = ctypes.c_size_t
+    lib.jitdb_schedule_workspace_bytes.argtypes = [ctypes.c_int64]
+    lib.jitdb_schedule.restype = ctypes.c_int
+    lib.jitdb_schedule.argtypes = [ctypes.c_void_p, ctypes.POINTER(_ScheduleStruct),
+                                   ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.jitdb_treelstm_workspace_bytes.restype = ctypes.c_size_t
+    lib.jitdb_treelstm_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
+                                                   ctypes.c_int32, ctypes.c_int]
+    lib.jitdb_treelstm_forward.restype = ctypes.c_int
+    lib.jitdb_treelstm_forward.argtypes = [
+        ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+        ctypes.c_int32, ctypes.c_int32, ctypes.c_int,
+        ctypes.POINTER(_ScheduleStruct), ctypes.c_void_p, ctypes.c_void_p,
+        ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.jitdb_strerror.restype = ctypes.c_char_p
+    lib.jitdb_strerror.argtypes = [ctypes.c_int]
+    lib.jitdb_version.restype = ctypes.c_char_p
+    lib.jitdb_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+def jitdb_strerror(code: int) -> str:
+    return load_library().jitdb_strerror(int(code)).decode()
+
+
+def jitdb_version() -> str:
+    return load_library().jitdb_version().decode()
+
+
+def jitdb_schedule_workspace_bytes(n_nodes: int) -> int:
+    return int(load_library().jitdb_schedule_workspace_bytes(int(n_nodes)))
+
+
+def jitdb_treelstm_workspace_bytes(n_nodes: int, n_edges: int, D: int, H: int, dtype: int) -> int:
+    return int(load_library().jitdb_treelstm_workspace_bytes(int(n_nodes), int(n_edges),
+                                                             int(D), int(H), int(dtype)))
+
+
+def _check(code: int):
+    if code != 0:
+        raise JitdbError(code, jitdb_strerror(code))
+
+
+def _stream_ptr(stream) -> int:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+class Schedule:
+    """Device arrays of one forest's schedule plus the C struct that points at them."""
+
+    def __init__(self, n_nodes: int, device):
+        import torch
+        n = int(n_nodes)
+        i32 = dict(dtype=torch.int32, device=device)
+        self.n_nodes = n
+        self.height = torch.empty(max(n, 1), **i32)
+        self.level_ptr = torch.empty(n + 1, **i32)
+        self.perm = torch.empty(max(n, 1), **i32)
+        self.inv_perm = torch.empty(max(n, 1), **i32)
+        self.child_ptr = torch.empty(n + 1, **i32)
+        self.child_idx = torch.empty(max(n, 1), **i32)
+        self.host_level_ptr = np.zeros(n + 1, dtype=np.int32)
+        self.n_levels = 0
+        self.n_edges = 0
+        self.struct = _ScheduleStruct(
+            n, self.height.data_ptr(), self.level_ptr.data_ptr(), self.perm.data_ptr(),
+            self.inv_perm.data_ptr(), self.child_ptr.data_ptr(), self.child_idx.data_ptr(),
+            self.host_level_ptr.ctypes.data, 0, 0)
+
+    def to_numpy(self) -> dict:
+        """Host copies trimmed to their valid lengths (for comparison in tests)."""
+        n, L, E = self.n_nodes, self.n_levels, self.n_edges
+        return dict(
+            height=self.height[:n].cpu().numpy(),
+            level_ptr=self.level_ptr[:L + 1].cpu().numpy(),
+            perm=self.perm[:n].cpu().numpy(),
+            inv_perm=self.inv_perm[:n].cpu().numpy(),
+            child_ptr=self.child_ptr[:n + 1].cpu().numpy(),
+            child_idx=self.child_idx[:E].cpu().numpy(),
+            n_levels=L, n_edges=E)
+
+
+def jitdb_schedule(parent, stream=None, workspace=None) -> Schedule:
+    """parent: int32 CUDA tensor [N], -1 = root.  Returns the forest's Schedule."""
+    import torch
+    lib = load_library()
+    if parent.dtype != torch.int32 or not parent.is_cuda or not parent.is_contiguous():
+        raise TypeError("parent must be a contiguous int32 CUDA tensor")
+    n = parent.numel()
+    sched = Schedule(n, parent.device)
+    need = jitdb_schedule_workspace_bytes(n)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=parent.device)
+    with torch.cuda.device(parent.device):
+        code = lib.jitdb_schedule(parent.data_ptr() if n else None, ctypes.byref(sched.struct),
+                                  workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
+    _check(code)
+    sched.n_levels = int(sched.struct.n_levels)
+    sched.n_edges = int(sched.struct.n_edges)
+    return sched
+
+
+def jitdb_treelstm_forward(x, W, U, b, schedule: Schedule, stream=None, workspace=None,
+                           out: Optional[Tuple] = None):
+    """x [N, D], W [4H, D], U [4H, H] (all fp32 or all bf16), b [4H] fp32, on the GPU.
+    Returns (h [N, H] in x's dtype, c [N, H] fp32), rows indexed by node id."""
+    import torch
+    lib = load_library()
+    if x.dtype == torch.float32:
+        dt = JITDB_F32
+    elif x.dtype == torch.bfloat16:
+        dt = JITDB_BF16
+    else:
+        raise TypeError("x must be float32 or bfloat16")
+    for t, name in ((x, "x"), (W, "W"), (U, "U"), (b, "b")):
+        if not t.is_cuda or not t.is_contiguous():
+            raise TypeError(f"{name} must be a contiguous CUDA tensor")
+    if W.dtype != x.dtype or U.dtype != x.dtype or b.dtype != torch.float32:
+        raise TypeError("W, U must have x's dtype and b must be float32")
+    n = schedule.n_nodes
+    H = U.shape[1]
+    D = W.shape[1]
+    if x.shape != (n, D) or W.shape[0] != 4 * H or U.shape[0] != 4 * H or b.numel() != 4 * H:
+        raise ValueError("shape mismatch between x, W, U, b and the schedule")
+    if out is None:
+        h = torch.empty((n, H), dtype=x.dtype, device=x.device)
+        c = torch.empty((n, H), dtype=torch.float32, device=x.device)
+    else:
+        h, c = out
+    need = jitdb_treelstm_workspace_bytes(n, schedule.n_edges, D, H, dt)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    with torch.cuda.device(x.device):
+        code = lib.jitdb_treelstm_forward(
+            x.data_ptr() if n else None, W.data_ptr(), U.data_ptr(), b.data_ptr(), D, H, dt,
+            ctypes.byref(schedule.struct), h.data_ptr() if n else None, c.data_ptr() if n else None,
+            workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
+    _check(code)
+    return h, c

@@ -1,0 +1,176 @@
+"""GPU parity: jitdb_treelstm_forward against the CPU oracle.
+
+Tolerances (max abs error over every element of h and c):
+  fp32 path  1e-4      bf16 MFMA / fp32 accumulate path  2e-2
+"""
+import numpy as np
+import pytest
+
+from oracle import treelstm_oracle as T
+from workloads import (CONFIGS, make_forest, make_values, make_workload, relabel, tree_ranges,
+                       chain_forest, star_forest)
+from gpu_util import run_gpu_forward
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def _oracle(c_oracle, parent, inputs):
+    x, W, U, b = inputs
+    h, c, _ = c_oracle(parent, x, W, U, b)
+    return h, c
+
+
+def _report(tag, h, c, ho, co):
+    eh, ec = float(np.abs(h - ho).max()), float(np.abs(c - co).max())
+    print(f"{tag}: max|dh|={eh:.3e} max|dc|={ec:.3e} max|c|={float(np.abs(co).max()):.2f}", flush=True)
+    return eh, ec
+
+
+@pytest.mark.parametrize("cfg,bias", [(1, "zero"), (1, "random"), (2, "zero"), (2, "random"),
+                                      (3, "zero"), (3, "random")])
+def test_small_configs_every_node(c_oracle, cfg, bias):
+    cfgo, p, x, W, U, b = make_workload(cfg, bias=bias)
+    print(f"forward parity cfg={cfg} bias={bias} dtype={cfgo.dtype} N={p.shape[0]}", flush=True)
+    s, h, c, seen = run_gpu_forward(p, x, W, U, b, cfgo.dtype)
+    ho, co = _oracle(c_oracle, p, seen)
+    eh, ec = _report(f"cfg{cfg}/{bias}", h, c, ho, co)
+    assert eh <= TOL[cfgo.dtype] and ec <= TOL[cfgo.dtype]
+
+
+def _sampled_tree_check(c_oracle, cfg, n_sample, dtype=None, bias="zero"):
+    cfgo, p, x, W, U, b = make_workload(cfg, bias=bias)
+    dtype = dtype or cfgo.dtype
+    print(f"forward parity cfg={cfg} dtype={dtype} N={p.shape[0]} (oracle on {n_sample} sampled trees)",
+          flush=True)
+    s, h, c, seen = run_gpu_forward(p, x, W, U, b, dtype)
+    xo, Wo, Uo, bo = seen
+    r = tree_ranges(p)
+    T_ = len(r) - 1
+    rng = np.random.default_rng(77)
+    pick = np.sort(rng.choice(T_, size=min(n_sample, T_), replace=False))
+    # always include the largest and the deepest-looking trees
+    sizes = np.diff(r)
+    pick = np.unique(np.concatenate([pick, [int(np.argmax(sizes))], np.arange(min(6, T_))]))
+    rows = np.concatenate([np.arange(r[t], r[t + 1]) for t in pick])
+    sub_parent = []
+    off = 0
+    for t in pick:
+        lo, hi = r[t], r[t + 1]
+        sp = p[lo:hi].astype(np.int64)
+        sub_parent.append(np.where(sp < 0, -1, sp - lo + off))
+        off += hi - lo
+    sub_parent = np.concatenate(sub_parent).astype(np.int32)
+    ho, co, _ = c_oracle(sub_parent, xo[rows], Wo, Uo, bo)
+    eh, ec = _report(f"cfg{cfg}/{dtype}", h[rows], c[rows], ho, co)
+    assert np.isfinite(h).all() and np.isfinite(c).all()
+    assert eh <= TOL[dtype] and ec <= TOL[dtype]
+
+
+@pytest.mark.timeout(400)
+def test_config4_full_size_sampled_trees(c_oracle):
+    _sampled_tree_check(c_oracle, 4, 240, bias="random")
+
+
+@pytest.mark.timeout(600)
+def test_config5_full_size_sampled_trees(c_oracle):
+    _sampled_tree_check(c_oracle, 5, 48)
+
+
+def test_config3_in_fp32_too(c_oracle):
+    _sampled_tree_check(c_oracle, 3, 300, dtype="f32", bias="random")
+
+
+def test_relabelled_ids_give_the_same_states(c_oracle):
+    cfgo, p, x, W, U, b = make_workload(2, bias="random")
+    q, new_of_old = relabel(p, 21)
+    xq = np.empty_like(x); xq[new_of_old] = x
+    _, h, c, _ = run_gpu_forward(p, x, W, U, b, "f32")
+    _, hq, cq, seen = run_gpu_forward(q, xq, W, U, b, "f32")
+    assert np.abs(hq[new_of_old] - h).max() <= 2e-5 and np.abs(cq[new_of_old] - c).max() <= 2e-5
+    ho, co = _oracle(c_oracle, q, seen)
+    assert np.abs(hq - ho).max() <= 1e-4 and np.abs(cq - co).max() <= 1e-4
+
+
+def test_forest_equals_trees_run_alone(c_oracle):
+    cfgo, p, x, W, U, b = make_workload(1, bias="random")
+    _, h, c, _ = run_gpu_forward(p, x, W, U, b, "f32")
+    r = tree_ranges(p)
+    for t in range(len(r) - 1):
+        lo, hi = r[t], r[t + 1]
+        pt = np.where(p[lo:hi] < 0, -1, p[lo:hi] - lo).astype(np.int32)
+        _, ht, ct, _ = run_gpu_forward(pt, x[lo:hi], W, U, b, "f32")
+        assert np.abs(ht - h[lo:hi]).max() <= 2e-5 and np.abs(ct - c[lo:hi]).max() <= 2e-5
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("name,H,D", [("H32", 32, 4), ("H33", 33, 8), ("H64", 64, 300),
+                                      ("H100", 100, 52), ("H257", 257, 300)])
+def test_odd_dimensions(c_oracle, name, H, D, dtype):
+    """Hidden sizes on and off every padding boundary; forests with leaves only,
+    one chain, one wide star and a ragged last row tile."""
+    parent = np.concatenate([
+        np.full(3, -1), chain_forest(37) + 3, star_forest(150) + 40,
+        np.where(make_forest(1) < 0, -1, make_forest(1) + 190)]).astype(np.int32)
+    parent[3] = -1; parent[40] = -1
+    x, W, U, b = make_values(1, parent.shape[0], "random", D=D, H=H)
+    print(f"forward odd dims {name} D={D} dtype={dtype} N={parent.shape[0]}", flush=True)
+    _, h, c, seen = run_gpu_forward(parent, x, W, U, b, dtype)
+    ho, co = _oracle(c_oracle, parent, seen)
+    eh, ec = _report(f"{name}/{dtype}", h, c, ho, co)
+    # the 149-child star reaches |c| ~ 50: scale the bf16 bound with the magnitude there
+    scale = max(1.0, float(np.abs(co).max()) / 8.0) if dtype == "bf16" else max(1.0, float(np.abs(co).max()) / 50.0)
+    assert eh <= TOL[dtype] and ec <= TOL[dtype] * scale
+
+
+def test_leaves_only_and_single_node(c_oracle):
+    for n in (1, 2, 129):
+        parent = np.full(n, -1, dtype=np.int32)
+        x, W, U, b = make_values(1, n, "random", D=300, H=150)
+        _, h, c, seen = run_gpu_forward(parent, x, W, U, b, "f32")
+        ho, co = _oracle(c_oracle, parent, seen)
+        assert np.abs(h - ho).max() <= 1e-4 and np.abs(c - co).max() <= 1e-4
+
+
+def test_deep_chain_fp32(c_oracle):
+    parent = chain_forest(128, 3)
+    x, W, U, b = make_values(4, parent.shape[0], "random", D=300, H=256)
+    _, h, c, seen = run_gpu_forward(parent, x, W, U, b, "f32")
+    ho, co = _oracle(c_oracle, parent, seen)
+    eh, ec = _report("chain128/f32", h, c, ho, co)
+    assert eh <= 1e-4 and ec <= 1e-4
+
+
+def test_empty_forest_forward():
+    import torch
+    import paper_1904_07421_amd as J
+    s = J.jitdb_schedule(torch.empty(0, dtype=torch.int32, device="cuda"))
+    x = torch.empty((0, 300), device="cuda"); W = torch.zeros((600, 300), device="cuda")
+    U = torch.zeros((600, 150), device="cuda"); b = torch.zeros(600, device="cuda")
+    h, c = J.jitdb_treelstm_forward(x, W, U, b, s)
+    assert h.shape == (0, 150) and c.shape == (0, 150)
+
+
+def test_bitwise_repeatable():
+    cfgo, p, x, W, U, b = make_workload(3)
+    _, h1, c1, _ = run_gpu_forward(p, x, W, U, b, "bf16")
+    _, h2, c2, _ = run_gpu_forward(p, x, W, U, b, "bf16")
+    assert np.array_equal(h1, h2) and np.array_equal(c1, c2)
+
+
+def test_bad_arguments_are_rejected():
+    import torch
+    import paper_1904_07421_amd as J
+    from gpu_util import dev_parent
+    s = J.jitdb_schedule(dev_parent(make_forest(1)))
+    n = s.n_nodes
+    x = torch.zeros((n, 302), device="cuda"); W = torch.zeros((600, 302), device="cuda")
+    U = torch.zeros((600, 150), device="cuda"); b = torch.zeros(600, device="cuda")
+    with pytest.raises(J.JitdbError) as e:          # D not a multiple of 4
+        J.jitdb_treelstm_forward(x, W, U, b, s)
+    assert e.value.code == -2
+    x = torch.zeros((n, 300), device="cuda"); W = torch.zeros((600, 300), device="cuda")
+    with pytest.raises(J.JitdbError) as e:          # workspace too small
+        J.jitdb_treelstm_forward(x, W, U, b, s, workspace=torch.empty(512, dtype=torch.uint8, device="cuda"))
+    assert e.value.code == -5

@@ -216,10 +216,11 @@ def to_bf16_bits(a: np.ndarray) -> np.ndarray:
     GPU path receive the very same bf16 values.
     """
     a32 = np.ascontiguousarray(a, dtype=np.float32)
-    bits = a32.view(np.uint32).astype(np.uint64)
-    lsb = (bits >> 16) & 1
-    rounded = (bits + 0x7FFF + lsb) >> 16
-    out = rounded.astype(np.uint16)
+    bits = a32.view(np.uint32)
+    rounded = (bits >> 16) & 1
+    rounded += 0x7FFF
+    rounded += bits                       # wraps only for NaN patterns, fixed below
+    out = (rounded >> 16).astype(np.uint16)
     nan = np.isnan(a32)
     if nan.any():
         out[nan] = 0x7FC0
