@@ -1,0 +1,203 @@
+#!/usr/bin/env python3
+"""Benchmark of the level-batched Tree-LSTM forward on one MI355X.
+
+One "step" = the whole hot path over one batch: jitdb_schedule (heights, level
+buckets, permutation, child CSR) followed by jitdb_treelstm_forward (all levels),
+on the large synthetic forest (config 5: 65536 random recursive trees, 8-64
+nodes each, D=300, H=512, bf16 operands with fp32 accumulate).  Inputs are
+resident in HBM before the timed region.  Prints ONE JSON line.
+
+  value        nodes/s of the whole step (schedule + forward)
+  roofline     the dominant kernel against its bound; duration from HIP events
+               recorded on the launch stream inside the timed region
+  cpu_baseline the fp64 C oracle timed on the host cores on the first trees of
+               the same forest (a reported baseline, not a target)
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_F32_MFMA_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=5, help="workload config index (1-5)")
+    ap.add_argument("--no-kernel-events", action="store_true",
+                    help="do not bracket kernels with events inside the timed region")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-trees", type=int, default=0, help="trees in the oracle sample (0 = auto)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the forest shards by tree with no "
+              "exchange; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_1904_07421_amd as J
+    from workloads import CONFIGS, make_forest, make_values, to_bf16_bits, bf16_bits_to_f32, tree_ranges
+
+    cfg = CONFIGS[args.config]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    t0 = time.time()
+    parent = make_forest(cfg.index)
+    N = int(parent.shape[0])
+    x, W, U, b = make_values(cfg.index, N)
+    log(f"config {cfg.index} ({cfg.name}): N={N} generated in {time.time() - t0:.1f}s")
+    D, H = cfg.D, cfg.H
+    if cfg.dtype == "bf16":
+        def up(a):
+            bits = to_bf16_bits(a)
+            return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(dev), bits
+        xt, xbits = up(x)
+        Wt, Wbits = up(W)
+        Ut, Ubits = up(U)
+        esz = 2
+        peak_tflops = PEAK_BF16_TFLOPS
+    else:
+        xt, Wt, Ut = (torch.from_numpy(a).to(dev) for a in (x, W, U))
+        esz = 4
+        peak_tflops = PEAK_F32_MFMA_TFLOPS
+    bt = torch.from_numpy(b).to(dev)
+    pt = torch.from_numpy(parent).to(dev)
+    log(f"inputs resident on {torch.cuda.get_device_name(0)} after {time.time() - t0:.1f}s")
+
+    # one untimed call sizes the buffers; they are then reused by every step
+    sched = J.jitdb_schedule(pt)
+    E, L = sched.n_edges, sched.n_levels
+    lp = sched.host_level_ptr[:L + 1].astype(np.int64)
+    n_leaf = int(lp[1])
+    n_int = N - n_leaf
+    ws_s = torch.empty(J.jitdb_schedule_workspace_bytes(N), dtype=torch.uint8, device=dev)
+    ws_f = torch.empty(J.jitdb_treelstm_workspace_bytes(N, E, D, H, J.JITDB_BF16 if esz == 2 else J.JITDB_F32),
+                       dtype=torch.uint8, device=dev)
+    h = torch.empty((N, H), dtype=xt.dtype, device=dev)
+    c = torch.empty((N, H), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        s = J.jitdb_schedule(pt, stream=stream, workspace=ws_s)
+        J.jitdb_treelstm_forward(xt, Wt, Ut, bt, s, stream=stream, workspace=ws_f, out=(h, c))
+        return s
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    launches_per_step = 1 + 3 * L
+    if not args.no_kernel_events:
+        J.jitdb_profile_start(launches_per_step * args.steps + 8)
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t_end = time.perf_counter()
+    prof = None if args.no_kernel_events else J.jitdb_profile_stop()
+    ms_per_step = (t_end - t_begin) * 1e3 / args.steps
+    value = N / (ms_per_step * 1e-3)
+
+    # schedule and forward separately (same buffers), HIP events on the launch stream
+    def timed(fn, reps):
+        e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            fn()
+        e1.record(stream)
+        e1.synchronize()
+        return e0.elapsed_time(e1) / reps
+    reps = max(3, min(args.steps, 10))
+    ms_sched = timed(lambda: J.jitdb_schedule(pt, stream=stream, workspace=ws_s), reps)
+    ms_fwd = timed(lambda: J.jitdb_treelstm_forward(xt, Wt, Ut, bt, sched, stream=stream,
+                                                     workspace=ws_f, out=(h, c)), reps)
+
+    # algorithmic work per step and per kernel class (padding and unused rows do not count)
+    flops = {
+        "leaf": n_leaf * 2.0 * D * 3 * H,
+        "internal": n_int * (2.0 * D * 4 * H + 2.0 * H * 3 * H),
+        "proj": E * 2.0 * H * H,
+    }
+    bytes_child_sum = (E + n_int) * H * esz
+    kernels = {}
+    roof = None
+    if prof is not None:
+        for name in ("leaf", "internal", "proj"):
+            ms = prof[name]["ms"] / args.steps
+            n_l = prof[name]["launches"] / args.steps
+            if ms > 0:
+                kernels[name] = {"ms_per_step": ms, "launches_per_step": n_l,
+                                 "tflops": flops[name] / (ms * 1e-3) / 1e12,
+                                 "frac_mfma_peak": flops[name] / (ms * 1e-3) / 1e12 / peak_tflops}
+        ms = prof["child_sum"]["ms"] / args.steps
+        if ms > 0:
+            kernels["child_sum"] = {"ms_per_step": ms,
+                                    "launches_per_step": prof["child_sum"]["launches"] / args.steps,
+                                    "gbs": bytes_child_sum / (ms * 1e-3) / 1e9,
+                                    "frac_hbm_peak": bytes_child_sum / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
+        kernels["pack"] = {"ms_per_step": prof["pack"]["ms"] / args.steps}
+        dom = max(("leaf", "internal", "proj"), key=lambda k: kernels.get(k, {}).get("ms_per_step", 0.0))
+        k = kernels[dom]
+        roof = {"kernel": f"level_kernel<{cfg.dtype},{dom}>", "bound": "mfma",
+                "achieved": k["tflops"], "peak": peak_tflops, "unit": "TFLOP/s",
+                "frac": k["frac_mfma_peak"], "traffic": None,
+                "avg_launch_ms": k["ms_per_step"] / max(k["launches_per_step"], 1),
+                "flops_per_step": flops[dom], "dropped_events": prof["dropped"]}
+        mfma_ms = sum(kernels[n]["ms_per_step"] for n in ("leaf", "internal", "proj") if n in kernels)
+        roof["all_mfma_kernels_frac"] = sum(flops.values()) / (mfma_ms * 1e-3) / 1e12 / peak_tflops
+
+    out = {
+        "metric": "Tree-LSTM forward nodes/sec on 1 MI355X",
+        "value": value, "unit": "nodes/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"config {cfg.index}: {cfg.name}", "n_trees": cfg.n_trees, "n_nodes": N,
+                   "n_edges": E, "n_levels": L, "D": D, "H": H,
+                   "step": "jitdb_schedule + jitdb_treelstm_forward"},
+        "ms_schedule": ms_sched, "ms_forward": ms_fwd,
+        "forward_only_nodes_per_s": N / (ms_fwd * 1e-3),
+        "roofline": roof, "kernels": kernels,
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle.build import forward_c
+        r = tree_ranges(parent)
+        n_trees = args.cpu_trees or min(len(r) - 1, max(64, int(8192 * (812 * 2048) / ((D + H) * 4.0 * H))))
+        n_trees = min(n_trees, len(r) - 1)
+        hi = int(r[n_trees])
+        sub = parent[:hi]
+        if esz == 2:
+            xo, Wo, Uo = (bf16_bits_to_f32(a) for a in (xbits[:hi], Wbits, Ubits))
+        else:
+            xo, Wo, Uo = x[:hi], W, U
+        forward_c(sub[:r[1]], xo[:r[1]], Wo, Uo, b)          # build + first-touch outside the clock
+        t1 = time.perf_counter()
+        _, _, used = forward_c(sub, xo, Wo, Uo, b)
+        dt = time.perf_counter() - t1
+        out["cpu_baseline"] = {"value": hi / dt, "unit": "nodes/s", "cores": int(used), "kind": "oracle",
+                               "sample": f"first {n_trees} trees ({hi} nodes) of the same forest, "
+                                         f"fp64 C oracle with OpenMP over trees, {dt:.1f}s"}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -141,8 +141,46 @@ int jitdb_treelstm_forward(const void *x, const void *W, const void *U, const fl
                            void *h_out, float *c_out,
                            void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * Per-kernel timing, for measuring the execution step against the hardware
+ * roofline (the paper reports only wall-clock samples/s, section 5; the
+ * kernels here are this implementation's own).  Between jitdb_profile_start
+ * and jitdb_profile_stop every kernel launch of jitdb_treelstm_forward is
+ * bracketed by a pair of HIP events recorded on the call's stream.
+ *
+ *   jitdb_profile_start(capacity)  creates `capacity` event pairs (host objects)
+ *                                  and switches recording on; launches beyond the
+ *                                  capacity run unrecorded and are counted in `dropped`.
+ *   jitdb_profile_stop(out)        waits for the recorded events, adds up the elapsed
+ *                                  time and launch count per kernel class, destroys
+ *                                  the events and switches recording off.
+ *
+ * Process-wide state, not thread safe: use from one thread, one stream at a time.
+ */
+typedef enum {
+    JITDB_K_PACK = 0,       /* weight re-packing */
+    JITDB_K_CHILD_SUM = 1,  /* hs_j = sum_k h_k */
+    JITDB_K_LEAF = 2,       /* leaf level: W x + cell */
+    JITDB_K_INTERNAL = 3,   /* internal levels: [x;hs][W;U] + cell with per-child forget gates */
+    JITDB_K_PROJ = 4,       /* P_k = U_f h_k */
+    JITDB_K_CLASSES = 5
+} jitdb_kernel_class;
+
+typedef struct {
+    double ms[JITDB_K_CLASSES];        /* summed event time per class, milliseconds */
+    int64_t launches[JITDB_K_CLASSES]; /* recorded launches per class */
+    int64_t dropped;                   /* launches that found no free event pair */
+} jitdb_profile_t;
+
+int jitdb_profile_start(int32_t capacity);
+int jitdb_profile_stop(jitdb_profile_t *out);
+
 /* Static, NUL-terminated description of a status code. */
 const char *jitdb_strerror(int code);
+
+/* Text describing the most recent HIP runtime failure behind a JITDB_E_HIP (which call site,
+ * which HIP error).  Process-wide, for diagnostics; static storage, never NULL. */
+const char *jitdb_last_hip_error(void);
 
 /* Library version, "major.minor". */
 const char *jitdb_version(void);

@@ -10,6 +10,8 @@ from .binding import (  # noqa: F401
     jitdb_treelstm_forward,
     jitdb_treelstm_workspace_bytes,
     jitdb_strerror,
+    jitdb_profile_start,
+    jitdb_profile_stop,
     jitdb_version,
     library_path,
     load_library,

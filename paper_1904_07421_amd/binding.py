@@ -43,6 +43,14 @@ class _ScheduleStruct(ctypes.Structure):
     ]
 
 
+K_CLASSES = ("pack", "child_sum", "leaf", "internal", "proj")
+
+
+class _ProfileStruct(ctypes.Structure):
+    _fields_ = [("ms", ctypes.c_double * 5), ("launches", ctypes.c_int64 * 5),
+                ("dropped", ctypes.c_int64)]
+
+
 _lib = None
 
 
@@ -73,8 +81,14 @@ def load_library():
         ctypes.c_int32, ctypes.c_int32, ctypes.c_int,
         ctypes.POINTER(_ScheduleStruct), ctypes.c_void_p, ctypes.c_void_p,
         ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.jitdb_profile_start.restype = ctypes.c_int
+    lib.jitdb_profile_start.argtypes = [ctypes.c_int32]
+    lib.jitdb_profile_stop.restype = ctypes.c_int
+    lib.jitdb_profile_stop.argtypes = [ctypes.POINTER(_ProfileStruct)]
     lib.jitdb_strerror.restype = ctypes.c_char_p
     lib.jitdb_strerror.argtypes = [ctypes.c_int]
+    lib.jitdb_last_hip_error.restype = ctypes.c_char_p
+    lib.jitdb_last_hip_error.argtypes = []
     lib.jitdb_version.restype = ctypes.c_char_p
     lib.jitdb_version.argtypes = []
     _lib = lib
@@ -89,6 +103,20 @@ def jitdb_version() -> str:
     return load_library().jitdb_version().decode()
 
 
+def jitdb_profile_start(capacity: int) -> None:
+    _check(load_library().jitdb_profile_start(int(capacity)))
+
+
+def jitdb_profile_stop() -> dict:
+    """{class: {"ms": total milliseconds, "launches": count}} plus "dropped"."""
+    p = _ProfileStruct()
+    _check(load_library().jitdb_profile_stop(ctypes.byref(p)))
+    out = {name: {"ms": float(p.ms[i]), "launches": int(p.launches[i])}
+           for i, name in enumerate(K_CLASSES)}
+    out["dropped"] = int(p.dropped)
+    return out
+
+
 def jitdb_schedule_workspace_bytes(n_nodes: int) -> int:
     return int(load_library().jitdb_schedule_workspace_bytes(int(n_nodes)))
 
@@ -100,7 +128,10 @@ def jitdb_treelstm_workspace_bytes(n_nodes: int, n_edges: int, D: int, H: int, d
 
 def _check(code: int):
     if code != 0:
-        raise JitdbError(code, jitdb_strerror(code))
+        msg = jitdb_strerror(code)
+        if code == -6:
+            msg += ": " + load_library().jitdb_last_hip_error().decode()
+        raise JitdbError(code, msg)
 
 
 def _stream_ptr(stream) -> int:

@@ -1,6 +1,8 @@
 // Entry points of the C ABI that need no kernels.
 #include "common.h"
 
+#include <stdio.h>
+
 extern "C" const char *jitdb_strerror(int code) {
     switch (code) {
         case JITDB_OK: return "ok";
@@ -14,5 +16,17 @@ extern "C" const char *jitdb_strerror(int code) {
         default: return "unknown jitdb status";
     }
 }
+
+namespace jitdb {
+static char g_hip_detail[256] = "no HIP failure recorded";
+void note_hip_failure(hipError_t e, const char *file, int line) {
+    const char *slash = file;
+    for (const char *p = file; *p; ++p)
+        if (*p == '/') slash = p + 1;
+    snprintf(g_hip_detail, sizeof(g_hip_detail), "%s (%d) at %s:%d", hipGetErrorString(e), (int)e, slash, line);
+}
+}  // namespace jitdb
+
+extern "C" const char *jitdb_last_hip_error(void) { return jitdb::g_hip_detail; }
 
 extern "C" const char *jitdb_version(void) { return "0.1"; }

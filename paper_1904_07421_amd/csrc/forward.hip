@@ -470,6 +470,31 @@ level_kernel(const LevelArgs a) {
 }
 
 // ---- host side ---------------------------------------------------------------------
+// Optional per-launch event pairs (see jitdb_profile_start in the header).
+struct Profiler {
+    bool on = false;
+    int capacity = 0, used = 0;
+    int64_t dropped = 0;
+    hipEvent_t *begin = nullptr, *end = nullptr;
+    int *cls = nullptr;
+};
+Profiler g_prof;
+
+struct ScopedLaunchTimer {
+    int slot = -1;
+    hipStream_t st;
+    ScopedLaunchTimer(int kernel_class, hipStream_t s) : st(s) {
+        if (!g_prof.on) return;
+        if (g_prof.used >= g_prof.capacity) { ++g_prof.dropped; return; }
+        slot = g_prof.used++;
+        g_prof.cls[slot] = kernel_class;
+        (void)hipEventRecord(g_prof.begin[slot], st);
+    }
+    ~ScopedLaunchTimer() {
+        if (slot >= 0) (void)hipEventRecord(g_prof.end[slot], st);
+    }
+};
+
 struct ForwardWs {
     void *Wp, *Up;
     float *bp;
@@ -528,6 +553,7 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
     {
         const int64_t total = (int64_t)d.NP * (d.Dp + d.Hp);
         const unsigned grid = (unsigned)(ceil_div(total, kThreads) < 4096 ? ceil_div(total, kThreads) : 4096);
+        ScopedLaunchTimer tm(JITDB_K_PACK, st);
         pack_weights_kernel<T><<<grid, kThreads, 0, st>>>(
             static_cast<const T *>(W), static_cast<const T *>(U), b, d.D, d.H, d.Dp, d.Hp, d.NP,
             static_cast<T *>(w.Wp), static_cast<T *>(w.Up), w.bp);
@@ -551,6 +577,7 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
         const int row_tiles = (int)ceil_div(n_rows, kBM);
         if (l > 0) {
             const int64_t pieces = (int64_t)n_rows * (d.Hp / Traits<T>::VEC);
+            ScopedLaunchTimer tm(JITDB_K_CHILD_SUM, st);
             child_sum_kernel<T><<<(unsigned)ceil_div(pieces, kThreads), kThreads, 0, st>>>(
                 static_cast<const T *>(a.hs), d.Hp, a.level_nodes, s->child_ptr, s->child_idx,
                 static_cast<T *>(w.hsum), n_rows);
@@ -558,15 +585,21 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
         }
         a.n_col_tiles = d.NP / kBN;
         a.n_blocks = row_tiles * a.n_col_tiles;
-        if (l == 0)
-            level_kernel<T, MODE_LEAF><<<a.n_blocks, kThreads, 0, st>>>(a);
-        else
-            level_kernel<T, MODE_INTERNAL><<<a.n_blocks, kThreads, 0, st>>>(a);
+        {
+            ScopedLaunchTimer tm(l == 0 ? JITDB_K_LEAF : JITDB_K_INTERNAL, st);
+            if (l == 0)
+                level_kernel<T, MODE_LEAF><<<a.n_blocks, kThreads, 0, st>>>(a);
+            else
+                level_kernel<T, MODE_INTERNAL><<<a.n_blocks, kThreads, 0, st>>>(a);
+        }
         JITDB_LAUNCH_CHECK();
         if (l + 1 < L) {   // these nodes have parents (except roots, whose rows go unused)
             a.n_col_tiles = (int)ceil_div(d.Hu / kUnit, 8);
             a.n_blocks = row_tiles * a.n_col_tiles;
-            level_kernel<T, MODE_PROJ><<<a.n_blocks, kThreads, 0, st>>>(a);
+            {
+                ScopedLaunchTimer tm(JITDB_K_PROJ, st);
+                level_kernel<T, MODE_PROJ><<<a.n_blocks, kThreads, 0, st>>>(a);
+            }
             JITDB_LAUNCH_CHECK();
         }
     }
@@ -577,6 +610,49 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
 }  // namespace jitdb
 
 using namespace jitdb;
+
+extern "C" int jitdb_profile_start(int32_t capacity) {
+    if (capacity < 1 || capacity > (1 << 20)) return JITDB_E_BADARG;
+    if (g_prof.on) return JITDB_E_BADARG;
+    g_prof.begin = new hipEvent_t[capacity];
+    g_prof.end = new hipEvent_t[capacity];
+    g_prof.cls = new int[capacity];
+    for (int i = 0; i < capacity; ++i) {
+        if (hipEventCreate(&g_prof.begin[i]) != hipSuccess || hipEventCreate(&g_prof.end[i]) != hipSuccess)
+            return JITDB_E_HIP;
+    }
+    g_prof.capacity = capacity;
+    g_prof.used = 0;
+    g_prof.dropped = 0;
+    g_prof.on = true;
+    return JITDB_OK;
+}
+
+extern "C" int jitdb_profile_stop(jitdb_profile_t *out) {
+    if (!out) return JITDB_E_NULL;
+    if (!g_prof.on) return JITDB_E_BADARG;
+    g_prof.on = false;
+    int rc = JITDB_OK;
+    for (int c = 0; c < JITDB_K_CLASSES; ++c) { out->ms[c] = 0.0; out->launches[c] = 0; }
+    out->dropped = g_prof.dropped;
+    for (int i = 0; i < g_prof.used; ++i) {
+        float ms = 0.0f;
+        if (hipEventSynchronize(g_prof.end[i]) != hipSuccess ||
+            hipEventElapsedTime(&ms, g_prof.begin[i], g_prof.end[i]) != hipSuccess) {
+            rc = JITDB_E_HIP;
+            continue;
+        }
+        out->ms[g_prof.cls[i]] += ms;
+        out->launches[g_prof.cls[i]] += 1;
+    }
+    for (int i = 0; i < g_prof.capacity; ++i) {
+        (void)hipEventDestroy(g_prof.begin[i]);
+        (void)hipEventDestroy(g_prof.end[i]);
+    }
+    delete[] g_prof.begin; delete[] g_prof.end; delete[] g_prof.cls;
+    g_prof = Profiler();
+    return rc;
+}
 
 extern "C" size_t jitdb_treelstm_workspace_bytes(int64_t n_nodes, int64_t n_edges,
                                                  int32_t D, int32_t H, jitdb_dtype dtype) {
@@ -590,6 +666,7 @@ extern "C" int jitdb_treelstm_forward(const void *x, const void *W, const void *
                                       const jitdb_schedule_t *s, void *h_out, float *c_out,
                                       void *workspace, size_t workspace_bytes, void *hip_stream) {
     if (!s) return JITDB_E_NULL;
+    drop_stale_hip_error();
     const int64_t n = s->n_nodes;
     if (!dims_ok(n, s->n_edges, D, H, (int)dtype)) return JITDB_E_BADARG;
     if (n == 0) return JITDB_OK;

@@ -413,6 +413,7 @@ extern "C" size_t jitdb_schedule_workspace_bytes(int64_t n_nodes) {
 extern "C" int jitdb_schedule(const int32_t *parent, jitdb_schedule_t *s,
                               void *workspace, size_t workspace_bytes, void *hip_stream) {
     if (!s) return JITDB_E_NULL;
+    drop_stale_hip_error();
     const int64_t n64 = s->n_nodes;
     if (n64 < 0 || n64 > JITDB_MAX_NODES) return JITDB_E_BADARG;
     if (!s->host_level_ptr) return JITDB_E_NULL;
