@@ -24,6 +24,11 @@
 
 #include "common.h"
 
+#include <type_traits>
+#ifdef JITDB_EXPERIMENT
+#include <stdlib.h>
+#endif
+
 namespace jitdb {
 namespace {
 
@@ -37,8 +42,9 @@ constexpr int kBN = 256;        // packed columns per block = 2 unit tiles x 4 g
 constexpr int kUnit = 32;       // hidden units per MFMA column tile
 constexpr int kGateTile = 128;  // packed rows per unit tile (4 gates x 32 units)
 
+constexpr int kEpiRows = 64;    // rows per epilogue pass
+constexpr int kEpiStride = 68;  // floats per epilogue LDS row: 64 units + 4 (keeps 16-byte alignment)
 constexpr int kLdsStride = 80;  // stage row + 16 bytes: 128-bit LDS reads of 32 rows hit distinct banks
-constexpr int kKPad = 32;       // D and H are padded to multiples of this many elements
 
 enum : int { MODE_LEAF = 0, MODE_INTERNAL = 1, MODE_PROJ = 2 };
 
@@ -77,27 +83,29 @@ template <typename T> __device__ __forceinline__ float tanh_t(float z) {
 
 // ---- weight packing ----------------------------------------------------------------
 // Packed row r = tile*128 + gate*32 + uu holds gate `gate` of hidden unit tile*32 + uu.
+// Wp has NP rows, Up has NPU >= NP rows; rows of units >= H and columns past D / H are zero.
 template <typename T>
 __global__ void __launch_bounds__(kThreads)
 pack_weights_kernel(const T *__restrict__ W, const T *__restrict__ U, const float *__restrict__ b,
-                    int D, int H, int Dp, int Hp, int NP,
+                    int D, int H, int Dp, int Hp, int NP, int NPU,
                     T *__restrict__ Wp, T *__restrict__ Up, float *__restrict__ bp) {
-    const int64_t total = (int64_t)NP * (Dp + Hp);
-    for (int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x; idx < total;
+    const int64_t n_w = (int64_t)NP * Dp, n_u = (int64_t)NPU * Hp;
+    for (int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x; idx < n_w + n_u;
          idx += (int64_t)gridDim.x * kThreads) {
-        const int r = (int)(idx / (Dp + Hp));
-        const int k = (int)(idx % (Dp + Hp));
+        const bool is_w = idx < n_w;
+        const int64_t j = is_w ? idx : idx - n_w;
+        const int ld = is_w ? Dp : Hp;
+        const int r = (int)(j / ld), k = (int)(j % ld);
         const int tile = r / kGateTile, gate = (r % kGateTile) / kUnit, uu = r % kUnit;
         const int unit = tile * kUnit + uu;
         const bool row_ok = unit < H;
         const int64_t src = (int64_t)gate * H + unit;
-        if (k < Dp) {
-            Wp[(int64_t)r * Dp + k] = (row_ok && k < D) ? W[src * D + k] : T(0);
+        if (is_w) {
+            Wp[j] = (row_ok && k < D) ? W[src * D + k] : T(0);
+            if (k == 0) bp[r] = row_ok ? b[src] : 0.0f;
         } else {
-            const int kk = k - Dp;
-            Up[(int64_t)r * Hp + kk] = (row_ok && kk < H) ? U[src * H + kk] : T(0);
+            Up[j] = (row_ok && k < H) ? U[src * H + k] : T(0);
         }
-        if (k == 0) bp[r] = row_ok ? b[src] : 0.0f;
     }
 }
 
@@ -163,21 +171,21 @@ struct LevelArgs {
     const int32_t *level_nodes;  // perm + level start: row -> node id
     const int32_t *child_ptr;
     const int32_t *child_idx;
-    // per-child forget projections, rows by node id, stride H
+    // per-child forget projections, rows by node id, stride Hq
     float *P;
+    float *cs;            // [N, Hq] c with rows padded to 4 floats, or == c_out when H % 4 == 0
     // outputs
     float *c_out;         // [N, H]
     void *h_out;          // [N, H]
     void *hs_out;         // [N, Hp] or == h_out when H == Hp
-    int D, Dp, H, Hp, Hu;
+    int D, Dp, H, Hp, Hu, Hq;
     int n_rows;
     int n_col_tiles;      // blocks along the packed-column axis
     int n_blocks;
+#ifdef JITDB_EXPERIMENT
+    int experiment;       // dev builds: bit0 skip main loop, bit1 skip epilogue
+#endif
 };
-
-// How a block's A rows are fetched for one K phase.
-enum : int { A_X = 0, A_HSUM = 1, A_HS = 2 };
-
 
 // Spread consecutive block ids (which the hardware deals round-robin to the 8
 // XCDs) so that blocks sharing an A row tile land on the same XCD and L2.
@@ -200,141 +208,230 @@ __device__ __forceinline__ void mfma_step(const uint4 &a, const uint4 &b, floatx
     }
 }
 
-// One K phase of the block GEMM: acc[i][g] += A_tile x B_tile^T over k in [0, Kp).
-//   A_KIND  where A rows come from (see above); B rows come from `Bsrc` (row stride Kp)
-//   NG      number of 32-column tiles of B each wave multiplies (gate tiles 0..NG-1)
+// What one thread holds of a K stage on its way from global memory to LDS:
+// 32 bytes of one A row and 16 bytes of each of four B rows.
+struct StageRegs {
+    uint4 a0, a1;
+    uint4 b0, b1, b2, b3;
+};
+
+// The block GEMM.  K runs over "stages" of 64 bytes per row: first the x / W
+// part (n_x stages), then the h / U part (n_h stages), as one software pipeline
+// across both parts: the global loads of stage s+1 are issued before the MFMAs
+// of stage s and land in the other LDS buffer after them.
+//
 // LDS layout per stage: row r at r*kLdsStride, K contiguous.  In each 16-wide
 // (bf16) or 8-wide (fp32) K group, lanes 0-31 take the first 16 bytes and
 // lanes 32-63 the next 16 for A and B alike; since the same assignment is
 // used on both operands any such split of K is a valid MFMA schedule.
-template <typename T, int A_KIND, int NG>
-__device__ __forceinline__ void gemm_phase(const LevelArgs &a, char *lds_a, char *lds_b,
-                                           const int *row_node, int tile_row0, int Kp,
-                                           const T *Bsrc, const int (&b_rows)[4], const bool (&b_need)[4],
+//
+// Staging map: thread t moves bytes [(t&1)*32, +32) of A row t/2, and the
+// 16-byte piece t&3 of B rows (t/128)*128 + g*32 + (t/4)%32 for g = 0..3, so
+// that g is the gate (or, for the projection, the unit tile) and whole gates
+// can be skipped at compile time.
+template <typename T, int MODE>
+__device__ __forceinline__ void block_gemm(const LevelArgs &a, char *lds_a, char *lds_b,
+                                           const int *row_node, int tile_row0, int col_tile,
                                            floatx16 (&acc)[2][4]) {
     constexpr int BK = Traits<T>::BK;
-    constexpr int VEC = Traits<T>::VEC;
-    // A chunks: X phase uses 4-element pieces (x rows are only 4-element aligned), others 16 bytes
-    constexpr int A_CH_ELEMS = (A_KIND == A_X) ? 4 : VEC;
-    constexpr int A_CH_BYTES = A_CH_ELEMS * (int)sizeof(T);
-    constexpr int A_CPR = BK / A_CH_ELEMS;                 // chunks per row per stage
-    constexpr int A_PER_THREAD = kBM * A_CPR / kThreads;   // 2 or 4
-    constexpr int B_CPR = BK / VEC;                        // 4
-    constexpr int B_PER_THREAD = kBN * B_CPR / kThreads;   // 4
+    constexpr int ESZ = (int)sizeof(T);
+    constexpr bool HAS_X = (MODE != MODE_PROJ);
+    constexpr bool HAS_H = (MODE != MODE_LEAF);
+    constexpr int NG_X = (MODE == MODE_LEAF) ? 3 : 4;      // gate tiles multiplied in the x part
+    constexpr int NG_H = (MODE == MODE_INTERNAL) ? 3 : 4;  // ... in the h part (U_f h~ is not needed)
 
     const int t = threadIdx.x;
     const int lane = t & 63, wave = t >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int hf = lane >> 5, l32 = lane & 31;
 
-    // per-thread A sources
-    const T *a_ptr[A_PER_THREAD];
-    int a_lds[A_PER_THREAD];
-    int a_k[A_PER_THREAD];
-#pragma unroll
-    for (int i = 0; i < A_PER_THREAD; ++i) {
-        const int c = t + i * kThreads;
-        const int r = c / A_CPR, ch = c % A_CPR;
-        a_lds[i] = r * kLdsStride + ch * A_CH_BYTES;
-        a_k[i] = ch * A_CH_ELEMS;
-        const int grow = tile_row0 + r;
-        if (grow < a.n_rows) {
-            if constexpr (A_KIND == A_X)
-                a_ptr[i] = static_cast<const T *>(a.x) + (int64_t)row_node[r] * a.D + a_k[i];
-            else if constexpr (A_KIND == A_HSUM)
-                a_ptr[i] = static_cast<const T *>(a.hsum) + (int64_t)grow * a.Hp + a_k[i];
-            else
-                a_ptr[i] = static_cast<const T *>(a.hs) + (int64_t)row_node[r] * a.Hp + a_k[i];
+    const int n_x = HAS_X ? a.Dp / BK : 0;
+    const int n_h = HAS_H ? a.Hp / BK : 0;
+
+    // ---- sources.  Rows past the end of the level are clamped to the last row:
+    //      they are computed twice and stored never.
+    const int ar = t >> 1;
+    int grow = tile_row0 + ar;
+    if (grow >= a.n_rows) grow = a.n_rows - 1;
+    const int anode = row_node[grow - tile_row0];
+    const char *ax = nullptr, *ah = nullptr;
+    if constexpr (HAS_X)
+        ax = static_cast<const char *>(a.x) + ((int64_t)anode * a.D) * ESZ + (t & 1) * 32;
+    if constexpr (MODE == MODE_INTERNAL)
+        ah = static_cast<const char *>(a.hsum) + ((int64_t)grow * a.Hp) * ESZ + (t & 1) * 32;
+    if constexpr (MODE == MODE_PROJ)
+        ah = static_cast<const char *>(a.hs) + ((int64_t)anode * a.Hp) * ESZ + (t & 1) * 32;
+    const int a_k = (t & 1) * (32 / ESZ);   // first element of this thread's A piece within a stage
+
+    // B rows: one pointer per part plus a uniform stride from one gate (or, for the
+    // projection, one unit tile of forget rows) to the next.  The packed U has
+    // zero rows up to a multiple of eight unit tiles, so no row needs a clamp.
+    const char *bw = nullptr, *bu = nullptr;
+    int64_t bw_gate = 0, bu_gate = 0;
+    {
+        const int uu = (t >> 2) & 31, half = t >> 7;
+        if constexpr (MODE == MODE_PROJ) {
+            const int64_t row = (int64_t)(col_tile * 8 + half * 4) * kGateTile + 3 * kUnit + uu;
+            bu = static_cast<const char *>(a.Up) + row * a.Hp * ESZ + (t & 3) * 16;
+            bu_gate = (int64_t)kGateTile * a.Hp * ESZ;
         } else {
-            a_ptr[i] = nullptr;
+            const int64_t row = (int64_t)col_tile * kBN + half * kGateTile + uu;
+            bw = static_cast<const char *>(a.Wp) + row * a.Dp * ESZ + (t & 3) * 16;
+            bw_gate = (int64_t)kUnit * a.Dp * ESZ;
+            bu = static_cast<const char *>(a.Up) + row * a.Hp * ESZ + (t & 3) * 16;
+            bu_gate = (int64_t)kUnit * a.Hp * ESZ;
         }
     }
-    const T *b_ptr[B_PER_THREAD];
-    int b_lds[B_PER_THREAD];
-#pragma unroll
-    for (int i = 0; i < B_PER_THREAD; ++i) {
-        const int c = t + i * kThreads;
-        const int r = c / B_CPR, ch = c % B_CPR;   // r = t/4 + 64 i
-        b_lds[i] = r * kLdsStride + ch * 16;
-        b_ptr[i] = Bsrc + (int64_t)b_rows[i] * Kp + ch * VEC;
-    }
-
-    uint4 a_reg[A_PER_THREAD];
-    uint4 b_reg[B_PER_THREAD];
-    const int k_limit = (A_KIND == A_X) ? a.D : Kp;
-
-    auto load_global = [&](int k0) {
-#pragma unroll
-        for (int i = 0; i < A_PER_THREAD; ++i) {
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (a_ptr[i] != nullptr && (k0 + a_k[i]) < k_limit) {
-                if constexpr (A_CH_BYTES == 16) {
-                    v = *reinterpret_cast<const uint4 *>(a_ptr[i] + k0);
-                } else {
-                    const uint2 w = *reinterpret_cast<const uint2 *>(a_ptr[i] + k0);
-                    v.x = w.x; v.y = w.y;
-                }
-            }
-            a_reg[i] = v;
-        }
-#pragma unroll
-        for (int i = 0; i < B_PER_THREAD; ++i)
-            if (b_need[i]) b_reg[i] = *reinterpret_cast<const uint4 *>(b_ptr[i] + k0);
-    };
-    auto store_lds = [&](int buf) {
-        char *sa = lds_a + buf * (kBM * kLdsStride);
-        char *sb = lds_b + buf * (kBN * kLdsStride);
-#pragma unroll
-        for (int i = 0; i < A_PER_THREAD; ++i) {
-            if constexpr (A_CH_BYTES == 16)
-                *reinterpret_cast<uint4 *>(sa + a_lds[i]) = a_reg[i];
-            else
-                *reinterpret_cast<uint2 *>(sa + a_lds[i]) = make_uint2(a_reg[i].x, a_reg[i].y);
-        }
-#pragma unroll
-        for (int i = 0; i < B_PER_THREAD; ++i)
-            if (b_need[i]) *reinterpret_cast<uint4 *>(sb + b_lds[i]) = b_reg[i];
-    };
-
+    const int a_wr = ar * kLdsStride + (t & 1) * 32;
+    const int b_wr = ((t >> 7) * kGateTile + ((t >> 2) & 31)) * kLdsStride + (t & 3) * 16;
     const int a_rd = (wm * 64 + l32) * kLdsStride + hf * 16;
     const int b_rd = (wn * 128 + l32) * kLdsStride + hf * 16;
-    auto compute = [&](int buf) {
+
+    auto ld16 = [](const char *p) { return *reinterpret_cast<const uint4 *>(p); };
+
+    // ---- global -> registers, one stage ---------------------------------------------
+    // x part, stage wholly inside D
+    auto fetch_x = [&](int s, StageRegs &r) {
+        const int64_t kb = (int64_t)s * BK * ESZ;
+        const char *p = ax + kb;
+        if constexpr (ESZ == 4) {
+            r.a0 = ld16(p);
+            r.a1 = ld16(p + 16);
+        } else {   // bf16 rows of x are only 8-byte aligned
+            const uint2 q0 = *reinterpret_cast<const uint2 *>(p);
+            const uint2 q1 = *reinterpret_cast<const uint2 *>(p + 8);
+            const uint2 q2 = *reinterpret_cast<const uint2 *>(p + 16);
+            const uint2 q3 = *reinterpret_cast<const uint2 *>(p + 24);
+            r.a0 = make_uint4(q0.x, q0.y, q1.x, q1.y);
+            r.a1 = make_uint4(q2.x, q2.y, q3.x, q3.y);
+        }
+        const char *pb = bw + kb;
+        r.b0 = ld16(pb);
+        r.b1 = ld16(pb + bw_gate);
+        r.b2 = ld16(pb + 2 * bw_gate);
+        if constexpr (NG_X == 4) r.b3 = ld16(pb + 3 * bw_gate);
+    };
+    // x part, last stage: zero-fill past D in 8-byte pieces (D % 4 == 0, so a piece
+    // of 4 bf16 or 2 floats is wholly inside or wholly outside)
+    auto fetch_x_tail = [&](int s, StageRegs &r) {
+        const int k0 = s * BK;
+        const int64_t kb = (int64_t)k0 * ESZ;
+        const char *p = ax + kb;
+        constexpr int PIECE = 8 / ESZ;
+        uint2 q0 = make_uint2(0u, 0u), q1 = q0, q2 = q0, q3 = q0;
+        if (k0 + a_k + 0 * PIECE < a.D) q0 = *reinterpret_cast<const uint2 *>(p);
+        if (k0 + a_k + 1 * PIECE < a.D) q1 = *reinterpret_cast<const uint2 *>(p + 8);
+        if (k0 + a_k + 2 * PIECE < a.D) q2 = *reinterpret_cast<const uint2 *>(p + 16);
+        if (k0 + a_k + 3 * PIECE < a.D) q3 = *reinterpret_cast<const uint2 *>(p + 24);
+        r.a0 = make_uint4(q0.x, q0.y, q1.x, q1.y);
+        r.a1 = make_uint4(q2.x, q2.y, q3.x, q3.y);
+        const char *pb = bw + kb;
+        r.b0 = ld16(pb);
+        r.b1 = ld16(pb + bw_gate);
+        r.b2 = ld16(pb + 2 * bw_gate);
+        if constexpr (NG_X == 4) r.b3 = ld16(pb + 3 * bw_gate);
+    };
+    auto fetch_h = [&](int s, StageRegs &r) {
+        const int64_t kb = (int64_t)s * BK * ESZ;
+        r.a0 = ld16(ah + kb);
+        r.a1 = ld16(ah + kb + 16);
+        r.b0 = ld16(bu + kb);
+        r.b1 = ld16(bu + kb + bu_gate);
+        r.b2 = ld16(bu + kb + 2 * bu_gate);
+        if constexpr (NG_H == 4) r.b3 = ld16(bu + kb + 3 * bu_gate);
+    };
+    // ---- registers -> LDS --------------------------------------------------------------
+    auto stash = [&](const StageRegs &r, int buf, auto ng_tag) {
+        constexpr int NG = decltype(ng_tag)::value;
+        char *sa = lds_a + buf * (kBM * kLdsStride) + a_wr;
+        char *sb = lds_b + buf * (kBN * kLdsStride) + b_wr;
+        *reinterpret_cast<uint4 *>(sa) = r.a0;
+        *reinterpret_cast<uint4 *>(sa + 16) = r.a1;
+        *reinterpret_cast<uint4 *>(sb) = r.b0;
+        *reinterpret_cast<uint4 *>(sb + 32 * kLdsStride) = r.b1;
+        *reinterpret_cast<uint4 *>(sb + 64 * kLdsStride) = r.b2;
+        if constexpr (NG == 4) *reinterpret_cast<uint4 *>(sb + 96 * kLdsStride) = r.b3;
+    };
+    // ---- LDS -> MFMA -------------------------------------------------------------------
+    auto mma = [&](int buf, auto ng_tag) {
+        constexpr int NG = decltype(ng_tag)::value;
         const char *sa = lds_a + buf * (kBM * kLdsStride) + a_rd;
         const char *sb = lds_b + buf * (kBN * kLdsStride) + b_rd;
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
+        for (int h = 0; h < 2; ++h) {
             uint4 av[2], bv[NG];
 #pragma unroll
             for (int i = 0; i < 2; ++i)
-                av[i] = *reinterpret_cast<const uint4 *>(sa + i * 32 * kLdsStride + s * 32);
+                av[i] = *reinterpret_cast<const uint4 *>(sa + i * 32 * kLdsStride + h * 32);
 #pragma unroll
             for (int g = 0; g < NG; ++g)
-                bv[g] = *reinterpret_cast<const uint4 *>(sb + g * 32 * kLdsStride + s * 32);
+                bv[g] = *reinterpret_cast<const uint4 *>(sb + g * 32 * kLdsStride + h * 32);
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int g = 0; g < NG; ++g) mfma_step<T>(av[i], bv[g], acc[i][g]);
         }
     };
+    const std::integral_constant<int, NG_X> ngx;
+    const std::integral_constant<int, NG_H> ngh;
 
-    const int n_kt = Kp / BK;
-    load_global(0);
-    store_lds(0);
-    __syncthreads();
-    for (int kt = 0; kt < n_kt; ++kt) {
-        const bool more = (kt + 1) < n_kt;
-        if (more) load_global((kt + 1) * BK);
-        compute(kt & 1);
-        if (more) store_lds((kt + 1) & 1);
+    // The pipeline, written out part by part so that every loop body is straight-line
+    // code: while stage s is multiplied out of one LDS buffer, stage s+1 travels
+    // global -> registers -> the other buffer.
+    StageRegs r;
+    int buf = 0;
+    if constexpr (HAS_X) {
+        const bool tail = (n_x * BK > a.D);      // the last x stage needs zero fill
+        if (n_x == 1 && tail) fetch_x_tail(0, r); else fetch_x(0, r);
+        stash(r, 0, ngx);
         __syncthreads();
+        for (int s = 0; s + 2 < n_x; ++s) {       // next stage is a full x stage
+            fetch_x(s + 1, r);
+            mma(buf, ngx);
+            stash(r, buf ^ 1, ngx);
+            __syncthreads();
+            buf ^= 1;
+        }
+        if (n_x > 1) {                            // next stage is the last x stage
+            if (tail) fetch_x_tail(n_x - 1, r); else fetch_x(n_x - 1, r);
+            mma(buf, ngx);
+            stash(r, buf ^ 1, ngx);
+            __syncthreads();
+            buf ^= 1;
+        }
+        if constexpr (HAS_H) {                    // last x stage; next is the first h stage
+            fetch_h(0, r);
+            mma(buf, ngx);
+            stash(r, buf ^ 1, ngh);
+            __syncthreads();
+            buf ^= 1;
+        } else {
+            mma(buf, ngx);
+        }
+    } else {
+        fetch_h(0, r);
+        stash(r, 0, ngh);
+        __syncthreads();
+    }
+    if constexpr (HAS_H) {
+        for (int s = 0; s + 1 < n_h; ++s) {
+            fetch_h(s + 1, r);
+            mma(buf, ngh);
+            stash(r, buf ^ 1, ngh);
+            __syncthreads();
+            buf ^= 1;
+        }
+        mma(buf, ngh);
     }
 }
 
 template <typename T, int MODE>
 __global__ void __launch_bounds__(kThreads, 2)
 level_kernel(const LevelArgs a) {
-    __shared__ __attribute__((aligned(16))) char lds_a[2 * kBM * kLdsStride];
-    __shared__ __attribute__((aligned(16))) char lds_b[2 * kBN * kLdsStride];
+    __shared__ __attribute__((aligned(16))) char lds[2 * (kBM + kBN) * kLdsStride];
+    char *lds_a = lds;
+    char *lds_b = lds + 2 * kBM * kLdsStride;
+    static_assert(3 * kEpiRows * kEpiStride * 4 <= 2 * (kBM + kBN) * kLdsStride, "epilogue tiles must fit the staging buffers");
     __shared__ int row_node[kBM];
     __shared__ int row_cb[kBM];
     __shared__ int row_ce[kBM];
@@ -373,40 +470,23 @@ level_kernel(const LevelArgs a) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][g][v] = 0.0f;
 
-    // B rows this thread stages: LDS row r = t/4 + 64 i  ->  packed weight row
-    int b_rows[4];
-    bool need_all[4], need_iou[4];
-    const int n_unit_tiles = a.Hu / kUnit;
+#ifdef JITDB_EXPERIMENT
+    if (!(a.experiment & 1))
+#endif
+    block_gemm<T, MODE>(a, lds_a, lds_b, row_node, tile_row0, col_tile, acc);
+#ifdef JITDB_EXPERIMENT
+    if (a.experiment & 2) {
+        float sum = 0.0f;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int r = (t >> 2) + 64 * i;              // 0..255 within the block's column tile
-        if constexpr (MODE == MODE_PROJ) {
-            // eight unit tiles of forget rows side by side
-            int ut = col_tile * 8 + (r >> 5);
-            if (ut >= n_unit_tiles) ut = n_unit_tiles - 1;   // results of such columns are dropped
-            b_rows[i] = ut * kGateTile + 3 * kUnit + (r & 31);
-            need_all[i] = true;
-            need_iou[i] = true;
-        } else {
-            b_rows[i] = col_tile * kBN + r;
-            const bool is_f = (r & 127) >= 3 * kUnit;
-            need_all[i] = (MODE == MODE_LEAF) ? !is_f : true;
-            need_iou[i] = !is_f;
-        }
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) sum += acc[i][g][v];
+        if (sum == 123.456f) a.c_out[0] = sum;
+        return;
     }
-
-    if constexpr (MODE == MODE_LEAF) {
-        gemm_phase<T, A_X, 3>(a, lds_a, lds_b, row_node, tile_row0, a.Dp,
-                              static_cast<const T *>(a.Wp), b_rows, need_all, acc);
-    } else if constexpr (MODE == MODE_INTERNAL) {
-        gemm_phase<T, A_X, 4>(a, lds_a, lds_b, row_node, tile_row0, a.Dp,
-                              static_cast<const T *>(a.Wp), b_rows, need_all, acc);
-        gemm_phase<T, A_HSUM, 3>(a, lds_a, lds_b, row_node, tile_row0, a.Hp,
-                                 static_cast<const T *>(a.Up), b_rows, need_iou, acc);
-    } else {
-        gemm_phase<T, A_HS, 4>(a, lds_a, lds_b, row_node, tile_row0, a.Hp,
-                               static_cast<const T *>(a.Up), b_rows, need_all, acc);
-    }
+#endif
 
     // ---- epilogue: accumulator element v of tile (i, g) is row
     //      wm*64 + i*32 + (v/4)*8 + hf*4 + v%4, column l32 of gate / unit tile g
@@ -421,50 +501,136 @@ level_kernel(const LevelArgs a) {
                 for (int v = 0; v < 16; ++v) {
                     const int r = wm * 64 + i * 32 + (v >> 2) * 8 + hf * 4 + (v & 3);
                     const int node = row_node[r];
-                    if (node >= 0) a.P[(int64_t)node * a.H + unit] = acc[i][g][v];
+                    if (node >= 0) a.P[(int64_t)node * a.Hq + unit] = acc[i][g][v];
                 }
         }
     } else {
-        const int unit = (col_tile * 2 + wn) * kUnit + l32;
+        // The cell update runs row-major.  In two passes of 64 rows the gate values
+        // go through LDS (the staging buffers are free now): each wave writes
+        // i*u, o and the x part of the forget gate for its 32 units, then every
+        // thread takes four rows x four consecutive units, so that the rows of the
+        // children (P_k and c_k) are read in 16-byte pieces, 256 bytes per row and
+        // array, with four rows in flight per thread.
         const int pcol = col_tile * kBN + wn * kGateTile + l32;   // packed row of gate i for this unit
         const float bi = a.bp[pcol], bo = a.bp[pcol + kUnit], bu = a.bp[pcol + 2 * kUnit];
         float bf = 0.0f;
         if constexpr (MODE == MODE_INTERNAL) bf = a.bp[pcol + 3 * kUnit];
+        float *s_iu = reinterpret_cast<float *>(lds);
+        float *s_o = s_iu + kEpiRows * kEpiStride;
+        float *s_fx = s_o + kEpiRows * kEpiStride;
         T *h_out = static_cast<T *>(a.h_out);
         T *hs_out = static_cast<T *>(a.hs_out);
         const bool separate_hs = (a.hs_out != a.h_out);
-        if (unit < a.Hp) {
+        const bool separate_cs = (a.cs != a.c_out);
+        const bool vec_ok = (a.H & 3) == 0;
+        const int unit0 = col_tile * 64 + (t & 15) * 4;
+        // unit groups past the padded width read the first group instead (and store nothing)
+        const int unit_ld = unit0 < a.Hq ? unit0 : 0;
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+        for (int p = 0; p < 2; ++p) {
+            __syncthreads();   // main loop (p = 0) or the previous pass (p = 1) is done with LDS
+            {
+                const int col = wn * 32 + l32;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int r = wm * 64 + i * 32 + (v >> 2) * 8 + hf * 4 + (v & 3);
-                    const int node = row_node[r];
-                    if (node < 0) continue;
-                    if (unit >= a.H) {   // zero pad column of the padded h copy
-                        if (separate_hs) hs_out[(int64_t)node * a.Hp + unit] = T(0);
-                        continue;
+                    const int rl = wm * 32 + (v >> 2) * 8 + hf * 4 + (v & 3);
+                    const float gi = sigmoid_t<T>(acc[p][0][v] + bi);
+                    const float go = sigmoid_t<T>(acc[p][1][v] + bo);
+                    const float gu = tanh_t<T>(acc[p][2][v] + bu);
+                    s_iu[rl * kEpiStride + col] = gi * gu;
+                    s_o[rl * kEpiStride + col] = go;
+                    if constexpr (MODE == MODE_INTERNAL) s_fx[rl * kEpiStride + col] = acc[p][3][v] + bf;
+                }
+            }
+            __syncthreads();
+            float4 cc[4], go4[4], fx4[4];
+            int node[4], e[4], ce[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int rl = (t >> 4) + 16 * q;
+                const int tr = (rl >> 5) * 64 + p * 32 + (rl & 31);
+                node[q] = row_node[tr];
+                e[q] = row_cb[tr];
+                ce[q] = row_ce[tr];
+                const int so = rl * kEpiStride + (t & 15) * 4;
+                cc[q] = *reinterpret_cast<const float4 *>(s_iu + so);
+                go4[q] = *reinterpret_cast<const float4 *>(s_o + so);
+                if constexpr (MODE == MODE_INTERNAL) fx4[q] = *reinterpret_cast<const float4 *>(s_fx + so);
+            }
+            if constexpr (MODE == MODE_INTERNAL) {
+                // One child of each of the four rows per round.  A row that has run out
+                // of children re-reads its last one with weight zero, which keeps the
+                // loads unconditional and independent of each other.
+                int64_t kofs[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) kofs[q] = unit_ld;
+                while ((e[0] < ce[0]) | (e[1] < ce[1]) | (e[2] < ce[2]) | (e[3] < ce[3])) {
+                    float wgt[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const bool has = e[q] < ce[q];
+                        wgt[q] = has ? 1.0f : 0.0f;
+                        if (has) kofs[q] = (int64_t)a.child_idx[e[q]] * a.Hq + unit_ld;
+                        ++e[q];
                     }
-                    const float gi = sigmoid_t<T>(acc[i][0][v] + bi);
-                    const float go = sigmoid_t<T>(acc[i][1][v] + bo);
-                    const float gu = tanh_t<T>(acc[i][2][v] + bu);
-                    float cc = gi * gu;
-                    if constexpr (MODE == MODE_INTERNAL) {
-                        const float fx = acc[i][3][v] + bf;
-                        const int cb = row_cb[r], ce = row_ce[r];
-                        for (int e = cb; e < ce; ++e) {
-                            const int64_t k = a.child_idx[e];
-                            const float pk = a.P[k * a.H + unit];
-                            const float ck = a.c_out[k * a.H + unit];
-                            cc += sigmoid_t<T>(fx + pk) * ck;
+                    float4 pk[4], ck[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        pk[q] = *reinterpret_cast<const float4 *>(a.P + kofs[q]);
+                        ck[q] = *reinterpret_cast<const float4 *>(a.cs + kofs[q]);
+                    }
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        cc[q].x += wgt[q] * sigmoid_t<T>(fx4[q].x + pk[q].x) * ck[q].x;
+                        cc[q].y += wgt[q] * sigmoid_t<T>(fx4[q].y + pk[q].y) * ck[q].y;
+                        cc[q].z += wgt[q] * sigmoid_t<T>(fx4[q].z + pk[q].z) * ck[q].z;
+                        cc[q].w += wgt[q] * sigmoid_t<T>(fx4[q].w + pk[q].w) * ck[q].w;
+                    }
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if (node[q] < 0) continue;
+                const float c4[4] = {cc[q].x, cc[q].y, cc[q].z, cc[q].w};
+                const float o4[4] = {go4[q].x, go4[q].y, go4[q].z, go4[q].w};
+                T hv[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) hv[j] = from_f32<T>(o4[j] * tanh_t<T>(c4[j]));
+                const int64_t nd = node[q];
+                if (vec_ok) {
+                    if (unit0 < a.H) {
+                        *reinterpret_cast<float4 *>(a.c_out + nd * a.H + unit0) = cc[q];
+                        if constexpr (sizeof(T) == 4) {
+                            const float4 h4 = make_float4(hv[0], hv[1], hv[2], hv[3]);
+                            *reinterpret_cast<float4 *>(h_out + nd * a.H + unit0) = h4;
+                            if (separate_hs) *reinterpret_cast<float4 *>(hs_out + nd * a.Hp + unit0) = h4;
+                        } else {
+                            const uint2 h2 = make_uint2((uint32_t)hv[0] | ((uint32_t)hv[1] << 16),
+                                                        (uint32_t)hv[2] | ((uint32_t)hv[3] << 16));
+                            *reinterpret_cast<uint2 *>(h_out + nd * a.H + unit0) = h2;
+                            if (separate_hs) *reinterpret_cast<uint2 *>(hs_out + nd * a.Hp + unit0) = h2;
+                        }
+                    } else if (separate_hs && unit0 < a.Hp) {   // zero pad columns of the padded h copy
+                        if constexpr (sizeof(T) == 4)
+                            *reinterpret_cast<float4 *>(hs_out + nd * a.Hp + unit0) = make_float4(0.f, 0.f, 0.f, 0.f);
+                        else
+                            *reinterpret_cast<uint2 *>(hs_out + nd * a.Hp + unit0) = make_uint2(0u, 0u);
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int unit = unit0 + j;
+                        if (unit < a.H) {
+                            a.c_out[nd * a.H + unit] = c4[j];
+                            if (separate_cs) a.cs[nd * a.Hq + unit] = c4[j];
+                            h_out[nd * a.H + unit] = hv[j];
+                            if (separate_hs) hs_out[nd * a.Hp + unit] = hv[j];
+                        } else if (separate_hs && unit < a.Hp) {
+                            hs_out[nd * a.Hp + unit] = T(0);
                         }
                     }
-                    const float hh = go * tanh_t<T>(cc);
-                    a.c_out[(int64_t)node * a.H + unit] = cc;
-                    const T hv = from_f32<T>(hh);
-                    h_out[(int64_t)node * a.H + unit] = hv;
-                    if (separate_hs) hs_out[(int64_t)node * a.Hp + unit] = hv;
                 }
+            }
         }
     }
 }
@@ -499,23 +665,30 @@ struct ForwardWs {
     void *Wp, *Up;
     float *bp;
     void *hsum;
-    void *hs;     // nullptr-sized when h_out can serve (H == Hp)
+    void *hs;     // nullptr when h_out can serve (H == Hp)
     float *P;
+    float *cs;    // nullptr when c_out can serve (H == Hq)
     size_t bytes;
 };
 
 struct Dims {
     int D, H, Dp, Hp, Hu, NP;
+    int Hq;       // H rounded up to 4: row stride of the fp32 side buffers (P, padded c)
+    int NPU;      // rows of the packed U: padded so the projection's 8-unit-tile blocks stay inside
     size_t esz;
 };
 
 Dims make_dims(int D, int H, jitdb_dtype dtype) {
     Dims d;
     d.D = D; d.H = H;
-    d.Dp = (int)round_up(D, kKPad);
-    d.Hp = (int)round_up(H, kKPad);
+    // K is padded to whole pipeline stages, so that only the last x stage can straddle D
+    const int kpad = dtype == JITDB_F32 ? Traits<float>::BK : Traits<bf16_t>::BK;
+    d.Dp = (int)round_up(D, kpad);
+    d.Hp = (int)round_up(H, kpad);
     d.Hu = (int)round_up(H, 2 * kUnit);
     d.NP = 4 * d.Hu;
+    d.Hq = (int)round_up(H, 4);
+    d.NPU = (int)round_up(d.Hu / kUnit, 8) * kGateTile;
     d.esz = dtype == JITDB_F32 ? 4 : 2;
     return d;
 }
@@ -525,12 +698,12 @@ ForwardWs carve_forward_ws(int64_t n, int64_t e, const Dims &d, void *base) {
     ForwardWs w;
     const int64_t hsum_rows = e < n ? e : n;   // an internal node has at least one child
     w.Wp = c.take<char>((size_t)d.NP * d.Dp * d.esz);
-    w.Up = c.take<char>((size_t)d.NP * d.Hp * d.esz);
+    w.Up = c.take<char>((size_t)d.NPU * d.Hp * d.esz);
     w.bp = c.take<float>(d.NP);
     w.hsum = c.take<char>((size_t)hsum_rows * d.Hp * d.esz);
     w.hs = (d.H == d.Hp) ? nullptr : c.take<char>((size_t)n * d.Hp * d.esz);
-    if (d.H == d.Hp) c.take<char>(0);
-    w.P = c.take<float>((size_t)n * d.H);
+    w.P = c.take<float>((size_t)n * d.Hq);
+    w.cs = (d.H == d.Hq) ? nullptr : c.take<float>((size_t)n * d.Hq);
     w.bytes = c.off;
     return w;
 }
@@ -551,21 +724,26 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
     const int32_t *lp = s->host_level_ptr;
 
     {
-        const int64_t total = (int64_t)d.NP * (d.Dp + d.Hp);
+        const int64_t total = (int64_t)d.NP * d.Dp + (int64_t)d.NPU * d.Hp;
         const unsigned grid = (unsigned)(ceil_div(total, kThreads) < 4096 ? ceil_div(total, kThreads) : 4096);
         ScopedLaunchTimer tm(JITDB_K_PACK, st);
         pack_weights_kernel<T><<<grid, kThreads, 0, st>>>(
-            static_cast<const T *>(W), static_cast<const T *>(U), b, d.D, d.H, d.Dp, d.Hp, d.NP,
+            static_cast<const T *>(W), static_cast<const T *>(U), b, d.D, d.H, d.Dp, d.Hp, d.NP, d.NPU,
             static_cast<T *>(w.Wp), static_cast<T *>(w.Up), w.bp);
         JITDB_LAUNCH_CHECK();
     }
 
     LevelArgs a;
+#ifdef JITDB_EXPERIMENT
+    a.experiment = getenv("JITDB_EXPERIMENT") ? atoi(getenv("JITDB_EXPERIMENT")) : 0;
+#endif
     a.x = x; a.hsum = w.hsum;
     a.hs = w.hs ? w.hs : h_out;
     a.Wp = w.Wp; a.Up = w.Up; a.bp = w.bp;
     a.child_ptr = s->child_ptr; a.child_idx = s->child_idx;
     a.P = w.P; a.c_out = c_out; a.h_out = h_out;
+    a.cs = w.cs ? w.cs : c_out;
+    a.Hq = d.Hq;
     a.hs_out = w.hs ? w.hs : h_out;
     a.D = d.D; a.Dp = d.Dp; a.H = d.H; a.Hp = d.Hp; a.Hu = d.Hu;
 
@@ -677,6 +855,7 @@ extern "C" int jitdb_treelstm_forward(const void *x, const void *W, const void *
     // row pieces are fetched 4 elements at a time (x) and 16 bytes at a time (h when H is unpadded)
     if ((reinterpret_cast<uintptr_t>(x) % (4 * esz)) != 0) return JITDB_E_BADARG;
     if ((reinterpret_cast<uintptr_t>(h_out) & 15) != 0) return JITDB_E_BADARG;
+    if ((reinterpret_cast<uintptr_t>(c_out) & 15) != 0) return JITDB_E_BADARG;
     const int L = s->n_levels;
     if (L < 1 || L > n) return JITDB_E_SCHEDULE;
     if (s->host_level_ptr[0] != 0 || s->host_level_ptr[L] != n) return JITDB_E_SCHEDULE;
