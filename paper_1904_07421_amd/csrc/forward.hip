@@ -44,17 +44,17 @@ constexpr int kGateTile = 128;  // packed rows per unit tile (4 gates x 32 units
 
 constexpr int kEpiRows = 64;    // rows per epilogue pass
 constexpr int kEpiStride = 68;  // floats per epilogue LDS row: 64 units + 4 (keeps 16-byte alignment)
-constexpr int kLdsStride = 80;  // stage row + 16 bytes: 128-bit LDS reads of 32 rows hit distinct banks
+constexpr int kLdsStride = 144; // stage row (128 bytes) + 16: 128-bit LDS reads of 32 rows hit distinct banks
 
 enum : int { MODE_LEAF = 0, MODE_INTERNAL = 1, MODE_PROJ = 2 };
 
 template <typename T> struct Traits;
 template <> struct Traits<float> {
-    static constexpr int BK = 16;   // elements of K per stage
+    static constexpr int BK = 32;   // elements of K per stage (128 bytes)
     static constexpr int VEC = 4;   // elements per 16 bytes
 };
 template <> struct Traits<bf16_t> {
-    static constexpr int BK = 32;
+    static constexpr int BK = 64;
     static constexpr int VEC = 8;
 };
 
@@ -209,26 +209,30 @@ __device__ __forceinline__ void mfma_step(const uint4 &a, const uint4 &b, floatx
 }
 
 // What one thread holds of a K stage on its way from global memory to LDS:
-// 32 bytes of one A row and 16 bytes of each of four B rows.
+// 64 bytes of A rows and 16 bytes of each of eight B rows.
 struct StageRegs {
-    uint4 a0, a1;
-    uint4 b0, b1, b2, b3;
+    uint4 a[4];
+    uint4 b[8];
 };
 
-// The block GEMM.  K runs over "stages" of 64 bytes per row: first the x / W
-// part (n_x stages), then the h / U part (n_h stages), as one software pipeline
-// across both parts: the global loads of stage s+1 are issued before the MFMAs
-// of stage s and land in the other LDS buffer after them.
+// The block GEMM.  K runs over "stages" of 128 bytes per row (one cache line):
+// first the x / W part (n_x stages), then the h / U part (n_h stages), as one
+// software pipeline across both parts.  There is ONE LDS buffer per block: the
+// global loads of stage s+1 are issued before the MFMAs of stage s and written
+// to LDS after them, between two barriers; the second block resident on the CU
+// keeps the matrix cores busy meanwhile.
 //
-// LDS layout per stage: row r at r*kLdsStride, K contiguous.  In each 16-wide
-// (bf16) or 8-wide (fp32) K group, lanes 0-31 take the first 16 bytes and
-// lanes 32-63 the next 16 for A and B alike; since the same assignment is
-// used on both operands any such split of K is a valid MFMA schedule.
+// LDS layout: row r at r*kLdsStride, K contiguous.  In each 16-wide (bf16) or
+// 8-wide (fp32) K group, lanes 0-31 take the first 16 bytes and lanes 32-63 the
+// next 16 for A and B alike; since the same assignment is used on both
+// operands any such split of K is a valid MFMA schedule.
 //
-// Staging map: thread t moves bytes [(t&1)*32, +32) of A row t/2, and the
-// 16-byte piece t&3 of B rows (t/128)*128 + g*32 + (t/4)%32 for g = 0..3, so
-// that g is the gate (or, for the projection, the unit tile) and whole gates
-// can be skipped at compile time.
+// Staging map: eight consecutive lanes move the eight 16-byte pieces of one row
+// (a whole line per row and load instruction); thread t handles piece t&7 of
+// rows t/8 + 32 i.  For B, i & 3 is the gate (or, for the projection, i is the
+// unit tile), so whole gates can be skipped at compile time.  Rows of x in
+// bf16 are only 8-byte aligned: there sixteen lanes move 8-byte pieces of one
+// row, thread t handling piece t&15 of rows t/16 + 16 i.
 template <typename T, int MODE>
 __device__ __forceinline__ void block_gemm(const LevelArgs &a, char *lds_a, char *lds_b,
                                            const int *row_node, int tile_row0, int col_tile,
@@ -239,6 +243,7 @@ __device__ __forceinline__ void block_gemm(const LevelArgs &a, char *lds_a, char
     constexpr bool HAS_H = (MODE != MODE_LEAF);
     constexpr int NG_X = (MODE == MODE_LEAF) ? 3 : 4;      // gate tiles multiplied in the x part
     constexpr int NG_H = (MODE == MODE_INTERNAL) ? 3 : 4;  // ... in the h part (U_f h~ is not needed)
+    constexpr bool X8 = HAS_X && (ESZ == 2);               // x pieces of 8 bytes
 
     const int t = threadIdx.x;
     const int lane = t & 63, wave = t >> 6;
@@ -248,117 +253,132 @@ __device__ __forceinline__ void block_gemm(const LevelArgs &a, char *lds_a, char
     const int n_x = HAS_X ? a.Dp / BK : 0;
     const int n_h = HAS_H ? a.Hp / BK : 0;
 
-    // ---- sources.  Rows past the end of the level are clamped to the last row:
+    // ---- A sources.  Rows past the end of the level are clamped to the last row:
     //      they are computed twice and stored never.
-    const int ar = t >> 1;
-    int grow = tile_row0 + ar;
-    if (grow >= a.n_rows) grow = a.n_rows - 1;
-    const int anode = row_node[grow - tile_row0];
-    const char *ax = nullptr, *ah = nullptr;
-    if constexpr (HAS_X)
-        ax = static_cast<const char *>(a.x) + ((int64_t)anode * a.D) * ESZ + (t & 1) * 32;
-    if constexpr (MODE == MODE_INTERNAL)
-        ah = static_cast<const char *>(a.hsum) + ((int64_t)grow * a.Hp) * ESZ + (t & 1) * 32;
-    if constexpr (MODE == MODE_PROJ)
-        ah = static_cast<const char *>(a.hs) + ((int64_t)anode * a.Hp) * ESZ + (t & 1) * 32;
-    const int a_k = (t & 1) * (32 / ESZ);   // first element of this thread's A piece within a stage
-
-    // B rows: one pointer per part plus a uniform stride from one gate (or, for the
-    // projection, one unit tile of forget rows) to the next.  The packed U has
-    // zero rows up to a multiple of eight unit tiles, so no row needs a clamp.
-    const char *bw = nullptr, *bu = nullptr;
-    int64_t bw_gate = 0, bu_gate = 0;
-    {
-        const int uu = (t >> 2) & 31, half = t >> 7;
-        if constexpr (MODE == MODE_PROJ) {
-            const int64_t row = (int64_t)(col_tile * 8 + half * 4) * kGateTile + 3 * kUnit + uu;
-            bu = static_cast<const char *>(a.Up) + row * a.Hp * ESZ + (t & 3) * 16;
-            bu_gate = (int64_t)kGateTile * a.Hp * ESZ;
-        } else {
-            const int64_t row = (int64_t)col_tile * kBN + half * kGateTile + uu;
-            bw = static_cast<const char *>(a.Wp) + row * a.Dp * ESZ + (t & 3) * 16;
-            bw_gate = (int64_t)kUnit * a.Dp * ESZ;
-            bu = static_cast<const char *>(a.Up) + row * a.Hp * ESZ + (t & 3) * 16;
-            bu_gate = (int64_t)kUnit * a.Hp * ESZ;
+    auto clamp_row = [&](int r) {
+        const int g = tile_row0 + r;
+        return g < a.n_rows ? g : a.n_rows - 1;
+    };
+    int xrow[X8 ? 8 : 4];       // node ids of the x rows this thread moves
+    int hrow[4];                // row index into hsum (level row) or hs (node id)
+    if constexpr (HAS_X) {
+#pragma unroll
+        for (int i = 0; i < (X8 ? 8 : 4); ++i) {
+            const int r = X8 ? (t >> 4) + 16 * i : (t >> 3) + 32 * i;
+            xrow[i] = row_node[clamp_row(r) - tile_row0];
         }
     }
-    const int a_wr = ar * kLdsStride + (t & 1) * 32;
-    const int b_wr = ((t >> 7) * kGateTile + ((t >> 2) & 31)) * kLdsStride + (t & 3) * 16;
+    if constexpr (HAS_H) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int g = clamp_row((t >> 3) + 32 * i);
+            hrow[i] = (MODE == MODE_INTERNAL) ? g : row_node[g - tile_row0];
+        }
+    }
+    const char *xbase = static_cast<const char *>(a.x) + (X8 ? (t & 15) * 8 : (t & 7) * 16);
+    const char *hbase = static_cast<const char *>(MODE == MODE_INTERNAL ? a.hsum : a.hs) + (t & 7) * 16;
+    const int64_t x_row_bytes = (int64_t)a.D * ESZ, h_row_bytes = (int64_t)a.Hp * ESZ;
+
+    // ---- B sources: one pointer per part plus a uniform stride from one staged row
+    //      group (32 rows) to the next.  The packed U has zero rows up to a multiple of
+    //      eight unit tiles, so the projection needs no clamp.
+    const char *bw = nullptr, *bu = nullptr;
+    int64_t bw_step = 0, bu_step = 0;
+    {
+        const int uu = t >> 3;
+        if constexpr (MODE == MODE_PROJ) {
+            const int64_t row = (int64_t)(col_tile * 8) * kGateTile + 3 * kUnit + uu;
+            bu = static_cast<const char *>(a.Up) + row * a.Hp * ESZ + (t & 7) * 16;
+            bu_step = (int64_t)kGateTile * a.Hp * ESZ;
+        } else {
+            const int64_t row = (int64_t)col_tile * kBN + uu;
+            bw = static_cast<const char *>(a.Wp) + row * a.Dp * ESZ + (t & 7) * 16;
+            bw_step = (int64_t)kUnit * a.Dp * ESZ;
+            bu = static_cast<const char *>(a.Up) + row * a.Hp * ESZ + (t & 7) * 16;
+            bu_step = (int64_t)kUnit * a.Hp * ESZ;
+        }
+    }
+    const int a_wr16 = (t >> 3) * kLdsStride + (t & 7) * 16;
+    const int a_wr8 = (t >> 4) * kLdsStride + (t & 15) * 8;
+    const int b_wr = (t >> 3) * kLdsStride + (t & 7) * 16;
     const int a_rd = (wm * 64 + l32) * kLdsStride + hf * 16;
     const int b_rd = (wn * 128 + l32) * kLdsStride + hf * 16;
 
     auto ld16 = [](const char *p) { return *reinterpret_cast<const uint4 *>(p); };
+    auto ld8 = [](const char *p) { return *reinterpret_cast<const uint2 *>(p); };
 
     // ---- global -> registers, one stage ---------------------------------------------
-    // x part, stage wholly inside D
-    auto fetch_x = [&](int s, StageRegs &r) {
-        const int64_t kb = (int64_t)s * BK * ESZ;
-        const char *p = ax + kb;
-        if constexpr (ESZ == 4) {
-            r.a0 = ld16(p);
-            r.a1 = ld16(p + 16);
-        } else {   // bf16 rows of x are only 8-byte aligned
-            const uint2 q0 = *reinterpret_cast<const uint2 *>(p);
-            const uint2 q1 = *reinterpret_cast<const uint2 *>(p + 8);
-            const uint2 q2 = *reinterpret_cast<const uint2 *>(p + 16);
-            const uint2 q3 = *reinterpret_cast<const uint2 *>(p + 24);
-            r.a0 = make_uint4(q0.x, q0.y, q1.x, q1.y);
-            r.a1 = make_uint4(q2.x, q2.y, q3.x, q3.y);
-        }
-        const char *pb = bw + kb;
-        r.b0 = ld16(pb);
-        r.b1 = ld16(pb + bw_gate);
-        r.b2 = ld16(pb + 2 * bw_gate);
-        if constexpr (NG_X == 4) r.b3 = ld16(pb + 3 * bw_gate);
+    auto fetch_b = [&](const char *p, int64_t step, StageRegs &r, auto ng_tag) {
+        constexpr int NG = decltype(ng_tag)::value;
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if ((i & 3) < NG || MODE == MODE_PROJ) r.b[i] = ld16(p + i * step);
     };
-    // x part, last stage: zero-fill past D in 8-byte pieces (D % 4 == 0, so a piece
-    // of 4 bf16 or 2 floats is wholly inside or wholly outside)
-    auto fetch_x_tail = [&](int s, StageRegs &r) {
+    // x part; `tail`: the stage straddles D, pieces past D are zero (D % 4 == 0, so an
+    // 8-byte piece of 4 bf16 or 2 floats is wholly inside or wholly outside)
+    auto fetch_x = [&](int s, StageRegs &r, auto tail_tag) {
+        constexpr bool TAIL = decltype(tail_tag)::value;
         const int k0 = s * BK;
         const int64_t kb = (int64_t)k0 * ESZ;
-        const char *p = ax + kb;
-        constexpr int PIECE = 8 / ESZ;
-        uint2 q0 = make_uint2(0u, 0u), q1 = q0, q2 = q0, q3 = q0;
-        if (k0 + a_k + 0 * PIECE < a.D) q0 = *reinterpret_cast<const uint2 *>(p);
-        if (k0 + a_k + 1 * PIECE < a.D) q1 = *reinterpret_cast<const uint2 *>(p + 8);
-        if (k0 + a_k + 2 * PIECE < a.D) q2 = *reinterpret_cast<const uint2 *>(p + 16);
-        if (k0 + a_k + 3 * PIECE < a.D) q3 = *reinterpret_cast<const uint2 *>(p + 24);
-        r.a0 = make_uint4(q0.x, q0.y, q1.x, q1.y);
-        r.a1 = make_uint4(q2.x, q2.y, q3.x, q3.y);
-        const char *pb = bw + kb;
-        r.b0 = ld16(pb);
-        r.b1 = ld16(pb + bw_gate);
-        r.b2 = ld16(pb + 2 * bw_gate);
-        if constexpr (NG_X == 4) r.b3 = ld16(pb + 3 * bw_gate);
+        if constexpr (X8) {
+            const int k = k0 + (t & 15) * 4;
+            uint2 q[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                q[i] = make_uint2(0u, 0u);
+                if (!TAIL || k < a.D) q[i] = ld8(xbase + xrow[i] * x_row_bytes + kb);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) r.a[i] = make_uint4(q[2 * i].x, q[2 * i].y, q[2 * i + 1].x, q[2 * i + 1].y);
+        } else {
+            const int k = k0 + (t & 7) * 4;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const char *p = xbase + xrow[i] * x_row_bytes + kb;
+                if constexpr (!TAIL) {
+                    r.a[i] = ld16(p);
+                } else {
+                    uint2 lo = make_uint2(0u, 0u), hi = lo;
+                    if (k < a.D) lo = ld8(p);
+                    if (k + 2 < a.D) hi = ld8(p + 8);
+                    r.a[i] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+                }
+            }
+        }
+        fetch_b(bw + kb, bw_step, r, std::integral_constant<int, NG_X>());
     };
     auto fetch_h = [&](int s, StageRegs &r) {
         const int64_t kb = (int64_t)s * BK * ESZ;
-        r.a0 = ld16(ah + kb);
-        r.a1 = ld16(ah + kb + 16);
-        r.b0 = ld16(bu + kb);
-        r.b1 = ld16(bu + kb + bu_gate);
-        r.b2 = ld16(bu + kb + 2 * bu_gate);
-        if constexpr (NG_H == 4) r.b3 = ld16(bu + kb + 3 * bu_gate);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r.a[i] = ld16(hbase + hrow[i] * h_row_bytes + kb);
+        fetch_b(bu + kb, bu_step, r, std::integral_constant<int, NG_H>());
     };
     // ---- registers -> LDS --------------------------------------------------------------
-    auto stash = [&](const StageRegs &r, int buf, auto ng_tag) {
+    auto stash = [&](const StageRegs &r, auto x8_tag, auto ng_tag) {
+        constexpr bool A8 = decltype(x8_tag)::value;
         constexpr int NG = decltype(ng_tag)::value;
-        char *sa = lds_a + buf * (kBM * kLdsStride) + a_wr;
-        char *sb = lds_b + buf * (kBN * kLdsStride) + b_wr;
-        *reinterpret_cast<uint4 *>(sa) = r.a0;
-        *reinterpret_cast<uint4 *>(sa + 16) = r.a1;
-        *reinterpret_cast<uint4 *>(sb) = r.b0;
-        *reinterpret_cast<uint4 *>(sb + 32 * kLdsStride) = r.b1;
-        *reinterpret_cast<uint4 *>(sb + 64 * kLdsStride) = r.b2;
-        if constexpr (NG == 4) *reinterpret_cast<uint4 *>(sb + 96 * kLdsStride) = r.b3;
+        if constexpr (A8) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                *reinterpret_cast<uint2 *>(lds_a + a_wr8 + (2 * i) * 16 * kLdsStride) = make_uint2(r.a[i].x, r.a[i].y);
+                *reinterpret_cast<uint2 *>(lds_a + a_wr8 + (2 * i + 1) * 16 * kLdsStride) = make_uint2(r.a[i].z, r.a[i].w);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4 *>(lds_a + a_wr16 + i * 32 * kLdsStride) = r.a[i];
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if ((i & 3) < NG || MODE == MODE_PROJ)
+                *reinterpret_cast<uint4 *>(lds_b + b_wr + i * 32 * kLdsStride) = r.b[i];
     };
     // ---- LDS -> MFMA -------------------------------------------------------------------
-    auto mma = [&](int buf, auto ng_tag) {
+    auto mma = [&](auto ng_tag) {
         constexpr int NG = decltype(ng_tag)::value;
-        const char *sa = lds_a + buf * (kBM * kLdsStride) + a_rd;
-        const char *sb = lds_b + buf * (kBN * kLdsStride) + b_rd;
+        const char *sa = lds_a + a_rd;
+        const char *sb = lds_b + b_rd;
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
+        for (int h = 0; h < 4; ++h) {
             uint4 av[2], bv[NG];
 #pragma unroll
             for (int i = 0; i < 2; ++i)
@@ -374,64 +394,65 @@ __device__ __forceinline__ void block_gemm(const LevelArgs &a, char *lds_a, char
     };
     const std::integral_constant<int, NG_X> ngx;
     const std::integral_constant<int, NG_H> ngh;
+    const std::integral_constant<bool, X8> x8;
+    const std::integral_constant<bool, false> no8;
+    const std::true_type is_tail;
+    const std::false_type no_tail;
 
-    // The pipeline, written out part by part so that every loop body is straight-line
-    // code: while stage s is multiplied out of one LDS buffer, stage s+1 travels
-    // global -> registers -> the other buffer.
+    // The pipeline, written out part by part so that every loop body is straight-line code.
     StageRegs r;
-    int buf = 0;
     if constexpr (HAS_X) {
         const bool tail = (n_x * BK > a.D);      // the last x stage needs zero fill
-        if (n_x == 1 && tail) fetch_x_tail(0, r); else fetch_x(0, r);
-        stash(r, 0, ngx);
+        if (n_x == 1 && tail) fetch_x(0, r, is_tail); else fetch_x(0, r, no_tail);
+        stash(r, x8, ngx);
         __syncthreads();
         for (int s = 0; s + 2 < n_x; ++s) {       // next stage is a full x stage
-            fetch_x(s + 1, r);
-            mma(buf, ngx);
-            stash(r, buf ^ 1, ngx);
+            fetch_x(s + 1, r, no_tail);
+            mma(ngx);
             __syncthreads();
-            buf ^= 1;
+            stash(r, x8, ngx);
+            __syncthreads();
         }
         if (n_x > 1) {                            // next stage is the last x stage
-            if (tail) fetch_x_tail(n_x - 1, r); else fetch_x(n_x - 1, r);
-            mma(buf, ngx);
-            stash(r, buf ^ 1, ngx);
+            if (tail) fetch_x(n_x - 1, r, is_tail); else fetch_x(n_x - 1, r, no_tail);
+            mma(ngx);
             __syncthreads();
-            buf ^= 1;
+            stash(r, x8, ngx);
+            __syncthreads();
         }
         if constexpr (HAS_H) {                    // last x stage; next is the first h stage
             fetch_h(0, r);
-            mma(buf, ngx);
-            stash(r, buf ^ 1, ngh);
+            mma(ngx);
             __syncthreads();
-            buf ^= 1;
+            stash(r, no8, ngh);
+            __syncthreads();
         } else {
-            mma(buf, ngx);
+            mma(ngx);
         }
     } else {
         fetch_h(0, r);
-        stash(r, 0, ngh);
+        stash(r, no8, ngh);
         __syncthreads();
     }
     if constexpr (HAS_H) {
         for (int s = 0; s + 1 < n_h; ++s) {
             fetch_h(s + 1, r);
-            mma(buf, ngh);
-            stash(r, buf ^ 1, ngh);
+            mma(ngh);
             __syncthreads();
-            buf ^= 1;
+            stash(r, no8, ngh);
+            __syncthreads();
         }
-        mma(buf, ngh);
+        mma(ngh);
     }
 }
 
 template <typename T, int MODE>
 __global__ void __launch_bounds__(kThreads, 2)
 level_kernel(const LevelArgs a) {
-    __shared__ __attribute__((aligned(16))) char lds[2 * (kBM + kBN) * kLdsStride];
+    __shared__ __attribute__((aligned(16))) char lds[(kBM + kBN) * kLdsStride];
     char *lds_a = lds;
-    char *lds_b = lds + 2 * kBM * kLdsStride;
-    static_assert(3 * kEpiRows * kEpiStride * 4 <= 2 * (kBM + kBN) * kLdsStride, "epilogue tiles must fit the staging buffers");
+    char *lds_b = lds + kBM * kLdsStride;
+    static_assert(3 * kEpiRows * kEpiStride * 4 <= (kBM + kBN) * kLdsStride, "epilogue tiles must fit the staging buffer");
     __shared__ int row_node[kBM];
     __shared__ int row_cb[kBM];
     __shared__ int row_ce[kBM];
