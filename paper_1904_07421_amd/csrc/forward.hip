@@ -5,8 +5,9 @@
 // (section 4.3).  Here a slot is one height level of the forest and the
 // subgraph is the Child-Sum Tree-LSTM cell (section 3).  Per level:
 //
-//   child_sum_kernel   hs_j = sum_k h_k over the child CSR (the arity-dependent
-//                      operator; HBM-bound, 16-byte coalesced row pieces)
+//   stack_kernel       row r of the level's input matrix = [x_j | sum_k h_k] over the
+//                      child CSR (the arity-dependent operator; HBM-bound, 16-byte
+//                      coalesced row pieces)
 //   level_kernel<GATES>   [x_j ; hs_j] x [W ; U]^T on MFMA with the whole cell
 //                      fused into the epilogue: per-child forget gates from the
 //                      precomputed P_k = U_f h_k, c_j and h_j written once
@@ -14,8 +15,9 @@
 //                      parent reads one row per child (every non-root node is a
 //                      child exactly once)
 //
-// "Stack" is a row gather through perm (level-major order), "slice" is the
-// scatter of rows back to node-id order in the epilogue.
+// "Stack" is the row gather through perm (level-major order) done by
+// stack_kernel, "slice" is the scatter of rows back to node-id order in the
+// epilogue.
 //
 // Weights are re-packed once per call: gate rows of 32 hidden units are
 // interleaved (i|o|u|f blocks of 32 rows), so that one wave holds all four
@@ -35,14 +37,19 @@ namespace {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef uint16_t bf16_t;  // storage type of bfloat16 values
+// Native vectors for data in flight (HIP's uint4 is a union-based struct, which the
+// optimiser does not always break up into registers).
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kThreads = 256;
-constexpr int kBM = 128;        // rows (nodes) per block
+constexpr int kThreads = 256;     // small kernels
+constexpr int kGemmThreads = 512; // level kernels: eight waves
+constexpr int kBM = 256;        // rows (nodes) per block
 constexpr int kBN = 256;        // packed columns per block = 2 unit tiles x 4 gates x 32
 constexpr int kUnit = 32;       // hidden units per MFMA column tile
 constexpr int kGateTile = 128;  // packed rows per unit tile (4 gates x 32 units)
 
-constexpr int kEpiRows = 64;    // rows per epilogue pass
+constexpr int kEpiRows = 128;   // rows per epilogue pass
 constexpr int kEpiStride = 68;  // floats per epilogue LDS row: 64 units + 4 (keeps 16-byte alignment)
 constexpr int kLdsStride = 144; // stage row (128 bytes) + 16: 128-bit LDS reads of 32 rows hit distinct banks
 
@@ -74,102 +81,130 @@ template <typename T> __device__ __forceinline__ float exp_t(float z);
 template <> __device__ __forceinline__ float exp_t<float>(float z) { return expf(z); }
 template <> __device__ __forceinline__ float exp_t<bf16_t>(float z) { return __expf(z); }
 
+// 1/(1+e) through the hardware reciprocal (1 ulp) instead of an IEEE division sequence.
 template <typename T> __device__ __forceinline__ float sigmoid_t(float z) {
-    return 1.0f / (1.0f + exp_t<T>(-z));
+    return __builtin_amdgcn_rcpf(1.0f + exp_t<T>(-z));
 }
 template <typename T> __device__ __forceinline__ float tanh_t(float z) {
-    return 1.0f - 2.0f / (1.0f + exp_t<T>(2.0f * z));
+    return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + exp_t<T>(2.0f * z));
 }
 
 // ---- weight packing ----------------------------------------------------------------
-// Packed row r = tile*128 + gate*32 + uu holds gate `gate` of hidden unit tile*32 + uu.
-// Wp has NP rows, Up has NPU >= NP rows; rows of units >= H and columns past D / H are zero.
+// Packed row r = tile*128 + gate*32 + uu holds gate `gate` of hidden unit tile*32 + uu as
+// [ W row (D values, zero padded to Dp) | U row (H values, zero padded to Hp) ].  There are
+// NPU >= NP rows; rows of units >= H are zero.
 template <typename T>
 __global__ void __launch_bounds__(kThreads)
 pack_weights_kernel(const T *__restrict__ W, const T *__restrict__ U, const float *__restrict__ b,
                     int D, int H, int Dp, int Hp, int NP, int NPU,
-                    T *__restrict__ Wp, T *__restrict__ Up, float *__restrict__ bp) {
-    const int64_t n_w = (int64_t)NP * Dp, n_u = (int64_t)NPU * Hp;
-    for (int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x; idx < n_w + n_u;
+                    T *__restrict__ Bp, float *__restrict__ bp) {
+    const int Kp = Dp + Hp;
+    const int64_t total = (int64_t)NPU * Kp;
+    for (int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x; idx < total;
          idx += (int64_t)gridDim.x * kThreads) {
-        const bool is_w = idx < n_w;
-        const int64_t j = is_w ? idx : idx - n_w;
-        const int ld = is_w ? Dp : Hp;
-        const int r = (int)(j / ld), k = (int)(j % ld);
+        const int r = (int)(idx / Kp), k = (int)(idx % Kp);
         const int tile = r / kGateTile, gate = (r % kGateTile) / kUnit, uu = r % kUnit;
         const int unit = tile * kUnit + uu;
         const bool row_ok = unit < H;
         const int64_t src = (int64_t)gate * H + unit;
-        if (is_w) {
-            Wp[j] = (row_ok && k < D) ? W[src * D + k] : T(0);
-            if (k == 0) bp[r] = row_ok ? b[src] : 0.0f;
-        } else {
-            Up[j] = (row_ok && k < H) ? U[src * H + k] : T(0);
+        T v = T(0);
+        if (row_ok) {
+            if (k < D) v = W[src * D + k];
+            else if (k >= Dp && k - Dp < H) v = U[src * H + (k - Dp)];
         }
+        Bp[idx] = v;
+        if (k == 0 && r < NP) bp[r] = row_ok ? b[src] : 0.0f;
     }
 }
 
-// ---- child sum ---------------------------------------------------------------------
-// hsum[row] = sum over children of hs[child]; one thread per 16-byte piece of a row.
-// hs rows have stride Hp (pad columns are zero), rows indexed by node id.
-template <typename T>
+// ---- stack -------------------------------------------------------------------------
+// The paper's "stack" step (section 4.3): the samples of one slot are laid side by
+// side on the batch axis.  Row r of the level's dense input matrix A is
+//     [ x_j (D values, zero padded to Dp) | hsum_j = sum over children of h_k (Hp values) ]
+// for the r-th node j of the level; leaves have the x part only.  One thread
+// per 16-byte piece of a row; child rows come from hs (stride Hp, pad columns zero,
+// rows by node id) in 16-byte pieces, 16 * cpr bytes contiguous per row.
+template <typename T, bool WITH_H>
 __global__ void __launch_bounds__(kThreads)
-child_sum_kernel(const T *__restrict__ hs, int Hp, const int32_t *__restrict__ level_nodes,
-                 const int32_t *__restrict__ child_ptr, const int32_t *__restrict__ child_idx,
-                 T *__restrict__ hsum, int n_rows) {
+stack_kernel(const T *__restrict__ x, int D, int Dp, const T *__restrict__ hs, int Hp,
+             const int32_t *__restrict__ level_nodes, const int32_t *__restrict__ child_ptr,
+             const int32_t *__restrict__ child_idx, T *__restrict__ A, int4 *__restrict__ row_rec,
+             int n_rows) {
     constexpr int VEC = Traits<T>::VEC;
-    const int cpr = Hp / VEC;
+    const int Kp = Dp + (WITH_H ? Hp : 0);
+    const int cpr = Kp / VEC;
     const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     const int64_t row = gid / cpr;
     const int ch = (int)(gid % cpr);
     if (row >= n_rows) return;
     const int node = level_nodes[row];
-    const int cb = child_ptr[node], ce = child_ptr[node + 1];
-    float acc[VEC];
+    const int k0 = ch * VEC;
+    if (WITH_H && ch == 0) {
+        // what the cell update needs to know about this row, in one 32-byte record:
+        // { node, arity, CSR start, - } { first four child ids (-1 where there is none) }
+        const int cb = child_ptr[node], ar = child_ptr[node + 1] - cb;
+        int kid[4];
 #pragma unroll
-    for (int j = 0; j < VEC; ++j) acc[j] = 0.0f;
-    for (int e = cb; e < ce; ++e) {
-        const int k = child_idx[e];
-        const uint4 v = *reinterpret_cast<const uint4 *>(hs + (int64_t)k * Hp + ch * VEC);
+        for (int j = 0; j < 4; ++j) kid[j] = j < ar ? child_idx[cb + j] : -1;
+        row_rec[2 * row] = make_int4(node, ar, cb, 0);
+        row_rec[2 * row + 1] = make_int4(kid[0], kid[1], kid[2], kid[3]);
+    }
+    uint4 o = make_uint4(0u, 0u, 0u, 0u);
+    if (k0 < Dp) {
+        // x rows are 4-element aligned (D % 4 == 0): move 4-element halves, zero past D
+        const T *src = x + (int64_t)node * D + k0;
         if constexpr (sizeof(T) == 4) {
-            acc[0] += __uint_as_float(v.x); acc[1] += __uint_as_float(v.y);
-            acc[2] += __uint_as_float(v.z); acc[3] += __uint_as_float(v.w);
+            if (k0 < D) o = *reinterpret_cast<const uint4 *>(src);
         } else {
-            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+            if (k0 < D) { const uint2 q = *reinterpret_cast<const uint2 *>(src); o.x = q.x; o.y = q.y; }
+            if (k0 + 4 < D) { const uint2 q = *reinterpret_cast<const uint2 *>(src + 4); o.z = q.x; o.w = q.y; }
+        }
+    } else if constexpr (WITH_H) {
+        const int kh = k0 - Dp;
+        const int cb = child_ptr[node], ce = child_ptr[node + 1];
+        float acc[VEC];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                acc[2 * j] += __uint_as_float(w[j] << 16);
-                acc[2 * j + 1] += __uint_as_float(w[j] & 0xFFFF0000u);
+        for (int j = 0; j < VEC; ++j) acc[j] = 0.0f;
+        for (int e = cb; e < ce; ++e) {
+            const int k = child_idx[e];
+            const uint4 v = *reinterpret_cast<const uint4 *>(hs + (int64_t)k * Hp + kh);
+            if constexpr (sizeof(T) == 4) {
+                acc[0] += __uint_as_float(v.x); acc[1] += __uint_as_float(v.y);
+                acc[2] += __uint_as_float(v.z); acc[3] += __uint_as_float(v.w);
+            } else {
+                const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    acc[2 * j] += __uint_as_float(w[j] << 16);
+                    acc[2 * j + 1] += __uint_as_float(w[j] & 0xFFFF0000u);
+                }
             }
         }
-    }
-    uint4 o;
-    if constexpr (sizeof(T) == 4) {
-        o.x = __float_as_uint(acc[0]); o.y = __float_as_uint(acc[1]);
-        o.z = __float_as_uint(acc[2]); o.w = __float_as_uint(acc[3]);
-    } else {
-        uint32_t w[4];
+        if constexpr (sizeof(T) == 4) {
+            o.x = __float_as_uint(acc[0]); o.y = __float_as_uint(acc[1]);
+            o.z = __float_as_uint(acc[2]); o.w = __float_as_uint(acc[3]);
+        } else {
+            uint32_t w[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            w[j] = (uint32_t)f32_to_bf16(acc[2 * j]) | ((uint32_t)f32_to_bf16(acc[2 * j + 1]) << 16);
-        o.x = w[0]; o.y = w[1]; o.z = w[2]; o.w = w[3];
+            for (int j = 0; j < 4; ++j)
+                w[j] = (uint32_t)f32_to_bf16(acc[2 * j]) | ((uint32_t)f32_to_bf16(acc[2 * j + 1]) << 16);
+            o.x = w[0]; o.y = w[1]; o.z = w[2]; o.w = w[3];
+        }
     }
-    *reinterpret_cast<uint4 *>(hsum + row * Hp + ch * VEC) = o;
+    *reinterpret_cast<uint4 *>(A + row * Kp + k0) = o;
 }
 
 // ---- the level GEMM ----------------------------------------------------------------
 struct LevelArgs {
     // A operands
-    const void *x;        // [N, D] rows by node id
-    const void *hsum;     // [n_rows, Hp] level-local rows (MODE_INTERNAL)
-    const void *hs;       // [N, Hp] rows by node id (MODE_PROJ)
-    // B operands (packed)
-    const void *Wp;       // [NP, Dp]
-    const void *Up;       // [NP, Hp]
-    const float *bp;      // [NP]
+    const void *stack;    // [n_rows, Dp (+ Hp)] the level's stacked input (leaf / internal)
+    const void *hs;       // [N, Hp] rows by node id (projection)
+    // B operand: packed [W | U], NPU rows of Dp + Hp
+    const void *Bp;
+    const float *bp;      // [NP] packed bias
     // schedule
     const int32_t *level_nodes;  // perm + level start: row -> node id
-    const int32_t *child_ptr;
+    const int4 *row_rec;         // two int4 per level row, written by stack_kernel (internal levels)
     const int32_t *child_idx;
     // per-child forget projections, rows by node id, stride Hq
     float *P;
@@ -196,266 +231,187 @@ __device__ __forceinline__ int xcd_remap(int b, int nb) {
 }
 
 template <typename T>
-__device__ __forceinline__ void mfma_step(const uint4 &a, const uint4 &b, floatx16 &acc) {
+__device__ __forceinline__ void mfma_step(const u32x4 &a, const u32x4 &b, floatx16 &acc) {
     if constexpr (sizeof(T) == 2) {
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
                                                       __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
     } else {
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[0]), __uint_as_float(b[0]), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[1]), __uint_as_float(b[1]), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[2]), __uint_as_float(b[2]), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[3]), __uint_as_float(b[3]), acc, 0, 0, 0);
     }
 }
 
 // What one thread holds of a K stage on its way from global memory to LDS:
-// 64 bytes of A rows and 16 bytes of each of eight B rows.
+// 16 bytes of each of four A rows and four B rows.
 struct StageRegs {
-    uint4 a[4];
-    uint4 b[8];
+    u32x4 a[4];
+    u32x4 b[4];
 };
 
-// The block GEMM.  K runs over "stages" of 128 bytes per row (one cache line):
-// first the x / W part (n_x stages), then the h / U part (n_h stages), as one
-// software pipeline across both parts.  There is ONE LDS buffer per block: the
-// global loads of stage s+1 are issued before the MFMAs of stage s and written
-// to LDS after them, between two barriers; the second block resident on the CU
-// keeps the matrix cores busy meanwhile.
+// The block GEMM: 256 rows x 256 packed columns per block of eight waves, each
+// wave a 64 x 128 sub-tile (2 x 4 MFMA tiles of 32 x 32).  A is the level's
+// stacked input [x | hsum] (row stride Kp = Dp + Hp), B the packed [W | U]
+// with the same K layout; K runs over "stages" of 128 bytes per row (one cache
+// line): n_x stages of the x part, then n_h of the h part, in which the forget
+// gate is skipped (U_f applies to each child's own h, not to the sum).  The
+// projection instead reads A rows from hs by node id and uses only the U part
+// of the forget rows.  One software pipeline with two LDS buffers and one
+// barrier per stage; in iteration g
+//   - the registers holding stage g+1 (requested one iteration ago) go to the
+//     idle LDS buffer; these writes drain through the 64-bytes-per-clock LDS
+//     write port while the matrix cores work,
+//   - stage g is multiplied out of the other buffer,
+//   - half way through, stage g+2 is requested from global memory (by then
+//     the LDS writes have released the registers).
 //
-// LDS layout: row r at r*kLdsStride, K contiguous.  In each 16-wide (bf16) or
-// 8-wide (fp32) K group, lanes 0-31 take the first 16 bytes and lanes 32-63 the
-// next 16 for A and B alike; since the same assignment is used on both
-// operands any such split of K is a valid MFMA schedule.
+// LDS layout: row r at r*kLdsStride, K contiguous, A rows 0-255 then B rows.
+// In each 16-wide (bf16) or 8-wide (fp32) K group, lanes 0-31 take the first
+// 16 bytes and lanes 32-63 the next 16 for A and B alike; since the same
+// assignment is used on both operands any such split of K is a valid MFMA
+// schedule.
 //
 // Staging map: eight consecutive lanes move the eight 16-byte pieces of one row
 // (a whole line per row and load instruction); thread t handles piece t&7 of
-// rows t/8 + 32 i.  For B, i & 3 is the gate (or, for the projection, i is the
-// unit tile), so whole gates can be skipped at compile time.  Rows of x in
-// bf16 are only 8-byte aligned: there sixteen lanes move 8-byte pieces of one
-// row, thread t handling piece t&15 of rows t/16 + 16 i.
+// A rows t/8 + 64 i.  Of B it handles hidden unit (t/8)%32 of unit tile t/256,
+// row group i being the gate (or, for the projection, unit tile 4*(t/256) + i),
+// so whole gates can be skipped at compile time.
 template <typename T, int MODE>
-__device__ __forceinline__ void block_gemm(const LevelArgs &a, char *lds_a, char *lds_b,
-                                           const int *row_node, int tile_row0, int col_tile,
-                                           floatx16 (&acc)[2][4]) {
+__device__ __forceinline__ void block_gemm(const LevelArgs &a, char *lds, const int *row_node,
+                                           int tile_row0, int col_tile, floatx16 (&acc)[2][4]) {
     constexpr int BK = Traits<T>::BK;
     constexpr int ESZ = (int)sizeof(T);
-    constexpr bool HAS_X = (MODE != MODE_PROJ);
-    constexpr bool HAS_H = (MODE != MODE_LEAF);
     constexpr int NG_X = (MODE == MODE_LEAF) ? 3 : 4;      // gate tiles multiplied in the x part
-    constexpr int NG_H = (MODE == MODE_INTERNAL) ? 3 : 4;  // ... in the h part (U_f h~ is not needed)
-    constexpr bool X8 = HAS_X && (ESZ == 2);               // x pieces of 8 bytes
+    constexpr int NG_H = (MODE == MODE_INTERNAL) ? 3 : 4;  // ... in the h part
 
     const int t = threadIdx.x;
     const int lane = t & 63, wave = t >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int hf = lane >> 5, l32 = lane & 31;
 
-    const int n_x = HAS_X ? a.Dp / BK : 0;
-    const int n_h = HAS_H ? a.Hp / BK : 0;
+    const int n_x = (MODE == MODE_PROJ) ? 0 : a.Dp / BK;
+    const int n_h = (MODE == MODE_LEAF) ? 0 : a.Hp / BK;
+    const int n_stages = n_x + n_h;
+    const int64_t b_row_bytes = (int64_t)(a.Dp + a.Hp) * ESZ;
 
-    // ---- A sources.  Rows past the end of the level are clamped to the last row:
-    //      they are computed twice and stored never.
-    auto clamp_row = [&](int r) {
-        const int g = tile_row0 + r;
-        return g < a.n_rows ? g : a.n_rows - 1;
-    };
-    int xrow[X8 ? 8 : 4];       // node ids of the x rows this thread moves
-    int hrow[4];                // row index into hsum (level row) or hs (node id)
-    if constexpr (HAS_X) {
-#pragma unroll
-        for (int i = 0; i < (X8 ? 8 : 4); ++i) {
-            const int r = X8 ? (t >> 4) + 16 * i : (t >> 3) + 32 * i;
-            xrow[i] = row_node[clamp_row(r) - tile_row0];
-        }
-    }
-    if constexpr (HAS_H) {
+    // ---- A source: rows tile_row0 + t/8 + 64 i of the stacked matrix (rows past the end
+    //      of the level lie inside the buffer, hold anything and are never stored), or
+    //      for the projection rows of hs by node id (clamped to the level's last row).
+    const char *ap[MODE == MODE_PROJ ? 4 : 1];
+    int64_t a_step = 0;
+    if constexpr (MODE == MODE_PROJ) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int g = clamp_row((t >> 3) + 32 * i);
-            hrow[i] = (MODE == MODE_INTERNAL) ? g : row_node[g - tile_row0];
+            int g = tile_row0 + (t >> 3) + 64 * i;
+            if (g >= a.n_rows) g = a.n_rows - 1;
+            ap[i] = static_cast<const char *>(a.hs) + (int64_t)row_node[g - tile_row0] * a.Hp * ESZ + (t & 7) * 16;
         }
+    } else {
+        const int64_t a_row_bytes = (int64_t)(a.Dp + (MODE == MODE_INTERNAL ? a.Hp : 0)) * ESZ;
+        ap[0] = static_cast<const char *>(a.stack) + (int64_t)(tile_row0 + (t >> 3)) * a_row_bytes + (t & 7) * 16;
+        a_step = 64 * a_row_bytes;
     }
-    const char *xbase = static_cast<const char *>(a.x) + (X8 ? (t & 15) * 8 : (t & 7) * 16);
-    const char *hbase = static_cast<const char *>(MODE == MODE_INTERNAL ? a.hsum : a.hs) + (t & 7) * 16;
-    const int64_t x_row_bytes = (int64_t)a.D * ESZ, h_row_bytes = (int64_t)a.Hp * ESZ;
-
-    // ---- B sources: one pointer per part plus a uniform stride from one staged row
-    //      group (32 rows) to the next.  The packed U has zero rows up to a multiple of
-    //      eight unit tiles, so the projection needs no clamp.
-    const char *bw = nullptr, *bu = nullptr;
-    int64_t bw_step = 0, bu_step = 0;
-    {
-        const int uu = t >> 3;
-        if constexpr (MODE == MODE_PROJ) {
-            const int64_t row = (int64_t)(col_tile * 8) * kGateTile + 3 * kUnit + uu;
-            bu = static_cast<const char *>(a.Up) + row * a.Hp * ESZ + (t & 7) * 16;
-            bu_step = (int64_t)kGateTile * a.Hp * ESZ;
-        } else {
-            const int64_t row = (int64_t)col_tile * kBN + uu;
-            bw = static_cast<const char *>(a.Wp) + row * a.Dp * ESZ + (t & 7) * 16;
-            bw_step = (int64_t)kUnit * a.Dp * ESZ;
-            bu = static_cast<const char *>(a.Up) + row * a.Hp * ESZ + (t & 7) * 16;
-            bu_step = (int64_t)kUnit * a.Hp * ESZ;
-        }
+    // ---- B source
+    const int uu = (t >> 3) & 31, ut = t >> 8;
+    const char *bp;
+    int64_t b_step;
+    if constexpr (MODE == MODE_PROJ) {
+        const int64_t row = (int64_t)(col_tile * 8 + ut * 4) * kGateTile + 3 * kUnit + uu;
+        bp = static_cast<const char *>(a.Bp) + row * b_row_bytes + (int64_t)a.Dp * ESZ + (t & 7) * 16;
+        b_step = (int64_t)kGateTile * b_row_bytes;
+    } else {
+        const int64_t row = (int64_t)col_tile * kBN + ut * kGateTile + uu;
+        bp = static_cast<const char *>(a.Bp) + row * b_row_bytes + (t & 7) * 16;
+        b_step = (int64_t)kUnit * b_row_bytes;
     }
-    const int a_wr16 = (t >> 3) * kLdsStride + (t & 7) * 16;
-    const int a_wr8 = (t >> 4) * kLdsStride + (t & 15) * 8;
-    const int b_wr = (t >> 3) * kLdsStride + (t & 7) * 16;
+    const int a_wr = (t >> 3) * kLdsStride + (t & 7) * 16;
+    const int b_wr = (kBM + ut * kGateTile + uu) * kLdsStride + (t & 7) * 16;
     const int a_rd = (wm * 64 + l32) * kLdsStride + hf * 16;
-    const int b_rd = (wn * 128 + l32) * kLdsStride + hf * 16;
+    const int b_rd = (kBM + wn * 128 + l32) * kLdsStride + hf * 16;
 
-    auto ld16 = [](const char *p) { return *reinterpret_cast<const uint4 *>(p); };
-    auto ld8 = [](const char *p) { return *reinterpret_cast<const uint2 *>(p); };
+    auto ld16 = [](const char *p) __attribute__((always_inline)) { return *reinterpret_cast<const u32x4 *>(p); };
 
-    // ---- global -> registers, one stage ---------------------------------------------
-    auto fetch_b = [&](const char *p, int64_t step, StageRegs &r, auto ng_tag) {
+    StageRegs r;
+    // global -> registers, stage g
+    auto fetch = [&](int g, auto ng_tag) __attribute__((always_inline)) {
         constexpr int NG = decltype(ng_tag)::value;
+        const int64_t kb = (int64_t)g * (BK * ESZ);
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
-            if ((i & 3) < NG || MODE == MODE_PROJ) r.b[i] = ld16(p + i * step);
-    };
-    // x part; `tail`: the stage straddles D, pieces past D are zero (D % 4 == 0, so an
-    // 8-byte piece of 4 bf16 or 2 floats is wholly inside or wholly outside)
-    auto fetch_x = [&](int s, StageRegs &r, auto tail_tag) {
-        constexpr bool TAIL = decltype(tail_tag)::value;
-        const int k0 = s * BK;
-        const int64_t kb = (int64_t)k0 * ESZ;
-        if constexpr (X8) {
-            const int k = k0 + (t & 15) * 4;
-            uint2 q[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                q[i] = make_uint2(0u, 0u);
-                if (!TAIL || k < a.D) q[i] = ld8(xbase + xrow[i] * x_row_bytes + kb);
-            }
-#pragma unroll
-            for (int i = 0; i < 4; ++i) r.a[i] = make_uint4(q[2 * i].x, q[2 * i].y, q[2 * i + 1].x, q[2 * i + 1].y);
-        } else {
-            const int k = k0 + (t & 7) * 4;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const char *p = xbase + xrow[i] * x_row_bytes + kb;
-                if constexpr (!TAIL) {
-                    r.a[i] = ld16(p);
-                } else {
-                    uint2 lo = make_uint2(0u, 0u), hi = lo;
-                    if (k < a.D) lo = ld8(p);
-                    if (k + 2 < a.D) hi = ld8(p + 8);
-                    r.a[i] = make_uint4(lo.x, lo.y, hi.x, hi.y);
-                }
-            }
-        }
-        fetch_b(bw + kb, bw_step, r, std::integral_constant<int, NG_X>());
-    };
-    auto fetch_h = [&](int s, StageRegs &r) {
-        const int64_t kb = (int64_t)s * BK * ESZ;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) r.a[i] = ld16(hbase + hrow[i] * h_row_bytes + kb);
-        fetch_b(bu + kb, bu_step, r, std::integral_constant<int, NG_H>());
-    };
-    // ---- registers -> LDS --------------------------------------------------------------
-    auto stash = [&](const StageRegs &r, auto x8_tag, auto ng_tag) {
-        constexpr bool A8 = decltype(x8_tag)::value;
-        constexpr int NG = decltype(ng_tag)::value;
-        if constexpr (A8) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                *reinterpret_cast<uint2 *>(lds_a + a_wr8 + (2 * i) * 16 * kLdsStride) = make_uint2(r.a[i].x, r.a[i].y);
-                *reinterpret_cast<uint2 *>(lds_a + a_wr8 + (2 * i + 1) * 16 * kLdsStride) = make_uint2(r.a[i].z, r.a[i].w);
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4 *>(lds_a + a_wr16 + i * 32 * kLdsStride) = r.a[i];
+        for (int i = 0; i < 4; ++i) {
+            if constexpr (MODE == MODE_PROJ) r.a[i] = ld16(ap[i] + kb);
+            else r.a[i] = ld16(ap[0] + i * a_step + kb);
         }
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
-            if ((i & 3) < NG || MODE == MODE_PROJ)
-                *reinterpret_cast<uint4 *>(lds_b + b_wr + i * 32 * kLdsStride) = r.b[i];
+        for (int i = 0; i < NG; ++i) r.b[i] = ld16(bp + i * b_step + kb);
     };
-    // ---- LDS -> MFMA -------------------------------------------------------------------
-    auto mma = [&](auto ng_tag) {
+    // registers -> LDS
+    auto stash = [&](char *buf, auto ng_tag) __attribute__((always_inline)) {
         constexpr int NG = decltype(ng_tag)::value;
-        const char *sa = lds_a + a_rd;
-        const char *sb = lds_b + b_rd;
 #pragma unroll
-        for (int h = 0; h < 4; ++h) {
-            uint4 av[2], bv[NG];
+        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(buf + a_wr + i * 64 * kLdsStride) = r.a[i];
+#pragma unroll
+        for (int i = 0; i < NG; ++i) *reinterpret_cast<u32x4 *>(buf + b_wr + i * 32 * kLdsStride) = r.b[i];
+    };
+    // LDS -> MFMA: K groups [h0, h0 + 2) of one stage
+    auto mma = [&](const char *buf, int h0, auto ng_tag) __attribute__((always_inline)) {
+        constexpr int NG = decltype(ng_tag)::value;
+        const char *sa = buf + a_rd;
+        const char *sb = buf + b_rd;
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+            const int h = h0 + hh;
+            u32x4 av[2], bv[NG];
 #pragma unroll
             for (int i = 0; i < 2; ++i)
-                av[i] = *reinterpret_cast<const uint4 *>(sa + i * 32 * kLdsStride + h * 32);
+                av[i] = *reinterpret_cast<const u32x4 *>(sa + i * 32 * kLdsStride + h * 32);
 #pragma unroll
             for (int g = 0; g < NG; ++g)
-                bv[g] = *reinterpret_cast<const uint4 *>(sb + g * 32 * kLdsStride + h * 32);
+                bv[g] = *reinterpret_cast<const u32x4 *>(sb + g * 32 * kLdsStride + h * 32);
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int g = 0; g < NG; ++g) mfma_step<T>(av[i], bv[g], acc[i][g]);
         }
     };
+
+    constexpr int kBufBytes = (kBM + kBN) * kLdsStride;
     const std::integral_constant<int, NG_X> ngx;
     const std::integral_constant<int, NG_H> ngh;
-    const std::integral_constant<bool, X8> x8;
-    const std::integral_constant<bool, false> no8;
-    const std::true_type is_tail;
-    const std::false_type no_tail;
-
-    // The pipeline, written out part by part so that every loop body is straight-line code.
-    StageRegs r;
-    if constexpr (HAS_X) {
-        const bool tail = (n_x * BK > a.D);      // the last x stage needs zero fill
-        if (n_x == 1 && tail) fetch_x(0, r, is_tail); else fetch_x(0, r, no_tail);
-        stash(r, x8, ngx);
+    // Stage kinds of the stash (g+1) and the fetch (g+2) differ from that of the MFMAs (g)
+    // only next to the boundary between the parts; they move registers only, so a uniform
+    // branch there is cheap.  The MFMA code of the two parts stays in separate loops so that
+    // the accumulators never pass through a branch merge.
+    auto fetch_any = [&](int g) __attribute__((always_inline)) { if (g < n_x) fetch(g, ngx); else fetch(g, ngh); };
+    auto stash_any = [&](int g, char *buf) __attribute__((always_inline)) { if (g < n_x) stash(buf, ngx); else stash(buf, ngh); };
+    auto iteration = [&](int g, auto ng_tag) __attribute__((always_inline)) {
+        char *cur = lds + (g & 1) * kBufBytes;
+        char *nxt = lds + ((g & 1) ^ 1) * kBufBytes;
+        if (g + 1 < n_stages) stash_any(g + 1, nxt);
+        mma(cur, 0, ng_tag);
+        __builtin_amdgcn_sched_barrier(0);
+        if (g + 2 < n_stages) fetch_any(g + 2);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(cur, 2, ng_tag);
         __syncthreads();
-        for (int s = 0; s + 2 < n_x; ++s) {       // next stage is a full x stage
-            fetch_x(s + 1, r, no_tail);
-            mma(ngx);
-            __syncthreads();
-            stash(r, x8, ngx);
-            __syncthreads();
-        }
-        if (n_x > 1) {                            // next stage is the last x stage
-            if (tail) fetch_x(n_x - 1, r, is_tail); else fetch_x(n_x - 1, r, no_tail);
-            mma(ngx);
-            __syncthreads();
-            stash(r, x8, ngx);
-            __syncthreads();
-        }
-        if constexpr (HAS_H) {                    // last x stage; next is the first h stage
-            fetch_h(0, r);
-            mma(ngx);
-            __syncthreads();
-            stash(r, no8, ngh);
-            __syncthreads();
-        } else {
-            mma(ngx);
-        }
-    } else {
-        fetch_h(0, r);
-        stash(r, no8, ngh);
-        __syncthreads();
-    }
-    if constexpr (HAS_H) {
-        for (int s = 0; s + 1 < n_h; ++s) {
-            fetch_h(s + 1, r);
-            mma(ngh);
-            __syncthreads();
-            stash(r, no8, ngh);
-            __syncthreads();
-        }
-        mma(ngh);
-    }
+    };
+    fetch_any(0);
+    stash_any(0, lds);
+    if (n_stages > 1) fetch_any(1);
+    __syncthreads();
+    for (int g = 0; g < n_x; ++g) iteration(g, ngx);
+    for (int g = n_x; g < n_stages; ++g) iteration(g, ngh);
 }
 
 template <typename T, int MODE>
-__global__ void __launch_bounds__(kThreads, 2)
+__global__ void __launch_bounds__(kGemmThreads, 1)
 level_kernel(const LevelArgs a) {
-    __shared__ __attribute__((aligned(16))) char lds[(kBM + kBN) * kLdsStride];
-    char *lds_a = lds;
-    char *lds_b = lds + kBM * kLdsStride;
-    static_assert(3 * kEpiRows * kEpiStride * 4 <= (kBM + kBN) * kLdsStride, "epilogue tiles must fit the staging buffer");
+    __shared__ __attribute__((aligned(16))) char lds[2 * (kBM + kBN) * kLdsStride];
+    static_assert(3 * kEpiRows * kEpiStride * 4 <= 2 * (kBM + kBN) * kLdsStride, "epilogue tiles must fit the staging buffers");
     __shared__ int row_node[kBM];
-    __shared__ int row_cb[kBM];
-    __shared__ int row_ce[kBM];
+    __shared__ int row_ar[kBM];     // number of children
+    __shared__ int row_cb[kBM];     // start of the child list in child_idx
+    __shared__ int4 row_kid[kBM];   // first four child ids
 
     const int t = threadIdx.x;
     const int lane = t & 63, wave = t >> 6;
@@ -469,17 +425,21 @@ level_kernel(const LevelArgs a) {
 
     if (t < kBM) {
         const int grow = tile_row0 + t;
-        int node = -1, cb = 0, ce = 0;
-        if (grow < a.n_rows) {
-            node = a.level_nodes[grow];
-            if constexpr (MODE == MODE_INTERNAL) {
-                cb = a.child_ptr[node];
-                ce = a.child_ptr[node + 1];
+        int node = -1;
+        if constexpr (MODE == MODE_INTERNAL) {
+            int4 r0 = make_int4(-1, 0, 0, 0), r1 = make_int4(-1, -1, -1, -1);
+            if (grow < a.n_rows) {
+                r0 = a.row_rec[2 * (int64_t)grow];
+                r1 = a.row_rec[2 * (int64_t)grow + 1];
             }
+            node = r0.x;
+            row_ar[t] = r0.y;
+            row_cb[t] = r0.z;
+            row_kid[t] = r1;
+        } else {
+            if (grow < a.n_rows) node = a.level_nodes[grow];
         }
         row_node[t] = node;
-        row_cb[t] = cb;
-        row_ce[t] = ce;
     }
     __syncthreads();
 
@@ -494,7 +454,7 @@ level_kernel(const LevelArgs a) {
 #ifdef JITDB_EXPERIMENT
     if (!(a.experiment & 1))
 #endif
-    block_gemm<T, MODE>(a, lds_a, lds_b, row_node, tile_row0, col_tile, acc);
+    block_gemm<T, MODE>(a, lds, row_node, tile_row0, col_tile, acc);
 #ifdef JITDB_EXPERIMENT
     if (a.experiment & 2) {
         float sum = 0.0f;
@@ -526,7 +486,7 @@ level_kernel(const LevelArgs a) {
                 }
         }
     } else {
-        // The cell update runs row-major.  In two passes of 64 rows the gate values
+        // The cell update runs row-major.  In two passes of 128 rows the gate values
         // go through LDS (the staging buffers are free now): each wave writes
         // i*u, o and the x part of the forget gate for its 32 units, then every
         // thread takes four rows x four consecutive units, so that the rows of the
@@ -554,7 +514,7 @@ level_kernel(const LevelArgs a) {
                 const int col = wn * 32 + l32;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int rl = wm * 32 + (v >> 2) * 8 + hf * 4 + (v & 3);
+                    const int rl = wm * 32 + (v >> 2) * 8 + hf * 4 + (v & 3);   // 0..127
                     const float gi = sigmoid_t<T>(acc[p][0][v] + bi);
                     const float go = sigmoid_t<T>(acc[p][1][v] + bo);
                     const float gu = tanh_t<T>(acc[p][2][v] + bu);
@@ -565,48 +525,70 @@ level_kernel(const LevelArgs a) {
             }
             __syncthreads();
             float4 cc[4], go4[4], fx4[4];
-            int node[4], e[4], ce[4];
+            int node[4], tr[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int rl = (t >> 4) + 16 * q;
-                const int tr = (rl >> 5) * 64 + p * 32 + (rl & 31);
-                node[q] = row_node[tr];
-                e[q] = row_cb[tr];
-                ce[q] = row_ce[tr];
+                const int rl = (t >> 4) + 32 * q;
+                tr[q] = (rl >> 5) * 64 + p * 32 + (rl & 31);
+                node[q] = row_node[tr[q]];
                 const int so = rl * kEpiStride + (t & 15) * 4;
                 cc[q] = *reinterpret_cast<const float4 *>(s_iu + so);
                 go4[q] = *reinterpret_cast<const float4 *>(s_o + so);
                 if constexpr (MODE == MODE_INTERNAL) fx4[q] = *reinterpret_cast<const float4 *>(s_fx + so);
             }
             if constexpr (MODE == MODE_INTERNAL) {
-                // One child of each of the four rows per round.  A row that has run out
-                // of children re-reads its last one with weight zero, which keeps the
-                // loads unconditional and independent of each other.
-                int64_t kofs[4];
+                // Children are taken two per row and round, for four rows at once: sixteen
+                // independent 16-byte loads in flight per thread.  The first four child ids
+                // of a row sit in LDS; longer lists (rare) continue from child_idx.  A slot
+                // without a child re-reads the row's last child with weight zero, which
+                // keeps every load unconditional.
+                int ar[4];
+                int max_ar = 0;
 #pragma unroll
-                for (int q = 0; q < 4; ++q) kofs[q] = unit_ld;
-                while ((e[0] < ce[0]) | (e[1] < ce[1]) | (e[2] < ce[2]) | (e[3] < ce[3])) {
-                    float wgt[4];
+                for (int q = 0; q < 4; ++q) {
+                    ar[q] = node[q] >= 0 ? row_ar[tr[q]] : 0;
+                    max_ar = max(max_ar, ar[q]);
+                }
+                int64_t last[4];
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const bool has = e[q] < ce[q];
-                        wgt[q] = has ? 1.0f : 0.0f;
-                        if (has) kofs[q] = (int64_t)a.child_idx[e[q]] * a.Hq + unit_ld;
-                        ++e[q];
-                    }
-                    float4 pk[4], ck[4];
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        pk[q] = *reinterpret_cast<const float4 *>(a.P + kofs[q]);
-                        ck[q] = *reinterpret_cast<const float4 *>(a.cs + kofs[q]);
-                    }
+                for (int q = 0; q < 4; ++q) last[q] = unit_ld;
+                for (int c0 = 0; c0 < max_ar; c0 += 2) {
+                    int64_t ofs[4][2];
+                    float wgt[4][2];
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
-                        cc[q].x += wgt[q] * sigmoid_t<T>(fx4[q].x + pk[q].x) * ck[q].x;
-                        cc[q].y += wgt[q] * sigmoid_t<T>(fx4[q].y + pk[q].y) * ck[q].y;
-                        cc[q].z += wgt[q] * sigmoid_t<T>(fx4[q].z + pk[q].z) * ck[q].z;
-                        cc[q].w += wgt[q] * sigmoid_t<T>(fx4[q].w + pk[q].w) * ck[q].w;
+                        int4 kids = make_int4(0, 0, 0, 0);
+                        if (c0 < 4) kids = row_kid[tr[q]];
+#pragma unroll
+                        for (int j = 0; j < 2; ++j) {
+                            const int c = c0 + j;
+                            const bool has = c < ar[q];
+                            int kid;
+                            if (c0 == 0) kid = j ? kids.y : kids.x;
+                            else if (c0 == 2) kid = j ? kids.w : kids.z;
+                            else kid = has ? a.child_idx[row_cb[tr[q]] + c] : 0;
+                            if (has) last[q] = (int64_t)kid * a.Hq + unit_ld;
+                            ofs[q][j] = last[q];
+                            wgt[q][j] = has ? 1.0f : 0.0f;
+                        }
                     }
+                    float4 pk[4][2], ck[4][2];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+#pragma unroll
+                        for (int j = 0; j < 2; ++j) {
+                            pk[q][j] = *reinterpret_cast<const float4 *>(a.P + ofs[q][j]);
+                            ck[q][j] = *reinterpret_cast<const float4 *>(a.cs + ofs[q][j]);
+                        }
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+#pragma unroll
+                        for (int j = 0; j < 2; ++j) {
+                            cc[q].x += wgt[q][j] * sigmoid_t<T>(fx4[q].x + pk[q][j].x) * ck[q][j].x;
+                            cc[q].y += wgt[q][j] * sigmoid_t<T>(fx4[q].y + pk[q][j].y) * ck[q][j].y;
+                            cc[q].z += wgt[q][j] * sigmoid_t<T>(fx4[q].z + pk[q][j].z) * ck[q][j].z;
+                            cc[q].w += wgt[q][j] * sigmoid_t<T>(fx4[q].w + pk[q][j].w) * ck[q][j].w;
+                        }
                 }
             }
 #pragma unroll
@@ -683,9 +665,10 @@ struct ScopedLaunchTimer {
 };
 
 struct ForwardWs {
-    void *Wp, *Up;
+    void *Bp;
     float *bp;
-    void *hsum;
+    void *stack;  // the current level's stacked input, (N + 256) rows of Dp + Hp
+    int4 *row_rec; // the current level's row records, two int4 per row
     void *hs;     // nullptr when h_out can serve (H == Hp)
     float *P;
     float *cs;    // nullptr when c_out can serve (H == Hq)
@@ -717,11 +700,12 @@ Dims make_dims(int D, int H, jitdb_dtype dtype) {
 ForwardWs carve_forward_ws(int64_t n, int64_t e, const Dims &d, void *base) {
     Carver c(base);
     ForwardWs w;
-    const int64_t hsum_rows = e < n ? e : n;   // an internal node has at least one child
-    w.Wp = c.take<char>((size_t)d.NP * d.Dp * d.esz);
-    w.Up = c.take<char>((size_t)d.NPU * d.Hp * d.esz);
+    (void)e;
+    w.Bp = c.take<char>((size_t)d.NPU * (d.Dp + d.Hp) * d.esz);
     w.bp = c.take<float>(d.NP);
-    w.hsum = c.take<char>((size_t)hsum_rows * d.Hp * d.esz);
+    // one level at a time; whole row tiles are read, hence the 256 spare rows
+    w.stack = c.take<char>((size_t)(n + kBM) * (d.Dp + d.Hp) * d.esz);
+    w.row_rec = c.take<int4>((size_t)2 * (n + kBM));
     w.hs = (d.H == d.Hp) ? nullptr : c.take<char>((size_t)n * d.Hp * d.esz);
     w.P = c.take<float>((size_t)n * d.Hq);
     w.cs = (d.H == d.Hq) ? nullptr : c.take<float>((size_t)n * d.Hq);
@@ -745,12 +729,12 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
     const int32_t *lp = s->host_level_ptr;
 
     {
-        const int64_t total = (int64_t)d.NP * d.Dp + (int64_t)d.NPU * d.Hp;
+        const int64_t total = (int64_t)d.NPU * (d.Dp + d.Hp);
         const unsigned grid = (unsigned)(ceil_div(total, kThreads) < 4096 ? ceil_div(total, kThreads) : 4096);
         ScopedLaunchTimer tm(JITDB_K_PACK, st);
         pack_weights_kernel<T><<<grid, kThreads, 0, st>>>(
             static_cast<const T *>(W), static_cast<const T *>(U), b, d.D, d.H, d.Dp, d.Hp, d.NP, d.NPU,
-            static_cast<T *>(w.Wp), static_cast<T *>(w.Up), w.bp);
+            static_cast<T *>(w.Bp), w.bp);
         JITDB_LAUNCH_CHECK();
     }
 
@@ -758,10 +742,11 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
 #ifdef JITDB_EXPERIMENT
     a.experiment = getenv("JITDB_EXPERIMENT") ? atoi(getenv("JITDB_EXPERIMENT")) : 0;
 #endif
-    a.x = x; a.hsum = w.hsum;
+    a.stack = w.stack;
     a.hs = w.hs ? w.hs : h_out;
-    a.Wp = w.Wp; a.Up = w.Up; a.bp = w.bp;
-    a.child_ptr = s->child_ptr; a.child_idx = s->child_idx;
+    a.Bp = w.Bp; a.bp = w.bp;
+    a.child_idx = s->child_idx;
+    a.row_rec = w.row_rec;
     a.P = w.P; a.c_out = c_out; a.h_out = h_out;
     a.cs = w.cs ? w.cs : c_out;
     a.Hq = d.Hq;
@@ -774,12 +759,19 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
         a.level_nodes = s->perm + lp[l];
         a.n_rows = n_rows;
         const int row_tiles = (int)ceil_div(n_rows, kBM);
-        if (l > 0) {
-            const int64_t pieces = (int64_t)n_rows * (d.Hp / Traits<T>::VEC);
+        {   // stack: gather the level's x rows and child sums into one dense matrix
+            const int Kp = d.Dp + (l > 0 ? d.Hp : 0);
+            const int64_t pieces = (int64_t)n_rows * (Kp / Traits<T>::VEC);
+            const unsigned grid = (unsigned)ceil_div(pieces, kThreads);
             ScopedLaunchTimer tm(JITDB_K_CHILD_SUM, st);
-            child_sum_kernel<T><<<(unsigned)ceil_div(pieces, kThreads), kThreads, 0, st>>>(
-                static_cast<const T *>(a.hs), d.Hp, a.level_nodes, s->child_ptr, s->child_idx,
-                static_cast<T *>(w.hsum), n_rows);
+            if (l == 0)
+                stack_kernel<T, false><<<grid, kThreads, 0, st>>>(
+                    static_cast<const T *>(x), d.D, d.Dp, static_cast<const T *>(a.hs), d.Hp, a.level_nodes,
+                    s->child_ptr, s->child_idx, static_cast<T *>(w.stack), w.row_rec, n_rows);
+            else
+                stack_kernel<T, true><<<grid, kThreads, 0, st>>>(
+                    static_cast<const T *>(x), d.D, d.Dp, static_cast<const T *>(a.hs), d.Hp, a.level_nodes,
+                    s->child_ptr, s->child_idx, static_cast<T *>(w.stack), w.row_rec, n_rows);
             JITDB_LAUNCH_CHECK();
         }
         a.n_col_tiles = d.NP / kBN;
@@ -787,9 +779,9 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
         {
             ScopedLaunchTimer tm(l == 0 ? JITDB_K_LEAF : JITDB_K_INTERNAL, st);
             if (l == 0)
-                level_kernel<T, MODE_LEAF><<<a.n_blocks, kThreads, 0, st>>>(a);
+                level_kernel<T, MODE_LEAF><<<a.n_blocks, kGemmThreads, 0, st>>>(a);
             else
-                level_kernel<T, MODE_INTERNAL><<<a.n_blocks, kThreads, 0, st>>>(a);
+                level_kernel<T, MODE_INTERNAL><<<a.n_blocks, kGemmThreads, 0, st>>>(a);
         }
         JITDB_LAUNCH_CHECK();
         if (l + 1 < L) {   // these nodes have parents (except roots, whose rows go unused)
@@ -797,7 +789,7 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
             a.n_blocks = row_tiles * a.n_col_tiles;
             {
                 ScopedLaunchTimer tm(JITDB_K_PROJ, st);
-                level_kernel<T, MODE_PROJ><<<a.n_blocks, kThreads, 0, st>>>(a);
+                level_kernel<T, MODE_PROJ><<<a.n_blocks, kGemmThreads, 0, st>>>(a);
             }
             JITDB_LAUNCH_CHECK();
         }
