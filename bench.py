@@ -31,6 +31,19 @@ PEAK_F32_MFMA_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
 
+def measured_traffic(cfg, kernel_class):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE + WRITE_SIZE scaled by a copy kernel of known size), or None."""
+    path = os.path.join(ROOT, "profiles", f"level_kernel_{cfg.dtype}_config{cfg.index}_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith(f"traffic_bytes_per_launch[{kernel_class}]:"):
+                return float(line.split(":", 1)[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
 def log(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
@@ -44,6 +57,8 @@ def main():
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not bracket kernels with events inside the timed region")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one 1 GiB device copy (reference for HBM counters)")
     ap.add_argument("--cpu-trees", type=int, default=0, help="trees in the oracle sample (0 = auto)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -100,6 +115,17 @@ def main():
         J.jitdb_treelstm_forward(xt, Wt, Ut, bt, s, stream=stream, workspace=ws_f, out=(h, c))
         return s
 
+    if args.calibration_copy:
+        # a plain copy of known size (1 GiB read + 1 GiB written, more than the 256 MB last-level
+        # cache holds), for scaling the
+        # FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this command
+        src = torch.empty(256 * 1024 * 1024, dtype=torch.float32, device=dev).fill_(1.0)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -137,7 +163,8 @@ def main():
         "internal": n_int * (2.0 * D * 4 * H + 2.0 * H * 3 * H),
         "proj": E * 2.0 * H * H,
     }
-    bytes_child_sum = (E + n_int) * H * esz
+    # stack step: reads every x row and every child's h row once, writes the stacked rows
+    bytes_stack = (2 * N * D + E * H + n_int * H) * esz
     kernels = {}
     roof = None
     if prof is not None:
@@ -148,18 +175,18 @@ def main():
                 kernels[name] = {"ms_per_step": ms, "launches_per_step": n_l,
                                  "tflops": flops[name] / (ms * 1e-3) / 1e12,
                                  "frac_mfma_peak": flops[name] / (ms * 1e-3) / 1e12 / peak_tflops}
-        ms = prof["child_sum"]["ms"] / args.steps
+        ms = prof["stack"]["ms"] / args.steps
         if ms > 0:
-            kernels["child_sum"] = {"ms_per_step": ms,
-                                    "launches_per_step": prof["child_sum"]["launches"] / args.steps,
-                                    "gbs": bytes_child_sum / (ms * 1e-3) / 1e9,
-                                    "frac_hbm_peak": bytes_child_sum / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
+            kernels["stack"] = {"ms_per_step": ms,
+                                "launches_per_step": prof["stack"]["launches"] / args.steps,
+                                "gbs": bytes_stack / (ms * 1e-3) / 1e9,
+                                "frac_hbm_peak": bytes_stack / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
         kernels["pack"] = {"ms_per_step": prof["pack"]["ms"] / args.steps}
         dom = max(("leaf", "internal", "proj"), key=lambda k: kernels.get(k, {}).get("ms_per_step", 0.0))
         k = kernels[dom]
         roof = {"kernel": f"level_kernel<{cfg.dtype},{dom}>", "bound": "mfma",
                 "achieved": k["tflops"], "peak": peak_tflops, "unit": "TFLOP/s",
-                "frac": k["frac_mfma_peak"], "traffic": None,
+                "frac": k["frac_mfma_peak"], "traffic": measured_traffic(cfg, dom),
                 "avg_launch_ms": k["ms_per_step"] / max(k["launches_per_step"], 1),
                 "flops_per_step": flops[dom], "dropped_events": prof["dropped"]}
         mfma_ms = sum(kernels[n]["ms_per_step"] for n in ("leaf", "internal", "proj") if n in kernels)

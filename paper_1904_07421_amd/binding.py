@@ -43,7 +43,7 @@ class _ScheduleStruct(ctypes.Structure):
     ]
 
 
-K_CLASSES = ("pack", "child_sum", "leaf", "internal", "proj")
+K_CLASSES = ("pack", "stack", "leaf", "internal", "proj")
 
 
 class _ProfileStruct(ctypes.Structure):

@@ -332,10 +332,14 @@ __device__ __forceinline__ void block_gemm(const LevelArgs &a, char *lds, const 
 
     auto ld16 = [](const char *p) __attribute__((always_inline)) { return *reinterpret_cast<const u32x4 *>(p); };
 
+    // B row groups moved per stage.  The internal levels move the forget rows in the h
+    // part too although they are not multiplied there: with x and h parts alike, every
+    // iteration of the pipeline is one straight-line block that can be scheduled as a whole.
+    constexpr int NG_F = (MODE == MODE_LEAF) ? 3 : 4;
+
     StageRegs r;
     // global -> registers, stage g
-    auto fetch = [&](int g, auto ng_tag) __attribute__((always_inline)) {
-        constexpr int NG = decltype(ng_tag)::value;
+    auto fetch = [&](int g) __attribute__((always_inline)) {
         const int64_t kb = (int64_t)g * (BK * ESZ);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -343,61 +347,74 @@ __device__ __forceinline__ void block_gemm(const LevelArgs &a, char *lds, const 
             else r.a[i] = ld16(ap[0] + i * a_step + kb);
         }
 #pragma unroll
-        for (int i = 0; i < NG; ++i) r.b[i] = ld16(bp + i * b_step + kb);
+        for (int i = 0; i < NG_F; ++i) r.b[i] = ld16(bp + i * b_step + kb);
     };
     // registers -> LDS
-    auto stash = [&](char *buf, auto ng_tag) __attribute__((always_inline)) {
-        constexpr int NG = decltype(ng_tag)::value;
+    auto stash = [&](char *buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(buf + a_wr + i * 64 * kLdsStride) = r.a[i];
 #pragma unroll
-        for (int i = 0; i < NG; ++i) *reinterpret_cast<u32x4 *>(buf + b_wr + i * 32 * kLdsStride) = r.b[i];
+        for (int i = 0; i < NG_F; ++i) *reinterpret_cast<u32x4 *>(buf + b_wr + i * 32 * kLdsStride) = r.b[i];
     };
-    // LDS -> MFMA: K groups [h0, h0 + 2) of one stage
-    auto mma = [&](const char *buf, int h0, auto ng_tag) __attribute__((always_inline)) {
+    constexpr int kBufBytes = (kBM + kBN) * kLdsStride;
+    const std::integral_constant<int, NG_X> ngx;
+    const std::integral_constant<int, NG_H> ngh;
+    const int last = n_stages - 1;
+
+    // One iteration: stage g is multiplied out of buffer g&1 while stage g+1 moves from
+    // the registers to the other buffer and stage g+2 from global memory to the registers.
+    // The issue order is fixed by hand: per K group first its LDS reads, then its MFMAs
+    // with one LDS write (K groups 0, 1) or one global load (K groups 2, 3) after every
+    // quarter of them.  Left to itself the compiler issues all LDS writes first, and since
+    // a wave issues in order its MFMAs then wait until the 64-bytes-per-clock write port
+    // has taken the writes of all eight waves.  The last iterations repeat the stash /
+    // fetch of the last stage (into the idle buffer, from addresses in range) instead of
+    // branching around them.
+    auto iteration = [&](int g, auto ng_tag) __attribute__((always_inline)) {
         constexpr int NG = decltype(ng_tag)::value;
-        const char *sa = buf + a_rd;
-        const char *sb = buf + b_rd;
+        constexpr int M = 2 * NG;   // MFMA tiles per K group
+        const char *sa = lds + (g & 1) * kBufBytes + a_rd;
+        const char *sb = lds + (g & 1) * kBufBytes + b_rd;
+        char *nxt = lds + ((g & 1) ^ 1) * kBufBytes;
+        const int gf = g + 2 < last ? g + 2 : last;
+        const int64_t kb = (int64_t)gf * (BK * ESZ);
 #pragma unroll
-        for (int hh = 0; hh < 2; ++hh) {
-            const int h = h0 + hh;
+        for (int h = 0; h < 4; ++h) {
             u32x4 av[2], bv[NG];
 #pragma unroll
             for (int i = 0; i < 2; ++i)
                 av[i] = *reinterpret_cast<const u32x4 *>(sa + i * 32 * kLdsStride + h * 32);
 #pragma unroll
-            for (int g = 0; g < NG; ++g)
-                bv[g] = *reinterpret_cast<const u32x4 *>(sb + g * 32 * kLdsStride + h * 32);
+            for (int q = 0; q < NG; ++q)
+                bv[q] = *reinterpret_cast<const u32x4 *>(sb + q * 32 * kLdsStride + h * 32);
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int j = 0; j < 4; ++j) {
 #pragma unroll
-                for (int g = 0; g < NG; ++g) mfma_step<T>(av[i], bv[g], acc[i][g]);
+                for (int m = j * M / 4; m < (j + 1) * M / 4; ++m)
+                    mfma_step<T>(av[m / NG], bv[m % NG], acc[m / NG][m % NG]);
+                __builtin_amdgcn_sched_barrier(0);
+                const int o = (h & 1) * 4 + j;      // which of the eight moves of this half
+                if (h < 2) {                         // registers -> LDS
+                    if (o < 4)
+                        *reinterpret_cast<u32x4 *>(nxt + a_wr + o * 64 * kLdsStride) = r.a[o];
+                    else if (o - 4 < NG_F)
+                        *reinterpret_cast<u32x4 *>(nxt + b_wr + (o - 4) * 32 * kLdsStride) = r.b[o - 4];
+                } else {                             // global -> registers
+                    if (o < 4) {
+                        if constexpr (MODE == MODE_PROJ) r.a[o] = ld16(ap[o] + kb);
+                        else r.a[o] = ld16(ap[0] + o * a_step + kb);
+                    } else if (o - 4 < NG_F) {
+                        r.b[o - 4] = ld16(bp + (o - 4) * b_step + kb);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
-    };
-
-    constexpr int kBufBytes = (kBM + kBN) * kLdsStride;
-    const std::integral_constant<int, NG_X> ngx;
-    const std::integral_constant<int, NG_H> ngh;
-    // Stage kinds of the stash (g+1) and the fetch (g+2) differ from that of the MFMAs (g)
-    // only next to the boundary between the parts; they move registers only, so a uniform
-    // branch there is cheap.  The MFMA code of the two parts stays in separate loops so that
-    // the accumulators never pass through a branch merge.
-    auto fetch_any = [&](int g) __attribute__((always_inline)) { if (g < n_x) fetch(g, ngx); else fetch(g, ngh); };
-    auto stash_any = [&](int g, char *buf) __attribute__((always_inline)) { if (g < n_x) stash(buf, ngx); else stash(buf, ngh); };
-    auto iteration = [&](int g, auto ng_tag) __attribute__((always_inline)) {
-        char *cur = lds + (g & 1) * kBufBytes;
-        char *nxt = lds + ((g & 1) ^ 1) * kBufBytes;
-        if (g + 1 < n_stages) stash_any(g + 1, nxt);
-        mma(cur, 0, ng_tag);
-        __builtin_amdgcn_sched_barrier(0);
-        if (g + 2 < n_stages) fetch_any(g + 2);
-        __builtin_amdgcn_sched_barrier(0);
-        mma(cur, 2, ng_tag);
         __syncthreads();
     };
-    fetch_any(0);
-    stash_any(0, lds);
-    if (n_stages > 1) fetch_any(1);
+    fetch(0);
+    stash(lds);
+    fetch(1 < last ? 1 : last);
     __syncthreads();
     for (int g = 0; g < n_x; ++g) iteration(g, ngx);
     for (int g = n_x; g < n_stages; ++g) iteration(g, ngh);
@@ -763,7 +780,7 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
             const int Kp = d.Dp + (l > 0 ? d.Hp : 0);
             const int64_t pieces = (int64_t)n_rows * (Kp / Traits<T>::VEC);
             const unsigned grid = (unsigned)ceil_div(pieces, kThreads);
-            ScopedLaunchTimer tm(JITDB_K_CHILD_SUM, st);
+            ScopedLaunchTimer tm(JITDB_K_STACK, st);
             if (l == 0)
                 stack_kernel<T, false><<<grid, kThreads, 0, st>>>(
                     static_cast<const T *>(x), d.D, d.Dp, static_cast<const T *>(a.hs), d.Hp, a.level_nodes,
