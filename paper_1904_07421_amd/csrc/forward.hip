@@ -206,8 +206,9 @@ struct LevelArgs {
     const int32_t *level_nodes;  // perm + level start: row -> node id
     const int4 *row_rec;         // two int4 per level row, written by stack_kernel (internal levels)
     const int32_t *child_idx;
-    // per-child forget projections, rows by node id, stride Hq
-    float *P;
+    // per-child forget projections U_f h_k, rows by node id, stride Hq, element type T
+    // (bf16 in the bf16 path: it halves the largest stream of the forward)
+    void *P;
     float *cs;            // [N, Hq] c with rows padded to 4 floats, or == c_out when H % 4 == 0
     // outputs
     float *c_out;         // [N, H]
@@ -499,7 +500,7 @@ level_kernel(const LevelArgs a) {
                 for (int v = 0; v < 16; ++v) {
                     const int r = wm * 64 + i * 32 + (v >> 2) * 8 + hf * 4 + (v & 3);
                     const int node = row_node[r];
-                    if (node >= 0) a.P[(int64_t)node * a.Hq + unit] = acc[i][g][v];
+                    if (node >= 0) static_cast<T *>(a.P)[(int64_t)node * a.Hq + unit] = from_f32<T>(acc[i][g][v]);
                 }
         }
     } else {
@@ -594,7 +595,13 @@ level_kernel(const LevelArgs a) {
                     for (int q = 0; q < 4; ++q)
 #pragma unroll
                         for (int j = 0; j < 2; ++j) {
-                            pk[q][j] = *reinterpret_cast<const float4 *>(a.P + ofs[q][j]);
+                            if constexpr (sizeof(T) == 4) {
+                                pk[q][j] = *reinterpret_cast<const float4 *>(static_cast<const float *>(a.P) + ofs[q][j]);
+                            } else {
+                                const uint2 w = *reinterpret_cast<const uint2 *>(static_cast<const bf16_t *>(a.P) + ofs[q][j]);
+                                pk[q][j] = make_float4(__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xFFFF0000u),
+                                                       __uint_as_float(w.y << 16), __uint_as_float(w.y & 0xFFFF0000u));
+                            }
                             ck[q][j] = *reinterpret_cast<const float4 *>(a.cs + ofs[q][j]);
                         }
 #pragma unroll
@@ -687,7 +694,7 @@ struct ForwardWs {
     void *stack;  // the current level's stacked input, (N + 256) rows of Dp + Hp
     int4 *row_rec; // the current level's row records, two int4 per row
     void *hs;     // nullptr when h_out can serve (H == Hp)
-    float *P;
+    void *P;
     float *cs;    // nullptr when c_out can serve (H == Hq)
     size_t bytes;
 };
@@ -724,7 +731,7 @@ ForwardWs carve_forward_ws(int64_t n, int64_t e, const Dims &d, void *base) {
     w.stack = c.take<char>((size_t)(n + kBM) * (d.Dp + d.Hp) * d.esz);
     w.row_rec = c.take<int4>((size_t)2 * (n + kBM));
     w.hs = (d.H == d.Hp) ? nullptr : c.take<char>((size_t)n * d.Hp * d.esz);
-    w.P = c.take<float>((size_t)n * d.Hq);
+    w.P = c.take<char>((size_t)n * d.Hq * d.esz);
     w.cs = (d.H == d.Hq) ? nullptr : c.take<float>((size_t)n * d.Hq);
     w.bytes = c.off;
     return w;
