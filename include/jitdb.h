@@ -127,8 +127,8 @@ size_t jitdb_treelstm_workspace_bytes(int64_t n_nodes, int64_t n_edges,
  *   h_out  dev [N, H] row-major, row = node id.          dtype elements
  *   c_out  dev [N, H] row-major, row = node id.          fp32 (both dtypes)
  *
- * D >= 1 with D % 4 == 0, H >= 1 (any H; rows are padded internally); x, h_out and
- * c_out 16-byte aligned.  With
+ * D >= 1, H >= 1 (any values; rows are padded internally; D % 4 == 0 takes the fast
+ * row copy); x, h_out and c_out 16-byte aligned.  With
  * JITDB_BF16, h is rounded to bfloat16 (nearest even) when stored and that
  * rounded value feeds the parents; sums, gates and c stay fp32.
  *
@@ -159,7 +159,7 @@ int jitdb_treelstm_forward(const void *x, const void *W, const void *U, const fl
  * Process-wide state, not thread safe: use from one thread, one stream at a time.
  */
 typedef enum {
-    JITDB_K_PACK = 0,       /* weight re-packing */
+    JITDB_K_PACK = 0,       /* once per call: weight re-packing, row records */
     JITDB_K_STACK = 1,      /* stack: row = [x_j | sum_k h_k] per level */
     JITDB_K_LEAF = 2,       /* leaf level: W x + cell */
     JITDB_K_INTERNAL = 3,   /* internal levels: [x;hs][W;U] + cell with per-child forget gates */

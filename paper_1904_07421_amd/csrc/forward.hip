@@ -50,7 +50,8 @@ constexpr int kUnit = 32;       // hidden units per MFMA column tile
 constexpr int kGateTile = 128;  // packed rows per unit tile (4 gates x 32 units)
 
 constexpr int kEpiRows = 128;   // rows per epilogue pass
-constexpr int kEpiStride = 68;  // floats per epilogue LDS row: 64 units + 4 (keeps 16-byte alignment)
+constexpr int kEpiStride = 72;  // floats per epilogue LDS row: 64 units + 8; rows 4 apart fall 32 banks apart
+constexpr int kProjStride = 264; // same for the projection's 256-unit rows
 constexpr int kLdsStride = 144; // stage row (128 bytes) + 16: 128-bit LDS reads of 32 rows hit distinct banks
 
 enum : int { MODE_LEAF = 0, MODE_INTERNAL = 1, MODE_PROJ = 2 };
@@ -117,19 +118,53 @@ pack_weights_kernel(const T *__restrict__ W, const T *__restrict__ U, const floa
     }
 }
 
+// ---- row records -------------------------------------------------------------------
+// What the stack step and the cell update need to know about the node at level
+// position p, in one 32-byte record: { node, arity, CSR start, - } { first four child
+// ids (-1 where there is none) }.  Written once per forward for all positions, so that
+// the per-level kernels start from one load instead of the chain perm -> child_ptr ->
+// child_idx.
+__global__ void __launch_bounds__(kThreads)
+row_record_kernel(const int32_t *__restrict__ perm, const int32_t *__restrict__ child_ptr,
+                  const int32_t *__restrict__ child_idx, int4 *__restrict__ row_rec, int n) {
+    const int64_t p = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (p >= n) return;
+    const int node = perm[p];
+    const int cb = child_ptr[node], ar = child_ptr[node + 1] - cb;
+    int kid[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) kid[j] = j < ar ? child_idx[cb + j] : -1;
+    row_rec[2 * p] = make_int4(node, ar, cb, 0);
+    row_rec[2 * p + 1] = make_int4(kid[0], kid[1], kid[2], kid[3]);
+}
+
 // ---- stack -------------------------------------------------------------------------
 // The paper's "stack" step (section 4.3): the samples of one slot are laid side by
 // side on the batch axis.  Row r of the level's dense input matrix A is
 //     [ x_j (D values, zero padded to Dp) | hsum_j = sum over children of h_k (Hp values) ]
 // for the r-th node j of the level; leaves have the x part only.  One thread
 // per 16-byte piece of a row; child rows come from hs (stride Hp, pad columns zero,
-// rows by node id) in 16-byte pieces, 16 * cpr bytes contiguous per row.
+// rows by node id) in 16-byte pieces, up to four children in flight.
+template <typename T>
+__device__ __forceinline__ void add_piece(float (&acc)[Traits<T>::VEC], const uint4 &v) {
+    if constexpr (sizeof(T) == 4) {
+        acc[0] += __uint_as_float(v.x); acc[1] += __uint_as_float(v.y);
+        acc[2] += __uint_as_float(v.z); acc[3] += __uint_as_float(v.w);
+    } else {
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            acc[2 * j] += __uint_as_float(w[j] << 16);
+            acc[2 * j + 1] += __uint_as_float(w[j] & 0xFFFF0000u);
+        }
+    }
+}
+
 template <typename T, bool WITH_H>
 __global__ void __launch_bounds__(kThreads)
 stack_kernel(const T *__restrict__ x, int D, int Dp, const T *__restrict__ hs, int Hp,
-             const int32_t *__restrict__ level_nodes, const int32_t *__restrict__ child_ptr,
-             const int32_t *__restrict__ child_idx, T *__restrict__ A, int4 *__restrict__ row_rec,
-             int n_rows) {
+             const int4 *__restrict__ row_rec, const int32_t *__restrict__ child_idx,
+             T *__restrict__ A, int n_rows) {
     constexpr int VEC = Traits<T>::VEC;
     const int Kp = Dp + (WITH_H ? Hp : 0);
     const int cpr = Kp / VEC;
@@ -137,48 +172,52 @@ stack_kernel(const T *__restrict__ x, int D, int Dp, const T *__restrict__ hs, i
     const int64_t row = gid / cpr;
     const int ch = (int)(gid % cpr);
     if (row >= n_rows) return;
-    const int node = level_nodes[row];
+    const int4 r0 = row_rec[2 * row];
+    const int node = r0.x;
     const int k0 = ch * VEC;
-    if (WITH_H && ch == 0) {
-        // what the cell update needs to know about this row, in one 32-byte record:
-        // { node, arity, CSR start, - } { first four child ids (-1 where there is none) }
-        const int cb = child_ptr[node], ar = child_ptr[node + 1] - cb;
-        int kid[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) kid[j] = j < ar ? child_idx[cb + j] : -1;
-        row_rec[2 * row] = make_int4(node, ar, cb, 0);
-        row_rec[2 * row + 1] = make_int4(kid[0], kid[1], kid[2], kid[3]);
-    }
     uint4 o = make_uint4(0u, 0u, 0u, 0u);
     if (k0 < Dp) {
-        // x rows are 4-element aligned (D % 4 == 0): move 4-element halves, zero past D
         const T *src = x + (int64_t)node * D + k0;
-        if constexpr (sizeof(T) == 4) {
-            if (k0 < D) o = *reinterpret_cast<const uint4 *>(src);
+        if ((D & 3) == 0) {
+            // rows of x are 4-element aligned: move 4-element halves, zero past D
+            if constexpr (sizeof(T) == 4) {
+                if (k0 < D) o = *reinterpret_cast<const uint4 *>(src);
+            } else {
+                if (k0 < D) { const uint2 q = *reinterpret_cast<const uint2 *>(src); o.x = q.x; o.y = q.y; }
+                if (k0 + 4 < D) { const uint2 q = *reinterpret_cast<const uint2 *>(src + 4); o.z = q.x; o.w = q.y; }
+            }
         } else {
-            if (k0 < D) { const uint2 q = *reinterpret_cast<const uint2 *>(src); o.x = q.x; o.y = q.y; }
-            if (k0 + 4 < D) { const uint2 q = *reinterpret_cast<const uint2 *>(src + 4); o.z = q.x; o.w = q.y; }
+            // any other D: element by element
+            T e[VEC];
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) e[j] = (k0 + j < D) ? src[j] : T(0);
+            if constexpr (sizeof(T) == 4) {
+                o.x = __float_as_uint(e[0]); o.y = __float_as_uint(e[1]);
+                o.z = __float_as_uint(e[2]); o.w = __float_as_uint(e[3]);
+            } else {
+                o.x = (uint32_t)e[0] | ((uint32_t)e[1] << 16); o.y = (uint32_t)e[2] | ((uint32_t)e[3] << 16);
+                o.z = (uint32_t)e[4] | ((uint32_t)e[5] << 16); o.w = (uint32_t)e[6] | ((uint32_t)e[7] << 16);
+            }
         }
     } else if constexpr (WITH_H) {
         const int kh = k0 - Dp;
-        const int cb = child_ptr[node], ce = child_ptr[node + 1];
+        const int ar = r0.y;
+        const int4 kids = row_rec[2 * row + 1];
+        const int kid[4] = {kids.x, kids.y, kids.z, kids.w};
         float acc[VEC];
 #pragma unroll
         for (int j = 0; j < VEC; ++j) acc[j] = 0.0f;
-        for (int e = cb; e < ce; ++e) {
-            const int k = child_idx[e];
-            const uint4 v = *reinterpret_cast<const uint4 *>(hs + (int64_t)k * Hp + kh);
-            if constexpr (sizeof(T) == 4) {
-                acc[0] += __uint_as_float(v.x); acc[1] += __uint_as_float(v.y);
-                acc[2] += __uint_as_float(v.z); acc[3] += __uint_as_float(v.w);
-            } else {
-                const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        uint4 v[4];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    acc[2 * j] += __uint_as_float(w[j] << 16);
-                    acc[2 * j + 1] += __uint_as_float(w[j] & 0xFFFF0000u);
-                }
-            }
+        for (int j = 0; j < 4; ++j) {
+            v[j] = make_uint4(0u, 0u, 0u, 0u);
+            if (j < ar) v[j] = *reinterpret_cast<const uint4 *>(hs + (int64_t)kid[j] * Hp + kh);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) add_piece<T>(acc, v[j]);   // ascending child id; zeros add nothing
+        for (int c = 4; c < ar; ++c) {
+            const int k = child_idx[r0.z + c];
+            add_piece<T>(acc, *reinterpret_cast<const uint4 *>(hs + (int64_t)k * Hp + kh));
         }
         if constexpr (sizeof(T) == 4) {
             o.x = __float_as_uint(acc[0]); o.y = __float_as_uint(acc[1]);
@@ -204,12 +243,12 @@ struct LevelArgs {
     const float *bp;      // [NP] packed bias
     // schedule
     const int32_t *level_nodes;  // perm + level start: row -> node id
-    const int4 *row_rec;         // two int4 per level row, written by stack_kernel (internal levels)
+    const int4 *row_rec;         // two int4 per level row (this level's slice of the records)
     const int32_t *child_idx;
     // per-child forget projections U_f h_k, rows by node id, stride Hq, element type T
     // (bf16 in the bf16 path: it halves the largest stream of the forward)
     void *P;
-    float *cs;            // [N, Hq] c with rows padded to 4 floats, or == c_out when H % 4 == 0
+    float *cs;            // [N, Hq] c with padded rows, or == c_out when H % 8 == 0
     // outputs
     float *c_out;         // [N, H]
     void *h_out;          // [N, H]
@@ -426,6 +465,7 @@ __global__ void __launch_bounds__(kGemmThreads, 1)
 level_kernel(const LevelArgs a) {
     __shared__ __attribute__((aligned(16))) char lds[2 * (kBM + kBN) * kLdsStride];
     static_assert(3 * kEpiRows * kEpiStride * 4 <= 2 * (kBM + kBN) * kLdsStride, "epilogue tiles must fit the staging buffers");
+    static_assert(kEpiRows * kProjStride * 4 <= 2 * (kBM + kBN) * kLdsStride, "projection tile must fit the staging buffers");
     __shared__ int row_node[kBM];
     __shared__ int row_ar[kBM];     // number of children
     __shared__ int row_cb[kBM];     // start of the child list in child_idx
@@ -490,18 +530,50 @@ level_kernel(const LevelArgs a) {
     // ---- epilogue: accumulator element v of tile (i, g) is row
     //      wm*64 + i*32 + (v/4)*8 + hf*4 + v%4, column l32 of gate / unit tile g
     if constexpr (MODE == MODE_PROJ) {
+        // P rows leave through LDS too (two passes of 128 rows, fp32 in LDS), so that a
+        // thread stores eight consecutive units of one row: 32 lanes cover 256 units.
+        float *sp = reinterpret_cast<float *>(lds);
+        T *P = static_cast<T *>(a.P);
+        const int u8 = (t & 31) * 8;
+        const int unit0 = col_tile * 256 + u8;
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int unit = (col_tile * 8 + wn * 4 + g) * kUnit + l32;
-            if (unit >= a.H) continue;
+        for (int p = 0; p < 2; ++p) {
+            __syncthreads();
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int g = 0; g < 4; ++g)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int r = wm * 64 + i * 32 + (v >> 2) * 8 + hf * 4 + (v & 3);
-                    const int node = row_node[r];
-                    if (node >= 0) static_cast<T *>(a.P)[(int64_t)node * a.Hq + unit] = from_f32<T>(acc[i][g][v]);
+                    const int rl = wm * 32 + (v >> 2) * 8 + hf * 4 + (v & 3);
+                    sp[rl * kProjStride + wn * 128 + g * 32 + l32] = acc[p][g][v];
                 }
+            __syncthreads();
+#pragma unroll
+            for (int sweep = 0; sweep < 8; ++sweep) {
+                const int rl = (t >> 5) + 16 * sweep;
+                const int node = row_node[(rl >> 5) * 64 + p * 32 + (rl & 31)];
+                if (node < 0 || unit0 >= a.H) continue;
+                const float4 lo = *reinterpret_cast<const float4 *>(sp + rl * kProjStride + u8);
+                const float4 hi = *reinterpret_cast<const float4 *>(sp + rl * kProjStride + u8 + 4);
+                const float f[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                T *dst = P + (int64_t)node * a.Hq + unit0;
+                if (unit0 + 8 <= a.H) {
+                    if constexpr (sizeof(T) == 4) {
+                        *reinterpret_cast<float4 *>(dst) = lo;
+                        *reinterpret_cast<float4 *>(dst + 4) = hi;
+                    } else {
+                        uint4 o;
+                        o.x = (uint32_t)f32_to_bf16(f[0]) | ((uint32_t)f32_to_bf16(f[1]) << 16);
+                        o.y = (uint32_t)f32_to_bf16(f[2]) | ((uint32_t)f32_to_bf16(f[3]) << 16);
+                        o.z = (uint32_t)f32_to_bf16(f[4]) | ((uint32_t)f32_to_bf16(f[5]) << 16);
+                        o.w = (uint32_t)f32_to_bf16(f[6]) | ((uint32_t)f32_to_bf16(f[7]) << 16);
+                        *reinterpret_cast<uint4 *>(dst) = o;
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if (unit0 + j < a.H) dst[j] = from_f32<T>(f[j]);
+                }
+            }
         }
     } else {
         // The cell update runs row-major.  In two passes of 128 rows the gate values
@@ -627,6 +699,7 @@ level_kernel(const LevelArgs a) {
                 if (vec_ok) {
                     if (unit0 < a.H) {
                         *reinterpret_cast<float4 *>(a.c_out + nd * a.H + unit0) = cc[q];
+                        if (separate_cs) *reinterpret_cast<float4 *>(a.cs + nd * a.Hq + unit0) = cc[q];
                         if constexpr (sizeof(T) == 4) {
                             const float4 h4 = make_float4(hv[0], hv[1], hv[2], hv[3]);
                             *reinterpret_cast<float4 *>(h_out + nd * a.H + unit0) = h4;
@@ -692,7 +765,7 @@ struct ForwardWs {
     void *Bp;
     float *bp;
     void *stack;  // the current level's stacked input, (N + 256) rows of Dp + Hp
-    int4 *row_rec; // the current level's row records, two int4 per row
+    int4 *row_rec; // row records of all level positions, two int4 each
     void *hs;     // nullptr when h_out can serve (H == Hp)
     void *P;
     float *cs;    // nullptr when c_out can serve (H == Hq)
@@ -701,7 +774,7 @@ struct ForwardWs {
 
 struct Dims {
     int D, H, Dp, Hp, Hu, NP;
-    int Hq;       // H rounded up to 4: row stride of the fp32 side buffers (P, padded c)
+    int Hq;       // H rounded up to 8: row stride of the side buffers (P, padded c)
     int NPU;      // rows of the packed U: padded so the projection's 8-unit-tile blocks stay inside
     size_t esz;
 };
@@ -715,7 +788,7 @@ Dims make_dims(int D, int H, jitdb_dtype dtype) {
     d.Hp = (int)round_up(H, kpad);
     d.Hu = (int)round_up(H, 2 * kUnit);
     d.NP = 4 * d.Hu;
-    d.Hq = (int)round_up(H, 4);
+    d.Hq = (int)round_up(H, 8);
     d.NPU = (int)round_up(d.Hu / kUnit, 8) * kGateTile;
     d.esz = dtype == JITDB_F32 ? 4 : 2;
     return d;
@@ -729,7 +802,7 @@ ForwardWs carve_forward_ws(int64_t n, int64_t e, const Dims &d, void *base) {
     w.bp = c.take<float>(d.NP);
     // one level at a time; whole row tiles are read, hence the 256 spare rows
     w.stack = c.take<char>((size_t)(n + kBM) * (d.Dp + d.Hp) * d.esz);
-    w.row_rec = c.take<int4>((size_t)2 * (n + kBM));
+    w.row_rec = c.take<int4>((size_t)2 * (n + kBM));   // every level position
     w.hs = (d.H == d.Hp) ? nullptr : c.take<char>((size_t)n * d.Hp * d.esz);
     w.P = c.take<char>((size_t)n * d.Hq * d.esz);
     w.cs = (d.H == d.Hq) ? nullptr : c.take<float>((size_t)n * d.Hq);
@@ -739,7 +812,7 @@ ForwardWs carve_forward_ws(int64_t n, int64_t e, const Dims &d, void *base) {
 
 bool dims_ok(int64_t n, int64_t e, int32_t D, int32_t H, int dtype) {
     if (n < 0 || n > JITDB_MAX_NODES || e < 0 || e > n) return false;
-    if (D < 1 || D > (1 << 16) || (D % 4) != 0) return false;
+    if (D < 1 || D > (1 << 16)) return false;
     if (H < 1 || H > (1 << 14)) return false;
     if (dtype != JITDB_F32 && dtype != JITDB_BF16) return false;
     return true;
@@ -762,6 +835,13 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
         JITDB_LAUNCH_CHECK();
     }
 
+    {
+        ScopedLaunchTimer tm(JITDB_K_PACK, st);
+        row_record_kernel<<<(unsigned)ceil_div(s->n_nodes, kThreads), kThreads, 0, st>>>(
+            s->perm, s->child_ptr, s->child_idx, w.row_rec, (int)s->n_nodes);
+        JITDB_LAUNCH_CHECK();
+    }
+
     LevelArgs a;
 #ifdef JITDB_EXPERIMENT
     a.experiment = getenv("JITDB_EXPERIMENT") ? atoi(getenv("JITDB_EXPERIMENT")) : 0;
@@ -770,7 +850,7 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
     a.hs = w.hs ? w.hs : h_out;
     a.Bp = w.Bp; a.bp = w.bp;
     a.child_idx = s->child_idx;
-    a.row_rec = w.row_rec;
+
     a.P = w.P; a.c_out = c_out; a.h_out = h_out;
     a.cs = w.cs ? w.cs : c_out;
     a.Hq = d.Hq;
@@ -781,6 +861,7 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
         const int n_rows = lp[l + 1] - lp[l];
         if (n_rows <= 0) return JITDB_E_SCHEDULE;
         a.level_nodes = s->perm + lp[l];
+        a.row_rec = w.row_rec + 2 * (int64_t)lp[l];
         a.n_rows = n_rows;
         const int row_tiles = (int)ceil_div(n_rows, kBM);
         {   // stack: gather the level's x rows and child sums into one dense matrix
@@ -790,12 +871,12 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
             ScopedLaunchTimer tm(JITDB_K_STACK, st);
             if (l == 0)
                 stack_kernel<T, false><<<grid, kThreads, 0, st>>>(
-                    static_cast<const T *>(x), d.D, d.Dp, static_cast<const T *>(a.hs), d.Hp, a.level_nodes,
-                    s->child_ptr, s->child_idx, static_cast<T *>(w.stack), w.row_rec, n_rows);
+                    static_cast<const T *>(x), d.D, d.Dp, static_cast<const T *>(a.hs), d.Hp, a.row_rec,
+                    s->child_idx, static_cast<T *>(w.stack), n_rows);
             else
                 stack_kernel<T, true><<<grid, kThreads, 0, st>>>(
-                    static_cast<const T *>(x), d.D, d.Dp, static_cast<const T *>(a.hs), d.Hp, a.level_nodes,
-                    s->child_ptr, s->child_idx, static_cast<T *>(w.stack), w.row_rec, n_rows);
+                    static_cast<const T *>(x), d.D, d.Dp, static_cast<const T *>(a.hs), d.Hp, a.row_rec,
+                    s->child_idx, static_cast<T *>(w.stack), n_rows);
             JITDB_LAUNCH_CHECK();
         }
         a.n_col_tiles = d.NP / kBN;
@@ -888,9 +969,8 @@ extern "C" int jitdb_treelstm_forward(const void *x, const void *W, const void *
     if (!x || !W || !U || !b || !h_out || !c_out || !workspace) return JITDB_E_NULL;
     if (!s->perm || !s->child_ptr || !s->child_idx || !s->host_level_ptr) return JITDB_E_NULL;
     if ((reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return JITDB_E_BADARG;
-    const size_t esz = dtype == JITDB_F32 ? 4 : 2;
-    // row pieces are fetched 4 elements at a time (x) and 16 bytes at a time (h when H is unpadded)
-    if ((reinterpret_cast<uintptr_t>(x) % (4 * esz)) != 0) return JITDB_E_BADARG;
+    // rows are fetched in 16-byte pieces where their stride allows
+    if ((reinterpret_cast<uintptr_t>(x) & 15) != 0) return JITDB_E_BADARG;
     if ((reinterpret_cast<uintptr_t>(h_out) & 15) != 0) return JITDB_E_BADARG;
     if ((reinterpret_cast<uintptr_t>(c_out) & 15) != 0) return JITDB_E_BADARG;
     const int L = s->n_levels;

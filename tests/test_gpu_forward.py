@@ -106,7 +106,8 @@ def test_forest_equals_trees_run_alone(c_oracle):
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("name,H,D", [("H32", 32, 4), ("H33", 33, 8), ("H64", 64, 300),
-                                      ("H100", 100, 52), ("H257", 257, 300)])
+                                      ("H100", 100, 52), ("H257", 257, 300),
+                                      ("H36-D7", 36, 7), ("H150-D302", 150, 302)])
 def test_odd_dimensions(c_oracle, name, H, D, dtype):
     """Hidden sizes on and off every padding boundary; forests with leaves only,
     one chain, one wide star and a ragged last row tile."""
@@ -165,12 +166,32 @@ def test_bad_arguments_are_rejected():
     from gpu_util import dev_parent
     s = J.jitdb_schedule(dev_parent(make_forest(1)))
     n = s.n_nodes
-    x = torch.zeros((n, 302), device="cuda"); W = torch.zeros((600, 302), device="cuda")
-    U = torch.zeros((600, 150), device="cuda"); b = torch.zeros(600, device="cuda")
-    with pytest.raises(J.JitdbError) as e:          # D not a multiple of 4
-        J.jitdb_treelstm_forward(x, W, U, b, s)
-    assert e.value.code == -2
     x = torch.zeros((n, 300), device="cuda"); W = torch.zeros((600, 300), device="cuda")
+    U = torch.zeros((600, 150), device="cuda"); b = torch.zeros(600, device="cuda")
+    h_misaligned = torch.zeros(n * 150 + 1, device="cuda")[1:].view(n, 150)   # 4 bytes off
+    with pytest.raises(J.JitdbError) as e:
+        J.jitdb_treelstm_forward(x, W, U, b, s, out=(h_misaligned, torch.zeros((n, 150), device="cuda")))
+    assert e.value.code == -2
     with pytest.raises(J.JitdbError) as e:          # workspace too small
         J.jitdb_treelstm_forward(x, W, U, b, s, workspace=torch.empty(512, dtype=torch.uint8, device="cuda"))
     assert e.value.code == -5
+
+
+def test_schedule_is_reusable_and_streams_are_honoured(c_oracle):
+    """One schedule, several forwards with different values, on a non-default stream."""
+    import torch
+    import paper_1904_07421_amd as J
+    from gpu_util import dev_parent
+    cfgo, p, x, W, U, b = make_workload(2, bias="random")
+    s = J.jitdb_schedule(dev_parent(p))
+    st = torch.cuda.Stream()
+    Wt, Ut, bt = (torch.from_numpy(a).cuda() for a in (W, U, b))
+    for scale in (1.0, -0.5):
+        xs = (x * scale).astype(np.float32)
+        xt = torch.from_numpy(xs).cuda()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(st):
+            h, c = J.jitdb_treelstm_forward(xt, Wt, Ut, bt, s, stream=st)
+        st.synchronize()
+        ho, co, _ = c_oracle(p, xs, W, U, b)
+        assert np.abs(h.cpu().numpy() - ho).max() <= 1e-4 and np.abs(c.cpu().numpy() - co).max() <= 1e-4
