@@ -49,8 +49,8 @@ constexpr int kBN = 256;        // packed columns per block = 2 unit tiles x 4 g
 constexpr int kUnit = 32;       // hidden units per MFMA column tile
 constexpr int kGateTile = 128;  // packed rows per unit tile (4 gates x 32 units)
 
-constexpr int kEpiRows = 128;   // rows per epilogue pass
-constexpr int kEpiStride = 72;  // floats per epilogue LDS row: 64 units + 8; rows 4 apart fall 32 banks apart
+constexpr int kEpiRows = 128;   // rows per pass of the projection's store epilogue
+constexpr int kEpiStride = 40;  // floats per row of a wave's epilogue region: 32 units + 8; rows 4 apart fall 32 banks apart
 constexpr int kProjStride = 264; // same for the projection's 256-unit rows
 constexpr int kLdsStride = 144; // stage row (128 bytes) + 16: 128-bit LDS reads of 32 rows hit distinct banks
 
@@ -464,7 +464,7 @@ template <typename T, int MODE>
 __global__ void __launch_bounds__(kGemmThreads, 1)
 level_kernel(const LevelArgs a) {
     __shared__ __attribute__((aligned(16))) char lds[2 * (kBM + kBN) * kLdsStride];
-    static_assert(3 * kEpiRows * kEpiStride * 4 <= 2 * (kBM + kBN) * kLdsStride, "epilogue tiles must fit the staging buffers");
+    static_assert(8 * 3 * 32 * kEpiStride * 4 <= 2 * (kBM + kBN) * kLdsStride, "epilogue regions must fit the staging buffers");
     static_assert(kEpiRows * kProjStride * 4 <= 2 * (kBM + kBN) * kLdsStride, "projection tile must fit the staging buffers");
     __shared__ int row_node[kBM];
     __shared__ int row_ar[kBM];     // number of children
@@ -576,52 +576,55 @@ level_kernel(const LevelArgs a) {
             }
         }
     } else {
-        // The cell update runs row-major.  In two passes of 128 rows the gate values
-        // go through LDS (the staging buffers are free now): each wave writes
-        // i*u, o and the x part of the forget gate for its 32 units, then every
-        // thread takes four rows x four consecutive units, so that the rows of the
-        // children (P_k and c_k) are read in 16-byte pieces, 256 bytes per row and
-        // array, with four rows in flight per thread.
+        // The cell update runs row-major, wave by wave.  Each wave owns 64 rows x 32
+        // units of the tile and a private LDS region (the staging buffers are free
+        // now).  In two passes of 32 rows it writes i*u, o and the x part of the forget
+        // gate there and reads them back with eight lanes per row, four consecutive
+        // units per lane: the rows of the children (P_k and c_k) are then fetched in
+        // 8- and 16-byte pieces, 64 / 128 contiguous bytes per row, with four rows in
+        // flight per lane.  Apart from the one barrier that retires the main loop the
+        // waves do not wait for each other, so the arithmetic of one overlaps the
+        // memory latency of the others.
         const int pcol = col_tile * kBN + wn * kGateTile + l32;   // packed row of gate i for this unit
         const float bi = a.bp[pcol], bo = a.bp[pcol + kUnit], bu = a.bp[pcol + 2 * kUnit];
         float bf = 0.0f;
         if constexpr (MODE == MODE_INTERNAL) bf = a.bp[pcol + 3 * kUnit];
-        float *s_iu = reinterpret_cast<float *>(lds);
-        float *s_o = s_iu + kEpiRows * kEpiStride;
-        float *s_fx = s_o + kEpiRows * kEpiStride;
+        float *s_iu = reinterpret_cast<float *>(lds) + wave * (3 * 32 * kEpiStride);
+        float *s_o = s_iu + 32 * kEpiStride;
+        float *s_fx = s_o + 32 * kEpiStride;
         T *h_out = static_cast<T *>(a.h_out);
         T *hs_out = static_cast<T *>(a.hs_out);
         const bool separate_hs = (a.hs_out != a.h_out);
         const bool separate_cs = (a.cs != a.c_out);
         const bool vec_ok = (a.H & 3) == 0;
-        const int unit0 = col_tile * 64 + (t & 15) * 4;
+        const int unit0 = (col_tile * 2 + wn) * kUnit + (lane & 7) * 4;
         // unit groups past the padded width read the first group instead (and store nothing)
         const int unit_ld = unit0 < a.Hq ? unit0 : 0;
+        __syncthreads();   // every wave is done reading the staging buffers
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
-            __syncthreads();   // main loop (p = 0) or the previous pass (p = 1) is done with LDS
-            {
-                const int col = wn * 32 + l32;
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int rl = wm * 32 + (v >> 2) * 8 + hf * 4 + (v & 3);   // 0..127
-                    const float gi = sigmoid_t<T>(acc[p][0][v] + bi);
-                    const float go = sigmoid_t<T>(acc[p][1][v] + bo);
-                    const float gu = tanh_t<T>(acc[p][2][v] + bu);
-                    s_iu[rl * kEpiStride + col] = gi * gu;
-                    s_o[rl * kEpiStride + col] = go;
-                    if constexpr (MODE == MODE_INTERNAL) s_fx[rl * kEpiStride + col] = acc[p][3][v] + bf;
-                }
+            for (int v = 0; v < 16; ++v) {
+                const int rl = (v >> 2) * 8 + hf * 4 + (v & 3);   // 0..31
+                const float gi = sigmoid_t<T>(acc[p][0][v] + bi);
+                const float go = sigmoid_t<T>(acc[p][1][v] + bo);
+                const float gu = tanh_t<T>(acc[p][2][v] + bu);
+                s_iu[rl * kEpiStride + l32] = gi * gu;
+                s_o[rl * kEpiStride + l32] = go;
+                if constexpr (MODE == MODE_INTERNAL) s_fx[rl * kEpiStride + l32] = acc[p][3][v] + bf;
             }
-            __syncthreads();
+            // the wave's own LDS writes are ordered before its reads; nothing else touches the region
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             float4 cc[4], go4[4], fx4[4];
             int node[4], tr[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int rl = (t >> 4) + 32 * q;
-                tr[q] = (rl >> 5) * 64 + p * 32 + (rl & 31);
+                const int rl = (lane >> 3) + 8 * q;
+                tr[q] = wm * 64 + p * 32 + rl;
                 node[q] = row_node[tr[q]];
-                const int so = rl * kEpiStride + (t & 15) * 4;
+                const int so = rl * kEpiStride + (lane & 7) * 4;
                 cc[q] = *reinterpret_cast<const float4 *>(s_iu + so);
                 go4[q] = *reinterpret_cast<const float4 *>(s_o + so);
                 if constexpr (MODE == MODE_INTERNAL) fx4[q] = *reinterpret_cast<const float4 *>(s_fx + so);
