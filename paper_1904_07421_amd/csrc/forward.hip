@@ -27,9 +27,6 @@
 #include "common.h"
 
 #include <type_traits>
-#ifdef JITDB_EXPERIMENT
-#include <stdlib.h>
-#endif
 
 namespace jitdb {
 namespace {
@@ -257,9 +254,6 @@ struct LevelArgs {
     int n_rows;
     int n_col_tiles;      // blocks along the packed-column axis
     int n_blocks;
-#ifdef JITDB_EXPERIMENT
-    int experiment;       // dev builds: bit0 skip main loop, bit1 skip epilogue
-#endif
 };
 
 // Spread consecutive block ids (which the hardware deals round-robin to the 8
@@ -317,9 +311,10 @@ struct StageRegs {
 // A rows t/8 + 64 i.  Of B it handles hidden unit (t/8)%32 of unit tile t/256,
 // row group i being the gate (or, for the projection, unit tile 4*(t/256) + i),
 // so whole gates can be skipped at compile time.
-template <typename T, int MODE>
+template <typename T, int MODE, typename Hook>
 __device__ __forceinline__ void block_gemm(const LevelArgs &a, char *lds, const int *row_node,
-                                           int tile_row0, int col_tile, floatx16 (&acc)[2][4]) {
+                                           int tile_row0, int col_tile, floatx16 (&acc)[2][4],
+                                           Hook &&after_first_requests) {
     constexpr int BK = Traits<T>::BK;
     constexpr int ESZ = (int)sizeof(T);
     constexpr int NG_X = (MODE == MODE_LEAF) ? 3 : 4;      // gate tiles multiplied in the x part
@@ -379,7 +374,7 @@ __device__ __forceinline__ void block_gemm(const LevelArgs &a, char *lds, const 
 
     StageRegs r;
     // global -> registers, stage g
-    auto fetch = [&](int g) __attribute__((always_inline)) {
+    auto fetch = [&](int g, StageRegs &r) __attribute__((always_inline)) {
         const int64_t kb = (int64_t)g * (BK * ESZ);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -390,7 +385,7 @@ __device__ __forceinline__ void block_gemm(const LevelArgs &a, char *lds, const 
         for (int i = 0; i < NG_F; ++i) r.b[i] = ld16(bp + i * b_step + kb);
     };
     // registers -> LDS
-    auto stash = [&](char *buf) __attribute__((always_inline)) {
+    auto stash = [&](char *buf, const StageRegs &r) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(buf + a_wr + i * 64 * kLdsStride) = r.a[i];
 #pragma unroll
@@ -418,20 +413,27 @@ __device__ __forceinline__ void block_gemm(const LevelArgs &a, char *lds, const 
         char *nxt = lds + ((g & 1) ^ 1) * kBufBytes;
         const int gf = g + 2 < last ? g + 2 : last;
         const int64_t kb = (int64_t)gf * (BK * ESZ);
-#pragma unroll
-        for (int h = 0; h < 4; ++h) {
-            u32x4 av[2], bv[NG];
+        // Fragments are double buffered: the LDS reads of K group h+1 are issued ahead of
+        // the MFMAs of K group h, so only the first group of a stage waits for LDS.
+        u32x4 av[2][2], bv[2][NG];
+        auto read_frags = [&](int h, int set) __attribute__((always_inline)) {
 #pragma unroll
             for (int i = 0; i < 2; ++i)
-                av[i] = *reinterpret_cast<const u32x4 *>(sa + i * 32 * kLdsStride + h * 32);
+                av[set][i] = *reinterpret_cast<const u32x4 *>(sa + i * 32 * kLdsStride + h * 32);
 #pragma unroll
             for (int q = 0; q < NG; ++q)
-                bv[q] = *reinterpret_cast<const u32x4 *>(sb + q * 32 * kLdsStride + h * 32);
+                bv[set][q] = *reinterpret_cast<const u32x4 *>(sb + q * 32 * kLdsStride + h * 32);
+        };
+        read_frags(0, 0);
+#pragma unroll
+        for (int h = 0; h < 4; ++h) {
+            const int cur = h & 1;
+            if (h < 3) read_frags(h + 1, cur ^ 1);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
 #pragma unroll
                 for (int m = j * M / 4; m < (j + 1) * M / 4; ++m)
-                    mfma_step<T>(av[m / NG], bv[m % NG], acc[m / NG][m % NG]);
+                    mfma_step<T>(av[cur][m / NG], bv[cur][m % NG], acc[m / NG][m % NG]);
                 __builtin_amdgcn_sched_barrier(0);
                 const int o = (h & 1) * 4 + j;      // which of the eight moves of this half
                 if (h < 2) {                         // registers -> LDS
@@ -452,9 +454,16 @@ __device__ __forceinline__ void block_gemm(const LevelArgs &a, char *lds, const 
         }
         __syncthreads();
     };
-    fetch(0);
-    stash(lds);
-    fetch(1 < last ? 1 : last);
+    // Start-up: stages 0 and 1 are requested together (the accumulators are not live yet,
+    // so a second register set is free), then the caller publishes its per-row data, whose
+    // loads it issued before calling: one memory latency instead of three in a row.
+    {
+        StageRegs r_first;
+        fetch(0, r_first);
+        fetch(1 < last ? 1 : last, r);
+        after_first_requests();
+        stash(lds, r_first);
+    }
     __syncthreads();
     for (int g = 0; g < n_x; ++g) iteration(g, ngx);
     for (int g = n_x; g < n_stages; ++g) iteration(g, ngh);
@@ -481,25 +490,29 @@ level_kernel(const LevelArgs a) {
     const int col_tile = logical % a.n_col_tiles;
     const int tile_row0 = row_tile * kBM;
 
-    if (t < kBM) {
-        const int grow = tile_row0 + t;
-        int node = -1;
+    // Per-row data of the tile: requested now, written to LDS by publish_rows().
+    int node_reg = -1;
+    int4 rec0 = make_int4(-1, 0, 0, 0), rec1 = make_int4(-1, -1, -1, -1);
+    if (t < kBM && tile_row0 + t < a.n_rows) {
         if constexpr (MODE == MODE_INTERNAL) {
-            int4 r0 = make_int4(-1, 0, 0, 0), r1 = make_int4(-1, -1, -1, -1);
-            if (grow < a.n_rows) {
-                r0 = a.row_rec[2 * (int64_t)grow];
-                r1 = a.row_rec[2 * (int64_t)grow + 1];
-            }
-            node = r0.x;
-            row_ar[t] = r0.y;
-            row_cb[t] = r0.z;
-            row_kid[t] = r1;
+            rec0 = a.row_rec[2 * (int64_t)(tile_row0 + t)];
+            rec1 = a.row_rec[2 * (int64_t)(tile_row0 + t) + 1];
         } else {
-            if (grow < a.n_rows) node = a.level_nodes[grow];
+            node_reg = a.level_nodes[tile_row0 + t];
         }
-        row_node[t] = node;
     }
-    __syncthreads();
+    auto publish_rows = [&]() __attribute__((always_inline)) {
+        if (t < kBM) {
+            if constexpr (MODE == MODE_INTERNAL) {
+                row_node[t] = rec0.x;
+                row_ar[t] = rec0.y;
+                row_cb[t] = rec0.z;
+                row_kid[t] = rec1;
+            } else {
+                row_node[t] = node_reg;
+            }
+        }
+    };
 
     floatx16 acc[2][4];
 #pragma unroll
@@ -509,23 +522,15 @@ level_kernel(const LevelArgs a) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][g][v] = 0.0f;
 
-#ifdef JITDB_EXPERIMENT
-    if (!(a.experiment & 1))
-#endif
-    block_gemm<T, MODE>(a, lds, row_node, tile_row0, col_tile, acc);
-#ifdef JITDB_EXPERIMENT
-    if (a.experiment & 2) {
-        float sum = 0.0f;
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int g = 0; g < 4; ++g)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) sum += acc[i][g][v];
-        if (sum == 123.456f) a.c_out[0] = sum;
-        return;
+    if constexpr (MODE == MODE_PROJ) {
+        // the projection gathers its A rows by node id, so the ids must be in LDS first
+        publish_rows();
+        __syncthreads();
     }
-#endif
+    if constexpr (MODE == MODE_PROJ)
+        block_gemm<T, MODE>(a, lds, row_node, tile_row0, col_tile, acc, []() {});
+    else
+        block_gemm<T, MODE>(a, lds, row_node, tile_row0, col_tile, acc, publish_rows);
 
     // ---- epilogue: accumulator element v of tile (i, g) is row
     //      wm*64 + i*32 + (v/4)*8 + hf*4 + v%4, column l32 of gate / unit tile g
@@ -846,9 +851,6 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
     }
 
     LevelArgs a;
-#ifdef JITDB_EXPERIMENT
-    a.experiment = getenv("JITDB_EXPERIMENT") ? atoi(getenv("JITDB_EXPERIMENT")) : 0;
-#endif
     a.stack = w.stack;
     a.hs = w.hs ? w.hs : h_out;
     a.Bp = w.Bp; a.bp = w.bp;
