@@ -35,23 +35,27 @@ def _torch_gate_rows(M, H):
     return torch.from_numpy(np.concatenate([i, f, u, o], axis=0))
 
 
-def test_leaf_closed_form(c_oracle):
+def pin_leaf(fwd, name="oracle"):
     rng = np.random.default_rng(0)
     D, H = 7, 5
     x, W, U, b = _rand(rng, 3, D, H)
     p = np.array([-1, -1, -1], dtype=np.int32)
     sg = lambda z: 1.0 / (1.0 + np.exp(-z))
+    h, c = fwd(p, x, W, U, b)
+    for j in range(3):
+        pre = W @ x[j] + b
+        cc = sg(pre[:H]) * np.tanh(pre[2 * H:3 * H])
+        hh = sg(pre[H:2 * H]) * np.tanh(cc)
+        assert np.allclose(c[j], cc, atol=1e-14), name
+        assert np.allclose(h[j], hh, atol=1e-14), name
+
+
+def test_leaf_closed_form(c_oracle):
     for name, fwd in _both(c_oracle):
-        h, c = fwd(p, x, W, U, b)
-        for j in range(3):
-            pre = W @ x[j] + b
-            cc = sg(pre[:H]) * np.tanh(pre[2 * H:3 * H])
-            hh = sg(pre[H:2 * H]) * np.tanh(cc)
-            assert np.allclose(c[j], cc, atol=1e-14), name
-            assert np.allclose(h[j], hh, atol=1e-14), name
+        pin_leaf(fwd, name)
 
 
-def test_chain_equals_library_lstm(c_oracle):
+def pin_chain(fwd, name="oracle"):
     """A chain is an LSTM over the sequence from the deepest node up to the root."""
     rng = np.random.default_rng(1)
     n, D, H = 9, 6, 4
@@ -66,13 +70,17 @@ def test_chain_equals_library_lstm(c_oracle):
         seq = torch.from_numpy(x[::-1].copy()).unsqueeze(1)
         out, (hn, cn) = lstm(seq)
     ref_h = out[:, 0, :].numpy()[::-1]
+    h, c = fwd(p, x, W, U, b)
+    assert np.allclose(h, ref_h, atol=1e-13), name
+    assert np.allclose(c[0], cn[0, 0].numpy(), atol=1e-13), name
+
+
+def test_chain_equals_library_lstm(c_oracle):
     for name, fwd in _both(c_oracle):
-        h, c = fwd(p, x, W, U, b)
-        assert np.allclose(h, ref_h, atol=1e-13), name
-        assert np.allclose(c[0], cn[0, 0].numpy(), atol=1e-13), name
+        pin_chain(fwd, name)
 
 
-def test_star_with_zero_Uf_equals_library_cell_on_summed_children(c_oracle):
+def pin_star_cell(fwd, name="oracle"):
     """With U_f = 0 the forget gate is the same for every child, so the parent
     is one LSTM-cell step from (sum of child h, sum of child c)."""
     rng = np.random.default_rng(2)
@@ -86,17 +94,21 @@ def test_star_with_zero_Uf_equals_library_cell_on_summed_children(c_oracle):
         cell.weight_hh.copy_(_torch_gate_rows(U, H))
         cell.bias_ih.copy_(_torch_gate_rows(b.reshape(-1, 1), H).reshape(-1))
         cell.bias_hh.zero_()
+    h, c = fwd(p, x, W, U, b)
+    with torch.no_grad():
+        h0 = torch.from_numpy(h[1:].sum(0, keepdims=True))
+        c0 = torch.from_numpy(c[1:].sum(0, keepdims=True))
+        h1, c1 = cell(torch.from_numpy(x[:1]), (h0, c0))
+    assert np.allclose(h[0], h1[0].numpy(), atol=1e-13), name
+    assert np.allclose(c[0], c1[0].numpy(), atol=1e-13), name
+
+
+def test_star_with_zero_Uf_equals_library_cell_on_summed_children(c_oracle):
     for name, fwd in _both(c_oracle):
-        h, c = fwd(p, x, W, U, b)
-        with torch.no_grad():
-            h0 = torch.from_numpy(h[1:].sum(0, keepdims=True))
-            c0 = torch.from_numpy(c[1:].sum(0, keepdims=True))
-            h1, c1 = cell(torch.from_numpy(x[:1]), (h0, c0))
-        assert np.allclose(h[0], h1[0].numpy(), atol=1e-13), name
-        assert np.allclose(c[0], c1[0].numpy(), atol=1e-13), name
+        pin_star_cell(fwd, name)
 
 
-def test_forget_gate_reads_each_childs_own_h(c_oracle):
+def pin_forget_own_h(fwd, name="oracle"):
     """U_f = 1000 I, W_f = 0, b_f = 0, U_iou = 0: every forget gate saturates to
     exactly 0 or 1 by the sign of that child's own h, so the parent's c is its
     leaf-like term plus the c of the children whose h is positive.  Using the
@@ -109,22 +121,25 @@ def test_forget_gate_reads_each_childs_own_h(c_oracle):
     W[3 * H:] = 0.0
     b[3 * H:] = 0.0
     p = star_forest(m + 1)
+    h, c = fwd(p, x, W, U, b)
+    hl, cl = fwd(np.array([-1], dtype=np.int32), x[:1], W, U, b)   # root as if it were a leaf
+    hk, ck = h[1:], c[1:]
+    sat = np.abs(hk) > 0.04                       # |1000 h| > 40: sigmoid is exactly 0 or 1
+    ok = sat.all(axis=0)                          # hidden units where every child saturates
+    mixed = ok & (hk > 0).any(0) & (hk < 0).any(0)
+    assert ok.sum() >= 4 and mixed.any()
+    expect = cl[0] + np.where(hk > 0, ck, 0.0).sum(0)
+    assert np.allclose(c[0][ok], expect[ok], atol=1e-12), name
+    wrong = cl[0] + np.where(hk.sum(0) > 0, 1.0, 0.0) * ck.sum(0)
+    assert not np.allclose(c[0][mixed], wrong[mixed], atol=1e-3), name
+
+
+def test_forget_gate_reads_each_childs_own_h(c_oracle):
     for name, fwd in _both(c_oracle):
-        h, c = fwd(p, x, W, U, b)
-        hl, cl = fwd(np.array([-1], dtype=np.int32), x[:1], W, U, b)   # root as if it were a leaf
-        hk, ck = h[1:], c[1:]
-        sat = np.abs(hk) > 0.04                       # |1000 h| > 40: sigmoid is exactly 0 or 1
-        ok = sat.all(axis=0)                          # hidden units where every child saturates
-        mixed = ok & (hk > 0).any(0) & (hk < 0).any(0)
-        assert ok.sum() >= 4 and mixed.any()
-        expect = cl[0] + np.where(hk > 0, ck, 0.0).sum(0)
-        assert np.allclose(c[0][ok], expect[ok], atol=1e-12), name
-        wrong = cl[0] + np.where(hk.sum(0) > 0, 1.0, 0.0) * ck.sum(0)
-        assert not np.allclose(c[0][mixed], wrong[mixed], atol=1e-3), name
+        pin_forget_own_h(fwd, name)
 
 
-@pytest.mark.parametrize("shape", ["cfg1", "kary", "star"])
-def test_zero_weights_closed_form_counts_subtrees(c_oracle, shape):
+def pin_zero_weights(fwd, name="oracle", shape="cfg1"):
     """W = U = 0: gates are constants.  With b_f = 40 the forget gate is exactly
     1.0 in fp64, so c_j = sigmoid(b_i) tanh(b_u) * (size of j's subtree); with a
     general b_f, c_j = s * sum_d n_d(j) sigmoid(b_f)^d over descendant depths."""
@@ -139,25 +154,30 @@ def test_zero_weights_closed_form_counts_subtrees(c_oracle, shape):
     for v in S.schedule_fast(p)["perm"]:          # leaves first
         if p[v] >= 0:
             size[p[v]] += size[v]
-    for name, fwd in _both(c_oracle):
-        b = np.concatenate([np.full(H, bi), np.full(H, bo), np.full(H, bu), np.full(H, 40.0)])
-        h, c = fwd(p, x, W, U, b)
-        assert np.allclose(c[:, 0], s * size, rtol=1e-13), name
-        assert np.allclose(h[:, 1], sg(bo) * np.tanh(s * size), rtol=1e-13), name
-        # general forget bias: polynomial in sigmoid(b_f) over descendant depths
-        bf = 0.4
-        b2 = np.concatenate([np.full(H, bi), np.full(H, bo), np.full(H, bu), np.full(H, bf)])
-        h2, c2 = fwd(p, x, W, U, b2)
-        poly = np.zeros(n)
-        for v in range(n):
-            w, d = v, 0
-            while w != -1:
-                poly[w] += sg(bf) ** d
-                w, d = int(p[w]), d + 1
-        assert np.allclose(c2[:, 0], s * poly, rtol=1e-12), name
+    b = np.concatenate([np.full(H, bi), np.full(H, bo), np.full(H, bu), np.full(H, 40.0)])
+    h, c = fwd(p, x, W, U, b)
+    assert np.allclose(c[:, 0], s * size, rtol=1e-13), name
+    assert np.allclose(h[:, 1], sg(bo) * np.tanh(s * size), rtol=1e-13), name
+    # general forget bias: polynomial in sigmoid(b_f) over descendant depths
+    bf = 0.4
+    b2 = np.concatenate([np.full(H, bi), np.full(H, bo), np.full(H, bu), np.full(H, bf)])
+    h2, c2 = fwd(p, x, W, U, b2)
+    poly = np.zeros(n)
+    for v in range(n):
+        w, d = v, 0
+        while w != -1:
+            poly[w] += sg(bf) ** d
+            w, d = int(p[w]), d + 1
+    assert np.allclose(c2[:, 0], s * poly, rtol=1e-12), name
     b0 = np.zeros(4 * H)
-    h0, c0 = T.forward(p, x, W, U, b0)
+    h0, c0 = fwd(p, x, W, U, b0)
     assert not h0.any() and not c0.any()
+
+
+@pytest.mark.parametrize("shape", ["cfg1", "kary", "star"])
+def test_zero_weights_closed_form_counts_subtrees(c_oracle, shape):
+    for name, fwd in _both(c_oracle):
+        pin_zero_weights(fwd, name, shape)
 
 
 def test_relabelling_leaves_states_unchanged(c_oracle):
@@ -211,3 +231,7 @@ def test_c_oracle_rejects_non_forests(c_oracle):
     for bad in ([1, 0, -1], [-1, 5, 0], [0, -1, 1]):
         with pytest.raises(ValueError):
             c_oracle(np.array(bad, dtype=np.int32), x, W, U, b)
+
+
+ALL_PINS = [pin_leaf, pin_chain, pin_star_cell, pin_forget_own_h,
+            lambda fwd, name="oracle": pin_zero_weights(fwd, name, "cfg1")]
