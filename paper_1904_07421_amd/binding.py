@@ -175,14 +175,17 @@ class Schedule:
             n_levels=L, n_edges=E)
 
 
-def jitdb_schedule(parent, stream=None, workspace=None) -> Schedule:
-    """parent: int32 CUDA tensor [N], -1 = root.  Returns the forest's Schedule."""
+def jitdb_schedule(parent, stream=None, workspace=None, out: Optional[Schedule] = None) -> Schedule:
+    """parent: int32 CUDA tensor [N], -1 = root.  Returns the forest's Schedule.
+    `out` reuses the buffers of an earlier Schedule of the same size."""
     import torch
     lib = load_library()
     if parent.dtype != torch.int32 or not parent.is_cuda or not parent.is_contiguous():
         raise TypeError("parent must be a contiguous int32 CUDA tensor")
     n = parent.numel()
-    sched = Schedule(n, parent.device)
+    if out is not None and out.n_nodes != n:
+        raise ValueError("out was made for a forest of another size")
+    sched = out if out is not None else Schedule(n, parent.device)
     need = jitdb_schedule_workspace_bytes(n)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=parent.device)

@@ -195,3 +195,35 @@ def test_schedule_is_reusable_and_streams_are_honoured(c_oracle):
         st.synchronize()
         ho, co, _ = c_oracle(p, xs, W, U, b)
         assert np.abs(h.cpu().numpy() - ho).max() <= 1e-4 and np.abs(c.cpu().numpy() - co).max() <= 1e-4
+
+
+def test_forward_can_be_captured_in_a_graph(c_oracle):
+    """The forward is asynchronous and allocates nothing, so it can be recorded into a HIP
+    graph; every replay (with new x in the same buffer, eager work in between) must match."""
+    import torch
+    import paper_1904_07421_amd as J
+    from gpu_util import dev_parent
+    cfgo, p, x, W, U, b = make_workload(2, bias="random")
+    s = J.jitdb_schedule(dev_parent(p))
+    n, D, H = p.shape[0], cfgo.D, cfgo.H
+    Wt, Ut, bt = (torch.from_numpy(a).cuda() for a in (W, U, b))
+    xt = torch.from_numpy(x).cuda()
+    h = torch.empty((n, H), device="cuda"); c = torch.empty((n, H), device="cuda")
+    ws = torch.empty(J.jitdb_treelstm_workspace_bytes(n, s.n_edges, D, H, J.JITDB_F32),
+                     dtype=torch.uint8, device="cuda")
+    st = torch.cuda.Stream()
+    st.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(st):                      # warm-up on the capture stream
+        J.jitdb_treelstm_forward(xt, Wt, Ut, bt, s, stream=st, workspace=ws, out=(h, c))
+    st.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=st):
+        J.jitdb_treelstm_forward(xt, Wt, Ut, bt, s, stream=st, workspace=ws, out=(h, c))
+    for scale in (1.0, 0.25, -2.0):
+        xs = (x * scale).astype(np.float32)
+        xt.copy_(torch.from_numpy(xs).cuda())        # eager work between replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        ho, co, _ = c_oracle(p, xs, W, U, b)
+        assert np.abs(h.cpu().numpy() - ho).max() <= 1e-4 and np.abs(c.cpu().numpy() - co).max() <= 1e-4
