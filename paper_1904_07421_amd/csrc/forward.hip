@@ -252,7 +252,8 @@ struct LevelArgs {
     void *hs_out;         // [N, Hp] or == h_out when H == Hp
     int D, Dp, H, Hp, Hu, Hq;
     int n_rows;
-    int n_col_tiles;      // blocks along the packed-column axis
+    int n_col_tiles;      // tiles along the column axis
+    int n_tiles;          // thin kernel: number of wave tiles
     int n_blocks;
 };
 
@@ -469,6 +470,166 @@ __device__ __forceinline__ void block_gemm(const LevelArgs &a, char *lds, const 
     for (int g = n_x; g < n_stages; ++g) iteration(g, ngh);
 }
 
+// ---- the cell update of one wave: 32 rows x 32 hidden units ---------------------------
+// acc[g][v] holds the pre-activation (without bias) of gate g for row
+// (v/4)*8 + hf*4 + v%4 and unit l32 of the wave's unit tile.  The wave writes i*u, o and
+// the x part of the forget gate to its private LDS region and reads them back row-major,
+// eight lanes per row and four consecutive units per lane: the rows of the children
+// (P_k and c_k) are then fetched in 8- and 16-byte pieces, 64 / 128 contiguous bytes per
+// row, with four rows in flight per lane.  rn / rar / rcb / rkid describe the 32 rows
+// (node id or -1, arity, CSR start, first four child ids).  No block barrier inside.
+template <typename T, int MODE>
+__device__ __forceinline__ void cell_pass(const LevelArgs &a, const floatx16 (&acc)[4], float *region,
+                                          const int *rn, const int *rar, const int *rcb,
+                                          const int4 *rkid, int unit_tile, int lane) {
+    const int hf = lane >> 5, l32 = lane & 31;
+    const int pcol = unit_tile * kGateTile + l32;   // packed row of gate i for this unit
+    const float bi = a.bp[pcol], bo = a.bp[pcol + kUnit], bu = a.bp[pcol + 2 * kUnit];
+    float bf = 0.0f;
+    if constexpr (MODE == MODE_INTERNAL) bf = a.bp[pcol + 3 * kUnit];
+    float *s_iu = region;
+    float *s_o = s_iu + 32 * kEpiStride;
+    float *s_fx = s_o + 32 * kEpiStride;
+    T *h_out = static_cast<T *>(a.h_out);
+    T *hs_out = static_cast<T *>(a.hs_out);
+    const bool separate_hs = (a.hs_out != a.h_out);
+    const bool separate_cs = (a.cs != a.c_out);
+    const bool vec_ok = (a.H & 3) == 0;
+    const int unit0 = unit_tile * kUnit + (lane & 7) * 4;
+    // unit groups past the padded width read the first group instead (and store nothing)
+    const int unit_ld = unit0 < a.Hq ? unit0 : 0;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int rl = (v >> 2) * 8 + hf * 4 + (v & 3);   // 0..31
+        const float gi = sigmoid_t<T>(acc[0][v] + bi);
+        const float go = sigmoid_t<T>(acc[1][v] + bo);
+        const float gu = tanh_t<T>(acc[2][v] + bu);
+        s_iu[rl * kEpiStride + l32] = gi * gu;
+        s_o[rl * kEpiStride + l32] = go;
+        if constexpr (MODE == MODE_INTERNAL) s_fx[rl * kEpiStride + l32] = acc[3][v] + bf;
+    }
+    // the wave's own LDS writes are ordered before its reads; nothing else touches the region
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    float4 cc[4], go4[4], fx4[4];
+    int node[4], tr[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        tr[q] = (lane >> 3) + 8 * q;
+        node[q] = rn[tr[q]];
+        const int so = tr[q] * kEpiStride + (lane & 7) * 4;
+        cc[q] = *reinterpret_cast<const float4 *>(s_iu + so);
+        go4[q] = *reinterpret_cast<const float4 *>(s_o + so);
+        if constexpr (MODE == MODE_INTERNAL) fx4[q] = *reinterpret_cast<const float4 *>(s_fx + so);
+    }
+    if constexpr (MODE == MODE_INTERNAL) {
+        // Children are taken two per row and round, for four rows at once: sixteen
+        // independent 16-byte loads in flight per thread.  The first four child ids
+        // of a row sit in LDS; longer lists (rare) continue from child_idx.  A slot
+        // without a child re-reads the row's last child with weight zero, which
+        // keeps every load unconditional.
+        int ar[4];
+        int max_ar = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            ar[q] = node[q] >= 0 ? rar[tr[q]] : 0;
+            max_ar = max(max_ar, ar[q]);
+        }
+        int64_t last[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) last[q] = unit_ld;
+        for (int c0 = 0; c0 < max_ar; c0 += 2) {
+            int64_t ofs[4][2];
+            float wgt[4][2];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                int4 kids = make_int4(0, 0, 0, 0);
+                if (c0 < 4) kids = rkid[tr[q]];
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const int c = c0 + j;
+                    const bool has = c < ar[q];
+                    int kid;
+                    if (c0 == 0) kid = j ? kids.y : kids.x;
+                    else if (c0 == 2) kid = j ? kids.w : kids.z;
+                    else kid = has ? a.child_idx[rcb[tr[q]] + c] : 0;
+                    if (has) last[q] = (int64_t)kid * a.Hq + unit_ld;
+                    ofs[q][j] = last[q];
+                    wgt[q][j] = has ? 1.0f : 0.0f;
+                }
+            }
+            float4 pk[4][2], ck[4][2];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    if constexpr (sizeof(T) == 4) {
+                        pk[q][j] = *reinterpret_cast<const float4 *>(static_cast<const float *>(a.P) + ofs[q][j]);
+                    } else {
+                        const uint2 w = *reinterpret_cast<const uint2 *>(static_cast<const bf16_t *>(a.P) + ofs[q][j]);
+                        pk[q][j] = make_float4(__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xFFFF0000u),
+                                               __uint_as_float(w.y << 16), __uint_as_float(w.y & 0xFFFF0000u));
+                    }
+                    ck[q][j] = *reinterpret_cast<const float4 *>(a.cs + ofs[q][j]);
+                }
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    cc[q].x += wgt[q][j] * sigmoid_t<T>(fx4[q].x + pk[q][j].x) * ck[q][j].x;
+                    cc[q].y += wgt[q][j] * sigmoid_t<T>(fx4[q].y + pk[q][j].y) * ck[q][j].y;
+                    cc[q].z += wgt[q][j] * sigmoid_t<T>(fx4[q].z + pk[q][j].z) * ck[q][j].z;
+                    cc[q].w += wgt[q][j] * sigmoid_t<T>(fx4[q].w + pk[q][j].w) * ck[q][j].w;
+                }
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        if (node[q] < 0) continue;
+        const float c4[4] = {cc[q].x, cc[q].y, cc[q].z, cc[q].w};
+        const float o4[4] = {go4[q].x, go4[q].y, go4[q].z, go4[q].w};
+        T hv[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) hv[j] = from_f32<T>(o4[j] * tanh_t<T>(c4[j]));
+        const int64_t nd = node[q];
+        if (vec_ok) {
+            if (unit0 < a.H) {
+                *reinterpret_cast<float4 *>(a.c_out + nd * a.H + unit0) = cc[q];
+                if (separate_cs) *reinterpret_cast<float4 *>(a.cs + nd * a.Hq + unit0) = cc[q];
+                if constexpr (sizeof(T) == 4) {
+                    const float4 h4 = make_float4(hv[0], hv[1], hv[2], hv[3]);
+                    *reinterpret_cast<float4 *>(h_out + nd * a.H + unit0) = h4;
+                    if (separate_hs) *reinterpret_cast<float4 *>(hs_out + nd * a.Hp + unit0) = h4;
+                } else {
+                    const uint2 h2 = make_uint2((uint32_t)hv[0] | ((uint32_t)hv[1] << 16),
+                                                (uint32_t)hv[2] | ((uint32_t)hv[3] << 16));
+                    *reinterpret_cast<uint2 *>(h_out + nd * a.H + unit0) = h2;
+                    if (separate_hs) *reinterpret_cast<uint2 *>(hs_out + nd * a.Hp + unit0) = h2;
+                }
+            } else if (separate_hs && unit0 < a.Hp) {   // zero pad columns of the padded h copy
+                if constexpr (sizeof(T) == 4)
+                    *reinterpret_cast<float4 *>(hs_out + nd * a.Hp + unit0) = make_float4(0.f, 0.f, 0.f, 0.f);
+                else
+                    *reinterpret_cast<uint2 *>(hs_out + nd * a.Hp + unit0) = make_uint2(0u, 0u);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int unit = unit0 + j;
+                if (unit < a.H) {
+                    a.c_out[nd * a.H + unit] = c4[j];
+                    if (separate_cs) a.cs[nd * a.Hq + unit] = c4[j];
+                    h_out[nd * a.H + unit] = hv[j];
+                    if (separate_hs) hs_out[nd * a.Hp + unit] = hv[j];
+                } else if (separate_hs && unit < a.Hp) {
+                    hs_out[nd * a.Hp + unit] = T(0);
+                }
+            }
+        }
+    }
+}
+
 template <typename T, int MODE>
 __global__ void __launch_bounds__(kGemmThreads, 1)
 level_kernel(const LevelArgs a) {
@@ -581,165 +742,150 @@ level_kernel(const LevelArgs a) {
             }
         }
     } else {
-        // The cell update runs row-major, wave by wave.  Each wave owns 64 rows x 32
-        // units of the tile and a private LDS region (the staging buffers are free
-        // now).  In two passes of 32 rows it writes i*u, o and the x part of the forget
-        // gate there and reads them back with eight lanes per row, four consecutive
-        // units per lane: the rows of the children (P_k and c_k) are then fetched in
-        // 8- and 16-byte pieces, 64 / 128 contiguous bytes per row, with four rows in
-        // flight per lane.  Apart from the one barrier that retires the main loop the
-        // waves do not wait for each other, so the arithmetic of one overlaps the
+        // The cell update runs wave by wave (cell_pass): each wave owns 64 rows x 32 units of
+        // the tile and a private LDS region (the staging buffers are free now), and handles
+        // them in two passes of 32 rows.  Apart from the one barrier that retires the main
+        // loop the waves do not wait for each other, so the arithmetic of one overlaps the
         // memory latency of the others.
-        const int pcol = col_tile * kBN + wn * kGateTile + l32;   // packed row of gate i for this unit
-        const float bi = a.bp[pcol], bo = a.bp[pcol + kUnit], bu = a.bp[pcol + 2 * kUnit];
-        float bf = 0.0f;
-        if constexpr (MODE == MODE_INTERNAL) bf = a.bp[pcol + 3 * kUnit];
-        float *s_iu = reinterpret_cast<float *>(lds) + wave * (3 * 32 * kEpiStride);
-        float *s_o = s_iu + 32 * kEpiStride;
-        float *s_fx = s_o + 32 * kEpiStride;
-        T *h_out = static_cast<T *>(a.h_out);
-        T *hs_out = static_cast<T *>(a.hs_out);
-        const bool separate_hs = (a.hs_out != a.h_out);
-        const bool separate_cs = (a.cs != a.c_out);
-        const bool vec_ok = (a.H & 3) == 0;
-        const int unit0 = (col_tile * 2 + wn) * kUnit + (lane & 7) * 4;
-        // unit groups past the padded width read the first group instead (and store nothing)
-        const int unit_ld = unit0 < a.Hq ? unit0 : 0;
+        float *region = reinterpret_cast<float *>(lds) + wave * (3 * 32 * kEpiStride);
         __syncthreads();   // every wave is done reading the staging buffers
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
+            const int r0 = wm * 64 + p * 32;
+            cell_pass<T, MODE>(a, acc[p], region, row_node + r0, row_ar + r0, row_cb + r0, row_kid + r0,
+                               col_tile * 2 + wn, lane);
+        }
+    }
+}
+
+// ---- thin levels ---------------------------------------------------------------------
+// A level with a few thousand rows gives the 256 x 256 tiles too few blocks to fill 256
+// CUs, and each block then runs one wave's whole K loop back to back: the level costs that
+// latency, not its work.  thin_kernel spreads such a level over many more waves.  Every
+// wave owns one tile of 32 rows x 32 hidden units (all four gates; the projection: 32 rows
+// x 4 unit tiles of forget rows), takes its MFMA operands straight from global memory /
+// L2 in fragment layout (16 bytes per lane, no LDS staging, four K groups requested
+// ahead), and finishes with the same cell_pass.  Waves never wait for each other.
+constexpr int kThinWaves = 4;     // waves (tiles) per block
+#ifndef JITDB_THIN_MAX_ROWS
+#define JITDB_THIN_MAX_ROWS 8192
+#endif
+constexpr int kThinMaxRows = JITDB_THIN_MAX_ROWS; // levels up to this many rows use the thin kernel
+constexpr int kThinAhead = 4;     // K groups in flight per wave
+
+template <typename T, int MODE>
+__global__ void __launch_bounds__(kThinWaves * 64, 2)
+thin_kernel(const LevelArgs a) {
+    constexpr int ESZ = (int)sizeof(T);
+    constexpr int NG_X = (MODE == MODE_LEAF) ? 3 : 4;
+    __shared__ __attribute__((aligned(16))) float regions[kThinWaves][3 * 32 * kEpiStride];
+    __shared__ int s_node[kThinWaves][32];
+    __shared__ int s_ar[kThinWaves][32];
+    __shared__ int s_cb[kThinWaves][32];
+    __shared__ int4 s_kid[kThinWaves][32];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int hf = lane >> 5, l32 = lane & 31;
+    const int tile = blockIdx.x * kThinWaves + wave;
+    if (tile >= a.n_tiles) return;            // whole waves leave; there is no block barrier below
+    const int row0 = (tile / a.n_col_tiles) * 32;
+    const int col = tile % a.n_col_tiles;     // unit tile (gates) or group of four unit tiles (projection)
+
+    // ---- the tile's rows
+    int my_row = row0 + l32;
+    const bool row_ok = my_row < a.n_rows;
+    if (!row_ok) my_row = a.n_rows - 1;       // computed twice, stored never
+    int my_node;
+    if constexpr (MODE == MODE_INTERNAL) {
+        const int4 r0 = a.row_rec[2 * (int64_t)my_row];
+        const int4 r1 = a.row_rec[2 * (int64_t)my_row + 1];
+        my_node = r0.x;
+        if (hf == 0) {
+            s_node[wave][l32] = row_ok ? r0.x : -1;
+            s_ar[wave][l32] = row_ok ? r0.y : 0;
+            s_cb[wave][l32] = r0.z;
+            s_kid[wave][l32] = r1;
+        }
+    } else {
+        my_node = a.level_nodes[my_row];
+        if (hf == 0) s_node[wave][l32] = row_ok ? my_node : -1;
+    }
+
+    // ---- operand addresses: lane (l32, hf) supplies row l32, bytes [hf*16, +16) of each
+    //      32-byte K group, for A and for every B row group alike
+    const int64_t b_row_bytes = (int64_t)(a.Dp + a.Hp) * ESZ;
+    const char *ap, *bp;
+    int64_t b_step;
+    int n_groups, n_groups_x;                 // K groups in total / with all four gates
+    if constexpr (MODE == MODE_PROJ) {
+        ap = static_cast<const char *>(a.hs) + (int64_t)my_node * a.Hp * ESZ + hf * 16;
+        const int64_t row = (int64_t)(col * 4) * kGateTile + 3 * kUnit + l32;
+        bp = static_cast<const char *>(a.Bp) + row * b_row_bytes + (int64_t)a.Dp * ESZ + hf * 16;
+        b_step = (int64_t)kGateTile * b_row_bytes;
+        n_groups = a.Hp * ESZ / 32;
+        n_groups_x = n_groups;
+    } else {
+        const int64_t a_row_bytes = (int64_t)(a.Dp + (MODE == MODE_INTERNAL ? a.Hp : 0)) * ESZ;
+        ap = static_cast<const char *>(a.stack) + (int64_t)my_row * a_row_bytes + hf * 16;
+        const int64_t row = (int64_t)col * kGateTile + l32;
+        bp = static_cast<const char *>(a.Bp) + row * b_row_bytes + hf * 16;
+        b_step = (int64_t)kUnit * b_row_bytes;
+        n_groups_x = a.Dp * ESZ / 32;
+        n_groups = (int)(a_row_bytes / 32);
+    }
+
+    floatx16 acc[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[g][v] = 0.0f;
+
+    u32x4 fa[kThinAhead], fb[kThinAhead][4];
+    auto request = [&](int g, int slot) __attribute__((always_inline)) {
+        const int64_t kb = (int64_t)g * 32;
+        fa[slot] = *reinterpret_cast<const u32x4 *>(ap + kb);
+#pragma unroll
+        for (int q = 0; q < NG_X; ++q) fb[slot][q] = *reinterpret_cast<const u32x4 *>(bp + q * b_step + kb);
+    };
+#pragma unroll
+    for (int s = 0; s < kThinAhead; ++s)
+        if (s < n_groups) request(s, s);
+    for (int g0 = 0; g0 < n_groups; g0 += kThinAhead) {
+#pragma unroll
+        for (int s = 0; s < kThinAhead; ++s) {
+            const int g = g0 + s;
+            if (g < n_groups) {
+                mfma_step<T>(fa[s], fb[s][0], acc[0]);
+                mfma_step<T>(fa[s], fb[s][1], acc[1]);
+                mfma_step<T>(fa[s], fb[s][2], acc[2]);
+                // the forget rows take part in the x part only (and in all of the projection)
+                if (NG_X == 4 && (MODE != MODE_INTERNAL || g < n_groups_x)) mfma_step<T>(fa[s], fb[s][3], acc[3]);
+                if (g + kThinAhead < n_groups) request(g + kThinAhead, s);
+            }
+        }
+    }
+
+    if constexpr (MODE == MODE_PROJ) {
+        T *P = static_cast<T *>(a.P);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int unit = (col * 4 + q) * kUnit + l32;
+            if (unit >= a.H) continue;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int rl = (v >> 2) * 8 + hf * 4 + (v & 3);   // 0..31
-                const float gi = sigmoid_t<T>(acc[p][0][v] + bi);
-                const float go = sigmoid_t<T>(acc[p][1][v] + bo);
-                const float gu = tanh_t<T>(acc[p][2][v] + bu);
-                s_iu[rl * kEpiStride + l32] = gi * gu;
-                s_o[rl * kEpiStride + l32] = go;
-                if constexpr (MODE == MODE_INTERNAL) s_fx[rl * kEpiStride + l32] = acc[p][3][v] + bf;
-            }
-            // the wave's own LDS writes are ordered before its reads; nothing else touches the region
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            float4 cc[4], go4[4], fx4[4];
-            int node[4], tr[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int rl = (lane >> 3) + 8 * q;
-                tr[q] = wm * 64 + p * 32 + rl;
-                node[q] = row_node[tr[q]];
-                const int so = rl * kEpiStride + (lane & 7) * 4;
-                cc[q] = *reinterpret_cast<const float4 *>(s_iu + so);
-                go4[q] = *reinterpret_cast<const float4 *>(s_o + so);
-                if constexpr (MODE == MODE_INTERNAL) fx4[q] = *reinterpret_cast<const float4 *>(s_fx + so);
-            }
-            if constexpr (MODE == MODE_INTERNAL) {
-                // Children are taken two per row and round, for four rows at once: sixteen
-                // independent 16-byte loads in flight per thread.  The first four child ids
-                // of a row sit in LDS; longer lists (rare) continue from child_idx.  A slot
-                // without a child re-reads the row's last child with weight zero, which
-                // keeps every load unconditional.
-                int ar[4];
-                int max_ar = 0;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    ar[q] = node[q] >= 0 ? row_ar[tr[q]] : 0;
-                    max_ar = max(max_ar, ar[q]);
-                }
-                int64_t last[4];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) last[q] = unit_ld;
-                for (int c0 = 0; c0 < max_ar; c0 += 2) {
-                    int64_t ofs[4][2];
-                    float wgt[4][2];
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        int4 kids = make_int4(0, 0, 0, 0);
-                        if (c0 < 4) kids = row_kid[tr[q]];
-#pragma unroll
-                        for (int j = 0; j < 2; ++j) {
-                            const int c = c0 + j;
-                            const bool has = c < ar[q];
-                            int kid;
-                            if (c0 == 0) kid = j ? kids.y : kids.x;
-                            else if (c0 == 2) kid = j ? kids.w : kids.z;
-                            else kid = has ? a.child_idx[row_cb[tr[q]] + c] : 0;
-                            if (has) last[q] = (int64_t)kid * a.Hq + unit_ld;
-                            ofs[q][j] = last[q];
-                            wgt[q][j] = has ? 1.0f : 0.0f;
-                        }
-                    }
-                    float4 pk[4][2], ck[4][2];
-#pragma unroll
-                    for (int q = 0; q < 4; ++q)
-#pragma unroll
-                        for (int j = 0; j < 2; ++j) {
-                            if constexpr (sizeof(T) == 4) {
-                                pk[q][j] = *reinterpret_cast<const float4 *>(static_cast<const float *>(a.P) + ofs[q][j]);
-                            } else {
-                                const uint2 w = *reinterpret_cast<const uint2 *>(static_cast<const bf16_t *>(a.P) + ofs[q][j]);
-                                pk[q][j] = make_float4(__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xFFFF0000u),
-                                                       __uint_as_float(w.y << 16), __uint_as_float(w.y & 0xFFFF0000u));
-                            }
-                            ck[q][j] = *reinterpret_cast<const float4 *>(a.cs + ofs[q][j]);
-                        }
-#pragma unroll
-                    for (int q = 0; q < 4; ++q)
-#pragma unroll
-                        for (int j = 0; j < 2; ++j) {
-                            cc[q].x += wgt[q][j] * sigmoid_t<T>(fx4[q].x + pk[q][j].x) * ck[q][j].x;
-                            cc[q].y += wgt[q][j] * sigmoid_t<T>(fx4[q].y + pk[q][j].y) * ck[q][j].y;
-                            cc[q].z += wgt[q][j] * sigmoid_t<T>(fx4[q].z + pk[q][j].z) * ck[q][j].z;
-                            cc[q].w += wgt[q][j] * sigmoid_t<T>(fx4[q].w + pk[q][j].w) * ck[q][j].w;
-                        }
-                }
-            }
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                if (node[q] < 0) continue;
-                const float c4[4] = {cc[q].x, cc[q].y, cc[q].z, cc[q].w};
-                const float o4[4] = {go4[q].x, go4[q].y, go4[q].z, go4[q].w};
-                T hv[4];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) hv[j] = from_f32<T>(o4[j] * tanh_t<T>(c4[j]));
-                const int64_t nd = node[q];
-                if (vec_ok) {
-                    if (unit0 < a.H) {
-                        *reinterpret_cast<float4 *>(a.c_out + nd * a.H + unit0) = cc[q];
-                        if (separate_cs) *reinterpret_cast<float4 *>(a.cs + nd * a.Hq + unit0) = cc[q];
-                        if constexpr (sizeof(T) == 4) {
-                            const float4 h4 = make_float4(hv[0], hv[1], hv[2], hv[3]);
-                            *reinterpret_cast<float4 *>(h_out + nd * a.H + unit0) = h4;
-                            if (separate_hs) *reinterpret_cast<float4 *>(hs_out + nd * a.Hp + unit0) = h4;
-                        } else {
-                            const uint2 h2 = make_uint2((uint32_t)hv[0] | ((uint32_t)hv[1] << 16),
-                                                        (uint32_t)hv[2] | ((uint32_t)hv[3] << 16));
-                            *reinterpret_cast<uint2 *>(h_out + nd * a.H + unit0) = h2;
-                            if (separate_hs) *reinterpret_cast<uint2 *>(hs_out + nd * a.Hp + unit0) = h2;
-                        }
-                    } else if (separate_hs && unit0 < a.Hp) {   // zero pad columns of the padded h copy
-                        if constexpr (sizeof(T) == 4)
-                            *reinterpret_cast<float4 *>(hs_out + nd * a.Hp + unit0) = make_float4(0.f, 0.f, 0.f, 0.f);
-                        else
-                            *reinterpret_cast<uint2 *>(hs_out + nd * a.Hp + unit0) = make_uint2(0u, 0u);
-                    }
-                } else {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int unit = unit0 + j;
-                        if (unit < a.H) {
-                            a.c_out[nd * a.H + unit] = c4[j];
-                            if (separate_cs) a.cs[nd * a.Hq + unit] = c4[j];
-                            h_out[nd * a.H + unit] = hv[j];
-                            if (separate_hs) hs_out[nd * a.Hp + unit] = hv[j];
-                        } else if (separate_hs && unit < a.Hp) {
-                            hs_out[nd * a.Hp + unit] = T(0);
-                        }
-                    }
+                const int r = row0 + (v >> 2) * 8 + hf * 4 + (v & 3);
+                if (r < a.n_rows) {
+                    const int node = a.level_nodes[r];
+                    P[(int64_t)node * a.Hq + unit] = from_f32<T>(acc[q][v]);
                 }
             }
         }
+    } else {
+        // the row data written above is read by this wave only
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        cell_pass<T, MODE>(a, acc, regions[wave], s_node[wave], s_ar[wave], s_cb[wave], s_kid[wave], col, lane);
     }
 }
 
@@ -884,25 +1030,47 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
                     s->child_idx, static_cast<T *>(w.stack), n_rows);
             JITDB_LAUNCH_CHECK();
         }
-        a.n_col_tiles = d.NP / kBN;
-        a.n_blocks = row_tiles * a.n_col_tiles;
+        // Levels too small to give every CU a 256 x 256 tile go to the thin kernel.
+        const bool thin = n_rows <= kThinMaxRows;
+        const int n_unit_tiles = d.Hu / kUnit;
+        if (thin) {
+            a.n_col_tiles = n_unit_tiles;
+            a.n_tiles = (int)ceil_div(n_rows, 32) * a.n_col_tiles;
+            a.n_blocks = (int)ceil_div(a.n_tiles, kThinWaves);
+        } else {
+            a.n_col_tiles = d.NP / kBN;
+            a.n_tiles = 0;
+            a.n_blocks = row_tiles * a.n_col_tiles;
+        }
         {
             ScopedLaunchTimer tm(l == 0 ? JITDB_K_LEAF : JITDB_K_INTERNAL, st);
-            if (l == 0)
-                level_kernel<T, MODE_LEAF><<<a.n_blocks, kGemmThreads, 0, st>>>(a);
-            else
-                level_kernel<T, MODE_INTERNAL><<<a.n_blocks, kGemmThreads, 0, st>>>(a);
+            if (thin) {
+                if (l == 0)
+                    thin_kernel<T, MODE_LEAF><<<a.n_blocks, kThinWaves * 64, 0, st>>>(a);
+                else
+                    thin_kernel<T, MODE_INTERNAL><<<a.n_blocks, kThinWaves * 64, 0, st>>>(a);
+            } else {
+                if (l == 0)
+                    level_kernel<T, MODE_LEAF><<<a.n_blocks, kGemmThreads, 0, st>>>(a);
+                else
+                    level_kernel<T, MODE_INTERNAL><<<a.n_blocks, kGemmThreads, 0, st>>>(a);
+            }
         }
         JITDB_LAUNCH_CHECK();
         if (l + 1 < L) {   // these nodes have parents (except roots, whose rows go unused)
-            a.n_col_tiles = (int)ceil_div(d.Hu / kUnit, 8);
-            a.n_blocks = row_tiles * a.n_col_tiles;
-            {
-                ScopedLaunchTimer tm(JITDB_K_PROJ, st);
+            ScopedLaunchTimer tm(JITDB_K_PROJ, st);
+            if (thin) {
+                a.n_col_tiles = (int)ceil_div(n_unit_tiles, 4);
+                a.n_tiles = (int)ceil_div(n_rows, 32) * a.n_col_tiles;
+                a.n_blocks = (int)ceil_div(a.n_tiles, kThinWaves);
+                thin_kernel<T, MODE_PROJ><<<a.n_blocks, kThinWaves * 64, 0, st>>>(a);
+            } else {
+                a.n_col_tiles = (int)ceil_div(n_unit_tiles, 8);
+                a.n_blocks = row_tiles * a.n_col_tiles;
                 level_kernel<T, MODE_PROJ><<<a.n_blocks, kGemmThreads, 0, st>>>(a);
             }
-            JITDB_LAUNCH_CHECK();
         }
+        JITDB_LAUNCH_CHECK();
     }
     return JITDB_OK;
 }
