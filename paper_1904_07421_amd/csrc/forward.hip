@@ -40,16 +40,12 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kThreads = 256;     // small kernels
-constexpr int kGemmThreads = 512; // level kernels: eight waves
-constexpr int kBM = 256;        // rows (nodes) per block
+constexpr int kRowPad = 256;    // level row counts are rounded up to this for the stacked input
 constexpr int kBN = 256;        // packed columns per block = 2 unit tiles x 4 gates x 32
 constexpr int kUnit = 32;       // hidden units per MFMA column tile
 constexpr int kGateTile = 128;  // packed rows per unit tile (4 gates x 32 units)
 
-constexpr int kEpiRows = 128;   // rows per pass of the projection's store epilogue
 constexpr int kEpiStride = 40;  // floats per row of a wave's epilogue region: 32 units + 8; rows 4 apart fall 32 banks apart
-constexpr int kProjStride = 264; // same for the projection's 256-unit rows
-constexpr int kLdsStride = 144; // stage row (128 bytes) + 16: 128-bit LDS reads of 32 rows hit distinct banks
 
 enum : int { MODE_LEAF = 0, MODE_INTERNAL = 1, MODE_PROJ = 2 };
 
@@ -62,6 +58,17 @@ template <> struct Traits<bf16_t> {
     static constexpr int BK = 64;
     static constexpr int VEC = 8;
 };
+
+// ---- operand layout ----------------------------------------------------------------
+// The two GEMM operands this file writes for itself (the stacked level input A and the
+// packed weights B) are stored K-blocked: bytes [64 s, 64 s + 64) of every row form slab
+// s, rows consecutive inside a slab.  A pipeline stage of the level kernel is 64 bytes of
+// K per row, so the 16 rows x 64 bytes that one direct-to-LDS load instruction moves are
+// 1 KB of consecutive memory, whole 128-byte lines.  (Fetching half a line now and the
+// other half a stage later costs a full line transfer from L2 each time.)
+__host__ __device__ __forceinline__ int64_t operand_offset(int64_t row, int64_t kbyte, int64_t n_rows_alloc) {
+    return ((kbyte >> 6) * n_rows_alloc + row) * 64 + (kbyte & 63);
+}
 
 // ---- scalar helpers ----------------------------------------------------------------
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float((uint32_t)v << 16); }
@@ -110,29 +117,80 @@ pack_weights_kernel(const T *__restrict__ W, const T *__restrict__ U, const floa
             if (k < D) v = W[src * D + k];
             else if (k >= Dp && k - Dp < H) v = U[src * H + (k - Dp)];
         }
-        Bp[idx] = v;
+        *reinterpret_cast<T *>(reinterpret_cast<char *>(Bp) +
+                               operand_offset(r, (int64_t)k * sizeof(T), NPU)) = v;
         if (k == 0 && r < NP) bp[r] = row_ok ? b[src] : 0.0f;
     }
 }
 
 // ---- row records -------------------------------------------------------------------
-// What the stack step and the cell update need to know about the node at level
-// position p, in one 32-byte record: { node, arity, CSR start, - } { first four child
-// ids (-1 where there is none) }.  Written once per forward for all positions, so that
-// the per-level kernels start from one load instead of the chain perm -> child_ptr ->
-// child_idx.
+// What the stack step and the cell update need to know about the node in row r of a
+// level, in one 32-byte record: { node, arity, CSR start, - } { first four child ids (-1
+// where there is none) }.  Written once per forward for all levels, so that the per-level
+// kernels start from one load instead of the chain perm -> child_ptr -> child_idx.
+//
+// The rows of a level are independent, so their order inside the level is free.  The
+// cell update walks the child lists of 32 rows in lock step and takes as many rounds as
+// the longest of them; with rows in node-id order that is about twice the average need.
+// The records are therefore ordered by falling arity inside windows of kRecWindow level
+// positions (a counting sort in LDS; positions are already ordered by level, and the
+// level is the major key so every row stays inside its level).  A window that spans 16 or
+// more levels is left in position order: its levels are too small for the order to matter.
+constexpr int kRecWindow = 4096;
+constexpr int kRecPerThread = kRecWindow / kThreads;
+
 __global__ void __launch_bounds__(kThreads)
-row_record_kernel(const int32_t *__restrict__ perm, const int32_t *__restrict__ child_ptr,
-                  const int32_t *__restrict__ child_idx, int4 *__restrict__ row_rec, int n) {
-    const int64_t p = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (p >= n) return;
-    const int node = perm[p];
-    const int cb = child_ptr[node], ar = child_ptr[node + 1] - cb;
-    int kid[4];
+row_record_kernel(const int32_t *__restrict__ perm, const int32_t *__restrict__ height,
+                  const int32_t *__restrict__ child_ptr, const int32_t *__restrict__ child_idx,
+                  int4 *__restrict__ row_rec, int n) {
+    __shared__ int s_count[256];   // per key: count, then the next free slot
+    __shared__ int s_scan[256];
+    const int t = threadIdx.x;
+    const int w0 = blockIdx.x * kRecWindow;
+    const int wn = (n - w0) < kRecWindow ? (n - w0) : kRecWindow;
+    const int lvl0 = height[perm[w0]];
+    const int lvl1 = height[perm[w0 + wn - 1]];
+    const bool sorted = (lvl1 - lvl0) < 16;
+    s_count[t] = 0;
+    __syncthreads();
+    int node[kRecPerThread], ar[kRecPerThread], cb[kRecPerThread], key[kRecPerThread];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) kid[j] = j < ar ? child_idx[cb + j] : -1;
-    row_rec[2 * p] = make_int4(node, ar, cb, 0);
-    row_rec[2 * p + 1] = make_int4(kid[0], kid[1], kid[2], kid[3]);
+    for (int i = 0; i < kRecPerThread; ++i) {
+        const int p = w0 + i * kThreads + t;
+        node[i] = -1; ar[i] = 0; cb[i] = 0; key[i] = 0;
+        if (p < w0 + wn) {
+            node[i] = perm[p];
+            cb[i] = child_ptr[node[i]];
+            ar[i] = child_ptr[node[i] + 1] - cb[i];
+            if (sorted) {
+                key[i] = (height[node[i]] - lvl0) * 16 + (15 - (ar[i] < 15 ? ar[i] : 15));
+                atomicAdd(&s_count[key[i]], 1);
+            }
+        }
+    }
+    __syncthreads();
+    // exclusive scan of the 256 counts
+    int v = s_count[t];
+    s_scan[t] = v;
+    __syncthreads();
+    for (int d = 1; d < 256; d <<= 1) {
+        const int add = t >= d ? s_scan[t - d] : 0;
+        __syncthreads();
+        s_scan[t] += add;
+        __syncthreads();
+    }
+    s_count[t] = s_scan[t] - v;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kRecPerThread; ++i) {
+        if (node[i] < 0) continue;
+        const int64_t q = sorted ? (int64_t)w0 + atomicAdd(&s_count[key[i]], 1) : (int64_t)w0 + i * kThreads + t;
+        int kid[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) kid[j] = j < ar[i] ? child_idx[cb[i] + j] : -1;
+        row_rec[2 * q] = make_int4(node[i], ar[i], cb[i], 0);
+        row_rec[2 * q + 1] = make_int4(kid[0], kid[1], kid[2], kid[3]);
+    }
 }
 
 // ---- stack -------------------------------------------------------------------------
@@ -161,7 +219,7 @@ template <typename T, bool WITH_H>
 __global__ void __launch_bounds__(kThreads)
 stack_kernel(const T *__restrict__ x, int D, int Dp, const T *__restrict__ hs, int Hp,
              const int4 *__restrict__ row_rec, const int32_t *__restrict__ child_idx,
-             T *__restrict__ A, int n_rows) {
+             T *__restrict__ A, int n_rows, int n_rows_alloc) {
     constexpr int VEC = Traits<T>::VEC;
     const int Kp = Dp + (WITH_H ? Hp : 0);
     const int cpr = Kp / VEC;
@@ -227,7 +285,8 @@ stack_kernel(const T *__restrict__ x, int D, int Dp, const T *__restrict__ hs, i
             o.x = w[0]; o.y = w[1]; o.z = w[2]; o.w = w[3];
         }
     }
-    *reinterpret_cast<uint4 *>(A + row * Kp + k0) = o;
+    *reinterpret_cast<uint4 *>(reinterpret_cast<char *>(A) +
+                               operand_offset(row, (int64_t)k0 * sizeof(T), n_rows_alloc)) = o;
 }
 
 // ---- the level GEMM ----------------------------------------------------------------
@@ -239,7 +298,6 @@ struct LevelArgs {
     const void *Bp;
     const float *bp;      // [NP] packed bias
     // schedule
-    const int32_t *level_nodes;  // perm + level start: row -> node id
     const int4 *row_rec;         // two int4 per level row (this level's slice of the records)
     const int32_t *child_idx;
     // per-child forget projections U_f h_k, rows by node id, stride Hq, element type T
@@ -252,6 +310,8 @@ struct LevelArgs {
     void *hs_out;         // [N, Hp] or == h_out when H == Hp
     int D, Dp, H, Hp, Hu, Hq;
     int n_rows;
+    int n_rows_alloc;     // rows per slab of the stacked input (n_rows rounded up to whole tiles)
+    int NPU;              // rows per slab of the packed weights
     int n_col_tiles;      // tiles along the column axis
     int n_tiles;          // thin kernel: number of wave tiles
     int n_blocks;
@@ -276,198 +336,6 @@ __device__ __forceinline__ void mfma_step(const u32x4 &a, const u32x4 &b, floatx
         acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[2]), __uint_as_float(b[2]), acc, 0, 0, 0);
         acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[3]), __uint_as_float(b[3]), acc, 0, 0, 0);
     }
-}
-
-// What one thread holds of a K stage on its way from global memory to LDS:
-// 16 bytes of each of four A rows and four B rows.
-struct StageRegs {
-    u32x4 a[4];
-    u32x4 b[4];
-};
-
-// The block GEMM: 256 rows x 256 packed columns per block of eight waves, each
-// wave a 64 x 128 sub-tile (2 x 4 MFMA tiles of 32 x 32).  A is the level's
-// stacked input [x | hsum] (row stride Kp = Dp + Hp), B the packed [W | U]
-// with the same K layout; K runs over "stages" of 128 bytes per row (one cache
-// line): n_x stages of the x part, then n_h of the h part, in which the forget
-// gate is skipped (U_f applies to each child's own h, not to the sum).  The
-// projection instead reads A rows from hs by node id and uses only the U part
-// of the forget rows.  One software pipeline with two LDS buffers and one
-// barrier per stage; in iteration g
-//   - the registers holding stage g+1 (requested one iteration ago) go to the
-//     idle LDS buffer; these writes drain through the 64-bytes-per-clock LDS
-//     write port while the matrix cores work,
-//   - stage g is multiplied out of the other buffer,
-//   - half way through, stage g+2 is requested from global memory (by then
-//     the LDS writes have released the registers).
-//
-// LDS layout: row r at r*kLdsStride, K contiguous, A rows 0-255 then B rows.
-// In each 16-wide (bf16) or 8-wide (fp32) K group, lanes 0-31 take the first
-// 16 bytes and lanes 32-63 the next 16 for A and B alike; since the same
-// assignment is used on both operands any such split of K is a valid MFMA
-// schedule.
-//
-// Staging map: eight consecutive lanes move the eight 16-byte pieces of one row
-// (a whole line per row and load instruction); thread t handles piece t&7 of
-// A rows t/8 + 64 i.  Of B it handles hidden unit (t/8)%32 of unit tile t/256,
-// row group i being the gate (or, for the projection, unit tile 4*(t/256) + i),
-// so whole gates can be skipped at compile time.
-template <typename T, int MODE, typename Hook>
-__device__ __forceinline__ void block_gemm(const LevelArgs &a, char *lds, const int *row_node,
-                                           int tile_row0, int col_tile, floatx16 (&acc)[2][4],
-                                           Hook &&after_first_requests) {
-    constexpr int BK = Traits<T>::BK;
-    constexpr int ESZ = (int)sizeof(T);
-    constexpr int NG_X = (MODE == MODE_LEAF) ? 3 : 4;      // gate tiles multiplied in the x part
-    constexpr int NG_H = (MODE == MODE_INTERNAL) ? 3 : 4;  // ... in the h part
-
-    const int t = threadIdx.x;
-    const int lane = t & 63, wave = t >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    const int hf = lane >> 5, l32 = lane & 31;
-
-    const int n_x = (MODE == MODE_PROJ) ? 0 : a.Dp / BK;
-    const int n_h = (MODE == MODE_LEAF) ? 0 : a.Hp / BK;
-    const int n_stages = n_x + n_h;
-    const int64_t b_row_bytes = (int64_t)(a.Dp + a.Hp) * ESZ;
-
-    // ---- A source: rows tile_row0 + t/8 + 64 i of the stacked matrix (rows past the end
-    //      of the level lie inside the buffer, hold anything and are never stored), or
-    //      for the projection rows of hs by node id (clamped to the level's last row).
-    const char *ap[MODE == MODE_PROJ ? 4 : 1];
-    int64_t a_step = 0;
-    if constexpr (MODE == MODE_PROJ) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            int g = tile_row0 + (t >> 3) + 64 * i;
-            if (g >= a.n_rows) g = a.n_rows - 1;
-            ap[i] = static_cast<const char *>(a.hs) + (int64_t)row_node[g - tile_row0] * a.Hp * ESZ + (t & 7) * 16;
-        }
-    } else {
-        const int64_t a_row_bytes = (int64_t)(a.Dp + (MODE == MODE_INTERNAL ? a.Hp : 0)) * ESZ;
-        ap[0] = static_cast<const char *>(a.stack) + (int64_t)(tile_row0 + (t >> 3)) * a_row_bytes + (t & 7) * 16;
-        a_step = 64 * a_row_bytes;
-    }
-    // ---- B source
-    const int uu = (t >> 3) & 31, ut = t >> 8;
-    const char *bp;
-    int64_t b_step;
-    if constexpr (MODE == MODE_PROJ) {
-        const int64_t row = (int64_t)(col_tile * 8 + ut * 4) * kGateTile + 3 * kUnit + uu;
-        bp = static_cast<const char *>(a.Bp) + row * b_row_bytes + (int64_t)a.Dp * ESZ + (t & 7) * 16;
-        b_step = (int64_t)kGateTile * b_row_bytes;
-    } else {
-        const int64_t row = (int64_t)col_tile * kBN + ut * kGateTile + uu;
-        bp = static_cast<const char *>(a.Bp) + row * b_row_bytes + (t & 7) * 16;
-        b_step = (int64_t)kUnit * b_row_bytes;
-    }
-    const int a_wr = (t >> 3) * kLdsStride + (t & 7) * 16;
-    const int b_wr = (kBM + ut * kGateTile + uu) * kLdsStride + (t & 7) * 16;
-    const int a_rd = (wm * 64 + l32) * kLdsStride + hf * 16;
-    const int b_rd = (kBM + wn * 128 + l32) * kLdsStride + hf * 16;
-
-    auto ld16 = [](const char *p) __attribute__((always_inline)) { return *reinterpret_cast<const u32x4 *>(p); };
-
-    // B row groups moved per stage.  The internal levels move the forget rows in the h
-    // part too although they are not multiplied there: with x and h parts alike, every
-    // iteration of the pipeline is one straight-line block that can be scheduled as a whole.
-    constexpr int NG_F = (MODE == MODE_LEAF) ? 3 : 4;
-
-    StageRegs r;
-    // global -> registers, stage g
-    auto fetch = [&](int g, StageRegs &r) __attribute__((always_inline)) {
-        const int64_t kb = (int64_t)g * (BK * ESZ);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            if constexpr (MODE == MODE_PROJ) r.a[i] = ld16(ap[i] + kb);
-            else r.a[i] = ld16(ap[0] + i * a_step + kb);
-        }
-#pragma unroll
-        for (int i = 0; i < NG_F; ++i) r.b[i] = ld16(bp + i * b_step + kb);
-    };
-    // registers -> LDS
-    auto stash = [&](char *buf, const StageRegs &r) __attribute__((always_inline)) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(buf + a_wr + i * 64 * kLdsStride) = r.a[i];
-#pragma unroll
-        for (int i = 0; i < NG_F; ++i) *reinterpret_cast<u32x4 *>(buf + b_wr + i * 32 * kLdsStride) = r.b[i];
-    };
-    constexpr int kBufBytes = (kBM + kBN) * kLdsStride;
-    const std::integral_constant<int, NG_X> ngx;
-    const std::integral_constant<int, NG_H> ngh;
-    const int last = n_stages - 1;
-
-    // One iteration: stage g is multiplied out of buffer g&1 while stage g+1 moves from
-    // the registers to the other buffer and stage g+2 from global memory to the registers.
-    // The issue order is fixed by hand: per K group first its LDS reads, then its MFMAs
-    // with one LDS write (K groups 0, 1) or one global load (K groups 2, 3) after every
-    // quarter of them.  Left to itself the compiler issues all LDS writes first, and since
-    // a wave issues in order its MFMAs then wait until the 64-bytes-per-clock write port
-    // has taken the writes of all eight waves.  The last iterations repeat the stash /
-    // fetch of the last stage (into the idle buffer, from addresses in range) instead of
-    // branching around them.
-    auto iteration = [&](int g, auto ng_tag) __attribute__((always_inline)) {
-        constexpr int NG = decltype(ng_tag)::value;
-        constexpr int M = 2 * NG;   // MFMA tiles per K group
-        const char *sa = lds + (g & 1) * kBufBytes + a_rd;
-        const char *sb = lds + (g & 1) * kBufBytes + b_rd;
-        char *nxt = lds + ((g & 1) ^ 1) * kBufBytes;
-        const int gf = g + 2 < last ? g + 2 : last;
-        const int64_t kb = (int64_t)gf * (BK * ESZ);
-        // Fragments are double buffered: the LDS reads of K group h+1 are issued ahead of
-        // the MFMAs of K group h, so only the first group of a stage waits for LDS.
-        u32x4 av[2][2], bv[2][NG];
-        auto read_frags = [&](int h, int set) __attribute__((always_inline)) {
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-                av[set][i] = *reinterpret_cast<const u32x4 *>(sa + i * 32 * kLdsStride + h * 32);
-#pragma unroll
-            for (int q = 0; q < NG; ++q)
-                bv[set][q] = *reinterpret_cast<const u32x4 *>(sb + q * 32 * kLdsStride + h * 32);
-        };
-        read_frags(0, 0);
-#pragma unroll
-        for (int h = 0; h < 4; ++h) {
-            const int cur = h & 1;
-            if (h < 3) read_frags(h + 1, cur ^ 1);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-#pragma unroll
-                for (int m = j * M / 4; m < (j + 1) * M / 4; ++m)
-                    mfma_step<T>(av[cur][m / NG], bv[cur][m % NG], acc[m / NG][m % NG]);
-                __builtin_amdgcn_sched_barrier(0);
-                const int o = (h & 1) * 4 + j;      // which of the eight moves of this half
-                if (h < 2) {                         // registers -> LDS
-                    if (o < 4)
-                        *reinterpret_cast<u32x4 *>(nxt + a_wr + o * 64 * kLdsStride) = r.a[o];
-                    else if (o - 4 < NG_F)
-                        *reinterpret_cast<u32x4 *>(nxt + b_wr + (o - 4) * 32 * kLdsStride) = r.b[o - 4];
-                } else {                             // global -> registers
-                    if (o < 4) {
-                        if constexpr (MODE == MODE_PROJ) r.a[o] = ld16(ap[o] + kb);
-                        else r.a[o] = ld16(ap[0] + o * a_step + kb);
-                    } else if (o - 4 < NG_F) {
-                        r.b[o - 4] = ld16(bp + (o - 4) * b_step + kb);
-                    }
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-        __syncthreads();
-    };
-    // Start-up: stages 0 and 1 are requested together (the accumulators are not live yet,
-    // so a second register set is free), then the caller publishes its per-row data, whose
-    // loads it issued before calling: one memory latency instead of three in a row.
-    {
-        StageRegs r_first;
-        fetch(0, r_first);
-        fetch(1 < last ? 1 : last, r);
-        after_first_requests();
-        stash(lds, r_first);
-    }
-    __syncthreads();
-    for (int g = 0; g < n_x; ++g) iteration(g, ngx);
-    for (int g = n_x; g < n_stages; ++g) iteration(g, ngh);
 }
 
 // ---- the cell update of one wave: 32 rows x 32 hidden units ---------------------------
@@ -630,40 +498,275 @@ __device__ __forceinline__ void cell_pass(const LevelArgs &a, const floatx16 (&a
     }
 }
 
-template <typename T, int MODE>
-__global__ void __launch_bounds__(kGemmThreads, 1)
-level_kernel(const LevelArgs a) {
-    __shared__ __attribute__((aligned(16))) char lds[2 * (kBM + kBN) * kLdsStride];
-    static_assert(8 * 3 * 32 * kEpiStride * 4 <= 2 * (kBM + kBN) * kLdsStride, "epilogue regions must fit the staging buffers");
-    static_assert(kEpiRows * kProjStride * 4 <= 2 * (kBM + kBN) * kLdsStride, "projection tile must fit the staging buffers");
-    __shared__ int row_node[kBM];
-    __shared__ int row_ar[kBM];     // number of children
-    __shared__ int row_cb[kBM];     // start of the child list in child_idx
-    __shared__ int4 row_kid[kBM];   // first four child ids
+// ---- the level GEMM, two blocks per CU --------------------------------------------------
+// Same tile arithmetic as block_gemm (wave tile 64 rows x 128 packed columns, cell update in
+// the epilogue), organised so that two blocks share a CU: while one block is in its
+// memory-bound epilogue or start-up the matrix cores work for the other.  That needs half
+// the LDS and registers per block: 128 rows x 256 packed columns per block of four waves,
+// and K stages of 64 bytes per row that travel from global memory straight into LDS
+// (global_load_lds, 16 bytes per lane) without passing through registers.  Three stage
+// buffers: stage g is multiplied while g+1 and g+2 are in flight; one barrier per stage.
+//
+// A direct load writes the 64 lanes' pieces to 1024 consecutive LDS bytes, i.e. 16 rows of
+// 64 bytes with no room for padding, so bank conflicts are avoided by permuting the four
+// 16-byte pieces of a row instead: piece p of row r is kept in slot p ^ ((r >> 2) & 3).
+// The lane that fills slot s of row r therefore fetches piece s ^ ((r >> 2) & 3), and a
+// fragment read of 16 consecutive rows touches 16 distinct 16-byte columns.
+constexpr int kDmaThreads = 256;
+constexpr int kDmaBM = 128;        // rows per block
+constexpr int kDmaStage = 64;      // bytes of K per row and stage
+constexpr int kDmaBuf = (kDmaBM + kBN) * kDmaStage;
+constexpr int kDmaBufs = 3;
+constexpr int kDmaProjStride = 136; // floats per row of a wave's projection store region (128 units + 8)
+
+#define JITDB_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
+#define JITDB_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
+
+// Waits until at most N of this wave's loads are outstanding and all its LDS operations
+// are done, then meets the block at a barrier.  Written as one asm statement with a memory
+// clobber so that nothing moves across it, and without the fence of __syncthreads(), which
+// would wait for every direct-to-LDS load in flight.
+template <int N>
+__device__ __forceinline__ void dma_wait_barrier() {
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+template <typename T, int MODE, typename Hook>
+__device__ __forceinline__ void dma_gemm(const LevelArgs &a, char *lds, const int *row_node,
+                                         int tile_row0, int col_tile, floatx16 (&acc)[2][4],
+                                         Hook &&after_first_requests) {
+    constexpr int ESZ = (int)sizeof(T);
+    constexpr int NG_X = (MODE == MODE_LEAF) ? 3 : 4;      // gate tiles multiplied in the x part
+    constexpr int NG_H = (MODE == MODE_INTERNAL) ? 3 : 4;  // ... in the h part
+    constexpr int NB = (MODE == MODE_LEAF) ? 3 : 4;        // 16-row B units a wave moves per stage
+    constexpr int NLOAD = 2 + NB;                          // loads per wave and stage
 
     const int t = threadIdx.x;
-    const int lane = t & 63, wave = t >> 6;
+    const int lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int wm = wave >> 1, wn = wave & 1;
     const int hf = lane >> 5, l32 = lane & 31;
+
+    const int n_x = (MODE == MODE_PROJ) ? 0 : a.Dp * ESZ / kDmaStage;
+    const int n_h = (MODE == MODE_LEAF) ? 0 : a.Hp * ESZ / kDmaStage;
+    const int n_stages = n_x + n_h;   // even and >= 2: K is padded to 128 bytes
+
+    // ---- mover: lane l fills slot l&3 of row l>>2 of each 16-row unit it is given
+    const int lrow = lane >> 2;
+    const int piece16 = ((lane & 3) ^ ((lane >> 4) & 3)) * 16;
+    const char *pa[2];
+    int a_lds[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int r = (wave + 4 * i) * 16 + lrow;      // row of the tile
+        a_lds[i] = (wave + 4 * i) * 16 * kDmaStage;
+        if constexpr (MODE == MODE_PROJ) {
+            int g = tile_row0 + r;
+            if (g >= a.n_rows) g = a.n_rows - 1;
+            pa[i] = static_cast<const char *>(a.hs) + (int64_t)row_node[g - tile_row0] * a.Hp * ESZ + piece16;
+        } else {
+            pa[i] = static_cast<const char *>(a.stack) + (int64_t)(tile_row0 + r) * kDmaStage + piece16;
+        }
+    }
+    // bytes from one stage to the next: a slab of A / of B; the projection's A rows are
+    // rows of h in node order, K contiguous
+    const int64_t a_stage = (MODE == MODE_PROJ) ? kDmaStage : (int64_t)a.n_rows_alloc * kDmaStage;
+    const int64_t b_stage = (int64_t)a.NPU * kDmaStage;
+    const char *pb[NB];
+    int b_lds[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        const int idx = wave * NB + i;
+        int lds_row;
+        int64_t src_row;
+        if constexpr (MODE == MODE_PROJ) {
+            // LDS row q*32 + u holds the forget row of unit u of unit tile col_tile*8 + q
+            const int q = idx >> 1;
+            lds_row = q * kUnit + (idx & 1) * 16;
+            src_row = (int64_t)(col_tile * 8 + q) * kGateTile + 3 * kUnit + (idx & 1) * 16 + lrow;
+        } else {
+            // LDS row = packed row within the block's 256; the leaf level skips the forget rows
+            const int ut = idx / (2 * NB), gate = (idx % (2 * NB)) >> 1;
+            lds_row = ut * kGateTile + gate * kUnit + (idx & 1) * 16;
+            src_row = (int64_t)col_tile * kBN + lds_row + lrow;
+        }
+        b_lds[i] = (kDmaBM + lds_row) * kDmaStage;
+        pb[i] = static_cast<const char *>(a.Bp) +
+                operand_offset(src_row, MODE == MODE_PROJ ? (int64_t)a.Dp * ESZ : 0, a.NPU) + piece16;
+    }
+    auto issue = [&](int s, int buf) __attribute__((always_inline)) {
+        char *dst = lds + buf * kDmaBuf;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            __builtin_amdgcn_global_load_lds(JITDB_GLOBAL_PTR(pa[i] + s * a_stage), JITDB_LDS_PTR(dst + a_lds[i]), 16, 0, 0);
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+            __builtin_amdgcn_global_load_lds(JITDB_GLOBAL_PTR(pb[i] + s * b_stage), JITDB_LDS_PTR(dst + b_lds[i]), 16, 0, 0);
+    };
+
+    // ---- fragments: K group h (0, 1) of a stage is pieces 2h (lanes 0-31) and 2h+1 (lanes 32-63)
+    const int sw = (l32 >> 2) & 3;
+    int a_rd[2], b_rd[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int slot16 = ((2 * h + hf) ^ sw) * 16;
+        a_rd[h] = (wm * 64 + l32) * kDmaStage + slot16;
+        b_rd[h] = (kDmaBM + wn * 128 + l32) * kDmaStage + slot16;
+    }
+    // Fragment reads are written as asm: the compiler would otherwise make every LDS read
+    // wait for all direct-to-LDS loads in flight, which it cannot tell apart from the
+    // buffer being read.  The waits for the reads are therefore placed by hand as well
+    // (LDS operations of a wave complete in order).  A K group's fragments: two of A, NG of B.
+    const uint32_t lds_base = (uint32_t)(uintptr_t)JITDB_LDS_PTR(lds);
+    struct Frags {
+        u32x4 a[2], b[4];
+    };
+    auto read_group = [&](int buf, int h, auto ng_tag, Frags &f) __attribute__((always_inline)) {
+        constexpr int NG = decltype(ng_tag)::value;
+        const uint32_t aa = lds_base + buf * kDmaBuf + a_rd[h];
+        const uint32_t bb = lds_base + buf * kDmaBuf + b_rd[h];
+        asm volatile("ds_read_b128 %0, %1" : "=v"(f.a[0]) : "v"(aa) : "memory");
+        asm volatile("ds_read_b128 %0, %1" : "=v"(f.b[0]) : "v"(bb) : "memory");
+        asm volatile("ds_read_b128 %0, %1 offset:2048" : "=v"(f.a[1]) : "v"(aa) : "memory");
+        asm volatile("ds_read_b128 %0, %1 offset:2048" : "=v"(f.b[1]) : "v"(bb) : "memory");
+        asm volatile("ds_read_b128 %0, %1 offset:4096" : "=v"(f.b[2]) : "v"(bb) : "memory");
+        if constexpr (NG == 4)
+            asm volatile("ds_read_b128 %0, %1 offset:6144" : "=v"(f.b[3]) : "v"(bb) : "memory");
+    };
+    // all LDS reads issued so far have arrived; ties the fragments to the wait
+    auto reads_done = [&](auto ng_tag, Frags &f) __attribute__((always_inline)) {
+        constexpr int NG = decltype(ng_tag)::value;
+        if constexpr (NG == 4)
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f.a[0]), "+v"(f.a[1]), "+v"(f.b[0]), "+v"(f.b[1]), "+v"(f.b[2]), "+v"(f.b[3]));
+        else
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f.a[0]), "+v"(f.a[1]), "+v"(f.b[0]), "+v"(f.b[1]), "+v"(f.b[2]));
+    };
+    auto multiply = [&](auto ng_tag, const Frags &f) __attribute__((always_inline)) {
+        constexpr int NG = decltype(ng_tag)::value;
+#pragma unroll
+        for (int m = 0; m < 2 * NG; ++m)
+            mfma_step<T>(f.a[m / NG], f.b[m % NG], acc[m / NG][m % NG]);
+    };
+    const std::integral_constant<int, NG_X> ngx;
+    const std::integral_constant<int, NG_H> ngh;
+
+    // One stage.  On entry P holds K group 0 of stage g (buffer cur).  The reads of K group 1
+    // go out, K group 0 is multiplied; once those reads are back nobody needs buffer cur any
+    // more, and after the barrier (which also publishes stage g+1) it takes the request for
+    // stage g+3.  K group 0 of stage g+1 is then read while K group 1 of stage g is multiplied.
+    Frags P, Q;
+    int cur = 0;
+    auto next_buf = [&]() __attribute__((always_inline)) { return cur == 2 ? 0 : cur + 1; };
+    auto step = [&](int g, auto ng_cur, auto ng_next, auto wait_tag) __attribute__((always_inline)) {
+        constexpr int WAIT = decltype(wait_tag)::value;
+        read_group(cur, 1, ng_cur, Q);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(ng_cur, P);
+        __builtin_amdgcn_sched_barrier(0);
+        reads_done(ng_cur, Q);
+        dma_wait_barrier<WAIT>();
+        read_group(next_buf(), 0, ng_next, P);
+        if (g + 3 < n_stages) issue(g + 3, cur);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(ng_cur, Q);
+        __builtin_amdgcn_sched_barrier(0);
+        reads_done(ng_next, P);
+        cur = next_buf();
+    };
+    const std::integral_constant<int, NLOAD> w_more;   // a younger stage stays in flight
+    const std::integral_constant<int, 0> w_none;
+
+    issue(0, 0);
+    issue(1, 1);
+    if (n_stages > 2) issue(2, 2);
+    after_first_requests();
+    if (n_stages > 2) dma_wait_barrier<2 * NLOAD>(); else dma_wait_barrier<NLOAD>();   // stage 0 is there
+    int g = 0;
+    if constexpr (MODE == MODE_PROJ) {
+        read_group(0, 0, ngh, P);
+        reads_done(ngh, P);
+    } else {
+        read_group(0, 0, ngx, P);
+        reads_done(ngx, P);
+        const int x_end = n_x - 1 < n_stages - 2 ? n_x - 1 : n_stages - 2;
+        for (; g < x_end; ++g) step(g, ngx, ngx, w_more);
+        if constexpr (MODE == MODE_INTERNAL) {   // n_h >= 2, so this stage is not among the last two
+            step(g, ngx, ngh, w_more);
+            ++g;
+        }
+    }
+    if constexpr (MODE == MODE_LEAF) {
+        step(g, ngx, ngx, w_none);
+        read_group(cur, 1, ngx, Q);
+        multiply(ngx, P);
+        reads_done(ngx, Q);
+        multiply(ngx, Q);
+    } else {
+        for (; g < n_stages - 2; ++g) step(g, ngh, ngh, w_more);
+        step(g, ngh, ngh, w_none);
+        read_group(cur, 1, ngh, Q);
+        multiply(ngh, P);
+        reads_done(ngh, Q);
+        multiply(ngh, Q);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    dma_wait_barrier<0>();       // every wave is done reading the stage buffers
+}
+
+#ifdef JITDB_TRACE
+__device__ unsigned long long g_trace[4 << 16];
+#define JITDB_TRACE_MARK(slot) \
+    if (MODE == MODE_INTERNAL && a.n_rows > 400000 && t == 0 && blockIdx.x < (1 << 16)) \
+        g_trace[blockIdx.x * 4 + (slot)] = wall_clock64();
+#else
+#define JITDB_TRACE_MARK(slot)
+#endif
+
+template <typename T, int MODE>
+__global__ void __launch_bounds__(kDmaThreads, 2)
+level_kernel2(const LevelArgs a) {
+    __shared__ __attribute__((aligned(1024))) char lds[kDmaBufs * kDmaBuf];
+    static_assert(4 * 3 * 32 * kEpiStride * 4 <= kDmaBufs * kDmaBuf, "epilogue regions must fit the stage buffers");
+    static_assert(4 * 32 * kDmaProjStride * 4 <= kDmaBufs * kDmaBuf, "projection regions must fit the stage buffers");
+    __shared__ int row_node[kDmaBM];
+    __shared__ int row_ar[kDmaBM];
+    __shared__ int row_cb[kDmaBM];
+    __shared__ int4 row_kid[kDmaBM];
+
+    const int t = threadIdx.x;
+    const int lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
 
     const int logical = xcd_remap(blockIdx.x, a.n_blocks);
     const int row_tile = logical / a.n_col_tiles;
     const int col_tile = logical % a.n_col_tiles;
-    const int tile_row0 = row_tile * kBM;
+    const int tile_row0 = row_tile * kDmaBM;
+#ifdef JITDB_STAGGER
+    if (blockIdx.x >= 256 && blockIdx.x < 512)
+        for (int i = 0; i < JITDB_STAGGER; ++i) __builtin_amdgcn_s_sleep(127);
+#endif
+#ifdef JITDB_TRACE
+    if (MODE == MODE_INTERNAL && a.n_rows > 400000 && t == 0 && blockIdx.x < (1 << 16)) {
+        const unsigned hw = __builtin_amdgcn_s_getreg((4) | (0 << 6) | (31 << 11));      // HW_REG_HW_ID, all 32 bits
+        const unsigned xcc = __builtin_amdgcn_s_getreg((20) | (0 << 6) | (31 << 11));    // HW_REG_XCC_ID
+        g_trace[blockIdx.x * 4 + 3] = ((unsigned long long)xcc << 32) | hw;
+    }
+    JITDB_TRACE_MARK(0)
+#endif
 
-    // Per-row data of the tile: requested now, written to LDS by publish_rows().
     int node_reg = -1;
     int4 rec0 = make_int4(-1, 0, 0, 0), rec1 = make_int4(-1, -1, -1, -1);
-    if (t < kBM && tile_row0 + t < a.n_rows) {
+    if (t < kDmaBM && tile_row0 + t < a.n_rows) {
         if constexpr (MODE == MODE_INTERNAL) {
             rec0 = a.row_rec[2 * (int64_t)(tile_row0 + t)];
             rec1 = a.row_rec[2 * (int64_t)(tile_row0 + t) + 1];
         } else {
-            node_reg = a.level_nodes[tile_row0 + t];
+            node_reg = a.row_rec[2 * (int64_t)(tile_row0 + t)].x;
         }
     }
     auto publish_rows = [&]() __attribute__((always_inline)) {
-        if (t < kBM) {
+        if (t < kDmaBM) {
             if constexpr (MODE == MODE_INTERNAL) {
                 row_node[t] = rec0.x;
                 row_ar[t] = rec0.y;
@@ -683,43 +786,55 @@ level_kernel(const LevelArgs a) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][g][v] = 0.0f;
 
+#ifdef JITDB_ABL_NO_MAIN
+    publish_rows();
+    __syncthreads();
+#else
     if constexpr (MODE == MODE_PROJ) {
-        // the projection gathers its A rows by node id, so the ids must be in LDS first
         publish_rows();
         __syncthreads();
+        dma_gemm<T, MODE>(a, lds, row_node, tile_row0, col_tile, acc, []() {});
+    } else {
+        dma_gemm<T, MODE>(a, lds, row_node, tile_row0, col_tile, acc, publish_rows);
     }
-    if constexpr (MODE == MODE_PROJ)
-        block_gemm<T, MODE>(a, lds, row_node, tile_row0, col_tile, acc, []() {});
-    else
-        block_gemm<T, MODE>(a, lds, row_node, tile_row0, col_tile, acc, publish_rows);
+#endif
+    JITDB_TRACE_MARK(1)
+#ifdef JITDB_ABL_NO_EPI
+    {
+        float sum = 0.f;
+        for (int i = 0; i < 2; ++i) for (int g = 0; g < 4; ++g) for (int v = 0; v < 16; ++v) sum += acc[i][g][v];
+        if (sum == 12345.678f) a.c_out[t] = sum;
+        return;
+    }
+#endif
 
-    // ---- epilogue: accumulator element v of tile (i, g) is row
-    //      wm*64 + i*32 + (v/4)*8 + hf*4 + v%4, column l32 of gate / unit tile g
     if constexpr (MODE == MODE_PROJ) {
-        // P rows leave through LDS too (two passes of 128 rows, fp32 in LDS), so that a
-        // thread stores eight consecutive units of one row: 32 lanes cover 256 units.
-        float *sp = reinterpret_cast<float *>(lds);
+        // Each wave turns its 64 rows x 128 units around in a private LDS region, 32 rows at
+        // a time, so that 16 lanes store one row's 128 units in 8-unit pieces.
+        float *region = reinterpret_cast<float *>(lds) + wave * (32 * kDmaProjStride);
+        const int hf = lane >> 5, l32 = lane & 31;
         T *P = static_cast<T *>(a.P);
-        const int u8 = (t & 31) * 8;
-        const int unit0 = col_tile * 256 + u8;
+        const int u8 = (lane & 15) * 8;
+        const int unit0 = col_tile * 256 + wn * 128 + u8;
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
-            __syncthreads();
 #pragma unroll
             for (int g = 0; g < 4; ++g)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int rl = wm * 32 + (v >> 2) * 8 + hf * 4 + (v & 3);
-                    sp[rl * kProjStride + wn * 128 + g * 32 + l32] = acc[p][g][v];
+                    const int rl = (v >> 2) * 8 + hf * 4 + (v & 3);
+                    region[rl * kDmaProjStride + g * 32 + l32] = acc[p][g][v];
                 }
-            __syncthreads();
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
             for (int sweep = 0; sweep < 8; ++sweep) {
-                const int rl = (t >> 5) + 16 * sweep;
-                const int node = row_node[(rl >> 5) * 64 + p * 32 + (rl & 31)];
+                const int rl = (lane >> 4) + 4 * sweep;
+                const int node = row_node[wm * 64 + p * 32 + rl];
                 if (node < 0 || unit0 >= a.H) continue;
-                const float4 lo = *reinterpret_cast<const float4 *>(sp + rl * kProjStride + u8);
-                const float4 hi = *reinterpret_cast<const float4 *>(sp + rl * kProjStride + u8 + 4);
+                const float4 lo = *reinterpret_cast<const float4 *>(region + rl * kDmaProjStride + u8);
+                const float4 hi = *reinterpret_cast<const float4 *>(region + rl * kDmaProjStride + u8 + 4);
                 const float f[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
                 T *dst = P + (int64_t)node * a.Hq + unit0;
                 if (unit0 + 8 <= a.H) {
@@ -740,15 +855,12 @@ level_kernel(const LevelArgs a) {
                         if (unit0 + j < a.H) dst[j] = from_f32<T>(f[j]);
                 }
             }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         }
     } else {
-        // The cell update runs wave by wave (cell_pass): each wave owns 64 rows x 32 units of
-        // the tile and a private LDS region (the staging buffers are free now), and handles
-        // them in two passes of 32 rows.  Apart from the one barrier that retires the main
-        // loop the waves do not wait for each other, so the arithmetic of one overlaps the
-        // memory latency of the others.
         float *region = reinterpret_cast<float *>(lds) + wave * (3 * 32 * kEpiStride);
-        __syncthreads();   // every wave is done reading the staging buffers
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
             const int r0 = wm * 64 + p * 32;
@@ -756,6 +868,7 @@ level_kernel(const LevelArgs a) {
                                col_tile * 2 + wn, lane);
         }
     }
+    JITDB_TRACE_MARK(2)
 }
 
 // ---- thin levels ---------------------------------------------------------------------
@@ -807,32 +920,36 @@ thin_kernel(const LevelArgs a) {
             s_kid[wave][l32] = r1;
         }
     } else {
-        my_node = a.level_nodes[my_row];
+        my_node = a.row_rec[2 * (int64_t)my_row].x;
         if (hf == 0) s_node[wave][l32] = row_ok ? my_node : -1;
     }
 
     // ---- operand addresses: lane (l32, hf) supplies row l32, bytes [hf*16, +16) of each
     //      32-byte K group, for A and for every B row group alike
-    const int64_t b_row_bytes = (int64_t)(a.Dp + a.Hp) * ESZ;
+    //      K group g is bytes [32 g, 32 g + 32) of a row's K: half of slab g/2 in the K-blocked operands
     const char *ap, *bp;
-    int64_t b_step;
+    int64_t b_step;                           // from one B row group to the next
+    int64_t a_pair, b_pair;                   // from K group g to g + 2
     int n_groups, n_groups_x;                 // K groups in total / with all four gates
     if constexpr (MODE == MODE_PROJ) {
         ap = static_cast<const char *>(a.hs) + (int64_t)my_node * a.Hp * ESZ + hf * 16;
+        a_pair = 64;
         const int64_t row = (int64_t)(col * 4) * kGateTile + 3 * kUnit + l32;
-        bp = static_cast<const char *>(a.Bp) + row * b_row_bytes + (int64_t)a.Dp * ESZ + hf * 16;
-        b_step = (int64_t)kGateTile * b_row_bytes;
+        bp = static_cast<const char *>(a.Bp) + operand_offset(row, (int64_t)a.Dp * ESZ, a.NPU) + hf * 16;
+        b_step = (int64_t)kGateTile * 64;
         n_groups = a.Hp * ESZ / 32;
         n_groups_x = n_groups;
     } else {
         const int64_t a_row_bytes = (int64_t)(a.Dp + (MODE == MODE_INTERNAL ? a.Hp : 0)) * ESZ;
-        ap = static_cast<const char *>(a.stack) + (int64_t)my_row * a_row_bytes + hf * 16;
+        ap = static_cast<const char *>(a.stack) + operand_offset(my_row, 0, a.n_rows_alloc) + hf * 16;
+        a_pair = (int64_t)a.n_rows_alloc * 64;
         const int64_t row = (int64_t)col * kGateTile + l32;
-        bp = static_cast<const char *>(a.Bp) + row * b_row_bytes + hf * 16;
-        b_step = (int64_t)kUnit * b_row_bytes;
+        bp = static_cast<const char *>(a.Bp) + operand_offset(row, 0, a.NPU) + hf * 16;
+        b_step = (int64_t)kUnit * 64;
         n_groups_x = a.Dp * ESZ / 32;
         n_groups = (int)(a_row_bytes / 32);
     }
+    b_pair = (int64_t)a.NPU * 64;
 
     floatx16 acc[4];
 #pragma unroll
@@ -842,8 +959,9 @@ thin_kernel(const LevelArgs a) {
 
     u32x4 fa[kThinAhead], fb[kThinAhead][4];
     auto request = [&](int g, int slot) __attribute__((always_inline)) {
-        const int64_t kb = (int64_t)g * 32;
-        fa[slot] = *reinterpret_cast<const u32x4 *>(ap + kb);
+        const int64_t ka = (int64_t)(g >> 1) * a_pair + (g & 1) * 32;
+        const int64_t kb = (int64_t)(g >> 1) * b_pair + (g & 1) * 32;
+        fa[slot] = *reinterpret_cast<const u32x4 *>(ap + ka);
 #pragma unroll
         for (int q = 0; q < NG_X; ++q) fb[slot][q] = *reinterpret_cast<const u32x4 *>(bp + q * b_step + kb);
     };
@@ -875,7 +993,7 @@ thin_kernel(const LevelArgs a) {
             for (int v = 0; v < 16; ++v) {
                 const int r = row0 + (v >> 2) * 8 + hf * 4 + (v & 3);
                 if (r < a.n_rows) {
-                    const int node = a.level_nodes[r];
+                    const int node = a.row_rec[2 * (int64_t)r].x;
                     P[(int64_t)node * a.Hq + unit] = from_f32<T>(acc[q][v]);
                 }
             }
@@ -955,8 +1073,8 @@ ForwardWs carve_forward_ws(int64_t n, int64_t e, const Dims &d, void *base) {
     w.Bp = c.take<char>((size_t)d.NPU * (d.Dp + d.Hp) * d.esz);
     w.bp = c.take<float>(d.NP);
     // one level at a time; whole row tiles are read, hence the 256 spare rows
-    w.stack = c.take<char>((size_t)(n + kBM) * (d.Dp + d.Hp) * d.esz);
-    w.row_rec = c.take<int4>((size_t)2 * (n + kBM));   // every level position
+    w.stack = c.take<char>((size_t)(n + kRowPad) * (d.Dp + d.Hp) * d.esz);
+    w.row_rec = c.take<int4>((size_t)2 * (n + kRowPad));   // every level position
     w.hs = (d.H == d.Hp) ? nullptr : c.take<char>((size_t)n * d.Hp * d.esz);
     w.P = c.take<char>((size_t)n * d.Hq * d.esz);
     w.cs = (d.H == d.Hq) ? nullptr : c.take<float>((size_t)n * d.Hq);
@@ -991,8 +1109,8 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
 
     {
         ScopedLaunchTimer tm(JITDB_K_PACK, st);
-        row_record_kernel<<<(unsigned)ceil_div(s->n_nodes, kThreads), kThreads, 0, st>>>(
-            s->perm, s->child_ptr, s->child_idx, w.row_rec, (int)s->n_nodes);
+        row_record_kernel<<<(unsigned)ceil_div(s->n_nodes, kRecWindow), kThreads, 0, st>>>(
+            s->perm, s->height, s->child_ptr, s->child_idx, w.row_rec, (int)s->n_nodes);
         JITDB_LAUNCH_CHECK();
     }
 
@@ -1007,14 +1125,15 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
     a.Hq = d.Hq;
     a.hs_out = w.hs ? w.hs : h_out;
     a.D = d.D; a.Dp = d.Dp; a.H = d.H; a.Hp = d.Hp; a.Hu = d.Hu;
+    a.NPU = d.NPU;
 
     for (int l = 0; l < L; ++l) {
         const int n_rows = lp[l + 1] - lp[l];
         if (n_rows <= 0) return JITDB_E_SCHEDULE;
-        a.level_nodes = s->perm + lp[l];
         a.row_rec = w.row_rec + 2 * (int64_t)lp[l];
         a.n_rows = n_rows;
-        const int row_tiles = (int)ceil_div(n_rows, kBM);
+        a.n_rows_alloc = (int)round_up(n_rows, kRowPad);
+        const int row_tiles = (int)ceil_div(n_rows, kDmaBM);
         {   // stack: gather the level's x rows and child sums into one dense matrix
             const int Kp = d.Dp + (l > 0 ? d.Hp : 0);
             const int64_t pieces = (int64_t)n_rows * (Kp / Traits<T>::VEC);
@@ -1023,11 +1142,11 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
             if (l == 0)
                 stack_kernel<T, false><<<grid, kThreads, 0, st>>>(
                     static_cast<const T *>(x), d.D, d.Dp, static_cast<const T *>(a.hs), d.Hp, a.row_rec,
-                    s->child_idx, static_cast<T *>(w.stack), n_rows);
+                    s->child_idx, static_cast<T *>(w.stack), n_rows, a.n_rows_alloc);
             else
                 stack_kernel<T, true><<<grid, kThreads, 0, st>>>(
                     static_cast<const T *>(x), d.D, d.Dp, static_cast<const T *>(a.hs), d.Hp, a.row_rec,
-                    s->child_idx, static_cast<T *>(w.stack), n_rows);
+                    s->child_idx, static_cast<T *>(w.stack), n_rows, a.n_rows_alloc);
             JITDB_LAUNCH_CHECK();
         }
         // Levels too small to give every CU a 256 x 256 tile go to the thin kernel.
@@ -1051,9 +1170,9 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
                     thin_kernel<T, MODE_INTERNAL><<<a.n_blocks, kThinWaves * 64, 0, st>>>(a);
             } else {
                 if (l == 0)
-                    level_kernel<T, MODE_LEAF><<<a.n_blocks, kGemmThreads, 0, st>>>(a);
+                    level_kernel2<T, MODE_LEAF><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
                 else
-                    level_kernel<T, MODE_INTERNAL><<<a.n_blocks, kGemmThreads, 0, st>>>(a);
+                    level_kernel2<T, MODE_INTERNAL><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
             }
         }
         JITDB_LAUNCH_CHECK();
@@ -1067,7 +1186,7 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
             } else {
                 a.n_col_tiles = (int)ceil_div(n_unit_tiles, 8);
                 a.n_blocks = row_tiles * a.n_col_tiles;
-                level_kernel<T, MODE_PROJ><<<a.n_blocks, kGemmThreads, 0, st>>>(a);
+                level_kernel2<T, MODE_PROJ><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
             }
         }
         JITDB_LAUNCH_CHECK();
@@ -1079,6 +1198,12 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
 }  // namespace jitdb
 
 using namespace jitdb;
+
+#ifdef JITDB_TRACE
+extern "C" int jitdb_trace_read(void *host, size_t bytes) {
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), bytes);
+}
+#endif
 
 extern "C" int jitdb_profile_start(int32_t capacity) {
     if (capacity < 1 || capacity > (1 << 20)) return JITDB_E_BADARG;
@@ -1140,7 +1265,7 @@ extern "C" int jitdb_treelstm_forward(const void *x, const void *W, const void *
     if (!dims_ok(n, s->n_edges, D, H, (int)dtype)) return JITDB_E_BADARG;
     if (n == 0) return JITDB_OK;
     if (!x || !W || !U || !b || !h_out || !c_out || !workspace) return JITDB_E_NULL;
-    if (!s->perm || !s->child_ptr || !s->child_idx || !s->host_level_ptr) return JITDB_E_NULL;
+    if (!s->perm || !s->height || !s->child_ptr || !s->child_idx || !s->host_level_ptr) return JITDB_E_NULL;
     if ((reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return JITDB_E_BADARG;
     // rows are fetched in 16-byte pieces where their stride allows
     if ((reinterpret_cast<uintptr_t>(x) & 15) != 0) return JITDB_E_BADARG;
