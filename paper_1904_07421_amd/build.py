@@ -15,7 +15,22 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
+    "-Rpass-analysis=kernel-resource-usage",
 ]
+
+
+def _check_no_scratch(lines) -> None:
+    """No kernel may use scratch memory.  The level kernel issues LDS reads from inline asm
+    and waits for them by hand; a register spill between the read and its wait would store
+    a value that has not arrived yet, so a spilling build is refused rather than run."""
+    name = None
+    for l in lines:
+        if "Function Name:" in l:
+            name = l.split("Function Name:")[1].split("[")[0].strip()
+        elif "ScratchSize [bytes/lane]:" in l:
+            size = int(l.split("ScratchSize [bytes/lane]:")[1].split("[")[0].strip())
+            if size != 0:
+                raise RuntimeError(f"kernel {name} uses {size} bytes/lane of scratch memory (register spill)")
 
 
 def build(verbose: bool = False) -> str:
@@ -27,9 +42,11 @@ def build(verbose: bool = False) -> str:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     # the host pass warns that it does not know the packed-fp32 feature: harmless
-    out = "\n".join(l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l)
+    lines = [l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l]
+    out = "\n".join(l for l in lines if "-Rpass-analysis" not in l)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + out)
+    _check_no_scratch(lines)
     if verbose and out.strip():
         print(out)
     return LIB

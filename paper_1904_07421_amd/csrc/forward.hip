@@ -8,12 +8,15 @@
 //   stack_kernel       row r of the level's input matrix = [x_j | sum_k h_k] over the
 //                      child CSR (the arity-dependent operator; HBM-bound, 16-byte
 //                      coalesced row pieces)
-//   level_kernel<GATES>   [x_j ; hs_j] x [W ; U]^T on MFMA with the whole cell
+//   level_kernel<LEAF|INTERNAL>   [x_j ; hs_j] x [W ; U]^T on MFMA with the whole cell
 //                      fused into the epilogue: per-child forget gates from the
 //                      precomputed P_k = U_f h_k, c_j and h_j written once
 //   level_kernel<PROJ> P_k = U_f h_k for the nodes just produced, so that their
 //                      parent reads one row per child (every non-root node is a
 //                      child exactly once)
+//   thin_kernel        the same three jobs for levels too small to fill the chip with
+//                      128 x 256 tiles: one 32 x 32-unit tile per wave, operands straight
+//                      from L2
 //
 // "Stack" is the row gather through perm (level-major order) done by
 // stack_kernel, "slice" is the scatter of rows back to node-id order in the
@@ -51,7 +54,7 @@ enum : int { MODE_LEAF = 0, MODE_INTERNAL = 1, MODE_PROJ = 2 };
 
 template <typename T> struct Traits;
 template <> struct Traits<float> {
-    static constexpr int BK = 32;   // elements of K per stage (128 bytes)
+    static constexpr int BK = 32;   // K is padded to multiples of this: 128 bytes, two pipeline stages
     static constexpr int VEC = 4;   // elements per 16 bytes
 };
 template <> struct Traits<bf16_t> {
@@ -498,14 +501,24 @@ __device__ __forceinline__ void cell_pass(const LevelArgs &a, const floatx16 (&a
     }
 }
 
-// ---- the level GEMM, two blocks per CU --------------------------------------------------
-// Same tile arithmetic as block_gemm (wave tile 64 rows x 128 packed columns, cell update in
-// the epilogue), organised so that two blocks share a CU: while one block is in its
-// memory-bound epilogue or start-up the matrix cores work for the other.  That needs half
-// the LDS and registers per block: 128 rows x 256 packed columns per block of four waves,
-// and K stages of 64 bytes per row that travel from global memory straight into LDS
-// (global_load_lds, 16 bytes per lane) without passing through registers.  Three stage
-// buffers: stage g is multiplied while g+1 and g+2 are in flight; one barrier per stage.
+// ---- the level GEMM ------------------------------------------------------------------
+// One block of four waves computes 128 rows x 256 packed columns (2 unit tiles x 4 gates x
+// 32 units); each wave a 64 x 128 sub-tile, i.e. 2 x 4 MFMA tiles of 32 x 32, so that all
+// four gates of a hidden unit end up in one wave's accumulators.  Two blocks share a CU
+// (half the LDS and at most 256 registers each): the start-up and the memory-bound cell
+// update of one leave the matrix cores to the other.
+//
+// A is the level's stacked input [x | hsum], B the packed [W | U]; K runs over stages of
+// 64 bytes per row, n_x stages of the x part, then n_h of the h part, in which the forget
+// gate is skipped (U_f applies to each child's own h, not to the sum).  The projection
+// instead reads A rows from h by node id and uses only the U part of the forget rows.
+// Stages travel from global memory straight into LDS (global_load_lds, 16 bytes per lane)
+// without passing through registers.  Three stage buffers: while stage g is multiplied,
+// g+1 and g+2 (and for half the time g+3) are in flight; one barrier per stage.
+//
+// In each 16-wide (bf16) or 8-wide (fp32) K group, lanes 0-31 take the first 16 bytes and
+// lanes 32-63 the next 16 for A and B alike; since the same assignment is used on both
+// operands any such split of K is a valid MFMA schedule.
 //
 // A direct load writes the 64 lanes' pieces to 1024 consecutive LDS bytes, i.e. 16 rows of
 // 64 bytes with no room for padding, so bank conflicts are avoided by permuting the four
@@ -534,7 +547,7 @@ __device__ __forceinline__ void dma_wait_barrier() {
 template <typename T, int MODE, typename Hook>
 __device__ __forceinline__ void dma_gemm(const LevelArgs &a, char *lds, const int *row_node,
                                          int tile_row0, int col_tile, floatx16 (&acc)[2][4],
-                                         Hook &&after_first_requests) {
+                                         char *sink, Hook &&after_first_requests) {
     constexpr int ESZ = (int)sizeof(T);
     constexpr int NG_X = (MODE == MODE_LEAF) ? 3 : 4;      // gate tiles multiplied in the x part
     constexpr int NG_H = (MODE == MODE_INTERNAL) ? 3 : 4;  // ... in the h part
@@ -594,6 +607,14 @@ __device__ __forceinline__ void dma_gemm(const LevelArgs &a, char *lds, const in
         pb[i] = static_cast<const char *>(a.Bp) +
                 operand_offset(src_row, MODE == MODE_PROJ ? (int64_t)a.Dp * ESZ : 0, a.NPU) + piece16;
     }
+    // load i (0 .. NLOAD-1) of stage s
+    auto issue_one = [&](int s, int buf, int i) __attribute__((always_inline)) {
+        char *dst = lds + buf * kDmaBuf;
+        if (i < 2)
+            __builtin_amdgcn_global_load_lds(JITDB_GLOBAL_PTR(pa[i] + s * a_stage), JITDB_LDS_PTR(dst + a_lds[i]), 16, 0, 0);
+        else
+            __builtin_amdgcn_global_load_lds(JITDB_GLOBAL_PTR(pb[i - 2] + s * b_stage), JITDB_LDS_PTR(dst + b_lds[i - 2]), 16, 0, 0);
+    };
     auto issue = [&](int s, int buf) __attribute__((always_inline)) {
         char *dst = lds + buf * kDmaBuf;
 #pragma unroll
@@ -647,6 +668,21 @@ __device__ __forceinline__ void dma_gemm(const LevelArgs &a, char *lds, const in
         for (int m = 0; m < 2 * NG; ++m)
             mfma_step<T>(f.a[m / NG], f.b[m % NG], acc[m / NG][m % NG]);
     };
+    // The same with the loads of stage s dealt out between the MFMAs, one after each: a
+    // wave issues in order, and a burst of loads in front of the MFMAs would hold them back
+    // until the memory pipeline has taken the loads of all waves of the CU.
+    // (The condition wraps each load, not the MFMAs: accumulators that meet again after
+    // a branch get copied.)
+    auto multiply_and_issue = [&](auto ng_tag, const Frags &f, int s, int buf, bool wanted) __attribute__((always_inline)) {
+        constexpr int NG = decltype(ng_tag)::value;
+#pragma unroll
+        for (int m = 0; m < 2 * NG; ++m) {
+            mfma_step<T>(f.a[m / NG], f.b[m % NG], acc[m / NG][m % NG]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (m < NLOAD && wanted) issue_one(s, buf, m);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
     const std::integral_constant<int, NG_X> ngx;
     const std::integral_constant<int, NG_H> ngh;
 
@@ -666,9 +702,8 @@ __device__ __forceinline__ void dma_gemm(const LevelArgs &a, char *lds, const in
         reads_done(ng_cur, Q);
         dma_wait_barrier<WAIT>();
         read_group(next_buf(), 0, ng_next, P);
-        if (g + 3 < n_stages) issue(g + 3, cur);
         __builtin_amdgcn_sched_barrier(0);
-        multiply(ng_cur, Q);
+        multiply_and_issue(ng_cur, Q, g + 3, cur, g + 3 < n_stages);
         __builtin_amdgcn_sched_barrier(0);
         reads_done(ng_next, P);
         cur = next_buf();
@@ -676,6 +711,20 @@ __device__ __forceinline__ void dma_gemm(const LevelArgs &a, char *lds, const in
     const std::integral_constant<int, NLOAD> w_more;   // a younger stage stays in flight
     const std::integral_constant<int, 0> w_none;
 
+    // Warm L2 with the block's share of its A tile, one 4-byte load per 128-byte line (the
+    // data goes to a sink): the stage loads further down the K loop then find their lines
+    // in L2 instead of each waiting for HBM with only two stages of lookahead.  The blocks
+    // of all column tiles of a row tile run side by side on one XCD and split the lines.
+    if constexpr (MODE != MODE_PROJ) {
+        char *sink_w = sink + wave * 256;
+        const int n_lines = n_stages * (kDmaBM * kDmaStage / 128);
+        const char *tile = static_cast<const char *>(a.stack) + (int64_t)tile_row0 * kDmaStage;
+        for (int li = col_tile + a.n_col_tiles * t; li < n_lines; li += a.n_col_tiles * kDmaThreads) {
+            const int slab = li >> 6, line = li & 63;
+            __builtin_amdgcn_global_load_lds(JITDB_GLOBAL_PTR(tile + slab * a_stage + line * 128),
+                                             JITDB_LDS_PTR(sink_w), 4, 0, 0);
+        }
+    }
     issue(0, 0);
     issue(1, 1);
     if (n_stages > 2) issue(2, 2);
@@ -713,18 +762,9 @@ __device__ __forceinline__ void dma_gemm(const LevelArgs &a, char *lds, const in
     dma_wait_barrier<0>();       // every wave is done reading the stage buffers
 }
 
-#ifdef JITDB_TRACE
-__device__ unsigned long long g_trace[4 << 16];
-#define JITDB_TRACE_MARK(slot) \
-    if (MODE == MODE_INTERNAL && a.n_rows > 400000 && t == 0 && blockIdx.x < (1 << 16)) \
-        g_trace[blockIdx.x * 4 + (slot)] = wall_clock64();
-#else
-#define JITDB_TRACE_MARK(slot)
-#endif
-
 template <typename T, int MODE>
 __global__ void __launch_bounds__(kDmaThreads, 2)
-level_kernel2(const LevelArgs a) {
+level_kernel(const LevelArgs a) {
     __shared__ __attribute__((aligned(1024))) char lds[kDmaBufs * kDmaBuf];
     static_assert(4 * 3 * 32 * kEpiStride * 4 <= kDmaBufs * kDmaBuf, "epilogue regions must fit the stage buffers");
     static_assert(4 * 32 * kDmaProjStride * 4 <= kDmaBufs * kDmaBuf, "projection regions must fit the stage buffers");
@@ -732,6 +772,7 @@ level_kernel2(const LevelArgs a) {
     __shared__ int row_ar[kDmaBM];
     __shared__ int row_cb[kDmaBM];
     __shared__ int4 row_kid[kDmaBM];
+    __shared__ __attribute__((aligned(256))) char sink[4 * 256];   // where the L2 warm-up loads end up
 
     const int t = threadIdx.x;
     const int lane = t & 63;
@@ -742,18 +783,6 @@ level_kernel2(const LevelArgs a) {
     const int row_tile = logical / a.n_col_tiles;
     const int col_tile = logical % a.n_col_tiles;
     const int tile_row0 = row_tile * kDmaBM;
-#ifdef JITDB_STAGGER
-    if (blockIdx.x >= 256 && blockIdx.x < 512)
-        for (int i = 0; i < JITDB_STAGGER; ++i) __builtin_amdgcn_s_sleep(127);
-#endif
-#ifdef JITDB_TRACE
-    if (MODE == MODE_INTERNAL && a.n_rows > 400000 && t == 0 && blockIdx.x < (1 << 16)) {
-        const unsigned hw = __builtin_amdgcn_s_getreg((4) | (0 << 6) | (31 << 11));      // HW_REG_HW_ID, all 32 bits
-        const unsigned xcc = __builtin_amdgcn_s_getreg((20) | (0 << 6) | (31 << 11));    // HW_REG_XCC_ID
-        g_trace[blockIdx.x * 4 + 3] = ((unsigned long long)xcc << 32) | hw;
-    }
-    JITDB_TRACE_MARK(0)
-#endif
 
     int node_reg = -1;
     int4 rec0 = make_int4(-1, 0, 0, 0), rec1 = make_int4(-1, -1, -1, -1);
@@ -786,27 +815,13 @@ level_kernel2(const LevelArgs a) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][g][v] = 0.0f;
 
-#ifdef JITDB_ABL_NO_MAIN
-    publish_rows();
-    __syncthreads();
-#else
     if constexpr (MODE == MODE_PROJ) {
         publish_rows();
         __syncthreads();
-        dma_gemm<T, MODE>(a, lds, row_node, tile_row0, col_tile, acc, []() {});
+        dma_gemm<T, MODE>(a, lds, row_node, tile_row0, col_tile, acc, sink, []() {});
     } else {
-        dma_gemm<T, MODE>(a, lds, row_node, tile_row0, col_tile, acc, publish_rows);
+        dma_gemm<T, MODE>(a, lds, row_node, tile_row0, col_tile, acc, sink, publish_rows);
     }
-#endif
-    JITDB_TRACE_MARK(1)
-#ifdef JITDB_ABL_NO_EPI
-    {
-        float sum = 0.f;
-        for (int i = 0; i < 2; ++i) for (int g = 0; g < 4; ++g) for (int v = 0; v < 16; ++v) sum += acc[i][g][v];
-        if (sum == 12345.678f) a.c_out[t] = sum;
-        return;
-    }
-#endif
 
     if constexpr (MODE == MODE_PROJ) {
         // Each wave turns its 64 rows x 128 units around in a private LDS region, 32 rows at
@@ -868,7 +883,6 @@ level_kernel2(const LevelArgs a) {
                                col_tile * 2 + wn, lane);
         }
     }
-    JITDB_TRACE_MARK(2)
 }
 
 // ---- thin levels ---------------------------------------------------------------------
@@ -880,10 +894,7 @@ level_kernel2(const LevelArgs a) {
 // L2 in fragment layout (16 bytes per lane, no LDS staging, four K groups requested
 // ahead), and finishes with the same cell_pass.  Waves never wait for each other.
 constexpr int kThinWaves = 4;     // waves (tiles) per block
-#ifndef JITDB_THIN_MAX_ROWS
-#define JITDB_THIN_MAX_ROWS 8192
-#endif
-constexpr int kThinMaxRows = JITDB_THIN_MAX_ROWS; // levels up to this many rows use the thin kernel
+constexpr int kThinMaxRows = 8192; // levels up to this many rows use the thin kernel
 constexpr int kThinAhead = 4;     // K groups in flight per wave
 
 template <typename T, int MODE>
@@ -1170,9 +1181,9 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
                     thin_kernel<T, MODE_INTERNAL><<<a.n_blocks, kThinWaves * 64, 0, st>>>(a);
             } else {
                 if (l == 0)
-                    level_kernel2<T, MODE_LEAF><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
+                    level_kernel<T, MODE_LEAF><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
                 else
-                    level_kernel2<T, MODE_INTERNAL><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
+                    level_kernel<T, MODE_INTERNAL><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
             }
         }
         JITDB_LAUNCH_CHECK();
@@ -1186,7 +1197,7 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
             } else {
                 a.n_col_tiles = (int)ceil_div(n_unit_tiles, 8);
                 a.n_blocks = row_tiles * a.n_col_tiles;
-                level_kernel2<T, MODE_PROJ><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
+                level_kernel<T, MODE_PROJ><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
             }
         }
         JITDB_LAUNCH_CHECK();
@@ -1199,11 +1210,6 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
 
 using namespace jitdb;
 
-#ifdef JITDB_TRACE
-extern "C" int jitdb_trace_read(void *host, size_t bytes) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), bytes);
-}
-#endif
 
 extern "C" int jitdb_profile_start(int32_t capacity) {
     if (capacity < 1 || capacity > (1 << 20)) return JITDB_E_BADARG;
