@@ -157,24 +157,29 @@ def main():
     ms_fwd = timed(lambda: J.jitdb_treelstm_forward(xt, Wt, Ut, bt, sched, stream=stream,
                                                      workspace=ws_f, out=(h, c)), reps)
 
-    # algorithmic work per step and per kernel class (padding and unused rows do not count)
-    flops = {
-        "leaf": n_leaf * 2.0 * D * 3 * H,
-        "internal": n_int * (2.0 * D * 4 * H + 2.0 * H * 3 * H),
-        "proj": E * 2.0 * H * H,
-    }
+    # algorithmic work per step and per kernel class (padding and unused rows do not count);
+    # the library reports how many level rows each class of launches covered
+    flops_row = {"leaf": 2.0 * D * 3 * H, "internal": 2.0 * D * 4 * H + 2.0 * H * 3 * H, "proj": 2.0 * H * H}
+    flops_total = {"leaf": n_leaf * flops_row["leaf"], "internal": n_int * flops_row["internal"],
+                   "proj": E * flops_row["proj"]}
     # stack step: reads every x row and every child's h row once, writes the stacked rows
     bytes_stack = (2 * N * D + E * H + n_int * H) * esz
     kernels = {}
     roof = None
     if prof is not None:
-        for name in ("leaf", "internal", "proj"):
+        proj_rows = (prof["proj"]["rows"] + prof["thin_proj"]["rows"]) / args.steps   # includes roots, whose P nobody reads
+        for name in ("leaf", "internal", "proj", "thin_leaf", "thin_internal", "thin_proj"):
+            job = name.replace("thin_", "")
             ms = prof[name]["ms"] / args.steps
             n_l = prof[name]["launches"] / args.steps
+            rows = prof[name]["rows"] / args.steps
+            fl = rows * flops_row[job]
+            if job == "proj" and proj_rows > 0:
+                fl *= E / proj_rows
             if ms > 0:
-                kernels[name] = {"ms_per_step": ms, "launches_per_step": n_l,
-                                 "tflops": flops[name] / (ms * 1e-3) / 1e12,
-                                 "frac_mfma_peak": flops[name] / (ms * 1e-3) / 1e12 / peak_tflops}
+                kernels[name] = {"ms_per_step": ms, "launches_per_step": n_l, "rows_per_step": rows,
+                                 "flops_per_step": fl, "tflops": fl / (ms * 1e-3) / 1e12,
+                                 "frac_mfma_peak": fl / (ms * 1e-3) / 1e12 / peak_tflops}
         ms = prof["stack"]["ms"] / args.steps
         if ms > 0:
             kernels["stack"] = {"ms_per_step": ms,
@@ -182,15 +187,18 @@ def main():
                                 "gbs": bytes_stack / (ms * 1e-3) / 1e9,
                                 "frac_hbm_peak": bytes_stack / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
         kernels["pack"] = {"ms_per_step": prof["pack"]["ms"] / args.steps}
-        dom = max(("leaf", "internal", "proj"), key=lambda k: kernels.get(k, {}).get("ms_per_step", 0.0))
+        mfma_names = [n for n in ("leaf", "internal", "proj", "thin_leaf", "thin_internal", "thin_proj") if n in kernels]
+        dom = max(mfma_names, key=lambda k: kernels[k]["ms_per_step"])
         k = kernels[dom]
-        roof = {"kernel": f"level_kernel<{cfg.dtype},{dom}>", "bound": "mfma",
+        kname = (f"thin_kernel<{cfg.dtype},{dom[5:]}>" if dom.startswith("thin_") else f"level_kernel<{cfg.dtype},{dom}>")
+        roof = {"kernel": kname, "bound": "mfma",
                 "achieved": k["tflops"], "peak": peak_tflops, "unit": "TFLOP/s",
                 "frac": k["frac_mfma_peak"], "traffic": measured_traffic(cfg, dom),
                 "avg_launch_ms": k["ms_per_step"] / max(k["launches_per_step"], 1),
-                "flops_per_step": flops[dom], "dropped_events": prof["dropped"]}
-        mfma_ms = sum(kernels[n]["ms_per_step"] for n in ("leaf", "internal", "proj") if n in kernels)
-        roof["all_mfma_kernels_frac"] = sum(flops.values()) / (mfma_ms * 1e-3) / 1e12 / peak_tflops
+                "flops_per_launch": k["flops_per_step"] / max(k["launches_per_step"], 1),
+                "flops_per_step": k["flops_per_step"], "dropped_events": prof["dropped"]}
+        mfma_ms = sum(kernels[n]["ms_per_step"] for n in mfma_names)
+        roof["all_mfma_kernels_frac"] = sum(flops_total.values()) / (mfma_ms * 1e-3) / 1e12 / peak_tflops
 
     out = {
         "metric": "Tree-LSTM forward nodes/sec on 1 MI355X",

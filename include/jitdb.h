@@ -161,15 +161,19 @@ int jitdb_treelstm_forward(const void *x, const void *W, const void *U, const fl
 typedef enum {
     JITDB_K_PACK = 0,       /* once per call: weight re-packing, row records */
     JITDB_K_STACK = 1,      /* stack: row = [x_j | sum_k h_k] per level */
-    JITDB_K_LEAF = 2,       /* leaf level: W x + cell */
-    JITDB_K_INTERNAL = 3,   /* internal levels: [x;hs][W;U] + cell with per-child forget gates */
-    JITDB_K_PROJ = 4,       /* P_k = U_f h_k */
-    JITDB_K_CLASSES = 5
+    JITDB_K_LEAF = 2,       /* leaf level: W x + cell (tiled kernel) */
+    JITDB_K_INTERNAL = 3,   /* internal levels: [x;hs][W;U] + cell with per-child forget gates (tiled kernel) */
+    JITDB_K_PROJ = 4,       /* P_k = U_f h_k (tiled kernel) */
+    JITDB_K_THIN_LEAF = 5,      /* the same three jobs done by the kernel for small levels */
+    JITDB_K_THIN_INTERNAL = 6,
+    JITDB_K_THIN_PROJ = 7,
+    JITDB_K_CLASSES = 8
 } jitdb_kernel_class;
 
 typedef struct {
     double ms[JITDB_K_CLASSES];        /* summed event time per class, milliseconds */
     int64_t launches[JITDB_K_CLASSES]; /* recorded launches per class */
+    int64_t rows[JITDB_K_CLASSES];     /* level rows (nodes) those launches covered; 0 for PACK */
     int64_t dropped;                   /* launches that found no free event pair */
 } jitdb_profile_t;
 

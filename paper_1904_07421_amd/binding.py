@@ -43,12 +43,12 @@ class _ScheduleStruct(ctypes.Structure):
     ]
 
 
-K_CLASSES = ("pack", "stack", "leaf", "internal", "proj")
+K_CLASSES = ("pack", "stack", "leaf", "internal", "proj", "thin_leaf", "thin_internal", "thin_proj")
 
 
 class _ProfileStruct(ctypes.Structure):
-    _fields_ = [("ms", ctypes.c_double * 5), ("launches", ctypes.c_int64 * 5),
-                ("dropped", ctypes.c_int64)]
+    _fields_ = [("ms", ctypes.c_double * 8), ("launches", ctypes.c_int64 * 8),
+                ("rows", ctypes.c_int64 * 8), ("dropped", ctypes.c_int64)]
 
 
 _lib = None
@@ -108,10 +108,10 @@ def jitdb_profile_start(capacity: int) -> None:
 
 
 def jitdb_profile_stop() -> dict:
-    """{class: {"ms": total milliseconds, "launches": count}} plus "dropped"."""
+    """{class: {"ms": total milliseconds, "launches": count, "rows": level rows covered}} plus "dropped"."""
     p = _ProfileStruct()
     _check(load_library().jitdb_profile_stop(ctypes.byref(p)))
-    out = {name: {"ms": float(p.ms[i]), "launches": int(p.launches[i])}
+    out = {name: {"ms": float(p.ms[i]), "launches": int(p.launches[i]), "rows": int(p.rows[i])}
            for i, name in enumerate(K_CLASSES)}
     out["dropped"] = int(p.dropped)
     return out

@@ -315,17 +315,32 @@ struct LevelArgs {
     int n_rows;
     int n_rows_alloc;     // rows per slab of the stacked input (n_rows rounded up to whole tiles)
     int NPU;              // rows per slab of the packed weights
+    int n_row_tiles;      // level kernel: tiles along the row axis
     int n_col_tiles;      // tiles along the column axis
     int n_tiles;          // thin kernel: number of wave tiles
     int n_blocks;
 };
 
-// Spread consecutive block ids (which the hardware deals round-robin to the 8
-// XCDs) so that blocks sharing an A row tile land on the same XCD and L2.
-__device__ __forceinline__ int xcd_remap(int b, int nb) {
+// Block id -> tile of the level kernel.  The hardware deals consecutive block ids
+// round-robin to the 8 XCDs, each with its own L2.  Row tile r belongs to XCD r % 8, so
+// that the blocks of all its column tiles read the same A rows through one L2.  Inside an
+// XCD the column tiles are taken in groups of kColGroup: the XCD sweeps all its row tiles
+// with one group of columns, then with the next, which bounds the B rows in use at a
+// time; A is fetched once per group.  (With 8 column tiles, H = 512, one group measured
+// faster than two: re-reading A costs more than the B rows that fall out of L2.)  The
+// grid holds 8 * ceil(R / 8) * C blocks; blocks past an XCD's share return at once.
+constexpr int kColGroup = 8;
+__device__ __forceinline__ bool block_to_tile(int b, int n_row_tiles, int n_col_tiles, int &row_tile, int &col_tile) {
     const int xcd = b & 7, idx = b >> 3;
-    const int q = nb >> 3, r = nb & 7;
-    return xcd * q + (xcd < r ? xcd : r) + idx;
+    const int rows_x = (n_row_tiles - xcd + 7) >> 3;        // row tiles of this XCD
+    if (idx >= rows_x * n_col_tiles) return false;
+    const int g = idx / (rows_x * kColGroup);
+    const int rem = idx - g * rows_x * kColGroup;
+    const int left = n_col_tiles - g * kColGroup;
+    const int cg = left < kColGroup ? left : kColGroup;    // columns in this group
+    row_tile = xcd + 8 * (rem / cg);
+    col_tile = g * kColGroup + rem % cg;
+    return true;
 }
 
 template <typename T>
@@ -714,12 +729,14 @@ __device__ __forceinline__ void dma_gemm(const LevelArgs &a, char *lds, const in
     // Warm L2 with the block's share of its A tile, one 4-byte load per 128-byte line (the
     // data goes to a sink): the stage loads further down the K loop then find their lines
     // in L2 instead of each waiting for HBM with only two stages of lookahead.  The blocks
-    // of all column tiles of a row tile run side by side on one XCD and split the lines.
+    // of one column group of a row tile run side by side on one XCD and split the lines.
     if constexpr (MODE != MODE_PROJ) {
         char *sink_w = sink + wave * 256;
         const int n_lines = n_stages * (kDmaBM * kDmaStage / 128);
         const char *tile = static_cast<const char *>(a.stack) + (int64_t)tile_row0 * kDmaStage;
-        for (int li = col_tile + a.n_col_tiles * t; li < n_lines; li += a.n_col_tiles * kDmaThreads) {
+        const int left = a.n_col_tiles - (col_tile / kColGroup) * kColGroup;
+        const int sharers = left < kColGroup ? left : kColGroup;
+        for (int li = col_tile % kColGroup + sharers * t; li < n_lines; li += sharers * kDmaThreads) {
             const int slab = li >> 6, line = li & 63;
             __builtin_amdgcn_global_load_lds(JITDB_GLOBAL_PTR(tile + slab * a_stage + line * 128),
                                              JITDB_LDS_PTR(sink_w), 4, 0, 0);
@@ -779,9 +796,8 @@ level_kernel(const LevelArgs a) {
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int wm = wave >> 1, wn = wave & 1;
 
-    const int logical = xcd_remap(blockIdx.x, a.n_blocks);
-    const int row_tile = logical / a.n_col_tiles;
-    const int col_tile = logical % a.n_col_tiles;
+    int row_tile, col_tile;
+    if (!block_to_tile(blockIdx.x, a.n_row_tiles, a.n_col_tiles, row_tile, col_tile)) return;
     const int tile_row0 = row_tile * kDmaBM;
 
     int node_reg = -1;
@@ -886,34 +902,38 @@ level_kernel(const LevelArgs a) {
 }
 
 // ---- thin levels ---------------------------------------------------------------------
-// A level with a few thousand rows gives the 256 x 256 tiles too few blocks to fill 256
-// CUs, and each block then runs one wave's whole K loop back to back: the level costs that
-// latency, not its work.  thin_kernel spreads such a level over many more waves.  Every
-// wave owns one tile of 32 rows x 32 hidden units (all four gates; the projection: 32 rows
-// x 4 unit tiles of forget rows), takes its MFMA operands straight from global memory /
-// L2 in fragment layout (16 bytes per lane, no LDS staging, four K groups requested
-// ahead), and finishes with the same cell_pass.  Waves never wait for each other.
-constexpr int kThinWaves = 4;     // waves (tiles) per block
+// A level with a few thousand rows gives the 128 x 256 tiles too few blocks to fill 256
+// CUs, and each block then runs a whole K loop back to back: the level costs that
+// latency, not its work.  thin_kernel spreads such a level over many more waves.  A block
+// of four waves owns one tile of 32 rows x 32 hidden units; wave g multiplies gate g (the
+// projection: wave g one of four unit tiles of forget rows), taking its MFMA operands
+// straight from global memory / L2 in fragment layout (16 bytes per lane, no LDS staging,
+// kThinAhead K groups requested ahead), so the K loop of a tile is a quarter as long as
+// with one wave per tile.  The gates meet in LDS and wave 0 finishes with the same
+// cell_pass.  One block barrier, none in the K loop.
+constexpr int kThinWaves = 4;
 constexpr int kThinMaxRows = 8192; // levels up to this many rows use the thin kernel
-constexpr int kThinAhead = 4;     // K groups in flight per wave
+constexpr int kThinAhead = 8;      // K groups in flight per wave
 
 template <typename T, int MODE>
 __global__ void __launch_bounds__(kThinWaves * 64, 2)
 thin_kernel(const LevelArgs a) {
     constexpr int ESZ = (int)sizeof(T);
-    constexpr int NG_X = (MODE == MODE_LEAF) ? 3 : 4;
-    __shared__ __attribute__((aligned(16))) float regions[kThinWaves][3 * 32 * kEpiStride];
-    __shared__ int s_node[kThinWaves][32];
-    __shared__ int s_ar[kThinWaves][32];
-    __shared__ int s_cb[kThinWaves][32];
-    __shared__ int4 s_kid[kThinWaves][32];
+    __shared__ __attribute__((aligned(16))) float region[3 * 32 * kEpiStride];
+    __shared__ __attribute__((aligned(16))) float exchange[3][16][64];   // accumulators of waves 1-3
+    __shared__ int s_node[32];
+    __shared__ int s_ar[32];
+    __shared__ int s_cb[32];
+    __shared__ int4 s_kid[32];
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int hf = lane >> 5, l32 = lane & 31;
-    const int tile = blockIdx.x * kThinWaves + wave;
-    if (tile >= a.n_tiles) return;            // whole waves leave; there is no block barrier below
+    const int tile = blockIdx.x;
     const int row0 = (tile / a.n_col_tiles) * 32;
     const int col = tile % a.n_col_tiles;     // unit tile (gates) or group of four unit tiles (projection)
+    if (MODE == MODE_LEAF && wave == 3) return;                                   // leaves have no forget gate
+    if (MODE == MODE_PROJ && (col * 4 + wave) * kUnit >= a.Hu) return;            // past the last unit tile
 
     // ---- the tile's rows
     int my_row = row0 + l32;
@@ -922,43 +942,38 @@ thin_kernel(const LevelArgs a) {
     int my_node;
     if constexpr (MODE == MODE_INTERNAL) {
         const int4 r0 = a.row_rec[2 * (int64_t)my_row];
-        const int4 r1 = a.row_rec[2 * (int64_t)my_row + 1];
         my_node = r0.x;
-        if (hf == 0) {
-            s_node[wave][l32] = row_ok ? r0.x : -1;
-            s_ar[wave][l32] = row_ok ? r0.y : 0;
-            s_cb[wave][l32] = r0.z;
-            s_kid[wave][l32] = r1;
+        if (wave == 0 && hf == 0) {
+            const int4 r1 = a.row_rec[2 * (int64_t)my_row + 1];
+            s_node[l32] = row_ok ? r0.x : -1;
+            s_ar[l32] = row_ok ? r0.y : 0;
+            s_cb[l32] = r0.z;
+            s_kid[l32] = r1;
         }
     } else {
         my_node = a.row_rec[2 * (int64_t)my_row].x;
-        if (hf == 0) s_node[wave][l32] = row_ok ? my_node : -1;
+        if (wave == 0 && hf == 0) s_node[l32] = row_ok ? my_node : -1;
     }
 
     // ---- operand addresses: lane (l32, hf) supplies row l32, bytes [hf*16, +16) of each
-    //      32-byte K group, for A and for every B row group alike
-    //      K group g is bytes [32 g, 32 g + 32) of a row's K: half of slab g/2 in the K-blocked operands
+    //      32-byte K group, for A and B alike.  K group g is bytes [32 g, 32 g + 32) of a
+    //      row's K: half of slab g/2 in the K-blocked operands.
     const char *ap, *bp;
-    int64_t b_step;                           // from one B row group to the next
     int64_t a_pair, b_pair;                   // from K group g to g + 2
-    int n_groups, n_groups_x;                 // K groups in total / with all four gates
+    int n_groups;                             // K groups this wave multiplies
     if constexpr (MODE == MODE_PROJ) {
         ap = static_cast<const char *>(a.hs) + (int64_t)my_node * a.Hp * ESZ + hf * 16;
         a_pair = 64;
-        const int64_t row = (int64_t)(col * 4) * kGateTile + 3 * kUnit + l32;
+        const int64_t row = (int64_t)(col * 4 + wave) * kGateTile + 3 * kUnit + l32;
         bp = static_cast<const char *>(a.Bp) + operand_offset(row, (int64_t)a.Dp * ESZ, a.NPU) + hf * 16;
-        b_step = (int64_t)kGateTile * 64;
         n_groups = a.Hp * ESZ / 32;
-        n_groups_x = n_groups;
     } else {
-        const int64_t a_row_bytes = (int64_t)(a.Dp + (MODE == MODE_INTERNAL ? a.Hp : 0)) * ESZ;
         ap = static_cast<const char *>(a.stack) + operand_offset(my_row, 0, a.n_rows_alloc) + hf * 16;
         a_pair = (int64_t)a.n_rows_alloc * 64;
-        const int64_t row = (int64_t)col * kGateTile + l32;
+        const int64_t row = (int64_t)col * kGateTile + wave * kUnit + l32;
         bp = static_cast<const char *>(a.Bp) + operand_offset(row, 0, a.NPU) + hf * 16;
-        b_step = (int64_t)kUnit * 64;
-        n_groups_x = a.Dp * ESZ / 32;
-        n_groups = (int)(a_row_bytes / 32);
+        // the forget rows take part in the x part only (U_f applies to each child's own h)
+        n_groups = (a.Dp + (MODE == MODE_INTERNAL && wave != 3 ? a.Hp : 0)) * ESZ / 32;
     }
     b_pair = (int64_t)a.NPU * 64;
 
@@ -968,13 +983,12 @@ thin_kernel(const LevelArgs a) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[g][v] = 0.0f;
 
-    u32x4 fa[kThinAhead], fb[kThinAhead][4];
+    u32x4 fa[kThinAhead], fb[kThinAhead];
     auto request = [&](int g, int slot) __attribute__((always_inline)) {
         const int64_t ka = (int64_t)(g >> 1) * a_pair + (g & 1) * 32;
         const int64_t kb = (int64_t)(g >> 1) * b_pair + (g & 1) * 32;
         fa[slot] = *reinterpret_cast<const u32x4 *>(ap + ka);
-#pragma unroll
-        for (int q = 0; q < NG_X; ++q) fb[slot][q] = *reinterpret_cast<const u32x4 *>(bp + q * b_step + kb);
+        fb[slot] = *reinterpret_cast<const u32x4 *>(bp + kb);
     };
 #pragma unroll
     for (int s = 0; s < kThinAhead; ++s)
@@ -984,11 +998,7 @@ thin_kernel(const LevelArgs a) {
         for (int s = 0; s < kThinAhead; ++s) {
             const int g = g0 + s;
             if (g < n_groups) {
-                mfma_step<T>(fa[s], fb[s][0], acc[0]);
-                mfma_step<T>(fa[s], fb[s][1], acc[1]);
-                mfma_step<T>(fa[s], fb[s][2], acc[2]);
-                // the forget rows take part in the x part only (and in all of the projection)
-                if (NG_X == 4 && (MODE != MODE_INTERNAL || g < n_groups_x)) mfma_step<T>(fa[s], fb[s][3], acc[3]);
+                mfma_step<T>(fa[s], fb[s], acc[0]);
                 if (g + kThinAhead < n_groups) request(g + kThinAhead, s);
             }
         }
@@ -996,25 +1006,31 @@ thin_kernel(const LevelArgs a) {
 
     if constexpr (MODE == MODE_PROJ) {
         T *P = static_cast<T *>(a.P);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int unit = (col * 4 + q) * kUnit + l32;
-            if (unit >= a.H) continue;
+        const int unit = (col * 4 + wave) * kUnit + l32;
+        if (unit < a.H) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int r = row0 + (v >> 2) * 8 + hf * 4 + (v & 3);
                 if (r < a.n_rows) {
                     const int node = a.row_rec[2 * (int64_t)r].x;
-                    P[(int64_t)node * a.Hq + unit] = from_f32<T>(acc[q][v]);
+                    P[(int64_t)node * a.Hq + unit] = from_f32<T>(acc[0][v]);
                 }
             }
         }
     } else {
-        // the row data written above is read by this wave only
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        cell_pass<T, MODE>(a, acc, regions[wave], s_node[wave], s_ar[wave], s_cb[wave], s_kid[wave], col, lane);
+        // gates 1-3 travel to wave 0, which holds gate 0 (every wave that is still here
+        // reaches this barrier; the forget wave of a leaf level left above)
+        if (wave > 0) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) exchange[wave - 1][v][lane] = acc[0][v];
+        }
+        __syncthreads();
+        if (wave > 0) return;
+#pragma unroll
+        for (int g = 1; g < (MODE == MODE_LEAF ? 3 : 4); ++g)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[g][v] = exchange[g - 1][v][lane];
+        cell_pass<T, MODE>(a, acc, region, s_node, s_ar, s_cb, s_kid, col, lane);
     }
 }
 
@@ -1026,17 +1042,19 @@ struct Profiler {
     int64_t dropped = 0;
     hipEvent_t *begin = nullptr, *end = nullptr;
     int *cls = nullptr;
+    int64_t *rows = nullptr;
 };
 Profiler g_prof;
 
 struct ScopedLaunchTimer {
     int slot = -1;
     hipStream_t st;
-    ScopedLaunchTimer(int kernel_class, hipStream_t s) : st(s) {
+    ScopedLaunchTimer(int kernel_class, int64_t rows, hipStream_t s) : st(s) {
         if (!g_prof.on) return;
         if (g_prof.used >= g_prof.capacity) { ++g_prof.dropped; return; }
         slot = g_prof.used++;
         g_prof.cls[slot] = kernel_class;
+        g_prof.rows[slot] = rows;
         (void)hipEventRecord(g_prof.begin[slot], st);
     }
     ~ScopedLaunchTimer() {
@@ -1111,7 +1129,7 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
     {
         const int64_t total = (int64_t)d.NPU * (d.Dp + d.Hp);
         const unsigned grid = (unsigned)(ceil_div(total, kThreads) < 4096 ? ceil_div(total, kThreads) : 4096);
-        ScopedLaunchTimer tm(JITDB_K_PACK, st);
+        ScopedLaunchTimer tm(JITDB_K_PACK, 0, st);
         pack_weights_kernel<T><<<grid, kThreads, 0, st>>>(
             static_cast<const T *>(W), static_cast<const T *>(U), b, d.D, d.H, d.Dp, d.Hp, d.NP, d.NPU,
             static_cast<T *>(w.Bp), w.bp);
@@ -1119,7 +1137,7 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
     }
 
     {
-        ScopedLaunchTimer tm(JITDB_K_PACK, st);
+        ScopedLaunchTimer tm(JITDB_K_PACK, 0, st);
         row_record_kernel<<<(unsigned)ceil_div(s->n_nodes, kRecWindow), kThreads, 0, st>>>(
             s->perm, s->height, s->child_ptr, s->child_idx, w.row_rec, (int)s->n_nodes);
         JITDB_LAUNCH_CHECK();
@@ -1149,7 +1167,7 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
             const int Kp = d.Dp + (l > 0 ? d.Hp : 0);
             const int64_t pieces = (int64_t)n_rows * (Kp / Traits<T>::VEC);
             const unsigned grid = (unsigned)ceil_div(pieces, kThreads);
-            ScopedLaunchTimer tm(JITDB_K_STACK, st);
+            ScopedLaunchTimer tm(JITDB_K_STACK, n_rows, st);
             if (l == 0)
                 stack_kernel<T, false><<<grid, kThreads, 0, st>>>(
                     static_cast<const T *>(x), d.D, d.Dp, static_cast<const T *>(a.hs), d.Hp, a.row_rec,
@@ -1166,14 +1184,16 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
         if (thin) {
             a.n_col_tiles = n_unit_tiles;
             a.n_tiles = (int)ceil_div(n_rows, 32) * a.n_col_tiles;
-            a.n_blocks = (int)ceil_div(a.n_tiles, kThinWaves);
+            a.n_blocks = a.n_tiles;
         } else {
             a.n_col_tiles = d.NP / kBN;
             a.n_tiles = 0;
-            a.n_blocks = row_tiles * a.n_col_tiles;
+            a.n_row_tiles = row_tiles;
+            a.n_blocks = 8 * (int)ceil_div(row_tiles, 8) * a.n_col_tiles;
         }
         {
-            ScopedLaunchTimer tm(l == 0 ? JITDB_K_LEAF : JITDB_K_INTERNAL, st);
+            ScopedLaunchTimer tm(thin ? (l == 0 ? JITDB_K_THIN_LEAF : JITDB_K_THIN_INTERNAL)
+                                      : (l == 0 ? JITDB_K_LEAF : JITDB_K_INTERNAL), n_rows, st);
             if (thin) {
                 if (l == 0)
                     thin_kernel<T, MODE_LEAF><<<a.n_blocks, kThinWaves * 64, 0, st>>>(a);
@@ -1188,15 +1208,16 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
         }
         JITDB_LAUNCH_CHECK();
         if (l + 1 < L) {   // these nodes have parents (except roots, whose rows go unused)
-            ScopedLaunchTimer tm(JITDB_K_PROJ, st);
+            ScopedLaunchTimer tm(thin ? JITDB_K_THIN_PROJ : JITDB_K_PROJ, n_rows, st);
             if (thin) {
                 a.n_col_tiles = (int)ceil_div(n_unit_tiles, 4);
                 a.n_tiles = (int)ceil_div(n_rows, 32) * a.n_col_tiles;
-                a.n_blocks = (int)ceil_div(a.n_tiles, kThinWaves);
+                a.n_blocks = a.n_tiles;
                 thin_kernel<T, MODE_PROJ><<<a.n_blocks, kThinWaves * 64, 0, st>>>(a);
             } else {
                 a.n_col_tiles = (int)ceil_div(n_unit_tiles, 8);
-                a.n_blocks = row_tiles * a.n_col_tiles;
+                a.n_row_tiles = row_tiles;
+                a.n_blocks = 8 * (int)ceil_div(row_tiles, 8) * a.n_col_tiles;
                 level_kernel<T, MODE_PROJ><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
             }
         }
@@ -1217,6 +1238,7 @@ extern "C" int jitdb_profile_start(int32_t capacity) {
     g_prof.begin = new hipEvent_t[capacity];
     g_prof.end = new hipEvent_t[capacity];
     g_prof.cls = new int[capacity];
+    g_prof.rows = new int64_t[capacity];
     for (int i = 0; i < capacity; ++i) {
         if (hipEventCreate(&g_prof.begin[i]) != hipSuccess || hipEventCreate(&g_prof.end[i]) != hipSuccess)
             return JITDB_E_HIP;
@@ -1233,7 +1255,7 @@ extern "C" int jitdb_profile_stop(jitdb_profile_t *out) {
     if (!g_prof.on) return JITDB_E_BADARG;
     g_prof.on = false;
     int rc = JITDB_OK;
-    for (int c = 0; c < JITDB_K_CLASSES; ++c) { out->ms[c] = 0.0; out->launches[c] = 0; }
+    for (int c = 0; c < JITDB_K_CLASSES; ++c) { out->ms[c] = 0.0; out->launches[c] = 0; out->rows[c] = 0; }
     out->dropped = g_prof.dropped;
     for (int i = 0; i < g_prof.used; ++i) {
         float ms = 0.0f;
@@ -1244,12 +1266,13 @@ extern "C" int jitdb_profile_stop(jitdb_profile_t *out) {
         }
         out->ms[g_prof.cls[i]] += ms;
         out->launches[g_prof.cls[i]] += 1;
+        out->rows[g_prof.cls[i]] += g_prof.rows[i];
     }
     for (int i = 0; i < g_prof.capacity; ++i) {
         (void)hipEventDestroy(g_prof.begin[i]);
         (void)hipEventDestroy(g_prof.end[i]);
     }
-    delete[] g_prof.begin; delete[] g_prof.end; delete[] g_prof.cls;
+    delete[] g_prof.begin; delete[] g_prof.end; delete[] g_prof.cls; delete[] g_prof.rows;
     g_prof = Profiler();
     return rc;
 }
