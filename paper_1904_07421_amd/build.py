@@ -2,8 +2,11 @@
 from __future__ import annotations
 
 import os
+import re
+import shutil
 import subprocess
 import sys
+import tempfile
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
@@ -33,20 +36,137 @@ def _check_no_scratch(lines) -> None:
                 raise RuntimeError(f"kernel {name} uses {size} bytes/lane of scratch memory (register spill)")
 
 
+_VREG = re.compile(r"\bv(\d+)\b|\bv\[(\d+):(\d+)\]")
+
+
+def _vregs(text: str) -> set:
+    out = set()
+    for m in _VREG.finditer(text):
+        if m.group(1) is not None:
+            out.add(int(m.group(1)))
+        else:
+            out.update(range(int(m.group(2)), int(m.group(3)) + 1))
+    return out
+
+
+def _join(a, b):
+    """Upper bound of two FIFO states (oldest first): align at the youngest end, unite per slot."""
+    if a is None:
+        return b
+    if b is None:
+        return a
+    n = max(len(a), len(b))
+    a = (frozenset(),) * (n - len(a)) + a
+    b = (frozenset(),) * (n - len(b)) + b
+    return tuple(x | y for x, y in zip(a, b))
+
+
+def check_lds_read_waits(asm_text: str, kernel_substr: str = "level_kernel") -> int:
+    """Static check of the generated code of the level kernel, whose LDS fragment reads are
+    inline asm the compiler knows nothing about: between a ds_read and the s_waitcnt
+    lgkmcnt that covers it, no other instruction may touch the registers it will write (a
+    compiler-made copy or spill there would move data that has not arrived).  LDS and
+    scalar-memory operations of a wave are counted by one in-order counter, modelled as a
+    FIFO of destination-register sets; the states are propagated over the control-flow
+    graph of each kernel to a fixed point.  Returns the number of ds_read instructions seen."""
+    # split into kernels, then basic blocks
+    kernels, cur = [], None
+    for raw in asm_text.splitlines():
+        line = raw.split(";")[0].strip()
+        if not line:
+            continue
+        if line.endswith(":") and not line.startswith("."):
+            cur = [] if kernel_substr in line else None
+            if cur is not None:
+                kernels.append(cur)
+            continue
+        if cur is None or (line.startswith(".") and not line.endswith(":")):
+            continue
+        cur.append(line)
+    seen = 0
+    for body in kernels:
+        blocks, names = [[]], {}
+        for line in body:
+            if line.endswith(":"):
+                if blocks[-1]:
+                    blocks.append([])
+                names[line[:-1]] = len(blocks) - 1
+                continue
+            blocks[-1].append(line)
+            op = line.split(" ")[0]
+            if op.startswith("s_cbranch") or op in ("s_branch", "s_endpgm"):
+                blocks.append([])
+        succ = []
+        for bi, blk in enumerate(blocks):
+            last = blk[-1].split() if blk else []
+            nxt = [bi + 1] if bi + 1 < len(blocks) else []
+            if last and last[0] == "s_branch":
+                succ.append([names[last[1]]])
+            elif last and last[0].startswith("s_cbranch"):
+                succ.append([names[last[1]]] + nxt)
+            elif last and last[0] == "s_endpgm":
+                succ.append([])
+            else:
+                succ.append(nxt)
+        state_in = [None] * len(blocks)
+        state_in[0] = ()
+        work = [0]
+        while work:
+            bi = work.pop()
+            pending = list(state_in[bi])
+            for line in blocks[bi]:
+                op, _, rest = line.partition(" ")
+                if op == "s_waitcnt":
+                    m = re.search(r"lgkmcnt\((\d+)\)", rest)
+                    if m and int(m.group(1)) < len(pending):
+                        pending = pending[len(pending) - int(m.group(1)):]
+                    continue
+                busy = frozenset().union(*pending) if pending else frozenset()
+                if busy:
+                    touched = _vregs(rest)
+                    if op.startswith("ds_read"):          # its address may be a register it overwrites
+                        touched = _vregs(rest.split(",")[0])
+                    if touched & busy:
+                        raise RuntimeError("register of an LDS read in flight is touched before its wait: " + line)
+                if op.startswith("ds_read"):
+                    pending.append(frozenset(_vregs(rest.split(",")[0])))
+                elif op.startswith("ds_") or op.startswith("s_load") or op.startswith("s_buffer_load"):
+                    pending.append(frozenset())
+                pending = pending[-64:]
+            out = tuple(pending)
+            for t in succ[bi]:
+                joined = _join(state_in[t], out)
+                if joined != state_in[t]:
+                    state_in[t] = joined
+                    work.append(t)
+        seen += sum(1 for line in body if line.startswith("ds_read"))
+    return seen
+
+
 def build(verbose: bool = False) -> str:
     """Always recompiles every source; returns the path of the shared library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     srcs = [os.path.join(CSRC, s) for s in SOURCES if os.path.exists(os.path.join(CSRC, s))]
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", LIB, *srcs]
+    cmd = [hipcc, *HIPCC_FLAGS, "--save-temps", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", LIB, *srcs]
     if verbose:
         print(" ".join(cmd), flush=True)
-    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    tmp = tempfile.mkdtemp(prefix="jitdb_build_")
+    try:
+        res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, cwd=tmp)
+        asm_path = os.path.join(tmp, "forward-hip-amdgcn-amd-amdhsa-gfx950.s")
+        asm_text = open(asm_path).read() if os.path.exists(asm_path) else None
+    finally:
+        shutil.rmtree(tmp, ignore_errors=True)
     # the host pass warns that it does not know the packed-fp32 feature: harmless
     lines = [l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l]
     out = "\n".join(l for l in lines if "-Rpass-analysis" not in l)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + out)
     _check_no_scratch(lines)
+    if asm_text is None:
+        raise RuntimeError("the device assembly of forward.hip was not produced; cannot check it")
+    if check_lds_read_waits(asm_text) == 0:
+        raise RuntimeError("no LDS reads found in the level kernel's assembly: the check is not looking at it")
     if verbose and out.strip():
         print(out)
     return LIB
