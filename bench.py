@@ -60,6 +60,7 @@ def main():
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one 1 GiB device copy (reference for HBM counters)")
     ap.add_argument("--cpu-trees", type=int, default=0, help="trees in the oracle sample (0 = auto)")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the copy / MFMA peak probes")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the forest shards by tree with no "
@@ -200,6 +201,23 @@ def main():
         mfma_ms = sum(kernels[n]["ms_per_step"] for n in mfma_names)
         roof["all_mfma_kernels_frac"] = sum(flops_total.values()) / (mfma_ms * 1e-3) / 1e12 / peak_tflops
 
+    # what this machine sustains: a plain device copy (1 GiB each way) and a loop of independent MFMAs
+    measured = None
+    if not args.no_peaks:
+        src = torch.empty(256 * 1024 * 1024, dtype=torch.float32, device=dev).fill_(1.0)
+        dst = torch.empty_like(src)
+        sink = torch.zeros(1, dtype=torch.float32, device=dev)
+        torch.cuda.synchronize()
+        measured = {"copy_gbs": J.jitdb_probe_copy(src, dst, stream=stream),
+                    "mfma_tflops": J.jitdb_probe_mfma(J.JITDB_BF16 if esz == 2 else J.JITDB_F32, sink, stream=stream),
+                    "what": "plain 1 GiB device copy, read + written; loop of independent 32x32 MFMAs on all CUs"}
+        del src, dst
+        if roof is not None:
+            roof["measured_peak"] = measured["mfma_tflops"]
+            roof["frac_of_measured_peak"] = roof["achieved"] / measured["mfma_tflops"]
+        if "stack" in kernels:
+            kernels["stack"]["frac_of_measured_copy"] = kernels["stack"]["gbs"] / measured["copy_gbs"]
+
     out = {
         "metric": "Tree-LSTM forward nodes/sec on 1 MI355X",
         "value": value, "unit": "nodes/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -210,7 +228,7 @@ def main():
                    "step": "jitdb_schedule + jitdb_treelstm_forward"},
         "ms_schedule": ms_sched, "ms_forward": ms_fwd,
         "forward_only_nodes_per_s": N / (ms_fwd * 1e-3),
-        "roofline": roof, "kernels": kernels,
+        "roofline": roof, "kernels": kernels, "measured_peaks": measured,
     }
 
     if not args.no_cpu_baseline:

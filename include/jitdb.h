@@ -180,6 +180,21 @@ typedef struct {
 int jitdb_profile_start(int32_t capacity);
 int jitdb_profile_stop(jitdb_profile_t *out);
 
+/*
+ * Machine peaks measured on the spot, for quoting kernel rates against what this device
+ * sustains as well as against the data sheet (the paper reports wall-clock throughput only,
+ * section 5; these calls exist for the benchmark and are not part of the method).
+ *
+ *   jitdb_probe_copy   times a plain device copy of `bytes` (multiple of 16; src, dst dev,
+ *                      16-byte aligned, not overlapping) and returns (read + written) GB/s.
+ *   jitdb_probe_mfma   times a loop of independent 32x32 MFMAs of the dtype's kind on every
+ *                      CU and returns TFLOP/s; `sink` is dev memory for one float (never
+ *                      written in practice).
+ * Both run on `hip_stream` and wait for it.
+ */
+int jitdb_probe_copy(const void *src, void *dst, size_t bytes, void *hip_stream, double *gb_per_s);
+int jitdb_probe_mfma(jitdb_dtype dtype, float *sink, void *hip_stream, double *tflop_per_s);
+
 /* Static, NUL-terminated description of a status code. */
 const char *jitdb_strerror(int code);
 

@@ -12,6 +12,8 @@ from .binding import (  # noqa: F401
     jitdb_strerror,
     jitdb_profile_start,
     jitdb_profile_stop,
+    jitdb_probe_copy,
+    jitdb_probe_mfma,
     jitdb_version,
     library_path,
     load_library,

@@ -85,6 +85,12 @@ def load_library():
     lib.jitdb_profile_start.argtypes = [ctypes.c_int32]
     lib.jitdb_profile_stop.restype = ctypes.c_int
     lib.jitdb_profile_stop.argtypes = [ctypes.POINTER(_ProfileStruct)]
+    lib.jitdb_probe_copy.restype = ctypes.c_int
+    lib.jitdb_probe_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
+                                     ctypes.POINTER(ctypes.c_double)]
+    lib.jitdb_probe_mfma.restype = ctypes.c_int
+    lib.jitdb_probe_mfma.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
+                                     ctypes.POINTER(ctypes.c_double)]
     lib.jitdb_strerror.restype = ctypes.c_char_p
     lib.jitdb_strerror.argtypes = [ctypes.c_int]
     lib.jitdb_last_hip_error.restype = ctypes.c_char_p
@@ -115,6 +121,24 @@ def jitdb_profile_stop() -> dict:
            for i, name in enumerate(K_CLASSES)}
     out["dropped"] = int(p.dropped)
     return out
+
+
+def jitdb_probe_copy(src, dst, stream=None) -> float:
+    """(read + written) GB/s of a plain device copy of src into dst (equal-sized device tensors)."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("src and dst differ in size")
+    out = ctypes.c_double(0.0)
+    _check(load_library().jitdb_probe_copy(src.data_ptr(), dst.data_ptr(), nbytes, _stream_ptr(stream),
+                                           ctypes.byref(out)))
+    return float(out.value)
+
+
+def jitdb_probe_mfma(dtype: int, sink, stream=None) -> float:
+    """TFLOP/s of a loop of independent MFMAs of the dtype's kind; sink = device tensor of one float."""
+    out = ctypes.c_double(0.0)
+    _check(load_library().jitdb_probe_mfma(int(dtype), sink.data_ptr(), _stream_ptr(stream), ctypes.byref(out)))
+    return float(out.value)
 
 
 def jitdb_schedule_workspace_bytes(n_nodes: int) -> int:
