@@ -61,6 +61,9 @@ def main():
                     help="also run one 1 GiB device copy (reference for HBM counters)")
     ap.add_argument("--cpu-trees", type=int, default=0, help="trees in the oracle sample (0 = auto)")
     ap.add_argument("--no-peaks", action="store_true", help="skip the copy / MFMA peak probes")
+    ap.add_argument("--serial", action="store_true",
+                    help="schedule and forward of a batch strictly one after the other on one stream "
+                         "(default: the schedule of the next batch overlaps the forward of this one)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the forest shards by tree with no "
@@ -111,10 +114,32 @@ def main():
     c = torch.empty((N, H), dtype=torch.float32, device=dev)
     stream = torch.cuda.current_stream()
 
-    def step():     # every buffer is reused; the schedule is recomputed from the parent array
-        s = J.jitdb_schedule(pt, stream=stream, workspace=ws_s, out=sched)
-        J.jitdb_treelstm_forward(xt, Wt, Ut, bt, s, stream=stream, workspace=ws_f, out=(h, c))
-        return s
+    if args.serial:
+        def step():     # every buffer is reused; the schedule is recomputed from the parent array
+            s = J.jitdb_schedule(pt, stream=stream, workspace=ws_s, out=sched)
+            J.jitdb_treelstm_forward(xt, Wt, Ut, bt, s, stream=stream, workspace=ws_f, out=(h, c))
+    else:
+        # Batches arrive one after another: the analysis of batch i+1 runs on a second stream while
+        # batch i executes (the call blocks the host, not the GPU).  Two schedule objects take turns;
+        # an event keeps the analysis from overwriting one that a forward still reads.  Every step is
+        # still one jitdb_schedule (from the parent array) and one jitdb_treelstm_forward.
+        s_fwd, s_sch = torch.cuda.Stream(), torch.cuda.Stream()
+        scheds = [sched, J.jitdb_schedule(pt)]
+        ws_ss = [ws_s, torch.empty_like(ws_s)]
+        last_use = [None, None]
+        turn = [0]
+        torch.cuda.synchronize()
+        J.jitdb_schedule(pt, stream=s_sch, workspace=ws_ss[0], out=scheds[0])
+
+        def step():
+            k = turn[0] & 1
+            J.jitdb_treelstm_forward(xt, Wt, Ut, bt, scheds[k], stream=s_fwd, workspace=ws_f, out=(h, c))
+            last_use[k] = torch.cuda.Event()
+            last_use[k].record(s_fwd)
+            if last_use[k ^ 1] is not None:
+                s_sch.wait_event(last_use[k ^ 1])
+            J.jitdb_schedule(pt, stream=s_sch, workspace=ws_ss[k ^ 1], out=scheds[k ^ 1])
+            turn[0] += 1
 
     if args.calibration_copy:
         # a plain copy of known size (1 GiB read + 1 GiB written, more than the 256 MB last-level
@@ -225,8 +250,9 @@ def main():
         "dtype": cfg.dtype if cfg.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"config {cfg.index}: {cfg.name}", "n_trees": cfg.n_trees, "n_nodes": N,
                    "n_edges": E, "n_levels": L, "D": D, "H": H,
-                   "step": "jitdb_schedule + jitdb_treelstm_forward"},
-        "ms_schedule": ms_sched, "ms_forward": ms_fwd,
+                   "step": "jitdb_schedule + jitdb_treelstm_forward per batch" +
+                           ("" if args.serial else "; schedule of batch i+1 on a second stream beside the forward of batch i")},
+        "ms_schedule": ms_sched, "ms_forward": ms_fwd, "ms_per_step_one_stream": ms_sched + ms_fwd,
         "forward_only_nodes_per_s": N / (ms_fwd * 1e-3),
         "roofline": roof, "kernels": kernels, "measured_peaks": measured,
     }
