@@ -103,6 +103,32 @@ size_t jitdb_schedule_workspace_bytes(int64_t n_nodes);
 int jitdb_schedule(const int32_t *parent, jitdb_schedule_t *s,
                    void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Bytes of device workspace jitdb_schedule_append needs (0 if an argument is invalid). */
+size_t jitdb_schedule_append_workspace_bytes(int64_t n_base, int64_t n_new);
+
+/*
+ * Incremental analysis: trees that arrive while earlier work is still executing (the
+ * serving case of section 2) are appended to a forest that has a schedule already, at
+ * the cost of analysing the new trees only.
+ *
+ *   base        a complete schedule of a forest of N_a nodes (N_a == 0 allowed; then only
+ *               n_nodes and host_level_ptr need to be set).  Read, not changed.
+ *   parent_new  dev [n_new] int32, the arriving trees with ids local to them (0 .. n_new-1,
+ *               -1 = root); node v becomes node N_a + v of the joint forest.
+ *   out         in/out like jitdb_schedule_t in jitdb_schedule, n_nodes == N_a + n_new and
+ *               every array sized for it; must not share memory with base.
+ *
+ * `out` receives exactly what jitdb_schedule returns for the concatenated parent array
+ * (the old parents followed by parent_new[v] + N_a): new ids sort after the old ones inside
+ * every level, and trees share no nodes, so the old level segments and child lists are
+ * kept and shifted (one linear pass) instead of being sorted again.  Errors in
+ * parent_new are reported as by jitdb_schedule.  Synchronises the stream as often as
+ * jitdb_schedule does for the new part; the merge itself is asynchronous on the stream.
+ */
+int jitdb_schedule_append(const jitdb_schedule_t *base, const int32_t *parent_new, int64_t n_new,
+                          jitdb_schedule_t *out, void *workspace, size_t workspace_bytes,
+                          void *hip_stream);
+
 /* Bytes of device workspace jitdb_treelstm_forward needs (0 if an argument is invalid). */
 size_t jitdb_treelstm_workspace_bytes(int64_t n_nodes, int64_t n_edges,
                                       int32_t D, int32_t H, jitdb_dtype dtype);

@@ -166,3 +166,14 @@ def schedule_fast(parent) -> dict:
     return dict(height=h.astype(np.int32), level_ptr=level_ptr, perm=perm,
                 inv_perm=inv_perm, child_ptr=child_ptr, child_idx=child_idx,
                 n_levels=L, n_edges=int(child_ptr[n]))
+
+
+def concat_forests(parent_a, parent_b) -> np.ndarray:
+    """Parent array of forest A followed by forest B: B's node v becomes node len(A) + v
+    (roots stay -1).  This is what "appending trees" means; the schedule of an appended
+    forest is by definition `schedule(concat_forests(a, b))` (section 2: new work joins
+    while earlier work is in flight; sections 4.2-4.3 define the table it joins)."""
+    a = np.asarray(parent_a, dtype=np.int64)
+    b = np.asarray(parent_b, dtype=np.int64)
+    shifted = np.where(b >= 0, b + a.shape[0], b)
+    return np.concatenate([a, shifted]).astype(np.int32)

@@ -7,6 +7,8 @@ from .binding import (  # noqa: F401
     Schedule,
     jitdb_schedule,
     jitdb_schedule_workspace_bytes,
+    jitdb_schedule_append,
+    jitdb_schedule_append_workspace_bytes,
     jitdb_treelstm_forward,
     jitdb_treelstm_workspace_bytes,
     jitdb_strerror,

@@ -72,6 +72,12 @@ def load_library():
     lib.jitdb_schedule.restype = ctypes.c_int
     lib.jitdb_schedule.argtypes = [ctypes.c_void_p, ctypes.POINTER(_ScheduleStruct),
                                    ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.jitdb_schedule_append_workspace_bytes.restype = ctypes.c_size_t
+    lib.jitdb_schedule_append_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int64]
+    lib.jitdb_schedule_append.restype = ctypes.c_int
+    lib.jitdb_schedule_append.argtypes = [ctypes.POINTER(_ScheduleStruct), ctypes.c_void_p, ctypes.c_int64,
+                                          ctypes.POINTER(_ScheduleStruct), ctypes.c_void_p, ctypes.c_size_t,
+                                          ctypes.c_void_p]
     lib.jitdb_treelstm_workspace_bytes.restype = ctypes.c_size_t
     lib.jitdb_treelstm_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
                                                    ctypes.c_int32, ctypes.c_int]
@@ -216,6 +222,38 @@ def jitdb_schedule(parent, stream=None, workspace=None, out: Optional[Schedule] 
     with torch.cuda.device(parent.device):
         code = lib.jitdb_schedule(parent.data_ptr() if n else None, ctypes.byref(sched.struct),
                                   workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
+    _check(code)
+    sched.n_levels = int(sched.struct.n_levels)
+    sched.n_edges = int(sched.struct.n_edges)
+    return sched
+
+
+def jitdb_schedule_append_workspace_bytes(n_base: int, n_new: int) -> int:
+    return int(load_library().jitdb_schedule_append_workspace_bytes(int(n_base), int(n_new)))
+
+
+def jitdb_schedule_append(base: Schedule, parent_new, stream=None, workspace=None,
+                          out: Optional[Schedule] = None) -> Schedule:
+    """Schedule of the forest `base` describes followed by the trees in parent_new (int32 CUDA
+    tensor, ids local to the new trees); new node v gets id base.n_nodes + v."""
+    import torch
+    lib = load_library()
+    if parent_new.dtype != torch.int32 or not parent_new.is_cuda or not parent_new.is_contiguous():
+        raise TypeError("parent_new must be a contiguous int32 CUDA tensor")
+    m = parent_new.numel()
+    n = base.n_nodes + m
+    if out is not None and (out.n_nodes != n or out is base):
+        raise ValueError("out must be another Schedule, made for the joint forest's size")
+    sched = out if out is not None else Schedule(n, parent_new.device)
+    base.struct.n_levels = base.n_levels
+    base.struct.n_edges = base.n_edges
+    need = jitdb_schedule_append_workspace_bytes(base.n_nodes, m)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=parent_new.device)
+    with torch.cuda.device(parent_new.device):
+        code = lib.jitdb_schedule_append(ctypes.byref(base.struct), parent_new.data_ptr() if m else None, m,
+                                         ctypes.byref(sched.struct), workspace.data_ptr(), workspace.numel(),
+                                         _stream_ptr(stream))
     _check(code)
     sched.n_levels = int(sched.struct.n_levels)
     sched.n_edges = int(sched.struct.n_edges)

@@ -411,6 +411,73 @@ ScheduleWs carve_schedule_ws(int64_t n, void *base) {
     return w;
 }
 
+// ---- appending trees to a schedule ---------------------------------------------------
+// New nodes get ids n_a + v, so inside every level they sort after the old ones and inside
+// every child list there is nothing to interleave (trees do not share nodes): the merged
+// schedule is the old one with every level segment shifted by the number of new nodes in
+// lower levels, and the new one shifted by the number of old nodes up to and including
+// its level.  lpa / lpn are the two level_ptr arrays (valid up to la / ln).
+__global__ void __launch_bounds__(kThreads)
+append_merge_kernel(const int32_t *__restrict__ ha, const int32_t *__restrict__ perma,
+                    const int32_t *__restrict__ cpa, const int32_t *__restrict__ cia,
+                    const int32_t *__restrict__ lpa, int32_t na, int32_t ea, int32_t la,
+                    const int32_t *__restrict__ hn, const int32_t *__restrict__ permn,
+                    const int32_t *__restrict__ cpn, const int32_t *__restrict__ cin,
+                    const int32_t *__restrict__ lpn, int32_t nn, int32_t en, int32_t ln,
+                    int32_t *__restrict__ height, int32_t *__restrict__ level_ptr, int32_t *__restrict__ perm,
+                    int32_t *__restrict__ inv_perm, int32_t *__restrict__ child_ptr,
+                    int32_t *__restrict__ child_idx) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int32_t l_out = la > ln ? la : ln;
+    if (i <= l_out) {
+        const int32_t a = na > 0 ? lpa[i < la ? i : la] : 0;
+        const int32_t b = nn > 0 ? lpn[i < ln ? i : ln] : 0;
+        level_ptr[i] = a + b;
+    }
+    if (i < na) {
+        height[i] = ha[i];
+        const int32_t node = perma[i];
+        const int32_t l = ha[node];
+        const int32_t shift = nn > 0 ? lpn[l < ln ? l : ln] : 0;     // new nodes in lower levels
+        perm[i + shift] = node;
+        inv_perm[node] = (int32_t)i + shift;
+        child_ptr[i] = cpa[i];
+    }
+    if (i < ea) child_idx[i] = cia[i];
+    if (i < nn) {
+        height[na + i] = hn[i];
+        const int32_t v = permn[i];
+        const int32_t l = hn[v];
+        const int32_t shift = na > 0 ? lpa[l + 1 < la ? l + 1 : la] : 0;   // old nodes up to its level
+        perm[i + shift] = na + v;
+        inv_perm[na + v] = (int32_t)i + shift;
+    }
+    if (i <= nn) child_ptr[na + i] = ea + (nn > 0 ? cpn[i] : 0);
+    if (i < en) child_idx[ea + i] = na + cin[i];
+}
+
+struct AppendWs {
+    int32_t *height, *level_ptr, *perm, *inv_perm, *child_ptr, *child_idx;   // schedule of the new part
+    void *sched_ws;
+    size_t sched_ws_bytes;
+    size_t bytes;
+};
+
+AppendWs carve_append_ws(int64_t n_new, void *base) {
+    Carver c(base);
+    AppendWs w;
+    w.height = c.take<int32_t>(n_new);
+    w.level_ptr = c.take<int32_t>(n_new + 1);
+    w.perm = c.take<int32_t>(n_new);
+    w.inv_perm = c.take<int32_t>(n_new);
+    w.child_ptr = c.take<int32_t>(n_new + 1);
+    w.child_idx = c.take<int32_t>(n_new);
+    w.sched_ws_bytes = carve_schedule_ws(n_new, nullptr).bytes;
+    w.sched_ws = c.take<char>(w.sched_ws_bytes);
+    w.bytes = c.off;
+    return w;
+}
+
 }  // namespace
 }  // namespace jitdb
 
@@ -512,5 +579,70 @@ extern "C" int jitdb_schedule(const int32_t *parent, jitdb_schedule_t *s,
                                    hipMemcpyDeviceToHost, st));
     JITDB_HIP_CHECK(hipStreamSynchronize(st));
     if (s->host_level_ptr[0] != 0 || s->host_level_ptr[L] != n) return JITDB_E_CYCLE;
+    return JITDB_OK;
+}
+
+extern "C" size_t jitdb_schedule_append_workspace_bytes(int64_t n_base, int64_t n_new) {
+    if (n_base < 0 || n_new < 0 || n_base + n_new > JITDB_MAX_NODES) return 0;
+    return carve_append_ws(n_new, nullptr).bytes;
+}
+
+extern "C" int jitdb_schedule_append(const jitdb_schedule_t *base, const int32_t *parent_new, int64_t n_new,
+                                     jitdb_schedule_t *out, void *workspace, size_t workspace_bytes,
+                                     void *hip_stream) {
+    if (!base || !out) return JITDB_E_NULL;
+    drop_stale_hip_error();
+    const int64_t na = base->n_nodes;
+    if (na < 0 || n_new < 0 || na + n_new > JITDB_MAX_NODES) return JITDB_E_BADARG;
+    if (out->n_nodes != na + n_new) return JITDB_E_BADARG;
+    if (!out->host_level_ptr || !base->host_level_ptr) return JITDB_E_NULL;
+    const int64_t n_out = na + n_new;
+    if (n_out > 0 && (!out->height || !out->level_ptr || !out->perm || !out->inv_perm || !out->child_ptr ||
+                      !out->child_idx))
+        return JITDB_E_NULL;
+    if (na > 0) {
+        if (!base->height || !base->level_ptr || !base->perm || !base->child_ptr || !base->child_idx)
+            return JITDB_E_NULL;
+        const int32_t la = base->n_levels;
+        if (la < 1 || la > na || base->n_edges < 0 || base->n_edges >= na) return JITDB_E_SCHEDULE;
+        if (base->host_level_ptr[0] != 0 || base->host_level_ptr[la] != na) return JITDB_E_SCHEDULE;
+    }
+    if (n_new > 0 && (!parent_new || !workspace)) return JITDB_E_NULL;
+    if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return JITDB_E_BADARG;
+    const AppendWs w = carve_append_ws(n_new, workspace);
+    if (n_new > 0 && workspace_bytes < w.bytes) return JITDB_E_WORKSPACE;
+    hipStream_t st = (hipStream_t)hip_stream;
+
+    // the arriving trees on their own; their host level_ptr lands in the tail of the
+    // output's host array, which the merged one (written front to back below) never
+    // overtakes: entry l of the merged array is written after entry l of the new one is read
+    jitdb_schedule_t fresh;
+    fresh.n_nodes = n_new;
+    fresh.height = w.height; fresh.level_ptr = w.level_ptr; fresh.perm = w.perm; fresh.inv_perm = w.inv_perm;
+    fresh.child_ptr = w.child_ptr; fresh.child_idx = w.child_idx;
+    fresh.host_level_ptr = out->host_level_ptr + na;
+    fresh.n_levels = 0; fresh.n_edges = 0;
+    if (n_new > 0) {
+        const int rc = jitdb_schedule(parent_new, &fresh, w.sched_ws, w.sched_ws_bytes, hip_stream);
+        if (rc != JITDB_OK) return rc;
+    }
+    const int32_t la = na > 0 ? base->n_levels : 0, ln = fresh.n_levels;
+    const int32_t l_out = la > ln ? la : ln;
+    const int64_t ea = na > 0 ? base->n_edges : 0, en = fresh.n_edges;
+    for (int32_t l = 0; l <= l_out; ++l) {
+        const int32_t b = n_new > 0 ? fresh.host_level_ptr[l < ln ? l : ln] : 0;
+        const int32_t a = na > 0 ? base->host_level_ptr[l < la ? l : la] : 0;
+        out->host_level_ptr[l] = a + b;
+    }
+    out->n_levels = l_out;
+    out->n_edges = ea + en;
+    if (n_out == 0) return JITDB_OK;
+
+    const int64_t span = (na > n_new ? na : n_new) + 1;
+    append_merge_kernel<<<(unsigned)ceil_div(span, kThreads), kThreads, 0, st>>>(
+        base->height, base->perm, base->child_ptr, base->child_idx, base->level_ptr, (int32_t)na, (int32_t)ea, la,
+        w.height, w.perm, w.child_ptr, w.child_idx, w.level_ptr, (int32_t)n_new, (int32_t)en, ln,
+        out->height, out->level_ptr, out->perm, out->inv_perm, out->child_ptr, out->child_idx);
+    JITDB_LAUNCH_CHECK();
     return JITDB_OK;
 }

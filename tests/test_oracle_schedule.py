@@ -133,3 +133,22 @@ def test_planted_mistake_is_caught():
             w = int(p[w])
         depth[v] = d
     assert not np.array_equal(depth, S.heights_bruteforce(p))
+
+
+def test_concat_forests_keeps_each_forest_intact():
+    """Appending is concatenation with shifted ids: heights and child lists of each part are
+    unchanged, level sizes add up, and inside a level the old nodes come first."""
+    a, b = make_forest(2), chain_forest(9, 2)
+    j = S.concat_forests(a, b)
+    assert j.dtype == np.int32 and len(j) == len(a) + len(b)
+    sa, sb, sj = S.schedule(a), S.schedule(b), S.schedule(j)
+    assert np.array_equal(sj["height"], np.concatenate([sa["height"], sb["height"]]))
+    L = sj["n_levels"]
+    size = lambda s, l: (s["level_ptr"][l + 1] - s["level_ptr"][l]) if l < s["n_levels"] else 0
+    for l in range(L):
+        seg = sj["perm"][sj["level_ptr"][l]:sj["level_ptr"][l + 1]]
+        assert len(seg) == size(sa, l) + size(sb, l)
+        assert np.all(seg[:size(sa, l)] < len(a)) and np.all(seg[size(sa, l):] >= len(a))
+    assert sj["n_edges"] == sa["n_edges"] + sb["n_edges"]
+    assert np.array_equal(sj["child_idx"][:sa["n_edges"]], sa["child_idx"])
+    assert np.array_equal(sj["child_idx"][sa["n_edges"]:], sb["child_idx"] + len(a))
