@@ -39,11 +39,13 @@ def test_small_configs_every_node(c_oracle, cfg, bias):
     assert eh <= TOL[cfgo.dtype] and ec <= TOL[cfgo.dtype]
 
 
-def _sampled_tree_check(c_oracle, cfg, n_sample, dtype=None, bias="zero"):
+def _sampled_tree_check(c_oracle, cfg, n_sample, dtype=None, bias="zero", D=None, H=None, scale_tol=False):
     cfgo, p, x, W, U, b = make_workload(cfg, bias=bias)
+    if D is not None or H is not None:
+        x, W, U, b = make_values(cfg, p.shape[0], bias, D=D, H=H)
     dtype = dtype or cfgo.dtype
-    print(f"forward parity cfg={cfg} dtype={dtype} N={p.shape[0]} (oracle on {n_sample} sampled trees)",
-          flush=True)
+    print(f"forward parity cfg={cfg} dtype={dtype} D={x.shape[1]} H={U.shape[1]} N={p.shape[0]} "
+          f"(oracle on {n_sample} sampled trees)", flush=True)
     s, h, c, seen = run_gpu_forward(p, x, W, U, b, dtype)
     xo, Wo, Uo, bo = seen
     r = tree_ranges(p)
@@ -65,7 +67,9 @@ def _sampled_tree_check(c_oracle, cfg, n_sample, dtype=None, bias="zero"):
     ho, co, _ = c_oracle(sub_parent, xo[rows], Wo, Uo, bo)
     eh, ec = _report(f"cfg{cfg}/{dtype}", h[rows], c[rows], ho, co)
     assert np.isfinite(h).all() and np.isfinite(c).all()
-    assert eh <= TOL[dtype] and ec <= TOL[dtype]
+    # |c| grows with the arity; the bf16 bound is stated for |c| of a few units
+    tol_c = TOL[dtype] * (max(1.0, float(np.abs(co).max()) / 8.0) if scale_tol else 1.0)
+    assert eh <= TOL[dtype] and ec <= tol_c
 
 
 @pytest.mark.timeout(400)
@@ -123,6 +127,17 @@ def test_odd_dimensions(c_oracle, name, H, D, dtype):
     # the 149-child star reaches |c| ~ 50: scale the bf16 bound with the magnitude there
     scale = max(1.0, float(np.abs(co).max()) / 8.0) if dtype == "bf16" else max(1.0, float(np.abs(co).max()) / 50.0)
     assert eh <= TOL[dtype] and ec <= TOL[dtype] * scale
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("name,H,D", [("H33-D8", 33, 8), ("H64-D4", 64, 4), ("H100-D52", 100, 52),
+                                      ("H257-D300", 257, 300), ("H36-D7", 36, 7), ("H150-D302", 150, 302),
+                                      ("H520-D64", 520, 64)])
+def test_odd_dimensions_on_levels_large_enough_for_the_tiled_kernel(c_oracle, name, H, D, dtype):
+    """Config 3's forest (leaf level 68 k rows, two more levels above the thin-kernel limit) with
+    hidden and input sizes on and off every padding boundary: partial unit tiles, partial column
+    tiles, a two-stage K loop (D = 4), more than eight column tiles (H = 520)."""
+    _sampled_tree_check(c_oracle, 3, 150, dtype=dtype, bias="random", D=D, H=H, scale_tol=True)
 
 
 def test_leaves_only_and_single_node(c_oracle):
