@@ -99,3 +99,35 @@ def test_repeatable():
     p = make_forest(4)
     a, b = _run(p).to_numpy(), _run(p).to_numpy()
     assert_schedule_equal(a, b)
+
+
+@pytest.mark.timeout(600)
+def test_largest_forest_the_interface_accepts():
+    """N = JITDB_MAX_NODES (2^28): 2^26 chains of four nodes, whose schedule has a closed form
+    (height = 3 - v % 4; level l holds the nodes 4t + 3 - l in ascending order; node 4t + k,
+    k < 3, has the single child 4t + k + 1).  Checked on the device; int32 offsets must not
+    wrap anywhere on the way."""
+    import torch
+    import paper_1904_07421_amd as J
+    n = 1 << 28
+    t = 1 << 26
+    print(f"schedule N={n}", flush=True)
+    v = torch.arange(n, dtype=torch.int32, device="cuda")
+    parent = torch.where((v & 3) == 0, torch.full_like(v, -1), v - 1)
+    s = J.jitdb_schedule(parent)
+    del parent
+    torch.cuda.synchronize()
+    assert s.n_levels == 4 and s.n_edges == 3 * t
+    assert list(s.host_level_ptr[:5]) == [0, t, 2 * t, 3 * t, 4 * t]
+    assert torch.equal(s.level_ptr[:5].cpu(), torch.tensor([0, t, 2 * t, 3 * t, 4 * t], dtype=torch.int32))
+    assert torch.equal(s.height, 3 - (v & 3))
+    lvl = torch.div(v, t, rounding_mode="floor")          # position -> level
+    want_perm = 4 * (v - lvl * t) + 3 - lvl
+    assert torch.equal(s.perm, want_perm)
+    del want_perm, lvl
+    assert torch.equal(s.inv_perm, (3 - (v & 3)) * t + torch.div(v, 4, rounding_mode="floor"))
+    k = v & 3
+    assert torch.equal(s.child_ptr[:n], 3 * torch.div(v, 4, rounding_mode="floor") + k)
+    assert int(s.child_ptr[n]) == 3 * t
+    e = v[:3 * t]
+    assert torch.equal(s.child_idx[:3 * t], 4 * torch.div(e, 3, rounding_mode="floor") + e % 3 + 1)
