@@ -10,6 +10,9 @@ Contents
   treelstm_oracle.py   node-by-node postorder evaluation in fp64 (numpy)
   treelstm_oracle.c    the same definition in plain C (fp64), one tree at a
                        time; used where the numpy version is too slow
+  treelstm_backward_oracle.py   reverse-mode gradients of the same forest, node by
+                       node in fp64 (no GPU path uses it yet: the definition a
+                       backward pass will be built against)
   build.py             compiles the C file with gcc
 
 Pins (tests/test_oracle_*.py): brute-force heights, chain / star / perfect
@@ -17,6 +20,8 @@ k-ary closed forms, stable-argsort CSR, leaf closed form, chain == library
 LSTM, star with U_f = 0 == library LSTM cell on summed child states, saturated
 forget gates select children by the sign of their own h, zero-weight closed
 form c = i*u*subtree_size, relabelling and forest-vs-single-tree invariance,
-numpy oracle vs C oracle.  Launch-count tables of the paper (Table 1, Table 2)
+numpy oracle vs C oracle; for the gradient oracle: autograd of an independently
+written torch forward, a library LSTM differentiated by the library, central
+differences of the forward oracle, a one-leaf closed form.  Launch-count tables of the paper (Table 1, Table 2)
 need its dataset: parity unpinned, nothing here reproduces them.
 """
