@@ -30,24 +30,16 @@ import numpy as np
 from .treelstm_oracle import _sigmoid, postorder
 
 
-def forward_backward(parent, x, W, U, b, gh, gc):
-    """Returns (h, c, dx, dW, dU, db), all fp64."""
-    x = np.asarray(x, dtype=np.float64)
-    W = np.asarray(W, dtype=np.float64)
-    U = np.asarray(U, dtype=np.float64)
-    b = np.asarray(b, dtype=np.float64)
-    gh = np.asarray(gh, dtype=np.float64)
-    gc = np.asarray(gc, dtype=np.float64)
-    n, D = x.shape
+def _forward_saved(parent, x, W, U, b):
+    n = x.shape[0]
     H = U.shape[1]
     Wg = [W[g * H:(g + 1) * H] for g in range(4)]
     Ug = [U[g * H:(g + 1) * H] for g in range(4)]
     bg = [b[g * H:(g + 1) * H] for g in range(4)]
     order, ch = postorder(parent)
-
     h = np.zeros((n, H)); c = np.zeros((n, H))
     gi = np.zeros((n, H)); go = np.zeros((n, H)); gu = np.zeros((n, H)); hs = np.zeros((n, H))
-    f = {}
+    f = np.zeros((n, H))          # row k: the forget gate the parent of k applies to k (roots: 0)
     for j in order:
         kids = ch[j]
         for k in kids:
@@ -61,6 +53,28 @@ def forward_backward(parent, x, W, U, b, gh, gc):
             f[k] = _sigmoid(fx + Ug[3] @ h[k])
             c[j] += f[k] * c[k]
         h[j] = go[j] * np.tanh(c[j])
+    return order, ch, Wg, Ug, h, c, gi, go, gu, hs, f
+
+
+def forward_saved(parent, x, W, U, b):
+    """(h, c, gates [N, 3H] = i | o | u after their non-linearities, fgate [N, H] with row k =
+    the forget gate applied to child k by its parent): what a training forward keeps."""
+    x, W, U, b = (np.asarray(a, dtype=np.float64) for a in (x, W, U, b))
+    _, _, _, _, h, c, gi, go, gu, _, f = _forward_saved(parent, x, W, U, b)
+    return h, c, np.concatenate([gi, go, gu], axis=1), f
+
+
+def forward_backward(parent, x, W, U, b, gh, gc):
+    """Returns (h, c, dx, dW, dU, db), all fp64."""
+    x = np.asarray(x, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    U = np.asarray(U, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    gh = np.asarray(gh, dtype=np.float64)
+    gc = np.asarray(gc, dtype=np.float64)
+    n, D = x.shape
+    H = U.shape[1]
+    order, ch, Wg, Ug, h, c, gi, go, gu, hs, f = _forward_saved(parent, x, W, U, b)
 
     dh = gh.copy(); dc = gc.copy()
     dx = np.zeros((n, D)); dW = np.zeros_like(W); dU = np.zeros_like(U); db = np.zeros_like(b)

@@ -87,6 +87,21 @@ def load_library():
         ctypes.c_int32, ctypes.c_int32, ctypes.c_int,
         ctypes.POINTER(_ScheduleStruct), ctypes.c_void_p, ctypes.c_void_p,
         ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.jitdb_treelstm_forward_train.restype = ctypes.c_int
+    lib.jitdb_treelstm_forward_train.argtypes = [
+        ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+        ctypes.c_int32, ctypes.c_int32, ctypes.c_int,
+        ctypes.POINTER(_ScheduleStruct), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+        ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.jitdb_treelstm_backward_workspace_bytes.restype = ctypes.c_size_t
+    lib.jitdb_treelstm_backward_workspace_bytes.argtypes = [ctypes.POINTER(_ScheduleStruct), ctypes.c_int32,
+                                                            ctypes.c_int32, ctypes.c_int]
+    lib.jitdb_treelstm_backward.restype = ctypes.c_int
+    lib.jitdb_treelstm_backward.argtypes = [
+        ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int,
+        ctypes.POINTER(_ScheduleStruct), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+        ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+        ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     lib.jitdb_profile_start.restype = ctypes.c_int
     lib.jitdb_profile_start.argtypes = [ctypes.c_int32]
     lib.jitdb_profile_stop.restype = ctypes.c_int
@@ -264,6 +279,71 @@ def jitdb_treelstm_forward(x, W, U, b, schedule: Schedule, stream=None, workspac
                            out: Optional[Tuple] = None):
     """x [N, D], W [4H, D], U [4H, H] (all fp32 or all bf16), b [4H] fp32, on the GPU.
     Returns (h [N, H] in x's dtype, c [N, H] fp32), rows indexed by node id."""
+    return _forward(x, W, U, b, schedule, stream, workspace, out, train=False)
+
+
+def jitdb_treelstm_forward_train(x, W, U, b, schedule: Schedule, stream=None, workspace=None,
+                                 out: Optional[Tuple] = None):
+    """As jitdb_treelstm_forward; returns (h, c, gates [N, 3H] fp32, fgate [N, H] fp32).
+    `out` = (h, c, gates, fgate) reuses buffers.  fgate rows of roots are left as they are."""
+    return _forward(x, W, U, b, schedule, stream, workspace, out, train=True)
+
+
+def jitdb_treelstm_backward_workspace_bytes(schedule: Schedule, D: int, H: int, dtype: int) -> int:
+    schedule.struct.n_levels = schedule.n_levels
+    schedule.struct.n_edges = schedule.n_edges
+    return int(load_library().jitdb_treelstm_backward_workspace_bytes(ctypes.byref(schedule.struct), int(D),
+                                                                      int(H), int(dtype)))
+
+
+def jitdb_treelstm_backward(x, W, U, schedule: Schedule, h, c, gates, fgate, gh=None, gc=None,
+                            stream=None, workspace=None, out: Optional[Tuple] = None):
+    """Gradients of L = sum <gh, h> + <gc, c> (gh, gc: fp32 [N, H] CUDA tensors or None = zeros)
+    from what jitdb_treelstm_forward_train returned.  Returns fp32 (dx [N, D], dW [4H, D],
+    dU [4H, H], db [4H])."""
+    import torch
+    lib = load_library()
+    dt = JITDB_F32 if x.dtype == torch.float32 else JITDB_BF16
+    if x.dtype not in (torch.float32, torch.bfloat16):
+        raise TypeError("x must be float32 or bfloat16")
+    n = schedule.n_nodes
+    H = U.shape[1]
+    D = W.shape[1]
+    for t, name in ((x, "x"), (W, "W"), (U, "U"), (h, "h"), (c, "c"), (gates, "gates"), (fgate, "fgate")):
+        if not t.is_cuda or not t.is_contiguous():
+            raise TypeError(f"{name} must be a contiguous CUDA tensor")
+    if W.dtype != x.dtype or U.dtype != x.dtype or h.dtype != x.dtype:
+        raise TypeError("W, U, h must have x's dtype")
+    for t, name in ((c, "c"), (gates, "gates"), (fgate, "fgate"), (gh, "gh"), (gc, "gc")):
+        if t is not None and (t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous()):
+            raise TypeError(f"{name} must be a contiguous float32 CUDA tensor")
+    if (x.shape != (n, D) or h.shape != (n, H) or c.shape != (n, H) or gates.shape != (n, 3 * H)
+            or fgate.shape != (n, H) or W.shape[0] != 4 * H or U.shape[0] != 4 * H):
+        raise ValueError("shape mismatch")
+    for t in (gh, gc):
+        if t is not None and t.shape != (n, H):
+            raise ValueError("gh, gc must be [N, H]")
+    if out is None:
+        f32 = dict(dtype=torch.float32, device=x.device)
+        dx = torch.empty((n, D), **f32); dW = torch.empty((4 * H, D), **f32)
+        dU = torch.empty((4 * H, H), **f32); db = torch.empty(4 * H, **f32)
+    else:
+        dx, dW, dU, db = out
+    need = jitdb_treelstm_backward_workspace_bytes(schedule, D, H, dt)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    ptr = lambda t: t.data_ptr() if (t is not None and t.numel()) else None
+    with torch.cuda.device(x.device):
+        code = lib.jitdb_treelstm_backward(
+            ptr(x), W.data_ptr(), U.data_ptr(), D, H, dt, ctypes.byref(schedule.struct),
+            ptr(h), ptr(c), ptr(gates), ptr(fgate), ptr(gh), ptr(gc),
+            ptr(dx), dW.data_ptr(), dU.data_ptr(), db.data_ptr(),
+            workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
+    _check(code)
+    return dx, dW, dU, db
+
+
+def _forward(x, W, U, b, schedule, stream, workspace, out, train):
     import torch
     lib = load_library()
     if x.dtype == torch.float32:
@@ -282,18 +362,31 @@ def jitdb_treelstm_forward(x, W, U, b, schedule: Schedule, stream=None, workspac
     D = W.shape[1]
     if x.shape != (n, D) or W.shape[0] != 4 * H or U.shape[0] != 4 * H or b.numel() != 4 * H:
         raise ValueError("shape mismatch between x, W, U, b and the schedule")
+    gates = fgate = None
     if out is None:
         h = torch.empty((n, H), dtype=x.dtype, device=x.device)
         c = torch.empty((n, H), dtype=torch.float32, device=x.device)
+        if train:
+            gates = torch.empty((n, 3 * H), dtype=torch.float32, device=x.device)
+            fgate = torch.zeros((n, H), dtype=torch.float32, device=x.device)
+    elif train:
+        h, c, gates, fgate = out
     else:
         h, c = out
     need = jitdb_treelstm_workspace_bytes(n, schedule.n_edges, D, H, dt)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
     with torch.cuda.device(x.device):
-        code = lib.jitdb_treelstm_forward(
-            x.data_ptr() if n else None, W.data_ptr(), U.data_ptr(), b.data_ptr(), D, H, dt,
-            ctypes.byref(schedule.struct), h.data_ptr() if n else None, c.data_ptr() if n else None,
-            workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
+        if train:
+            code = lib.jitdb_treelstm_forward_train(
+                x.data_ptr() if n else None, W.data_ptr(), U.data_ptr(), b.data_ptr(), D, H, dt,
+                ctypes.byref(schedule.struct), h.data_ptr() if n else None, c.data_ptr() if n else None,
+                gates.data_ptr() if n else None, fgate.data_ptr() if n else None,
+                workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
+        else:
+            code = lib.jitdb_treelstm_forward(
+                x.data_ptr() if n else None, W.data_ptr(), U.data_ptr(), b.data_ptr(), D, H, dt,
+                ctypes.byref(schedule.struct), h.data_ptr() if n else None, c.data_ptr() if n else None,
+                workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
     _check(code)
-    return h, c
+    return (h, c, gates, fgate) if train else (h, c)

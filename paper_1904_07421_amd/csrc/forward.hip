@@ -311,6 +311,9 @@ struct LevelArgs {
     float *c_out;         // [N, H]
     void *h_out;          // [N, H]
     void *hs_out;         // [N, Hp] or == h_out when H == Hp
+    // training only: activations the backward pass needs
+    float *gates;         // [N, 3H] i | o | u after their non-linearities, rows by node id
+    float *fgate;         // [N, H] row k = forget gate the parent of k applied to k
     int D, Dp, H, Hp, Hu, Hq;
     int n_rows;
     int n_rows_alloc;     // rows per slab of the stacked input (n_rows rounded up to whole tiles)
@@ -364,7 +367,7 @@ __device__ __forceinline__ void mfma_step(const u32x4 &a, const u32x4 &b, floatx
 // (P_k and c_k) are then fetched in 8- and 16-byte pieces, 64 / 128 contiguous bytes per
 // row, with four rows in flight per lane.  rn / rar / rcb / rkid describe the 32 rows
 // (node id or -1, arity, CSR start, first four child ids).  No block barrier inside.
-template <typename T, int MODE>
+template <typename T, int MODE, bool SAVE = false>
 __device__ __forceinline__ void cell_pass(const LevelArgs &a, const floatx16 (&acc)[4], float *region,
                                           const int *rn, const int *rar, const int *rcb,
                                           const int4 *rkid, int unit_tile, int lane) {
@@ -393,6 +396,16 @@ __device__ __forceinline__ void cell_pass(const LevelArgs &a, const floatx16 (&a
         s_iu[rl * kEpiStride + l32] = gi * gu;
         s_o[rl * kEpiStride + l32] = go;
         if constexpr (MODE == MODE_INTERNAL) s_fx[rl * kEpiStride + l32] = acc[3][v] + bf;
+        if constexpr (SAVE) {
+            const int nd = rn[rl];
+            const int unit = unit_tile * kUnit + l32;
+            if (nd >= 0 && unit < a.H) {
+                float *g = a.gates + (int64_t)nd * 3 * a.H + unit;
+                g[0] = gi;
+                g[a.H] = go;
+                g[2 * a.H] = gu;
+            }
+        }
     }
     // the wave's own LDS writes are ordered before its reads; nothing else touches the region
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -428,6 +441,7 @@ __device__ __forceinline__ void cell_pass(const LevelArgs &a, const floatx16 (&a
         for (int c0 = 0; c0 < max_ar; c0 += 2) {
             int64_t ofs[4][2];
             float wgt[4][2];
+            int kidv[4][2];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 int4 kids = make_int4(0, 0, 0, 0);
@@ -443,6 +457,7 @@ __device__ __forceinline__ void cell_pass(const LevelArgs &a, const floatx16 (&a
                     if (has) last[q] = (int64_t)kid * a.Hq + unit_ld;
                     ofs[q][j] = last[q];
                     wgt[q][j] = has ? 1.0f : 0.0f;
+                    kidv[q][j] = has ? kid : -1;
                 }
             }
             float4 pk[4][2], ck[4][2];
@@ -463,10 +478,21 @@ __device__ __forceinline__ void cell_pass(const LevelArgs &a, const floatx16 (&a
             for (int q = 0; q < 4; ++q)
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
-                    cc[q].x += wgt[q][j] * sigmoid_t<T>(fx4[q].x + pk[q][j].x) * ck[q][j].x;
-                    cc[q].y += wgt[q][j] * sigmoid_t<T>(fx4[q].y + pk[q][j].y) * ck[q][j].y;
-                    cc[q].z += wgt[q][j] * sigmoid_t<T>(fx4[q].z + pk[q][j].z) * ck[q][j].z;
-                    cc[q].w += wgt[q][j] * sigmoid_t<T>(fx4[q].w + pk[q][j].w) * ck[q][j].w;
+                    const float f0 = sigmoid_t<T>(fx4[q].x + pk[q][j].x), f1 = sigmoid_t<T>(fx4[q].y + pk[q][j].y);
+                    const float f2 = sigmoid_t<T>(fx4[q].z + pk[q][j].z), f3 = sigmoid_t<T>(fx4[q].w + pk[q][j].w);
+                    cc[q].x += wgt[q][j] * f0 * ck[q][j].x;
+                    cc[q].y += wgt[q][j] * f1 * ck[q][j].y;
+                    cc[q].z += wgt[q][j] * f2 * ck[q][j].z;
+                    cc[q].w += wgt[q][j] * f3 * ck[q][j].w;
+                    if constexpr (SAVE) {
+                        if (kidv[q][j] >= 0) {
+                            const float fv[4] = {f0, f1, f2, f3};
+                            float *dst = a.fgate + (int64_t)kidv[q][j] * a.H + unit0;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (unit0 + e < a.H) dst[e] = fv[e];
+                        }
+                    }
                 }
         }
     }
@@ -779,7 +805,7 @@ __device__ __forceinline__ void dma_gemm(const LevelArgs &a, char *lds, const in
     dma_wait_barrier<0>();       // every wave is done reading the stage buffers
 }
 
-template <typename T, int MODE>
+template <typename T, int MODE, bool SAVE = false>
 __global__ void __launch_bounds__(kDmaThreads, 2)
 level_kernel(const LevelArgs a) {
     __shared__ __attribute__((aligned(1024))) char lds[kDmaBufs * kDmaBuf];
@@ -895,7 +921,7 @@ level_kernel(const LevelArgs a) {
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
             const int r0 = wm * 64 + p * 32;
-            cell_pass<T, MODE>(a, acc[p], region, row_node + r0, row_ar + r0, row_cb + r0, row_kid + r0,
+            cell_pass<T, MODE, SAVE>(a, acc[p], region, row_node + r0, row_ar + r0, row_cb + r0, row_kid + r0,
                                col_tile * 2 + wn, lane);
         }
     }
@@ -915,7 +941,7 @@ constexpr int kThinWaves = 4;
 constexpr int kThinMaxRows = 8192; // levels up to this many rows use the thin kernel
 constexpr int kThinAhead = 8;      // K groups in flight per wave
 
-template <typename T, int MODE>
+template <typename T, int MODE, bool SAVE = false>
 __global__ void __launch_bounds__(kThinWaves * 64, 2)
 thin_kernel(const LevelArgs a) {
     constexpr int ESZ = (int)sizeof(T);
@@ -1030,7 +1056,7 @@ thin_kernel(const LevelArgs a) {
         for (int g = 1; g < (MODE == MODE_LEAF ? 3 : 4); ++g)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[g][v] = exchange[g - 1][v][lane];
-        cell_pass<T, MODE>(a, acc, region, s_node, s_ar, s_cb, s_kid, col, lane);
+        cell_pass<T, MODE, SAVE>(a, acc, region, s_node, s_ar, s_cb, s_kid, col, lane);
     }
 }
 
@@ -1119,10 +1145,10 @@ bool dims_ok(int64_t n, int64_t e, int32_t D, int32_t H, int dtype) {
     return true;
 }
 
-template <typename T>
+template <typename T, bool SAVE>
 int run_forward(const void *x, const void *W, const void *U, const float *b, const Dims &d,
-                const jitdb_schedule_t *s, void *h_out, float *c_out, const ForwardWs &w,
-                hipStream_t st) {
+                const jitdb_schedule_t *s, void *h_out, float *c_out, float *gates, float *fgate,
+                const ForwardWs &w, hipStream_t st) {
     const int L = s->n_levels;
     const int32_t *lp = s->host_level_ptr;
 
@@ -1153,6 +1179,8 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
     a.cs = w.cs ? w.cs : c_out;
     a.Hq = d.Hq;
     a.hs_out = w.hs ? w.hs : h_out;
+    a.gates = gates;
+    a.fgate = fgate;
     a.D = d.D; a.Dp = d.Dp; a.H = d.H; a.Hp = d.Hp; a.Hu = d.Hu;
     a.NPU = d.NPU;
 
@@ -1196,14 +1224,14 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
                                       : (l == 0 ? JITDB_K_LEAF : JITDB_K_INTERNAL), n_rows, st);
             if (thin) {
                 if (l == 0)
-                    thin_kernel<T, MODE_LEAF><<<a.n_blocks, kThinWaves * 64, 0, st>>>(a);
+                    thin_kernel<T, MODE_LEAF, SAVE><<<a.n_blocks, kThinWaves * 64, 0, st>>>(a);
                 else
-                    thin_kernel<T, MODE_INTERNAL><<<a.n_blocks, kThinWaves * 64, 0, st>>>(a);
+                    thin_kernel<T, MODE_INTERNAL, SAVE><<<a.n_blocks, kThinWaves * 64, 0, st>>>(a);
             } else {
                 if (l == 0)
-                    level_kernel<T, MODE_LEAF><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
+                    level_kernel<T, MODE_LEAF, SAVE><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
                 else
-                    level_kernel<T, MODE_INTERNAL><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
+                    level_kernel<T, MODE_INTERNAL, SAVE><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
             }
         }
         JITDB_LAUNCH_CHECK();
@@ -1284,16 +1312,18 @@ extern "C" size_t jitdb_treelstm_workspace_bytes(int64_t n_nodes, int64_t n_edge
     return carve_forward_ws(n_nodes, n_edges, d, nullptr).bytes;
 }
 
-extern "C" int jitdb_treelstm_forward(const void *x, const void *W, const void *U, const float *b,
-                                      int32_t D, int32_t H, jitdb_dtype dtype,
-                                      const jitdb_schedule_t *s, void *h_out, float *c_out,
-                                      void *workspace, size_t workspace_bytes, void *hip_stream) {
+namespace {
+int forward_entry(const void *x, const void *W, const void *U, const float *b, int32_t D, int32_t H,
+                  jitdb_dtype dtype, const jitdb_schedule_t *s, void *h_out, float *c_out,
+                  float *gates, float *fgate, bool save,
+                  void *workspace, size_t workspace_bytes, void *hip_stream) {
     if (!s) return JITDB_E_NULL;
     drop_stale_hip_error();
     const int64_t n = s->n_nodes;
     if (!dims_ok(n, s->n_edges, D, H, (int)dtype)) return JITDB_E_BADARG;
     if (n == 0) return JITDB_OK;
     if (!x || !W || !U || !b || !h_out || !c_out || !workspace) return JITDB_E_NULL;
+    if (save && (!gates || !fgate)) return JITDB_E_NULL;
     if (!s->perm || !s->height || !s->child_ptr || !s->child_idx || !s->host_level_ptr) return JITDB_E_NULL;
     if ((reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return JITDB_E_BADARG;
     // rows are fetched in 16-byte pieces where their stride allows
@@ -1310,7 +1340,28 @@ extern "C" int jitdb_treelstm_forward(const void *x, const void *W, const void *
     const ForwardWs w = carve_forward_ws(n, s->n_edges, d, workspace);
     if (workspace_bytes < w.bytes) return JITDB_E_WORKSPACE;
     hipStream_t st = (hipStream_t)hip_stream;
-    if (dtype == JITDB_F32)
-        return run_forward<float>(x, W, U, b, d, s, h_out, c_out, w, st);
-    return run_forward<bf16_t>(x, W, U, b, d, s, h_out, c_out, w, st);
+    if (dtype == JITDB_F32) {
+        if (save) return run_forward<float, true>(x, W, U, b, d, s, h_out, c_out, gates, fgate, w, st);
+        return run_forward<float, false>(x, W, U, b, d, s, h_out, c_out, nullptr, nullptr, w, st);
+    }
+    if (save) return run_forward<bf16_t, true>(x, W, U, b, d, s, h_out, c_out, gates, fgate, w, st);
+    return run_forward<bf16_t, false>(x, W, U, b, d, s, h_out, c_out, nullptr, nullptr, w, st);
+}
+}  // namespace
+
+extern "C" int jitdb_treelstm_forward(const void *x, const void *W, const void *U, const float *b,
+                                      int32_t D, int32_t H, jitdb_dtype dtype,
+                                      const jitdb_schedule_t *s, void *h_out, float *c_out,
+                                      void *workspace, size_t workspace_bytes, void *hip_stream) {
+    return forward_entry(x, W, U, b, D, H, dtype, s, h_out, c_out, nullptr, nullptr, false,
+                         workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" int jitdb_treelstm_forward_train(const void *x, const void *W, const void *U, const float *b,
+                                            int32_t D, int32_t H, jitdb_dtype dtype,
+                                            const jitdb_schedule_t *s, void *h_out, float *c_out,
+                                            float *gates_out, float *fgate_out,
+                                            void *workspace, size_t workspace_bytes, void *hip_stream) {
+    return forward_entry(x, W, U, b, D, H, dtype, s, h_out, c_out, gates_out, fgate_out, true,
+                         workspace, workspace_bytes, hip_stream);
 }
