@@ -84,3 +84,84 @@ def test_backward_against_the_gradient_oracle(kind, D, H, dtype):
     print("   relative-to-max errors:", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
     for k, v in errs.items():
         assert v <= tol, (k, v)
+
+
+def _sampled_backward_check(cfg, n_sample, dtype, D=None, H=None):
+    """Full-size forest on the GPU; cotangents are non-zero only on sampled trees, so that the
+    oracle, run on those trees alone, predicts every output: dx on their rows (zero elsewhere)
+    and dW, dU, db in full.  Saved activations are checked on the same rows."""
+    from workloads import CONFIGS, tree_ranges
+    cfgo = CONFIGS[cfg]
+    parent = make_forest(cfg)
+    n = len(parent)
+    x, W, U, b = make_values(cfg, n, "random", D=D, H=H)
+    H_ = U.shape[1]
+    r = tree_ranges(parent)
+    T_ = len(r) - 1
+    rng = np.random.default_rng(123)
+    pick = np.unique(np.concatenate([rng.choice(T_, size=min(n_sample, T_), replace=False),
+                                     [int(np.argmax(np.diff(r)))], np.arange(min(4, T_))]))
+    rows = np.concatenate([np.arange(r[t], r[t + 1]) for t in pick])
+    gh = np.zeros((n, H_), dtype=np.float32); gc = np.zeros((n, H_), dtype=np.float32)
+    gh[rows] = rng.standard_normal((len(rows), H_)).astype(np.float32)
+    gc[rows] = rng.standard_normal((len(rows), H_)).astype(np.float32)
+    print(f"backward cfg={cfg} dtype={dtype} D={x.shape[1]} H={H_} N={n}, cotangents on {len(pick)} trees "
+          f"({len(rows)} nodes)", flush=True)
+    dev, seen = _upload(x, W, U, b, dtype)
+    s = J.jitdb_schedule(torch.from_numpy(parent).cuda())
+    h, c, gates, fgate = J.jitdb_treelstm_forward_train(*dev, s)
+    dx, dW, dU, db = J.jitdb_treelstm_backward(dev[0], dev[1], dev[2], s, h, c, gates, fgate,
+                                               torch.from_numpy(gh).cuda(), torch.from_numpy(gc).cuda())
+    torch.cuda.synchronize()
+    # oracle on the sampled trees, re-based to a forest of their own
+    sub, off = [], 0
+    for t in pick:
+        p = parent[r[t]:r[t + 1]].astype(np.int64)
+        sub.append(np.where(p < 0, -1, p - r[t] + off)); off += r[t + 1] - r[t]
+    sub = np.concatenate(sub).astype(np.int32)
+    xo, Wo, Uo, bo = seen
+    ho, co, rx, rW, rU, rb = B.forward_backward(sub, xo[rows], Wo, Uo, bo, gh[rows], gc[rows])
+    _, _, go, fo = B.forward_saved(sub, xo[rows], Wo, Uo, bo)
+    tol = TOL[dtype]
+    dxn = dx.cpu().numpy()
+    errs = {"dx": _rel(dxn[rows], rx), "dW": _rel(dW.cpu().numpy(), rW), "dU": _rel(dU.cpu().numpy(), rU),
+            "db": _rel(db.cpu().numpy(), rb), "gates": float(np.abs(gates.cpu().numpy()[rows] - go).max())}
+    hp = sub >= 0
+    errs["fgate"] = float(np.abs(fgate.cpu().numpy()[rows][hp] - fo[hp]).max())
+    print("   errors:", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+    mask = np.ones(n, dtype=bool); mask[rows] = False
+    assert not dxn[mask].any()                      # no cotangent reaches the other trees
+    for k, v in errs.items():
+        assert v <= tol, (k, v)
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("cfg,dtype,n_sample", [(3, "bf16", 200), (3, "f32", 200), (4, "f32", 120), (5, "bf16", 24)])
+def test_backward_at_full_size_with_cotangents_on_sampled_trees(cfg, dtype, n_sample):
+    _sampled_backward_check(cfg, n_sample, dtype)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_backward_odd_sizes_on_large_levels(dtype):
+    _sampled_backward_check(3, 100, dtype, D=52, H=100)
+
+
+def test_backward_without_cotangents_and_on_an_empty_forest():
+    parent = make_forest(1)
+    n = len(parent)
+    x, W, U, b = make_values(1, n, "random")
+    dev, _ = _upload(x, W, U, b, "f32")
+    s = J.jitdb_schedule(torch.from_numpy(parent).cuda())
+    h, c, gates, fgate = J.jitdb_treelstm_forward_train(*dev, s)
+    print("backward with gh = gc = None", flush=True)
+    dx, dW, dU, db = J.jitdb_treelstm_backward(dev[0], dev[1], dev[2], s, h, c, gates, fgate)
+    torch.cuda.synchronize()
+    assert not dx.any() and not dW.any() and not dU.any() and not db.any()
+    print("backward on an empty forest", flush=True)
+    e = J.jitdb_schedule(torch.zeros(0, dtype=torch.int32, device="cuda"))
+    z = lambda *shape: torch.zeros(shape, device="cuda")
+    dx, dW, dU, db = J.jitdb_treelstm_backward(z(0, 300), dev[1], dev[2], e, z(0, 150), z(0, 150), z(0, 450), z(0, 150),
+                                               out=(z(0, 300), torch.ones(600, 300, device="cuda"),
+                                                    torch.ones(600, 150, device="cuda"), torch.ones(600, device="cuda")))
+    torch.cuda.synchronize()
+    assert not dW.any() and not dU.any() and not db.any()
