@@ -165,8 +165,9 @@ def build(verbose: bool = False) -> str:
     _check_no_scratch(lines)
     if asm_text is None:
         raise RuntimeError("the device assembly of forward.hip was not produced; cannot check it")
-    if check_lds_read_waits(asm_text) == 0:
-        raise RuntimeError("no LDS reads found in the level kernel's assembly: the check is not looking at it")
+    for name in ("level_kernel", "gemm_kb_kernel"):      # the kernels built on the asm-read GEMM core
+        if check_lds_read_waits(asm_text, name) == 0:
+            raise RuntimeError(f"no LDS reads found in the assembly of {name}: the check is not looking at it")
     if verbose and out.strip():
         print(out)
     return LIB

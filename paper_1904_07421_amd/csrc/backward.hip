@@ -71,13 +71,13 @@ fill_bytes16_kernel(u32x4 *p, int64_t n16) {
 }
 
 // ---- weights for the data-gradient GEMMs ---------------------------------------------
-// Mt [D + H rows, 4 Hk]: row n < D is column n of W, row D + n' column n' of U, the four gates
+// Mt [D + H rows, 4 Hk] (K-blocked, for the tiled GEMM): row n < D is column n of W, row D + n' column n' of U, the four gates
 // side by side at stride Hk (H rounded up, pad zero); the forget gate has no h-sum part, so
 // its block is zero in the rows of U.  Uft [H rows, Hk]: row n = column n of U_f.
 template <typename T>
 __global__ void __launch_bounds__(kT)
 pack_bwd_weights_kernel(const T *__restrict__ W, const T *__restrict__ U, int D, int H, int Hk,
-                        T *__restrict__ Mt, T *__restrict__ Uft) {
+                        T *__restrict__ Mt, int64_t mt_rows_alloc, T *__restrict__ Uft) {
     const int64_t total = (int64_t)(D + H) * 4 * Hk;
     for (int64_t idx = (int64_t)blockIdx.x * kT + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * kT) {
         const int n = (int)(idx / (4 * Hk)), k = (int)(idx % (4 * Hk));
@@ -87,7 +87,7 @@ pack_bwd_weights_kernel(const T *__restrict__ W, const T *__restrict__ U, int D,
             if (n < D) v = W[((int64_t)g * H + m) * D + n];
             else if (g < 3) v = U[((int64_t)g * H + m) * H + (n - D)];
         }
-        Mt[idx] = v;
+        *reinterpret_cast<T *>(reinterpret_cast<char *>(Mt) + operand_offset(n, (int64_t)k * sizeof(T), mt_rows_alloc)) = v;
     }
     const int64_t total_f = (int64_t)H * Hk;
     for (int64_t idx = (int64_t)blockIdx.x * kT + threadIdx.x; idx < total_f; idx += (int64_t)gridDim.x * kT) {
@@ -107,10 +107,17 @@ bwd_cell_kernel(const int32_t *__restrict__ nodes, int n_rows, int H, int Hk,
                 const int32_t *__restrict__ child_ptr, const int32_t *__restrict__ child_idx,
                 const float *__restrict__ c, const float *__restrict__ gates, const float *__restrict__ fgate,
                 const float *__restrict__ dh, float *__restrict__ dc,
-                T *__restrict__ dZ, T *__restrict__ G) {
+                T *__restrict__ dZ, int64_t dz_rows_alloc, T *__restrict__ G) {
     const int64_t id = (int64_t)blockIdx.x * kT + threadIdx.x;
-    if (id >= (int64_t)n_rows * H) return;
-    const int r = (int)(id / H), m = (int)(id % H);
+    if (id >= (int64_t)n_rows * Hk) return;
+    const int r = (int)(id / Hk), m = (int)(id % Hk);
+    char *zb = reinterpret_cast<char *>(dZ);
+    if (m >= H) {       // pad columns of the K-blocked operand
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+            *reinterpret_cast<T *>(zb + operand_offset(r, (int64_t)(g * Hk + m) * sizeof(T), dz_rows_alloc)) = T(0);
+        return;
+    }
     const int64_t j = nodes[r];
     const float gi = gates[j * 3 * H + m], go = gates[j * 3 * H + H + m], gu = gates[j * 3 * H + 2 * H + m];
     const float t = tanhf(c[j * H + m]);
@@ -129,11 +136,10 @@ bwd_cell_kernel(const int32_t *__restrict__ nodes, int n_rows, int H, int Hk,
         G[k * Hk + m] = from_f32<T>(dzf);
         dc[k * H + m] += dcj * fk;
     }
-    T *z = dZ + (int64_t)r * 4 * Hk + m;
-    z[0] = from_f32<T>(dzi);
-    z[Hk] = from_f32<T>(dzo);
-    z[2 * Hk] = from_f32<T>(dzu);
-    z[3 * Hk] = from_f32<T>(dzf_sum);
+    const float dz[4] = {dzi, dzo, dzu, dzf_sum};
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+        *reinterpret_cast<T *>(zb + operand_offset(r, (int64_t)(g * Hk + m) * sizeof(T), dz_rows_alloc)) = from_f32<T>(dz[g]);
 }
 
 // dh_k += dhs_r for every child k of the node in level row r
@@ -167,10 +173,14 @@ bwd_hsum_kernel(const int32_t *__restrict__ nodes, int n_rows, int H,
 // ---- transpose with an optional row gather -------------------------------------------
 // dst[c][r] = src[row(r)][c] for r < n_rows, 0 for n_rows <= r < ld_dst (the reduction axis
 // of the weight-gradient GEMMs is padded with zeros).  row(r) = index[r] or r.
+// The destination is a K-blocked operand (dst_rows_alloc rows per slab) whose K axis is r, padded
+// with zeros up to k_pad; the source is row-major with stride ld_src, or K-blocked itself when
+// src_rows_alloc > 0.
 template <typename T>
 __global__ void __launch_bounds__(kT)
 transpose_rows_kernel(const T *__restrict__ src, const int32_t *__restrict__ index, int64_t ld_src,
-                      int n_rows, int n_cols, T *__restrict__ dst, int64_t ld_dst) {
+                      int64_t src_rows_alloc, int n_rows, int n_cols, T *__restrict__ dst,
+                      int64_t dst_rows_alloc, int k_pad) {
     __shared__ T tile[32][33];
     const int r0 = blockIdx.x * 32, c0 = blockIdx.y * 32;
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;     // 32 x 8
@@ -180,7 +190,11 @@ transpose_rows_kernel(const T *__restrict__ src, const int32_t *__restrict__ ind
         T v = T(0);
         if (r < n_rows && cc < n_cols) {
             const int64_t row = index ? index[r] : r;
-            v = src[row * ld_src + cc];
+            if (src_rows_alloc > 0)
+                v = *reinterpret_cast<const T *>(reinterpret_cast<const char *>(src) +
+                                                 operand_offset(row, (int64_t)cc * sizeof(T), src_rows_alloc));
+            else
+                v = src[row * ld_src + cc];
         }
         tile[ty + 8 * i][tx] = v;
     }
@@ -188,18 +202,21 @@ transpose_rows_kernel(const T *__restrict__ src, const int32_t *__restrict__ ind
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int cc = c0 + ty + 8 * i, r = r0 + tx;
-        if (cc < n_cols && r < ld_dst) dst[(int64_t)cc * ld_dst + r] = tile[tx][ty + 8 * i];
+        if (cc < n_cols && r < k_pad)
+            *reinterpret_cast<T *>(reinterpret_cast<char *>(dst) +
+                                   operand_offset(cc, (int64_t)r * sizeof(T), dst_rows_alloc)) = tile[tx][ty + 8 * i];
     }
 }
 
 // db_p += sum over the row of dZt (fp32 sum of the operand values)
 template <typename T>
 __global__ void __launch_bounds__(kT)
-rowsum_kernel(const T *__restrict__ src, int64_t ld, int n, float *__restrict__ out) {
+rowsum_kernel(const T *__restrict__ src, int64_t rows_alloc, int n, float *__restrict__ out) {
     __shared__ float part[kT];
-    const T *row = src + (int64_t)blockIdx.x * ld;
     float s = 0.0f;
-    for (int i = threadIdx.x; i < n; i += kT) s += to_f32<T>(row[i]);
+    for (int i = threadIdx.x; i < n; i += kT)
+        s += to_f32<T>(*reinterpret_cast<const T *>(reinterpret_cast<const char *>(src) +
+                                                    operand_offset(blockIdx.x, (int64_t)i * sizeof(T), rows_alloc)));
     part[threadIdx.x] = s;
     __syncthreads();
     for (int d = kT / 2; d > 0; d >>= 1) {
@@ -230,15 +247,17 @@ struct EpiAddRows {        // dst[node[row]] += v
         dst[(int64_t)node[row] * ld + col] += v;
     }
 };
-struct EpiAcc {            // C += v
+struct EpiAtomicAcc {      // C += v, from several blocks that split the reduction axis
     float *C; int ldc;
-    __device__ __forceinline__ void operator()(int row, int col, float v) const { C[(int64_t)row * ldc + col] += v; }
+    __device__ __forceinline__ void operator()(int row, int col, float v) const {
+        atomicAdd(&C[(int64_t)row * ldc + col], v);
+    }
 };
 
 template <typename T, typename Epi>
 __global__ void __launch_bounds__(kT, 2)
 gemm_nt_kernel(const T *__restrict__ A, const int32_t *__restrict__ a_index, int64_t lda, int M,
-               const T *__restrict__ B, int64_t ldb, int N, int K, Epi epi) {
+               const T *__restrict__ B, int64_t ldb, int N, int K, int k_chunk, Epi epi) {
     constexpr int ESZ = (int)sizeof(T);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int hf = lane >> 5, l32 = lane & 31;
@@ -248,15 +267,18 @@ gemm_nt_kernel(const T *__restrict__ A, const int32_t *__restrict__ a_index, int
     int ar = m0 + l32;
     if (ar >= M) ar = M - 1;
     const int64_t arow = a_index ? a_index[ar] : ar;
-    const char *ap = reinterpret_cast<const char *>(A) + arow * lda * ESZ + hf * 16;
+    // blockIdx.z takes the K range [z * k_chunk, min(K, (z + 1) * k_chunk))
+    const int64_t k_begin = (int64_t)blockIdx.z * k_chunk;
+    const int k_len = (int)((K - k_begin) < k_chunk ? (K - k_begin) : k_chunk);
+    const char *ap = reinterpret_cast<const char *>(A) + (arow * lda + k_begin) * ESZ + hf * 16;
     const char *bp[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         int br = n0 + q * 32 + l32;
         if (br >= N) br = N - 1;
-        bp[q] = reinterpret_cast<const char *>(B) + (int64_t)br * ldb * ESZ + hf * 16;
+        bp[q] = reinterpret_cast<const char *>(B) + ((int64_t)br * ldb + k_begin) * ESZ + hf * 16;
     }
-    const int n_groups = K * ESZ / 32;
+    const int n_groups = k_len * ESZ / 32;
     floatx16 acc[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q)
@@ -294,14 +316,27 @@ gemm_nt_kernel(const T *__restrict__ A, const int32_t *__restrict__ a_index, int
     }
 }
 
+// k_splits > 1 cuts the reduction axis into that many ranges (multiples of 64 elements) handled
+// by different blocks; the epilogue must then add atomically.
 template <typename T, typename Epi>
 int launch_gemm_nt(const T *A, const int32_t *a_index, int64_t lda, int M, const T *B, int64_t ldb, int N, int K,
-                   Epi epi, hipStream_t st) {
+                   Epi epi, hipStream_t st, int k_splits = 1) {
     if (M <= 0 || N <= 0 || K <= 0) return JITDB_OK;
-    dim3 grid((unsigned)ceil_div(M, 128), (unsigned)ceil_div(N, 128));
-    gemm_nt_kernel<T, Epi><<<grid, kT, 0, st>>>(A, a_index, lda, M, B, ldb, N, K, epi);
+    int k_chunk = K;
+    if (k_splits > 1) k_chunk = (int)round_up(ceil_div(K, k_splits), 64);
+    dim3 grid((unsigned)ceil_div(M, 128), (unsigned)ceil_div(N, 128), (unsigned)ceil_div(K, k_chunk));
+    gemm_nt_kernel<T, Epi><<<grid, kT, 0, st>>>(A, a_index, lda, M, B, ldb, N, K, k_chunk, epi);
     JITDB_LAUNCH_CHECK();
     return JITDB_OK;
+}
+
+// enough ranges of the reduction axis to give every SIMD several waves, none shorter than 512
+inline int splits_for(int M, int N, int K) {
+    const int64_t tiles = ceil_div(M, 128) * ceil_div(N, 128);
+    int64_t want = ceil_div(4096, tiles);
+    const int64_t most = K / 512 > 0 ? K / 512 : 1;
+    if (want > most) want = most;
+    return (int)(want < 1 ? 1 : want);
 }
 
 // dW [4H, D], dU [4H, H], db [4H] from the packed accumulators (gate stride Hk)
@@ -340,15 +375,15 @@ BwdWs carve_bwd_ws(int64_t n, const BwdDims &d, void *base) {
     w.dMp = c.take<float>((size_t)4 * d.Hk * (d.D + d.H));
     w.dUfp = c.take<float>((size_t)d.Hk * d.H);
     w.dbp = c.take<float>((size_t)4 * d.Hk);
-    w.Mt = c.take<char>((size_t)(d.D + d.H) * 4 * d.Hk * d.esz);
+    w.Mt = c.take<char>((size_t)round_up(d.D + d.H, 256) * 4 * d.Hk * d.esz);
     w.Uft = c.take<char>((size_t)d.H * d.Hk * d.esz);
-    w.dZ = c.take<char>((size_t)d.n_max * 4 * d.Hk * d.esz);
+    w.dZ = c.take<char>((size_t)round_up(d.n_max, 128) * 4 * d.Hk * d.esz);
     w.G = c.take<char>((size_t)n * d.Hk * d.esz);
     w.hs = c.take<char>((size_t)d.n_max * d.H * d.esz);
-    w.dZt = c.take<char>((size_t)4 * d.Hk * d.n_pad * d.esz);
-    w.At = c.take<char>((size_t)(d.D + d.H) * d.n_pad * d.esz);
-    w.Gt = c.take<char>((size_t)d.Hk * d.n_pad * d.esz);
-    w.Hkt = c.take<char>((size_t)d.H * d.n_pad * d.esz);
+    w.dZt = c.take<char>((size_t)round_up(4 * d.Hk, 128) * d.n_pad * d.esz);
+    w.At = c.take<char>((size_t)round_up(d.D + d.H, 256) * d.n_pad * d.esz);
+    w.Gt = c.take<char>((size_t)round_up(d.Hk, 128) * d.n_pad * d.esz);
+    w.Hkt = c.take<char>((size_t)round_up(d.H, 256) * d.n_pad * d.esz);
     w.bytes = c.off;
     return w;
 }
@@ -380,11 +415,13 @@ int run_backward(const T *x, const T *W, const T *U, const BwdDims &d, const jit
     }
     // pad columns and the rows of roots must read as zero
     if ((rc = zero_bytes(w.G, round_up((size_t)n * Hk * d.esz, 256), st)) != JITDB_OK) return rc;
-    if ((rc = zero_bytes(w.dZ, round_up((size_t)d.n_max * 4 * Hk * d.esz, 256), st)) != JITDB_OK) return rc;
     if ((rc = zero_bytes(w.dMp, round_up((size_t)4 * Hk * (D + H) * 4, 256), st)) != JITDB_OK) return rc;
     if ((rc = zero_bytes(w.dUfp, round_up((size_t)Hk * H * 4, 256), st)) != JITDB_OK) return rc;
     if ((rc = zero_bytes(w.dbp, round_up((size_t)4 * Hk * 4, 256), st)) != JITDB_OK) return rc;
-    pack_bwd_weights_kernel<T><<<1024, kT, 0, st>>>(W, U, D, H, Hk, static_cast<T *>(w.Mt), static_cast<T *>(w.Uft));
+    const int64_t mt_alloc = round_up(D + H, 256), zt_alloc = round_up(4 * Hk, 128), at_alloc = round_up(D + H, 256);
+    const int64_t gt_alloc = round_up(Hk, 128), ht_alloc = round_up(H, 256);
+    const jitdb_dtype dtype = sizeof(T) == 4 ? JITDB_F32 : JITDB_BF16;
+    pack_bwd_weights_kernel<T><<<1024, kT, 0, st>>>(W, U, D, H, Hk, static_cast<T *>(w.Mt), mt_alloc, static_cast<T *>(w.Uft));
     JITDB_LAUNCH_CHECK();
 
     T *dZ = static_cast<T *>(w.dZ), *G = static_cast<T *>(w.G), *hs = static_cast<T *>(w.hs);
@@ -394,26 +431,44 @@ int run_backward(const T *x, const T *W, const T *U, const BwdDims &d, const jit
         if (rows <= 0) return JITDB_E_SCHEDULE;
         const int32_t *nodes = s->perm + lp[l];
         const int kpad = (int)round_up(rows, 64);           // reduction length of the weight GEMMs
+        const int64_t dz_alloc = round_up(rows, 128);
         const unsigned g_elem = (unsigned)ceil_div((int64_t)rows * H, kT);
-        const dim3 t_grid_rows((unsigned)ceil_div(kpad, 32), 1);
+        const unsigned g_elem_k = (unsigned)ceil_div((int64_t)rows * Hk, kT);
+        const unsigned tr = (unsigned)ceil_div(kpad, 32);
+        auto weight_gemm = [&](const T *A, int64_t a_alloc, int M, const T *B, int64_t b_alloc, int N, float *C, int ldc) {
+            KbGemm g = {};
+            g.A = A; g.a_rows_alloc = a_alloc; g.M = M; g.B = B; g.b_rows_alloc = b_alloc; g.N = N;
+            g.k_bytes = (int64_t)kpad * sizeof(T);
+            const int64_t tiles = ceil_div(M, 128) * ceil_div(N, 256);
+            int64_t want = ceil_div(2048, tiles);
+            const int64_t most = kpad / 512 > 0 ? kpad / 512 : 1;
+            g.k_splits = (int)(want < most ? want : most);
+            g.epilogue = KB_EPI_ATOMIC_ACC; g.out0 = C; g.ldc = ldc;
+            return launch_kb_gemm(dtype, g, st);
+        };
         if (l < L - 1) {
             // these nodes may have parents: dh_k += G_k U_f, and dU_f += sum_k G_k (x) h_k
             if ((rc = launch_gemm_nt<T>(G, nodes, Hk, rows, static_cast<const T *>(w.Uft), Hk, H, Hk,
                                         EpiAddRows{w.dh, nodes, H}, st)) != JITDB_OK) return rc;
-            transpose_rows_kernel<T><<<dim3((unsigned)ceil_div(kpad, 32), (unsigned)ceil_div(Hk, 32)), kT, 0, st>>>(
-                G, nodes, Hk, rows, Hk, Gt, d.n_pad);
+            transpose_rows_kernel<T><<<dim3(tr, (unsigned)ceil_div(Hk, 32)), kT, 0, st>>>(
+                G, nodes, Hk, 0, rows, Hk, Gt, gt_alloc, kpad);
             JITDB_LAUNCH_CHECK();
-            transpose_rows_kernel<T><<<dim3((unsigned)ceil_div(kpad, 32), (unsigned)ceil_div(H, 32)), kT, 0, st>>>(
-                h, nodes, H, rows, H, Hkt, d.n_pad);
+            transpose_rows_kernel<T><<<dim3(tr, (unsigned)ceil_div(H, 32)), kT, 0, st>>>(
+                h, nodes, H, 0, rows, H, Hkt, ht_alloc, kpad);
             JITDB_LAUNCH_CHECK();
-            if ((rc = launch_gemm_nt<T>(Gt, nullptr, d.n_pad, Hk, Hkt, d.n_pad, H, kpad,
-                                        EpiAcc{w.dUfp, H}, st)) != JITDB_OK) return rc;
+            if ((rc = weight_gemm(Gt, gt_alloc, Hk, Hkt, ht_alloc, H, w.dUfp, H)) != JITDB_OK) return rc;
         }
-        bwd_cell_kernel<T><<<g_elem, kT, 0, st>>>(nodes, rows, H, Hk, s->child_ptr, s->child_idx, c, gates, fgate,
-                                                  w.dh, w.dc, dZ, G);
+        bwd_cell_kernel<T><<<g_elem_k, kT, 0, st>>>(nodes, rows, H, Hk, s->child_ptr, s->child_idx, c, gates, fgate,
+                                                    w.dh, w.dc, dZ, dz_alloc, G);
         JITDB_LAUNCH_CHECK();
-        if ((rc = launch_gemm_nt<T>(dZ, nullptr, 4 * Hk, rows, static_cast<const T *>(w.Mt), 4 * Hk, D + H, 4 * Hk,
-                                    EpiDxDhs{dx, nodes, D, w.dhs, H}, st)) != JITDB_OK) return rc;
+        {   // [dx | dhs] = dZ [W | U]
+            KbGemm g = {};
+            g.A = dZ; g.a_rows_alloc = dz_alloc; g.M = rows;
+            g.B = w.Mt; g.b_rows_alloc = mt_alloc; g.N = D + H;
+            g.k_bytes = (int64_t)4 * Hk * sizeof(T); g.k_splits = 1;
+            g.epilogue = KB_EPI_DX_DHS; g.out0 = dx; g.out1 = w.dhs; g.node = nodes; g.D = D; g.H = H;
+            if ((rc = launch_kb_gemm(dtype, g, st)) != JITDB_OK) return rc;
+        }
         if (l > 0) {
             bwd_scatter_kernel<<<g_elem, kT, 0, st>>>(nodes, rows, H, s->child_ptr, s->child_idx, w.dhs, w.dh);
             JITDB_LAUNCH_CHECK();
@@ -421,24 +476,23 @@ int run_backward(const T *x, const T *W, const T *U, const BwdDims &d, const jit
             JITDB_LAUNCH_CHECK();
         }
         // weight gradients: dMp += dZ^T [x | hs] (leaves have hs = 0: the x columns only)
-        transpose_rows_kernel<T><<<dim3((unsigned)ceil_div(kpad, 32), (unsigned)ceil_div(4 * Hk, 32)), kT, 0, st>>>(
-            dZ, nullptr, 4 * Hk, rows, 4 * Hk, dZt, d.n_pad);
+        transpose_rows_kernel<T><<<dim3(tr, (unsigned)ceil_div(4 * Hk, 32)), kT, 0, st>>>(
+            dZ, nullptr, 0, dz_alloc, rows, 4 * Hk, dZt, zt_alloc, kpad);
         JITDB_LAUNCH_CHECK();
-        transpose_rows_kernel<T><<<dim3((unsigned)ceil_div(kpad, 32), (unsigned)ceil_div(D, 32)), kT, 0, st>>>(
-            x, nodes, D, rows, D, At, d.n_pad);
+        transpose_rows_kernel<T><<<dim3(tr, (unsigned)ceil_div(D, 32)), kT, 0, st>>>(
+            x, nodes, D, 0, rows, D, At, at_alloc, kpad);
         JITDB_LAUNCH_CHECK();
         int q_cols = D;
         if (l > 0) {
-            transpose_rows_kernel<T><<<dim3((unsigned)ceil_div(kpad, 32), (unsigned)ceil_div(H, 32)), kT, 0, st>>>(
-                hs, nullptr, H, rows, H, At + (int64_t)D * d.n_pad, d.n_pad);
+            transpose_rows_kernel<T><<<dim3(tr, (unsigned)ceil_div(H, 32)), kT, 0, st>>>(
+                hs, nullptr, H, 0, rows, H,
+                reinterpret_cast<T *>(reinterpret_cast<char *>(At) + (int64_t)D * 64), at_alloc, kpad);
             JITDB_LAUNCH_CHECK();
             q_cols = D + H;
         }
-        if ((rc = launch_gemm_nt<T>(dZt, nullptr, d.n_pad, 4 * Hk, At, d.n_pad, q_cols, kpad,
-                                    EpiAcc{w.dMp, D + H}, st)) != JITDB_OK) return rc;
-        rowsum_kernel<T><<<4 * Hk, kT, 0, st>>>(dZt, d.n_pad, rows, w.dbp);
+        if ((rc = weight_gemm(dZt, zt_alloc, 4 * Hk, At, at_alloc, q_cols, w.dMp, D + H)) != JITDB_OK) return rc;
+        rowsum_kernel<T><<<4 * Hk, kT, 0, st>>>(dZt, zt_alloc, rows, w.dbp);
         JITDB_LAUNCH_CHECK();
-        (void)t_grid_rows;
     }
     unpack_grads_kernel<<<1024, kT, 0, st>>>(w.dMp, w.dUfp, w.dbp, D, H, Hk, dW, dU, db);
     JITDB_LAUNCH_CHECK();

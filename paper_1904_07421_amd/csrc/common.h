@@ -47,4 +47,28 @@ void note_hip_failure(hipError_t e, const char *file, int line);
 // that the launch checks only see this library's own launches.
 inline void drop_stale_hip_error() { (void)hipGetLastError(); }
 
+// K-blocked operand layout of the tiled GEMM core: bytes [64 s, 64 s + 64) of every row form
+// slab s, rows consecutive inside a slab (n_rows_alloc rows per slab).  Byte offset of byte
+// `kbyte` of row `row`.
+__host__ __device__ __forceinline__ int64_t operand_offset(int64_t row, int64_t kbyte, int64_t n_rows_alloc) {
+    return ((kbyte >> 6) * n_rows_alloc + row) * 64 + (kbyte & 63);
+}
+
+// C = A B^T on the tiled GEMM core of the level kernel (128 x 256 tiles, stages straight into
+// LDS), for operands in the K-blocked layout above.  A has M rows (a_rows_alloc >= M rounded up
+// to 128 per slab), B has N rows (b_rows_alloc >= N rounded up to 256); K is k_bytes / element
+// size, k_bytes a multiple of 128.  k_splits > 1 deals ranges of K to different blocks.
+enum KbEpilogue : int {
+    KB_EPI_DX_DHS = 0,       // col < D: out0[node[row] * D + col] = v, else out1[row * H + col - D] = v
+    KB_EPI_ATOMIC_ACC = 1    // atomicAdd(out0[row * ldc + col], v)
+};
+struct KbGemm {
+    const void *A; int64_t a_rows_alloc; int M;
+    const void *B; int64_t b_rows_alloc; int N;
+    int64_t k_bytes; int k_splits;
+    int epilogue;
+    float *out0; float *out1; const int32_t *node; int D; int H; int ldc;
+};
+int launch_kb_gemm(jitdb_dtype dtype, const KbGemm &g, hipStream_t st);
+
 }  // namespace jitdb

@@ -50,7 +50,7 @@ constexpr int kGateTile = 128;  // packed rows per unit tile (4 gates x 32 units
 
 constexpr int kEpiStride = 40;  // floats per row of a wave's epilogue region: 32 units + 8; rows 4 apart fall 32 banks apart
 
-enum : int { MODE_LEAF = 0, MODE_INTERNAL = 1, MODE_PROJ = 2 };
+enum : int { MODE_LEAF = 0, MODE_INTERNAL = 1, MODE_PROJ = 2, MODE_GENERIC = 3 };   // GENERIC: plain C = A B^T
 
 template <typename T> struct Traits;
 template <> struct Traits<float> {
@@ -69,9 +69,7 @@ template <> struct Traits<bf16_t> {
 // K per row, so the 16 rows x 64 bytes that one direct-to-LDS load instruction moves are
 // 1 KB of consecutive memory, whole 128-byte lines.  (Fetching half a line now and the
 // other half a stage later costs a full line transfer from L2 each time.)
-__host__ __device__ __forceinline__ int64_t operand_offset(int64_t row, int64_t kbyte, int64_t n_rows_alloc) {
-    return ((kbyte >> 6) * n_rows_alloc + row) * 64 + (kbyte & 63);
-}
+// (operand_offset itself is in common.h: the backward pass writes operands in the same layout)
 
 // ---- scalar helpers ----------------------------------------------------------------
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float((uint32_t)v << 16); }
@@ -927,6 +925,69 @@ level_kernel(const LevelArgs a) {
     }
 }
 
+// ---- the same GEMM core as a plain C = A B^T ------------------------------------------
+// For the backward pass: both operands K-blocked, all four column groups multiplied in every
+// stage, no cell update.  blockIdx.y selects a range of K stages (split reduction); an output
+// element goes to the epilogue named in the arguments.
+struct KbEpiArgs {
+    int kind;
+    float *out0; float *out1; const int32_t *node; int D; int H; int ldc;
+    int M, N;
+    int stages_total, stages_per_split;
+};
+
+template <typename T>
+__global__ void __launch_bounds__(kDmaThreads, 2)
+gemm_kb_kernel(LevelArgs a, const KbEpiArgs e) {
+    __shared__ __attribute__((aligned(1024))) char lds[kDmaBufs * kDmaBuf];
+    __shared__ __attribute__((aligned(256))) char sink[4 * 256];
+    const int t = threadIdx.x;
+    const int lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int hf = lane >> 5, l32 = lane & 31;
+    int row_tile, col_tile;
+    if (!block_to_tile(blockIdx.x, a.n_row_tiles, a.n_col_tiles, row_tile, col_tile)) return;
+    const int tile_row0 = row_tile * kDmaBM;
+    // this block's range of K stages
+    const int s0 = blockIdx.y * e.stages_per_split;
+    int n_st = e.stages_total - s0;
+    if (n_st > e.stages_per_split) n_st = e.stages_per_split;
+    a.stack = static_cast<const char *>(a.stack) + (int64_t)s0 * a.n_rows_alloc * kDmaStage;
+    a.Bp = static_cast<const char *>(a.Bp) + (int64_t)s0 * a.NPU * kDmaStage;
+    a.Dp = n_st * kDmaStage / (int)sizeof(T);
+    a.Hp = 0;
+
+    floatx16 acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][g][v] = 0.0f;
+    dma_gemm<T, MODE_GENERIC>(a, lds, nullptr, tile_row0, col_tile, acc, sink, []() {});
+
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int col = col_tile * kBN + wn * 128 + g * 32 + l32;
+            if (col >= e.N) continue;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = tile_row0 + wm * 64 + i * 32 + (v >> 2) * 8 + hf * 4 + (v & 3);
+                if (row >= e.M) continue;
+                const float val = acc[i][g][v];
+                if (e.kind == KB_EPI_DX_DHS) {
+                    if (col < e.D) e.out0[(int64_t)e.node[row] * e.D + col] = val;
+                    else e.out1[(int64_t)row * e.H + (col - e.D)] = val;
+                } else {
+                    atomicAdd(&e.out0[(int64_t)row * e.ldc + col], val);
+                }
+            }
+        }
+}
+
 // ---- thin levels ---------------------------------------------------------------------
 // A level with a few thousand rows gives the 128 x 256 tiles too few blocks to fill 256
 // CUs, and each block then runs a whole K loop back to back: the level costs that
@@ -1255,6 +1316,37 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
 }
 
 }  // namespace
+
+int launch_kb_gemm(jitdb_dtype dtype, const KbGemm &g, hipStream_t st) {
+    if (g.M <= 0 || g.N <= 0 || g.k_bytes <= 0) return JITDB_OK;
+    if (g.k_bytes % 128 != 0) return JITDB_E_BADARG;
+    LevelArgs a = {};
+    a.stack = g.A;
+    a.n_rows_alloc = (int)g.a_rows_alloc;
+    a.Bp = g.B;
+    a.NPU = (int)g.b_rows_alloc;
+    a.n_rows = g.M;
+    a.n_row_tiles = (int)ceil_div(g.M, kDmaBM);
+    a.n_col_tiles = (int)ceil_div(g.N, kBN);
+    a.n_blocks = 8 * (int)ceil_div(a.n_row_tiles, 8) * a.n_col_tiles;
+    KbEpiArgs e;
+    e.kind = g.epilogue; e.out0 = g.out0; e.out1 = g.out1; e.node = g.node; e.D = g.D; e.H = g.H; e.ldc = g.ldc;
+    e.M = g.M; e.N = g.N;
+    e.stages_total = (int)(g.k_bytes / kDmaStage);
+    // ranges of at least two stages (the pipeline's minimum); the last one may be shorter but
+    // not a single stage, in which case the ranges are made a stage longer
+    int splits = g.k_splits < 1 ? 1 : g.k_splits;
+    e.stages_per_split = (int)ceil_div(e.stages_total, splits);
+    if (e.stages_per_split < 2) e.stages_per_split = 2;
+    while (e.stages_per_split < e.stages_total && e.stages_total % e.stages_per_split == 1) ++e.stages_per_split;
+    splits = (int)ceil_div(e.stages_total, e.stages_per_split);
+    dim3 grid((unsigned)a.n_blocks, (unsigned)splits);
+    if (dtype == JITDB_F32) gemm_kb_kernel<float><<<grid, kDmaThreads, 0, st>>>(a, e);
+    else gemm_kb_kernel<bf16_t><<<grid, kDmaThreads, 0, st>>>(a, e);
+    JITDB_LAUNCH_CHECK();
+    return JITDB_OK;
+}
+
 }  // namespace jitdb
 
 using namespace jitdb;
