@@ -44,6 +44,74 @@ def measured_traffic(cfg, kernel_class):
     return None
 
 
+def train_bench(args, J, torch, cfg, dev, N, D, H, esz, peak_tflops, xt, Wt, Ut, bt, pt, sched, ws_s,
+                n_leaf, n_int, E, L):
+    """Training step = jitdb_schedule + jitdb_treelstm_forward_train + jitdb_treelstm_backward, one stream."""
+    dt = J.JITDB_BF16 if esz == 2 else J.JITDB_F32
+    f32 = dict(dtype=torch.float32, device=dev)
+    ws_f = torch.empty(J.jitdb_treelstm_workspace_bytes(N, E, D, H, dt), dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(J.jitdb_treelstm_backward_workspace_bytes(sched, D, H, dt), dtype=torch.uint8, device=dev)
+    h = torch.empty((N, H), dtype=xt.dtype, device=dev)
+    c = torch.empty((N, H), **f32)
+    gates = torch.empty((N, 3 * H), **f32)
+    fgate = torch.zeros((N, H), **f32)
+    gh = torch.randn((N, H), **f32)
+    gc = torch.randn((N, H), **f32)
+    grads = (torch.empty((N, D), **f32), torch.empty((4 * H, D), **f32), torch.empty((4 * H, H), **f32),
+             torch.empty(4 * H, **f32))
+    stream = torch.cuda.current_stream()
+
+    def fwd():
+        J.jitdb_treelstm_forward_train(xt, Wt, Ut, bt, sched, stream=stream, workspace=ws_f, out=(h, c, gates, fgate))
+
+    def bwd():
+        J.jitdb_treelstm_backward(xt, Wt, Ut, sched, h, c, gates, fgate, gh, gc, stream=stream, workspace=ws_b,
+                                  out=grads)
+
+    def step():
+        J.jitdb_schedule(pt, stream=stream, workspace=ws_s, out=sched)
+        fwd()
+        bwd()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    def timed(fn, reps):
+        e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            fn()
+        e1.record(stream)
+        e1.synchronize()
+        return e0.elapsed_time(e1) / reps
+    reps = max(2, min(args.steps, 5))
+    ms_f, ms_b = timed(fwd, reps), timed(bwd, reps)
+    # every multiply-add of the forward has two in the backward (data and weight gradient)
+    f_min = n_leaf * 2.0 * D * 3 * H + n_int * (2.0 * D * 4 * H + 2.0 * H * 3 * H) + E * 2.0 * H * H
+    out = {
+        "metric": "Tree-LSTM training step nodes/sec on 1 MI355X", "value": N / (ms_step * 1e-3), "unit": "nodes/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype if cfg.dtype == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"config {cfg.index}: {cfg.name}", "n_trees": cfg.n_trees, "n_nodes": N, "n_edges": E,
+                   "n_levels": L, "D": D, "H": H,
+                   "step": "jitdb_schedule + jitdb_treelstm_forward_train + jitdb_treelstm_backward "
+                           "(cotangents on h and c of every node), one stream"},
+        "ms_forward_train": ms_f, "ms_backward": ms_b,
+        "roofline": {"kernel": "backward pass as a whole (its GEMMs: gemm_kb_kernel, gemm_nt_kernel)",
+                     "bound": "mfma", "achieved": 2.0 * f_min / (ms_b * 1e-3) / 1e12, "peak": peak_tflops,
+                     "unit": "TFLOP/s", "frac": 2.0 * f_min / (ms_b * 1e-3) / 1e12 / peak_tflops, "traffic": None,
+                     "flops_per_step": 2.0 * f_min},
+    }
+    print(json.dumps(out), flush=True)
+
+
 def log(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
@@ -61,6 +129,9 @@ def main():
                     help="also run one 1 GiB device copy (reference for HBM counters)")
     ap.add_argument("--cpu-trees", type=int, default=0, help="trees in the oracle sample (0 = auto)")
     ap.add_argument("--no-peaks", action="store_true", help="skip the copy / MFMA peak probes")
+    ap.add_argument("--train", action="store_true",
+                    help="time the training step instead (schedule + forward that keeps the gates + backward); "
+                         "not the headline metric")
     ap.add_argument("--serial", action="store_true",
                     help="schedule and forward of a batch strictly one after the other on one stream "
                          "(default: the schedule of the next batch overlaps the forward of this one)")
@@ -108,6 +179,9 @@ def main():
     n_leaf = int(lp[1])
     n_int = N - n_leaf
     ws_s = torch.empty(J.jitdb_schedule_workspace_bytes(N), dtype=torch.uint8, device=dev)
+    if args.train:
+        return train_bench(args, J, torch, cfg, dev, N, D, H, esz, peak_tflops, xt, Wt, Ut, bt, pt, sched, ws_s,
+                           n_leaf, n_int, E, L)
     ws_f = torch.empty(J.jitdb_treelstm_workspace_bytes(N, E, D, H, J.JITDB_BF16 if esz == 2 else J.JITDB_F32),
                        dtype=torch.uint8, device=dev)
     h = torch.empty((N, H), dtype=xt.dtype, device=dev)

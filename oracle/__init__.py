@@ -11,8 +11,7 @@ Contents
   treelstm_oracle.c    the same definition in plain C (fp64), one tree at a
                        time; used where the numpy version is too slow
   treelstm_backward_oracle.py   reverse-mode gradients of the same forest, node by
-                       node in fp64 (no GPU path uses it yet: the definition a
-                       backward pass will be built against)
+                       node in fp64, and the activations a training forward keeps
   build.py             compiles the C file with gcc
 
 Pins (tests/test_oracle_*.py): brute-force heights, chain / star / perfect

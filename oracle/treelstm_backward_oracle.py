@@ -20,8 +20,7 @@ children:
     dW_g   += dz_g (x) x_j,  dU_g += dz_g (x) hs,  db_g += dz_g               g in i, o, u
     dW_f   += (sum_k dz_f,k) (x) x_j,  dU_f += sum_k dz_f,k (x) h_k,  db_f += sum_k dz_f,k
 
-No GPU path uses it yet; it is pinned (tests/test_oracle_backward.py) so that one can be
-built against it.  Test infrastructure only.
+Pinned in tests/test_oracle_backward.py.  Test infrastructure only; no code shared with the GPU path.
 """
 from __future__ import annotations
 
