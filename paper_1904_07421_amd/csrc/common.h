@@ -59,8 +59,9 @@ __host__ __device__ __forceinline__ int64_t operand_offset(int64_t row, int64_t 
 // to 128 per slab), B has N rows (b_rows_alloc >= N rounded up to 256); K is k_bytes / element
 // size, k_bytes a multiple of 128.  k_splits > 1 deals ranges of K to different blocks.
 enum KbEpilogue : int {
-    KB_EPI_DX_DHS = 0,       // col < D: out0[node[row] * D + col] = v, else out1[row * H + col - D] = v
-    KB_EPI_ATOMIC_ACC = 1    // atomicAdd(out0[row * ldc + col], v)
+    KB_EPI_DX_DHS = 0,       // col < D: out0[node[row] * D + col] = v, else out1[node[row] * H + col - D] = v
+    KB_EPI_ATOMIC_ACC = 1,   // atomicAdd(out0[row * ldc + col], v)
+    KB_EPI_ADD_ROWS = 2      // out0[node[row] * ldc + col] += v (rows are distinct nodes)
 };
 struct KbGemm {
     const void *A; int64_t a_rows_alloc; int M;
