@@ -204,31 +204,54 @@ bwd_hsum_kernel(const int32_t *__restrict__ nodes, int n_rows, int H,
 // block moves one 64-byte slab of the destination's K axis (RT = 32 bf16 / 16 fp32 source rows)
 // times 64 columns; a thread stores 16 bytes, and since consecutive destination rows are
 // consecutive inside a slab a wave stores 1 KB of consecutive memory.
-template <typename T>
+// SRC selects how the tile is read: SRC_SCALAR one element per thread and step (any row
+// stride), SRC_VEC 16 bytes per thread (row-major rows that start on 16-byte boundaries),
+// SRC_KB 16 bytes per thread from a K-blocked source whose width is a multiple of 64.
+enum { SRC_SCALAR = 0, SRC_VEC = 1, SRC_KB = 2 };
+template <typename T, int SRC>
 __global__ void __launch_bounds__(kT)
 transpose_kb_kernel(const T *__restrict__ src, const int32_t *__restrict__ index, int64_t ld_src,
                     int64_t src_rows_alloc, int n_rows, int n_cols, T *__restrict__ dst, int64_t dst_rows_alloc) {
     constexpr int RT = 64 / (int)sizeof(T);
-    constexpr int PER = 16 / (int)sizeof(T);        // elements a thread stores
+    constexpr int PER = 16 / (int)sizeof(T);        // elements in 16 bytes
     __shared__ T tile[RT][64 + 2];
     const int r0 = blockIdx.x * RT, c0 = blockIdx.y * 64;
     const int t = threadIdx.x;
-    {
+    if (SRC == SRC_SCALAR) {
         const int tx = t & 63, ty = t >> 6;          // 64 columns x 4 rows per sweep
 #pragma unroll
         for (int i = 0; i < RT / 4; ++i) {
             const int r = r0 + ty + 4 * i, cc = c0 + tx;
             T v = T(0);
-            if (r < n_rows && cc < n_cols) {
-                const int64_t row = index ? index[r] : r;
-                if (src_rows_alloc > 0)
-                    v = *reinterpret_cast<const T *>(reinterpret_cast<const char *>(src) +
-                                                     operand_offset(row, (int64_t)cc * sizeof(T), src_rows_alloc));
-                else
-                    v = src[row * ld_src + cc];
-            }
+            if (r < n_rows && cc < n_cols) v = src[(int64_t)(index ? index[r] : r) * ld_src + cc];
             tile[ty + 4 * i][tx] = v;
         }
+    } else {
+        // 256 threads x 16 bytes = the whole tile.  Row-major: a row's 64 columns are 64 / PER
+        // pieces.  K-blocked: the tile is 64 / RT slabs of RT rows x 64 bytes.
+        int row, col;
+        const char *a = nullptr;
+        if (SRC == SRC_VEC) {
+            row = t / (64 / PER); col = (t % (64 / PER)) * PER;
+            if (r0 + row < n_rows && c0 + col < n_cols)
+                a = reinterpret_cast<const char *>(src + (int64_t)(index ? index[r0 + row] : r0 + row) * ld_src + c0 + col);
+        } else {
+            const int piece = t & 3, sl = (t >> 2) / RT;
+            row = (t >> 2) % RT; col = sl * RT + piece * PER;
+            if (r0 + row < n_rows)
+                a = reinterpret_cast<const char *>(src) +
+                    ((int64_t)((c0 + col) / RT) * src_rows_alloc + r0 + row) * 64 + piece * 16;
+        }
+        T v[PER];
+        if (a != nullptr && (SRC == SRC_KB || c0 + col + PER <= n_cols)) {
+            *reinterpret_cast<u32x4 *>(v) = *reinterpret_cast<const u32x4 *>(a);
+        } else {
+#pragma unroll
+            for (int e = 0; e < PER; ++e)
+                v[e] = (a != nullptr && c0 + col + e < n_cols) ? reinterpret_cast<const T *>(a)[e] : T(0);
+        }
+#pragma unroll
+        for (int e = 0; e < PER; ++e) tile[row][col + e] = v[e];
     }
     __syncthreads();
     const int cc = t >> 2, piece = t & 3;
@@ -238,6 +261,24 @@ transpose_kb_kernel(const T *__restrict__ src, const int32_t *__restrict__ index
     for (int e = 0; e < PER; ++e) out[e] = tile[piece * PER + e][cc];
     char *d = reinterpret_cast<char *>(dst) + ((int64_t)blockIdx.x * dst_rows_alloc + (c0 + cc)) * 64 + piece * 16;
     *reinterpret_cast<u32x4 *>(d) = *reinterpret_cast<const u32x4 *>(out);
+}
+
+// picks the widest read the source allows
+template <typename T>
+int launch_transpose(const T *src, const int32_t *index, int64_t ld_src, int64_t src_rows_alloc, int n_rows, int n_cols,
+                     int k_pad, T *dst, int64_t dst_rows_alloc, hipStream_t st) {
+    constexpr int RT = 64 / (int)sizeof(T);
+    const dim3 grid((unsigned)(k_pad / RT), (unsigned)ceil_div(n_cols, 64));
+    if (src_rows_alloc > 0) {
+        if (n_cols % 64 != 0) return JITDB_E_BADARG;
+        transpose_kb_kernel<T, SRC_KB><<<grid, kT, 0, st>>>(src, index, ld_src, src_rows_alloc, n_rows, n_cols, dst, dst_rows_alloc);
+    } else if ((ld_src * sizeof(T)) % 16 == 0 && reinterpret_cast<uintptr_t>(src) % 16 == 0) {
+        transpose_kb_kernel<T, SRC_VEC><<<grid, kT, 0, st>>>(src, index, ld_src, 0, n_rows, n_cols, dst, dst_rows_alloc);
+    } else {
+        transpose_kb_kernel<T, SRC_SCALAR><<<grid, kT, 0, st>>>(src, index, ld_src, 0, n_rows, n_cols, dst, dst_rows_alloc);
+    }
+    JITDB_LAUNCH_CHECK();
+    return JITDB_OK;
 }
 
 // one K-blocked row of ones (r < n_rows) and zeros (up to k_pad): the column of the weight
@@ -321,7 +362,6 @@ int run_backward(const T *x, const T *W, const T *U, const BwdDims &d, const jit
     const int32_t *lp = s->host_level_ptr;
     const int D = d.D, H = d.H, Hk = d.Hk;
     const jitdb_dtype dtype = sizeof(T) == 4 ? JITDB_F32 : JITDB_BF16;
-    constexpr int RT = 64 / (int)sizeof(T);
     int rc;
     if ((rc = zero_bytes(w.dMp, round_up((size_t)4 * Hk * (D + 1 + H) * 4, 256), st)) != JITDB_OK) return rc;
     if ((rc = zero_bytes(w.dUfp, round_up((size_t)Hk * H * 4, 256), st)) != JITDB_OK) return rc;
@@ -349,7 +389,6 @@ int run_backward(const T *x, const T *W, const T *U, const BwdDims &d, const jit
         const int64_t lvl_alloc = round_up(rows, 128);
         const unsigned g_elem = (unsigned)ceil_div((int64_t)rows * H, kT);
         const unsigned g_elem_k = (unsigned)ceil_div((int64_t)rows * Hk, kT);
-        const unsigned tr = (unsigned)(kpad / RT);
         auto weight_gemm = [&](const T *A, int64_t a_alloc, int M, const T *B, int64_t b_alloc, int N, float *C, int ldc) {
             KbGemm g = {};
             g.A = A; g.a_rows_alloc = a_alloc; g.M = M; g.B = B; g.b_rows_alloc = b_alloc; g.N = N;
@@ -373,12 +412,8 @@ int run_backward(const T *x, const T *W, const T *U, const BwdDims &d, const jit
             g.k_bytes = (int64_t)Hk * sizeof(T); g.k_splits = 1;
             g.epilogue = KB_EPI_ADD_ROWS; g.out0 = w.dh; g.node = nodes; g.ldc = H;
             if ((rc = launch_kb_gemm(dtype, g, st)) != JITDB_OK) return rc;
-            transpose_kb_kernel<T><<<dim3(tr, (unsigned)ceil_div(Hk, 64)), kT, 0, st>>>(
-                G, nullptr, 0, lvl_alloc, rows, Hk, Gt, gt_alloc);
-            JITDB_LAUNCH_CHECK();
-            transpose_kb_kernel<T><<<dim3(tr, (unsigned)ceil_div(H, 64)), kT, 0, st>>>(
-                h, nodes, H, 0, rows, H, Hkt, ht_alloc);
-            JITDB_LAUNCH_CHECK();
+            if ((rc = launch_transpose<T>(G, nullptr, 0, lvl_alloc, rows, Hk, kpad, Gt, gt_alloc, st)) != JITDB_OK) return rc;
+            if ((rc = launch_transpose<T>(h, nodes, H, 0, rows, H, kpad, Hkt, ht_alloc, st)) != JITDB_OK) return rc;
             if ((rc = weight_gemm(Gt, gt_alloc, Hk, Hkt, ht_alloc, H, w.dUfp, H)) != JITDB_OK) return rc;
         }
         bwd_cell_kernel<T><<<g_elem_k, kT, 0, st>>>(nodes, rows, H, Hk, s->child_ptr, s->child_idx, c, gates, fgate,
@@ -393,22 +428,17 @@ int run_backward(const T *x, const T *W, const T *U, const BwdDims &d, const jit
             if ((rc = launch_kb_gemm(dtype, g, st)) != JITDB_OK) return rc;
         }
         // weight gradients: dMp += dZ^T [x | 1 | hs] (leaves have hs = 0: the x and bias columns only)
-        transpose_kb_kernel<T><<<dim3(tr, (unsigned)ceil_div(4 * Hk, 64)), kT, 0, st>>>(
-            dZ, nullptr, 0, lvl_alloc, rows, 4 * Hk, dZt, zt_alloc);
-        JITDB_LAUNCH_CHECK();
-        transpose_kb_kernel<T><<<dim3(tr, (unsigned)ceil_div(D, 64)), kT, 0, st>>>(
-            x, nodes, D, 0, rows, D, At, at_alloc);
-        JITDB_LAUNCH_CHECK();
+        if ((rc = launch_transpose<T>(dZ, nullptr, 0, lvl_alloc, rows, 4 * Hk, kpad, dZt, zt_alloc, st)) != JITDB_OK) return rc;
+        if ((rc = launch_transpose<T>(x, nodes, D, 0, rows, D, kpad, At, at_alloc, st)) != JITDB_OK) return rc;
         ones_row_kernel<T><<<(unsigned)ceil_div(kpad, kT), kT, 0, st>>>(At, at_alloc, D, rows, kpad);
         JITDB_LAUNCH_CHECK();
         int q_cols = D + 1;
         if (l > 0) {
             bwd_hsum_kernel<T><<<g_elem, kT, 0, st>>>(nodes, rows, H, s->child_ptr, s->child_idx, h, hs);
             JITDB_LAUNCH_CHECK();
-            transpose_kb_kernel<T><<<dim3(tr, (unsigned)ceil_div(H, 64)), kT, 0, st>>>(
-                hs, nullptr, H, 0, rows, H,
-                reinterpret_cast<T *>(reinterpret_cast<char *>(At) + (int64_t)(D + 1) * 64), at_alloc);
-            JITDB_LAUNCH_CHECK();
+            if ((rc = launch_transpose<T>(hs, nullptr, H, 0, rows, H, kpad,
+                                          reinterpret_cast<T *>(reinterpret_cast<char *>(At) + (int64_t)(D + 1) * 64),
+                                          at_alloc, st)) != JITDB_OK) return rc;
             q_cols = D + 1 + H;
         }
         if ((rc = weight_gemm(dZt, zt_alloc, 4 * Hk, At, at_alloc, q_cols, w.dMp, D + 1 + H)) != JITDB_OK) return rc;
