@@ -115,7 +115,7 @@ fill_i32_kernel(int32_t *p, int64_t n, int32_t v) {
 // One thread per (level row, unit of the padded width).  The parent p of node k was
 // processed in a higher level and left its total dc in dc[p] and its dhs in dhs[p]:
 //     dz_f,k = dc_p c_k f_k (1 - f_k)  -> row r of G (K-blocked, level order; zero for a root)
-//     dh_k   = gh_k + dhs_p            (U_f^T dz_f,k is added by the GEMM that follows)
+//     dh_k   = gh_k + dhs_p            (U_f^T dz_f,k comes from the GEMM that follows; the cell kernel adds it)
 //     dc_k   = gc_k + dc_p f_k
 template <typename T>
 __global__ void __launch_bounds__(kT)
@@ -144,15 +144,16 @@ bwd_receive_kernel(const int32_t *__restrict__ nodes, int n_rows, int H, int Hk,
 }
 
 // ---- the cell's elementwise derivative ---------------------------------------------
-// One thread per (level row, unit of the padded width).  dh_j and dc_j are complete when
-// this runs.  Writes dZ row r = [dz_i | dz_o | dz_u | sum_k dz_f,k] (K-blocked, gate stride
+// One thread per (level row, unit of the padded width).  dh_j = dh[j] + ufg[r], where ufg
+// (level order, may be null) is the product U_f^T dz_f,j that the GEMM before this kernel
+// left; dc_j is complete.  Writes dZ row r = [dz_i | dz_o | dz_u | sum_k dz_f,k] (K-blocked, gate stride
 // Hk) and leaves the total dc_j in dc[j] for the children's level.
 template <typename T>
 __global__ void __launch_bounds__(kT)
 bwd_cell_kernel(const int32_t *__restrict__ nodes, int n_rows, int H, int Hk,
                 const int32_t *__restrict__ child_ptr, const int32_t *__restrict__ child_idx,
                 const float *__restrict__ c, const float *__restrict__ gates, const float *__restrict__ fgate,
-                const float *__restrict__ dh, float *__restrict__ dc,
+                const float *__restrict__ dh, const float *__restrict__ ufg, float *__restrict__ dc,
                 T *__restrict__ dZ, int64_t dz_rows_alloc) {
     const int64_t id = (int64_t)blockIdx.x * kT + threadIdx.x;
     if (id >= (int64_t)n_rows * Hk) return;
@@ -167,7 +168,7 @@ bwd_cell_kernel(const int32_t *__restrict__ nodes, int n_rows, int H, int Hk,
     const int64_t j = nodes[r];
     const float gi = gates[j * 3 * H + m], go = gates[j * 3 * H + H + m], gu = gates[j * 3 * H + 2 * H + m];
     const float t = tanhf(c[j * H + m]);
-    const float dhj = dh[j * H + m];
+    const float dhj = dh[j * H + m] + (ufg ? ufg[(int64_t)r * H + m] : 0.0f);
     const float dcj = dc[j * H + m] + dhj * go * (1.0f - t * t);
     dc[j * H + m] = dcj;
     float dzf_sum = 0.0f;
@@ -316,7 +317,7 @@ struct BwdDims {
     size_t esz;
 };
 struct BwdWs {
-    float *dh, *dc, *dhs, *dMp, *dUfp;
+    float *dh, *dc, *dhs, *ufg, *dMp, *dUfp;
     int32_t *parent_of;
     void *Mt, *Uft, *dZ, *G, *hs, *dZt, *At, *Gt, *Hkt;
     size_t bytes;
@@ -328,6 +329,7 @@ BwdWs carve_bwd_ws(int64_t n, const BwdDims &d, void *base) {
     w.dh = c.take<float>((size_t)n * d.H);
     w.dc = c.take<float>((size_t)n * d.H);
     w.dhs = c.take<float>((size_t)n * d.H);
+    w.ufg = c.take<float>((size_t)d.n_max * d.H);
     w.dMp = c.take<float>((size_t)4 * d.Hk * (d.D + 1 + d.H));
     w.dUfp = c.take<float>((size_t)d.Hk * d.H);
     w.parent_of = c.take<int32_t>((size_t)n);
@@ -394,7 +396,7 @@ int run_backward(const T *x, const T *W, const T *U, const BwdDims &d, const jit
             g.A = A; g.a_rows_alloc = a_alloc; g.M = M; g.B = B; g.b_rows_alloc = b_alloc; g.N = N;
             g.k_bytes = (int64_t)kpad * sizeof(T);
             const int64_t tiles = ceil_div(M, 128) * ceil_div(N, 256);
-            const int64_t want = ceil_div(2048, tiles);
+            const int64_t want = ceil_div(512, tiles);      // two blocks per CU
             const int64_t most = kpad / 512 > 0 ? kpad / 512 : 1;
             g.k_splits = (int)(want < most ? want : most);
             g.epilogue = KB_EPI_ATOMIC_ACC; g.out0 = C; g.ldc = ldc;
@@ -405,19 +407,19 @@ int run_backward(const T *x, const T *W, const T *U, const BwdDims &d, const jit
                                                        w.dh, w.dc, G, lvl_alloc);
         JITDB_LAUNCH_CHECK();
         if (l < L - 1) {
-            // dh_k += U_f^T dz_f,k, and dU_f += sum_k dz_f,k (x) h_k
+            // ufg_r = U_f^T dz_f,k (level order), and dU_f += sum_k dz_f,k (x) h_k
             KbGemm g = {};
             g.A = G; g.a_rows_alloc = lvl_alloc; g.M = rows;
             g.B = w.Uft; g.b_rows_alloc = uft_alloc; g.N = H;
             g.k_bytes = (int64_t)Hk * sizeof(T); g.k_splits = 1;
-            g.epilogue = KB_EPI_ADD_ROWS; g.out0 = w.dh; g.node = nodes; g.ldc = H;
+            g.epilogue = KB_EPI_STORE; g.out0 = w.ufg; g.ldc = H;
             if ((rc = launch_kb_gemm(dtype, g, st)) != JITDB_OK) return rc;
             if ((rc = launch_transpose<T>(G, nullptr, 0, lvl_alloc, rows, Hk, kpad, Gt, gt_alloc, st)) != JITDB_OK) return rc;
             if ((rc = launch_transpose<T>(h, nodes, H, 0, rows, H, kpad, Hkt, ht_alloc, st)) != JITDB_OK) return rc;
             if ((rc = weight_gemm(Gt, gt_alloc, Hk, Hkt, ht_alloc, H, w.dUfp, H)) != JITDB_OK) return rc;
         }
         bwd_cell_kernel<T><<<g_elem_k, kT, 0, st>>>(nodes, rows, H, Hk, s->child_ptr, s->child_idx, c, gates, fgate,
-                                                    w.dh, w.dc, dZ, lvl_alloc);
+                                                    w.dh, l < L - 1 ? w.ufg : nullptr, w.dc, dZ, lvl_alloc);
         JITDB_LAUNCH_CHECK();
         {   // [dx | dhs] = dZ [W | U]; leaves have nobody to pass dhs to
             KbGemm g = {};

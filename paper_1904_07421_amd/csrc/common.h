@@ -61,7 +61,7 @@ __host__ __device__ __forceinline__ int64_t operand_offset(int64_t row, int64_t 
 enum KbEpilogue : int {
     KB_EPI_DX_DHS = 0,       // col < D: out0[node[row] * D + col] = v, else out1[node[row] * H + col - D] = v
     KB_EPI_ATOMIC_ACC = 1,   // atomicAdd(out0[row * ldc + col], v)
-    KB_EPI_ADD_ROWS = 2      // out0[node[row] * ldc + col] += v (rows are distinct nodes)
+    KB_EPI_STORE = 2         // out0[row * ldc + col] = v
 };
 struct KbGemm {
     const void *A; int64_t a_rows_alloc; int M;

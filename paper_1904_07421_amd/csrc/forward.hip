@@ -981,8 +981,8 @@ gemm_kb_kernel(LevelArgs a, const KbEpiArgs e) {
                 if (e.kind == KB_EPI_DX_DHS) {
                     if (col < e.D) e.out0[(int64_t)e.node[row] * e.D + col] = val;
                     else e.out1[(int64_t)e.node[row] * e.H + (col - e.D)] = val;
-                } else if (e.kind == KB_EPI_ADD_ROWS) {
-                    e.out0[(int64_t)e.node[row] * e.ldc + col] += val;
+                } else if (e.kind == KB_EPI_STORE) {
+                    e.out0[(int64_t)row * e.ldc + col] = val;
                 } else {
                     atomicAdd(&e.out0[(int64_t)row * e.ldc + col], val);
                 }
