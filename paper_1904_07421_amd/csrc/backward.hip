@@ -111,10 +111,33 @@ fill_i32_kernel(int32_t *p, int64_t n, int32_t v) {
     for (int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x; i < n; i += (int64_t)gridDim.x * kT) p[i] = v;
 }
 
-// ---- what a level's nodes receive from their parents --------------------------------
-// One thread per (level row, unit of the padded width).  The parent p of node k was
-// processed in a higher level and left its total dc in dc[p] and its dhs in dhs[p]:
-//     dz_f,k = dc_p c_k f_k (1 - f_k)  -> row r of G (K-blocked, level order; zero for a root)
+// ---- elementwise kernels on (RT rows) x (64 units) tiles ------------------------------
+// RT = 32 (bf16) / 16 (fp32) level rows fill one 64-byte slab of a K-blocked operand whose K
+// axis is the level's rows.  Wave w of a block takes the rows w, w + 4, ... of the tile, a
+// lane one unit; what a kernel produces goes out twice: row-wise into the K-blocked operand
+// of the data-gradient GEMM, and, through an LDS tile, transposed into the operand of the
+// weight-gradient GEMM (a thread stores 16 bytes, a wave 1 KB of consecutive memory).  Rows
+// past the level's end and units past H are written as zeros in the transposed operand (they
+// are part of the reduction); grid = (padded rows / RT, Hk / 64).
+template <typename T, int NG>
+__device__ __forceinline__ void store_transposed_tile(const T (*tile)[64 / sizeof(T)][64 + 2], int t, int Hk, int m0,
+                                                      T *__restrict__ dst, int64_t dst_rows_alloc) {
+    constexpr int PER = 16 / (int)sizeof(T);
+    const int cc = t >> 2, piece = t & 3;
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+        T out[PER];
+#pragma unroll
+        for (int e = 0; e < PER; ++e) out[e] = tile[g][piece * PER + e][cc];
+        char *d = reinterpret_cast<char *>(dst) +
+                  ((int64_t)blockIdx.x * dst_rows_alloc + (g * Hk + m0 + cc)) * 64 + piece * 16;
+        *reinterpret_cast<u32x4 *>(d) = *reinterpret_cast<const u32x4 *>(out);
+    }
+}
+
+// What a level's nodes receive from their parents.  The parent p of node k was processed in a
+// higher level and left its total dc in dc[p] and its dhs in dhs[p]:
+//     dz_f,k = dc_p c_k f_k (1 - f_k)  -> row r of G and column r of Gt (zero for a root)
 //     dh_k   = gh_k + dhs_p            (U_f^T dz_f,k comes from the GEMM that follows; the cell kernel adds it)
 //     dc_k   = gc_k + dc_p f_k
 template <typename T>
@@ -123,64 +146,85 @@ bwd_receive_kernel(const int32_t *__restrict__ nodes, int n_rows, int H, int Hk,
                    const int32_t *__restrict__ parent_of, const float *__restrict__ c,
                    const float *__restrict__ fgate, const float *__restrict__ gh, const float *__restrict__ gc,
                    const float *__restrict__ dhs, float *__restrict__ dh, float *__restrict__ dc,
-                   T *__restrict__ G, int64_t g_rows_alloc) {
-    const int64_t id = (int64_t)blockIdx.x * kT + threadIdx.x;
-    if (id >= (int64_t)n_rows * Hk) return;
-    const int r = (int)(id / Hk), m = (int)(id % Hk);
-    T *g = reinterpret_cast<T *>(reinterpret_cast<char *>(G) + operand_offset(r, (int64_t)m * sizeof(T), g_rows_alloc));
-    if (m >= H) { *g = T(0); return; }
-    const int64_t k = nodes[r];
-    const int64_t p = parent_of[k];
-    float dhk = gh ? gh[k * H + m] : 0.0f, dck = gc ? gc[k * H + m] : 0.0f, dzf = 0.0f;
-    if (p >= 0) {
-        const float dcp = dc[p * H + m], fk = fgate[k * H + m];
-        dzf = dcp * c[k * H + m] * fk * (1.0f - fk);
-        dhk += dhs[p * H + m];
-        dck += dcp * fk;
+                   T *__restrict__ G, int64_t g_rows_alloc, T *__restrict__ Gt, int64_t gt_rows_alloc) {
+    constexpr int RT = 64 / (int)sizeof(T);
+    __shared__ T tile[1][RT][64 + 2];
+    const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+    const int r0 = blockIdx.x * RT, m0 = blockIdx.y * 64, m = m0 + lane;
+#pragma unroll
+    for (int i = 0; i < RT / 4; ++i) {
+        const int rr = w + 4 * i, r = r0 + rr;
+        float dzf = 0.0f;
+        if (r < n_rows && m < H) {
+            const int64_t k = nodes[r];
+            const int64_t p = parent_of[k];
+            float dhk = gh ? gh[k * H + m] : 0.0f, dck = gc ? gc[k * H + m] : 0.0f;
+            if (p >= 0) {
+                const float dcp = dc[p * H + m], fk = fgate[k * H + m];
+                dzf = dcp * c[k * H + m] * fk * (1.0f - fk);
+                dhk += dhs[p * H + m];
+                dck += dcp * fk;
+            }
+            dh[k * H + m] = dhk;
+            dc[k * H + m] = dck;
+        }
+        const T v = from_f32<T>(dzf);
+        tile[0][rr][lane] = v;
+        if (r < n_rows)
+            *reinterpret_cast<T *>(reinterpret_cast<char *>(G) + operand_offset(r, (int64_t)m * sizeof(T), g_rows_alloc)) = v;
     }
-    *g = from_f32<T>(dzf);
-    dh[k * H + m] = dhk;
-    dc[k * H + m] = dck;
+    __syncthreads();
+    store_transposed_tile<T, 1>(tile, t, Hk, m0, Gt, gt_rows_alloc);
 }
 
-// ---- the cell's elementwise derivative ---------------------------------------------
-// One thread per (level row, unit of the padded width).  dh_j = dh[j] + ufg[r], where ufg
-// (level order, may be null) is the product U_f^T dz_f,j that the GEMM before this kernel
-// left; dc_j is complete.  Writes dZ row r = [dz_i | dz_o | dz_u | sum_k dz_f,k] (K-blocked, gate stride
-// Hk) and leaves the total dc_j in dc[j] for the children's level.
+// The cell's elementwise derivative.  dh_j = dh[j] + ufg[r], where ufg (level order, may be
+// null) is the product U_f^T dz_f,j that the GEMM before this kernel left; dc_j is complete.
+// Writes dZ row r = [dz_i | dz_o | dz_u | sum_k dz_f,k] (K-blocked, gate stride Hk), the same
+// transposed into dZt, and leaves the total dc_j in dc[j] for the children's level.
 template <typename T>
 __global__ void __launch_bounds__(kT)
 bwd_cell_kernel(const int32_t *__restrict__ nodes, int n_rows, int H, int Hk,
                 const int32_t *__restrict__ child_ptr, const int32_t *__restrict__ child_idx,
                 const float *__restrict__ c, const float *__restrict__ gates, const float *__restrict__ fgate,
                 const float *__restrict__ dh, const float *__restrict__ ufg, float *__restrict__ dc,
-                T *__restrict__ dZ, int64_t dz_rows_alloc) {
-    const int64_t id = (int64_t)blockIdx.x * kT + threadIdx.x;
-    if (id >= (int64_t)n_rows * Hk) return;
-    const int r = (int)(id / Hk), m = (int)(id % Hk);
+                T *__restrict__ dZ, int64_t dz_rows_alloc, T *__restrict__ dZt, int64_t zt_rows_alloc) {
+    constexpr int RT = 64 / (int)sizeof(T);
+    __shared__ T tile[4][RT][64 + 2];
+    const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+    const int r0 = blockIdx.x * RT, m0 = blockIdx.y * 64, m = m0 + lane;
     char *zb = reinterpret_cast<char *>(dZ);
-    if (m >= H) {       // pad columns of the K-blocked operand
 #pragma unroll
-        for (int g = 0; g < 4; ++g)
-            *reinterpret_cast<T *>(zb + operand_offset(r, (int64_t)(g * Hk + m) * sizeof(T), dz_rows_alloc)) = T(0);
-        return;
-    }
-    const int64_t j = nodes[r];
-    const float gi = gates[j * 3 * H + m], go = gates[j * 3 * H + H + m], gu = gates[j * 3 * H + 2 * H + m];
-    const float t = tanhf(c[j * H + m]);
-    const float dhj = dh[j * H + m] + (ufg ? ufg[(int64_t)r * H + m] : 0.0f);
-    const float dcj = dc[j * H + m] + dhj * go * (1.0f - t * t);
-    dc[j * H + m] = dcj;
-    float dzf_sum = 0.0f;
-    for (int e = child_ptr[j]; e < child_ptr[j + 1]; ++e) {
-        const int64_t k = child_idx[e];
-        const float fk = fgate[k * H + m];
-        dzf_sum += dcj * c[k * H + m] * fk * (1.0f - fk);
-    }
-    const float dz[4] = {dcj * gu * gi * (1.0f - gi), dhj * t * go * (1.0f - go), dcj * gi * (1.0f - gu * gu), dzf_sum};
+    for (int i = 0; i < RT / 4; ++i) {
+        const int rr = w + 4 * i, r = r0 + rr;
+        float dz[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (r < n_rows && m < H) {
+            const int64_t j = nodes[r];
+            const float gi = gates[j * 3 * H + m], go = gates[j * 3 * H + H + m], gu = gates[j * 3 * H + 2 * H + m];
+            const float th = tanhf(c[j * H + m]);
+            const float dhj = dh[j * H + m] + (ufg ? ufg[(int64_t)r * H + m] : 0.0f);
+            const float dcj = dc[j * H + m] + dhj * go * (1.0f - th * th);
+            dc[j * H + m] = dcj;
+            float dzf_sum = 0.0f;
+            for (int e = child_ptr[j]; e < child_ptr[j + 1]; ++e) {
+                const int64_t k = child_idx[e];
+                const float fk = fgate[k * H + m];
+                dzf_sum += dcj * c[k * H + m] * fk * (1.0f - fk);
+            }
+            dz[0] = dcj * gu * gi * (1.0f - gi);
+            dz[1] = dhj * th * go * (1.0f - go);
+            dz[2] = dcj * gi * (1.0f - gu * gu);
+            dz[3] = dzf_sum;
+        }
 #pragma unroll
-    for (int g = 0; g < 4; ++g)
-        *reinterpret_cast<T *>(zb + operand_offset(r, (int64_t)(g * Hk + m) * sizeof(T), dz_rows_alloc)) = from_f32<T>(dz[g]);
+        for (int g = 0; g < 4; ++g) {
+            const T v = from_f32<T>(dz[g]);
+            tile[g][rr][lane] = v;
+            if (r < n_rows)
+                *reinterpret_cast<T *>(zb + operand_offset(r, (int64_t)(g * Hk + m) * sizeof(T), dz_rows_alloc)) = v;
+        }
+    }
+    __syncthreads();
+    store_transposed_tile<T, 4>(tile, t, Hk, m0, dZt, zt_rows_alloc);
 }
 
 // hs_r = sum over children of h_k (fp32 sum, rounded once), level order
@@ -390,7 +434,7 @@ int run_backward(const T *x, const T *W, const T *U, const BwdDims &d, const jit
         const int kpad = (int)round_up(rows, 64);           // reduction length of the weight GEMMs
         const int64_t lvl_alloc = round_up(rows, 128);
         const unsigned g_elem = (unsigned)ceil_div((int64_t)rows * H, kT);
-        const unsigned g_elem_k = (unsigned)ceil_div((int64_t)rows * Hk, kT);
+        const dim3 tile_grid((unsigned)(kpad / (64 / (int)sizeof(T))), (unsigned)(Hk / 64));
         auto weight_gemm = [&](const T *A, int64_t a_alloc, int M, const T *B, int64_t b_alloc, int N, float *C, int ldc) {
             KbGemm g = {};
             g.A = A; g.a_rows_alloc = a_alloc; g.M = M; g.B = B; g.b_rows_alloc = b_alloc; g.N = N;
@@ -403,8 +447,8 @@ int run_backward(const T *x, const T *W, const T *U, const BwdDims &d, const jit
             return launch_kb_gemm(dtype, g, st);
         };
         // what the level receives from above
-        bwd_receive_kernel<T><<<g_elem_k, kT, 0, st>>>(nodes, rows, H, Hk, w.parent_of, c, fgate, gh, gc, w.dhs,
-                                                       w.dh, w.dc, G, lvl_alloc);
+        bwd_receive_kernel<T><<<tile_grid, kT, 0, st>>>(nodes, rows, H, Hk, w.parent_of, c, fgate, gh, gc, w.dhs,
+                                                        w.dh, w.dc, G, lvl_alloc, Gt, gt_alloc);
         JITDB_LAUNCH_CHECK();
         if (l < L - 1) {
             // ufg_r = U_f^T dz_f,k (level order), and dU_f += sum_k dz_f,k (x) h_k
@@ -414,12 +458,11 @@ int run_backward(const T *x, const T *W, const T *U, const BwdDims &d, const jit
             g.k_bytes = (int64_t)Hk * sizeof(T); g.k_splits = 1;
             g.epilogue = KB_EPI_STORE; g.out0 = w.ufg; g.ldc = H;
             if ((rc = launch_kb_gemm(dtype, g, st)) != JITDB_OK) return rc;
-            if ((rc = launch_transpose<T>(G, nullptr, 0, lvl_alloc, rows, Hk, kpad, Gt, gt_alloc, st)) != JITDB_OK) return rc;
             if ((rc = launch_transpose<T>(h, nodes, H, 0, rows, H, kpad, Hkt, ht_alloc, st)) != JITDB_OK) return rc;
             if ((rc = weight_gemm(Gt, gt_alloc, Hk, Hkt, ht_alloc, H, w.dUfp, H)) != JITDB_OK) return rc;
         }
-        bwd_cell_kernel<T><<<g_elem_k, kT, 0, st>>>(nodes, rows, H, Hk, s->child_ptr, s->child_idx, c, gates, fgate,
-                                                    w.dh, l < L - 1 ? w.ufg : nullptr, w.dc, dZ, lvl_alloc);
+        bwd_cell_kernel<T><<<tile_grid, kT, 0, st>>>(nodes, rows, H, Hk, s->child_ptr, s->child_idx, c, gates, fgate,
+                                                     w.dh, l < L - 1 ? w.ufg : nullptr, w.dc, dZ, lvl_alloc, dZt, zt_alloc);
         JITDB_LAUNCH_CHECK();
         {   // [dx | dhs] = dZ [W | U]; leaves have nobody to pass dhs to
             KbGemm g = {};
@@ -430,7 +473,6 @@ int run_backward(const T *x, const T *W, const T *U, const BwdDims &d, const jit
             if ((rc = launch_kb_gemm(dtype, g, st)) != JITDB_OK) return rc;
         }
         // weight gradients: dMp += dZ^T [x | 1 | hs] (leaves have hs = 0: the x and bias columns only)
-        if ((rc = launch_transpose<T>(dZ, nullptr, 0, lvl_alloc, rows, 4 * Hk, kpad, dZt, zt_alloc, st)) != JITDB_OK) return rc;
         if ((rc = launch_transpose<T>(x, nodes, D, 0, rows, D, kpad, At, at_alloc, st)) != JITDB_OK) return rc;
         ones_row_kernel<T><<<(unsigned)ceil_div(kpad, kT), kT, 0, st>>>(At, at_alloc, D, rows, kpad);
         JITDB_LAUNCH_CHECK();
