@@ -1,28 +1,29 @@
 // jitdb_treelstm_backward: reverse-mode gradients of the level-batched Tree-LSTM forward.
 //
 // The paper trains through the same batched graph it infers with (section 5).  Here the
-// levels of the schedule are visited from the roots down; per level
+// levels of the schedule are visited from the roots down.  A node's parent lies in a higher
+// level, so when a level is reached every parent has already left its total dc and its dhs =
+// U_iou^T dz_iou (by node id); per level
 //
-//   (nodes that have parents)  dh_k += U_f^T dz_f,k              one GEMM over the level's rows
-//                              dU_f += sum_k dz_f,k (x) h_k      one GEMM, reduction over rows
-//   bwd_cell_kernel            the cell's elementwise derivative: dz_i, dz_o, dz_u and the
-//                              per-child dz_f,k, dc_k from dh_j, dc_j and the saved gates
-//   [dx_j | dhs_j] = dZ_j [W | U]                                one GEMM over the level's rows
-//   bwd_scatter_kernel         dh_k += dhs_parent(k)             over the child CSR
-//   dW, dU_iou, db += dZ^T [x | hs]                              one GEMM, reduction over rows
+//   bwd_receive_kernel   per node k with parent p: dz_f,k = dc_p c_k f_k (1 - f_k) (rows of G),
+//                        dh_k = gh_k + dhs_p, dc_k = gc_k + dc_p f_k
+//   ufg = G U_f                                      GEMM over the level's rows
+//   dU_f += G^T h                                    GEMM, reduction over the level's rows
+//   bwd_cell_kernel      dz_i, dz_o, dz_u, sum_k dz_f,k from dh_j + ufg_j, dc_j and the saved gates
+//   [dx_j | dhs_j] = dZ_j [W | U]                    GEMM over the level's rows
+//   [dW | db | dU_iou] += dZ^T [x | 1 | hs]          GEMM, reduction over the level's rows
 //
-// This first version keeps every step separate and simple: the GEMMs are one generic
-// MFMA kernel (C = A B^T, both operands K-contiguous, fragments straight from global
-// memory / L2), reductions over rows go through explicit transposes.  Gradients are fp32;
-// with JITDB_BF16 the GEMM operands (dz, x, h, hs, weights) are bfloat16, sums fp32.
+// All four GEMMs run on the forward's tiled MFMA core (launch_kb_gemm: both operands
+// K-blocked).  A reduction over rows needs operands whose K axis is the level's rows: the two
+// elementwise kernels write their results a second time, transposed through LDS, and x, h
+// and hs are transposed by transpose_kb_kernel.  Gradients are fp32; with JITDB_BF16 the GEMM
+// operands (dz, x, h, hs, weights) are bfloat16, sums fp32.
 
 #include "common.h"
 
 namespace jitdb {
 namespace {
 
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef uint16_t bf16_t;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -41,28 +42,10 @@ template <typename T> __device__ __forceinline__ float to_f32(T v);
 template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ float to_f32<bf16_t>(bf16_t v) { return bf16_to_f32(v); }
 
-template <typename T>
-__device__ __forceinline__ void mfma_step(const u32x4 &a, const u32x4 &b, floatx16 &acc) {
-    if constexpr (sizeof(T) == 2) {
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
-                                                      __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
-    } else {
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[0]), __uint_as_float(b[0]), acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[1]), __uint_as_float(b[1]), acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[2]), __uint_as_float(b[2]), acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[3]), __uint_as_float(b[3]), acc, 0, 0, 0);
-    }
-}
-
 // ---- small helpers -----------------------------------------------------------------
 __global__ void __launch_bounds__(kT)
 fill_f32_kernel(float *p, int64_t n, float v) {
     for (int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x; i < n; i += (int64_t)gridDim.x * kT) p[i] = v;
-}
-__global__ void __launch_bounds__(kT)
-copy_or_zero_kernel(const float *src, float *dst, int64_t n) {
-    for (int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x; i < n; i += (int64_t)gridDim.x * kT)
-        dst[i] = src ? src[i] : 0.0f;
 }
 __global__ void __launch_bounds__(kT)
 fill_bytes16_kernel(u32x4 *p, int64_t n16) {

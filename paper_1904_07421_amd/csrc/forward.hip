@@ -927,13 +927,17 @@ level_kernel(const LevelArgs a) {
 
 // ---- the same GEMM core as a plain C = A B^T ------------------------------------------
 // For the backward pass: both operands K-blocked, all four column groups multiplied in every
-// stage, no cell update.  blockIdx.y selects a range of K stages (split reduction); an output
-// element goes to the epilogue named in the arguments.
+// stage, no cell update.  An output element goes to the epilogue named in the arguments.
+// With a split reduction (splits > 1) the grid is one-dimensional and a block's K range
+// decides its XCD: blocks are dealt to the eight XCDs round-robin, so block b runs on XCD
+// b % 8, takes a split s with s % 8 == b % 8 and one of the output tiles of that split.  All
+// tiles of a K range then share one L2, which reads that range of both operands once, and
+// every XCD has work however few output tiles there are.
 struct KbEpiArgs {
     int kind;
     float *out0; float *out1; const int32_t *node; int D; int H; int ldc;
     int M, N;
-    int stages_total, stages_per_split;
+    int stages_total, stages_per_split, splits;
 };
 
 template <typename T>
@@ -946,11 +950,19 @@ gemm_kb_kernel(LevelArgs a, const KbEpiArgs e) {
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int wm = wave >> 1, wn = wave & 1;
     const int hf = lane >> 5, l32 = lane & 31;
-    int row_tile, col_tile;
-    if (!block_to_tile(blockIdx.x, a.n_row_tiles, a.n_col_tiles, row_tile, col_tile)) return;
+    int row_tile, col_tile, split = 0;
+    if (e.splits > 1) {
+        const int q = blockIdx.x >> 3, tiles = a.n_row_tiles * a.n_col_tiles;
+        split = (blockIdx.x & 7) + 8 * (q / tiles);
+        if (split >= e.splits) return;
+        row_tile = (q % tiles) / a.n_col_tiles;
+        col_tile = (q % tiles) % a.n_col_tiles;
+    } else if (!block_to_tile(blockIdx.x, a.n_row_tiles, a.n_col_tiles, row_tile, col_tile)) {
+        return;
+    }
     const int tile_row0 = row_tile * kDmaBM;
     // this block's range of K stages
-    const int s0 = blockIdx.y * e.stages_per_split;
+    const int s0 = split * e.stages_per_split;
     int n_st = e.stages_total - s0;
     if (n_st > e.stages_per_split) n_st = e.stages_per_split;
     a.stack = static_cast<const char *>(a.stack) + (int64_t)s0 * a.n_rows_alloc * kDmaStage;
@@ -1342,7 +1354,9 @@ int launch_kb_gemm(jitdb_dtype dtype, const KbGemm &g, hipStream_t st) {
     if (e.stages_per_split < 2) e.stages_per_split = 2;
     while (e.stages_per_split < e.stages_total && e.stages_total % e.stages_per_split == 1) ++e.stages_per_split;
     splits = (int)ceil_div(e.stages_total, e.stages_per_split);
-    dim3 grid((unsigned)a.n_blocks, (unsigned)splits);
+    e.splits = splits;
+    if (splits > 1) a.n_blocks = 8 * a.n_row_tiles * a.n_col_tiles * (int)ceil_div(splits, 8);
+    dim3 grid((unsigned)a.n_blocks);
     if (dtype == JITDB_F32) gemm_kb_kernel<float><<<grid, kDmaThreads, 0, st>>>(a, e);
     else gemm_kb_kernel<bf16_t><<<grid, kDmaThreads, 0, st>>>(a, e);
     JITDB_LAUNCH_CHECK();
