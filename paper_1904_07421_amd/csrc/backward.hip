@@ -104,11 +104,12 @@ fill_i32_kernel(int32_t *p, int64_t n, int32_t v) {
 // are part of the reduction); grid = (padded rows / RT, Hk / 64).
 template <typename T, int NG>
 __device__ __forceinline__ void store_transposed_tile(const T (*tile)[64 / sizeof(T)][64 + 2], int t, int Hk, int m0,
-                                                      T *__restrict__ dst, int64_t dst_rows_alloc) {
+                                                      T *__restrict__ dst, int64_t dst_rows_alloc, int n_gates = NG) {
     constexpr int PER = 16 / (int)sizeof(T);
     const int cc = t >> 2, piece = t & 3;
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
+        if (g >= n_gates) break;
         T out[PER];
 #pragma unroll
         for (int e = 0; e < PER; ++e) out[e] = tile[g][piece * PER + e][cc];
@@ -163,14 +164,15 @@ bwd_receive_kernel(const int32_t *__restrict__ nodes, int n_rows, int H, int Hk,
 // The cell's elementwise derivative.  dh_j = dh[j] + ufg[r], where ufg (level order, may be
 // null) is the product U_f^T dz_f,j that the GEMM before this kernel left; dc_j is complete.
 // Writes dZ row r = [dz_i | dz_o | dz_u | sum_k dz_f,k] (K-blocked, gate stride Hk), the same
-// transposed into dZt, and leaves the total dc_j in dc[j] for the children's level.
+// transposed into dZt, and leaves the total dc_j in dc[j] for the children's level.  Only the
+// first n_gates blocks are written (3 at the leaf level, whose forget block is zero and unused).
 template <typename T>
 __global__ void __launch_bounds__(kT)
 bwd_cell_kernel(const int32_t *__restrict__ nodes, int n_rows, int H, int Hk,
                 const int32_t *__restrict__ child_ptr, const int32_t *__restrict__ child_idx,
                 const float *__restrict__ c, const float *__restrict__ gates, const float *__restrict__ fgate,
                 const float *__restrict__ dh, const float *__restrict__ ufg, float *__restrict__ dc,
-                T *__restrict__ dZ, int64_t dz_rows_alloc, T *__restrict__ dZt, int64_t zt_rows_alloc) {
+                T *__restrict__ dZ, int64_t dz_rows_alloc, T *__restrict__ dZt, int64_t zt_rows_alloc, int n_gates) {
     constexpr int RT = 64 / (int)sizeof(T);
     __shared__ T tile[4][RT][64 + 2];
     const int t = threadIdx.x, lane = t & 63, w = t >> 6;
@@ -200,6 +202,7 @@ bwd_cell_kernel(const int32_t *__restrict__ nodes, int n_rows, int H, int Hk,
         }
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
+            if (g >= n_gates) break;
             const T v = from_f32<T>(dz[g]);
             tile[g][rr][lane] = v;
             if (r < n_rows)
@@ -207,22 +210,7 @@ bwd_cell_kernel(const int32_t *__restrict__ nodes, int n_rows, int H, int Hk,
         }
     }
     __syncthreads();
-    store_transposed_tile<T, 4>(tile, t, Hk, m0, dZt, zt_rows_alloc);
-}
-
-// hs_r = sum over children of h_k (fp32 sum, rounded once), level order
-template <typename T>
-__global__ void __launch_bounds__(kT)
-bwd_hsum_kernel(const int32_t *__restrict__ nodes, int n_rows, int H,
-                const int32_t *__restrict__ child_ptr, const int32_t *__restrict__ child_idx,
-                const T *__restrict__ h, T *__restrict__ hs) {
-    const int64_t id = (int64_t)blockIdx.x * kT + threadIdx.x;
-    if (id >= (int64_t)n_rows * H) return;
-    const int r = (int)(id / H), m = (int)(id % H);
-    const int64_t j = nodes[r];
-    float s = 0.0f;
-    for (int e = child_ptr[j]; e < child_ptr[j + 1]; ++e) s += to_f32<T>(h[(int64_t)child_idx[e] * H + m]);
-    hs[(int64_t)r * H + m] = from_f32<T>(s);
+    store_transposed_tile<T, 4>(tile, t, Hk, m0, dZt, zt_rows_alloc, n_gates);
 }
 
 // ---- transposes into K-blocked operands ---------------------------------------------
@@ -309,6 +297,51 @@ int launch_transpose(const T *src, const int32_t *index, int64_t ld_src, int64_t
     return JITDB_OK;
 }
 
+// The child sums of a level, transposed: dst row c, K position r = sum over the children k of
+// node nodes[r] of h_k[c], summed in fp32 and rounded once as the forward does.  Same tiles
+// and stores as transpose_kb_kernel; VEC reads 16 bytes of a child's row per thread.
+template <typename T, bool VEC>
+__global__ void __launch_bounds__(kT)
+hsum_transpose_kernel(const T *__restrict__ h, const int32_t *__restrict__ nodes, int n_rows, int H,
+                      const int32_t *__restrict__ child_ptr, const int32_t *__restrict__ child_idx,
+                      T *__restrict__ dst, int64_t dst_rows_alloc) {
+    constexpr int RT = 64 / (int)sizeof(T);
+    constexpr int PER = 16 / (int)sizeof(T);
+    __shared__ T tile[RT][64 + 2];
+    const int r0 = blockIdx.x * RT, c0 = blockIdx.y * 64;
+    const int t = threadIdx.x;
+    const int row = t / (64 / PER), col = (t % (64 / PER)) * PER;
+    float sum[PER];
+#pragma unroll
+    for (int e = 0; e < PER; ++e) sum[e] = 0.0f;
+    if (r0 + row < n_rows && c0 + col < H) {
+        const int64_t j = nodes[r0 + row];
+        for (int ce = child_ptr[j]; ce < child_ptr[j + 1]; ++ce) {
+            const T *a = h + (int64_t)child_idx[ce] * H + c0 + col;
+            if (VEC && c0 + col + PER <= H) {
+                T v[PER];
+                *reinterpret_cast<u32x4 *>(v) = *reinterpret_cast<const u32x4 *>(a);
+#pragma unroll
+                for (int e = 0; e < PER; ++e) sum[e] += to_f32<T>(v[e]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < PER; ++e)
+                    if (c0 + col + e < H) sum[e] += to_f32<T>(a[e]);
+            }
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < PER; ++e) tile[row][col + e] = from_f32<T>(sum[e]);
+    __syncthreads();
+    const int cc = t >> 2, piece = t & 3;
+    if (c0 + cc >= H) return;
+    T out[PER];
+#pragma unroll
+    for (int e = 0; e < PER; ++e) out[e] = tile[piece * PER + e][cc];
+    char *d = reinterpret_cast<char *>(dst) + ((int64_t)blockIdx.x * dst_rows_alloc + (c0 + cc)) * 64 + piece * 16;
+    *reinterpret_cast<u32x4 *>(d) = *reinterpret_cast<const u32x4 *>(out);
+}
+
 // one K-blocked row of ones (r < n_rows) and zeros (up to k_pad): the column of the weight
 // GEMM's right operand that turns its result into the bias gradient
 template <typename T>
@@ -346,7 +379,7 @@ struct BwdDims {
 struct BwdWs {
     float *dh, *dc, *dhs, *ufg, *dMp, *dUfp;
     int32_t *parent_of;
-    void *Mt, *Uft, *dZ, *G, *hs, *dZt, *At, *Gt, *Hkt;
+    void *Mt, *Uft, *dZ, *G, *dZt, *At, *Gt, *Hkt;
     size_t bytes;
 };
 
@@ -364,7 +397,6 @@ BwdWs carve_bwd_ws(int64_t n, const BwdDims &d, void *base) {
     w.Uft = c.take<char>((size_t)round_up(d.H, 256) * d.Hk * d.esz);
     w.dZ = c.take<char>((size_t)round_up(d.n_max, 128) * 4 * d.Hk * d.esz);
     w.G = c.take<char>((size_t)round_up(d.n_max, 128) * d.Hk * d.esz);
-    w.hs = c.take<char>((size_t)d.n_max * d.H * d.esz);
     w.dZt = c.take<char>((size_t)round_up(4 * d.Hk, 128) * d.n_pad * d.esz);
     w.At = c.take<char>((size_t)round_up(d.D + 1 + d.H, 256) * d.n_pad * d.esz);
     w.Gt = c.take<char>((size_t)round_up(d.Hk, 128) * d.n_pad * d.esz);
@@ -408,7 +440,7 @@ int run_backward(const T *x, const T *W, const T *U, const BwdDims &d, const jit
         JITDB_LAUNCH_CHECK();
     }
 
-    T *dZ = static_cast<T *>(w.dZ), *G = static_cast<T *>(w.G), *hs = static_cast<T *>(w.hs);
+    T *dZ = static_cast<T *>(w.dZ), *G = static_cast<T *>(w.G);
     T *dZt = static_cast<T *>(w.dZt), *At = static_cast<T *>(w.At), *Gt = static_cast<T *>(w.Gt), *Hkt = static_cast<T *>(w.Hkt);
     for (int l = L - 1; l >= 0; --l) {
         const int rows = lp[l + 1] - lp[l];
@@ -416,7 +448,6 @@ int run_backward(const T *x, const T *W, const T *U, const BwdDims &d, const jit
         const int32_t *nodes = s->perm + lp[l];
         const int kpad = (int)round_up(rows, 64);           // reduction length of the weight GEMMs
         const int64_t lvl_alloc = round_up(rows, 128);
-        const unsigned g_elem = (unsigned)ceil_div((int64_t)rows * H, kT);
         const dim3 tile_grid((unsigned)(kpad / (64 / (int)sizeof(T))), (unsigned)(Hk / 64));
         auto weight_gemm = [&](const T *A, int64_t a_alloc, int M, const T *B, int64_t b_alloc, int N, float *C, int ldc) {
             KbGemm g = {};
@@ -429,6 +460,8 @@ int run_backward(const T *x, const T *W, const T *U, const BwdDims &d, const jit
             g.epilogue = KB_EPI_ATOMIC_ACC; g.out0 = C; g.ldc = ldc;
             return launch_kb_gemm(dtype, g, st);
         };
+        // leaves have no children: their forget-gate block of dZ is zero and is left out of both GEMMs
+        const int n_gates = l > 0 ? 4 : 3;
         // what the level receives from above
         bwd_receive_kernel<T><<<tile_grid, kT, 0, st>>>(nodes, rows, H, Hk, w.parent_of, c, fgate, gh, gc, w.dhs,
                                                         w.dh, w.dc, G, lvl_alloc, Gt, gt_alloc);
@@ -445,13 +478,13 @@ int run_backward(const T *x, const T *W, const T *U, const BwdDims &d, const jit
             if ((rc = weight_gemm(Gt, gt_alloc, Hk, Hkt, ht_alloc, H, w.dUfp, H)) != JITDB_OK) return rc;
         }
         bwd_cell_kernel<T><<<tile_grid, kT, 0, st>>>(nodes, rows, H, Hk, s->child_ptr, s->child_idx, c, gates, fgate,
-                                                     w.dh, l < L - 1 ? w.ufg : nullptr, w.dc, dZ, lvl_alloc, dZt, zt_alloc);
+                                                     w.dh, l < L - 1 ? w.ufg : nullptr, w.dc, dZ, lvl_alloc, dZt, zt_alloc, n_gates);
         JITDB_LAUNCH_CHECK();
         {   // [dx | dhs] = dZ [W | U]; leaves have nobody to pass dhs to
             KbGemm g = {};
             g.A = dZ; g.a_rows_alloc = lvl_alloc; g.M = rows;
             g.B = w.Mt; g.b_rows_alloc = mt_alloc; g.N = l > 0 ? D + H : D;
-            g.k_bytes = (int64_t)4 * Hk * sizeof(T); g.k_splits = 1;
+            g.k_bytes = (int64_t)n_gates * Hk * sizeof(T); g.k_splits = 1;
             g.epilogue = KB_EPI_DX_DHS; g.out0 = dx; g.out1 = w.dhs; g.node = nodes; g.D = D; g.H = H;
             if ((rc = launch_kb_gemm(dtype, g, st)) != JITDB_OK) return rc;
         }
@@ -461,14 +494,16 @@ int run_backward(const T *x, const T *W, const T *U, const BwdDims &d, const jit
         JITDB_LAUNCH_CHECK();
         int q_cols = D + 1;
         if (l > 0) {
-            bwd_hsum_kernel<T><<<g_elem, kT, 0, st>>>(nodes, rows, H, s->child_ptr, s->child_idx, h, hs);
+            T *hs_rows = reinterpret_cast<T *>(reinterpret_cast<char *>(At) + (int64_t)(D + 1) * 64);
+            const dim3 grid((unsigned)(kpad / (64 / (int)sizeof(T))), (unsigned)ceil_div(H, 64));
+            if ((H * sizeof(T)) % 16 == 0)
+                hsum_transpose_kernel<T, true><<<grid, kT, 0, st>>>(h, nodes, rows, H, s->child_ptr, s->child_idx, hs_rows, at_alloc);
+            else
+                hsum_transpose_kernel<T, false><<<grid, kT, 0, st>>>(h, nodes, rows, H, s->child_ptr, s->child_idx, hs_rows, at_alloc);
             JITDB_LAUNCH_CHECK();
-            if ((rc = launch_transpose<T>(hs, nullptr, H, 0, rows, H, kpad,
-                                          reinterpret_cast<T *>(reinterpret_cast<char *>(At) + (int64_t)(D + 1) * 64),
-                                          at_alloc, st)) != JITDB_OK) return rc;
             q_cols = D + 1 + H;
         }
-        if ((rc = weight_gemm(dZt, zt_alloc, 4 * Hk, At, at_alloc, q_cols, w.dMp, D + 1 + H)) != JITDB_OK) return rc;
+        if ((rc = weight_gemm(dZt, zt_alloc, n_gates * Hk, At, at_alloc, q_cols, w.dMp, D + 1 + H)) != JITDB_OK) return rc;
     }
     unpack_grads_kernel<<<1024, kT, 0, st>>>(w.dMp, w.dUfp, D, H, Hk, dW, dU, db);
     JITDB_LAUNCH_CHECK();
