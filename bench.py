@@ -104,7 +104,7 @@ def train_bench(args, J, torch, cfg, dev, N, D, H, esz, peak_tflops, xt, Wt, Ut,
                    "step": "jitdb_schedule + jitdb_treelstm_forward_train + jitdb_treelstm_backward "
                            "(cotangents on h and c of every node), one stream"},
         "ms_forward_train": ms_f, "ms_backward": ms_b,
-        "roofline": {"kernel": "backward pass as a whole (its GEMMs: gemm_kb_kernel, gemm_nt_kernel)",
+        "roofline": {"kernel": "backward pass as a whole (its GEMMs: gemm_kb_kernel)",
                      "bound": "mfma", "achieved": 2.0 * f_min / (ms_b * 1e-3) / 1e12, "peak": peak_tflops,
                      "unit": "TFLOP/s", "frac": 2.0 * f_min / (ms_b * 1e-3) / 1e12 / peak_tflops, "traffic": None,
                      "flops_per_step": 2.0 * f_min},
