@@ -12,6 +12,8 @@ Contents
                        time; used where the numpy version is too slow
   treelstm_backward_oracle.py   reverse-mode gradients of the same forest, node by
                        node in fp64, and the activations a training forward keeps
+  cache_oracle.py      fingerprint of a parent array (the key of the schedule cache) and
+                       the cache's replacement policy
   build.py             compiles the C file with gcc
 
 Pins (tests/test_oracle_*.py): brute-force heights, chain / star / perfect
@@ -21,6 +23,7 @@ forget gates select children by the sign of their own h, zero-weight closed
 form c = i*u*subtree_size, relabelling and forest-vs-single-tree invariance,
 numpy oracle vs C oracle; for the gradient oracle: autograd of an independently
 written torch forward, a library LSTM differentiated by the library, central
-differences of the forward oracle, a one-leaf closed form.  Launch-count tables of the paper (Table 1, Table 2)
+differences of the forward oracle, a one-leaf closed form; for the fingerprint:
+the published SplitMix64 stream, hand arithmetic, sensitivity to single edits.  Launch-count tables of the paper (Table 1, Table 2)
 need its dataset: parity unpinned, nothing here reproduces them.
 """
