@@ -129,6 +129,44 @@ int jitdb_schedule_append(const jitdb_schedule_t *base, const int32_t *parent_ne
                           jitdb_schedule_t *out, void *workspace, size_t workspace_bytes,
                           void *hip_stream);
 
+/*
+ * Schedule cache (the paper keeps the rewritten graph and reuses it when the same structure
+ * returns, section 4.3).  The key is a 128-bit fingerprint of the parent array plus N:
+ *
+ *     word_i = i * 2^32 + (parent[i] mod 2^32)
+ *     fp[0]  = sum_i mix64(word_i + 0x9E3779B97F4A7C15)   mod 2^64
+ *     fp[1]  = sum_i mix64(word_i xor 0xD1B54A32D192ED03) mod 2^64
+ *
+ * with mix64 the output function of SplitMix64.  Two different forests of equal size share a
+ * key with probability about 2^-128; a caller that cannot accept that compares the parent
+ * arrays on a hit.
+ *
+ *   parent    dev [n_nodes] int32 (any values: the fingerprint does not validate the forest)
+ *   fp_dev    dev [2] uint64, written by the kernels
+ *   fp_host   host [2] uint64 or NULL.  If given, the result is copied there and the stream is
+ *             synchronised once; if NULL the call is asynchronous.
+ */
+int jitdb_forest_fingerprint(const int32_t *parent, int64_t n_nodes, uint64_t *fp_dev,
+                             uint64_t *fp_host, void *hip_stream);
+
+/*
+ * The table of the cache, host side only (no GPU call): it maps a key to one of `capacity`
+ * slots; the caller keeps the schedule objects, slot by slot, and owns their memory.
+ * Thread-safe.  Replacement: least recently used, a successful lookup counts as a use.
+ *
+ *   jitdb_cache_lookup   slot of the key, or -1 (also for NULL arguments)
+ *   jitdb_cache_insert   slot now assigned to the key: the key's own if present, else the
+ *                        lowest unused slot, else the slot of the least recently used key,
+ *                        which is dropped (*evicted = 1; evicted may be NULL)
+ *   jitdb_cache_stats    counts of lookups that hit / missed and of keys held (NULLs skipped)
+ */
+typedef struct jitdb_cache jitdb_cache_t;
+int jitdb_cache_create(int32_t capacity, jitdb_cache_t **out);   /* capacity in [1, 2^20] */
+void jitdb_cache_destroy(jitdb_cache_t *cache);
+int32_t jitdb_cache_lookup(jitdb_cache_t *cache, const uint64_t *fp, int64_t n_nodes);
+int32_t jitdb_cache_insert(jitdb_cache_t *cache, const uint64_t *fp, int64_t n_nodes, int32_t *evicted);
+void jitdb_cache_stats(const jitdb_cache_t *cache, int64_t *hits, int64_t *misses, int32_t *entries);
+
 /* Bytes of device workspace jitdb_treelstm_forward needs (0 if an argument is invalid). */
 size_t jitdb_treelstm_workspace_bytes(int64_t n_nodes, int64_t n_edges,
                                       int32_t D, int32_t H, jitdb_dtype dtype);

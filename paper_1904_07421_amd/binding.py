@@ -112,6 +112,21 @@ def load_library():
     lib.jitdb_probe_mfma.restype = ctypes.c_int
     lib.jitdb_probe_mfma.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
                                      ctypes.POINTER(ctypes.c_double)]
+    lib.jitdb_forest_fingerprint.restype = ctypes.c_int
+    lib.jitdb_forest_fingerprint.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
+                                             ctypes.POINTER(ctypes.c_uint64), ctypes.c_void_p]
+    lib.jitdb_cache_create.restype = ctypes.c_int
+    lib.jitdb_cache_create.argtypes = [ctypes.c_int32, ctypes.POINTER(ctypes.c_void_p)]
+    lib.jitdb_cache_destroy.restype = None
+    lib.jitdb_cache_destroy.argtypes = [ctypes.c_void_p]
+    lib.jitdb_cache_lookup.restype = ctypes.c_int32
+    lib.jitdb_cache_lookup.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_uint64), ctypes.c_int64]
+    lib.jitdb_cache_insert.restype = ctypes.c_int32
+    lib.jitdb_cache_insert.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_uint64), ctypes.c_int64,
+                                       ctypes.POINTER(ctypes.c_int32)]
+    lib.jitdb_cache_stats.restype = None
+    lib.jitdb_cache_stats.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64),
+                                      ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int32)]
     lib.jitdb_strerror.restype = ctypes.c_char_p
     lib.jitdb_strerror.argtypes = [ctypes.c_int]
     lib.jitdb_last_hip_error.restype = ctypes.c_char_p
@@ -390,3 +405,81 @@ def _forward(x, W, U, b, schedule, stream, workspace, out, train):
                 workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
     _check(code)
     return (h, c, gates, fgate) if train else (h, c)
+
+
+def jitdb_forest_fingerprint(parent, stream=None, fp_dev=None) -> Tuple[int, int]:
+    """(fp[0], fp[1]) of an int32 CUDA parent tensor; synchronises the stream."""
+    import torch
+    if parent.dtype != torch.int32 or not parent.is_cuda or not parent.is_contiguous():
+        raise TypeError("parent must be a contiguous int32 CUDA tensor")
+    if fp_dev is None:
+        fp_dev = torch.empty(2, dtype=torch.int64, device=parent.device)
+    host = (ctypes.c_uint64 * 2)()
+    n = parent.numel()
+    with torch.cuda.device(parent.device):
+        _check(load_library().jitdb_forest_fingerprint(parent.data_ptr() if n else None, n, fp_dev.data_ptr(),
+                                                       host, _stream_ptr(stream)))
+    return int(host[0]), int(host[1])
+
+
+class CacheTable:
+    """The library's key -> slot table (host only; usable without a GPU)."""
+
+    def __init__(self, capacity: int):
+        self._lib = load_library()
+        self._h = ctypes.c_void_p()
+        _check(self._lib.jitdb_cache_create(int(capacity), ctypes.byref(self._h)))
+        self.capacity = int(capacity)
+
+    def close(self):
+        if self._h:
+            self._lib.jitdb_cache_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def lookup(self, fp: Tuple[int, int], n_nodes: int) -> int:
+        return int(self._lib.jitdb_cache_lookup(self._h, (ctypes.c_uint64 * 2)(*fp), int(n_nodes)))
+
+    def insert(self, fp: Tuple[int, int], n_nodes: int) -> Tuple[int, bool]:
+        ev = ctypes.c_int32(0)
+        slot = int(self._lib.jitdb_cache_insert(self._h, (ctypes.c_uint64 * 2)(*fp), int(n_nodes), ctypes.byref(ev)))
+        return slot, bool(ev.value)
+
+    def stats(self) -> dict:
+        h, m, e = ctypes.c_int64(0), ctypes.c_int64(0), ctypes.c_int32(0)
+        self._lib.jitdb_cache_stats(self._h, ctypes.byref(h), ctypes.byref(m), ctypes.byref(e))
+        return {"hits": int(h.value), "misses": int(m.value), "entries": int(e.value)}
+
+
+class ScheduleCache:
+    """Schedules kept by fingerprint of their parent array: get(parent) returns the cached
+    Schedule when this forest was scheduled before, else schedules it and keeps the result
+    (dropping the least recently used one when full).  verify=True also keeps the parent
+    arrays and compares them on a hit."""
+
+    def __init__(self, capacity: int = 16, verify: bool = False):
+        self.table = CacheTable(capacity)
+        self._slots = [None] * int(capacity)
+        self._parents = [None] * int(capacity) if verify else None
+        self._fp_dev = None
+
+    def get(self, parent, stream=None) -> Tuple[Schedule, bool]:
+        import torch
+        if self._fp_dev is None or self._fp_dev.device != parent.device:
+            self._fp_dev = torch.empty(2, dtype=torch.int64, device=parent.device)
+        fp = jitdb_forest_fingerprint(parent, stream=stream, fp_dev=self._fp_dev)
+        n = parent.numel()
+        slot = self.table.lookup(fp, n)
+        if slot >= 0 and (self._parents is None or torch.equal(self._parents[slot], parent)):
+            return self._slots[slot], True
+        sched = jitdb_schedule(parent, stream=stream)
+        slot, _ = self.table.insert(fp, n)
+        self._slots[slot] = sched
+        if self._parents is not None:
+            self._parents[slot] = parent.clone()
+        return sched, False
