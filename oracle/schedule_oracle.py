@@ -177,3 +177,50 @@ def concat_forests(parent_a, parent_b) -> np.ndarray:
     b = np.asarray(parent_b, dtype=np.int64)
     shifted = np.where(b >= 0, b + a.shape[0], b)
     return np.concatenate([a, shifted]).astype(np.int32)
+
+
+def schedule_typed(parent, sig, n_sig: int) -> dict:
+    """The look-up table of the generic batcher (section 4.2): nodes are filed by depth and by
+    a signature that stands for (operator type, settings, input layouts).  Same outputs as
+    `schedule`, with positions sorted by (height, sig, id), plus
+      key[N] = height * n_sig + sig,
+      slot_ptr[L * n_sig + 1]: slot (l, t) holds positions [slot_ptr[l*n_sig+t], slot_ptr[l*n_sig+t+1]).
+    Plain Python: sorted() on tuples and counting."""
+    parent = np.asarray(parent)
+    sig = np.asarray(sig)
+    n = parent.shape[0]
+    if sig.shape[0] != n or ((sig < 0) | (sig >= n_sig)).any():
+        raise ForestError("range", "signature outside [0, n_sig)")
+    out = schedule(parent)
+    h = out["height"]
+    L = out["n_levels"]
+    order = sorted(range(n), key=lambda v: (int(h[v]), int(sig[v]), v))
+    perm = np.array(order, dtype=np.int32)
+    inv_perm = np.zeros(n, dtype=np.int32)
+    for pos, v in enumerate(order):
+        inv_perm[v] = pos
+    key = (h.astype(np.int64) * n_sig + sig).astype(np.int32)
+    slot_ptr = np.zeros(L * n_sig + 1, dtype=np.int32)
+    for q in range(L * n_sig + 1):
+        slot_ptr[q] = int(np.count_nonzero(key < q))
+    out.update(perm=perm, inv_perm=inv_perm, key=key, slot_ptr=slot_ptr, n_sig=n_sig)
+    return out
+
+
+def schedule_typed_fast(parent, sig, n_sig: int) -> dict:
+    """schedule_typed with numpy routines (lexsort, bincount), for large forests; checked
+    against schedule_typed in the CPU tests."""
+    sig = np.asarray(sig).astype(np.int64)
+    out = schedule_fast(parent)
+    n = sig.shape[0]
+    if ((sig < 0) | (sig >= n_sig)).any():
+        raise ForestError("range", "signature outside [0, n_sig)")
+    h = out["height"].astype(np.int64)
+    L = out["n_levels"]
+    key = h * n_sig + sig
+    perm = np.lexsort((np.arange(n), key)).astype(np.int32)
+    inv_perm = np.empty(n, dtype=np.int32)
+    inv_perm[perm] = np.arange(n, dtype=np.int32)
+    slot_ptr = np.concatenate(([0], np.cumsum(np.bincount(key, minlength=L * n_sig)))).astype(np.int32)
+    out.update(perm=perm, inv_perm=inv_perm, key=key.astype(np.int32), slot_ptr=slot_ptr, n_sig=n_sig)
+    return out

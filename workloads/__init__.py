@@ -17,4 +17,7 @@ from .forests import (  # noqa: F401
     chain_forest,
     star_forest,
     perfect_kary_tree,
+    tree_signatures,
+    mixed_forest,
+    make_values_typed,
 )

@@ -246,3 +246,46 @@ def perfect_kary_tree(k: int, depth: int) -> np.ndarray:
     par = (np.arange(n, dtype=np.int64) - 1) // k
     par[0] = -1
     return par.astype(np.int32)
+
+
+# --------------------------------------------------------------------------
+# several networks in one batch (the generic batcher's signatures)
+# --------------------------------------------------------------------------
+def tree_signatures(parent: np.ndarray, n_sig: int, seed: int) -> np.ndarray:
+    """sig [N] int32: every tree draws one of n_sig signatures uniformly; all its nodes carry it."""
+    r = tree_ranges(parent)
+    rng = np.random.default_rng(seed)
+    per_tree = rng.integers(0, n_sig, size=len(r) - 1).astype(np.int32)
+    return np.repeat(per_tree, np.diff(r)).astype(np.int32)
+
+
+def mixed_forest(cfg_index: int, n_trees: int, n_seqs: int, len_lo: int, len_hi: int, seed: int):
+    """(parent, sig): n_trees trees of the config (signature 0) followed by n_seqs chains of
+    length U[len_lo, len_hi] (signature 1) - a Tree-LSTM batch and a variable-length LSTM
+    batch filed in one table.  Trees are laid out one after another, root first."""
+    trees = make_forest(cfg_index, n_trees)
+    rng = np.random.default_rng(seed)
+    lens = rng.integers(len_lo, len_hi + 1, size=n_seqs)
+    seqs = _concat([_chain_parents(int(n)) for n in lens]) if n_seqs else np.zeros(0, dtype=np.int32)
+    parent = _concat([trees, seqs]) if n_seqs else trees
+    sig = np.concatenate([np.zeros(trees.shape[0], np.int32), np.ones(seqs.shape[0], np.int32)])
+    return parent.astype(np.int32), sig
+
+
+def make_values_typed(cfg_index: int, n_nodes: int, n_sig: int, bias: str = "random",
+                      D: int | None = None, H: int | None = None):
+    """x [N, D], W [n_sig, 4H, D], U [n_sig, 4H, H], b [n_sig, 4H]: one weight set per signature,
+    drawn like make_values from different streams."""
+    cfg = CONFIGS[cfg_index]
+    D = cfg.D if D is None else D
+    H = cfg.H if H is None else H
+    x = make_values(cfg_index, n_nodes, bias, D, H)[0]
+    Ws, Us, bs = [], [], []
+    for t in range(n_sig):
+        rng = np.random.default_rng(5000 + 17 * cfg.index + t)
+        kw, ku = 1.0 / np.sqrt(D), 1.0 / np.sqrt(H)
+        Ws.append(rng.uniform(-kw, kw, size=(4 * H, D)).astype(np.float32))
+        Us.append(rng.uniform(-ku, ku, size=(4 * H, H)).astype(np.float32))
+        bs.append(rng.uniform(-0.5, 0.5, size=4 * H).astype(np.float32) if bias == "random"
+                  else np.zeros(4 * H, np.float32))
+    return x, np.stack(Ws), np.stack(Us), np.stack(bs)
