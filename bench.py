@@ -112,6 +112,76 @@ def train_bench(args, J, torch, cfg, dev, N, D, H, esz, peak_tflops, xt, Wt, Ut,
     print(json.dumps(out), flush=True)
 
 
+def typed_bench(args, J, torch, cfg, dev, N, D, H, esz, peak_tflops, xt, parent, n_leaf, n_int, E):
+    """Several cells in one table: step = jitdb_schedule_typed + jitdb_treelstm_forward_typed, one stream.
+    Every tree draws one of --signatures networks; the work per node is that of the headline step."""
+    from workloads import tree_signatures, make_values_typed, to_bf16_bits
+    T = args.signatures
+    sig = tree_signatures(parent, T, 99)
+    _, W, U, b = make_values_typed(cfg.index, 1, T, bias="zero")
+    if esz == 2:
+        up = lambda a: torch.from_numpy(to_bf16_bits(a).view(np.int16)).view(torch.bfloat16).to(dev)
+    else:
+        up = lambda a: torch.from_numpy(a).to(dev)
+    Wt, Ut, bt = up(W), up(U), torch.from_numpy(b).to(dev)
+    pt, st_ = torch.from_numpy(parent).to(dev), torch.from_numpy(sig).to(dev)
+    dt = J.JITDB_BF16 if esz == 2 else J.JITDB_F32
+    sched = J.jitdb_schedule_typed(pt, st_, T)
+    ws_s = torch.empty(J.jitdb_schedule_typed_workspace_bytes(N, T), dtype=torch.uint8, device=dev)
+    ws_f = torch.empty(J.jitdb_treelstm_typed_workspace_bytes(N, E, D, H, dt, T), dtype=torch.uint8, device=dev)
+    h = torch.empty((N, H), dtype=xt.dtype, device=dev)
+    c = torch.empty((N, H), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def sch():
+        J.jitdb_schedule_typed(pt, st_, T, stream=stream, workspace=ws_s, out=sched)
+
+    def fwd():
+        J.jitdb_treelstm_forward_typed(xt, Wt, Ut, bt, sched, stream=stream, workspace=ws_f, out=(h, c))
+
+    def step():
+        sch()
+        fwd()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    def timed(fn, reps):
+        e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            fn()
+        e1.record(stream)
+        e1.synchronize()
+        return e0.elapsed_time(e1) / reps
+    reps = max(3, min(args.steps, 10))
+    ms_s, ms_f = timed(sch, reps), timed(fwd, reps)
+    f_min = n_leaf * 2.0 * D * 3 * H + n_int * (2.0 * D * 4 * H + 2.0 * H * 3 * H) + E * 2.0 * H * H
+    S = sched.n_levels * T
+    nonempty = int(np.count_nonzero(np.diff(sched.host_slot_ptr[:S + 1])))
+    out = {
+        "metric": f"Tree-LSTM forward nodes/sec on 1 MI355X, {T} cells in one table", "value": N / (ms_step * 1e-3),
+        "unit": "nodes/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"config {cfg.index}: {cfg.name}, each tree under one of {T} networks",
+                   "n_trees": cfg.n_trees, "n_nodes": N, "n_edges": E, "n_levels": sched.n_levels, "n_sig": T,
+                   "slots": S, "non_empty_slots": nonempty, "D": D, "H": H,
+                   "step": "jitdb_schedule_typed + jitdb_treelstm_forward_typed, one stream"},
+        "ms_schedule": ms_s, "ms_forward": ms_f,
+        "roofline": {"kernel": "typed forward as a whole (level_kernel / thin_kernel per slot)", "bound": "mfma",
+                     "achieved": f_min / (ms_f * 1e-3) / 1e12, "peak": peak_tflops, "unit": "TFLOP/s",
+                     "frac": f_min / (ms_f * 1e-3) / 1e12 / peak_tflops, "traffic": None, "flops_per_step": f_min},
+    }
+    print(json.dumps(out), flush=True)
+
+
 def log(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
@@ -132,6 +202,9 @@ def main():
     ap.add_argument("--train", action="store_true",
                     help="time the training step instead (schedule + forward that keeps the gates + backward); "
                          "not the headline metric")
+    ap.add_argument("--signatures", type=int, default=0,
+                    help="time the typed table instead: every tree under one of this many networks "
+                         "(jitdb_schedule_typed + jitdb_treelstm_forward_typed); not the headline metric")
     ap.add_argument("--serial", action="store_true",
                     help="schedule and forward of a batch strictly one after the other on one stream "
                          "(default: the schedule of the next batch overlaps the forward of this one)")
@@ -179,6 +252,8 @@ def main():
     n_leaf = int(lp[1])
     n_int = N - n_leaf
     ws_s = torch.empty(J.jitdb_schedule_workspace_bytes(N), dtype=torch.uint8, device=dev)
+    if args.signatures > 0:
+        return typed_bench(args, J, torch, cfg, dev, N, D, H, esz, peak_tflops, xt, parent, n_leaf, n_int, E)
     if args.train:
         return train_bench(args, J, torch, cfg, dev, N, D, H, esz, peak_tflops, xt, Wt, Ut, bt, pt, sched, ws_s,
                            n_leaf, n_int, E, L)

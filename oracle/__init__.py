@@ -8,8 +8,8 @@ Contents
   schedule_oracle.py   heights / level buckets / permutation / child CSR, plus
                        an independent brute-force height routine for tiny trees;
                        schedule_typed: the same table filed by (depth, signature)
-  treelstm_oracle.py   node-by-node postorder evaluation in fp64 (numpy); forward_typed:
-                       one cell (weight set) per signature
+  treelstm_oracle.py   node-by-node postorder evaluation in fp64 (numpy)
+  treelstm_typed_oracle.py   the same with one cell (weight set) per signature
   treelstm_oracle.c    the same definition in plain C (fp64), one tree at a
                        time; used where the numpy version is too slow
   treelstm_backward_oracle.py   reverse-mode gradients of the same forest, node by

@@ -43,6 +43,16 @@ class _ScheduleStruct(ctypes.Structure):
     ]
 
 
+class _SlotsStruct(ctypes.Structure):
+    _fields_ = [
+        ("n_sig", ctypes.c_int32),
+        ("slot_capacity", ctypes.c_int64),
+        ("key", ctypes.c_void_p),
+        ("slot_ptr", ctypes.c_void_p),
+        ("host_slot_ptr", ctypes.c_void_p),
+    ]
+
+
 K_CLASSES = ("pack", "stack", "leaf", "internal", "proj", "thin_leaf", "thin_internal", "thin_proj")
 
 
@@ -112,6 +122,21 @@ def load_library():
     lib.jitdb_probe_mfma.restype = ctypes.c_int
     lib.jitdb_probe_mfma.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
                                      ctypes.POINTER(ctypes.c_double)]
+    lib.jitdb_schedule_typed_workspace_bytes.restype = ctypes.c_size_t
+    lib.jitdb_schedule_typed_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32]
+    lib.jitdb_schedule_typed.restype = ctypes.c_int
+    lib.jitdb_schedule_typed.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.POINTER(_ScheduleStruct),
+                                         ctypes.POINTER(_SlotsStruct), ctypes.c_void_p, ctypes.c_size_t,
+                                         ctypes.c_void_p]
+    lib.jitdb_treelstm_typed_workspace_bytes.restype = ctypes.c_size_t
+    lib.jitdb_treelstm_typed_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
+                                                         ctypes.c_int32, ctypes.c_int, ctypes.c_int32]
+    lib.jitdb_treelstm_forward_typed.restype = ctypes.c_int
+    lib.jitdb_treelstm_forward_typed.argtypes = [
+        ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+        ctypes.c_int32, ctypes.c_int32, ctypes.c_int,
+        ctypes.POINTER(_ScheduleStruct), ctypes.POINTER(_SlotsStruct), ctypes.c_void_p, ctypes.c_void_p,
+        ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     lib.jitdb_forest_fingerprint.restype = ctypes.c_int
     lib.jitdb_forest_fingerprint.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
                                              ctypes.POINTER(ctypes.c_uint64), ctypes.c_void_p]
@@ -483,3 +508,102 @@ class ScheduleCache:
         if self._parents is not None:
             self._parents[slot] = parent.clone()
         return sched, False
+
+
+class TypedSchedule(Schedule):
+    """A Schedule whose positions are filed by (height, signature), plus the slot table."""
+
+    def __init__(self, n_nodes: int, n_sig: int, device, slot_capacity: Optional[int] = None):
+        import torch
+        super().__init__(n_nodes, device)
+        self.n_sig = int(n_sig)
+        cap = int(n_nodes) * self.n_sig + 1 if slot_capacity is None else int(slot_capacity)
+        self.key = torch.empty(max(int(n_nodes), 1), dtype=torch.int32, device=device)
+        self.slot_ptr = torch.empty(cap, dtype=torch.int32, device=device)
+        self.host_slot_ptr = np.zeros(cap, dtype=np.int32)
+        self.slots = _SlotsStruct(self.n_sig, cap, self.key.data_ptr(), self.slot_ptr.data_ptr(),
+                                  self.host_slot_ptr.ctypes.data)
+
+    def to_numpy(self) -> dict:
+        out = super().to_numpy()
+        S = self.n_levels * self.n_sig
+        out.update(key=self.key[:self.n_nodes].cpu().numpy(), slot_ptr=self.slot_ptr[:S + 1].cpu().numpy(),
+                   host_slot_ptr=self.host_slot_ptr[:S + 1].copy(), n_sig=self.n_sig)
+        return out
+
+
+def jitdb_schedule_typed_workspace_bytes(n_nodes: int, n_sig: int) -> int:
+    return int(load_library().jitdb_schedule_typed_workspace_bytes(int(n_nodes), int(n_sig)))
+
+
+def jitdb_schedule_typed(parent, sig, n_sig: int, stream=None, workspace=None,
+                         out: Optional[TypedSchedule] = None, slot_capacity: Optional[int] = None) -> TypedSchedule:
+    """parent, sig: int32 CUDA tensors [N]; sig[v] in [0, n_sig), constant inside a tree."""
+    import torch
+    lib = load_library()
+    for t, name in ((parent, "parent"), (sig, "sig")):
+        if t.dtype != torch.int32 or not t.is_cuda or not t.is_contiguous():
+            raise TypeError(f"{name} must be a contiguous int32 CUDA tensor")
+    n = parent.numel()
+    if sig.numel() != n:
+        raise ValueError("sig and parent differ in length")
+    if out is not None and (out.n_nodes != n or out.n_sig != n_sig):
+        raise ValueError("out was made for another size or signature count")
+    sched = out if out is not None else TypedSchedule(n, n_sig, parent.device, slot_capacity)
+    need = jitdb_schedule_typed_workspace_bytes(n, n_sig)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=parent.device)
+    with torch.cuda.device(parent.device):
+        code = lib.jitdb_schedule_typed(parent.data_ptr() if n else None, sig.data_ptr() if n else None,
+                                        ctypes.byref(sched.struct), ctypes.byref(sched.slots),
+                                        workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
+    _check(code)
+    sched.n_levels = int(sched.struct.n_levels)
+    sched.n_edges = int(sched.struct.n_edges)
+    return sched
+
+
+def jitdb_treelstm_typed_workspace_bytes(n_nodes: int, n_edges: int, D: int, H: int, dtype: int, n_sig: int) -> int:
+    return int(load_library().jitdb_treelstm_typed_workspace_bytes(int(n_nodes), int(n_edges), int(D), int(H),
+                                                                   int(dtype), int(n_sig)))
+
+
+def jitdb_treelstm_forward_typed(x, W, U, b, schedule: TypedSchedule, stream=None, workspace=None,
+                                 out: Optional[Tuple] = None):
+    """x [N, D]; W [n_sig, 4H, D], U [n_sig, 4H, H] in x's dtype, b [n_sig, 4H] fp32: node j is
+    evaluated by cell sig[j].  Returns (h, c) as jitdb_treelstm_forward."""
+    import torch
+    lib = load_library()
+    if x.dtype == torch.float32:
+        dt = JITDB_F32
+    elif x.dtype == torch.bfloat16:
+        dt = JITDB_BF16
+    else:
+        raise TypeError("x must be float32 or bfloat16")
+    for t, name in ((x, "x"), (W, "W"), (U, "U"), (b, "b")):
+        if not t.is_cuda or not t.is_contiguous():
+            raise TypeError(f"{name} must be a contiguous CUDA tensor")
+    if W.dtype != x.dtype or U.dtype != x.dtype or b.dtype != torch.float32:
+        raise TypeError("W, U must have x's dtype and b must be float32")
+    n, T = schedule.n_nodes, schedule.n_sig
+    if W.dim() != 3 or U.dim() != 3 or b.dim() != 2:
+        raise ValueError("W, U, b need a leading signature axis")
+    H, D = U.shape[2], W.shape[2]
+    if x.shape != (n, D) or W.shape != (T, 4 * H, D) or U.shape != (T, 4 * H, H) or b.shape != (T, 4 * H):
+        raise ValueError("shape mismatch between x, W, U, b and the schedule")
+    if out is None:
+        h = torch.empty((n, H), dtype=x.dtype, device=x.device)
+        c = torch.empty((n, H), dtype=torch.float32, device=x.device)
+    else:
+        h, c = out
+    need = jitdb_treelstm_typed_workspace_bytes(n, schedule.n_edges, D, H, dt, T)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    with torch.cuda.device(x.device):
+        code = lib.jitdb_treelstm_forward_typed(
+            x.data_ptr() if n else None, W.data_ptr(), U.data_ptr(), b.data_ptr(), D, H, dt,
+            ctypes.byref(schedule.struct), ctypes.byref(schedule.slots),
+            h.data_ptr() if n else None, c.data_ptr() if n else None,
+            workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
+    _check(code)
+    return h, c

@@ -1196,12 +1196,15 @@ Dims make_dims(int D, int H, jitdb_dtype dtype) {
     return d;
 }
 
-ForwardWs carve_forward_ws(int64_t n, int64_t e, const Dims &d, void *base) {
+// packed weights of one cell: bytes of Bp, floats of bp (one set per signature, back to back)
+size_t packed_w_bytes(const Dims &d) { return (size_t)d.NPU * (d.Dp + d.Hp) * d.esz; }
+
+ForwardWs carve_forward_ws(int64_t n, int64_t e, const Dims &d, void *base, int n_sig = 1) {
     Carver c(base);
     ForwardWs w;
     (void)e;
-    w.Bp = c.take<char>((size_t)d.NPU * (d.Dp + d.Hp) * d.esz);
-    w.bp = c.take<float>(d.NP);
+    w.Bp = c.take<char>(packed_w_bytes(d) * n_sig);
+    w.bp = c.take<float>((size_t)d.NP * n_sig);
     // one level at a time; whole row tiles are read, hence the 256 spare rows
     w.stack = c.take<char>((size_t)(n + kRowPad) * (d.Dp + d.Hp) * d.esz);
     w.row_rec = c.take<int4>((size_t)2 * (n + kRowPad));   // every level position
@@ -1220,34 +1223,39 @@ bool dims_ok(int64_t n, int64_t e, int32_t D, int32_t H, int dtype) {
     return true;
 }
 
+// One batched evaluation per slot of the table, levels in ascending order.  Without `slots` a
+// level is one slot and there is one cell; with it, slot (l, t) is evaluated by cell t (its
+// own packed weights), and the records keep every row inside its slot.
 template <typename T, bool SAVE>
 int run_forward(const void *x, const void *W, const void *U, const float *b, const Dims &d,
-                const jitdb_schedule_t *s, void *h_out, float *c_out, float *gates, float *fgate,
+                const jitdb_schedule_t *s, const jitdb_slots_t *slots,
+                void *h_out, float *c_out, float *gates, float *fgate,
                 const ForwardWs &w, hipStream_t st) {
     const int L = s->n_levels;
-    const int32_t *lp = s->host_level_ptr;
+    const int n_sig = slots ? slots->n_sig : 1;
+    const int32_t *sp = slots ? slots->host_slot_ptr : s->host_level_ptr;
 
-    {
+    for (int t = 0; t < n_sig; ++t) {
         const int64_t total = (int64_t)d.NPU * (d.Dp + d.Hp);
         const unsigned grid = (unsigned)(ceil_div(total, kThreads) < 4096 ? ceil_div(total, kThreads) : 4096);
         ScopedLaunchTimer tm(JITDB_K_PACK, 0, st);
         pack_weights_kernel<T><<<grid, kThreads, 0, st>>>(
-            static_cast<const T *>(W), static_cast<const T *>(U), b, d.D, d.H, d.Dp, d.Hp, d.NP, d.NPU,
-            static_cast<T *>(w.Bp), w.bp);
+            static_cast<const T *>(W) + (size_t)t * 4 * d.H * d.D, static_cast<const T *>(U) + (size_t)t * 4 * d.H * d.H,
+            b + (size_t)t * 4 * d.H, d.D, d.H, d.Dp, d.Hp, d.NP, d.NPU,
+            reinterpret_cast<T *>(static_cast<char *>(w.Bp) + packed_w_bytes(d) * t), w.bp + (size_t)d.NP * t);
         JITDB_LAUNCH_CHECK();
     }
 
     {
         ScopedLaunchTimer tm(JITDB_K_PACK, 0, st);
         row_record_kernel<<<(unsigned)ceil_div(s->n_nodes, kRecWindow), kThreads, 0, st>>>(
-            s->perm, s->height, s->child_ptr, s->child_idx, w.row_rec, (int)s->n_nodes);
+            s->perm, slots ? slots->key : s->height, s->child_ptr, s->child_idx, w.row_rec, (int)s->n_nodes);
         JITDB_LAUNCH_CHECK();
     }
 
     LevelArgs a;
     a.stack = w.stack;
     a.hs = w.hs ? w.hs : h_out;
-    a.Bp = w.Bp; a.bp = w.bp;
     a.child_idx = s->child_idx;
 
     a.P = w.P; a.c_out = c_out; a.h_out = h_out;
@@ -1259,10 +1267,14 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
     a.D = d.D; a.Dp = d.Dp; a.H = d.H; a.Hp = d.Hp; a.Hu = d.Hu;
     a.NPU = d.NPU;
 
-    for (int l = 0; l < L; ++l) {
-        const int n_rows = lp[l + 1] - lp[l];
-        if (n_rows <= 0) return JITDB_E_SCHEDULE;
-        a.row_rec = w.row_rec + 2 * (int64_t)lp[l];
+    for (int q = 0; q < L * n_sig; ++q) {
+        const int l = q / n_sig, sig = q % n_sig;
+        const int n_rows = sp[q + 1] - sp[q];
+        if (n_rows < 0 || (n_rows == 0 && !slots)) return JITDB_E_SCHEDULE;
+        if (n_rows == 0) continue;
+        a.Bp = static_cast<char *>(w.Bp) + packed_w_bytes(d) * sig;
+        a.bp = w.bp + (size_t)d.NP * sig;
+        a.row_rec = w.row_rec + 2 * (int64_t)sp[q];
         a.n_rows = n_rows;
         a.n_rows_alloc = (int)round_up(n_rows, kRowPad);
         const int row_tiles = (int)ceil_div(n_rows, kDmaBM);
@@ -1422,10 +1434,12 @@ extern "C" size_t jitdb_treelstm_workspace_bytes(int64_t n_nodes, int64_t n_edge
 
 namespace {
 int forward_entry(const void *x, const void *W, const void *U, const float *b, int32_t D, int32_t H,
-                  jitdb_dtype dtype, const jitdb_schedule_t *s, void *h_out, float *c_out,
-                  float *gates, float *fgate, bool save,
+                  jitdb_dtype dtype, const jitdb_schedule_t *s, const jitdb_slots_t *slots,
+                  void *h_out, float *c_out, float *gates, float *fgate, bool save,
                   void *workspace, size_t workspace_bytes, void *hip_stream) {
     if (!s) return JITDB_E_NULL;
+    const int n_sig = slots ? slots->n_sig : 1;
+    if (n_sig < 1 || n_sig > JITDB_MAX_SIGNATURES) return JITDB_E_BADARG;
     drop_stale_hip_error();
     const int64_t n = s->n_nodes;
     if (!dims_ok(n, s->n_edges, D, H, (int)dtype)) return JITDB_E_BADARG;
@@ -1443,17 +1457,25 @@ int forward_entry(const void *x, const void *W, const void *U, const float *b, i
     if (s->host_level_ptr[0] != 0 || s->host_level_ptr[L] != n) return JITDB_E_SCHEDULE;
     for (int l = 0; l < L; ++l)
         if (s->host_level_ptr[l + 1] <= s->host_level_ptr[l]) return JITDB_E_SCHEDULE;
+    if (slots) {
+        if (!slots->key || !slots->host_slot_ptr) return JITDB_E_NULL;
+        if (slots->slot_capacity < (int64_t)L * n_sig + 1) return JITDB_E_SCHEDULE;
+        for (int q = 0; q < L * n_sig; ++q)
+            if (slots->host_slot_ptr[q + 1] < slots->host_slot_ptr[q]) return JITDB_E_SCHEDULE;
+        for (int l = 0; l <= L; ++l)
+            if (slots->host_slot_ptr[(int64_t)l * n_sig] != s->host_level_ptr[l]) return JITDB_E_SCHEDULE;
+    }
 
     const Dims d = make_dims(D, H, dtype);
-    const ForwardWs w = carve_forward_ws(n, s->n_edges, d, workspace);
+    const ForwardWs w = carve_forward_ws(n, s->n_edges, d, workspace, n_sig);
     if (workspace_bytes < w.bytes) return JITDB_E_WORKSPACE;
     hipStream_t st = (hipStream_t)hip_stream;
     if (dtype == JITDB_F32) {
-        if (save) return run_forward<float, true>(x, W, U, b, d, s, h_out, c_out, gates, fgate, w, st);
-        return run_forward<float, false>(x, W, U, b, d, s, h_out, c_out, nullptr, nullptr, w, st);
+        if (save) return run_forward<float, true>(x, W, U, b, d, s, slots, h_out, c_out, gates, fgate, w, st);
+        return run_forward<float, false>(x, W, U, b, d, s, slots, h_out, c_out, nullptr, nullptr, w, st);
     }
-    if (save) return run_forward<bf16_t, true>(x, W, U, b, d, s, h_out, c_out, gates, fgate, w, st);
-    return run_forward<bf16_t, false>(x, W, U, b, d, s, h_out, c_out, nullptr, nullptr, w, st);
+    if (save) return run_forward<bf16_t, true>(x, W, U, b, d, s, slots, h_out, c_out, gates, fgate, w, st);
+    return run_forward<bf16_t, false>(x, W, U, b, d, s, slots, h_out, c_out, nullptr, nullptr, w, st);
 }
 }  // namespace
 
@@ -1461,7 +1483,24 @@ extern "C" int jitdb_treelstm_forward(const void *x, const void *W, const void *
                                       int32_t D, int32_t H, jitdb_dtype dtype,
                                       const jitdb_schedule_t *s, void *h_out, float *c_out,
                                       void *workspace, size_t workspace_bytes, void *hip_stream) {
-    return forward_entry(x, W, U, b, D, H, dtype, s, h_out, c_out, nullptr, nullptr, false,
+    return forward_entry(x, W, U, b, D, H, dtype, s, nullptr, h_out, c_out, nullptr, nullptr, false,
+                         workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" size_t jitdb_treelstm_typed_workspace_bytes(int64_t n_nodes, int64_t n_edges, int32_t D, int32_t H,
+                                                       jitdb_dtype dtype, int32_t n_sig) {
+    if (!dims_ok(n_nodes, n_edges, D, H, (int)dtype) || n_sig < 1 || n_sig > JITDB_MAX_SIGNATURES) return 0;
+    const Dims d = make_dims(D, H, dtype);
+    return carve_forward_ws(n_nodes, n_edges, d, nullptr, n_sig).bytes;
+}
+
+extern "C" int jitdb_treelstm_forward_typed(const void *x, const void *W, const void *U, const float *b,
+                                            int32_t D, int32_t H, jitdb_dtype dtype,
+                                            const jitdb_schedule_t *s, const jitdb_slots_t *slots,
+                                            void *h_out, float *c_out,
+                                            void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (!slots) return JITDB_E_NULL;
+    return forward_entry(x, W, U, b, D, H, dtype, s, slots, h_out, c_out, nullptr, nullptr, false,
                          workspace, workspace_bytes, hip_stream);
 }
 
@@ -1470,6 +1509,6 @@ extern "C" int jitdb_treelstm_forward_train(const void *x, const void *W, const 
                                             const jitdb_schedule_t *s, void *h_out, float *c_out,
                                             float *gates_out, float *fgate_out,
                                             void *workspace, size_t workspace_bytes, void *hip_stream) {
-    return forward_entry(x, W, U, b, D, H, dtype, s, h_out, c_out, gates_out, fgate_out, true,
+    return forward_entry(x, W, U, b, D, H, dtype, s, nullptr, h_out, c_out, gates_out, fgate_out, true,
                          workspace, workspace_bytes, hip_stream);
 }

@@ -29,7 +29,7 @@ constexpr int kWave = 64;
 constexpr int kWavesPerBlock = kThreads / kWave;
 
 // ---- device-side bookkeeping words -------------------------------------------------
-enum : int { META_ERR = 0, META_EDGES = 1, META_MAXH = 2, META_LIVE = 8, META_WORDS = 64 };
+enum : int { META_ERR = 0, META_EDGES = 1, META_MAXH = 2, META_SIG = 3, META_LIVE = 8, META_WORDS = 64 };
 
 // Thousands of waves updating ONE word with atomics serialise in L2 (about 10 ns each on
 // MI355X, measured: 0.4 ms for one atomic per wave at 2.4 M nodes).  Flags are therefore set
@@ -165,6 +165,39 @@ count_children_kernel(const int32_t *__restrict__ parent, int32_t n, int32_t *__
     }
     const unsigned long long bads = __ballot(bad);
     if (bads && (threadIdx.x & (kWave - 1)) == 0) atomicOr(&meta[META_ERR], 1);   // rare
+}
+
+// ---- signatures (the generic batcher's second key) ----------------------------------
+// A signature must lie in [0, n_sig) and be the same along every edge: the unit that carries
+// a signature is a sample's whole graph (a tree and the network that evaluates it).
+__global__ void __launch_bounds__(kThreads)
+check_signatures_kernel(const int32_t *__restrict__ parent, const int32_t *__restrict__ sig, int32_t n,
+                        int32_t n_sig, int32_t *__restrict__ meta) {
+    const int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    bool bad = false;
+    if (v < n) {
+        const int32_t t = sig[v], p = parent[v];
+        bad = t < 0 || t >= n_sig;
+        if (!bad && p >= 0 && p < n && p != (int32_t)v) bad = sig[p] != t;
+    }
+    const unsigned long long bads = __ballot(bad);
+    if (bads && (threadIdx.x & (kWave - 1)) == 0) atomicOr(&meta[META_SIG], 1);   // rare
+}
+
+// key = height * n_sig + sig: sorting by it files the nodes by (depth, signature)
+__global__ void __launch_bounds__(kThreads)
+slot_key_kernel(const int32_t *__restrict__ height, const int32_t *__restrict__ sig, int32_t n, int32_t n_sig,
+                int32_t *__restrict__ key) {
+    const int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (v < n) key[v] = height[v] * n_sig + sig[v];
+}
+
+// level_ptr[l] = slot_ptr[l * n_sig], l = 0 .. n_levels
+__global__ void __launch_bounds__(kThreads)
+level_from_slots_kernel(const int32_t *__restrict__ slot_ptr, int32_t n_levels, int32_t n_sig,
+                        int32_t *__restrict__ level_ptr) {
+    const int64_t l = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (l <= n_levels) level_ptr[l] = slot_ptr[l * n_sig];
 }
 
 // Round k of pointer jumping.  anc_in[v] is the 2^k-th ancestor of v (or -1).
@@ -391,12 +424,12 @@ struct ScheduleWs {
     size_t bytes;
 };
 
-ScheduleWs carve_schedule_ws(int64_t n, void *base) {
+ScheduleWs carve_schedule_ws(int64_t n, void *base, int64_t n_sig = 1) {
     Carver c(base);
     ScheduleWs w;
     const int64_t n_blocks = ceil_div(n > 0 ? n : 1, kBlockTile);
     const int64_t hist_len = (int64_t)kRadix * n_blocks;
-    const int64_t scan_len = (hist_len > n + 1 ? hist_len : n + 1);
+    const int64_t scan_len = (hist_len > n * n_sig + 1 ? hist_len : n * n_sig + 1);   // longest array ever scanned
     w.meta = c.take<int32_t>(META_WORDS);
     w.cnt = c.take<int32_t>(n + 1);
     w.anc[0] = c.take<int32_t>(n);
@@ -488,10 +521,20 @@ extern "C" size_t jitdb_schedule_workspace_bytes(int64_t n_nodes) {
     return carve_schedule_ws(n_nodes, nullptr).bytes;
 }
 
-extern "C" int jitdb_schedule(const int32_t *parent, jitdb_schedule_t *s,
-                              void *workspace, size_t workspace_bytes, void *hip_stream) {
+namespace {
+// The analysis, plain (sig == nullptr: one slot per level) or filed by (depth, signature).
+int schedule_impl(const int32_t *parent, const int32_t *sig, jitdb_slots_t *slots, jitdb_schedule_t *s,
+                  void *workspace, size_t workspace_bytes, void *hip_stream) {
     if (!s) return JITDB_E_NULL;
     drop_stale_hip_error();
+    const int32_t n_sig = slots ? slots->n_sig : 1;
+    if (slots) {
+        if (n_sig < 1 || n_sig > JITDB_MAX_SIGNATURES) return JITDB_E_BADARG;
+        if (s->n_nodes * (int64_t)n_sig >= (int64_t(1) << 31)) return JITDB_E_BADARG;
+        if (!slots->host_slot_ptr) return JITDB_E_NULL;
+        if (slots->slot_capacity < 1) return JITDB_E_BADARG;
+        slots->host_slot_ptr[0] = 0;
+    }
     const int64_t n64 = s->n_nodes;
     if (n64 < 0 || n64 > JITDB_MAX_NODES) return JITDB_E_BADARG;
     if (!s->host_level_ptr) return JITDB_E_NULL;
@@ -499,6 +542,10 @@ extern "C" int jitdb_schedule(const int32_t *parent, jitdb_schedule_t *s,
     s->n_edges = 0;
     if (n64 == 0) {
         s->host_level_ptr[0] = 0;
+        if (slots && slots->slot_ptr) {
+            int rc = launch_fill(slots->slot_ptr, 1, 0, (hipStream_t)hip_stream);
+            if (rc != JITDB_OK) return rc;
+        }
         if (s->level_ptr) {
             int rc = launch_fill(s->level_ptr, 1, 0, (hipStream_t)hip_stream);
             if (rc != JITDB_OK) return rc;
@@ -512,8 +559,9 @@ extern "C" int jitdb_schedule(const int32_t *parent, jitdb_schedule_t *s,
     if (!parent || !s->height || !s->level_ptr || !s->perm || !s->inv_perm || !s->child_ptr ||
         !s->child_idx || !workspace)
         return JITDB_E_NULL;
+    if (slots && (!sig || !slots->key || !slots->slot_ptr)) return JITDB_E_NULL;
     if ((reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return JITDB_E_BADARG;
-    ScheduleWs w = carve_schedule_ws(n64, workspace);
+    ScheduleWs w = carve_schedule_ws(n64, workspace, n_sig);
     if (workspace_bytes < w.bytes) return JITDB_E_WORKSPACE;
 
     hipStream_t st = (hipStream_t)hip_stream;
@@ -526,6 +574,10 @@ extern "C" int jitdb_schedule(const int32_t *parent, jitdb_schedule_t *s,
     if ((rc = launch_fill(w.cnt, n64 + 1, 0, st)) != JITDB_OK) return rc;
     count_children_kernel<<<grid, kThreads, 0, st>>>(parent, n, w.cnt, w.anc[0], s->height, w.meta);
     JITDB_LAUNCH_CHECK();
+    if (slots) {
+        check_signatures_kernel<<<grid, kThreads, 0, st>>>(parent, sig, n, n_sig, w.meta);
+        JITDB_LAUNCH_CHECK();
+    }
 
     // 2. child_ptr = exclusive scan of the counts (N + 1 entries, the last is E)
     if ((rc = launch_exclusive_scan(w.cnt, n64, s->child_ptr, n64 + 1, w.sort.partial, st)) != JITDB_OK)
@@ -549,6 +601,7 @@ extern "C" int jitdb_schedule(const int32_t *parent, jitdb_schedule_t *s,
     JITDB_HIP_CHECK(hipMemcpyAsync(meta, w.meta, sizeof(meta), hipMemcpyDeviceToHost, st));
     JITDB_HIP_CHECK(hipStreamSynchronize(st));
     if (meta[META_ERR] != 0) return JITDB_E_PARENT_RANGE;
+    if (meta[META_SIG] != 0) return JITDB_E_SIGNATURE;
     if (rounds > 0 && meta[META_LIVE + rounds - 1] != 0) return JITDB_E_CYCLE;
     if (meta[META_EDGES] >= n) return JITDB_E_CYCLE;  // every node has a parent: no forest
     const int32_t L = meta[META_MAXH] + 1;
@@ -556,18 +609,34 @@ extern "C" int jitdb_schedule(const int32_t *parent, jitdb_schedule_t *s,
     s->n_levels = L;
     s->n_edges = meta[META_EDGES];
 
-    // 4. level_ptr = exclusive scan of the height histogram
-    if ((rc = launch_fill(s->level_ptr, (int64_t)L + 1, 0, st)) != JITDB_OK) return rc;
+    // 4. the table's slot boundaries = exclusive scan of the key histogram; key = height (one
+    //    slot per level) or height * n_sig + sig
+    const int64_t S = (int64_t)L * n_sig;             // slots, empty ones included
+    const int32_t *key = s->height;
+    int32_t *bounds = s->level_ptr;
+    if (slots) {
+        if (S + 1 > slots->slot_capacity) return JITDB_E_WORKSPACE;
+        slot_key_kernel<<<grid, kThreads, 0, st>>>(s->height, sig, n, n_sig, slots->key);
+        JITDB_LAUNCH_CHECK();
+        key = slots->key;
+        bounds = slots->slot_ptr;
+    }
+    if ((rc = launch_fill(bounds, S + 1, 0, st)) != JITDB_OK) return rc;
     {
         const unsigned g = (unsigned)(ceil_div(n64, kThreads) < 1024 ? ceil_div(n64, kThreads) : 1024);
-        level_hist_kernel<<<g, kThreads, 0, st>>>(s->height, n, L, s->level_ptr);
+        level_hist_kernel<<<g, kThreads, 0, st>>>(key, n, (int32_t)S, bounds);
         JITDB_LAUNCH_CHECK();
     }
-    if ((rc = launch_exclusive_scan(s->level_ptr, L, s->level_ptr, (int64_t)L + 1, w.sort.partial, st)) != JITDB_OK)
+    if ((rc = launch_exclusive_scan(bounds, S, bounds, S + 1, w.sort.partial, st)) != JITDB_OK)
         return rc;
+    if (slots) {
+        level_from_slots_kernel<<<(unsigned)ceil_div((int64_t)L + 1, kThreads), kThreads, 0, st>>>(
+            slots->slot_ptr, L, n_sig, s->level_ptr);
+        JITDB_LAUNCH_CHECK();
+    }
 
-    // 5. perm: node ids sorted by (height, id); inv_perm its inverse
-    if ((rc = radix_sort_ids(s->height, n, bits_needed(L - 1), -1, s->perm, w.sort, st)) != JITDB_OK) return rc;
+    // 5. perm: node ids sorted by (key, id); inv_perm its inverse
+    if ((rc = radix_sort_ids(key, n, bits_needed(S - 1), -1, s->perm, w.sort, st)) != JITDB_OK) return rc;
     invert_perm_kernel<<<grid, kThreads, 0, st>>>(s->perm, n, s->inv_perm);
     JITDB_LAUNCH_CHECK();
 
@@ -575,11 +644,37 @@ extern "C" int jitdb_schedule(const int32_t *parent, jitdb_schedule_t *s,
     //    outside the first E entries
     if ((rc = radix_sort_ids(parent, n, bits_needed(n64), n, s->child_idx, w.sort, st)) != JITDB_OK) return rc;
 
-    JITDB_HIP_CHECK(hipMemcpyAsync(s->host_level_ptr, s->level_ptr, sizeof(int32_t) * ((size_t)L + 1),
-                                   hipMemcpyDeviceToHost, st));
-    JITDB_HIP_CHECK(hipStreamSynchronize(st));
+    if (slots) {
+        JITDB_HIP_CHECK(hipMemcpyAsync(slots->host_slot_ptr, slots->slot_ptr, sizeof(int32_t) * ((size_t)S + 1),
+                                       hipMemcpyDeviceToHost, st));
+        JITDB_HIP_CHECK(hipStreamSynchronize(st));
+        for (int l = 0; l <= L; ++l) s->host_level_ptr[l] = slots->host_slot_ptr[(int64_t)l * n_sig];
+    } else {
+        JITDB_HIP_CHECK(hipMemcpyAsync(s->host_level_ptr, s->level_ptr, sizeof(int32_t) * ((size_t)L + 1),
+                                       hipMemcpyDeviceToHost, st));
+        JITDB_HIP_CHECK(hipStreamSynchronize(st));
+    }
     if (s->host_level_ptr[0] != 0 || s->host_level_ptr[L] != n) return JITDB_E_CYCLE;
     return JITDB_OK;
+}
+}  // namespace
+
+extern "C" int jitdb_schedule(const int32_t *parent, jitdb_schedule_t *s,
+                              void *workspace, size_t workspace_bytes, void *hip_stream) {
+    return schedule_impl(parent, nullptr, nullptr, s, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" size_t jitdb_schedule_typed_workspace_bytes(int64_t n_nodes, int32_t n_sig) {
+    if (n_nodes < 0 || n_nodes > JITDB_MAX_NODES || n_sig < 1 || n_sig > JITDB_MAX_SIGNATURES) return 0;
+    if (n_nodes * (int64_t)n_sig >= (int64_t(1) << 31)) return 0;
+    return carve_schedule_ws(n_nodes, nullptr, n_sig).bytes;
+}
+
+extern "C" int jitdb_schedule_typed(const int32_t *parent, const int32_t *sig, jitdb_schedule_t *s,
+                                    jitdb_slots_t *slots, void *workspace, size_t workspace_bytes,
+                                    void *hip_stream) {
+    if (!slots) return JITDB_E_NULL;
+    return schedule_impl(parent, sig, slots, s, workspace, workspace_bytes, hip_stream);
 }
 
 extern "C" size_t jitdb_schedule_append_workspace_bytes(int64_t n_base, int64_t n_new) {

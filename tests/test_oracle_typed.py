@@ -4,6 +4,7 @@ import pytest
 
 from oracle import schedule_oracle as S
 from oracle import treelstm_oracle as T
+from oracle import treelstm_typed_oracle as TT
 from workloads import (make_forest, make_values, make_values_typed, tree_signatures, mixed_forest, tree_ranges,
                        relabel, chain_forest)
 
@@ -75,11 +76,11 @@ def test_forward_typed_with_one_cell_is_forward():
     p = make_forest(1)
     x, W, U, b = make_values(1, p.shape[0], "random", D=12, H=7)
     h0, c0 = T.forward(p, x, W, U, b)
-    h1, c1 = T.forward_typed(p, np.zeros(p.shape[0], np.int32), x, W[None], U[None], b[None])
+    h1, c1 = TT.forward_typed(p, np.zeros(p.shape[0], np.int32), x, W[None], U[None], b[None])
     assert np.allclose(h0, h1, atol=1e-14) and np.allclose(c0, c1, atol=1e-14)
     # two signatures naming equal weights change nothing
     sig = tree_signatures(p, 2, 0)
-    h2, c2 = T.forward_typed(p, sig, x, np.stack([W, W]), np.stack([U, U]), np.stack([b, b]))
+    h2, c2 = TT.forward_typed(p, sig, x, np.stack([W, W]), np.stack([U, U]), np.stack([b, b]))
     assert np.allclose(h0, h2, atol=1e-14) and np.allclose(c0, c2, atol=1e-14)
 
 
@@ -87,13 +88,13 @@ def test_forward_typed_is_each_network_on_its_own_trees():
     p, sig = mixed_forest(1, 6, 5, 2, 9, 3)
     n = p.shape[0]
     x, W, U, b = make_values_typed(1, n, 2, D=10, H=6)
-    h, c = T.forward_typed(p, sig, x, W, U, b)
+    h, c = TT.forward_typed(p, sig, x, W, U, b)
     for t in range(2):
         sub, ids = _sub_forest(p, sig == t)
         ht, ct = T.forward(sub, x[ids], W[t], U[t], b[t])
         assert np.allclose(h[ids], ht, atol=1e-14) and np.allclose(c[ids], ct, atol=1e-14)
     # and the weights matter: swapping the two networks changes the states
-    h_sw, _ = T.forward_typed(p, 1 - sig, x, W, U, b)
+    h_sw, _ = TT.forward_typed(p, 1 - sig, x, W, U, b)
     assert np.abs(h_sw - h).max() > 1e-3
 
 
@@ -113,5 +114,5 @@ def test_forward_typed_parent_cell_owns_the_forget_gate():
     i = sg(z0[:H] + U[1][:H] @ h1); o = sg(z0[H:2 * H] + U[1][H:2 * H] @ h1)
     u = np.tanh(z0[2 * H:3 * H] + U[1][2 * H:3 * H] @ h1); f = sg(z0[3 * H:] + U[1][3 * H:] @ h1)
     c0 = i * u + f * c1; h0 = o * np.tanh(c0)
-    h, c = T.forward_typed(p, sig, x, W, U, b)
+    h, c = TT.forward_typed(p, sig, x, W, U, b)
     assert np.allclose(h, [h0, h1], atol=1e-13) and np.allclose(c, [c0, c1], atol=1e-13)
