@@ -977,7 +977,12 @@ gemm_kb_kernel(LevelArgs a, const KbEpiArgs e) {
         for (int g = 0; g < 4; ++g)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][g][v] = 0.0f;
+    // node ids of the tile's rows, fetched while the GEMM runs (the epilogue would otherwise
+    // wait for one dependent load per output row)
+    __shared__ int s_node[kDmaBM];
+    if (e.kind == KB_EPI_DX_DHS && t < kDmaBM) s_node[t] = tile_row0 + t < e.M ? e.node[tile_row0 + t] : 0;
     dma_gemm<T, MODE_GENERIC>(a, lds, nullptr, tile_row0, col_tile, acc, sink, []() {});
+    __syncthreads();
 
 #pragma unroll
     for (int i = 0; i < 2; ++i)
@@ -991,8 +996,9 @@ gemm_kb_kernel(LevelArgs a, const KbEpiArgs e) {
                 if (row >= e.M) continue;
                 const float val = acc[i][g][v];
                 if (e.kind == KB_EPI_DX_DHS) {
-                    if (col < e.D) e.out0[(int64_t)e.node[row] * e.D + col] = val;
-                    else e.out1[(int64_t)e.node[row] * e.H + (col - e.D)] = val;
+                    const int64_t nd = s_node[row - tile_row0];
+                    if (col < e.D) e.out0[nd * e.D + col] = val;
+                    else e.out1[nd * e.H + (col - e.D)] = val;
                 } else if (e.kind == KB_EPI_STORE) {
                     e.out0[(int64_t)row * e.ldc + col] = val;
                 } else {
