@@ -5,11 +5,11 @@
 // level, so when a level is reached every parent has already left its total dc and its dhs =
 // U_iou^T dz_iou (by node id); per level
 //
-//   bwd_receive_kernel   per node k with parent p: dz_f,k = dc_p c_k f_k (1 - f_k) (rows of G),
-//                        dh_k = gh_k + dhs_p, dc_k = gc_k + dc_p f_k
+//   bwd_receive_kernel   per node k with parent p: dz_f,k = dc_p c_k f_k (1 - f_k) (rows of G)
 //   ufg = G U_f                                      GEMM over the level's rows
 //   dU_f += G^T h                                    GEMM, reduction over the level's rows
-//   bwd_cell_kernel      dz_i, dz_o, dz_u, sum_k dz_f,k from dh_j + ufg_j, dc_j and the saved gates
+//   bwd_cell_kernel      dh_j = gh_j + dhs_p + ufg_j, dc_j = gc_j + dc_p f_j + ..., then dz_i, dz_o,
+//                        dz_u, sum_k dz_f,k from them and the saved gates
 //   [dx_j | dhs_j] = dZ_j [W | U]                    GEMM over the level's rows
 //   [dW | db | dU_iou] += dZ^T [x | 1 | hs]          GEMM, reduction over the level's rows
 //
@@ -119,17 +119,14 @@ __device__ __forceinline__ void store_transposed_tile(const T (*tile)[64 / sizeo
     }
 }
 
-// What a level's nodes receive from their parents.  The parent p of node k was processed in a
-// higher level and left its total dc in dc[p] and its dhs in dhs[p]:
-//     dz_f,k = dc_p c_k f_k (1 - f_k)  -> row r of G and column r of Gt (zero for a root)
-//     dh_k   = gh_k + dhs_p            (U_f^T dz_f,k comes from the GEMM that follows; the cell kernel adds it)
-//     dc_k   = gc_k + dc_p f_k
+// dz_f of a level's nodes.  The parent p of node k was processed in a higher level and left its
+// total dc in dc[p]:  dz_f,k = dc_p c_k f_k (1 - f_k)  -> row r of G and column r of Gt (zero for
+// a root).  It has to exist before the level's cell kernel, because U_f^T dz_f,k is part of dh_k.
 template <typename T>
 __global__ void __launch_bounds__(kT)
 bwd_receive_kernel(const int32_t *__restrict__ nodes, int n_rows, int H, int Hk,
                    const int32_t *__restrict__ parent_of, const float *__restrict__ c,
-                   const float *__restrict__ fgate, const float *__restrict__ gh, const float *__restrict__ gc,
-                   const float *__restrict__ dhs, float *__restrict__ dh, float *__restrict__ dc,
+                   const float *__restrict__ fgate, const float *__restrict__ dc,
                    T *__restrict__ G, int64_t g_rows_alloc, T *__restrict__ Gt, int64_t gt_rows_alloc) {
     constexpr int RT = 64 / (int)sizeof(T);
     __shared__ T tile[1][RT][64 + 2];
@@ -142,15 +139,10 @@ bwd_receive_kernel(const int32_t *__restrict__ nodes, int n_rows, int H, int Hk,
         if (r < n_rows && m < H) {
             const int64_t k = nodes[r];
             const int64_t p = parent_of[k];
-            float dhk = gh ? gh[k * H + m] : 0.0f, dck = gc ? gc[k * H + m] : 0.0f;
             if (p >= 0) {
-                const float dcp = dc[p * H + m], fk = fgate[k * H + m];
-                dzf = dcp * c[k * H + m] * fk * (1.0f - fk);
-                dhk += dhs[p * H + m];
-                dck += dcp * fk;
+                const float fk = fgate[k * H + m];
+                dzf = dc[p * H + m] * c[k * H + m] * fk * (1.0f - fk);
             }
-            dh[k * H + m] = dhk;
-            dc[k * H + m] = dck;
         }
         const T v = from_f32<T>(dzf);
         tile[0][rr][lane] = v;
@@ -161,8 +153,11 @@ bwd_receive_kernel(const int32_t *__restrict__ nodes, int n_rows, int H, int Hk,
     store_transposed_tile<T, 1>(tile, t, Hk, m0, Gt, gt_rows_alloc);
 }
 
-// The cell's elementwise derivative.  dh_j = dh[j] + ufg[r], where ufg (level order, may be
-// null) is the product U_f^T dz_f,j that the GEMM before this kernel left; dc_j is complete.
+// The cell's elementwise derivative.  What node j receives is fetched here, by node id, from
+// what its parent p left in a higher level (total dc_p, dhs_p = U_iou^T dz_iou,p):
+//     dh_j = gh_j + dhs_p + ufg_r      ufg (level order, may be null) = U_f^T dz_f,j, the product
+//                                      the GEMM before this kernel left
+//     dc_j = gc_j + dc_p f_j + dh_j o_j (1 - tanh^2 c_j)
 // Writes dZ row r = [dz_i | dz_o | dz_u | sum_k dz_f,k] (K-blocked, gate stride Hk), the same
 // transposed into dZt, and leaves the total dc_j in dc[j] for the children's level.  Only the
 // first n_gates blocks are written (3 at the leaf level, whose forget block is zero and unused).
@@ -170,8 +165,10 @@ template <typename T>
 __global__ void __launch_bounds__(kT)
 bwd_cell_kernel(const int32_t *__restrict__ nodes, int n_rows, int H, int Hk,
                 const int32_t *__restrict__ child_ptr, const int32_t *__restrict__ child_idx,
+                const int32_t *__restrict__ parent_of,
                 const float *__restrict__ c, const float *__restrict__ gates, const float *__restrict__ fgate,
-                const float *__restrict__ dh, const float *__restrict__ ufg, float *__restrict__ dc,
+                const float *__restrict__ gh, const float *__restrict__ gc, const float *__restrict__ dhs,
+                const float *__restrict__ ufg, float *__restrict__ dc,
                 T *__restrict__ dZ, int64_t dz_rows_alloc, T *__restrict__ dZt, int64_t zt_rows_alloc, int n_gates) {
     constexpr int RT = 64 / (int)sizeof(T);
     __shared__ T tile[4][RT][64 + 2];
@@ -186,8 +183,14 @@ bwd_cell_kernel(const int32_t *__restrict__ nodes, int n_rows, int H, int Hk,
             const int64_t j = nodes[r];
             const float gi = gates[j * 3 * H + m], go = gates[j * 3 * H + H + m], gu = gates[j * 3 * H + 2 * H + m];
             const float th = tanhf(c[j * H + m]);
-            const float dhj = dh[j * H + m] + (ufg ? ufg[(int64_t)r * H + m] : 0.0f);
-            const float dcj = dc[j * H + m] + dhj * go * (1.0f - th * th);
+            const int64_t p = parent_of[j];
+            float dhj = (gh ? gh[j * H + m] : 0.0f) + (ufg ? ufg[(int64_t)r * H + m] : 0.0f);
+            float dcj = gc ? gc[j * H + m] : 0.0f;
+            if (p >= 0) {
+                dhj += dhs[p * H + m];
+                dcj += dc[p * H + m] * fgate[j * H + m];
+            }
+            dcj += dhj * go * (1.0f - th * th);
             dc[j * H + m] = dcj;
             float dzf_sum = 0.0f;
             for (int e = child_ptr[j]; e < child_ptr[j + 1]; ++e) {
@@ -377,7 +380,7 @@ struct BwdDims {
     size_t esz;
 };
 struct BwdWs {
-    float *dh, *dc, *dhs, *ufg, *dMp, *dUfp;
+    float *dc, *dhs, *ufg, *dMp, *dUfp;
     int32_t *parent_of;
     void *Mt, *Uft, *dZ, *G, *dZt, *At, *Gt, *Hkt;
     size_t bytes;
@@ -386,7 +389,6 @@ struct BwdWs {
 BwdWs carve_bwd_ws(int64_t n, const BwdDims &d, void *base) {
     Carver c(base);
     BwdWs w;
-    w.dh = c.take<float>((size_t)n * d.H);
     w.dc = c.take<float>((size_t)n * d.H);
     w.dhs = c.take<float>((size_t)n * d.H);
     w.ufg = c.take<float>((size_t)d.n_max * d.H);
@@ -463,10 +465,10 @@ int run_backward(const T *x, const T *W, const T *U, const BwdDims &d, const jit
         // leaves have no children: their forget-gate block of dZ is zero and is left out of both GEMMs
         const int n_gates = l > 0 ? 4 : 3;
         // what the level receives from above
-        bwd_receive_kernel<T><<<tile_grid, kT, 0, st>>>(nodes, rows, H, Hk, w.parent_of, c, fgate, gh, gc, w.dhs,
-                                                        w.dh, w.dc, G, lvl_alloc, Gt, gt_alloc);
-        JITDB_LAUNCH_CHECK();
         if (l < L - 1) {
+            bwd_receive_kernel<T><<<tile_grid, kT, 0, st>>>(nodes, rows, H, Hk, w.parent_of, c, fgate, w.dc,
+                                                            G, lvl_alloc, Gt, gt_alloc);
+            JITDB_LAUNCH_CHECK();
             // ufg_r = U_f^T dz_f,k (level order), and dU_f += sum_k dz_f,k (x) h_k
             KbGemm g = {};
             g.A = G; g.a_rows_alloc = lvl_alloc; g.M = rows;
@@ -477,8 +479,9 @@ int run_backward(const T *x, const T *W, const T *U, const BwdDims &d, const jit
             if ((rc = launch_transpose<T>(h, nodes, H, 0, rows, H, kpad, Hkt, ht_alloc, st)) != JITDB_OK) return rc;
             if ((rc = weight_gemm(Gt, gt_alloc, Hk, Hkt, ht_alloc, H, w.dUfp, H)) != JITDB_OK) return rc;
         }
-        bwd_cell_kernel<T><<<tile_grid, kT, 0, st>>>(nodes, rows, H, Hk, s->child_ptr, s->child_idx, c, gates, fgate,
-                                                     w.dh, l < L - 1 ? w.ufg : nullptr, w.dc, dZ, lvl_alloc, dZt, zt_alloc, n_gates);
+        bwd_cell_kernel<T><<<tile_grid, kT, 0, st>>>(nodes, rows, H, Hk, s->child_ptr, s->child_idx, w.parent_of, c,
+                                                     gates, fgate, gh, gc, w.dhs, l < L - 1 ? w.ufg : nullptr, w.dc,
+                                                     dZ, lvl_alloc, dZt, zt_alloc, n_gates);
         JITDB_LAUNCH_CHECK();
         {   // [dx | dhs] = dZ [W | U]; leaves have nobody to pass dhs to
             KbGemm g = {};
