@@ -5,11 +5,11 @@
 // level, so when a level is reached every parent has already left its total dc and its dhs =
 // U_iou^T dz_iou (by node id); per level
 //
-//   bwd_receive_kernel   per node k with parent p: dz_f,k = dc_p c_k f_k (1 - f_k) (rows of G)
+//   (rows of G for this level: dz_f,k = dc_p c_k f_k (1 - f_k), written by the parents' cell kernels)
 //   ufg = G U_f                                      GEMM over the level's rows
 //   dU_f += G^T h                                    GEMM, reduction over the level's rows
 //   bwd_cell_kernel      dh_j = gh_j + dhs_p + ufg_j, dc_j = gc_j + dc_p f_j + ..., then dz_i, dz_o,
-//                        dz_u, sum_k dz_f,k from them and the saved gates
+//                        dz_u, sum_k dz_f,k from them and the saved gates; each child's dz_f,k -> G
 //   [dx_j | dhs_j] = dZ_j [W | U]                    GEMM over the level's rows
 //   [dW | db | dU_iou] += dZ^T [x | 1 | hs]          GEMM, reduction over the level's rows
 //
@@ -119,38 +119,22 @@ __device__ __forceinline__ void store_transposed_tile(const T (*tile)[64 / sizeo
     }
 }
 
-// dz_f of a level's nodes.  The parent p of node k was processed in a higher level and left its
-// total dc in dc[p]:  dz_f,k = dc_p c_k f_k (1 - f_k)  -> row r of G and column r of Gt (zero for
-// a root).  It has to exist before the level's cell kernel, because U_f^T dz_f,k is part of dh_k.
+// G holds dz_f,k = dc_p c_k f_k (1 - f_k) for every node k, K-blocked, rows in the order of the
+// schedule's positions (all levels in one operand: a level is a range of rows).  The rows of
+// nodes with a parent are written by the parent's cell kernel; this kernel zeroes the rows of
+// the level's roots.  One thread per (level row, 16 bytes of the row).
 template <typename T>
 __global__ void __launch_bounds__(kT)
-bwd_receive_kernel(const int32_t *__restrict__ nodes, int n_rows, int H, int Hk,
-                   const int32_t *__restrict__ parent_of, const float *__restrict__ c,
-                   const float *__restrict__ fgate, const float *__restrict__ dc,
-                   T *__restrict__ G, int64_t g_rows_alloc, T *__restrict__ Gt, int64_t gt_rows_alloc) {
-    constexpr int RT = 64 / (int)sizeof(T);
-    __shared__ T tile[1][RT][64 + 2];
-    const int t = threadIdx.x, lane = t & 63, w = t >> 6;
-    const int r0 = blockIdx.x * RT, m0 = blockIdx.y * 64, m = m0 + lane;
-#pragma unroll
-    for (int i = 0; i < RT / 4; ++i) {
-        const int rr = w + 4 * i, r = r0 + rr;
-        float dzf = 0.0f;
-        if (r < n_rows && m < H) {
-            const int64_t k = nodes[r];
-            const int64_t p = parent_of[k];
-            if (p >= 0) {
-                const float fk = fgate[k * H + m];
-                dzf = dc[p * H + m] * c[k * H + m] * fk * (1.0f - fk);
-            }
-        }
-        const T v = from_f32<T>(dzf);
-        tile[0][rr][lane] = v;
-        if (r < n_rows)
-            *reinterpret_cast<T *>(reinterpret_cast<char *>(G) + operand_offset(r, (int64_t)m * sizeof(T), g_rows_alloc)) = v;
-    }
-    __syncthreads();
-    store_transposed_tile<T, 1>(tile, t, Hk, m0, Gt, gt_rows_alloc);
+zero_root_rows_kernel(const int32_t *__restrict__ nodes, int n_rows, int Hk, const int32_t *__restrict__ parent_of,
+                      T *__restrict__ G, int64_t g_rows_alloc) {
+    constexpr int PER = 16 / (int)sizeof(T);
+    const int pieces = Hk / PER;
+    const int64_t id = (int64_t)blockIdx.x * kT + threadIdx.x;
+    if (id >= (int64_t)n_rows * pieces) return;
+    const int r = (int)(id / pieces), q = (int)(id % pieces);
+    if (parent_of[nodes[r]] >= 0) return;
+    const u32x4 z = {0, 0, 0, 0};
+    *reinterpret_cast<u32x4 *>(reinterpret_cast<char *>(G) + operand_offset(r, (int64_t)q * 16, g_rows_alloc)) = z;
 }
 
 // The cell's elementwise derivative.  What node j receives is fetched here, by node id, from
@@ -158,6 +142,8 @@ bwd_receive_kernel(const int32_t *__restrict__ nodes, int n_rows, int H, int Hk,
 //     dh_j = gh_j + dhs_p + ufg_r      ufg (level order, may be null) = U_f^T dz_f,j, the product
 //                                      the GEMM before this kernel left
 //     dc_j = gc_j + dc_p f_j + dh_j o_j (1 - tanh^2 c_j)
+// Every child k of j gets its dz_f,k = dc_j c_k f_k (1 - f_k) written to row inv_perm[k] of G (the
+// operand of the child level's GEMMs; pad units as zeros).
 // Writes dZ row r = [dz_i | dz_o | dz_u | sum_k dz_f,k] (K-blocked, gate stride Hk), the same
 // transposed into dZt, and leaves the total dc_j in dc[j] for the children's level.  Only the
 // first n_gates blocks are written (3 at the leaf level, whose forget block is zero and unused).
@@ -169,6 +155,7 @@ bwd_cell_kernel(const int32_t *__restrict__ nodes, int n_rows, int H, int Hk,
                 const float *__restrict__ c, const float *__restrict__ gates, const float *__restrict__ fgate,
                 const float *__restrict__ gh, const float *__restrict__ gc, const float *__restrict__ dhs,
                 const float *__restrict__ ufg, float *__restrict__ dc,
+                const int32_t *__restrict__ inv_perm, T *__restrict__ G, int64_t g_rows_alloc,
                 T *__restrict__ dZ, int64_t dz_rows_alloc, T *__restrict__ dZt, int64_t zt_rows_alloc, int n_gates) {
     constexpr int RT = 64 / (int)sizeof(T);
     __shared__ T tile[4][RT][64 + 2];
@@ -196,12 +183,20 @@ bwd_cell_kernel(const int32_t *__restrict__ nodes, int n_rows, int H, int Hk,
             for (int e = child_ptr[j]; e < child_ptr[j + 1]; ++e) {
                 const int64_t k = child_idx[e];
                 const float fk = fgate[k * H + m];
-                dzf_sum += dcj * c[k * H + m] * fk * (1.0f - fk);
+                const float dzf = dcj * c[k * H + m] * fk * (1.0f - fk);
+                dzf_sum += dzf;
+                *reinterpret_cast<T *>(reinterpret_cast<char *>(G) +
+                                       operand_offset(inv_perm[k], (int64_t)m * sizeof(T), g_rows_alloc)) = from_f32<T>(dzf);
             }
             dz[0] = dcj * gu * gi * (1.0f - gi);
             dz[1] = dhj * th * go * (1.0f - go);
             dz[2] = dcj * gi * (1.0f - gu * gu);
             dz[3] = dzf_sum;
+        } else if (r < n_rows) {    // pad units of the children's rows
+            const int64_t j = nodes[r];
+            for (int e = child_ptr[j]; e < child_ptr[j + 1]; ++e)
+                *reinterpret_cast<T *>(reinterpret_cast<char *>(G) +
+                                       operand_offset(inv_perm[child_idx[e]], (int64_t)m * sizeof(T), g_rows_alloc)) = T(0);
         }
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
@@ -398,7 +393,7 @@ BwdWs carve_bwd_ws(int64_t n, const BwdDims &d, void *base) {
     w.Mt = c.take<char>((size_t)round_up(d.D + d.H, 256) * 4 * d.Hk * d.esz);
     w.Uft = c.take<char>((size_t)round_up(d.H, 256) * d.Hk * d.esz);
     w.dZ = c.take<char>((size_t)round_up(d.n_max, 128) * 4 * d.Hk * d.esz);
-    w.G = c.take<char>((size_t)round_up(d.n_max, 128) * d.Hk * d.esz);
+    w.G = c.take<char>((size_t)(round_up(n, 128) + 128) * d.Hk * d.esz);   // all levels; whole row tiles are read
     w.dZt = c.take<char>((size_t)round_up(4 * d.Hk, 128) * d.n_pad * d.esz);
     w.At = c.take<char>((size_t)round_up(d.D + 1 + d.H, 256) * d.n_pad * d.esz);
     w.Gt = c.take<char>((size_t)round_up(d.Hk, 128) * d.n_pad * d.esz);
@@ -442,7 +437,8 @@ int run_backward(const T *x, const T *W, const T *U, const BwdDims &d, const jit
         JITDB_LAUNCH_CHECK();
     }
 
-    T *dZ = static_cast<T *>(w.dZ), *G = static_cast<T *>(w.G);
+    T *dZ = static_cast<T *>(w.dZ), *G_all = static_cast<T *>(w.G);
+    const int64_t g_alloc = round_up(n, 128) + 128;
     T *dZt = static_cast<T *>(w.dZt), *At = static_cast<T *>(w.At), *Gt = static_cast<T *>(w.Gt), *Hkt = static_cast<T *>(w.Hkt);
     for (int l = L - 1; l >= 0; --l) {
         const int rows = lp[l + 1] - lp[l];
@@ -466,12 +462,16 @@ int run_backward(const T *x, const T *W, const T *U, const BwdDims &d, const jit
         const int n_gates = l > 0 ? 4 : 3;
         // what the level receives from above
         if (l < L - 1) {
-            bwd_receive_kernel<T><<<tile_grid, kT, 0, st>>>(nodes, rows, H, Hk, w.parent_of, c, fgate, w.dc,
-                                                            G, lvl_alloc, Gt, gt_alloc);
+            // the level's rows of G: written by the parents' cell kernels, zero for roots
+            T *G = reinterpret_cast<T *>(reinterpret_cast<char *>(G_all) + (int64_t)lp[l] * 64);
+            const int pieces = Hk / (16 / (int)sizeof(T));
+            zero_root_rows_kernel<T><<<(unsigned)ceil_div((int64_t)rows * pieces, kT), kT, 0, st>>>(
+                nodes, rows, Hk, w.parent_of, G, g_alloc);
             JITDB_LAUNCH_CHECK();
+            if ((rc = launch_transpose<T>(G, nullptr, 0, g_alloc, rows, Hk, kpad, Gt, gt_alloc, st)) != JITDB_OK) return rc;
             // ufg_r = U_f^T dz_f,k (level order), and dU_f += sum_k dz_f,k (x) h_k
             KbGemm g = {};
-            g.A = G; g.a_rows_alloc = lvl_alloc; g.M = rows;
+            g.A = G; g.a_rows_alloc = g_alloc; g.M = rows;
             g.B = w.Uft; g.b_rows_alloc = uft_alloc; g.N = H;
             g.k_bytes = (int64_t)Hk * sizeof(T); g.k_splits = 1;
             g.epilogue = KB_EPI_STORE; g.out0 = w.ufg; g.ldc = H;
@@ -481,7 +481,7 @@ int run_backward(const T *x, const T *W, const T *U, const BwdDims &d, const jit
         }
         bwd_cell_kernel<T><<<tile_grid, kT, 0, st>>>(nodes, rows, H, Hk, s->child_ptr, s->child_idx, w.parent_of, c,
                                                      gates, fgate, gh, gc, w.dhs, l < L - 1 ? w.ufg : nullptr, w.dc,
-                                                     dZ, lvl_alloc, dZt, zt_alloc, n_gates);
+                                                     s->inv_perm, G_all, g_alloc, dZ, lvl_alloc, dZt, zt_alloc, n_gates);
         JITDB_LAUNCH_CHECK();
         {   // [dx | dhs] = dZ [W | U]; leaves have nobody to pass dhs to
             KbGemm g = {};
@@ -565,7 +565,7 @@ extern "C" int jitdb_treelstm_backward(const void *x, const void *W, const void 
         return JITDB_OK;
     }
     if (!x || !h || !c || !gates || !fgate || !dx || !workspace) return JITDB_E_NULL;
-    if (!s->perm || !s->child_ptr || !s->child_idx || !s->host_level_ptr) return JITDB_E_NULL;
+    if (!s->perm || !s->inv_perm || !s->child_ptr || !s->child_idx || !s->host_level_ptr) return JITDB_E_NULL;
     if ((reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return JITDB_E_BADARG;
     // operand rows are read in 16-byte pieces
     if ((reinterpret_cast<uintptr_t>(x) & 15) || (reinterpret_cast<uintptr_t>(h) & 15)) return JITDB_E_BADARG;
