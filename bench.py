@@ -53,8 +53,8 @@ def train_bench(args, J, torch, cfg, dev, N, D, H, esz, peak_tflops, xt, Wt, Ut,
     ws_b = torch.empty(J.jitdb_treelstm_backward_workspace_bytes(sched, D, H, dt), dtype=torch.uint8, device=dev)
     h = torch.empty((N, H), dtype=xt.dtype, device=dev)
     c = torch.empty((N, H), **f32)
-    gates = torch.empty((N, 3 * H), **f32)
-    fgate = torch.zeros((N, H), **f32)
+    gates = torch.empty((N, 3 * H), dtype=xt.dtype, device=dev)
+    fgate = torch.zeros((N, H), dtype=xt.dtype, device=dev)
     gh = torch.randn((N, H), **f32)
     gc = torch.randn((N, H), **f32)
     grads = (torch.empty((N, D), **f32), torch.empty((4 * H, D), **f32), torch.empty((4 * H, H), **f32),

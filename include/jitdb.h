@@ -268,15 +268,18 @@ int jitdb_treelstm_forward(const void *x, const void *W, const void *U, const fl
  * Execution step for training (the paper runs its backward pass through the same batched
  * graph, section 5): jitdb_treelstm_forward plus the activations a backward pass needs.
  *
- *   gates_out  dev [N, 3H] fp32, rows by node id: i | o | u after their non-linearities.
- *   fgate_out  dev [N, H] fp32: row k = the forget gate f_k the parent of node k applied to
- *              it; rows of roots are not written.
+ *   gates_out  dev [N, 3H] in dtype elements (like h), rows by node id: i | o | u after their
+ *              non-linearities.
+ *   fgate_out  dev [N, H] in dtype elements: row k = the forget gate f_k the parent of node k
+ *              applied to it; rows of roots are not written.
+ * With JITDB_BF16 the kept activations are bfloat16 (the usual mixed-precision choice: they are
+ * values in [-1, 1], the cell state c stays fp32); this halves what the training step moves for them.
  * Everything else as in jitdb_treelstm_forward (same workspace size, same results).
  */
 int jitdb_treelstm_forward_train(const void *x, const void *W, const void *U, const float *b,
                                  int32_t D, int32_t H, jitdb_dtype dtype,
                                  const jitdb_schedule_t *s,
-                                 void *h_out, float *c_out, float *gates_out, float *fgate_out,
+                                 void *h_out, float *c_out, void *gates_out, void *fgate_out,
                                  void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Bytes of device workspace jitdb_treelstm_backward needs for this schedule (0 if an argument is invalid). */
@@ -290,7 +293,7 @@ size_t jitdb_treelstm_backward_workspace_bytes(const jitdb_schedule_t *s, int32_
  * it returns dL/dx, dL/dW, dL/dU, dL/db of the forward defined at jitdb_treelstm_forward.
  *
  *   x, W, U, s, dtype   as handed to jitdb_treelstm_forward_train.
- *   h, c, gates, fgate  what that call returned (dev; h in dtype elements, the rest fp32).
+ *   h, c, gates, fgate  what that call returned (dev; c fp32, the others in dtype elements).
  *   gh, gc              dev [N, H] fp32 cotangents of h and c for every node; either may be NULL (= zeros).
  *   dx [N, D], dW [4H, D], dU [4H, H], db [4H]   dev, fp32, overwritten.
  *
@@ -299,7 +302,7 @@ size_t jitdb_treelstm_backward_workspace_bytes(const jitdb_schedule_t *s, int32_
  */
 int jitdb_treelstm_backward(const void *x, const void *W, const void *U,
                             int32_t D, int32_t H, jitdb_dtype dtype, const jitdb_schedule_t *s,
-                            const void *h, const float *c, const float *gates, const float *fgate,
+                            const void *h, const float *c, const void *gates, const void *fgate,
                             const float *gh, const float *gc,
                             float *dx, float *dW, float *dU, float *db,
                             void *workspace, size_t workspace_bytes, void *hip_stream);

@@ -324,7 +324,7 @@ def jitdb_treelstm_forward(x, W, U, b, schedule: Schedule, stream=None, workspac
 
 def jitdb_treelstm_forward_train(x, W, U, b, schedule: Schedule, stream=None, workspace=None,
                                  out: Optional[Tuple] = None):
-    """As jitdb_treelstm_forward; returns (h, c, gates [N, 3H] fp32, fgate [N, H] fp32).
+    """As jitdb_treelstm_forward; returns (h, c, gates [N, 3H], fgate [N, H]), the last two in x's dtype.
     `out` = (h, c, gates, fgate) reuses buffers.  fgate rows of roots are left as they are."""
     return _forward(x, W, U, b, schedule, stream, workspace, out, train=True)
 
@@ -352,9 +352,9 @@ def jitdb_treelstm_backward(x, W, U, schedule: Schedule, h, c, gates, fgate, gh=
     for t, name in ((x, "x"), (W, "W"), (U, "U"), (h, "h"), (c, "c"), (gates, "gates"), (fgate, "fgate")):
         if not t.is_cuda or not t.is_contiguous():
             raise TypeError(f"{name} must be a contiguous CUDA tensor")
-    if W.dtype != x.dtype or U.dtype != x.dtype or h.dtype != x.dtype:
-        raise TypeError("W, U, h must have x's dtype")
-    for t, name in ((c, "c"), (gates, "gates"), (fgate, "fgate"), (gh, "gh"), (gc, "gc")):
+    if any(t.dtype != x.dtype for t in (W, U, h, gates, fgate)):
+        raise TypeError("W, U, h, gates, fgate must have x's dtype")
+    for t, name in ((c, "c"), (gh, "gh"), (gc, "gc")):
         if t is not None and (t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous()):
             raise TypeError(f"{name} must be a contiguous float32 CUDA tensor")
     if (x.shape != (n, D) or h.shape != (n, H) or c.shape != (n, H) or gates.shape != (n, 3 * H)
@@ -407,8 +407,8 @@ def _forward(x, W, U, b, schedule, stream, workspace, out, train):
         h = torch.empty((n, H), dtype=x.dtype, device=x.device)
         c = torch.empty((n, H), dtype=torch.float32, device=x.device)
         if train:
-            gates = torch.empty((n, 3 * H), dtype=torch.float32, device=x.device)
-            fgate = torch.zeros((n, H), dtype=torch.float32, device=x.device)
+            gates = torch.empty((n, 3 * H), dtype=x.dtype, device=x.device)
+            fgate = torch.zeros((n, H), dtype=x.dtype, device=x.device)
     elif train:
         h, c, gates, fgate = out
     else:

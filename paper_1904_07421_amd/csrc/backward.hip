@@ -152,7 +152,7 @@ __global__ void __launch_bounds__(kT)
 bwd_cell_kernel(const int32_t *__restrict__ nodes, int n_rows, int H, int Hk,
                 const int32_t *__restrict__ child_ptr, const int32_t *__restrict__ child_idx,
                 const int32_t *__restrict__ parent_of,
-                const float *__restrict__ c, const float *__restrict__ gates, const float *__restrict__ fgate,
+                const float *__restrict__ c, const T *__restrict__ gates, const T *__restrict__ fgate,
                 const float *__restrict__ gh, const float *__restrict__ gc, const float *__restrict__ dhs,
                 const float *__restrict__ ufg, float *__restrict__ dc,
                 const int32_t *__restrict__ inv_perm, T *__restrict__ G, int64_t g_rows_alloc,
@@ -168,21 +168,22 @@ bwd_cell_kernel(const int32_t *__restrict__ nodes, int n_rows, int H, int Hk,
         float dz[4] = {0.0f, 0.0f, 0.0f, 0.0f};
         if (r < n_rows && m < H) {
             const int64_t j = nodes[r];
-            const float gi = gates[j * 3 * H + m], go = gates[j * 3 * H + H + m], gu = gates[j * 3 * H + 2 * H + m];
+            const float gi = to_f32<T>(gates[j * 3 * H + m]), go = to_f32<T>(gates[j * 3 * H + H + m]),
+                        gu = to_f32<T>(gates[j * 3 * H + 2 * H + m]);
             const float th = tanhf(c[j * H + m]);
             const int64_t p = parent_of[j];
             float dhj = (gh ? gh[j * H + m] : 0.0f) + (ufg ? ufg[(int64_t)r * H + m] : 0.0f);
             float dcj = gc ? gc[j * H + m] : 0.0f;
             if (p >= 0) {
                 dhj += dhs[p * H + m];
-                dcj += dc[p * H + m] * fgate[j * H + m];
+                dcj += dc[p * H + m] * to_f32<T>(fgate[j * H + m]);
             }
             dcj += dhj * go * (1.0f - th * th);
             dc[j * H + m] = dcj;
             float dzf_sum = 0.0f;
             for (int e = child_ptr[j]; e < child_ptr[j + 1]; ++e) {
                 const int64_t k = child_idx[e];
-                const float fk = fgate[k * H + m];
+                const float fk = to_f32<T>(fgate[k * H + m]);
                 const float dzf = dcj * c[k * H + m] * fk * (1.0f - fk);
                 dzf_sum += dzf;
                 *reinterpret_cast<T *>(reinterpret_cast<char *>(G) +
@@ -412,7 +413,7 @@ int zero_bytes(void *p, size_t bytes, hipStream_t st) {    // bytes is a multipl
 
 template <typename T>
 int run_backward(const T *x, const T *W, const T *U, const BwdDims &d, const jitdb_schedule_t *s,
-                 const T *h, const float *c, const float *gates, const float *fgate,
+                 const T *h, const float *c, const T *gates, const T *fgate,
                  const float *gh, const float *gc, float *dx, float *dW, float *dU, float *db,
                  const BwdWs &w, hipStream_t st) {
     const int64_t n = s->n_nodes;
@@ -544,7 +545,7 @@ extern "C" size_t jitdb_treelstm_backward_workspace_bytes(const jitdb_schedule_t
 
 extern "C" int jitdb_treelstm_backward(const void *x, const void *W, const void *U,
                                        int32_t D, int32_t H, jitdb_dtype dtype, const jitdb_schedule_t *s,
-                                       const void *h, const float *c, const float *gates, const float *fgate,
+                                       const void *h, const float *c, const void *gates, const void *fgate,
                                        const float *gh, const float *gc,
                                        float *dx, float *dW, float *dU, float *db,
                                        void *workspace, size_t workspace_bytes, void *hip_stream) {
@@ -575,9 +576,9 @@ extern "C" int jitdb_treelstm_backward(const void *x, const void *W, const void 
     if (workspace_bytes < w.bytes) return JITDB_E_WORKSPACE;
     if (dtype == JITDB_F32)
         return run_backward<float>(static_cast<const float *>(x), static_cast<const float *>(W),
-                                   static_cast<const float *>(U), d, s, static_cast<const float *>(h), c, gates,
-                                   fgate, gh, gc, dx, dW, dU, db, w, st);
+                                   static_cast<const float *>(U), d, s, static_cast<const float *>(h), c,
+                                   static_cast<const float *>(gates), static_cast<const float *>(fgate), gh, gc, dx, dW, dU, db, w, st);
     return run_backward<bf16_t>(static_cast<const bf16_t *>(x), static_cast<const bf16_t *>(W),
-                                static_cast<const bf16_t *>(U), d, s, static_cast<const bf16_t *>(h), c, gates,
-                                fgate, gh, gc, dx, dW, dU, db, w, st);
+                                static_cast<const bf16_t *>(U), d, s, static_cast<const bf16_t *>(h), c,
+                                static_cast<const bf16_t *>(gates), static_cast<const bf16_t *>(fgate), gh, gc, dx, dW, dU, db, w, st);
 }

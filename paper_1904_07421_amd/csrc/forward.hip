@@ -310,8 +310,8 @@ struct LevelArgs {
     void *h_out;          // [N, H]
     void *hs_out;         // [N, Hp] or == h_out when H == Hp
     // training only: activations the backward pass needs
-    float *gates;         // [N, 3H] i | o | u after their non-linearities, rows by node id
-    float *fgate;         // [N, H] row k = forget gate the parent of k applied to k
+    void *gates;          // [N, 3H] of T: i | o | u after their non-linearities, rows by node id
+    void *fgate;          // [N, H] of T: row k = forget gate the parent of k applied to k
     int D, Dp, H, Hp, Hu, Hq;
     int n_rows;
     int n_rows_alloc;     // rows per slab of the stacked input (n_rows rounded up to whole tiles)
@@ -398,10 +398,10 @@ __device__ __forceinline__ void cell_pass(const LevelArgs &a, const floatx16 (&a
             const int nd = rn[rl];
             const int unit = unit_tile * kUnit + l32;
             if (nd >= 0 && unit < a.H) {
-                float *g = a.gates + (int64_t)nd * 3 * a.H + unit;
-                g[0] = gi;
-                g[a.H] = go;
-                g[2 * a.H] = gu;
+                T *g = static_cast<T *>(a.gates) + (int64_t)nd * 3 * a.H + unit;
+                g[0] = from_f32<T>(gi);
+                g[a.H] = from_f32<T>(go);
+                g[2 * a.H] = from_f32<T>(gu);
             }
         }
     }
@@ -485,10 +485,10 @@ __device__ __forceinline__ void cell_pass(const LevelArgs &a, const floatx16 (&a
                     if constexpr (SAVE) {
                         if (kidv[q][j] >= 0) {
                             const float fv[4] = {f0, f1, f2, f3};
-                            float *dst = a.fgate + (int64_t)kidv[q][j] * a.H + unit0;
+                            T *dst = static_cast<T *>(a.fgate) + (int64_t)kidv[q][j] * a.H + unit0;
 #pragma unroll
                             for (int e = 0; e < 4; ++e)
-                                if (unit0 + e < a.H) dst[e] = fv[e];
+                                if (unit0 + e < a.H) dst[e] = from_f32<T>(fv[e]);
                         }
                     }
                 }
@@ -1235,7 +1235,7 @@ bool dims_ok(int64_t n, int64_t e, int32_t D, int32_t H, int dtype) {
 template <typename T, bool SAVE>
 int run_forward(const void *x, const void *W, const void *U, const float *b, const Dims &d,
                 const jitdb_schedule_t *s, const jitdb_slots_t *slots,
-                void *h_out, float *c_out, float *gates, float *fgate,
+                void *h_out, float *c_out, void *gates, void *fgate,
                 const ForwardWs &w, hipStream_t st) {
     const int L = s->n_levels;
     const int n_sig = slots ? slots->n_sig : 1;
@@ -1441,7 +1441,7 @@ extern "C" size_t jitdb_treelstm_workspace_bytes(int64_t n_nodes, int64_t n_edge
 namespace {
 int forward_entry(const void *x, const void *W, const void *U, const float *b, int32_t D, int32_t H,
                   jitdb_dtype dtype, const jitdb_schedule_t *s, const jitdb_slots_t *slots,
-                  void *h_out, float *c_out, float *gates, float *fgate, bool save,
+                  void *h_out, float *c_out, void *gates, void *fgate, bool save,
                   void *workspace, size_t workspace_bytes, void *hip_stream) {
     if (!s) return JITDB_E_NULL;
     const int n_sig = slots ? slots->n_sig : 1;
@@ -1513,7 +1513,7 @@ extern "C" int jitdb_treelstm_forward_typed(const void *x, const void *W, const 
 extern "C" int jitdb_treelstm_forward_train(const void *x, const void *W, const void *U, const float *b,
                                             int32_t D, int32_t H, jitdb_dtype dtype,
                                             const jitdb_schedule_t *s, void *h_out, float *c_out,
-                                            float *gates_out, float *fgate_out,
+                                            void *gates_out, void *fgate_out,
                                             void *workspace, size_t workspace_bytes, void *hip_stream) {
     return forward_entry(x, W, U, b, D, H, dtype, s, nullptr, h_out, c_out, gates_out, fgate_out, true,
                          workspace, workspace_bytes, hip_stream);

@@ -51,10 +51,10 @@ def test_training_forward_keeps_the_gate_activations(kind, D, H, dtype):
     ho, co, go, fo = B.forward_saved(parent, *seen)
     tol = TOL[dtype]
     assert np.abs(h.float().cpu().numpy() - ho).max() <= tol
-    assert np.abs(gates.cpu().numpy() - go).max() <= tol
+    assert np.abs(gates.float().cpu().numpy() - go).max() <= tol
     has_parent = parent >= 0
-    assert np.abs(fgate.cpu().numpy()[has_parent] - fo[has_parent]).max() <= tol
-    assert not fgate.cpu().numpy()[~has_parent].any()          # rows of roots stay as handed in (zeros)
+    assert np.abs(fgate.float().cpu().numpy()[has_parent] - fo[has_parent]).max() <= tol
+    assert not fgate.float().cpu().numpy()[~has_parent].any()          # rows of roots stay as handed in (zeros)
 
 
 def _rel(got, want):
@@ -125,9 +125,9 @@ def _sampled_backward_check(cfg, n_sample, dtype, D=None, H=None):
     tol = TOL[dtype]
     dxn = dx.cpu().numpy()
     errs = {"dx": _rel(dxn[rows], rx), "dW": _rel(dW.cpu().numpy(), rW), "dU": _rel(dU.cpu().numpy(), rU),
-            "db": _rel(db.cpu().numpy(), rb), "gates": float(np.abs(gates.cpu().numpy()[rows] - go).max())}
+            "db": _rel(db.cpu().numpy(), rb), "gates": float(np.abs(gates.float().cpu().numpy()[rows] - go).max())}
     hp = sub >= 0
-    errs["fgate"] = float(np.abs(fgate.cpu().numpy()[rows][hp] - fo[hp]).max())
+    errs["fgate"] = float(np.abs(fgate.float().cpu().numpy()[rows][hp] - fo[hp]).max())
     print("   errors:", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
     mask = np.ones(n, dtype=bool); mask[rows] = False
     assert not dxn[mask].any()                      # no cotangent reaches the other trees
