@@ -220,10 +220,11 @@ bwd_cell_kernel(const int32_t *__restrict__ nodes, int n_rows, int H, int Hk,
 // times 64 columns; a thread stores 16 bytes, and since consecutive destination rows are
 // consecutive inside a slab a wave stores 1 KB of consecutive memory.
 // SRC selects how the tile is read: SRC_SCALAR one element per thread and step (any row
-// stride), SRC_VEC 16 bytes per thread (row-major rows that start on 16-byte boundaries),
-// SRC_KB 16 bytes per thread from a K-blocked source whose width is a multiple of 64.
+// stride), SRC_VEC LW bytes per thread and step (row-major rows that start on LW-byte
+// boundaries; LW = 16 or 8), SRC_KB 16 bytes per thread from a K-blocked source whose width is
+// a multiple of 64.
 enum { SRC_SCALAR = 0, SRC_VEC = 1, SRC_KB = 2 };
-template <typename T, int SRC>
+template <typename T, int SRC, int LW = 16>
 __global__ void __launch_bounds__(kT)
 transpose_kb_kernel(const T *__restrict__ src, const int32_t *__restrict__ index, int64_t ld_src,
                     int64_t src_rows_alloc, int n_rows, int n_cols, T *__restrict__ dst, int64_t dst_rows_alloc) {
@@ -241,30 +242,41 @@ transpose_kb_kernel(const T *__restrict__ src, const int32_t *__restrict__ index
             if (r < n_rows && cc < n_cols) v = src[(int64_t)(index ? index[r] : r) * ld_src + cc];
             tile[ty + 4 * i][tx] = v;
         }
-    } else {
-        // 256 threads x 16 bytes = the whole tile.  Row-major: a row's 64 columns are 64 / PER
-        // pieces.  K-blocked: the tile is 64 / RT slabs of RT rows x 64 bytes.
-        int row, col;
-        const char *a = nullptr;
-        if (SRC == SRC_VEC) {
-            row = t / (64 / PER); col = (t % (64 / PER)) * PER;
-            if (r0 + row < n_rows && c0 + col < n_cols)
-                a = reinterpret_cast<const char *>(src + (int64_t)(index ? index[r0 + row] : r0 + row) * ld_src + c0 + col);
-        } else {
-            const int piece = t & 3, sl = (t >> 2) / RT;
-            row = (t >> 2) % RT; col = sl * RT + piece * PER;
-            if (r0 + row < n_rows)
-                a = reinterpret_cast<const char *>(src) +
-                    ((int64_t)((c0 + col) / RT) * src_rows_alloc + r0 + row) * 64 + piece * 16;
-        }
-        T v[PER];
-        if (a != nullptr && (SRC == SRC_KB || c0 + col + PER <= n_cols)) {
-            *reinterpret_cast<u32x4 *>(v) = *reinterpret_cast<const u32x4 *>(a);
-        } else {
+    } else if (SRC == SRC_VEC) {
+        // a row's 64 columns are 64 / PL pieces of LW bytes; 256 threads sweep the tile
+        constexpr int PL = LW / (int)sizeof(T);
+        constexpr int PPR = 64 / PL;
 #pragma unroll
-            for (int e = 0; e < PER; ++e)
-                v[e] = (a != nullptr && c0 + col + e < n_cols) ? reinterpret_cast<const T *>(a)[e] : T(0);
+        for (int it = 0; it < RT * PPR / kT; ++it) {
+            const int idx = t + kT * it;
+            const int row = idx / PPR, col = (idx % PPR) * PL;
+            T v[PL];
+#pragma unroll
+            for (int e = 0; e < PL; ++e) v[e] = T(0);
+            if (r0 + row < n_rows && c0 + col < n_cols) {
+                const T *a = src + (int64_t)(index ? index[r0 + row] : r0 + row) * ld_src + c0 + col;
+                if (c0 + col + PL <= n_cols) {
+                    if constexpr (LW == 16) *reinterpret_cast<u32x4 *>(v) = *reinterpret_cast<const u32x4 *>(a);
+                    else *reinterpret_cast<uint2 *>(v) = *reinterpret_cast<const uint2 *>(a);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < PL; ++e)
+                        if (c0 + col + e < n_cols) v[e] = a[e];
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < PL; ++e) tile[row][col + e] = v[e];
         }
+    } else {
+        // the tile is 64 / RT slabs of RT rows x 64 bytes: 256 threads x 16 bytes
+        const int piece = t & 3, sl = (t >> 2) / RT;
+        const int row = (t >> 2) % RT, col = sl * RT + piece * PER;
+        T v[PER];
+#pragma unroll
+        for (int e = 0; e < PER; ++e) v[e] = T(0);
+        if (r0 + row < n_rows)
+            *reinterpret_cast<u32x4 *>(v) = *reinterpret_cast<const u32x4 *>(
+                reinterpret_cast<const char *>(src) + ((int64_t)((c0 + col) / RT) * src_rows_alloc + r0 + row) * 64 + piece * 16);
 #pragma unroll
         for (int e = 0; e < PER; ++e) tile[row][col + e] = v[e];
     }
@@ -284,11 +296,15 @@ int launch_transpose(const T *src, const int32_t *index, int64_t ld_src, int64_t
                      int k_pad, T *dst, int64_t dst_rows_alloc, hipStream_t st) {
     constexpr int RT = 64 / (int)sizeof(T);
     const dim3 grid((unsigned)(k_pad / RT), (unsigned)ceil_div(n_cols, 64));
+    const uintptr_t base = reinterpret_cast<uintptr_t>(src);
+    const int64_t row_bytes = ld_src * (int64_t)sizeof(T);
     if (src_rows_alloc > 0) {
         if (n_cols % 64 != 0) return JITDB_E_BADARG;
         transpose_kb_kernel<T, SRC_KB><<<grid, kT, 0, st>>>(src, index, ld_src, src_rows_alloc, n_rows, n_cols, dst, dst_rows_alloc);
-    } else if ((ld_src * sizeof(T)) % 16 == 0 && reinterpret_cast<uintptr_t>(src) % 16 == 0) {
-        transpose_kb_kernel<T, SRC_VEC><<<grid, kT, 0, st>>>(src, index, ld_src, 0, n_rows, n_cols, dst, dst_rows_alloc);
+    } else if (row_bytes % 16 == 0 && base % 16 == 0) {
+        transpose_kb_kernel<T, SRC_VEC, 16><<<grid, kT, 0, st>>>(src, index, ld_src, 0, n_rows, n_cols, dst, dst_rows_alloc);
+    } else if (row_bytes % 8 == 0 && base % 8 == 0) {
+        transpose_kb_kernel<T, SRC_VEC, 8><<<grid, kT, 0, st>>>(src, index, ld_src, 0, n_rows, n_cols, dst, dst_rows_alloc);
     } else {
         transpose_kb_kernel<T, SRC_SCALAR><<<grid, kT, 0, st>>>(src, index, ld_src, 0, n_rows, n_cols, dst, dst_rows_alloc);
     }
