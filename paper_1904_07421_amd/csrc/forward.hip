@@ -569,6 +569,7 @@ constexpr int kDmaBM = 128;        // rows per block
 constexpr int kDmaStage = 64;      // bytes of K per row and stage
 constexpr int kDmaBuf = (kDmaBM + kBN) * kDmaStage;
 constexpr int kDmaBufs = 3;
+constexpr int kWarmMaxStages = 256; // longest K loop whose A tile is requested up front (2 MB)
 constexpr int kDmaProjStride = 136; // floats per row of a wave's projection store region (128 units + 8)
 
 #define JITDB_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
@@ -754,7 +755,9 @@ __device__ __forceinline__ void dma_gemm(const LevelArgs &a, char *lds, const in
     // data goes to a sink): the stage loads further down the K loop then find their lines
     // in L2 instead of each waiting for HBM with only two stages of lookahead.  The blocks
     // of one column group of a row tile run side by side on one XCD and split the lines.
-    if constexpr (MODE != MODE_PROJ) {
+    // (A long reduction axis, as in the weight-gradient GEMMs, would ask for far more than L2
+    // holds; there the stage loads take their chances.)
+    if (MODE != MODE_PROJ && n_stages <= kWarmMaxStages) {
         char *sink_w = sink + wave * 256;
         const int n_lines = n_stages * (kDmaBM * kDmaStage / 128);
         const char *tile = static_cast<const char *>(a.stack) + (int64_t)tile_row0 * kDmaStage;
