@@ -368,8 +368,8 @@ ones_row_kernel(T *__restrict__ dst, int64_t dst_rows_alloc, int row, int n_rows
         from_f32<T>(r < n_rows ? 1.0f : 0.0f);
 }
 
-// dW [4H, D], dU [4H, H], db [4H] from the packed accumulators: dMp [4 Hk, D + 1 + H] with column
-// D the bias gradient, dUfp [Hk, H]
+// dW [4H, D], dU [4H, H], db [4H] from the packed accumulators: dMp [D + 1 + H, 4 Hk] (transposed:
+// row n < D belongs to x_n, row D to the bias, row D + 1 + n' to hs_n'), dUfp [Hk, H]
 __global__ void __launch_bounds__(kT)
 unpack_grads_kernel(const float *__restrict__ dMp, const float *__restrict__ dUfp,
                     int D, int H, int Hk, float *__restrict__ dW, float *__restrict__ dU, float *__restrict__ db) {
@@ -378,7 +378,7 @@ unpack_grads_kernel(const float *__restrict__ dMp, const float *__restrict__ dUf
     for (int64_t idx = (int64_t)blockIdx.x * kT + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * kT) {
         const int row = (int)(idx / ld), col = (int)(idx % ld);
         const int g = row / H, m = row % H;
-        const float v = dMp[((int64_t)g * Hk + m) * ld + col];
+        const float v = dMp[(int64_t)col * 4 * Hk + g * Hk + m];
         if (col < D) dW[(int64_t)row * D + col] = v;
         else if (col == D) db[row] = v;
         else dU[(int64_t)row * H + (col - D - 1)] = g < 3 ? v : dUfp[(int64_t)m * H + (col - D - 1)];
@@ -469,7 +469,9 @@ int run_backward(const T *x, const T *W, const T *U, const BwdDims &d, const jit
             g.A = A; g.a_rows_alloc = a_alloc; g.M = M; g.B = B; g.b_rows_alloc = b_alloc; g.N = N;
             g.k_bytes = (int64_t)kpad * sizeof(T);
             const int64_t tiles = ceil_div(M, 128) * ceil_div(N, 256);
-            const int64_t want = ceil_div(512, tiles);      // two blocks per CU
+            // one round of blocks (two per CU), in multiples of eight splits: a split's XCD is split % 8
+            int64_t want = 8 * (512 / (8 * tiles));
+            if (want < 8) want = tiles >= 512 ? 1 : 8;
             const int64_t most = kpad / 512 > 0 ? kpad / 512 : 1;
             g.k_splits = (int)(want < most ? want : most);
             g.epilogue = KB_EPI_ATOMIC_ACC; g.out0 = C; g.ldc = ldc;
@@ -508,7 +510,7 @@ int run_backward(const T *x, const T *W, const T *U, const BwdDims &d, const jit
             g.epilogue = KB_EPI_DX_DHS; g.out0 = dx; g.out1 = w.dhs; g.node = nodes; g.D = D; g.H = H;
             if ((rc = launch_kb_gemm(dtype, g, st)) != JITDB_OK) return rc;
         }
-        // weight gradients: dMp += dZ^T [x | 1 | hs] (leaves have hs = 0: the x and bias columns only)
+        // weight gradients: dMp += [x | 1 | hs]^T dZ (leaves have hs = 0: the x and bias rows only)
         if ((rc = launch_transpose<T>(x, nodes, D, 0, rows, D, kpad, At, at_alloc, st)) != JITDB_OK) return rc;
         ones_row_kernel<T><<<(unsigned)ceil_div(kpad, kT), kT, 0, st>>>(At, at_alloc, D, rows, kpad);
         JITDB_LAUNCH_CHECK();
@@ -523,7 +525,9 @@ int run_backward(const T *x, const T *W, const T *U, const BwdDims &d, const jit
             JITDB_LAUNCH_CHECK();
             q_cols = D + 1 + H;
         }
-        if ((rc = weight_gemm(dZt, zt_alloc, n_gates * Hk, At, at_alloc, q_cols, w.dMp, D + 1 + H)) != JITDB_OK) return rc;
+        // [x | 1 | hs]^T dZ rather than its transpose: the narrow side (813 or 301) then pads to
+        // 128-row tiles instead of 256-column tiles
+        if ((rc = weight_gemm(At, at_alloc, q_cols, dZt, zt_alloc, n_gates * Hk, w.dMp, 4 * Hk)) != JITDB_OK) return rc;
     }
     unpack_grads_kernel<<<1024, kT, 0, st>>>(w.dMp, w.dUfp, D, H, Hk, dW, dU, db);
     JITDB_LAUNCH_CHECK();
