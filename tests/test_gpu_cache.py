@@ -80,3 +80,26 @@ def test_cached_schedule_gives_the_same_forward():
     assert hit
     h_b, c_b = J.jitdb_treelstm_forward(dev(x), dev(W), dev(U), dev(b), s_b)
     assert torch.equal(h_a, h_b) and torch.equal(c_a, c_b)
+
+
+@pytest.mark.timeout(600)
+def test_fingerprint_of_the_largest_forest():
+    """N = 2^28: the position enters the hashed word in its upper half; nothing may wrap at 2^31."""
+    import torch
+    import paper_1904_07421_amd as J
+    n = 1 << 28
+    v = np.arange(n, dtype=np.int32)
+    p = np.where((v & 3) == 0, -1, v - 1).astype(np.int32)
+    del v
+    print(f"fingerprint N={n}", flush=True)
+    got = J.jitdb_forest_fingerprint(torch.from_numpy(p).cuda())
+    want = (0, 0)
+    step = 1 << 24                                   # the oracle's sums, piecewise to bound host memory
+    for lo in range(0, n, step):
+        q = p[lo:lo + step]
+        with np.errstate(over="ignore"):
+            word = ((np.arange(lo, lo + q.shape[0], dtype=np.uint64)) << np.uint64(32)) | q.view(np.uint32).astype(np.uint64)
+            f0 = C._mix64_np(word + np.uint64(C.GOLDEN)).sum(dtype=np.uint64)
+            f1 = C._mix64_np(word ^ np.uint64(C.KEY1)).sum(dtype=np.uint64)
+        want = ((want[0] + int(f0)) & C.MASK, (want[1] + int(f1)) & C.MASK)
+    assert got == want

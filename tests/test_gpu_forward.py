@@ -242,3 +242,32 @@ def test_forward_can_be_captured_in_a_graph(c_oracle):
         torch.cuda.synchronize()
         ho, co, _ = c_oracle(p, xs, W, U, b)
         assert np.abs(h.cpu().numpy() - ho).max() <= 1e-4 and np.abs(c.cpu().numpy() - co).max() <= 1e-4
+
+
+@pytest.mark.timeout(900)
+def test_largest_forest_the_interface_accepts():
+    """N = JITDB_MAX_NODES (2^28) with D = H = 1: 2^26 chains of four nodes that all carry the same
+    inputs, so every chain must reproduce the oracle's states for one chain.  What is tested is the
+    addressing: node ids, row offsets and workspace offsets beyond 2^31 bytes in every kernel."""
+    import torch
+    import paper_1904_07421_amd as J
+    n, t = 1 << 28, 1 << 26
+    print(f"forward N={n} D=H=1 bf16", flush=True)
+    v = torch.arange(n, dtype=torch.int32, device="cuda")
+    parent = torch.where((v & 3) == 0, torch.full_like(v, -1), v - 1)
+    xs = np.array([0.5, -1.0, 0.25, 2.0], dtype=np.float32)          # exact in bf16
+    W = np.array([[0.75], [-0.5], [1.25], [0.375]], dtype=np.float32)
+    U = np.array([[0.5], [0.25], [-0.75], [1.5]], dtype=np.float32)
+    b = np.array([0.125, -0.25, 0.5, 0.0625], dtype=np.float32)
+    x = torch.from_numpy(xs).cuda().to(torch.bfloat16)[(v & 3).long()].reshape(n, 1).contiguous()
+    del v
+    s = J.jitdb_schedule(parent)
+    del parent
+    dev = lambda a: torch.from_numpy(a).cuda().to(torch.bfloat16)
+    h, c = J.jitdb_treelstm_forward(x, dev(W), dev(U), torch.from_numpy(b).cuda(), s)
+    torch.cuda.synchronize()
+    ho, co = T.forward(np.array([-1, 0, 1, 2], dtype=np.int32), xs.reshape(4, 1), W, U, b)
+    h4, c4 = h.view(t, 4), c.view(t, 4)
+    assert np.abs(h4[0].float().cpu().numpy() - ho[:, 0]).max() <= TOL["bf16"]
+    assert np.abs(c4[0].cpu().numpy() - co[:, 0]).max() <= TOL["bf16"]
+    assert bool((h4 == h4[0]).all()) and bool((c4 == c4[0]).all())
