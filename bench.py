@@ -434,9 +434,17 @@ def main():
         t1 = time.perf_counter()
         _, _, used = forward_c(sub, xo, Wo, Uo, b)
         dt = time.perf_counter() - t1
+        # the same oracle on one thread, on a sixteenth of the sample
+        n1 = max(1, n_trees // 16)
+        hi1 = int(r[n1])
+        t1 = time.perf_counter()
+        forward_c(sub[:hi1], xo[:hi1], Wo, Uo, b, n_threads=1)
+        dt1 = time.perf_counter() - t1
         out["cpu_baseline"] = {"value": hi / dt, "unit": "nodes/s", "cores": int(used), "kind": "oracle",
                                "sample": f"first {n_trees} trees ({hi} nodes) of the same forest, "
-                                         f"fp64 C oracle with OpenMP over trees, {dt:.1f}s"}
+                                         f"fp64 C oracle with OpenMP over trees, {dt:.1f}s",
+                               "one_thread": {"value": hi1 / dt1, "unit": "nodes/s", "cores": 1,
+                                              "sample": f"first {n1} trees ({hi1} nodes), {dt1:.1f}s"}}
     print(json.dumps(out), flush=True)
 
 
