@@ -211,7 +211,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the forest shards by tree with no "
-              "exchange; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+              "exchange). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import torch
