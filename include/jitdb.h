@@ -298,7 +298,7 @@ size_t jitdb_treelstm_backward_workspace_bytes(const jitdb_schedule_t *s, int32_
  *   dx [N, D], dW [4H, D], dU [4H, H], db [4H]   dev, fp32, overwritten.
  *
  * With JITDB_BF16 the GEMM operands (gate derivatives, x, h, weights) are bfloat16 and all
- * sums fp32.  Asynchronous on `hip_stream`; N == 0 zeroes dW, dU, db.  x and h 16-byte aligned.
+ * sums fp32.  Asynchronous on `hip_stream`; N == 0 zeroes dW, dU, db.  x, h and dx 16-byte aligned.
  */
 int jitdb_treelstm_backward(const void *x, const void *W, const void *U,
                             int32_t D, int32_t H, jitdb_dtype dtype, const jitdb_schedule_t *s,

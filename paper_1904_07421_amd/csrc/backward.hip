@@ -153,8 +153,8 @@ bwd_cell_kernel(const int32_t *__restrict__ nodes, int n_rows, int H, int Hk,
                 const int32_t *__restrict__ child_ptr, const int32_t *__restrict__ child_idx,
                 const int32_t *__restrict__ parent_of,
                 const float *__restrict__ c, const T *__restrict__ gates, const T *__restrict__ fgate,
-                const float *__restrict__ gh, const float *__restrict__ gc, const float *__restrict__ dhs,
-                const float *__restrict__ ufg, float *__restrict__ dc,
+                const float *__restrict__ gh, const float *__restrict__ gc, const T *__restrict__ dhs,
+                const T *__restrict__ ufg, float *__restrict__ dc,
                 const int32_t *__restrict__ inv_perm, T *__restrict__ G, int64_t g_rows_alloc,
                 T *__restrict__ dZ, int64_t dz_rows_alloc, T *__restrict__ dZt, int64_t zt_rows_alloc, int n_gates) {
     constexpr int RT = 64 / (int)sizeof(T);
@@ -172,10 +172,10 @@ bwd_cell_kernel(const int32_t *__restrict__ nodes, int n_rows, int H, int Hk,
                         gu = to_f32<T>(gates[j * 3 * H + 2 * H + m]);
             const float th = tanhf(c[j * H + m]);
             const int64_t p = parent_of[j];
-            float dhj = (gh ? gh[j * H + m] : 0.0f) + (ufg ? ufg[(int64_t)r * H + m] : 0.0f);
+            float dhj = (gh ? gh[j * H + m] : 0.0f) + (ufg ? to_f32<T>(ufg[(int64_t)r * H + m]) : 0.0f);
             float dcj = gc ? gc[j * H + m] : 0.0f;
             if (p >= 0) {
-                dhj += dhs[p * H + m];
+                dhj += to_f32<T>(dhs[p * H + m]);
                 dcj += dc[p * H + m] * to_f32<T>(fgate[j * H + m]);
             }
             dcj += dhj * go * (1.0f - th * th);
@@ -392,7 +392,8 @@ struct BwdDims {
     size_t esz;
 };
 struct BwdWs {
-    float *dc, *dhs, *ufg, *dMp, *dUfp;
+    float *dc, *dMp, *dUfp;
+    void *dhs, *ufg;      // in the operands' element type
     int32_t *parent_of;
     void *Mt, *Uft, *dZ, *G, *dZt, *At, *Gt, *Hkt;
     size_t bytes;
@@ -402,8 +403,8 @@ BwdWs carve_bwd_ws(int64_t n, const BwdDims &d, void *base) {
     Carver c(base);
     BwdWs w;
     w.dc = c.take<float>((size_t)n * d.H);
-    w.dhs = c.take<float>((size_t)n * d.H);
-    w.ufg = c.take<float>((size_t)d.n_max * d.H);
+    w.dhs = c.take<char>((size_t)n * d.H * d.esz);
+    w.ufg = c.take<char>((size_t)d.n_max * d.H * d.esz);
     w.dMp = c.take<float>((size_t)4 * d.Hk * (d.D + 1 + d.H));
     w.dUfp = c.take<float>((size_t)d.Hk * d.H);
     w.parent_of = c.take<int32_t>((size_t)n);
@@ -499,7 +500,8 @@ int run_backward(const T *x, const T *W, const T *U, const BwdDims &d, const jit
             if ((rc = weight_gemm(Gt, gt_alloc, Hk, Hkt, ht_alloc, H, w.dUfp, H)) != JITDB_OK) return rc;
         }
         bwd_cell_kernel<T><<<tile_grid, kT, 0, st>>>(nodes, rows, H, Hk, s->child_ptr, s->child_idx, w.parent_of, c,
-                                                     gates, fgate, gh, gc, w.dhs, l < L - 1 ? w.ufg : nullptr, w.dc,
+                                                     gates, fgate, gh, gc, static_cast<const T *>(w.dhs),
+                                                     l < L - 1 ? static_cast<const T *>(w.ufg) : nullptr, w.dc,
                                                      s->inv_perm, G_all, g_alloc, dZ, lvl_alloc, dZt, zt_alloc, n_gates);
         JITDB_LAUNCH_CHECK();
         {   // [dx | dhs] = dZ [W | U]; leaves have nobody to pass dhs to
@@ -589,7 +591,9 @@ extern "C" int jitdb_treelstm_backward(const void *x, const void *W, const void 
     if (!s->perm || !s->inv_perm || !s->child_ptr || !s->child_idx || !s->host_level_ptr) return JITDB_E_NULL;
     if ((reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return JITDB_E_BADARG;
     // operand rows are read in 16-byte pieces
-    if ((reinterpret_cast<uintptr_t>(x) & 15) || (reinterpret_cast<uintptr_t>(h) & 15)) return JITDB_E_BADARG;
+    if ((reinterpret_cast<uintptr_t>(x) & 15) || (reinterpret_cast<uintptr_t>(h) & 15) ||
+        (reinterpret_cast<uintptr_t>(dx) & 15))
+        return JITDB_E_BADARG;
     const int L = s->n_levels;
     if (L < 1 || L > n || s->host_level_ptr[0] != 0 || s->host_level_ptr[L] != n) return JITDB_E_SCHEDULE;
     const BwdWs w = carve_bwd_ws(n, d, workspace);

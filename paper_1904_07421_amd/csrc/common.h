@@ -59,16 +59,17 @@ __host__ __device__ __forceinline__ int64_t operand_offset(int64_t row, int64_t 
 // to 128 per slab), B has N rows (b_rows_alloc >= N rounded up to 256); K is k_bytes / element
 // size, k_bytes a multiple of 128.  k_splits > 1 deals ranges of K to different blocks.
 enum KbEpilogue : int {
-    KB_EPI_DX_DHS = 0,       // col < D: out0[node[row] * D + col] = v, else out1[node[row] * H + col - D] = v
-    KB_EPI_ATOMIC_ACC = 1,   // atomicAdd(out0[row * ldc + col], v)
-    KB_EPI_STORE = 2         // out0[row * ldc + col] = v
+    KB_EPI_DX_DHS = 0,       // col < D: out0[node[row] * D + col] = v (fp32), else out1[node[row] * H + col - D] = v
+                             // (in the operands' element type)
+    KB_EPI_ATOMIC_ACC = 1,   // atomicAdd(out0[row * ldc + col], v), fp32
+    KB_EPI_STORE = 2         // out0[row * ldc + col] = v, in the operands' element type
 };
 struct KbGemm {
     const void *A; int64_t a_rows_alloc; int M;
     const void *B; int64_t b_rows_alloc; int N;
     int64_t k_bytes; int k_splits;
     int epilogue;
-    float *out0; float *out1; const int32_t *node; int D; int H; int ldc;
+    void *out0; void *out1; const int32_t *node; int D; int H; int ldc;
 };
 int launch_kb_gemm(jitdb_dtype dtype, const KbGemm &g, hipStream_t st);
 

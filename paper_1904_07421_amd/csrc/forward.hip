@@ -938,7 +938,7 @@ level_kernel(const LevelArgs a) {
 // every XCD has work however few output tiles there are.
 struct KbEpiArgs {
     int kind;
-    float *out0; float *out1; const int32_t *node; int D; int H; int ldc;
+    void *out0; void *out1; const int32_t *node; int D; int H; int ldc;
     int M, N;
     int stages_total, stages_per_split, splits;
 };
@@ -987,28 +987,92 @@ gemm_kb_kernel(LevelArgs a, const KbEpiArgs e) {
     dma_gemm<T, MODE_GENERIC>(a, lds, nullptr, tile_row0, col_tile, acc, sink, []() {});
     __syncthreads();
 
+    if (e.kind == KB_EPI_ATOMIC_ACC) {
+        float *out = static_cast<float *>(e.out0);
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int col = col_tile * kBN + wn * 128 + g * 32 + l32;
-            if (col >= e.N) continue;
+            for (int g = 0; g < 4; ++g) {
+                const int col = col_tile * kBN + wn * 128 + g * 32 + l32;
+                if (col >= e.N) continue;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = tile_row0 + wm * 64 + i * 32 + (v >> 2) * 8 + hf * 4 + (v & 3);
-                if (row >= e.M) continue;
-                const float val = acc[i][g][v];
-                if (e.kind == KB_EPI_DX_DHS) {
-                    const int64_t nd = s_node[row - tile_row0];
-                    if (col < e.D) e.out0[nd * e.D + col] = val;
-                    else e.out1[nd * e.H + (col - e.D)] = val;
-                } else if (e.kind == KB_EPI_STORE) {
-                    e.out0[(int64_t)row * e.ldc + col] = val;
+                for (int v = 0; v < 16; ++v) {
+                    const int row = tile_row0 + wm * 64 + i * 32 + (v >> 2) * 8 + hf * 4 + (v & 3);
+                    if (row < e.M) atomicAdd(&out[(int64_t)row * e.ldc + col], acc[i][g][v]);
+                }
+            }
+        return;
+    }
+    // Row-wise epilogues: a wave turns its 64 x 128 sub-tile, 32 rows at a time, through a
+    // region of the (now free) stage buffers, so that a lane ends up with four consecutive
+    // columns of one row and the wave stores whole 512-byte row segments.
+    constexpr int kStride = 128 + 4;
+    static_assert(4 * 32 * kStride * 4 <= kDmaBufs * kDmaBuf, "epilogue regions must fit the stage buffers");
+    float *region = reinterpret_cast<float *>(lds) + wave * (32 * kStride);
+    const int c4 = (lane & 31) * 4;
+    const int col = col_tile * kBN + wn * 128 + c4;
+    const bool vec_ok = e.kind == KB_EPI_STORE ? (e.ldc & 3) == 0 : ((e.D & 3) == 0 && (e.H & 3) == 0);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                region[((v >> 2) * 8 + hf * 4 + (v & 3)) * kStride + g * 32 + l32] = acc[i][g][v];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll 4
+        for (int sweep = 0; sweep < 16; ++sweep) {
+            const int rl = (lane >> 5) + 2 * sweep;
+            const int row = tile_row0 + wm * 64 + i * 32 + rl;
+            if (row >= e.M || col >= e.N) continue;
+            const float4 q = *reinterpret_cast<const float4 *>(region + rl * kStride + c4);
+            const float f[4] = {q.x, q.y, q.z, q.w};
+            if (e.kind == KB_EPI_STORE) {
+                T *dst = static_cast<T *>(e.out0) + (int64_t)row * e.ldc + col;
+                if (vec_ok && col + 4 <= e.N) {
+                    if constexpr (sizeof(T) == 4) {
+                        *reinterpret_cast<float4 *>(dst) = q;
+                    } else {
+                        *reinterpret_cast<uint2 *>(dst) =
+                            make_uint2((uint32_t)f32_to_bf16(f[0]) | ((uint32_t)f32_to_bf16(f[1]) << 16),
+                                       (uint32_t)f32_to_bf16(f[2]) | ((uint32_t)f32_to_bf16(f[3]) << 16));
+                    }
                 } else {
-                    atomicAdd(&e.out0[(int64_t)row * e.ldc + col], val);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (col + j < e.N) dst[j] = from_f32<T>(f[j]);
+                }
+            } else {   // KB_EPI_DX_DHS
+                const int64_t nd = s_node[row - tile_row0];
+                float *dx = static_cast<float *>(e.out0) + nd * e.D;
+                T *dhs = static_cast<T *>(e.out1) + nd * e.H;
+                if (vec_ok && col + 4 <= e.N) {        // D % 4 == 0: the four columns lie on one side of D
+                    if (col < e.D) {
+                        *reinterpret_cast<float4 *>(dx + col) = q;
+                    } else if constexpr (sizeof(T) == 4) {
+                        *reinterpret_cast<float4 *>(dhs + (col - e.D)) = q;
+                    } else {
+                        *reinterpret_cast<uint2 *>(dhs + (col - e.D)) =
+                            make_uint2((uint32_t)f32_to_bf16(f[0]) | ((uint32_t)f32_to_bf16(f[1]) << 16),
+                                       (uint32_t)f32_to_bf16(f[2]) | ((uint32_t)f32_to_bf16(f[3]) << 16));
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int cj = col + j;
+                        if (cj >= e.N) continue;
+                        if (cj < e.D) dx[cj] = f[j];
+                        else dhs[cj - e.D] = from_f32<T>(f[j]);
+                    }
                 }
             }
         }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
 }
 
 // ---- thin levels ---------------------------------------------------------------------
