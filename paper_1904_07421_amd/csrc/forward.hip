@@ -29,6 +29,8 @@
 
 #include "common.h"
 
+#include <vector>
+
 #include <type_traits>
 
 namespace jitdb {
@@ -216,15 +218,21 @@ __device__ __forceinline__ void add_piece(float (&acc)[Traits<T>::VEC], const ui
     }
 }
 
+struct StackArgs {
+    const void *x; int D, Dp; const void *hs; int Hp;
+    const int4 *row_rec; const int32_t *child_idx;
+    void *A; int n_rows, n_rows_alloc;
+};
+
+// block `block` of the stack step (kThreads threads)
 template <typename T, bool WITH_H>
-__global__ void __launch_bounds__(kThreads)
-stack_kernel(const T *__restrict__ x, int D, int Dp, const T *__restrict__ hs, int Hp,
-             const int4 *__restrict__ row_rec, const int32_t *__restrict__ child_idx,
-             T *__restrict__ A, int n_rows, int n_rows_alloc) {
+__device__ __forceinline__ void stack_body(const T *__restrict__ x, int D, int Dp, const T *__restrict__ hs, int Hp,
+                                           const int4 *__restrict__ row_rec, const int32_t *__restrict__ child_idx,
+                                           T *__restrict__ A, int n_rows, int n_rows_alloc, int64_t block) {
     constexpr int VEC = Traits<T>::VEC;
     const int Kp = Dp + (WITH_H ? Hp : 0);
     const int cpr = Kp / VEC;
-    const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int64_t gid = block * kThreads + threadIdx.x;
     const int64_t row = gid / cpr;
     const int ch = (int)(gid % cpr);
     if (row >= n_rows) return;
@@ -288,6 +296,14 @@ stack_kernel(const T *__restrict__ x, int D, int Dp, const T *__restrict__ hs, i
     }
     *reinterpret_cast<uint4 *>(reinterpret_cast<char *>(A) +
                                operand_offset(row, (int64_t)k0 * sizeof(T), n_rows_alloc)) = o;
+}
+
+template <typename T, bool WITH_H>
+__global__ void __launch_bounds__(kThreads)
+stack_kernel(const T *__restrict__ x, int D, int Dp, const T *__restrict__ hs, int Hp,
+             const int4 *__restrict__ row_rec, const int32_t *__restrict__ child_idx,
+             T *__restrict__ A, int n_rows, int n_rows_alloc) {
+    stack_body<T, WITH_H>(x, D, Dp, hs, Hp, row_rec, child_idx, A, n_rows, n_rows_alloc, blockIdx.x);
 }
 
 // ---- the level GEMM ----------------------------------------------------------------
@@ -1090,8 +1106,7 @@ constexpr int kThinMaxRows = 8192; // levels up to this many rows use the thin k
 constexpr int kThinAhead = 8;      // K groups in flight per wave
 
 template <typename T, int MODE, bool SAVE = false>
-__global__ void __launch_bounds__(kThinWaves * 64, 2)
-thin_kernel(const LevelArgs a) {
+__device__ __forceinline__ void thin_body(const LevelArgs &a, int tile) {
     constexpr int ESZ = (int)sizeof(T);
     __shared__ __attribute__((aligned(16))) float region[3 * 32 * kEpiStride];
     __shared__ __attribute__((aligned(16))) float exchange[3][16][64];   // accumulators of waves 1-3
@@ -1103,7 +1118,6 @@ thin_kernel(const LevelArgs a) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int hf = lane >> 5, l32 = lane & 31;
-    const int tile = blockIdx.x;
     const int row0 = (tile / a.n_col_tiles) * 32;
     const int col = tile % a.n_col_tiles;     // unit tile (gates) or group of four unit tiles (projection)
     if (MODE == MODE_LEAF && wave == 3) return;                                   // leaves have no forget gate
@@ -1181,15 +1195,11 @@ thin_kernel(const LevelArgs a) {
     if constexpr (MODE == MODE_PROJ) {
         T *P = static_cast<T *>(a.P);
         const int unit = (col * 4 + wave) * kUnit + l32;
-        if (unit < a.H) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int r = row0 + (v >> 2) * 8 + hf * 4 + (v & 3);
-                if (r < a.n_rows) {
-                    const int node = a.row_rec[2 * (int64_t)r].x;
-                    P[(int64_t)node * a.Hq + unit] = from_f32<T>(acc[0][v]);
-                }
-            }
+        for (int v = 0; v < 16; ++v) {
+            const int rl = (v >> 2) * 8 + hf * 4 + (v & 3);
+            const int node = __shfl(my_node, rl, 64);      // lane rl holds the node of tile row rl (all lanes take part)
+            if (unit < a.H && row0 + rl < a.n_rows) P[(int64_t)node * a.Hq + unit] = from_f32<T>(acc[0][v]);
         }
     } else {
         // gates 1-3 travel to wave 0, which holds gate 0 (every wave that is still here
@@ -1206,6 +1216,27 @@ thin_kernel(const LevelArgs a) {
             for (int v = 0; v < 16; ++v) acc[g][v] = exchange[g - 1][v][lane];
         cell_pass<T, MODE, SAVE>(a, acc, region, s_node, s_ar, s_cb, s_kid, col, lane);
     }
+}
+
+template <typename T, int MODE, bool SAVE = false>
+__global__ void __launch_bounds__(kThinWaves * 64, 2)
+thin_kernel(const LevelArgs a) {
+    thin_body<T, MODE, SAVE>(a, blockIdx.x);
+}
+
+// The projection of a thin slot and the stack step of the slot after it in one launch: both
+// only need what the level kernel before them wrote, and a thin level costs its chain of
+// launches, not its work.  Blocks [0, a.n_blocks) are projection tiles, the rest stack blocks.
+template <typename T>
+__global__ void __launch_bounds__(kThinWaves * 64, 2)
+thin_proj_stack_kernel(const LevelArgs a, const StackArgs s) {
+    static_assert(kThinWaves * 64 == kThreads, "both bodies use the same block size");
+    if ((int)blockIdx.x < a.n_blocks)
+        thin_body<T, MODE_PROJ>(a, blockIdx.x);
+    else
+        stack_body<T, true>(static_cast<const T *>(s.x), s.D, s.Dp, static_cast<const T *>(s.hs), s.Hp, s.row_rec,
+                            s.child_idx, static_cast<T *>(s.A), s.n_rows, s.n_rows_alloc,
+                            (int64_t)blockIdx.x - a.n_blocks);
 }
 
 // ---- host side ---------------------------------------------------------------------
@@ -1340,32 +1371,51 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
     a.D = d.D; a.Dp = d.Dp; a.H = d.H; a.Hp = d.Hp; a.Hu = d.Hu;
     a.NPU = d.NPU;
 
+    // the non-empty slots in order
+    struct Seg { int l, sig, begin, rows; };
+    std::vector<Seg> segs;
+    segs.reserve((size_t)L * n_sig);
     for (int q = 0; q < L * n_sig; ++q) {
-        const int l = q / n_sig, sig = q % n_sig;
         const int n_rows = sp[q + 1] - sp[q];
         if (n_rows < 0 || (n_rows == 0 && !slots)) return JITDB_E_SCHEDULE;
-        if (n_rows == 0) continue;
+        if (n_rows > 0) segs.push_back({q / n_sig, q % n_sig, sp[q], n_rows});
+    }
+    // stack: gather a slot's x rows and child sums into one dense matrix
+    auto stack_args = [&](const Seg &g) {
+        StackArgs sa;
+        sa.x = x; sa.D = d.D; sa.Dp = d.Dp; sa.hs = a.hs; sa.Hp = d.Hp;
+        sa.row_rec = w.row_rec + 2 * (int64_t)g.begin; sa.child_idx = s->child_idx;
+        sa.A = w.stack; sa.n_rows = g.rows; sa.n_rows_alloc = (int)round_up(g.rows, kRowPad);
+        return sa;
+    };
+    auto stack_blocks = [&](const Seg &g) {
+        const int Kp = d.Dp + (g.l > 0 ? d.Hp : 0);
+        return (unsigned)ceil_div((int64_t)g.rows * (Kp / Traits<T>::VEC), kThreads);
+    };
+    bool stacked_ahead = false;     // the slot's stack step already ran with the projection before it
+
+    for (size_t i = 0; i < segs.size(); ++i) {
+        const int l = segs[i].l, sig = segs[i].sig, n_rows = segs[i].rows;
         a.Bp = static_cast<char *>(w.Bp) + packed_w_bytes(d) * sig;
         a.bp = w.bp + (size_t)d.NP * sig;
-        a.row_rec = w.row_rec + 2 * (int64_t)sp[q];
+        a.row_rec = w.row_rec + 2 * (int64_t)segs[i].begin;
         a.n_rows = n_rows;
         a.n_rows_alloc = (int)round_up(n_rows, kRowPad);
         const int row_tiles = (int)ceil_div(n_rows, kDmaBM);
-        {   // stack: gather the level's x rows and child sums into one dense matrix
-            const int Kp = d.Dp + (l > 0 ? d.Hp : 0);
-            const int64_t pieces = (int64_t)n_rows * (Kp / Traits<T>::VEC);
-            const unsigned grid = (unsigned)ceil_div(pieces, kThreads);
+        if (!stacked_ahead) {
+            const StackArgs sa = stack_args(segs[i]);
             ScopedLaunchTimer tm(JITDB_K_STACK, n_rows, st);
             if (l == 0)
-                stack_kernel<T, false><<<grid, kThreads, 0, st>>>(
-                    static_cast<const T *>(x), d.D, d.Dp, static_cast<const T *>(a.hs), d.Hp, a.row_rec,
-                    s->child_idx, static_cast<T *>(w.stack), n_rows, a.n_rows_alloc);
+                stack_kernel<T, false><<<stack_blocks(segs[i]), kThreads, 0, st>>>(
+                    static_cast<const T *>(sa.x), sa.D, sa.Dp, static_cast<const T *>(sa.hs), sa.Hp, sa.row_rec,
+                    sa.child_idx, static_cast<T *>(sa.A), sa.n_rows, sa.n_rows_alloc);
             else
-                stack_kernel<T, true><<<grid, kThreads, 0, st>>>(
-                    static_cast<const T *>(x), d.D, d.Dp, static_cast<const T *>(a.hs), d.Hp, a.row_rec,
-                    s->child_idx, static_cast<T *>(w.stack), n_rows, a.n_rows_alloc);
+                stack_kernel<T, true><<<stack_blocks(segs[i]), kThreads, 0, st>>>(
+                    static_cast<const T *>(sa.x), sa.D, sa.Dp, static_cast<const T *>(sa.hs), sa.Hp, sa.row_rec,
+                    sa.child_idx, static_cast<T *>(sa.A), sa.n_rows, sa.n_rows_alloc);
             JITDB_LAUNCH_CHECK();
         }
+        stacked_ahead = false;
         // Levels too small to give every CU a 256 x 256 tile go to the thin kernel.
         const bool thin = n_rows <= kThinMaxRows;
         const int n_unit_tiles = d.Hu / kUnit;
@@ -1401,7 +1451,15 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
                 a.n_col_tiles = (int)ceil_div(n_unit_tiles, 4);
                 a.n_tiles = (int)ceil_div(n_rows, 32) * a.n_col_tiles;
                 a.n_blocks = a.n_tiles;
-                thin_kernel<T, MODE_PROJ><<<a.n_blocks, kThinWaves * 64, 0, st>>>(a);
+                // the stack step of the next slot rides along (the level kernel above was the
+                // stack buffer's only reader); its rows are counted with this launch's class
+                if (i + 1 < segs.size() && segs[i + 1].l > 0) {
+                    thin_proj_stack_kernel<T><<<a.n_blocks + stack_blocks(segs[i + 1]), kThinWaves * 64, 0, st>>>(
+                        a, stack_args(segs[i + 1]));
+                    stacked_ahead = true;
+                } else {
+                    thin_kernel<T, MODE_PROJ><<<a.n_blocks, kThinWaves * 64, 0, st>>>(a);
+                }
             } else {
                 a.n_col_tiles = (int)ceil_div(n_unit_tiles, 8);
                 a.n_row_tiles = row_tiles;
