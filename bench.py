@@ -263,32 +263,52 @@ def main():
     c = torch.empty((N, H), dtype=torch.float32, device=dev)
     stream = torch.cuda.current_stream()
 
-    if args.serial:
-        def step():     # every buffer is reused; the schedule is recomputed from the parent array
-            s = J.jitdb_schedule(pt, stream=stream, workspace=ws_s, out=sched)
-            J.jitdb_treelstm_forward(xt, Wt, Ut, bt, s, stream=stream, workspace=ws_f, out=(h, c))
-    else:
-        # Batches arrive one after another: the analysis of batch i+1 runs on a second stream while
-        # batch i executes (the call blocks the host, not the GPU).  Two schedule objects take turns;
-        # an event keeps the analysis from overwriting one that a forward still reads.  Every step is
-        # still one jitdb_schedule (from the parent array) and one jitdb_treelstm_forward.
-        s_fwd, s_sch = torch.cuda.Stream(), torch.cuda.Stream()
-        scheds = [sched, J.jitdb_schedule(pt)]
-        ws_ss = [ws_s, torch.empty_like(ws_s)]
-        last_use = [None, None]
-        turn = [0]
+    def step_serial():     # every buffer is reused; the schedule is recomputed from the parent array
+        s = J.jitdb_schedule(pt, stream=stream, workspace=ws_s, out=sched)
+        J.jitdb_treelstm_forward(xt, Wt, Ut, bt, s, stream=stream, workspace=ws_f, out=(h, c))
+
+    # Batches arrive one after another: the analysis of batch i+1 runs on a second stream while
+    # batch i executes (the call blocks the host, not the GPU).  Two schedule objects take turns;
+    # an event keeps the analysis from overwriting one that a forward still reads.  Every step is
+    # still one jitdb_schedule (from the parent array) and one jitdb_treelstm_forward.
+    s_fwd, s_sch = torch.cuda.Stream(), torch.cuda.Stream()
+    scheds = [sched, J.jitdb_schedule(pt)]
+    ws_ss = [ws_s, torch.empty_like(ws_s)]
+    last_use = [None, None]
+    turn = [0]
+
+    def step_pipelined():
+        k = turn[0] & 1
+        J.jitdb_treelstm_forward(xt, Wt, Ut, bt, scheds[k], stream=s_fwd, workspace=ws_f, out=(h, c))
+        last_use[k] = torch.cuda.Event()
+        last_use[k].record(s_fwd)
+        if last_use[k ^ 1] is not None:
+            s_sch.wait_event(last_use[k ^ 1])
+        J.jitdb_schedule(pt, stream=s_sch, workspace=ws_ss[k ^ 1], out=scheds[k ^ 1])
+        turn[0] += 1
+
+    def rate(fn, n):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n
+
+    # Forests with many thin levels are a chain of short dependent kernels; there a second stream
+    # only gets in the way.  Unless --serial forces it, a short trial picks the faster mode.
+    pipelined = not args.serial
+    if pipelined:
         torch.cuda.synchronize()
         J.jitdb_schedule(pt, stream=s_sch, workspace=ws_ss[0], out=scheds[0])
-
-        def step():
-            k = turn[0] & 1
-            J.jitdb_treelstm_forward(xt, Wt, Ut, bt, scheds[k], stream=s_fwd, workspace=ws_f, out=(h, c))
-            last_use[k] = torch.cuda.Event()
-            last_use[k].record(s_fwd)
-            if last_use[k ^ 1] is not None:
-                s_sch.wait_event(last_use[k ^ 1])
-            J.jitdb_schedule(pt, stream=s_sch, workspace=ws_ss[k ^ 1], out=scheds[k ^ 1])
-            turn[0] += 1
+        rate(step_pipelined, 2); rate(step_serial, 2)
+        t_pipe, t_ser = rate(step_pipelined, 3), rate(step_serial, 3)
+        pipelined = t_pipe <= t_ser
+        log(f"trial: pipelined {t_pipe * 1e3:.3f} ms/step, serial {t_ser * 1e3:.3f} ms/step -> "
+            f"{'pipelined' if pipelined else 'serial'}")
+        if pipelined:       # leave the pipeline primed: scheds[turn & 1] holds a finished analysis
+            torch.cuda.synchronize()
+    step = step_pipelined if pipelined else step_serial
 
     if args.calibration_copy:
         # a plain copy of known size (1 GiB read + 1 GiB written, more than the 256 MB last-level
@@ -305,18 +325,27 @@ def main():
         step()
     torch.cuda.synchronize()
 
-    launches_per_step = 1 + 3 * L
-    if not args.no_kernel_events:
-        J.jitdb_profile_start(launches_per_step * args.steps + 8)
+    # The timed region: exactly K steps, nothing but the library's own launches on the streams.
     torch.cuda.synchronize()
     t_begin = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     t_end = time.perf_counter()
-    prof = None if args.no_kernel_events else J.jitdb_profile_stop()
     ms_per_step = (t_end - t_begin) * 1e3 / args.steps
     value = N / (ms_per_step * 1e-3)
+
+    # The same K steps once more with a HIP event pair around every kernel launch, on the launch
+    # stream (jitdb_profile_start/stop): the per-kernel durations behind `roofline` and `kernels`.
+    # Kept out of the region above because the event records themselves keep consecutive kernels
+    # from overlapping (about 3 % of a step at config 5, a third for a forest of many thin levels).
+    launches_per_step = 1 + 3 * L
+    prof = None
+    ms_with_events = None
+    if not args.no_kernel_events:
+        J.jitdb_profile_start(launches_per_step * args.steps + 8)
+        ms_with_events = rate(step, args.steps) * 1e3
+        prof = J.jitdb_profile_stop()
 
     # schedule and forward separately (same buffers), HIP events on the launch stream
     def timed(fn, reps):
@@ -412,9 +441,10 @@ def main():
         "config": {"workload": f"config {cfg.index}: {cfg.name}", "n_trees": cfg.n_trees, "n_nodes": N,
                    "n_edges": E, "n_levels": L, "D": D, "H": H,
                    "step": "jitdb_schedule + jitdb_treelstm_forward per batch" +
-                           ("" if args.serial else "; schedule of batch i+1 on a second stream beside the forward of batch i")},
+                           ("; schedule of batch i+1 on a second stream beside the forward of batch i" if pipelined else "; one stream")},
         "ms_schedule": ms_sched, "ms_forward": ms_fwd, "ms_per_step_one_stream": ms_sched + ms_fwd,
         "ms_schedule_cache_hit": ms_cache_hit,
+        "ms_per_step_with_kernel_events": ms_with_events,
         "forward_only_nodes_per_s": N / (ms_fwd * 1e-3),
         "roofline": roof, "kernels": kernels, "measured_peaks": measured,
     }
