@@ -12,12 +12,18 @@
  *   jitdb_schedule           the analysis: depth table, slot order, child lists
  *   jitdb_treelstm_forward   the execution: one batched cell evaluation per depth
  *
+ * Around them: jitdb_schedule_append (trees that arrive later join a table), jitdb_forest_fingerprint
+ * and jitdb_cache_* (a cache of tables keyed by the parent array), jitdb_schedule_typed and
+ * jitdb_treelstm_forward_typed (the table keyed by depth and signature, one cell per signature),
+ * jitdb_treelstm_forward_train and jitdb_treelstm_backward (the training step).
+ *
  * Conventions
  *   - Every function returns JITDB_OK (0) or a negative jitdb_status.  Nothing
  *     throws, exits or prints.
  *   - "dev" pointers are device (HBM) memory of the current HIP device, owned
  *     by the caller; "host" pointers are ordinary host memory.  The library
- *     allocates nothing: scratch comes from caller-supplied workspaces whose
+ *     allocates no device memory (jitdb_cache_create allocates a small host-side table, and the
+ *     profiling calls create HIP events): scratch comes from caller-supplied workspaces whose
  *     sizes the *_workspace_bytes queries return.  Workspaces must be 256-byte
  *     aligned.  Nothing is retained after a call returns except what was
  *     written into caller buffers.
