@@ -221,9 +221,10 @@ size_t jitdb_treelstm_typed_workspace_bytes(int64_t n_nodes, int64_t n_edges,
 /*
  * jitdb_treelstm_forward over a typed table: W is dev [n_sig, 4H, D], U dev [n_sig, 4H, H],
  * b dev [n_sig, 4H]; node j is evaluated by cell sig[j].  One batched evaluation per
- * non-empty slot, levels in ascending order; a slot's launches are those of a level in
+ * non-empty slot, levels in ascending order; a slot's steps are those of a level in
  * jitdb_treelstm_forward (stack, gate GEMM + cell update, forget projection), on the slot's
- * rows and the slot's weights.  `s` and `slots` come from jitdb_schedule_typed.
+ * rows and the slot's weights; the slots of a large level share one grouped launch per step.
+ * `s` and `slots` come from jitdb_schedule_typed (slot_ptr is read on the device).
  */
 int jitdb_treelstm_forward_typed(const void *x, const void *W, const void *U, const float *b,
                                  int32_t D, int32_t H, jitdb_dtype dtype,

@@ -336,6 +336,11 @@ struct LevelArgs {
     int n_col_tiles;      // tiles along the column axis
     int n_tiles;          // thin kernel: number of wave tiles
     int n_blocks;
+    // grouped launch over the slots of one level (typed table): row tile i covers level rows
+    // [tiles[i].x, min(tiles[i].x + 128, tiles[i].y)) and is evaluated by cell tiles[i].z
+    const int4 *tiles;
+    int64_t w_bytes;      // bytes between the packed weights of consecutive cells
+    int NP;               // floats between their packed biases
 };
 
 // Block id -> tile of the level kernel.  The hardware deals consecutive block ids
@@ -822,9 +827,10 @@ __device__ __forceinline__ void dma_gemm(const LevelArgs &a, char *lds, const in
     dma_wait_barrier<0>();       // every wave is done reading the stage buffers
 }
 
-template <typename T, int MODE, bool SAVE = false>
+template <typename T, int MODE, bool SAVE = false, bool GROUPED = false>
 __global__ void __launch_bounds__(kDmaThreads, 2)
-level_kernel(const LevelArgs a) {
+level_kernel(const LevelArgs a_in) {
+    LevelArgs a = a_in;
     __shared__ __attribute__((aligned(1024))) char lds[kDmaBufs * kDmaBuf];
     static_assert(4 * 3 * 32 * kEpiStride * 4 <= kDmaBufs * kDmaBuf, "epilogue regions must fit the stage buffers");
     static_assert(4 * 32 * kDmaProjStride * 4 <= kDmaBufs * kDmaBuf, "projection regions must fit the stage buffers");
@@ -841,7 +847,15 @@ level_kernel(const LevelArgs a) {
 
     int row_tile, col_tile;
     if (!block_to_tile(blockIdx.x, a.n_row_tiles, a.n_col_tiles, row_tile, col_tile)) return;
-    const int tile_row0 = row_tile * kDmaBM;
+    int tile_row0 = row_tile * kDmaBM;
+    if constexpr (GROUPED) {     // the tile's slot: where its rows start and end, whose weights apply
+        const int4 e = a.tiles[row_tile];
+        tile_row0 = __builtin_amdgcn_readfirstlane(e.x);
+        a.n_rows = __builtin_amdgcn_readfirstlane(e.y);
+        const int sig = __builtin_amdgcn_readfirstlane(e.z);
+        a.Bp = static_cast<const char *>(a.Bp) + sig * a.w_bytes;
+        a.bp = a.bp + (int64_t)sig * a.NP;
+    }
 
     int node_reg = -1;
     int4 rec0 = make_int4(-1, 0, 0, 0), rec1 = make_int4(-1, -1, -1, -1);
@@ -1239,6 +1253,30 @@ thin_proj_stack_kernel(const LevelArgs a, const StackArgs s) {
                             (int64_t)blockIdx.x - a.n_blocks);
 }
 
+// ---- tile table of a typed level ---------------------------------------------------------
+// One block.  slot_ptr holds the n_sig + 1 boundaries of the level's slots (positions of the
+// whole forest); entry i of the table describes the i-th 128-row tile when every slot is cut
+// into tiles of its own: (first row, end row of its slot, signature), rows relative to the level.
+__global__ void __launch_bounds__(kThreads)
+tile_table_kernel(const int32_t *__restrict__ slot_ptr, int n_sig, int4 *__restrict__ tiles) {
+    __shared__ int s_first[JITDB_MAX_SIGNATURES + 1];
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int t = 0; t < n_sig; ++t) {
+            s_first[t] = run;
+            run += (slot_ptr[t + 1] - slot_ptr[t] + kDmaBM - 1) / kDmaBM;
+        }
+        s_first[n_sig] = run;
+    }
+    __syncthreads();
+    const int base = slot_ptr[0];
+    for (int t = 0; t < n_sig; ++t) {
+        const int lo = slot_ptr[t] - base, hi = slot_ptr[t + 1] - base;
+        for (int j = threadIdx.x; j < s_first[t + 1] - s_first[t]; j += kThreads)
+            tiles[s_first[t] + j] = make_int4(lo + j * kDmaBM, hi, t, 0);
+    }
+}
+
 // ---- host side ---------------------------------------------------------------------
 // Optional per-launch event pairs (see jitdb_profile_start in the header).
 struct Profiler {
@@ -1275,6 +1313,7 @@ struct ForwardWs {
     void *hs;     // nullptr when h_out can serve (H == Hp)
     void *P;
     float *cs;    // nullptr when c_out can serve (H == Hq)
+    int4 *tiles;  // tile table of one typed level (nullptr with one cell)
     size_t bytes;
 };
 
@@ -1315,6 +1354,7 @@ ForwardWs carve_forward_ws(int64_t n, int64_t e, const Dims &d, void *base, int 
     w.hs = (d.H == d.Hp) ? nullptr : c.take<char>((size_t)n * d.Hp * d.esz);
     w.P = c.take<char>((size_t)n * d.Hq * d.esz);
     w.cs = (d.H == d.Hq) ? nullptr : c.take<float>((size_t)n * d.Hq);
+    w.tiles = n_sig > 1 ? c.take<int4>((size_t)(n / kDmaBM + n_sig + 1)) : nullptr;
     w.bytes = c.off;
     return w;
 }
@@ -1371,14 +1411,29 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
     a.D = d.D; a.Dp = d.Dp; a.H = d.H; a.Hp = d.Hp; a.Hu = d.Hu;
     a.NPU = d.NPU;
 
-    // the non-empty slots in order
-    struct Seg { int l, sig, begin, rows; };
+    // The launches in order: one per non-empty slot, except that a level of a typed table that
+    // is large enough for the tiled kernel runs all its slots in one grouped launch (sig = -1;
+    // n_tiles = 128-row tiles when every slot is cut into tiles of its own).
+    struct Seg { int l, sig, begin, rows, n_tiles; };
     std::vector<Seg> segs;
     segs.reserve((size_t)L * n_sig);
-    for (int q = 0; q < L * n_sig; ++q) {
-        const int n_rows = sp[q + 1] - sp[q];
-        if (n_rows < 0 || (n_rows == 0 && !slots)) return JITDB_E_SCHEDULE;
-        if (n_rows > 0) segs.push_back({q / n_sig, q % n_sig, sp[q], n_rows});
+    for (int l = 0; l < L; ++l) {
+        const int lvl_rows = sp[(l + 1) * n_sig] - sp[l * n_sig];
+        int n_tiles = 0, used = 0;
+        for (int t = 0; t < n_sig; ++t) {
+            const int r = sp[l * n_sig + t + 1] - sp[l * n_sig + t];
+            if (r < 0 || (r == 0 && !slots)) return JITDB_E_SCHEDULE;
+            n_tiles += (int)ceil_div(r, kDmaBM);
+            used += r > 0;
+        }
+        if (used > 1 && lvl_rows > kThinMaxRows) {
+            segs.push_back({l, -1, sp[l * n_sig], lvl_rows, n_tiles});
+        } else {
+            for (int t = 0; t < n_sig; ++t) {
+                const int r = sp[l * n_sig + t + 1] - sp[l * n_sig + t];
+                if (r > 0) segs.push_back({l, t, sp[l * n_sig + t], r, 0});
+            }
+        }
     }
     // stack: gather a slot's x rows and child sums into one dense matrix
     auto stack_args = [&](const Seg &g) {
@@ -1396,12 +1451,21 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
 
     for (size_t i = 0; i < segs.size(); ++i) {
         const int l = segs[i].l, sig = segs[i].sig, n_rows = segs[i].rows;
-        a.Bp = static_cast<char *>(w.Bp) + packed_w_bytes(d) * sig;
-        a.bp = w.bp + (size_t)d.NP * sig;
+        const bool grouped = sig < 0;
+        a.Bp = static_cast<char *>(w.Bp) + packed_w_bytes(d) * (grouped ? 0 : sig);
+        a.bp = w.bp + (size_t)d.NP * (grouped ? 0 : sig);
         a.row_rec = w.row_rec + 2 * (int64_t)segs[i].begin;
         a.n_rows = n_rows;
         a.n_rows_alloc = (int)round_up(n_rows, kRowPad);
-        const int row_tiles = (int)ceil_div(n_rows, kDmaBM);
+        a.tiles = nullptr;
+        const int row_tiles = grouped ? segs[i].n_tiles : (int)ceil_div(n_rows, kDmaBM);
+        if (grouped) {
+            a.tiles = w.tiles;
+            a.w_bytes = (int64_t)packed_w_bytes(d);
+            a.NP = d.NP;
+            tile_table_kernel<<<1, kThreads, 0, st>>>(slots->slot_ptr + (int64_t)l * n_sig, n_sig, w.tiles);
+            JITDB_LAUNCH_CHECK();
+        }
         if (!stacked_ahead) {
             const StackArgs sa = stack_args(segs[i]);
             ScopedLaunchTimer tm(JITDB_K_STACK, n_rows, st);
@@ -1437,6 +1501,11 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
                     thin_kernel<T, MODE_LEAF, SAVE><<<a.n_blocks, kThinWaves * 64, 0, st>>>(a);
                 else
                     thin_kernel<T, MODE_INTERNAL, SAVE><<<a.n_blocks, kThinWaves * 64, 0, st>>>(a);
+            } else if (grouped) {
+                if (l == 0)
+                    level_kernel<T, MODE_LEAF, false, true><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
+                else
+                    level_kernel<T, MODE_INTERNAL, false, true><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
             } else {
                 if (l == 0)
                     level_kernel<T, MODE_LEAF, SAVE><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
@@ -1464,7 +1533,10 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
                 a.n_col_tiles = (int)ceil_div(n_unit_tiles, 8);
                 a.n_row_tiles = row_tiles;
                 a.n_blocks = 8 * (int)ceil_div(row_tiles, 8) * a.n_col_tiles;
-                level_kernel<T, MODE_PROJ><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
+                if (grouped)
+                    level_kernel<T, MODE_PROJ, false, true><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
+                else
+                    level_kernel<T, MODE_PROJ><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
             }
         }
         JITDB_LAUNCH_CHECK();
@@ -1589,7 +1661,7 @@ int forward_entry(const void *x, const void *W, const void *U, const float *b, i
     for (int l = 0; l < L; ++l)
         if (s->host_level_ptr[l + 1] <= s->host_level_ptr[l]) return JITDB_E_SCHEDULE;
     if (slots) {
-        if (!slots->key || !slots->host_slot_ptr) return JITDB_E_NULL;
+        if (!slots->key || !slots->slot_ptr || !slots->host_slot_ptr) return JITDB_E_NULL;
         if (slots->slot_capacity < (int64_t)L * n_sig + 1) return JITDB_E_SCHEDULE;
         for (int q = 0; q < L * n_sig; ++q)
             if (slots->host_slot_ptr[q + 1] < slots->host_slot_ptr[q]) return JITDB_E_SCHEDULE;
