@@ -179,12 +179,24 @@ def concat_forests(parent_a, parent_b) -> np.ndarray:
     return np.concatenate([a, shifted]).astype(np.int32)
 
 
+def parent_signatures(parent, sig) -> np.ndarray:
+    """psig[v] = signature of v's parent; a root carries its own."""
+    parent = np.asarray(parent).astype(np.int64)
+    sig = np.asarray(sig)
+    return np.where(parent >= 0, sig[np.maximum(parent, 0)], sig).astype(np.int32)
+
+
 def schedule_typed(parent, sig, n_sig: int) -> dict:
     """The look-up table of the generic batcher (section 4.2): nodes are filed by depth and by
-    a signature that stands for (operator type, settings, input layouts).  Same outputs as
-    `schedule`, with positions sorted by (height, sig, id), plus
-      key[N] = height * n_sig + sig,
-      slot_ptr[L * n_sig + 1]: slot (l, t) holds positions [slot_ptr[l*n_sig+t], slot_ptr[l*n_sig+t+1]).
+    a signature that stands for (operator type, settings, input layouts).  A node takes part in
+    two batched operations with different partners: its own cell, shared with the nodes of its
+    (height, sig), and the forget projection its PARENT's cell applies to it, shared with the
+    nodes of its (height, parent's sig).  The table therefore files by (height, sig, psig):
+    Same outputs as `schedule`, with positions sorted by (height, sig, psig, id), plus
+      key[N] = (height * n_sig + sig) * n_sig + psig,
+      slot_ptr[L * n_sig^2 + 1]: sub-slot (l, t, p) holds positions
+      [slot_ptr[(l*n_sig + t)*n_sig + p], slot_ptr[(l*n_sig + t)*n_sig + p + 1]);
+      slot (l, t), the cell's batch, is the run of its n_sig sub-slots.
     Plain Python: sorted() on tuples and counting."""
     parent = np.asarray(parent)
     sig = np.asarray(sig)
@@ -194,14 +206,16 @@ def schedule_typed(parent, sig, n_sig: int) -> dict:
     out = schedule(parent)
     h = out["height"]
     L = out["n_levels"]
-    order = sorted(range(n), key=lambda v: (int(h[v]), int(sig[v]), v))
+    psig = parent_signatures(parent, sig)
+    order = sorted(range(n), key=lambda v: (int(h[v]), int(sig[v]), int(psig[v]), v))
     perm = np.array(order, dtype=np.int32)
     inv_perm = np.zeros(n, dtype=np.int32)
     for pos, v in enumerate(order):
         inv_perm[v] = pos
-    key = (h.astype(np.int64) * n_sig + sig).astype(np.int32)
-    slot_ptr = np.zeros(L * n_sig + 1, dtype=np.int32)
-    for q in range(L * n_sig + 1):
+    key = ((h.astype(np.int64) * n_sig + sig) * n_sig + psig).astype(np.int32)
+    S = L * n_sig * n_sig
+    slot_ptr = np.zeros(S + 1, dtype=np.int32)
+    for q in range(S + 1):
         slot_ptr[q] = int(np.count_nonzero(key < q))
     out.update(perm=perm, inv_perm=inv_perm, key=key, slot_ptr=slot_ptr, n_sig=n_sig)
     return out
@@ -217,10 +231,10 @@ def schedule_typed_fast(parent, sig, n_sig: int) -> dict:
         raise ForestError("range", "signature outside [0, n_sig)")
     h = out["height"].astype(np.int64)
     L = out["n_levels"]
-    key = h * n_sig + sig
+    key = (h * n_sig + sig) * n_sig + parent_signatures(parent, sig)
     perm = np.lexsort((np.arange(n), key)).astype(np.int32)
     inv_perm = np.empty(n, dtype=np.int32)
     inv_perm[perm] = np.arange(n, dtype=np.int32)
-    slot_ptr = np.concatenate(([0], np.cumsum(np.bincount(key, minlength=L * n_sig)))).astype(np.int32)
+    slot_ptr = np.concatenate(([0], np.cumsum(np.bincount(key, minlength=L * n_sig * n_sig)))).astype(np.int32)
     out.update(perm=perm, inv_perm=inv_perm, key=key.astype(np.int32), slot_ptr=slot_ptr, n_sig=n_sig)
     return out

@@ -5,8 +5,8 @@ import pytest
 from oracle import schedule_oracle as S
 from oracle import treelstm_oracle as T
 from oracle import treelstm_typed_oracle as TT
-from workloads import (make_forest, make_values, make_values_typed, tree_signatures, mixed_forest, tree_ranges,
-                       relabel, chain_forest)
+from workloads import (make_forest, make_values, make_values_typed, tree_signatures, node_signatures, mixed_forest,
+                       tree_ranges, relabel, chain_forest)
 
 
 def _sub_forest(parent, keep):
@@ -27,6 +27,30 @@ def test_one_signature_is_the_plain_schedule():
     assert np.array_equal(b["slot_ptr"], a["level_ptr"]) and np.array_equal(b["key"], a["height"])
 
 
+def test_sub_slots_hold_exactly_their_nodes_in_id_order_with_signatures_per_node():
+    p = make_forest(2)
+    n_sig = 3
+    sig = node_signatures(p, n_sig, 4)
+    psig = S.parent_signatures(p, sig)
+    assert (psig[p < 0] == sig[p < 0]).all() and (psig[p >= 0] == sig[p[p >= 0]]).all()
+    s = S.schedule_typed(p, sig, n_sig)
+    h = s["height"]
+    seen = 0
+    for l in range(s["n_levels"]):
+        assert s["slot_ptr"][l * n_sig * n_sig] == s["level_ptr"][l]
+        for t in range(n_sig):
+            for q in range(n_sig):
+                i = (l * n_sig + t) * n_sig + q
+                a, b = s["slot_ptr"][i], s["slot_ptr"][i + 1]
+                want = [v for v in range(p.shape[0]) if h[v] == l and sig[v] == t and psig[v] == q]   # brute force
+                assert list(s["perm"][a:b]) == want
+                seen += b - a
+    assert seen == p.shape[0]
+    f = S.schedule_typed_fast(p, sig, n_sig)
+    for k in ("perm", "inv_perm", "key", "slot_ptr", "level_ptr"):
+        assert np.array_equal(s[k], f[k]), k
+
+
 @pytest.mark.parametrize("n_sig", [2, 3])
 def test_slots_hold_exactly_their_nodes_in_id_order(n_sig):
     p = make_forest(2)
@@ -36,9 +60,9 @@ def test_slots_hold_exactly_their_nodes_in_id_order(n_sig):
     L = s["n_levels"]
     assert s["slot_ptr"][0] == 0 and s["slot_ptr"][-1] == p.shape[0]
     for l in range(L):
-        assert s["slot_ptr"][l * n_sig] == s["level_ptr"][l]
-        for t in range(n_sig):
-            a, b = s["slot_ptr"][l * n_sig + t], s["slot_ptr"][l * n_sig + t + 1]
+        assert s["slot_ptr"][l * n_sig * n_sig] == s["level_ptr"][l]
+        for t in range(n_sig):        # the cell's batch (l, t): the run of its sub-slots
+            a, b = s["slot_ptr"][(l * n_sig + t) * n_sig], s["slot_ptr"][(l * n_sig + t + 1) * n_sig]
             want = [v for v in range(p.shape[0]) if h[v] == l and sig[v] == t]     # brute force
             assert list(s["perm"][a:b]) == want
     assert np.array_equal(s["inv_perm"][s["perm"]], np.arange(p.shape[0]))

@@ -18,6 +18,7 @@ from .forests import (  # noqa: F401
     star_forest,
     perfect_kary_tree,
     tree_signatures,
+    node_signatures,
     mixed_forest,
     make_values_typed,
 )

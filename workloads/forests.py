@@ -289,3 +289,16 @@ def make_values_typed(cfg_index: int, n_nodes: int, n_sig: int, bias: str = "ran
         bs.append(rng.uniform(-0.5, 0.5, size=4 * H).astype(np.float32) if bias == "random"
                   else np.zeros(4 * H, np.float32))
     return x, np.stack(Ws), np.stack(Us), np.stack(bs)
+
+
+def node_signatures(parent: np.ndarray, n_sig: int, seed: int) -> np.ndarray:
+    """sig [N] int32 drawn per NODE: leaves get signature 0 (a "word" cell), every other node one
+    of the remaining n_sig - 1 uniformly (n_sig >= 2), so parents and children differ freely."""
+    rng = np.random.default_rng(seed)
+    n = parent.shape[0]
+    has_child = np.zeros(n, dtype=bool)
+    has_child[parent[parent >= 0]] = True
+    sig = np.zeros(n, dtype=np.int32)
+    k = int(has_child.sum())
+    sig[has_child] = 1 + rng.integers(0, n_sig - 1, size=k).astype(np.int32)
+    return sig
