@@ -115,9 +115,9 @@ def train_bench(args, J, torch, cfg, dev, N, D, H, esz, peak_tflops, xt, Wt, Ut,
 def typed_bench(args, J, torch, cfg, dev, N, D, H, esz, peak_tflops, xt, parent, n_leaf, n_int, E):
     """Several cells in one table: step = jitdb_schedule_typed + jitdb_treelstm_forward_typed, one stream.
     Every tree draws one of --signatures networks; the work per node is that of the headline step."""
-    from workloads import tree_signatures, make_values_typed, to_bf16_bits
+    from workloads import tree_signatures, node_signatures, make_values_typed, to_bf16_bits
     T = args.signatures
-    sig = tree_signatures(parent, T, 99)
+    sig = node_signatures(parent, T, 99) if args.signatures_per_node else tree_signatures(parent, T, 99)
     _, W, U, b = make_values_typed(cfg.index, 1, T, bias="zero")
     if esz == 2:
         up = lambda a: torch.from_numpy(to_bf16_bits(a).view(np.int16)).view(torch.bfloat16).to(dev)
@@ -163,14 +163,15 @@ def typed_bench(args, J, torch, cfg, dev, N, D, H, esz, peak_tflops, xt, parent,
     reps = max(3, min(args.steps, 10))
     ms_s, ms_f = timed(sch, reps), timed(fwd, reps)
     f_min = n_leaf * 2.0 * D * 3 * H + n_int * (2.0 * D * 4 * H + 2.0 * H * 3 * H) + E * 2.0 * H * H
-    S = sched.n_levels * T
+    S = sched.n_levels * T * T
     nonempty = int(np.count_nonzero(np.diff(sched.host_slot_ptr[:S + 1])))
     out = {
         "metric": f"Tree-LSTM forward nodes/sec on 1 MI355X, {T} cells in one table", "value": N / (ms_step * 1e-3),
         "unit": "nodes/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype if cfg.dtype == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": f"config {cfg.index}: {cfg.name}, each tree under one of {T} networks",
+        "config": {"workload": f"config {cfg.index}: {cfg.name}, " + (f"leaves under cell 0, every other node under one of {T - 1} cells"
+                                                                   if args.signatures_per_node else f"each tree under one of {T} networks"),
                    "n_trees": cfg.n_trees, "n_nodes": N, "n_edges": E, "n_levels": sched.n_levels, "n_sig": T,
                    "slots": S, "non_empty_slots": nonempty, "D": D, "H": H,
                    "step": "jitdb_schedule_typed + jitdb_treelstm_forward_typed, one stream"},
@@ -205,6 +206,8 @@ def main():
     ap.add_argument("--signatures", type=int, default=0,
                     help="time the typed table instead: every tree under one of this many networks "
                          "(jitdb_schedule_typed + jitdb_treelstm_forward_typed); not the headline metric")
+    ap.add_argument("--signatures-per-node", action="store_true",
+                    help="with --signatures >= 2: draw the signature per node (leaves cell 0, others 1..n-1) instead of per tree")
     ap.add_argument("--serial", action="store_true",
                     help="schedule and forward of a batch strictly one after the other on one stream "
                          "(default: the schedule of the next batch overlaps the forward of this one)")

@@ -51,7 +51,7 @@ typedef enum {
     JITDB_E_WORKSPACE = -5,    /* workspace smaller than the matching *_workspace_bytes */
     JITDB_E_HIP = -6,          /* a HIP runtime call failed */
     JITDB_E_SCHEDULE = -7,     /* forward was handed a schedule that is not complete */
-    JITDB_E_SIGNATURE = -8     /* a signature is outside [0, n_sig) or differs from its parent's */
+    JITDB_E_SIGNATURE = -8     /* a signature is outside [0, n_sig) */
 } jitdb_status;
 
 typedef enum {
@@ -61,8 +61,8 @@ typedef enum {
 
 /* Largest forest one call accepts (ids and offsets are int32 with headroom). */
 #define JITDB_MAX_NODES (1 << 28)
-/* Most signatures one table distinguishes; also N * n_sig must stay below 2^31. */
-#define JITDB_MAX_SIGNATURES 256
+/* Most signatures one table distinguishes; also N * n_sig^2 must stay below 2^31. */
+#define JITDB_MAX_SIGNATURES 64
 
 /*
  * The schedule of a forest: the paper's depth-keyed table (section 4.2),
@@ -179,18 +179,21 @@ void jitdb_cache_stats(const jitdb_cache_t *cache, int64_t *hits, int64_t *misse
 /*
  * The generic table (sections 4.2 and 4.3): the paper files every node under a key made of its
  * depth and of what must agree for two nodes to run as one batch: operator type, settings,
- * input layouts.  Here the caller folds those into one integer per node, the signature; nodes
- * are filed by (depth, signature), and one batched launch serves one slot.  A signature is
- * constant along every edge: what carries it is a sample's whole graph, i.e. a tree together
- * with the network that evaluates it (several networks, or a Tree-LSTM batch and a
- * variable-length LSTM batch written as chains, filed in one table).
+ * input layouts.  Here the caller folds those into one integer per node, the signature, and
+ * each signature names one cell (one weight set).  A node takes part in two batched operations
+ * with different partners: its own cell, shared with the nodes of its (height, signature), and
+ * the forget projection that its PARENT's cell applies to it, shared with the nodes of its
+ * (height, parent's signature).  Nodes are therefore filed by (height, sig, psig), psig being the
+ * parent's signature (a root: its own): sub-slot (l, t, p) is the batch of one projection, and
+ * slot (l, t), the batch of one cell, is the run of its n_sig sub-slots.
  *
- *   n_sig          in: number of signatures, 1 .. JITDB_MAX_SIGNATURES, N * n_sig < 2^31
- *   slot_capacity  in: entries slot_ptr and host_slot_ptr have room for; n_levels * n_sig + 1
- *                  are needed (N * n_sig + 1 always suffices), else JITDB_E_WORKSPACE
- *   key            dev [N] out: height * n_sig + sig
- *   slot_ptr       dev out: slot (l, t) = positions slot_ptr[l*n_sig + t] .. slot_ptr[l*n_sig + t + 1]
- *                  of perm; empty slots allowed; level_ptr[l] == slot_ptr[l * n_sig]
+ *   n_sig          in: number of signatures, 1 .. JITDB_MAX_SIGNATURES, N * n_sig^2 < 2^31
+ *   slot_capacity  in: entries slot_ptr and host_slot_ptr have room for; n_levels * n_sig^2 + 1
+ *                  are needed (N * n_sig^2 + 1 always suffices), else JITDB_E_WORKSPACE
+ *   key            dev [N] out: (height * n_sig + sig) * n_sig + psig
+ *   slot_ptr       dev out: sub-slot (l, t, p) = positions slot_ptr[q] .. slot_ptr[q + 1] of perm,
+ *                  q = (l * n_sig + t) * n_sig + p; empty ones allowed;
+ *                  level_ptr[l] == slot_ptr[l * n_sig^2]
  *   host_slot_ptr  host copy of slot_ptr, filled before the call returns
  */
 typedef struct jitdb_slots {
@@ -205,10 +208,11 @@ typedef struct jitdb_slots {
 size_t jitdb_schedule_typed_workspace_bytes(int64_t n_nodes, int32_t n_sig);
 
 /*
- * jitdb_schedule with the second key.  `sig` is dev [N] int32.  `s` receives what
- * jitdb_schedule returns except that positions are ordered by (height, sig, id), so every
- * level is a run of n_sig slots; `slots` receives the slot boundaries.  Errors as
- * jitdb_schedule, plus JITDB_E_SIGNATURE.  Synchronises the stream twice.
+ * jitdb_schedule with the second key.  `sig` is dev [N] int32, any value in [0, n_sig) per node.
+ * `s` receives what jitdb_schedule returns except that positions are ordered by
+ * (height, sig, psig, id), so every level is a run of n_sig slots of n_sig sub-slots each;
+ * `slots` receives the boundaries.  Errors as jitdb_schedule, plus JITDB_E_SIGNATURE.
+ * Synchronises the stream twice.
  */
 int jitdb_schedule_typed(const int32_t *parent, const int32_t *sig, jitdb_schedule_t *s,
                          jitdb_slots_t *slots, void *workspace, size_t workspace_bytes,
@@ -220,10 +224,11 @@ size_t jitdb_treelstm_typed_workspace_bytes(int64_t n_nodes, int64_t n_edges,
 
 /*
  * jitdb_treelstm_forward over a typed table: W is dev [n_sig, 4H, D], U dev [n_sig, 4H, H],
- * b dev [n_sig, 4H]; node j is evaluated by cell sig[j].  One batched evaluation per
- * non-empty slot, levels in ascending order; a slot's steps are those of a level in
- * jitdb_treelstm_forward (stack, gate GEMM + cell update, forget projection), on the slot's
- * rows and the slot's weights; the slots of a large level share one grouped launch per step.
+ * b dev [n_sig, 4H]; node j is evaluated by cell sig[j], including the forget gates it applies
+ * to its children.  One batched evaluation per non-empty slot, levels in ascending order; a
+ * slot's steps are those of a level in jitdb_treelstm_forward (stack, gate GEMM + cell update
+ * with the slot's weights; forget projection per sub-slot with the parent cell's weights); the
+ * slots of a large level share one grouped launch per step.
  * `s` and `slots` come from jitdb_schedule_typed (slot_ptr is read on the device).
  */
 int jitdb_treelstm_forward_typed(const void *x, const void *W, const void *U, const float *b,

@@ -511,13 +511,14 @@ class ScheduleCache:
 
 
 class TypedSchedule(Schedule):
-    """A Schedule whose positions are filed by (height, signature), plus the slot table."""
+    """A Schedule whose positions are filed by (height, signature, parent's signature), plus the
+    table of sub-slot boundaries (n_sig * n_sig per level)."""
 
     def __init__(self, n_nodes: int, n_sig: int, device, slot_capacity: Optional[int] = None):
         import torch
         super().__init__(n_nodes, device)
         self.n_sig = int(n_sig)
-        cap = int(n_nodes) * self.n_sig + 1 if slot_capacity is None else int(slot_capacity)
+        cap = int(n_nodes) * self.n_sig * self.n_sig + 1 if slot_capacity is None else int(slot_capacity)
         self.key = torch.empty(max(int(n_nodes), 1), dtype=torch.int32, device=device)
         self.slot_ptr = torch.empty(cap, dtype=torch.int32, device=device)
         self.host_slot_ptr = np.zeros(cap, dtype=np.int32)
@@ -526,7 +527,7 @@ class TypedSchedule(Schedule):
 
     def to_numpy(self) -> dict:
         out = super().to_numpy()
-        S = self.n_levels * self.n_sig
+        S = self.n_levels * self.n_sig * self.n_sig
         out.update(key=self.key[:self.n_nodes].cpu().numpy(), slot_ptr=self.slot_ptr[:S + 1].cpu().numpy(),
                    host_slot_ptr=self.host_slot_ptr[:S + 1].copy(), n_sig=self.n_sig)
         return out
@@ -538,7 +539,7 @@ def jitdb_schedule_typed_workspace_bytes(n_nodes: int, n_sig: int) -> int:
 
 def jitdb_schedule_typed(parent, sig, n_sig: int, stream=None, workspace=None,
                          out: Optional[TypedSchedule] = None, slot_capacity: Optional[int] = None) -> TypedSchedule:
-    """parent, sig: int32 CUDA tensors [N]; sig[v] in [0, n_sig), constant inside a tree."""
+    """parent, sig: int32 CUDA tensors [N]; sig[v] in [0, n_sig) names the cell that evaluates node v."""
     import torch
     lib = load_library()
     for t, name in ((parent, "parent"), (sig, "sig")):

@@ -13,7 +13,7 @@ extern "C" const char *jitdb_strerror(int code) {
         case JITDB_E_WORKSPACE: return "workspace is smaller than required";
         case JITDB_E_HIP: return "a HIP runtime call failed";
         case JITDB_E_SCHEDULE: return "schedule is incomplete or does not match the call";
-        case JITDB_E_SIGNATURE: return "a signature is outside [0, n_sig) or differs from its parent's";
+        case JITDB_E_SIGNATURE: return "a signature is outside [0, n_sig)";
         default: return "unknown jitdb status";
     }
 }

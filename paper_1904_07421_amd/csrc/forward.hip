@@ -1253,27 +1253,32 @@ thin_proj_stack_kernel(const LevelArgs a, const StackArgs s) {
                             (int64_t)blockIdx.x - a.n_blocks);
 }
 
-// ---- tile table of a typed level ---------------------------------------------------------
-// One block.  slot_ptr holds the n_sig + 1 boundaries of the level's slots (positions of the
-// whole forest); entry i of the table describes the i-th 128-row tile when every slot is cut
-// into tiles of its own: (first row, end row of its slot, signature), rows relative to the level.
+// ---- tile tables of a typed level --------------------------------------------------------
+// One block.  bounds[e * stride] .. bounds[(e + 1) * stride], e < n_entries, are consecutive
+// ranges of positions (the level's slots with stride = n_sig, its sub-slots with stride = 1);
+// range e uses weight set e % n_sig when stride == 1 (a sub-slot is named by the parent's
+// signature last), else e.  Entry i of the table describes the i-th 128-row tile when every
+// range is cut into tiles of its own: (first row, end row of its range, weight set), rows
+// relative to the level.
+constexpr int kMaxTableEntries = JITDB_MAX_SIGNATURES * JITDB_MAX_SIGNATURES;
 __global__ void __launch_bounds__(kThreads)
-tile_table_kernel(const int32_t *__restrict__ slot_ptr, int n_sig, int4 *__restrict__ tiles) {
-    __shared__ int s_first[JITDB_MAX_SIGNATURES + 1];
+tile_table_kernel(const int32_t *__restrict__ bounds, int n_entries, int stride, int n_sig, int4 *__restrict__ tiles) {
+    __shared__ int s_first[kMaxTableEntries + 1];
     if (threadIdx.x == 0) {
         int run = 0;
-        for (int t = 0; t < n_sig; ++t) {
-            s_first[t] = run;
-            run += (slot_ptr[t + 1] - slot_ptr[t] + kDmaBM - 1) / kDmaBM;
+        for (int e = 0; e < n_entries; ++e) {
+            s_first[e] = run;
+            run += (bounds[(e + 1) * stride] - bounds[e * stride] + kDmaBM - 1) / kDmaBM;
         }
-        s_first[n_sig] = run;
+        s_first[n_entries] = run;
     }
     __syncthreads();
-    const int base = slot_ptr[0];
-    for (int t = 0; t < n_sig; ++t) {
-        const int lo = slot_ptr[t] - base, hi = slot_ptr[t + 1] - base;
-        for (int j = threadIdx.x; j < s_first[t + 1] - s_first[t]; j += kThreads)
-            tiles[s_first[t] + j] = make_int4(lo + j * kDmaBM, hi, t, 0);
+    const int base = bounds[0];
+    for (int e = 0; e < n_entries; ++e) {
+        const int lo = bounds[e * stride] - base, hi = bounds[(e + 1) * stride] - base;
+        const int wset = stride == 1 ? e % n_sig : e;
+        for (int j = threadIdx.x; j < s_first[e + 1] - s_first[e]; j += kThreads)
+            tiles[s_first[e] + j] = make_int4(lo + j * kDmaBM, hi, wset, 0);
     }
 }
 
@@ -1313,7 +1318,8 @@ struct ForwardWs {
     void *hs;     // nullptr when h_out can serve (H == Hp)
     void *P;
     float *cs;    // nullptr when c_out can serve (H == Hq)
-    int4 *tiles;  // tile table of one typed level (nullptr with one cell)
+    int4 *tiles;  // tile tables of one typed level: cell batches, then projection batches (nullptr with one cell)
+    int64_t tiles_each;
     size_t bytes;
 };
 
@@ -1354,7 +1360,8 @@ ForwardWs carve_forward_ws(int64_t n, int64_t e, const Dims &d, void *base, int 
     w.hs = (d.H == d.Hp) ? nullptr : c.take<char>((size_t)n * d.Hp * d.esz);
     w.P = c.take<char>((size_t)n * d.Hq * d.esz);
     w.cs = (d.H == d.Hq) ? nullptr : c.take<float>((size_t)n * d.Hq);
-    w.tiles = n_sig > 1 ? c.take<int4>((size_t)(n / kDmaBM + n_sig + 1)) : nullptr;
+    w.tiles_each = n / kDmaBM + (int64_t)n_sig * n_sig + 1;
+    w.tiles = n_sig > 1 ? c.take<int4>((size_t)(2 * w.tiles_each)) : nullptr;
     w.bytes = c.off;
     return w;
 }
@@ -1411,27 +1418,35 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
     a.D = d.D; a.Dp = d.Dp; a.H = d.H; a.Hp = d.Hp; a.Hu = d.Hu;
     a.NPU = d.NPU;
 
+    // The table's ranges: slot (l, t) = the cell's batch = sub-slots (l, t, 0 .. n_sig-1); the
+    // projection of sub-slot (l, t, p) uses the forget weights of cell p, the parent's.
+    const int T2 = n_sig * n_sig;
+    auto slot_begin = [&](int l, int t) { return sp[(l * n_sig + t) * (slots ? n_sig : 1)]; };
+    auto sub_begin = [&](int l, int t, int p) { return sp[(l * n_sig + t) * n_sig + p]; };
     // The launches in order: one per non-empty slot, except that a level of a typed table that
     // is large enough for the tiled kernel runs all its slots in one grouped launch (sig = -1;
-    // n_tiles = 128-row tiles when every slot is cut into tiles of its own).
-    struct Seg { int l, sig, begin, rows, n_tiles; };
+    // n_tiles / n_proj_tiles = 128-row tiles when every slot / sub-slot is cut into tiles of its own).
+    struct Seg { int l, sig, begin, rows, n_tiles, n_proj_tiles; };
     std::vector<Seg> segs;
     segs.reserve((size_t)L * n_sig);
     for (int l = 0; l < L; ++l) {
-        const int lvl_rows = sp[(l + 1) * n_sig] - sp[l * n_sig];
-        int n_tiles = 0, used = 0;
+        const int lvl_rows = slot_begin(l + 1, 0) - slot_begin(l, 0);
+        int n_tiles = 0, n_proj_tiles = 0, used = 0;
         for (int t = 0; t < n_sig; ++t) {
-            const int r = sp[l * n_sig + t + 1] - sp[l * n_sig + t];
+            const int r = slot_begin(l, t + 1) - slot_begin(l, t);
             if (r < 0 || (r == 0 && !slots)) return JITDB_E_SCHEDULE;
             n_tiles += (int)ceil_div(r, kDmaBM);
             used += r > 0;
+            if (slots)
+                for (int p = 0; p < n_sig; ++p)
+                    n_proj_tiles += (int)ceil_div(sub_begin(l, t, p + 1) - sub_begin(l, t, p), kDmaBM);
         }
         if (used > 1 && lvl_rows > kThinMaxRows) {
-            segs.push_back({l, -1, sp[l * n_sig], lvl_rows, n_tiles});
+            segs.push_back({l, -1, slot_begin(l, 0), lvl_rows, n_tiles, n_proj_tiles});
         } else {
             for (int t = 0; t < n_sig; ++t) {
-                const int r = sp[l * n_sig + t + 1] - sp[l * n_sig + t];
-                if (r > 0) segs.push_back({l, t, sp[l * n_sig + t], r, 0});
+                const int r = slot_begin(l, t + 1) - slot_begin(l, t);
+                if (r > 0) segs.push_back({l, t, slot_begin(l, t), r, 0, 0});
             }
         }
     }
@@ -1448,6 +1463,9 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
         return (unsigned)ceil_div((int64_t)g.rows * (Kp / Traits<T>::VEC), kThreads);
     };
     bool stacked_ahead = false;     // the slot's stack step already ran with the projection before it
+    const int n_unit_tiles = d.Hu / kUnit;
+    a.w_bytes = (int64_t)packed_w_bytes(d);
+    a.NP = d.NP;
 
     for (size_t i = 0; i < segs.size(); ++i) {
         const int l = segs[i].l, sig = segs[i].sig, n_rows = segs[i].rows;
@@ -1459,12 +1477,13 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
         a.n_rows_alloc = (int)round_up(n_rows, kRowPad);
         a.tiles = nullptr;
         const int row_tiles = grouped ? segs[i].n_tiles : (int)ceil_div(n_rows, kDmaBM);
-        if (grouped) {
-            a.tiles = w.tiles;
-            a.w_bytes = (int64_t)packed_w_bytes(d);
-            a.NP = d.NP;
-            tile_table_kernel<<<1, kThreads, 0, st>>>(slots->slot_ptr + (int64_t)l * n_sig, n_sig, w.tiles);
+        if (grouped) {      // both tile tables of the level: cell batches, projection batches
+            const int32_t *lvl = slots->slot_ptr + (int64_t)l * T2;
+            tile_table_kernel<<<1, kThreads, 0, st>>>(lvl, n_sig, n_sig, n_sig, w.tiles);
             JITDB_LAUNCH_CHECK();
+            tile_table_kernel<<<1, kThreads, 0, st>>>(lvl, T2, 1, n_sig, w.tiles + w.tiles_each);
+            JITDB_LAUNCH_CHECK();
+            a.tiles = w.tiles;
         }
         if (!stacked_ahead) {
             const StackArgs sa = stack_args(segs[i]);
@@ -1482,7 +1501,6 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
         stacked_ahead = false;
         // Levels too small to give every CU a 256 x 256 tile go to the thin kernel.
         const bool thin = n_rows <= kThinMaxRows;
-        const int n_unit_tiles = d.Hu / kUnit;
         if (thin) {
             a.n_col_tiles = n_unit_tiles;
             a.n_tiles = (int)ceil_div(n_rows, 32) * a.n_col_tiles;
@@ -1514,15 +1532,43 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
             }
         }
         JITDB_LAUNCH_CHECK();
-        if (l + 1 < L) {   // these nodes have parents (except roots, whose rows go unused)
-            ScopedLaunchTimer tm(thin ? JITDB_K_THIN_PROJ : JITDB_K_PROJ, n_rows, st);
-            if (thin) {
+        if (l + 1 >= L) continue;     // the top level has no parents to project for
+
+        // Forget projections of these nodes (roots' rows go unused), with the PARENT's weights.
+        if (grouped) {
+            ScopedLaunchTimer tm(JITDB_K_PROJ, n_rows, st);
+            a.Bp = w.Bp; a.bp = w.bp;
+            a.tiles = w.tiles + w.tiles_each;
+            a.n_col_tiles = (int)ceil_div(n_unit_tiles, 8);
+            a.n_row_tiles = segs[i].n_proj_tiles;
+            a.n_blocks = 8 * (int)ceil_div(a.n_row_tiles, 8) * a.n_col_tiles;
+            level_kernel<T, MODE_PROJ, false, true><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
+            JITDB_LAUNCH_CHECK();
+            continue;
+        }
+        // one launch per non-empty sub-slot (a single one without a typed table)
+        const int n_sub = slots ? n_sig : 1;
+        int last_sub = -1;
+        for (int p = 0; p < n_sub; ++p)
+            if (!slots || sub_begin(l, sig, p + 1) > sub_begin(l, sig, p)) last_sub = p;
+        for (int p = 0; p < n_sub; ++p) {
+            const int begin = slots ? sub_begin(l, sig, p) : segs[i].begin;
+            const int rows = slots ? sub_begin(l, sig, p + 1) - begin : n_rows;
+            if (rows <= 0) continue;
+            a.Bp = static_cast<char *>(w.Bp) + packed_w_bytes(d) * p;
+            a.bp = w.bp + (size_t)d.NP * p;
+            a.row_rec = w.row_rec + 2 * (int64_t)begin;
+            a.n_rows = rows;
+            const bool thin_p = rows <= kThinMaxRows;
+            ScopedLaunchTimer tm(thin_p ? JITDB_K_THIN_PROJ : JITDB_K_PROJ, rows, st);
+            if (thin_p) {
                 a.n_col_tiles = (int)ceil_div(n_unit_tiles, 4);
-                a.n_tiles = (int)ceil_div(n_rows, 32) * a.n_col_tiles;
+                a.n_tiles = (int)ceil_div(rows, 32) * a.n_col_tiles;
                 a.n_blocks = a.n_tiles;
-                // the stack step of the next slot rides along (the level kernel above was the
-                // stack buffer's only reader); its rows are counted with this launch's class
-                if (i + 1 < segs.size() && segs[i + 1].l > 0) {
+                // the stack step of the next slot rides along with the slot's last projection (the
+                // level kernel above was the stack buffer's only reader); its rows are counted with
+                // this launch's class
+                if (p == last_sub && i + 1 < segs.size() && segs[i + 1].l > 0) {
                     thin_proj_stack_kernel<T><<<a.n_blocks + stack_blocks(segs[i + 1]), kThinWaves * 64, 0, st>>>(
                         a, stack_args(segs[i + 1]));
                     stacked_ahead = true;
@@ -1531,15 +1577,12 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
                 }
             } else {
                 a.n_col_tiles = (int)ceil_div(n_unit_tiles, 8);
-                a.n_row_tiles = row_tiles;
-                a.n_blocks = 8 * (int)ceil_div(row_tiles, 8) * a.n_col_tiles;
-                if (grouped)
-                    level_kernel<T, MODE_PROJ, false, true><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
-                else
-                    level_kernel<T, MODE_PROJ><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
+                a.n_row_tiles = (int)ceil_div(rows, kDmaBM);
+                a.n_blocks = 8 * (int)ceil_div(a.n_row_tiles, 8) * a.n_col_tiles;
+                level_kernel<T, MODE_PROJ><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
             }
+            JITDB_LAUNCH_CHECK();
         }
-        JITDB_LAUNCH_CHECK();
     }
     return JITDB_OK;
 }
@@ -1662,11 +1705,12 @@ int forward_entry(const void *x, const void *W, const void *U, const float *b, i
         if (s->host_level_ptr[l + 1] <= s->host_level_ptr[l]) return JITDB_E_SCHEDULE;
     if (slots) {
         if (!slots->key || !slots->slot_ptr || !slots->host_slot_ptr) return JITDB_E_NULL;
-        if (slots->slot_capacity < (int64_t)L * n_sig + 1) return JITDB_E_SCHEDULE;
-        for (int q = 0; q < L * n_sig; ++q)
+        const int64_t T2 = (int64_t)n_sig * n_sig;
+        if (slots->slot_capacity < L * T2 + 1) return JITDB_E_SCHEDULE;
+        for (int64_t q = 0; q < L * T2; ++q)
             if (slots->host_slot_ptr[q + 1] < slots->host_slot_ptr[q]) return JITDB_E_SCHEDULE;
         for (int l = 0; l <= L; ++l)
-            if (slots->host_slot_ptr[(int64_t)l * n_sig] != s->host_level_ptr[l]) return JITDB_E_SCHEDULE;
+            if (slots->host_slot_ptr[l * T2] != s->host_level_ptr[l]) return JITDB_E_SCHEDULE;
     }
 
     const Dims d = make_dims(D, H, dtype);

@@ -168,36 +168,40 @@ count_children_kernel(const int32_t *__restrict__ parent, int32_t n, int32_t *__
 }
 
 // ---- signatures (the generic batcher's second key) ----------------------------------
-// A signature must lie in [0, n_sig) and be the same along every edge: the unit that carries
-// a signature is a sample's whole graph (a tree and the network that evaluates it).
+// A signature must lie in [0, n_sig).
 __global__ void __launch_bounds__(kThreads)
-check_signatures_kernel(const int32_t *__restrict__ parent, const int32_t *__restrict__ sig, int32_t n,
-                        int32_t n_sig, int32_t *__restrict__ meta) {
+check_signatures_kernel(const int32_t *__restrict__ sig, int32_t n, int32_t n_sig, int32_t *__restrict__ meta) {
     const int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     bool bad = false;
     if (v < n) {
-        const int32_t t = sig[v], p = parent[v];
+        const int32_t t = sig[v];
         bad = t < 0 || t >= n_sig;
-        if (!bad && p >= 0 && p < n && p != (int32_t)v) bad = sig[p] != t;
     }
     const unsigned long long bads = __ballot(bad);
     if (bads && (threadIdx.x & (kWave - 1)) == 0) atomicOr(&meta[META_SIG], 1);   // rare
 }
 
-// key = height * n_sig + sig: sorting by it files the nodes by (depth, signature)
+// key = (height * n_sig + sig) * n_sig + psig, psig = the parent's signature (a root: its own).
+// A node meets two sets of partners: its own cell batches it with its (height, sig), the forget
+// projection of its parent's cell with its (height, psig); sorting by this key keeps both
+// contiguous (the first as a run of n_sig sub-slots).  Runs after the parent array and the
+// signatures have been validated.
 __global__ void __launch_bounds__(kThreads)
-slot_key_kernel(const int32_t *__restrict__ height, const int32_t *__restrict__ sig, int32_t n, int32_t n_sig,
-                int32_t *__restrict__ key) {
+slot_key_kernel(const int32_t *__restrict__ parent, const int32_t *__restrict__ height,
+                const int32_t *__restrict__ sig, int32_t n, int32_t n_sig, int32_t *__restrict__ key) {
     const int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (v < n) key[v] = height[v] * n_sig + sig[v];
+    if (v >= n) return;
+    const int32_t p = parent[v];
+    const int32_t t = sig[v];
+    key[v] = (height[v] * n_sig + t) * n_sig + (p >= 0 ? sig[p] : t);
 }
 
-// level_ptr[l] = slot_ptr[l * n_sig], l = 0 .. n_levels
+// level_ptr[l] = slot_ptr[l * stride], l = 0 .. n_levels
 __global__ void __launch_bounds__(kThreads)
-level_from_slots_kernel(const int32_t *__restrict__ slot_ptr, int32_t n_levels, int32_t n_sig,
+level_from_slots_kernel(const int32_t *__restrict__ slot_ptr, int32_t n_levels, int32_t stride,
                         int32_t *__restrict__ level_ptr) {
     const int64_t l = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (l <= n_levels) level_ptr[l] = slot_ptr[l * n_sig];
+    if (l <= n_levels) level_ptr[l] = slot_ptr[l * stride];
 }
 
 // Round k of pointer jumping.  anc_in[v] is the 2^k-th ancestor of v (or -1).
@@ -424,12 +428,12 @@ struct ScheduleWs {
     size_t bytes;
 };
 
-ScheduleWs carve_schedule_ws(int64_t n, void *base, int64_t n_sig = 1) {
+ScheduleWs carve_schedule_ws(int64_t n, void *base, int64_t n_keys = 1) {   // n_keys: sort keys per level
     Carver c(base);
     ScheduleWs w;
     const int64_t n_blocks = ceil_div(n > 0 ? n : 1, kBlockTile);
     const int64_t hist_len = (int64_t)kRadix * n_blocks;
-    const int64_t scan_len = (hist_len > n * n_sig + 1 ? hist_len : n * n_sig + 1);   // longest array ever scanned
+    const int64_t scan_len = (hist_len > n * n_keys + 1 ? hist_len : n * n_keys + 1);   // longest array ever scanned
     w.meta = c.take<int32_t>(META_WORDS);
     w.cnt = c.take<int32_t>(n + 1);
     w.anc[0] = c.take<int32_t>(n);
@@ -528,9 +532,10 @@ int schedule_impl(const int32_t *parent, const int32_t *sig, jitdb_slots_t *slot
     if (!s) return JITDB_E_NULL;
     drop_stale_hip_error();
     const int32_t n_sig = slots ? slots->n_sig : 1;
+    const int64_t n_keys = (int64_t)n_sig * n_sig;      // sub-slots per level
     if (slots) {
         if (n_sig < 1 || n_sig > JITDB_MAX_SIGNATURES) return JITDB_E_BADARG;
-        if (s->n_nodes * (int64_t)n_sig >= (int64_t(1) << 31)) return JITDB_E_BADARG;
+        if (s->n_nodes * n_keys >= (int64_t(1) << 31)) return JITDB_E_BADARG;
         if (!slots->host_slot_ptr) return JITDB_E_NULL;
         if (slots->slot_capacity < 1) return JITDB_E_BADARG;
         slots->host_slot_ptr[0] = 0;
@@ -561,7 +566,7 @@ int schedule_impl(const int32_t *parent, const int32_t *sig, jitdb_slots_t *slot
         return JITDB_E_NULL;
     if (slots && (!sig || !slots->key || !slots->slot_ptr)) return JITDB_E_NULL;
     if ((reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return JITDB_E_BADARG;
-    ScheduleWs w = carve_schedule_ws(n64, workspace, n_sig);
+    ScheduleWs w = carve_schedule_ws(n64, workspace, n_keys);
     if (workspace_bytes < w.bytes) return JITDB_E_WORKSPACE;
 
     hipStream_t st = (hipStream_t)hip_stream;
@@ -575,7 +580,7 @@ int schedule_impl(const int32_t *parent, const int32_t *sig, jitdb_slots_t *slot
     count_children_kernel<<<grid, kThreads, 0, st>>>(parent, n, w.cnt, w.anc[0], s->height, w.meta);
     JITDB_LAUNCH_CHECK();
     if (slots) {
-        check_signatures_kernel<<<grid, kThreads, 0, st>>>(parent, sig, n, n_sig, w.meta);
+        check_signatures_kernel<<<grid, kThreads, 0, st>>>(sig, n, n_sig, w.meta);
         JITDB_LAUNCH_CHECK();
     }
 
@@ -610,13 +615,13 @@ int schedule_impl(const int32_t *parent, const int32_t *sig, jitdb_slots_t *slot
     s->n_edges = meta[META_EDGES];
 
     // 4. the table's slot boundaries = exclusive scan of the key histogram; key = height (one
-    //    slot per level) or height * n_sig + sig
-    const int64_t S = (int64_t)L * n_sig;             // slots, empty ones included
+    //    slot per level) or (height * n_sig + sig) * n_sig + psig
+    const int64_t S = (int64_t)L * n_keys;            // (sub-)slots, empty ones included
     const int32_t *key = s->height;
     int32_t *bounds = s->level_ptr;
     if (slots) {
         if (S + 1 > slots->slot_capacity) return JITDB_E_WORKSPACE;
-        slot_key_kernel<<<grid, kThreads, 0, st>>>(s->height, sig, n, n_sig, slots->key);
+        slot_key_kernel<<<grid, kThreads, 0, st>>>(parent, s->height, sig, n, n_sig, slots->key);
         JITDB_LAUNCH_CHECK();
         key = slots->key;
         bounds = slots->slot_ptr;
@@ -631,7 +636,7 @@ int schedule_impl(const int32_t *parent, const int32_t *sig, jitdb_slots_t *slot
         return rc;
     if (slots) {
         level_from_slots_kernel<<<(unsigned)ceil_div((int64_t)L + 1, kThreads), kThreads, 0, st>>>(
-            slots->slot_ptr, L, n_sig, s->level_ptr);
+            slots->slot_ptr, L, (int32_t)n_keys, s->level_ptr);
         JITDB_LAUNCH_CHECK();
     }
 
@@ -648,7 +653,7 @@ int schedule_impl(const int32_t *parent, const int32_t *sig, jitdb_slots_t *slot
         JITDB_HIP_CHECK(hipMemcpyAsync(slots->host_slot_ptr, slots->slot_ptr, sizeof(int32_t) * ((size_t)S + 1),
                                        hipMemcpyDeviceToHost, st));
         JITDB_HIP_CHECK(hipStreamSynchronize(st));
-        for (int l = 0; l <= L; ++l) s->host_level_ptr[l] = slots->host_slot_ptr[(int64_t)l * n_sig];
+        for (int l = 0; l <= L; ++l) s->host_level_ptr[l] = slots->host_slot_ptr[(int64_t)l * n_keys];
     } else {
         JITDB_HIP_CHECK(hipMemcpyAsync(s->host_level_ptr, s->level_ptr, sizeof(int32_t) * ((size_t)L + 1),
                                        hipMemcpyDeviceToHost, st));
@@ -666,8 +671,8 @@ extern "C" int jitdb_schedule(const int32_t *parent, jitdb_schedule_t *s,
 
 extern "C" size_t jitdb_schedule_typed_workspace_bytes(int64_t n_nodes, int32_t n_sig) {
     if (n_nodes < 0 || n_nodes > JITDB_MAX_NODES || n_sig < 1 || n_sig > JITDB_MAX_SIGNATURES) return 0;
-    if (n_nodes * (int64_t)n_sig >= (int64_t(1) << 31)) return 0;
-    return carve_schedule_ws(n_nodes, nullptr, n_sig).bytes;
+    if (n_nodes * (int64_t)n_sig * n_sig >= (int64_t(1) << 31)) return 0;
+    return carve_schedule_ws(n_nodes, nullptr, (int64_t)n_sig * n_sig).bytes;
 }
 
 extern "C" int jitdb_schedule_typed(const int32_t *parent, const int32_t *sig, jitdb_schedule_t *s,
