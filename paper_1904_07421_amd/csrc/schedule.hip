@@ -213,16 +213,15 @@ __global__ void __launch_bounds__(kThreads)
 jump_kernel(const int32_t *__restrict__ anc_in, int32_t *__restrict__ anc_out,
             int32_t *height, int32_t n, int k, int32_t *meta) {
     if (k > 0 && meta[META_LIVE + k - 1] == 0) return;  // uniform: nothing moved last round
-    const int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     bool live = false;
-    if (v < n) {
+    for (int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x; v < n; v += (int64_t)gridDim.x * kThreads) {
         const int32_t a = anc_in[v];
         int32_t next = -1;
         if (a >= 0) {
             const int32_t hv = __atomic_load_n(&height[v], __ATOMIC_RELAXED);
             atomicMax(&height[a], hv + (1 << k));
             next = anc_in[a];
-            live = next >= 0;
+            live |= next >= 0;
         }
         anc_out[v] = next;
     }
@@ -592,8 +591,11 @@ int schedule_impl(const int32_t *parent, const int32_t *sig, jitdb_slots_t *slot
     //    ancestors; in a forest they are all -1 once 2^rounds >= N.
     int rounds = 0;
     while ((int64_t(1) << rounds) < n64) ++rounds;
+    // (a capped grid with a stride loop: the rounds after the last live one are launched all the
+    //  same and should cost a few thousand blocks' worth of "return", not a block per 256 nodes)
+    const unsigned jump_grid = grid < 4096 ? grid : 4096;
     for (int k = 0; k < rounds; ++k) {
-        jump_kernel<<<grid, kThreads, 0, st>>>(w.anc[k & 1], w.anc[(k + 1) & 1], s->height, n, k, w.meta);
+        jump_kernel<<<jump_grid, kThreads, 0, st>>>(w.anc[k & 1], w.anc[(k + 1) & 1], s->height, n, k, w.meta);
         JITDB_LAUNCH_CHECK();
     }
     {
