@@ -324,7 +324,9 @@ int jitdb_treelstm_backward(const void *x, const void *W, const void *U,
  * roofline (the paper reports only wall-clock samples/s, section 5; the
  * kernels here are this implementation's own).  Between jitdb_profile_start
  * and jitdb_profile_stop every kernel launch of jitdb_treelstm_forward is
- * bracketed by a pair of HIP events recorded on the call's stream.
+ * bracketed by a pair of HIP events recorded on the call's stream.  The event records keep
+ * consecutive kernels from overlapping, so a recorded call runs a few per cent slower (much
+ * slower for forests of many thin levels): time throughput without recording.
  *
  *   jitdb_profile_start(capacity)  creates `capacity` event pairs (host objects)
  *                                  and switches recording on; launches beyond the
@@ -343,7 +345,7 @@ typedef enum {
     JITDB_K_PROJ = 4,       /* P_k = U_f h_k (tiled kernel) */
     JITDB_K_THIN_LEAF = 5,      /* the same three jobs done by the kernel for small levels */
     JITDB_K_THIN_INTERNAL = 6,
-    JITDB_K_THIN_PROJ = 7,
+    JITDB_K_THIN_PROJ = 7,      /* includes the next slot's stack step when the two share a launch */
     JITDB_K_CLASSES = 8
 } jitdb_kernel_class;
 
