@@ -1565,10 +1565,10 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
                 a.n_col_tiles = (int)ceil_div(n_unit_tiles, 4);
                 a.n_tiles = (int)ceil_div(rows, 32) * a.n_col_tiles;
                 a.n_blocks = a.n_tiles;
-                // the stack step of the next slot rides along with the slot's last projection (the
-                // level kernel above was the stack buffer's only reader); its rows are counted with
-                // this launch's class
-                if (p == last_sub && i + 1 < segs.size() && segs[i + 1].l > 0) {
+                // the stack step of the next slot, if that is thin too, rides along with the slot's
+                // last projection (the level kernel above was the stack buffer's only reader); its
+                // rows are counted with this launch's class
+                if (p == last_sub && i + 1 < segs.size() && segs[i + 1].l > 0 && segs[i + 1].rows <= kThinMaxRows) {
                     thin_proj_stack_kernel<T><<<a.n_blocks + stack_blocks(segs[i + 1]), kThinWaves * 64, 0, st>>>(
                         a, stack_args(segs[i + 1]));
                     stacked_ahead = true;
