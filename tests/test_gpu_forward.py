@@ -149,6 +149,22 @@ def test_leaves_only_and_single_node(c_oracle):
         assert np.abs(h - ho).max() <= 1e-4 and np.abs(c - co).max() <= 1e-4
 
 
+@pytest.mark.parametrize("name,n_stars,size,dtype", [("three-wide", 3, 5000, "f32"), ("many-tiled", 9000, 41, "f32"),
+                                                    ("many-tiled", 9000, 41, "bf16")])
+def test_stars_with_long_child_lists(c_oracle, name, n_stars, size, dtype):
+    """Child lists far beyond the four ids a row record carries, on the thin kernel (three roots with
+    4999 children each) and on the tiled kernel (9000 roots with 40 children: a level of more than 8192
+    rows).  The cell state of a root grows with its arity, and so does the bound on its error."""
+    parent = star_forest(size, n_stars)
+    x, W, U, b = make_values(2, parent.shape[0], "random", D=64, H=96)
+    print(f"forward stars {name} {n_stars} x {size} {dtype}", flush=True)
+    _, h, c, seen = run_gpu_forward(parent, x, W, U, b, dtype)
+    ho, co = _oracle(c_oracle, parent, seen)
+    eh, ec = _report(f"stars/{name}/{dtype}", h, c, ho, co)
+    assert np.isfinite(h).all() and np.isfinite(c).all()
+    assert eh <= TOL[dtype] and ec <= TOL[dtype] * max(1.0, float(np.abs(co).max()) / 8.0)
+
+
 def test_deep_chain_fp32(c_oracle):
     parent = chain_forest(128, 3)
     x, W, U, b = make_values(4, parent.shape[0], "random", D=300, H=256)
