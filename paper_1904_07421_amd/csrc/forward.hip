@@ -101,15 +101,21 @@ template <typename T> __device__ __forceinline__ float tanh_t(float z) {
 // Packed row r = tile*128 + gate*32 + uu holds gate `gate` of hidden unit tile*32 + uu as
 // [ W row (D values, zero padded to Dp) | U row (H values, zero padded to Hp) ].  There are
 // NPU >= NP rows; rows of units >= H are zero.
+struct PackArgs {
+    const void *W, *U; const float *b;
+    int D, H, Dp, Hp, NP, NPU;
+    void *Bp; float *bp;
+};
+
+// block `block` of `n_blocks` (kThreads threads each, stride loop)
 template <typename T>
-__global__ void __launch_bounds__(kThreads)
-pack_weights_kernel(const T *__restrict__ W, const T *__restrict__ U, const float *__restrict__ b,
-                    int D, int H, int Dp, int Hp, int NP, int NPU,
-                    T *__restrict__ Bp, float *__restrict__ bp) {
+__device__ __forceinline__ void pack_weights_body(const T *__restrict__ W, const T *__restrict__ U,
+                                                  const float *__restrict__ b, int D, int H, int Dp, int Hp,
+                                                  int NP, int NPU, T *__restrict__ Bp, float *__restrict__ bp,
+                                                  int64_t block, int64_t n_blocks) {
     const int Kp = Dp + Hp;
     const int64_t total = (int64_t)NPU * Kp;
-    for (int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x; idx < total;
-         idx += (int64_t)gridDim.x * kThreads) {
+    for (int64_t idx = block * kThreads + threadIdx.x; idx < total; idx += n_blocks * kThreads) {
         const int r = (int)(idx / Kp), k = (int)(idx % Kp);
         const int tile = r / kGateTile, gate = (r % kGateTile) / kUnit, uu = r % kUnit;
         const int unit = tile * kUnit + uu;
@@ -124,6 +130,13 @@ pack_weights_kernel(const T *__restrict__ W, const T *__restrict__ U, const floa
                                operand_offset(r, (int64_t)k * sizeof(T), NPU)) = v;
         if (k == 0 && r < NP) bp[r] = row_ok ? b[src] : 0.0f;
     }
+}
+
+template <typename T>
+__global__ void __launch_bounds__(kThreads)
+pack_weights_kernel(const PackArgs p) {
+    pack_weights_body<T>(static_cast<const T *>(p.W), static_cast<const T *>(p.U), p.b, p.D, p.H, p.Dp, p.Hp, p.NP,
+                         p.NPU, static_cast<T *>(p.Bp), p.bp, blockIdx.x, gridDim.x);
 }
 
 // ---- row records -------------------------------------------------------------------
@@ -142,14 +155,15 @@ pack_weights_kernel(const T *__restrict__ W, const T *__restrict__ U, const floa
 constexpr int kRecWindow = 4096;
 constexpr int kRecPerThread = kRecWindow / kThreads;
 
-__global__ void __launch_bounds__(kThreads)
-row_record_kernel(const int32_t *__restrict__ perm, const int32_t *__restrict__ height,
-                  const int32_t *__restrict__ child_ptr, const int32_t *__restrict__ child_idx,
-                  int4 *__restrict__ row_rec, int n) {
+// window `window` of the records (kThreads threads)
+__device__ __forceinline__ void row_record_body(const int32_t *__restrict__ perm, const int32_t *__restrict__ height,
+                                                const int32_t *__restrict__ child_ptr,
+                                                const int32_t *__restrict__ child_idx,
+                                                int4 *__restrict__ row_rec, int n, int window) {
     __shared__ int s_count[256];   // per key: count, then the next free slot
     __shared__ int s_scan[256];
     const int t = threadIdx.x;
-    const int w0 = blockIdx.x * kRecWindow;
+    const int w0 = window * kRecWindow;
     const int wn = (n - w0) < kRecWindow ? (n - w0) : kRecWindow;
     const int lvl0 = height[perm[w0]];
     const int lvl1 = height[perm[w0 + wn - 1]];
@@ -194,6 +208,22 @@ row_record_kernel(const int32_t *__restrict__ perm, const int32_t *__restrict__ 
         row_rec[2 * q] = make_int4(node[i], ar[i], cb[i], 0);
         row_rec[2 * q + 1] = make_int4(kid[0], kid[1], kid[2], kid[3]);
     }
+}
+
+// Once per forward, in one launch: the row records of every level position (blocks
+// [0, n_windows)) and the first cell's packed weights (the remaining blocks); neither needs
+// the other.
+template <typename T>
+__global__ void __launch_bounds__(kThreads)
+prepare_kernel(const int32_t *__restrict__ perm, const int32_t *__restrict__ key,
+               const int32_t *__restrict__ child_ptr, const int32_t *__restrict__ child_idx,
+               int4 *__restrict__ row_rec, int n, int n_windows, const PackArgs p) {
+    if ((int)blockIdx.x < n_windows)
+        row_record_body(perm, key, child_ptr, child_idx, row_rec, n, blockIdx.x);
+    else
+        pack_weights_body<T>(static_cast<const T *>(p.W), static_cast<const T *>(p.U), p.b, p.D, p.H, p.Dp, p.Hp,
+                             p.NP, p.NPU, static_cast<T *>(p.Bp), p.bp, (int64_t)blockIdx.x - n_windows,
+                             (int64_t)gridDim.x - n_windows);
 }
 
 // ---- stack -------------------------------------------------------------------------
@@ -1386,22 +1416,32 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
     const int n_sig = slots ? slots->n_sig : 1;
     const int32_t *sp = slots ? slots->host_slot_ptr : s->host_level_ptr;
 
-    for (int t = 0; t < n_sig; ++t) {
+    {   // row records and packed weights (one launch; further cells' weights one launch each)
         const int64_t total = (int64_t)d.NPU * (d.Dp + d.Hp);
-        const unsigned grid = (unsigned)(ceil_div(total, kThreads) < 4096 ? ceil_div(total, kThreads) : 4096);
-        ScopedLaunchTimer tm(JITDB_K_PACK, 0, st);
-        pack_weights_kernel<T><<<grid, kThreads, 0, st>>>(
-            static_cast<const T *>(W) + (size_t)t * 4 * d.H * d.D, static_cast<const T *>(U) + (size_t)t * 4 * d.H * d.H,
-            b + (size_t)t * 4 * d.H, d.D, d.H, d.Dp, d.Hp, d.NP, d.NPU,
-            reinterpret_cast<T *>(static_cast<char *>(w.Bp) + packed_w_bytes(d) * t), w.bp + (size_t)d.NP * t);
-        JITDB_LAUNCH_CHECK();
-    }
-
-    {
-        ScopedLaunchTimer tm(JITDB_K_PACK, 0, st);
-        row_record_kernel<<<(unsigned)ceil_div(s->n_nodes, kRecWindow), kThreads, 0, st>>>(
-            s->perm, slots ? slots->key : s->height, s->child_ptr, s->child_idx, w.row_rec, (int)s->n_nodes);
-        JITDB_LAUNCH_CHECK();
+        const unsigned pack_grid = (unsigned)(ceil_div(total, kThreads) < 4096 ? ceil_div(total, kThreads) : 4096);
+        auto pack_args = [&](int t) {
+            PackArgs p;
+            p.W = static_cast<const T *>(W) + (size_t)t * 4 * d.H * d.D;
+            p.U = static_cast<const T *>(U) + (size_t)t * 4 * d.H * d.H;
+            p.b = b + (size_t)t * 4 * d.H;
+            p.D = d.D; p.H = d.H; p.Dp = d.Dp; p.Hp = d.Hp; p.NP = d.NP; p.NPU = d.NPU;
+            p.Bp = static_cast<char *>(w.Bp) + packed_w_bytes(d) * t;
+            p.bp = w.bp + (size_t)d.NP * t;
+            return p;
+        };
+        const int n_windows = (int)ceil_div(s->n_nodes, kRecWindow);
+        {
+            ScopedLaunchTimer tm(JITDB_K_PACK, 0, st);
+            prepare_kernel<T><<<(unsigned)n_windows + pack_grid, kThreads, 0, st>>>(
+                s->perm, slots ? slots->key : s->height, s->child_ptr, s->child_idx, w.row_rec, (int)s->n_nodes,
+                n_windows, pack_args(0));
+            JITDB_LAUNCH_CHECK();
+        }
+        for (int t = 1; t < n_sig; ++t) {
+            ScopedLaunchTimer tm(JITDB_K_PACK, 0, st);
+            pack_weights_kernel<T><<<pack_grid, kThreads, 0, st>>>(pack_args(t));
+            JITDB_LAUNCH_CHECK();
+        }
     }
 
     LevelArgs a;
