@@ -11,13 +11,14 @@
 //   bwd_cell_kernel      dh_j = gh_j + dhs_p + ufg_j, dc_j = gc_j + dc_p f_j + ..., then dz_i, dz_o,
 //                        dz_u, sum_k dz_f,k from them and the saved gates; each child's dz_f,k -> G
 //   [dx_j | dhs_j] = dZ_j [W | U]                    GEMM over the level's rows
-//   [dW | db | dU_iou] += dZ^T [x | 1 | hs]          GEMM, reduction over the level's rows
+//   [dW | db | dU_iou]^T += [x | 1 | hs]^T dZ        GEMM, reduction over the level's rows
 //
 // All four GEMMs run on the forward's tiled MFMA core (launch_kb_gemm: both operands
-// K-blocked).  A reduction over rows needs operands whose K axis is the level's rows: the two
-// elementwise kernels write their results a second time, transposed through LDS, and x, h
-// and hs are transposed by transpose_kb_kernel.  Gradients are fp32; with JITDB_BF16 the GEMM
-// operands (dz, x, h, hs, weights) are bfloat16, sums fp32.
+// K-blocked).  A reduction over rows needs operands whose K axis is the level's rows: the cell
+// kernel writes dZ a second time, transposed through LDS; G, x and h are transposed by
+// transpose_kb_kernel, the child sums hs are formed inside hsum_transpose_kernel.  Gradients
+// are fp32; with JITDB_BF16 the GEMM operands (dz, x, h, hs, weights) and the values handed
+// from level to level through dhs and ufg are bfloat16, every sum and dc fp32.
 
 #include "common.h"
 
