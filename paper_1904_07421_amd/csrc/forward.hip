@@ -16,7 +16,13 @@
 //                      child exactly once)
 //   thin_kernel        the same three jobs for levels too small to fill the chip with
 //                      128 x 256 tiles: one 32 x 32-unit tile per wave, operands straight
-//                      from L2
+//                      from L2; a thin level's projection and the next level's stack
+//                      step share one launch (thin_proj_stack_kernel)
+//
+// With a typed table (jitdb_treelstm_forward_typed) a slot is (level, signature): each
+// signature has its own packed weights, the projection of a sub-slot uses the parent
+// cell's, and the slots of a large level run in one grouped launch through a tile table.
+// gemm_kb_kernel is the same GEMM core as a plain C = A B^T for the backward pass.
 //
 // "Stack" is the row gather through perm (level-major order) done by
 // stack_kernel, "slice" is the scatter of rows back to node-id order in the

@@ -15,6 +15,10 @@
 //   perm / inv_perm       stable LSD radix sort of node ids by height
 //   child_idx             stable LSD radix sort of node ids by parent
 //
+// jitdb_schedule_typed files by (height, signature, parent's signature) instead: the sort key
+// and the histogram take that triple, everything else is the same code.  jitdb_schedule_append
+// schedules arriving trees alone and merges the two tables in one linear pass.
+//
 // Stability of the radix passes is what gives the ascending-id order inside a
 // level and inside a child list, so the result is unique and bit-reproducible.
 // All atomics are integer add / max / or (order independent).
