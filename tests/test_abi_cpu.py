@@ -33,8 +33,8 @@ def test_every_declared_symbol_is_exported(lib):
 def test_strerror_and_version(lib):
     import paper_1904_07421_amd as J
     assert J.jitdb_strerror(0) == "ok"
-    seen = {J.jitdb_strerror(c) for c in range(-7, 1)}
-    assert len(seen) == 8
+    seen = {J.jitdb_strerror(c) for c in range(-8, 1)}
+    assert len(seen) == 9
     assert "unknown" in J.jitdb_strerror(-99)
     assert re.fullmatch(r"\d+\.\d+", J.jitdb_version())
 
@@ -52,6 +52,18 @@ def test_workspace_queries(lib):
     assert J.jitdb_treelstm_workspace_bytes(100, 90, 300, 0, J.JITDB_F32) == 0
     assert J.jitdb_treelstm_workspace_bytes(100, 90, 300, 150, 7) == 0
     assert J.jitdb_treelstm_workspace_bytes(-1, 0, 300, 150, 0) == 0
+    # typed table: more weight sets and the tile tables; signature count and N * n_sig^2 are bounded
+    one = J.jitdb_treelstm_workspace_bytes(1000, 900, 300, 150, J.JITDB_BF16)
+    assert J.jitdb_treelstm_typed_workspace_bytes(1000, 900, 300, 150, J.JITDB_BF16, 1) == one
+    assert J.jitdb_treelstm_typed_workspace_bytes(1000, 900, 300, 150, J.JITDB_BF16, 3) > one
+    assert J.jitdb_treelstm_typed_workspace_bytes(1000, 900, 300, 150, J.JITDB_BF16, 0) == 0
+    assert J.jitdb_treelstm_typed_workspace_bytes(1000, 900, 300, 150, J.JITDB_BF16, 65) == 0
+    assert J.jitdb_schedule_typed_workspace_bytes(1000, 1) == J.jitdb_schedule_workspace_bytes(1000)
+    assert J.jitdb_schedule_typed_workspace_bytes(1000, 4) >= J.jitdb_schedule_workspace_bytes(1000)
+    assert J.jitdb_schedule_typed_workspace_bytes(1 << 28, 3) == 0          # 2^28 * 9 does not fit int32 keys
+    assert J.jitdb_schedule_typed_workspace_bytes(1000, 0) == 0
+    assert J.jitdb_schedule_append_workspace_bytes(1000, 10) > 0
+    assert J.jitdb_schedule_append_workspace_bytes(-1, 10) == 0
 
 
 def test_argument_errors_before_any_gpu_work(lib):
