@@ -86,6 +86,18 @@ def test_config3_in_fp32_too(c_oracle):
     _sampled_tree_check(c_oracle, 3, 300, dtype="f32", bias="random")
 
 
+@pytest.mark.timeout(600)
+def test_config5_in_fp32_too(c_oracle):
+    """The fp32 MFMA path on the largest forest (million-row levels, H = 512), with a bias."""
+    _sampled_tree_check(c_oracle, 5, 48, dtype="f32", bias="random")
+
+
+@pytest.mark.timeout(400)
+def test_config4_in_bf16_too(c_oracle):
+    """The bf16 path on the deep / wide shapes (128 levels, 64-child stars)."""
+    _sampled_tree_check(c_oracle, 4, 240, dtype="bf16", bias="random", scale_tol=True)
+
+
 def test_relabelled_ids_give_the_same_states(c_oracle):
     cfgo, p, x, W, U, b = make_workload(2, bias="random")
     q, new_of_old = relabel(p, 21)
