@@ -437,7 +437,7 @@ def main():
             kernels["stack"]["frac_of_measured_copy"] = kernels["stack"]["gbs"] / measured["copy_gbs"]
 
     out = {
-        "metric": "Tree-LSTM forward nodes/sec on 1 MI355X",
+        "metric": "Tree-LSTM forward nodes/sec on 1 MI355X; MFMA util % + HBM GB/s vs peak",
         "value": value, "unit": "nodes/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype if cfg.dtype == "bf16" else "f32", "data": "synthetic",
@@ -450,6 +450,12 @@ def main():
         "ms_per_step_with_kernel_events": ms_with_events,
         "forward_only_nodes_per_s": N / (ms_fwd * 1e-3),
         "roofline": roof, "kernels": kernels, "measured_peaks": measured,
+        # the metric's other two figures: useful flops of all MFMA kernels / their summed time, as % of the bf16
+        # (fp32) MFMA peak; algorithmic bytes of the gather ("stack") kernels / their time, and as % of 8 TB/s
+        "mfma_util_pct": None if roof is None else 100.0 * roof["all_mfma_kernels_frac"],
+        "hbm_gbs_gather": kernels.get("stack", {}).get("gbs"),
+        "hbm_pct_gather": None if "stack" not in kernels or "gbs" not in kernels["stack"]
+        else 100.0 * kernels["stack"]["frac_hbm_peak"],
     }
 
     if not args.no_cpu_baseline:
