@@ -1299,21 +1299,34 @@ thin_proj_stack_kernel(const LevelArgs a, const StackArgs s) {
 constexpr int kMaxTableEntries = JITDB_MAX_SIGNATURES * JITDB_MAX_SIGNATURES;
 __global__ void __launch_bounds__(kThreads)
 tile_table_kernel(const int32_t *__restrict__ bounds, int n_entries, int stride, int n_sig, int4 *__restrict__ tiles) {
-    __shared__ int s_first[kMaxTableEntries + 1];
+    __shared__ int s_first[kMaxTableEntries + 1];      // tiles before entry e
+    __shared__ int s_part[kThreads];
+    // tiles per entry, then an exclusive scan: every thread owns a contiguous run of entries
+    const int per = (n_entries + kThreads - 1) / kThreads;
+    const int e0 = threadIdx.x * per, e1 = min(e0 + per, n_entries);
+    int sum = 0;
+    for (int e = e0; e < e1; ++e) {
+        const int c = (bounds[(e + 1) * stride] - bounds[e * stride] + kDmaBM - 1) / kDmaBM;
+        s_first[e] = sum;
+        sum += c;
+    }
+    s_part[threadIdx.x] = sum;
+    __syncthreads();
     if (threadIdx.x == 0) {
         int run = 0;
-        for (int e = 0; e < n_entries; ++e) {
-            s_first[e] = run;
-            run += (bounds[(e + 1) * stride] - bounds[e * stride] + kDmaBM - 1) / kDmaBM;
-        }
+        for (int t = 0; t < kThreads; ++t) { const int v = s_part[t]; s_part[t] = run; run += v; }
         s_first[n_entries] = run;
     }
     __syncthreads();
+    for (int e = e0; e < e1; ++e) s_first[e] += s_part[threadIdx.x];
+    __syncthreads();
     const int base = bounds[0];
     for (int e = 0; e < n_entries; ++e) {
+        const int n_t = s_first[e + 1] - s_first[e];
+        if (n_t == 0) continue;
         const int lo = bounds[e * stride] - base, hi = bounds[(e + 1) * stride] - base;
         const int wset = stride == 1 ? e % n_sig : e;
-        for (int j = threadIdx.x; j < s_first[e + 1] - s_first[e]; j += kThreads)
+        for (int j = threadIdx.x; j < n_t; j += kThreads)
             tiles[s_first[e] + j] = make_int4(lo + j * kDmaBM, hi, wset, 0);
     }
 }

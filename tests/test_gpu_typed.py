@@ -31,7 +31,7 @@ def _sched(p, sig, n_sig, **kw):
     return J.jitdb_schedule_typed(dev_parent(p), dev_parent(sig), n_sig, **kw)
 
 
-@pytest.mark.parametrize("cfg,n_sig", [(1, 2), (2, 2), (2, 3), (3, 2), (4, 4), (5, 2)])
+@pytest.mark.parametrize("cfg,n_sig", [(1, 2), (2, 2), (2, 3), (3, 2), (3, 16), (4, 4), (5, 2)])
 def test_typed_schedule_bit_exact(cfg, n_sig):
     p = make_forest(cfg)
     sig = tree_signatures(p, n_sig, 10 + cfg)
@@ -197,7 +197,7 @@ def test_typed_forward_trees_and_sequences_in_one_table(c_oracle, dtype):
 
 
 @pytest.mark.timeout(400)
-@pytest.mark.parametrize("cfg,n_sig", [(4, 3), (5, 2)])
+@pytest.mark.parametrize("cfg,n_sig", [(3, 16), (4, 3), (5, 2)])
 def test_typed_forward_full_size_sampled_trees(c_oracle, cfg, n_sig):
     from workloads import CONFIGS
     dtype = CONFIGS[cfg].dtype
