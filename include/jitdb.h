@@ -277,6 +277,28 @@ int jitdb_treelstm_forward(const void *x, const void *W, const void *U, const fl
                            void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Weights packed once for many calls.  jitdb_treelstm_forward re-packs W, U, b into the GEMM's
+ * operand layout in every call (two short launches; one more per further signature); a serving
+ * loop whose weights do not change packs them once and hands the result to
+ * jitdb_treelstm_forward_packed, which is jitdb_treelstm_forward (slots == NULL, one cell) or
+ * jitdb_treelstm_forward_typed (slots from jitdb_schedule_typed) without that step.
+ *
+ *   W, U, b   as in jitdb_treelstm_forward_typed: [n_sig, 4H, D], [n_sig, 4H, H], [n_sig, 4H]
+ *   packed    dev, 256-byte aligned, jitdb_treelstm_packed_bytes(D, H, dtype, n_sig) bytes; the
+ *             layout is private to the library and depends on (D, H, dtype, n_sig)
+ * Workspace of the forward call: jitdb_treelstm_typed_workspace_bytes(..., n_sig).  Results
+ * equal those of the unpacked calls bit for bit.
+ */
+size_t jitdb_treelstm_packed_bytes(int32_t D, int32_t H, jitdb_dtype dtype, int32_t n_sig);
+int jitdb_treelstm_pack(const void *W, const void *U, const float *b, int32_t D, int32_t H,
+                        jitdb_dtype dtype, int32_t n_sig, void *packed, size_t packed_bytes,
+                        void *hip_stream);
+int jitdb_treelstm_forward_packed(const void *x, const void *packed, int32_t D, int32_t H,
+                                  jitdb_dtype dtype, const jitdb_schedule_t *s,
+                                  const jitdb_slots_t *slots, void *h_out, float *c_out,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Execution step for training (the paper runs its backward pass through the same batched
  * graph, section 5): jitdb_treelstm_forward plus the activations a backward pass needs.
  *

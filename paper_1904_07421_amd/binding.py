@@ -137,6 +137,17 @@ def load_library():
         ctypes.c_int32, ctypes.c_int32, ctypes.c_int,
         ctypes.POINTER(_ScheduleStruct), ctypes.POINTER(_SlotsStruct), ctypes.c_void_p, ctypes.c_void_p,
         ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.jitdb_treelstm_packed_bytes.restype = ctypes.c_size_t
+    lib.jitdb_treelstm_packed_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int, ctypes.c_int32]
+    lib.jitdb_treelstm_pack.restype = ctypes.c_int
+    lib.jitdb_treelstm_pack.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
+                                        ctypes.c_int32, ctypes.c_int, ctypes.c_int32, ctypes.c_void_p,
+                                        ctypes.c_size_t, ctypes.c_void_p]
+    lib.jitdb_treelstm_forward_packed.restype = ctypes.c_int
+    lib.jitdb_treelstm_forward_packed.argtypes = [
+        ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int,
+        ctypes.POINTER(_ScheduleStruct), ctypes.POINTER(_SlotsStruct), ctypes.c_void_p, ctypes.c_void_p,
+        ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     lib.jitdb_forest_fingerprint.restype = ctypes.c_int
     lib.jitdb_forest_fingerprint.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
                                              ctypes.POINTER(ctypes.c_uint64), ctypes.c_void_p]
@@ -604,6 +615,68 @@ def jitdb_treelstm_forward_typed(x, W, U, b, schedule: TypedSchedule, stream=Non
         code = lib.jitdb_treelstm_forward_typed(
             x.data_ptr() if n else None, W.data_ptr(), U.data_ptr(), b.data_ptr(), D, H, dt,
             ctypes.byref(schedule.struct), ctypes.byref(schedule.slots),
+            h.data_ptr() if n else None, c.data_ptr() if n else None,
+            workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
+    _check(code)
+    return h, c
+
+
+class PackedWeights:
+    """W, U, b of one or several cells in the library's operand layout (jitdb_treelstm_pack)."""
+
+    def __init__(self, buffer, D: int, H: int, dtype: int, n_sig: int, torch_dtype):
+        self.buffer, self.D, self.H, self.dtype, self.n_sig, self.torch_dtype = buffer, D, H, dtype, n_sig, torch_dtype
+
+
+def jitdb_treelstm_pack(W, U, b, stream=None) -> PackedWeights:
+    """W [4H, D] (or [n_sig, 4H, D]), U, b likewise: pack once, reuse in jitdb_treelstm_forward_packed."""
+    import torch
+    lib = load_library()
+    if W.dim() == 2:
+        W, U, b = W[None], U[None], b[None]
+    for t, name in ((W, "W"), (U, "U"), (b, "b")):
+        if not t.is_cuda or not t.is_contiguous():
+            raise TypeError(f"{name} must be a contiguous CUDA tensor")
+    if W.dtype not in (torch.float32, torch.bfloat16) or U.dtype != W.dtype or b.dtype != torch.float32:
+        raise TypeError("W, U float32 or bfloat16 alike, b float32")
+    dt = JITDB_F32 if W.dtype == torch.float32 else JITDB_BF16
+    T, H, D = U.shape[0], U.shape[2], W.shape[2]
+    if W.shape != (T, 4 * H, D) or U.shape != (T, 4 * H, H) or b.shape != (T, 4 * H):
+        raise ValueError("shape mismatch between W, U, b")
+    need = int(lib.jitdb_treelstm_packed_bytes(D, H, dt, T))
+    buf = torch.empty(max(need, 256), dtype=torch.uint8, device=W.device)
+    with torch.cuda.device(W.device):
+        _check(lib.jitdb_treelstm_pack(W.data_ptr(), U.data_ptr(), b.data_ptr(), D, H, dt, T, buf.data_ptr(),
+                                       buf.numel(), _stream_ptr(stream)))
+    return PackedWeights(buf, D, H, dt, T, W.dtype)
+
+
+def jitdb_treelstm_forward_packed(x, packed: PackedWeights, schedule: Schedule, stream=None, workspace=None,
+                                  out: Optional[Tuple] = None):
+    """jitdb_treelstm_forward / _typed with weights packed beforehand.  A TypedSchedule selects the
+    typed path (its n_sig must match the packed weights'); a plain Schedule needs one packed cell."""
+    import torch
+    lib = load_library()
+    typed = isinstance(schedule, TypedSchedule)
+    if (schedule.n_sig if typed else 1) != packed.n_sig:
+        raise ValueError("the schedule and the packed weights differ in the number of signatures")
+    if x.dtype != packed.torch_dtype or not x.is_cuda or not x.is_contiguous():
+        raise TypeError("x must be a contiguous CUDA tensor of the packed weights' dtype")
+    n, D, H = schedule.n_nodes, packed.D, packed.H
+    if x.shape != (n, D):
+        raise ValueError("x must be [N, D]")
+    if out is None:
+        h = torch.empty((n, H), dtype=x.dtype, device=x.device)
+        c = torch.empty((n, H), dtype=torch.float32, device=x.device)
+    else:
+        h, c = out
+    need = jitdb_treelstm_typed_workspace_bytes(n, schedule.n_edges, D, H, packed.dtype, packed.n_sig)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    with torch.cuda.device(x.device):
+        code = lib.jitdb_treelstm_forward_packed(
+            x.data_ptr() if n else None, packed.buffer.data_ptr(), D, H, packed.dtype,
+            ctypes.byref(schedule.struct), ctypes.byref(schedule.slots) if typed else None,
             h.data_ptr() if n else None, c.data_ptr() if n else None,
             workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
     _check(code)

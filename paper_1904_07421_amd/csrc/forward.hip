@@ -1430,7 +1430,14 @@ template <typename T, bool SAVE>
 int run_forward(const void *x, const void *W, const void *U, const float *b, const Dims &d,
                 const jitdb_schedule_t *s, const jitdb_slots_t *slots,
                 void *h_out, float *c_out, void *gates, void *fgate,
-                const ForwardWs &w, hipStream_t st) {
+                const ForwardWs &w_in, const void *packed, hipStream_t st) {
+    // weights packed by an earlier jitdb_treelstm_pack are used where they lie
+    ForwardWs w = w_in;
+    const int n_sig_w = slots ? slots->n_sig : 1;
+    if (packed) {
+        w.Bp = const_cast<void *>(packed);
+        w.bp = reinterpret_cast<float *>(static_cast<char *>(w.Bp) + round_up(packed_w_bytes(d) * n_sig_w, 256));
+    }
     const int L = s->n_levels;
     const int n_sig = slots ? slots->n_sig : 1;
     const int32_t *sp = slots ? slots->host_slot_ptr : s->host_level_ptr;
@@ -1451,12 +1458,12 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
         const int n_windows = (int)ceil_div(s->n_nodes, kRecWindow);
         {
             ScopedLaunchTimer tm(JITDB_K_PACK, 0, st);
-            prepare_kernel<T><<<(unsigned)n_windows + pack_grid, kThreads, 0, st>>>(
+            prepare_kernel<T><<<(unsigned)n_windows + (packed ? 0u : pack_grid), kThreads, 0, st>>>(
                 s->perm, slots ? slots->key : s->height, s->child_ptr, s->child_idx, w.row_rec, (int)s->n_nodes,
                 n_windows, pack_args(0));
             JITDB_LAUNCH_CHECK();
         }
-        for (int t = 1; t < n_sig; ++t) {
+        for (int t = 1; t < n_sig && !packed; ++t) {
             ScopedLaunchTimer tm(JITDB_K_PACK, 0, st);
             pack_weights_kernel<T><<<pack_grid, kThreads, 0, st>>>(pack_args(t));
             JITDB_LAUNCH_CHECK();
@@ -1741,7 +1748,7 @@ namespace {
 int forward_entry(const void *x, const void *W, const void *U, const float *b, int32_t D, int32_t H,
                   jitdb_dtype dtype, const jitdb_schedule_t *s, const jitdb_slots_t *slots,
                   void *h_out, float *c_out, void *gates, void *fgate, bool save,
-                  void *workspace, size_t workspace_bytes, void *hip_stream) {
+                  void *workspace, size_t workspace_bytes, void *hip_stream, const void *packed = nullptr) {
     if (!s) return JITDB_E_NULL;
     const int n_sig = slots ? slots->n_sig : 1;
     if (n_sig < 1 || n_sig > JITDB_MAX_SIGNATURES) return JITDB_E_BADARG;
@@ -1749,7 +1756,9 @@ int forward_entry(const void *x, const void *W, const void *U, const float *b, i
     const int64_t n = s->n_nodes;
     if (!dims_ok(n, s->n_edges, D, H, (int)dtype)) return JITDB_E_BADARG;
     if (n == 0) return JITDB_OK;
-    if (!x || !W || !U || !b || !h_out || !c_out || !workspace) return JITDB_E_NULL;
+    if (!x || !h_out || !c_out || !workspace) return JITDB_E_NULL;
+    if (!packed && (!W || !U || !b)) return JITDB_E_NULL;
+    if (packed && (reinterpret_cast<uintptr_t>(packed) & 255) != 0) return JITDB_E_BADARG;
     if (save && (!gates || !fgate)) return JITDB_E_NULL;
     if (!s->perm || !s->height || !s->child_ptr || !s->child_idx || !s->host_level_ptr) return JITDB_E_NULL;
     if ((reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return JITDB_E_BADARG;
@@ -1777,13 +1786,60 @@ int forward_entry(const void *x, const void *W, const void *U, const float *b, i
     if (workspace_bytes < w.bytes) return JITDB_E_WORKSPACE;
     hipStream_t st = (hipStream_t)hip_stream;
     if (dtype == JITDB_F32) {
-        if (save) return run_forward<float, true>(x, W, U, b, d, s, slots, h_out, c_out, gates, fgate, w, st);
-        return run_forward<float, false>(x, W, U, b, d, s, slots, h_out, c_out, nullptr, nullptr, w, st);
+        if (save) return run_forward<float, true>(x, W, U, b, d, s, slots, h_out, c_out, gates, fgate, w, packed, st);
+        return run_forward<float, false>(x, W, U, b, d, s, slots, h_out, c_out, nullptr, nullptr, w, packed, st);
     }
-    if (save) return run_forward<bf16_t, true>(x, W, U, b, d, s, slots, h_out, c_out, gates, fgate, w, st);
-    return run_forward<bf16_t, false>(x, W, U, b, d, s, slots, h_out, c_out, nullptr, nullptr, w, st);
+    if (save) return run_forward<bf16_t, true>(x, W, U, b, d, s, slots, h_out, c_out, gates, fgate, w, packed, st);
+    return run_forward<bf16_t, false>(x, W, U, b, d, s, slots, h_out, c_out, nullptr, nullptr, w, packed, st);
+}
+
+size_t packed_total_bytes(const Dims &d, int n_sig) {
+    return (size_t)round_up(packed_w_bytes(d) * n_sig, 256) + (size_t)round_up((int64_t)d.NP * n_sig * 4, 256);
 }
 }  // namespace
+
+extern "C" size_t jitdb_treelstm_packed_bytes(int32_t D, int32_t H, jitdb_dtype dtype, int32_t n_sig) {
+    if (!dims_ok(0, 0, D, H, (int)dtype) || n_sig < 1 || n_sig > JITDB_MAX_SIGNATURES) return 0;
+    return packed_total_bytes(make_dims(D, H, dtype), n_sig);
+}
+
+extern "C" int jitdb_treelstm_pack(const void *W, const void *U, const float *b, int32_t D, int32_t H,
+                                   jitdb_dtype dtype, int32_t n_sig, void *packed, size_t packed_bytes,
+                                   void *hip_stream) {
+    if (!W || !U || !b || !packed) return JITDB_E_NULL;
+    if (!dims_ok(0, 0, D, H, (int)dtype) || n_sig < 1 || n_sig > JITDB_MAX_SIGNATURES) return JITDB_E_BADARG;
+    if ((reinterpret_cast<uintptr_t>(packed) & 255) != 0) return JITDB_E_BADARG;
+    drop_stale_hip_error();
+    const Dims d = make_dims(D, H, dtype);
+    if (packed_bytes < packed_total_bytes(d, n_sig)) return JITDB_E_WORKSPACE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int64_t total = (int64_t)d.NPU * (d.Dp + d.Hp);
+    const unsigned grid = (unsigned)(ceil_div(total, kThreads) < 4096 ? ceil_div(total, kThreads) : 4096);
+    float *bp0 = reinterpret_cast<float *>(static_cast<char *>(packed) + round_up(packed_w_bytes(d) * n_sig, 256));
+    for (int t = 0; t < n_sig; ++t) {
+        PackArgs p;
+        const size_t esz = d.esz;
+        p.W = static_cast<const char *>(W) + (size_t)t * 4 * d.H * d.D * esz;
+        p.U = static_cast<const char *>(U) + (size_t)t * 4 * d.H * d.H * esz;
+        p.b = b + (size_t)t * 4 * d.H;
+        p.D = d.D; p.H = d.H; p.Dp = d.Dp; p.Hp = d.Hp; p.NP = d.NP; p.NPU = d.NPU;
+        p.Bp = static_cast<char *>(packed) + packed_w_bytes(d) * t;
+        p.bp = bp0 + (size_t)d.NP * t;
+        if (dtype == JITDB_F32) pack_weights_kernel<float><<<grid, kThreads, 0, st>>>(p);
+        else pack_weights_kernel<bf16_t><<<grid, kThreads, 0, st>>>(p);
+        JITDB_LAUNCH_CHECK();
+    }
+    return JITDB_OK;
+}
+
+extern "C" int jitdb_treelstm_forward_packed(const void *x, const void *packed, int32_t D, int32_t H,
+                                             jitdb_dtype dtype, const jitdb_schedule_t *s,
+                                             const jitdb_slots_t *slots, void *h_out, float *c_out,
+                                             void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (!packed) return JITDB_E_NULL;
+    return forward_entry(x, nullptr, nullptr, nullptr, D, H, dtype, s, slots, h_out, c_out, nullptr, nullptr, false,
+                         workspace, workspace_bytes, hip_stream, packed);
+}
 
 extern "C" int jitdb_treelstm_forward(const void *x, const void *W, const void *U, const float *b,
                                       int32_t D, int32_t H, jitdb_dtype dtype,

@@ -299,3 +299,23 @@ def test_largest_forest_the_interface_accepts():
     assert np.abs(h4[0].float().cpu().numpy() - ho[:, 0]).max() <= TOL["bf16"]
     assert np.abs(c4[0].cpu().numpy() - co[:, 0]).max() <= TOL["bf16"]
     assert bool((h4 == h4[0]).all()) and bool((c4 == c4[0]).all())
+
+
+@pytest.mark.parametrize("cfg", [2, 3])
+def test_packed_weights_give_the_same_forward(cfg):
+    """Weights packed once, forward called twice with them: bit-identical to the call that packs."""
+    import torch
+    import paper_1904_07421_amd as J
+    from gpu_util import bf16_tensor, dev_parent
+    cfgo, p, x, W, U, b = make_workload(cfg, bias="random")
+    dev = (lambda a: bf16_tensor(a)[0]) if cfgo.dtype == "bf16" else (lambda a: torch.from_numpy(a).cuda())
+    xt, Wt, Ut, bt = dev(x), dev(W), dev(U), torch.from_numpy(b).cuda()
+    s = J.jitdb_schedule(dev_parent(p))
+    h0, c0 = J.jitdb_treelstm_forward(xt, Wt, Ut, bt, s)
+    pk = J.jitdb_treelstm_pack(Wt, Ut, bt)
+    for _ in range(2):
+        h1, c1 = J.jitdb_treelstm_forward_packed(xt, pk, s)
+        assert torch.equal(h0, h1) and torch.equal(c0, c1)
+    with pytest.raises(ValueError):
+        J.jitdb_treelstm_forward_packed(xt, J.jitdb_treelstm_pack(torch.stack([Wt, Wt]), torch.stack([Ut, Ut]),
+                                                                  torch.stack([bt, bt])), s)

@@ -243,3 +243,18 @@ def test_typed_forward_rejects_mismatched_tables():
     with pytest.raises(J.JitdbError) as e:
         J.jitdb_treelstm_forward_typed(dev(x), dev(W), dev(U), dev(b), s)
     assert e.value.code == -7
+
+
+def test_packed_weights_on_a_typed_table():
+    import torch
+    import paper_1904_07421_amd as J
+    p = make_forest(3)
+    sig = node_signatures(p, 3, 8)
+    x, W, U, b = make_values_typed(3, p.shape[0], 3)
+    s = _sched(p, sig, 3)
+    xt, Wt, Ut = bf16_tensor(x)[0], bf16_tensor(W)[0], bf16_tensor(U)[0]
+    bt = torch.from_numpy(b).cuda()
+    h0, c0 = J.jitdb_treelstm_forward_typed(xt, Wt, Ut, bt, s)
+    pk = J.jitdb_treelstm_pack(Wt, Ut, bt)
+    h1, c1 = J.jitdb_treelstm_forward_packed(xt, pk, s)
+    assert torch.equal(h0, h1) and torch.equal(c0, c1)
