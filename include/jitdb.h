@@ -15,6 +15,7 @@
  * Around them: jitdb_schedule_append (trees that arrive later join a table), jitdb_forest_fingerprint
  * and jitdb_cache_* (a cache of tables keyed by the parent array), jitdb_schedule_typed and
  * jitdb_treelstm_forward_typed (the table keyed by depth and signature, one cell per signature),
+ * jitdb_treelstm_pack and jitdb_treelstm_forward_packed (weights packed once for many calls),
  * jitdb_treelstm_forward_train and jitdb_treelstm_backward (the training step).
  *
  * Conventions
