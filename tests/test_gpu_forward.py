@@ -319,3 +319,39 @@ def test_packed_weights_give_the_same_forward(cfg):
     with pytest.raises(ValueError):
         J.jitdb_treelstm_forward_packed(xt, J.jitdb_treelstm_pack(torch.stack([Wt, Wt]), torch.stack([Ut, Ut]),
                                                                   torch.stack([bt, bt])), s)
+
+
+def test_variable_length_sequences_against_the_library_lstm():
+    """A batch of sequences of different lengths, written as chains, through the HIP path and through
+    torch.nn.LSTM on the CPU (fp64, each sequence on its own): the "variable-length LSTM batch" workload,
+    checked against the library directly rather than through the oracle."""
+    import torch
+    rng = np.random.default_rng(12)
+    D, H = 48, 64
+    lens = rng.integers(1, 60, size=200)
+    W = (rng.uniform(-1, 1, (4 * H, D)) / np.sqrt(D)).astype(np.float32)
+    U = (rng.uniform(-1, 1, (4 * H, H)) / np.sqrt(H)).astype(np.float32)
+    b = rng.uniform(-0.5, 0.5, 4 * H).astype(np.float32)
+    parts, off = [], 0
+    for n in lens:                                         # chain: node i's parent is i - 1, the last node is the leaf
+        parts.append(np.where(np.arange(n) == 0, -1, np.arange(n) - 1 + off)); off += n
+    parent = np.concatenate(parts).astype(np.int32)
+    x = rng.standard_normal((parent.shape[0], D)).astype(np.float32)
+    _, h, c, _ = run_gpu_forward(parent, x, W, U, b, "f32")
+
+    def torch_rows(M):                                     # our gate order (i, o, u, f) -> torch's (i, f, g, o)
+        i, o, u, f = (M[g * H:(g + 1) * H] for g in range(4))
+        return torch.from_numpy(np.concatenate([i, f, u, o]).astype(np.float64))
+    lstm = torch.nn.LSTM(D, H).double()
+    with torch.no_grad():
+        lstm.weight_ih_l0.copy_(torch_rows(W)); lstm.weight_hh_l0.copy_(torch_rows(U))
+        lstm.bias_ih_l0.copy_(torch_rows(b.reshape(-1, 1)).reshape(-1)); lstm.bias_hh_l0.zero_()
+        off, worst = 0, 0.0
+        for n in lens:
+            seq = torch.from_numpy(x[off:off + n][::-1].astype(np.float64).copy()).unsqueeze(1)   # leaf first
+            out, (hn, cn) = lstm(seq)
+            worst = max(worst, float(np.abs(out[:, 0, :].numpy()[::-1] - h[off:off + n]).max()),
+                        float(np.abs(cn[0, 0].numpy() - c[off]).max()))
+            off += n
+    print(f"sequences vs torch.nn.LSTM: max error {worst:.3e}", flush=True)
+    assert worst <= 1e-4
