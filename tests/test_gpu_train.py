@@ -165,3 +165,54 @@ def test_backward_without_cotangents_and_on_an_empty_forest():
                                                     torch.ones(600, 150, device="cuda"), torch.ones(600, device="cuda")))
     torch.cuda.synchronize()
     assert not dW.any() and not dU.any() and not db.any()
+
+
+def test_backward_on_sequences_against_the_library_lstm_autograd():
+    """Chains through the HIP training step, the same sequences through torch.nn.LSTM and its own
+    autograd on the CPU (fp64): gradients of L = sum <gh_t, h_t> compared directly, no oracle between."""
+    rng = np.random.default_rng(21)
+    D, H = 24, 32
+    lens = rng.integers(1, 40, size=60)
+    W = (rng.uniform(-1, 1, (4 * H, D)) / np.sqrt(D)).astype(np.float32)
+    U = (rng.uniform(-1, 1, (4 * H, H)) / np.sqrt(H)).astype(np.float32)
+    b = rng.uniform(-0.5, 0.5, 4 * H).astype(np.float32)
+    parts, off = [], 0
+    for n in lens:
+        parts.append(np.where(np.arange(n) == 0, -1, np.arange(n) - 1 + off)); off += n
+    parent = np.concatenate(parts).astype(np.int32)
+    N = parent.shape[0]
+    x = rng.standard_normal((N, D)).astype(np.float32)
+    gh = rng.standard_normal((N, H)).astype(np.float32)
+    dev = [torch.from_numpy(a).cuda() for a in (x, W, U, b)]
+    s = J.jitdb_schedule(torch.from_numpy(parent).cuda())
+    h, c, gates, fgate = J.jitdb_treelstm_forward_train(*dev, s)
+    dx, dW, dU, db = J.jitdb_treelstm_backward(dev[0], dev[1], dev[2], s, h, c, gates, fgate,
+                                               torch.from_numpy(gh).cuda(), None)
+    torch.cuda.synchronize()
+
+    def torch_rows(M):            # our gate order (i, o, u, f) -> torch's (i, f, g, o)
+        i, o, u, f = (M[g * H:(g + 1) * H] for g in range(4))
+        return torch.from_numpy(np.concatenate([i, f, u, o]).astype(np.float64))
+
+    def our_rows(M):              # and back, for the gradients
+        i, f, g, o = (M[k * H:(k + 1) * H] for k in range(4))
+        return np.concatenate([i, o, g, f])
+    lstm = torch.nn.LSTM(D, H).double()
+    with torch.no_grad():
+        lstm.weight_ih_l0.copy_(torch_rows(W)); lstm.weight_hh_l0.copy_(torch_rows(U))
+        lstm.bias_ih_l0.copy_(torch_rows(b.reshape(-1, 1)).reshape(-1)); lstm.bias_hh_l0.zero_()
+    xt = torch.from_numpy(x.astype(np.float64)).requires_grad_(True)
+    loss, off = 0.0, 0
+    for n in lens:
+        seq = xt[off:off + n].flip(0).unsqueeze(1)                         # leaf (last node) first
+        out, _ = lstm(seq)
+        loss = loss + (out[:, 0, :].flip(0) * torch.from_numpy(gh[off:off + n].astype(np.float64))).sum()
+        off += n
+    loss.backward()
+    want = {"dx": xt.grad.numpy(), "dW": our_rows(lstm.weight_ih_l0.grad.numpy()),
+            "dU": our_rows(lstm.weight_hh_l0.grad.numpy()), "db": our_rows(lstm.bias_ih_l0.grad.numpy().reshape(-1, 1)).reshape(-1)}
+    got = {"dx": dx, "dW": dW, "dU": dU, "db": db}
+    errs = {k: _rel(got[k].cpu().numpy(), want[k]) for k in want}
+    print("   sequences vs torch autograd, relative-to-max errors:", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+    for k, v in errs.items():
+        assert v <= 1e-4, (k, v)
