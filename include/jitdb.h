@@ -20,7 +20,7 @@
  *
  * Conventions
  *   - Every function returns JITDB_OK (0) or a negative jitdb_status.  Nothing
- *     throws, exits or prints.
+ *     throws, exits or prints (a failed host-side allocation comes back as JITDB_E_NOMEM).
  *   - "dev" pointers are device (HBM) memory of the current HIP device, owned
  *     by the caller; "host" pointers are ordinary host memory.  The library
  *     allocates no device memory (jitdb_cache_create allocates a small host-side table, and the
@@ -52,7 +52,8 @@ typedef enum {
     JITDB_E_WORKSPACE = -5,    /* workspace smaller than the matching *_workspace_bytes */
     JITDB_E_HIP = -6,          /* a HIP runtime call failed */
     JITDB_E_SCHEDULE = -7,     /* forward was handed a schedule that is not complete */
-    JITDB_E_SIGNATURE = -8     /* a signature is outside [0, n_sig) */
+    JITDB_E_SIGNATURE = -8,    /* a signature is outside [0, n_sig) */
+    JITDB_E_NOMEM = -9         /* a host-side allocation failed (launch list, cache table, profiling events) */
 } jitdb_status;
 
 typedef enum {
@@ -167,7 +168,8 @@ int jitdb_forest_fingerprint(const int32_t *parent, int64_t n_nodes, uint64_t *f
  *   jitdb_cache_lookup   slot of the key, or -1 (also for NULL arguments)
  *   jitdb_cache_insert   slot now assigned to the key: the key's own if present, else the
  *                        lowest unused slot, else the slot of the least recently used key,
- *                        which is dropped (*evicted = 1; evicted may be NULL)
+ *                        which is dropped (*evicted = 1; evicted may be NULL); -1 for NULL
+ *                        arguments or when the host is out of memory (the table is unchanged)
  *   jitdb_cache_stats    counts of lookups that hit / missed and of keys held (NULLs skipped)
  */
 typedef struct jitdb_cache jitdb_cache_t;

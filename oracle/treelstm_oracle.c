@@ -1,5 +1,7 @@
 /*
- * Plain-C state oracle: Child-Sum Tree-LSTM forward, node by node, fp64.
+ * Plain-C state oracle: Child-Sum Tree-LSTM forward, node by node, in fp64
+ * (the parity reference).  Compiled a second time with -DORACLE_REAL=float the
+ * same source gives the fp32 build that is only ever timed, never compared.
  *
  * TEST INFRASTRUCTURE ONLY - never linked into or called by the product.
  *
@@ -22,48 +24,53 @@
 #include <omp.h>
 #endif
 
-static double sigmoid(double z) {
+#ifndef ORACLE_REAL
+#define ORACLE_REAL double
+#endif
+typedef ORACLE_REAL real;
+
+static real sigmoid(real z) {
     if (z >= 0.0) return 1.0 / (1.0 + exp(-z));
-    double e = exp(z);
+    real e = exp(z);
     return e / (1.0 + e);
 }
 
-static double dot(const double *a, const double *v, int n) {
-    double s = 0.0;
+static real dot(const real *a, const real *v, int n) {
+    real s = 0.0;
     for (int t = 0; t < n; ++t) s += a[t] * v[t];
     return s;
 }
 
 /* one node: children are k = cidx[0..nc) */
 static void eval_node(int64_t j, const int32_t *cidx, int nc, int D, int H,
-                      const double *x, const double *W, const double *U, const double *b,
-                      double *h, double *c, double *hs, double *fx) {
-    const double *xj = x + (size_t)j * D;
+                      const real *x, const real *W, const real *U, const real *b,
+                      real *h, real *c, real *hs, real *fx) {
+    const real *xj = x + (size_t)j * D;
     for (int d = 0; d < H; ++d) hs[d] = 0.0;
     for (int q = 0; q < nc; ++q) {
-        const double *hk = h + (size_t)cidx[q] * H;
+        const real *hk = h + (size_t)cidx[q] * H;
         for (int d = 0; d < H; ++d) hs[d] += hk[d];
     }
-    double *cj = c + (size_t)j * H, *hj = h + (size_t)j * H;
+    real *cj = c + (size_t)j * H, *hj = h + (size_t)j * H;
     for (int d = 0; d < H; ++d) {
         int ri = d, ro = H + d, ru = 2 * H + d, rf = 3 * H + d;
-        double gi = sigmoid(dot(W + (size_t)ri * D, xj, D) + dot(U + (size_t)ri * H, hs, H) + b[ri]);
-        double gu = tanh(dot(W + (size_t)ru * D, xj, D) + dot(U + (size_t)ru * H, hs, H) + b[ru]);
+        real gi = sigmoid(dot(W + (size_t)ri * D, xj, D) + dot(U + (size_t)ri * H, hs, H) + b[ri]);
+        real gu = tanh(dot(W + (size_t)ru * D, xj, D) + dot(U + (size_t)ru * H, hs, H) + b[ru]);
         cj[d] = gi * gu;
         fx[d] = dot(W + (size_t)rf * D, xj, D) + b[rf];
         (void)ro;
     }
     for (int q = 0; q < nc; ++q) {
-        const double *hk = h + (size_t)cidx[q] * H;
-        const double *ck = c + (size_t)cidx[q] * H;
+        const real *hk = h + (size_t)cidx[q] * H;
+        const real *ck = c + (size_t)cidx[q] * H;
         for (int d = 0; d < H; ++d) {
-            double f = sigmoid(fx[d] + dot(U + (size_t)(3 * H + d) * H, hk, H));
+            real f = sigmoid(fx[d] + dot(U + (size_t)(3 * H + d) * H, hk, H));
             cj[d] += f * ck[d];
         }
     }
     for (int d = 0; d < H; ++d) {
         int ro = H + d;
-        double go = sigmoid(dot(W + (size_t)ro * D, xj, D) + dot(U + (size_t)ro * H, hs, H) + b[ro]);
+        real go = sigmoid(dot(W + (size_t)ro * D, xj, D) + dot(U + (size_t)ro * H, hs, H) + b[ro]);
         hj[d] = go * tanh(cj[d]);
     }
 }
@@ -75,8 +82,8 @@ static void eval_node(int64_t j, const int32_t *cidx, int nc, int D, int H,
  * the number of threads that ran.
  */
 int oracle_treelstm_forward(int64_t n, const int32_t *parent, int D, int H,
-                            const double *x, const double *W, const double *U, const double *b,
-                            double *h, double *c, int n_threads, int *threads_used) {
+                            const real *x, const real *W, const real *U, const real *b,
+                            real *h, real *c, int n_threads, int *threads_used) {
     if (threads_used) *threads_used = 1;
     if (n == 0) return 0;
     int32_t *cptr = (int32_t *)calloc((size_t)n + 1, sizeof(int32_t));
@@ -126,8 +133,8 @@ int oracle_treelstm_forward(int64_t n, const int32_t *parent, int D, int H,
 #endif
 #pragma omp parallel
     {
-        double *hs = (double *)malloc((size_t)H * sizeof(double));
-        double *fx = (double *)malloc((size_t)H * sizeof(double));
+        real *hs = (real *)malloc((size_t)H * sizeof(real));
+        real *fx = (real *)malloc((size_t)H * sizeof(real));
 #ifdef _OPENMP
 #pragma omp single
         { if (threads_used) *threads_used = omp_get_num_threads(); }

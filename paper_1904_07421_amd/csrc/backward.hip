@@ -25,23 +25,9 @@
 namespace jitdb {
 namespace {
 
-typedef uint16_t bf16_t;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kT = 256;
-
-__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float((uint32_t)v << 16); }
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {  // round to nearest even
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (bf16_t)(u >> 16);
-}
-template <typename T> __device__ __forceinline__ T from_f32(float f);
-template <> __device__ __forceinline__ float from_f32<float>(float f) { return f; }
-template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float f) { return f32_to_bf16(f); }
-template <typename T> __device__ __forceinline__ float to_f32(T v);
-template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
-template <> __device__ __forceinline__ float to_f32<bf16_t>(bf16_t v) { return bf16_to_f32(v); }
 
 // ---- small helpers -----------------------------------------------------------------
 __global__ void __launch_bounds__(kT)

@@ -108,7 +108,7 @@ extern "C" int jitdb_cache_create(int32_t capacity, jitdb_cache_t **out) {
     *out = nullptr;
     if (capacity < 1 || capacity > (1 << 20)) return JITDB_E_BADARG;
     jitdb_cache *c = new (std::nothrow) jitdb_cache;
-    if (!c) return JITDB_E_BADARG;
+    if (!c) return JITDB_E_NOMEM;
     c->capacity = capacity;
     *out = c;
     return JITDB_OK;
@@ -140,6 +140,15 @@ extern "C" int32_t jitdb_cache_insert(jitdb_cache_t *cache, const uint64_t *fp, 
         cache->order.splice(cache->order.end(), cache->order, it->second);
         return it->second->second;
     }
+    // Everything that allocates happens before the table changes: a failure reports "no slot"
+    // (-1) and leaves the table as it was.
+    std::list<std::pair<Key, int32_t>> fresh;
+    try {
+        fresh.emplace_back(k, 0);
+        cache->where.emplace(k, fresh.begin());
+    } catch (...) {
+        return -1;
+    }
     int32_t slot;
     if ((int32_t)cache->order.size() < cache->capacity) {
         // lowest free slot: slots are handed out densely, and freed only by eviction, which
@@ -151,8 +160,8 @@ extern "C" int32_t jitdb_cache_insert(jitdb_cache_t *cache, const uint64_t *fp, 
         cache->order.pop_front();
         if (evicted) *evicted = 1;
     }
-    cache->order.emplace_back(k, slot);
-    cache->where[k] = std::prev(cache->order.end());
+    fresh.front().second = slot;
+    cache->order.splice(cache->order.end(), fresh);      // iterators stay valid across a splice
     return slot;
 }
 

@@ -5,6 +5,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <new>
+
 #include "jitdb.h"
 
 namespace jitdb {
@@ -46,6 +48,29 @@ void note_hip_failure(hipError_t e, const char *file, int line);
 // made by the host program; every entry point drops whatever it inherits so
 // that the launch checks only see this library's own launches.
 inline void drop_stale_hip_error() { (void)hipGetLastError(); }
+
+// Nothing may throw across the C ABI: host-side containers and `new` can (std::bad_alloc).
+// Every extern "C" entry point that reaches such code wraps its body in these.
+#define JITDB_ABI_TRY try {
+#define JITDB_ABI_CATCH                                         \
+    }                                                           \
+    catch (const std::bad_alloc &) { return JITDB_E_NOMEM; }    \
+    catch (...) { return JITDB_E_NOMEM; }
+
+// ---- bfloat16 as stored (uint16_t bit patterns); shared by the forward and backward kernels
+typedef uint16_t bf16_t;
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float((uint32_t)v << 16); }
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {  // round to nearest even
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+template <typename T> __device__ __forceinline__ T from_f32(float f);
+template <> __device__ __forceinline__ float from_f32<float>(float f) { return f; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float f) { return f32_to_bf16(f); }
+template <typename T> __device__ __forceinline__ float to_f32(T v);
+template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_f32<bf16_t>(bf16_t v) { return bf16_to_f32(v); }
 
 // K-blocked operand layout of the tiled GEMM core: bytes [64 s, 64 s + 64) of every row form
 // slab s, rows consecutive inside a slab (n_rows_alloc rows per slab).  Byte offset of byte

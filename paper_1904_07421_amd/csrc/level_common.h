@@ -1,0 +1,302 @@
+// Device-side pieces shared by the level kernels (forward.hip: 128 x 256 tiles, two blocks per CU,
+// fp32 and bf16, training and typed variants; level256.hip: 256 x 256 tiles, one block per CU, bf16):
+// operand types, the arguments of one level launch, and the fused cell update of one wave.
+#pragma once
+
+#include "common.h"
+
+#include <type_traits>
+
+namespace jitdb {
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+// Native vectors for data in flight (HIP's uint4 is a union-based struct, which the
+// optimiser does not always break up into registers).
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kThreads = 256;     // small kernels
+constexpr int kRowPad = 256;    // level row counts are rounded up to this for the stacked input
+constexpr int kBN = 256;        // packed columns per block = 2 unit tiles x 4 gates x 32
+constexpr int kUnit = 32;       // hidden units per MFMA column tile
+constexpr int kGateTile = 128;  // packed rows per unit tile (4 gates x 32 units)
+
+constexpr int kEpiStride = 40;  // floats per row of a wave's epilogue region: 32 units + 8; rows 4 apart fall 32 banks apart
+
+enum : int { MODE_LEAF = 0, MODE_INTERNAL = 1, MODE_PROJ = 2, MODE_GENERIC = 3 };   // GENERIC: plain C = A B^T
+
+template <typename T> struct Traits;
+template <> struct Traits<float> {
+    static constexpr int BK = 32;   // K is padded to multiples of this: 128 bytes, two pipeline stages
+    static constexpr int VEC = 4;   // elements per 16 bytes
+};
+template <> struct Traits<bf16_t> {
+    static constexpr int BK = 64;
+    static constexpr int VEC = 8;
+};
+
+// ---- operand layout ----------------------------------------------------------------
+// The two GEMM operands this file writes for itself (the stacked level input A and the
+// packed weights B) are stored K-blocked: bytes [64 s, 64 s + 64) of every row form slab
+// s, rows consecutive inside a slab.  A pipeline stage of the level kernel is 64 bytes of
+// K per row, so the 16 rows x 64 bytes that one direct-to-LDS load instruction moves are
+// 1 KB of consecutive memory, whole 128-byte lines.  (Fetching half a line now and the
+// other half a stage later costs a full line transfer from L2 each time.)
+// (operand_offset itself is in common.h: the backward pass writes operands in the same layout)
+
+// ---- scalar helpers (bf16 conversions are in common.h) --------------------------------
+// fp32 path: library exp (about 1 ulp); bf16 path: the hardware exp2-based fast form.
+template <typename T> __device__ __forceinline__ float exp_t(float z);
+template <> __device__ __forceinline__ float exp_t<float>(float z) { return expf(z); }
+template <> __device__ __forceinline__ float exp_t<bf16_t>(float z) { return __expf(z); }
+
+// 1/(1+e) through the hardware reciprocal (1 ulp) instead of an IEEE division sequence.
+template <typename T> __device__ __forceinline__ float sigmoid_t(float z) {
+    return __builtin_amdgcn_rcpf(1.0f + exp_t<T>(-z));
+}
+template <typename T> __device__ __forceinline__ float tanh_t(float z) {
+    return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + exp_t<T>(2.0f * z));
+}
+
+
+// ---- the level GEMM ----------------------------------------------------------------
+struct LevelArgs {
+    // A operands
+    const void *stack;    // [n_rows, Dp (+ Hp)] the level's stacked input (leaf / internal)
+    const void *hs;       // [N, Hp] rows by node id (projection)
+    // B operand: packed [W | U], NPU rows of Dp + Hp
+    const void *Bp;
+    const float *bp;      // [NP] packed bias
+    // schedule
+    const int4 *row_rec;         // two int4 per level row (this level's slice of the records)
+    const int32_t *child_idx;
+    // per-child forget projections U_f h_k, rows by node id, stride Hq, element type T
+    // (bf16 in the bf16 path: it halves the largest stream of the forward)
+    void *P;
+    float *cs;            // [N, Hq] c with padded rows, or == c_out when H % 8 == 0
+    // outputs
+    float *c_out;         // [N, H]
+    void *h_out;          // [N, H]
+    void *hs_out;         // [N, Hp] or == h_out when H == Hp
+    // training only: activations the backward pass needs
+    void *gates;          // [N, 3H] of T: i | o | u after their non-linearities, rows by node id
+    void *fgate;          // [N, H] of T: row k = forget gate the parent of k applied to k
+    int D, Dp, H, Hp, Hu, Hq;
+    int n_rows;
+    int n_rows_alloc;     // rows per slab of the stacked input (n_rows rounded up to whole tiles)
+    int NPU;              // rows per slab of the packed weights
+    int n_row_tiles;      // level kernel: tiles along the row axis
+    int n_col_tiles;      // tiles along the column axis
+    int n_tiles;          // thin kernel: number of wave tiles
+    int n_blocks;
+    // grouped launch over the slots of one level (typed table): row tile i covers level rows
+    // [tiles[i].x, min(tiles[i].x + 128, tiles[i].y)) and is evaluated by cell tiles[i].z
+    const int4 *tiles;
+    int64_t w_bytes;      // bytes between the packed weights of consecutive cells
+    int NP;               // floats between their packed biases
+};
+
+
+template <typename T>
+__device__ __forceinline__ void mfma_step(const u32x4 &a, const u32x4 &b, floatx16 &acc) {
+    if constexpr (sizeof(T) == 2) {
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                      __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+    } else {
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[0]), __uint_as_float(b[0]), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[1]), __uint_as_float(b[1]), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[2]), __uint_as_float(b[2]), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[3]), __uint_as_float(b[3]), acc, 0, 0, 0);
+    }
+}
+
+// ---- the cell update of one wave: 32 rows x 32 hidden units ---------------------------
+// acc[g][v] holds the pre-activation (without bias) of gate g for row
+// (v/4)*8 + hf*4 + v%4 and unit l32 of the wave's unit tile.  The wave writes i*u, o and
+// the x part of the forget gate to its private LDS region and reads them back row-major,
+// eight lanes per row and four consecutive units per lane: the rows of the children
+// (P_k and c_k) are then fetched in 8- and 16-byte pieces, 64 / 128 contiguous bytes per
+// row, with four rows in flight per lane.  rn / rar / rcb / rkid describe the 32 rows
+// (node id or -1, arity, CSR start, first four child ids).  No block barrier inside.
+template <typename T, int MODE, bool SAVE = false>
+__device__ __forceinline__ void cell_pass(const LevelArgs &a, const floatx16 (&acc)[4], float *region,
+                                          const int *rn, const int *rar, const int *rcb,
+                                          const int4 *rkid, int unit_tile, int lane) {
+    const int hf = lane >> 5, l32 = lane & 31;
+    const int pcol = unit_tile * kGateTile + l32;   // packed row of gate i for this unit
+    const float bi = a.bp[pcol], bo = a.bp[pcol + kUnit], bu = a.bp[pcol + 2 * kUnit];
+    float bf = 0.0f;
+    if constexpr (MODE == MODE_INTERNAL) bf = a.bp[pcol + 3 * kUnit];
+    float *s_iu = region;
+    float *s_o = s_iu + 32 * kEpiStride;
+    float *s_fx = s_o + 32 * kEpiStride;
+    T *h_out = static_cast<T *>(a.h_out);
+    T *hs_out = static_cast<T *>(a.hs_out);
+    const bool separate_hs = (a.hs_out != a.h_out);
+    const bool separate_cs = (a.cs != a.c_out);
+    const bool vec_ok = (a.H & 3) == 0;
+    const int unit0 = unit_tile * kUnit + (lane & 7) * 4;
+    // unit groups past the padded width read the first group instead (and store nothing)
+    const int unit_ld = unit0 < a.Hq ? unit0 : 0;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int rl = (v >> 2) * 8 + hf * 4 + (v & 3);   // 0..31
+        const float gi = sigmoid_t<T>(acc[0][v] + bi);
+        const float go = sigmoid_t<T>(acc[1][v] + bo);
+        const float gu = tanh_t<T>(acc[2][v] + bu);
+        s_iu[rl * kEpiStride + l32] = gi * gu;
+        s_o[rl * kEpiStride + l32] = go;
+        if constexpr (MODE == MODE_INTERNAL) s_fx[rl * kEpiStride + l32] = acc[3][v] + bf;
+        if constexpr (SAVE) {
+            const int nd = rn[rl];
+            const int unit = unit_tile * kUnit + l32;
+            if (nd >= 0 && unit < a.H) {
+                T *g = static_cast<T *>(a.gates) + (int64_t)nd * 3 * a.H + unit;
+                g[0] = from_f32<T>(gi);
+                g[a.H] = from_f32<T>(go);
+                g[2 * a.H] = from_f32<T>(gu);
+            }
+        }
+    }
+    // the wave's own LDS writes are ordered before its reads; nothing else touches the region
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    float4 cc[4], go4[4], fx4[4];
+    int node[4], tr[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        tr[q] = (lane >> 3) + 8 * q;
+        node[q] = rn[tr[q]];
+        const int so = tr[q] * kEpiStride + (lane & 7) * 4;
+        cc[q] = *reinterpret_cast<const float4 *>(s_iu + so);
+        go4[q] = *reinterpret_cast<const float4 *>(s_o + so);
+        if constexpr (MODE == MODE_INTERNAL) fx4[q] = *reinterpret_cast<const float4 *>(s_fx + so);
+    }
+    if constexpr (MODE == MODE_INTERNAL) {
+        // Children are taken two per row and round, for four rows at once: sixteen
+        // independent 16-byte loads in flight per thread.  The first four child ids
+        // of a row sit in LDS; longer lists (rare) continue from child_idx.  A slot
+        // without a child re-reads the row's last child with weight zero, which
+        // keeps every load unconditional.
+        int ar[4];
+        int max_ar = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            ar[q] = node[q] >= 0 ? rar[tr[q]] : 0;
+            max_ar = max(max_ar, ar[q]);
+        }
+        int64_t last[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) last[q] = unit_ld;
+        for (int c0 = 0; c0 < max_ar; c0 += 2) {
+            int64_t ofs[4][2];
+            float wgt[4][2];
+            int kidv[4][2];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                int4 kids = make_int4(0, 0, 0, 0);
+                if (c0 < 4) kids = rkid[tr[q]];
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const int c = c0 + j;
+                    const bool has = c < ar[q];
+                    int kid;
+                    if (c0 == 0) kid = j ? kids.y : kids.x;
+                    else if (c0 == 2) kid = j ? kids.w : kids.z;
+                    else kid = has ? a.child_idx[rcb[tr[q]] + c] : 0;
+                    if (has) last[q] = (int64_t)kid * a.Hq + unit_ld;
+                    ofs[q][j] = last[q];
+                    wgt[q][j] = has ? 1.0f : 0.0f;
+                    kidv[q][j] = has ? kid : -1;
+                }
+            }
+            float4 pk[4][2], ck[4][2];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    if constexpr (sizeof(T) == 4) {
+                        pk[q][j] = *reinterpret_cast<const float4 *>(static_cast<const float *>(a.P) + ofs[q][j]);
+                    } else {
+                        const uint2 w = *reinterpret_cast<const uint2 *>(static_cast<const bf16_t *>(a.P) + ofs[q][j]);
+                        pk[q][j] = make_float4(__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xFFFF0000u),
+                                               __uint_as_float(w.y << 16), __uint_as_float(w.y & 0xFFFF0000u));
+                    }
+                    ck[q][j] = *reinterpret_cast<const float4 *>(a.cs + ofs[q][j]);
+                }
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const float f0 = sigmoid_t<T>(fx4[q].x + pk[q][j].x), f1 = sigmoid_t<T>(fx4[q].y + pk[q][j].y);
+                    const float f2 = sigmoid_t<T>(fx4[q].z + pk[q][j].z), f3 = sigmoid_t<T>(fx4[q].w + pk[q][j].w);
+                    cc[q].x += wgt[q][j] * f0 * ck[q][j].x;
+                    cc[q].y += wgt[q][j] * f1 * ck[q][j].y;
+                    cc[q].z += wgt[q][j] * f2 * ck[q][j].z;
+                    cc[q].w += wgt[q][j] * f3 * ck[q][j].w;
+                    if constexpr (SAVE) {
+                        if (kidv[q][j] >= 0) {
+                            const float fv[4] = {f0, f1, f2, f3};
+                            T *dst = static_cast<T *>(a.fgate) + (int64_t)kidv[q][j] * a.H + unit0;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (unit0 + e < a.H) dst[e] = from_f32<T>(fv[e]);
+                        }
+                    }
+                }
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        if (node[q] < 0) continue;
+        const float c4[4] = {cc[q].x, cc[q].y, cc[q].z, cc[q].w};
+        const float o4[4] = {go4[q].x, go4[q].y, go4[q].z, go4[q].w};
+        T hv[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) hv[j] = from_f32<T>(o4[j] * tanh_t<T>(c4[j]));
+        const int64_t nd = node[q];
+        if (vec_ok) {
+            if (unit0 < a.H) {
+                *reinterpret_cast<float4 *>(a.c_out + nd * a.H + unit0) = cc[q];
+                if (separate_cs) *reinterpret_cast<float4 *>(a.cs + nd * a.Hq + unit0) = cc[q];
+                if constexpr (sizeof(T) == 4) {
+                    const float4 h4 = make_float4(hv[0], hv[1], hv[2], hv[3]);
+                    *reinterpret_cast<float4 *>(h_out + nd * a.H + unit0) = h4;
+                    if (separate_hs) *reinterpret_cast<float4 *>(hs_out + nd * a.Hp + unit0) = h4;
+                } else {
+                    const uint2 h2 = make_uint2((uint32_t)hv[0] | ((uint32_t)hv[1] << 16),
+                                                (uint32_t)hv[2] | ((uint32_t)hv[3] << 16));
+                    *reinterpret_cast<uint2 *>(h_out + nd * a.H + unit0) = h2;
+                    if (separate_hs) *reinterpret_cast<uint2 *>(hs_out + nd * a.Hp + unit0) = h2;
+                }
+            } else if (separate_hs && unit0 < a.Hp) {   // zero pad columns of the padded h copy
+                if constexpr (sizeof(T) == 4)
+                    *reinterpret_cast<float4 *>(hs_out + nd * a.Hp + unit0) = make_float4(0.f, 0.f, 0.f, 0.f);
+                else
+                    *reinterpret_cast<uint2 *>(hs_out + nd * a.Hp + unit0) = make_uint2(0u, 0u);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int unit = unit0 + j;
+                if (unit < a.H) {
+                    a.c_out[nd * a.H + unit] = c4[j];
+                    if (separate_cs) a.cs[nd * a.Hq + unit] = c4[j];
+                    h_out[nd * a.H + unit] = hv[j];
+                    if (separate_hs) hs_out[nd * a.Hp + unit] = hv[j];
+                } else if (separate_hs && unit < a.Hp) {
+                    hs_out[nd * a.Hp + unit] = T(0);
+                }
+            }
+        }
+    }
+}
+
+#define JITDB_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
+#define JITDB_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
+
+}  // namespace
+}  // namespace jitdb
