@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libjitdb.so")
-SOURCES = ["schedule.hip", "forward.hip", "backward.hip", "cache.hip", "probe.hip", "api.hip"]
+SOURCES = ["schedule.hip", "forward.hip", "level256.hip", "backward.hip", "cache.hip", "probe.hip", "api.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -153,8 +153,10 @@ def build(verbose: bool = False) -> str:
     tmp = tempfile.mkdtemp(prefix="jitdb_build_")
     try:
         res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, cwd=tmp)
-        asm_path = os.path.join(tmp, "forward-hip-amdgcn-amd-amdhsa-gfx950.s")
-        asm_text = open(asm_path).read() if os.path.exists(asm_path) else None
+        asm_texts = {}
+        for stem in ("forward", "level256"):
+            asm_path = os.path.join(tmp, stem + "-hip-amdgcn-amd-amdhsa-gfx950.s")
+            asm_texts[stem] = open(asm_path).read() if os.path.exists(asm_path) else None
     finally:
         shutil.rmtree(tmp, ignore_errors=True)
     # the host pass warns that it does not know the packed-fp32 feature: harmless
@@ -163,10 +165,11 @@ def build(verbose: bool = False) -> str:
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + out)
     _check_no_scratch(lines)
-    if asm_text is None:
-        raise RuntimeError("the device assembly of forward.hip was not produced; cannot check it")
-    for name in ("level_kernel", "gemm_kb_kernel"):      # the kernels built on the asm-read GEMM core
-        if check_lds_read_waits(asm_text, name) == 0:
+    # the kernels whose LDS reads (and, for the 256 x 256 tile kernel, weight loads) are inline asm
+    for stem, name in (("forward", "level_kernel"), ("forward", "gemm_kb_kernel"), ("level256", "tile256_kernel")):
+        if asm_texts.get(stem) is None:
+            raise RuntimeError(f"the device assembly of {stem}.hip was not produced; cannot check it")
+        if check_lds_read_waits(asm_texts[stem], name) == 0:
             raise RuntimeError(f"no LDS reads found in the assembly of {name}: the check is not looking at it")
     if verbose and out.strip():
         print(out)

@@ -79,6 +79,17 @@ __host__ __device__ __forceinline__ int64_t operand_offset(int64_t row, int64_t 
     return ((kbyte >> 6) * n_rows_alloc + row) * 64 + (kbyte & 63);
 }
 
+// Fragment-major layout of the packed weights for the 256 x 256 tile kernel: the 32 packed rows of
+// one gate of one unit tile (packed row = unit_tile * 128 + gate * 32 + u) times one K group of 32
+// bytes form 1 KB in MFMA operand order, lane (u, half) holding bytes [16 half, 16 half + 16) of the
+// group; the four gates of a K group are consecutive, then the K groups (n_kg per packed row), then
+// the unit tiles.  Byte offset of byte `kbyte` of packed row `row`.
+__host__ __device__ __forceinline__ int64_t fragment_offset(int64_t row, int64_t kbyte, int64_t n_kg) {
+    const int64_t ut = row >> 7, gate = (row >> 5) & 3, u = row & 31;
+    const int64_t kg = kbyte >> 5, half = (kbyte >> 4) & 1;
+    return ((((ut * n_kg + kg) * 4 + gate) * 64) + half * 32 + u) * 16 + (kbyte & 15);
+}
+
 // C = A B^T on the tiled GEMM core of the level kernel (128 x 256 tiles, stages straight into
 // LDS), for operands in the K-blocked layout above.  A has M rows (a_rows_alloc >= M rounded up
 // to 128 per slab), B has N rows (b_rows_alloc >= N rounded up to 256); K is k_bytes / element

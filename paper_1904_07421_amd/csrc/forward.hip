@@ -48,6 +48,7 @@ struct PackArgs {
     const void *W, *U; const float *b;
     int D, H, Dp, Hp, NP, NPU;
     void *Bp; float *bp;
+    void *Bf;       // the same rows fragment-major for the 256 x 256 tile kernel (bf16, one cell), or null
 };
 
 // block `block` of `n_blocks` (kThreads threads each, stride loop)
@@ -55,7 +56,7 @@ template <typename T>
 __device__ __forceinline__ void pack_weights_body(const T *__restrict__ W, const T *__restrict__ U,
                                                   const float *__restrict__ b, int D, int H, int Dp, int Hp,
                                                   int NP, int NPU, T *__restrict__ Bp, float *__restrict__ bp,
-                                                  int64_t block, int64_t n_blocks) {
+                                                  T *__restrict__ Bf, int64_t block, int64_t n_blocks) {
     const int Kp = Dp + Hp;
     const int64_t total = (int64_t)NPU * Kp;
     for (int64_t idx = block * kThreads + threadIdx.x; idx < total; idx += n_blocks * kThreads) {
@@ -71,6 +72,8 @@ __device__ __forceinline__ void pack_weights_body(const T *__restrict__ W, const
         }
         *reinterpret_cast<T *>(reinterpret_cast<char *>(Bp) +
                                operand_offset(r, (int64_t)k * sizeof(T), NPU)) = v;
+        if (Bf)
+            *reinterpret_cast<T *>(reinterpret_cast<char *>(Bf) + fragment_offset(r, (int64_t)k * sizeof(T), Kp * (int)sizeof(T) / 32)) = v;
         if (k == 0 && r < NP) bp[r] = row_ok ? b[src] : 0.0f;
     }
 }
@@ -79,7 +82,7 @@ template <typename T>
 __global__ void __launch_bounds__(kThreads)
 pack_weights_kernel(const PackArgs p) {
     pack_weights_body<T>(static_cast<const T *>(p.W), static_cast<const T *>(p.U), p.b, p.D, p.H, p.Dp, p.Hp, p.NP,
-                         p.NPU, static_cast<T *>(p.Bp), p.bp, blockIdx.x, gridDim.x);
+                         p.NPU, static_cast<T *>(p.Bp), p.bp, static_cast<T *>(p.Bf), blockIdx.x, gridDim.x);
 }
 
 // ---- row records -------------------------------------------------------------------
@@ -165,8 +168,8 @@ prepare_kernel(const int32_t *__restrict__ perm, const int32_t *__restrict__ key
         row_record_body(perm, key, child_ptr, child_idx, row_rec, n, blockIdx.x);
     else
         pack_weights_body<T>(static_cast<const T *>(p.W), static_cast<const T *>(p.U), p.b, p.D, p.H, p.Dp, p.Hp,
-                             p.NP, p.NPU, static_cast<T *>(p.Bp), p.bp, (int64_t)blockIdx.x - n_windows,
-                             (int64_t)gridDim.x - n_windows);
+                             p.NP, p.NPU, static_cast<T *>(p.Bp), p.bp, static_cast<T *>(p.Bf),
+                             (int64_t)blockIdx.x - n_windows, (int64_t)gridDim.x - n_windows);
 }
 
 // ---- stack -------------------------------------------------------------------------
@@ -331,7 +334,6 @@ constexpr int kDmaStage = 64;      // bytes of K per row and stage
 constexpr int kDmaBuf = (kDmaBM + kBN) * kDmaStage;
 constexpr int kDmaBufs = 3;
 constexpr int kWarmMaxStages = 256; // longest K loop whose A tile is requested up front (2 MB)
-constexpr int kDmaProjStride = 136; // floats per row of a wave's projection store region (128 units + 8)
 
 
 // Waits until at most N of this wave's loads are outstanding and all its LDS operations
@@ -638,53 +640,9 @@ level_kernel(const LevelArgs a_in) {
         // Each wave turns its 64 rows x 128 units around in a private LDS region, 32 rows at
         // a time, so that 16 lanes store one row's 128 units in 8-unit pieces.
         float *region = reinterpret_cast<float *>(lds) + wave * (32 * kDmaProjStride);
-        const int hf = lane >> 5, l32 = lane & 31;
-        T *P = static_cast<T *>(a.P);
-        const int u8 = (lane & 15) * 8;
-        const int unit0 = col_tile * 256 + wn * 128 + u8;
 #pragma unroll
-        for (int p = 0; p < 2; ++p) {
-#pragma unroll
-            for (int g = 0; g < 4; ++g)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int rl = (v >> 2) * 8 + hf * 4 + (v & 3);
-                    region[rl * kDmaProjStride + g * 32 + l32] = acc[p][g][v];
-                }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
-            for (int sweep = 0; sweep < 8; ++sweep) {
-                const int rl = (lane >> 4) + 4 * sweep;
-                const int node = row_node[wm * 64 + p * 32 + rl];
-                if (node < 0 || unit0 >= a.H) continue;
-                const float4 lo = *reinterpret_cast<const float4 *>(region + rl * kDmaProjStride + u8);
-                const float4 hi = *reinterpret_cast<const float4 *>(region + rl * kDmaProjStride + u8 + 4);
-                const float f[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-                T *dst = P + (int64_t)node * a.Hq + unit0;
-                if (unit0 + 8 <= a.H) {
-                    if constexpr (sizeof(T) == 4) {
-                        *reinterpret_cast<float4 *>(dst) = lo;
-                        *reinterpret_cast<float4 *>(dst + 4) = hi;
-                    } else {
-                        uint4 o;
-                        o.x = (uint32_t)f32_to_bf16(f[0]) | ((uint32_t)f32_to_bf16(f[1]) << 16);
-                        o.y = (uint32_t)f32_to_bf16(f[2]) | ((uint32_t)f32_to_bf16(f[3]) << 16);
-                        o.z = (uint32_t)f32_to_bf16(f[4]) | ((uint32_t)f32_to_bf16(f[5]) << 16);
-                        o.w = (uint32_t)f32_to_bf16(f[6]) | ((uint32_t)f32_to_bf16(f[7]) << 16);
-                        *reinterpret_cast<uint4 *>(dst) = o;
-                    }
-                } else {
-#pragma unroll
-                    for (int j = 0; j < 8; ++j)
-                        if (unit0 + j < a.H) dst[j] = from_f32<T>(f[j]);
-                }
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        }
+        for (int p = 0; p < 2; ++p)
+            proj_pass<T>(a, acc[p], region, row_node + wm * 64 + p * 32, col_tile * 256 + wn * 128, lane);
     } else {
         float *region = reinterpret_cast<float *>(lds) + wave * (3 * 32 * kEpiStride);
 #pragma unroll
@@ -1064,6 +1022,7 @@ struct ScopedLaunchTimer {
 struct ForwardWs {
     void *Bp;
     float *bp;
+    void *Bf;     // fragment-major copy of the packed weights (bf16 with one cell), else nullptr
     void *stack;  // the current level's stacked input, (N + 256) rows of Dp + Hp
     int4 *row_rec; // row records of all level positions, two int4 each
     void *hs;     // nullptr when h_out can serve (H == Hp)
@@ -1098,6 +1057,8 @@ Dims make_dims(int D, int H, jitdb_dtype dtype) {
 
 // packed weights of one cell: bytes of Bp, floats of bp (one set per signature, back to back)
 size_t packed_w_bytes(const Dims &d) { return (size_t)d.NPU * (d.Dp + d.Hp) * d.esz; }
+// the 256 x 256 tile kernel (bf16, one cell) reads the weights in a second, fragment-major layout
+bool has_fragment_copy(const Dims &d, int n_sig) { return d.esz == 2 && n_sig == 1; }
 
 ForwardWs carve_forward_ws(int64_t n, int64_t e, const Dims &d, void *base, int n_sig = 1) {
     Carver c(base);
@@ -1105,6 +1066,7 @@ ForwardWs carve_forward_ws(int64_t n, int64_t e, const Dims &d, void *base, int 
     (void)e;
     w.Bp = c.take<char>(packed_w_bytes(d) * n_sig);
     w.bp = c.take<float>((size_t)d.NP * n_sig);
+    w.Bf = has_fragment_copy(d, n_sig) ? c.take<char>(packed_w_bytes(d)) : nullptr;
     // one level at a time; whole row tiles are read, hence the 256 spare rows
     w.stack = c.take<char>((size_t)(n + kRowPad) * (d.Dp + d.Hp) * d.esz);
     w.row_rec = c.take<int4>((size_t)2 * (n + kRowPad));   // every level position
@@ -1139,6 +1101,8 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
     if (packed) {
         w.Bp = const_cast<void *>(packed);
         w.bp = reinterpret_cast<float *>(static_cast<char *>(w.Bp) + round_up(packed_w_bytes(d) * n_sig_w, 256));
+        w.Bf = has_fragment_copy(d, n_sig_w)
+                   ? reinterpret_cast<char *>(w.bp) + round_up((int64_t)d.NP * n_sig_w * 4, 256) : nullptr;
     }
     const int L = s->n_levels;
     const int n_sig = slots ? slots->n_sig : 1;
@@ -1155,6 +1119,7 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
             p.D = d.D; p.H = d.H; p.Dp = d.Dp; p.Hp = d.Hp; p.NP = d.NP; p.NPU = d.NPU;
             p.Bp = static_cast<char *>(w.Bp) + packed_w_bytes(d) * t;
             p.bp = w.bp + (size_t)d.NP * t;
+            p.Bf = t == 0 ? w.Bf : nullptr;
             return p;
         };
         const int n_windows = (int)ceil_div(s->n_nodes, kRecWindow);
@@ -1174,6 +1139,10 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
 
     LevelArgs a;
     a.stack = w.stack;
+    a.Bf = w.Bf;
+    // bf16 levels that are large enough run on 256 x 256 tiles (level256.hip); training and typed
+    // tables keep the 128 x 256 kernel, which has those variants
+    const bool may256 = std::is_same<T, bf16_t>::value && !SAVE && !slots && w.Bf != nullptr;
     a.hs = w.hs ? w.hs : h_out;
     a.child_idx = s->child_idx;
 
@@ -1287,6 +1256,9 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
                     thin_kernel<T, MODE_LEAF, SAVE><<<a.n_blocks, kThinWaves * 64, 0, st>>>(a);
                 else
                     thin_kernel<T, MODE_INTERNAL, SAVE><<<a.n_blocks, kThinWaves * 64, 0, st>>>(a);
+            } else if (may256 && tile256_applies(l == 0 ? MODE_LEAF : MODE_INTERNAL, a)) {
+                const int rc = launch_tile256(l == 0 ? MODE_LEAF : MODE_INTERNAL, a, st);
+                if (rc != JITDB_OK) return rc;
             } else if (grouped) {
                 if (l == 0)
                     level_kernel<T, MODE_LEAF, false, true><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
@@ -1343,6 +1315,9 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
                 } else {
                     thin_kernel<T, MODE_PROJ><<<a.n_blocks, kThinWaves * 64, 0, st>>>(a);
                 }
+            } else if (may256 && tile256_applies(MODE_PROJ, a)) {
+                const int rc = launch_tile256(MODE_PROJ, a, st);
+                if (rc != JITDB_OK) return rc;
             } else {
                 a.n_col_tiles = (int)ceil_div(n_unit_tiles, 8);
                 a.n_row_tiles = (int)ceil_div(rows, kDmaBM);
@@ -1512,7 +1487,8 @@ int forward_entry(const void *x, const void *W, const void *U, const float *b, i
 }
 
 size_t packed_total_bytes(const Dims &d, int n_sig) {
-    return (size_t)round_up(packed_w_bytes(d) * n_sig, 256) + (size_t)round_up((int64_t)d.NP * n_sig * 4, 256);
+    return (size_t)round_up(packed_w_bytes(d) * n_sig, 256) + (size_t)round_up((int64_t)d.NP * n_sig * 4, 256) +
+           (has_fragment_copy(d, n_sig) ? (size_t)round_up(packed_w_bytes(d), 256) : 0);
 }
 }  // namespace
 
@@ -1543,6 +1519,7 @@ extern "C" int jitdb_treelstm_pack(const void *W, const void *U, const float *b,
         p.D = d.D; p.H = d.H; p.Dp = d.Dp; p.Hp = d.Hp; p.NP = d.NP; p.NPU = d.NPU;
         p.Bp = static_cast<char *>(packed) + packed_w_bytes(d) * t;
         p.bp = bp0 + (size_t)d.NP * t;
+        p.Bf = has_fragment_copy(d, n_sig) ? reinterpret_cast<char *>(bp0) + round_up((int64_t)d.NP * n_sig * 4, 256) : nullptr;
         if (dtype == JITDB_F32) pack_weights_kernel<float><<<grid, kThreads, 0, st>>>(p);
         else pack_weights_kernel<bf16_t><<<grid, kThreads, 0, st>>>(p);
         JITDB_LAUNCH_CHECK();

@@ -23,6 +23,12 @@ constexpr int kBN = 256;        // packed columns per block = 2 unit tiles x 4 g
 constexpr int kUnit = 32;       // hidden units per MFMA column tile
 constexpr int kGateTile = 128;  // packed rows per unit tile (4 gates x 32 units)
 
+// Smallest level (rows) each kind of launch hands to the 256 x 256 tile kernel (level256.hip), by mode
+// (leaf, internal, projection); INT32_MAX = never.  Measured on config 5: with one wave per SIMD nothing
+// overlaps the cell update's activation arithmetic, so the leaf and internal launches (activation-heavy)
+// are faster on 128 x 256 tiles with two blocks per CU; the projection has no activations.
+constexpr int kTile256MinRows[3] = {INT32_MAX, INT32_MAX, INT32_MAX};
+
 constexpr int kEpiStride = 40;  // floats per row of a wave's epilogue region: 32 units + 8; rows 4 apart fall 32 banks apart
 
 enum : int { MODE_LEAF = 0, MODE_INTERNAL = 1, MODE_PROJ = 2, MODE_GENERIC = 3 };   // GENERIC: plain C = A B^T
@@ -61,13 +67,16 @@ template <typename T> __device__ __forceinline__ float tanh_t(float z) {
 }
 
 
-// ---- the level GEMM ----------------------------------------------------------------
+}  // namespace
+
+// ---- the arguments of one level launch (a named type: it crosses translation units) -----
 struct LevelArgs {
     // A operands
     const void *stack;    // [n_rows, Dp (+ Hp)] the level's stacked input (leaf / internal)
     const void *hs;       // [N, Hp] rows by node id (projection)
     // B operand: packed [W | U], NPU rows of Dp + Hp
     const void *Bp;
+    const void *Bf;       // the same rows fragment-major (tile256_kernel), or null
     const float *bp;      // [NP] packed bias
     // schedule
     const int4 *row_rec;         // two int4 per level row (this level's slice of the records)
@@ -97,6 +106,9 @@ struct LevelArgs {
     int64_t w_bytes;      // bytes between the packed weights of consecutive cells
     int NP;               // floats between their packed biases
 };
+
+namespace {
+
 
 
 template <typename T>
@@ -295,8 +307,67 @@ __device__ __forceinline__ void cell_pass(const LevelArgs &a, const floatx16 (&a
     }
 }
 
+// ---- the projection's store of one wave: 32 rows x 128 units ----------------------------
+// acc[g][v] holds P = U_f h for row (v/4)*8 + hf*4 + v%4 and unit unit_base + g*32 + l32.  The wave
+// turns the tile around in its private LDS region so that 16 lanes store one row's 128 units in
+// 8-unit pieces (16 bytes of bf16).  rn: node ids of the 32 rows (-1: no such row).
+constexpr int kDmaProjStride = 136; // floats per row of a wave's projection store region (128 units + 8)
+template <typename T>
+__device__ __forceinline__ void proj_pass(const LevelArgs &a, const floatx16 (&acc)[4], float *region,
+                                          const int *rn, int unit_base, int lane) {
+    const int hf = lane >> 5, l32 = lane & 31;
+    T *P = static_cast<T *>(a.P);
+    const int u8 = (lane & 15) * 8;
+    const int unit0 = unit_base + u8;
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int rl = (v >> 2) * 8 + hf * 4 + (v & 3);
+            region[rl * kDmaProjStride + g * 32 + l32] = acc[g][v];
+        }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int sweep = 0; sweep < 8; ++sweep) {
+        const int rl = (lane >> 4) + 4 * sweep;
+        const int node = rn[rl];
+        if (node < 0 || unit0 >= a.H) continue;
+        const float4 lo = *reinterpret_cast<const float4 *>(region + rl * kDmaProjStride + u8);
+        const float4 hi = *reinterpret_cast<const float4 *>(region + rl * kDmaProjStride + u8 + 4);
+        const float f[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+        T *dst = P + (int64_t)node * a.Hq + unit0;
+        if (unit0 + 8 <= a.H) {
+            if constexpr (sizeof(T) == 4) {
+                *reinterpret_cast<float4 *>(dst) = lo;
+                *reinterpret_cast<float4 *>(dst + 4) = hi;
+            } else {
+                uint4 o;
+                o.x = (uint32_t)f32_to_bf16(f[0]) | ((uint32_t)f32_to_bf16(f[1]) << 16);
+                o.y = (uint32_t)f32_to_bf16(f[2]) | ((uint32_t)f32_to_bf16(f[3]) << 16);
+                o.z = (uint32_t)f32_to_bf16(f[4]) | ((uint32_t)f32_to_bf16(f[5]) << 16);
+                o.w = (uint32_t)f32_to_bf16(f[6]) | ((uint32_t)f32_to_bf16(f[7]) << 16);
+                *reinterpret_cast<uint4 *>(dst) = o;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (unit0 + j < a.H) dst[j] = from_f32<T>(f[j]);
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 #define JITDB_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 #define JITDB_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
 }  // namespace
+
+// level256.hip
+bool tile256_applies(int mode, const LevelArgs &a);
+int launch_tile256(int mode, LevelArgs a, hipStream_t st);
+
 }  // namespace jitdb
