@@ -236,6 +236,27 @@ def _stream_ptr(stream) -> int:
     return int(s.cuda_stream)
 
 
+def _empty(stream, *args, **kw):
+    import torch
+    with _on_stream(stream):
+        return torch.empty(*args, **kw)
+
+
+def _zeros(stream, *args, **kw):
+    import torch
+    with _on_stream(stream):
+        return torch.zeros(*args, **kw)
+
+
+def _on_stream(stream):
+    """Context in which default buffers are allocated: the stream the launches go to.  Memory the
+    caching allocator hands out belongs to the stream that is current at that moment; allocated under
+    another stream it could be given to other work while these kernels still use it."""
+    import contextlib
+    import torch
+    return contextlib.nullcontext() if stream is None else torch.cuda.stream(stream)
+
+
 class Schedule:
     """Device arrays of one forest's schedule plus the C struct that points at them."""
 
@@ -376,13 +397,13 @@ def jitdb_treelstm_backward(x, W, U, schedule: Schedule, h, c, gates, fgate, gh=
             raise ValueError("gh, gc must be [N, H]")
     if out is None:
         f32 = dict(dtype=torch.float32, device=x.device)
-        dx = torch.empty((n, D), **f32); dW = torch.empty((4 * H, D), **f32)
-        dU = torch.empty((4 * H, H), **f32); db = torch.empty(4 * H, **f32)
+        dx = _empty(stream, (n, D), **f32); dW = _empty(stream, (4 * H, D), **f32)
+        dU = _empty(stream, (4 * H, H), **f32); db = _empty(stream, 4 * H, **f32)
     else:
         dx, dW, dU, db = out
     need = jitdb_treelstm_backward_workspace_bytes(schedule, D, H, dt)
     if workspace is None:
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+        workspace = _empty(stream, max(need, 256), dtype=torch.uint8, device=x.device)
     ptr = lambda t: t.data_ptr() if (t is not None and t.numel()) else None
     with torch.cuda.device(x.device):
         code = lib.jitdb_treelstm_backward(
@@ -415,18 +436,18 @@ def _forward(x, W, U, b, schedule, stream, workspace, out, train):
         raise ValueError("shape mismatch between x, W, U, b and the schedule")
     gates = fgate = None
     if out is None:
-        h = torch.empty((n, H), dtype=x.dtype, device=x.device)
-        c = torch.empty((n, H), dtype=torch.float32, device=x.device)
+        h = _empty(stream, (n, H), dtype=x.dtype, device=x.device)
+        c = _empty(stream, (n, H), dtype=torch.float32, device=x.device)
         if train:
-            gates = torch.empty((n, 3 * H), dtype=x.dtype, device=x.device)
-            fgate = torch.zeros((n, H), dtype=x.dtype, device=x.device)
+            gates = _empty(stream, (n, 3 * H), dtype=x.dtype, device=x.device)
+            fgate = _zeros(stream, (n, H), dtype=x.dtype, device=x.device)
     elif train:
         h, c, gates, fgate = out
     else:
         h, c = out
     need = jitdb_treelstm_workspace_bytes(n, schedule.n_edges, D, H, dt)
     if workspace is None:
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+        workspace = _empty(stream, max(need, 256), dtype=torch.uint8, device=x.device)
     with torch.cuda.device(x.device):
         if train:
             code = lib.jitdb_treelstm_forward_train(
@@ -604,13 +625,13 @@ def jitdb_treelstm_forward_typed(x, W, U, b, schedule: TypedSchedule, stream=Non
     if x.shape != (n, D) or W.shape != (T, 4 * H, D) or U.shape != (T, 4 * H, H) or b.shape != (T, 4 * H):
         raise ValueError("shape mismatch between x, W, U, b and the schedule")
     if out is None:
-        h = torch.empty((n, H), dtype=x.dtype, device=x.device)
-        c = torch.empty((n, H), dtype=torch.float32, device=x.device)
+        h = _empty(stream, (n, H), dtype=x.dtype, device=x.device)
+        c = _empty(stream, (n, H), dtype=torch.float32, device=x.device)
     else:
         h, c = out
     need = jitdb_treelstm_typed_workspace_bytes(n, schedule.n_edges, D, H, dt, T)
     if workspace is None:
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+        workspace = _empty(stream, max(need, 256), dtype=torch.uint8, device=x.device)
     with torch.cuda.device(x.device):
         code = lib.jitdb_treelstm_forward_typed(
             x.data_ptr() if n else None, W.data_ptr(), U.data_ptr(), b.data_ptr(), D, H, dt,
@@ -644,7 +665,7 @@ def jitdb_treelstm_pack(W, U, b, stream=None) -> PackedWeights:
     if W.shape != (T, 4 * H, D) or U.shape != (T, 4 * H, H) or b.shape != (T, 4 * H):
         raise ValueError("shape mismatch between W, U, b")
     need = int(lib.jitdb_treelstm_packed_bytes(D, H, dt, T))
-    buf = torch.empty(max(need, 256), dtype=torch.uint8, device=W.device)
+    buf = _empty(stream, max(need, 256), dtype=torch.uint8, device=W.device)
     with torch.cuda.device(W.device):
         _check(lib.jitdb_treelstm_pack(W.data_ptr(), U.data_ptr(), b.data_ptr(), D, H, dt, T, buf.data_ptr(),
                                        buf.numel(), _stream_ptr(stream)))
@@ -666,13 +687,13 @@ def jitdb_treelstm_forward_packed(x, packed: PackedWeights, schedule: Schedule, 
     if x.shape != (n, D):
         raise ValueError("x must be [N, D]")
     if out is None:
-        h = torch.empty((n, H), dtype=x.dtype, device=x.device)
-        c = torch.empty((n, H), dtype=torch.float32, device=x.device)
+        h = _empty(stream, (n, H), dtype=x.dtype, device=x.device)
+        c = _empty(stream, (n, H), dtype=torch.float32, device=x.device)
     else:
         h, c = out
     need = jitdb_treelstm_typed_workspace_bytes(n, schedule.n_edges, D, H, packed.dtype, packed.n_sig)
     if workspace is None:
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+        workspace = _empty(stream, max(need, 256), dtype=torch.uint8, device=x.device)
     with torch.cuda.device(x.device):
         code = lib.jitdb_treelstm_forward_packed(
             x.data_ptr() if n else None, packed.buffer.data_ptr(), D, H, packed.dtype,

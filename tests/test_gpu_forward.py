@@ -404,3 +404,28 @@ def test_variable_length_sequences_against_the_library_lstm():
             off += n
     print(f"sequences vs torch.nn.LSTM: max error {worst:.3e}", flush=True)
     assert worst <= 1e-4
+
+
+def test_default_buffers_follow_the_launch_stream(c_oracle):
+    """stream=st WITHOUT making st current: the buffers the binding allocates by default must belong to
+    st, so that other work on the current stream cannot be handed them while the forward still runs."""
+    import torch
+    import paper_1904_07421_amd as J
+    from gpu_util import dev_parent
+    cfgo, p, x, W, U, b = make_workload(2, bias="random")
+    s = J.jitdb_schedule(dev_parent(p))
+    xt, Wt, Ut, bt = (torch.from_numpy(a).cuda() for a in (x, W, U, b))
+    st = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    outs = []
+    for _ in range(4):
+        h, c = J.jitdb_treelstm_forward(xt, Wt, Ut, bt, s, stream=st)      # current stream stays the default one
+        # work on the current stream that would love to reuse freed blocks
+        junk = [torch.full((p.shape[0], cfgo.H), float("nan"), device="cuda") for _ in range(8)]
+        del junk
+        outs.append((h, c))
+    st.synchronize()
+    torch.cuda.synchronize()
+    ho, co, _ = c_oracle(p, x, W, U, b)
+    for h, c in outs:
+        assert np.abs(h.cpu().numpy() - ho).max() <= 1e-4 and np.abs(c.cpu().numpy() - co).max() <= 1e-4
