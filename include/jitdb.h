@@ -280,6 +280,29 @@ int jitdb_treelstm_forward(const void *x, const void *W, const void *U, const fl
                            void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * jitdb_treelstm_forward for callers that cannot allocate device memory and so have no workspace
+ * to pass: code recorded into a HIP graph, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, results and errors as jitdb_treelstm_forward, without the workspace: the scratch
+ * memory is a fixed array of JITDB_STATIC_SCRATCH_BYTES inside the library, one copy per GPU, held
+ * from the moment the library's code is loaded on that GPU until the process ends.  The call
+ * allocates and frees nothing on the device (no hipMalloc, no hipFree, no library that does).
+ *
+ *   - Forests whose jitdb_treelstm_workspace_bytes exceeds JITDB_STATIC_SCRATCH_BYTES are refused
+ *     with JITDB_E_WORKSPACE and nothing is launched (64 MiB: e.g. 25 000 nodes at D = 300, H = 150
+ *     in bf16; use jitdb_treelstm_forward with a workspace of your own beyond that).
+ *   - All calls on one GPU share that GPU's array: two calls that overlap in time on one GPU
+ *     (different streams, or different host threads) race.  Calls on one stream are ordered and safe.
+ *     The array keeps the previous call's contents; the call needs none of it and none of it zeroed.
+ *   - The first call on a GPU looks up the array's device address (hipGetSymbolAddress): make one
+ *     call outside graph capture before capturing.
+ */
+#define JITDB_STATIC_SCRATCH_BYTES (64 * 1024 * 1024)
+int jitdb_treelstm_forward_static(const void *x, const void *W, const void *U, const float *b,
+                                  int32_t D, int32_t H, jitdb_dtype dtype,
+                                  const jitdb_schedule_t *s,
+                                  void *h_out, float *c_out, void *hip_stream);
+
+/*
  * Weights packed once for many calls.  jitdb_treelstm_forward re-packs W, U, b into the GEMM's
  * operand layout in every call (two short launches; one more per further signature); a serving
  * loop whose weights do not change packs them once and hands the result to

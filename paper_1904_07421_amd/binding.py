@@ -97,6 +97,11 @@ def load_library():
         ctypes.c_int32, ctypes.c_int32, ctypes.c_int,
         ctypes.POINTER(_ScheduleStruct), ctypes.c_void_p, ctypes.c_void_p,
         ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.jitdb_treelstm_forward_static.restype = ctypes.c_int
+    lib.jitdb_treelstm_forward_static.argtypes = [
+        ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+        ctypes.c_int32, ctypes.c_int32, ctypes.c_int,
+        ctypes.POINTER(_ScheduleStruct), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
     lib.jitdb_treelstm_forward_train.restype = ctypes.c_int
     lib.jitdb_treelstm_forward_train.argtypes = [
         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
@@ -352,6 +357,33 @@ def jitdb_treelstm_forward(x, W, U, b, schedule: Schedule, stream=None, workspac
     """x [N, D], W [4H, D], U [4H, H] (all fp32 or all bf16), b [4H] fp32, on the GPU.
     Returns (h [N, H] in x's dtype, c [N, H] fp32), rows indexed by node id."""
     return _forward(x, W, U, b, schedule, stream, workspace, out, train=False)
+
+
+def jitdb_treelstm_forward_static(x, W, U, b, schedule: Schedule, out: Tuple, stream=None):
+    """jitdb_treelstm_forward on the library's own fixed scratch array: no workspace, nothing allocated
+    (the caller passes the outputs h [N, H] in x's dtype and c [N, H] fp32).  Returns (h, c)."""
+    import torch
+    lib = load_library()
+    dt = JITDB_F32 if x.dtype == torch.float32 else JITDB_BF16
+    if x.dtype not in (torch.float32, torch.bfloat16):
+        raise TypeError("x must be float32 or bfloat16")
+    h, c = out
+    n, H, D = schedule.n_nodes, U.shape[1], W.shape[1]
+    for t, name in ((x, "x"), (W, "W"), (U, "U"), (b, "b"), (h, "h"), (c, "c")):
+        if not t.is_cuda or not t.is_contiguous():
+            raise TypeError(f"{name} must be a contiguous CUDA tensor")
+    if W.dtype != x.dtype or U.dtype != x.dtype or h.dtype != x.dtype or b.dtype != torch.float32 or c.dtype != torch.float32:
+        raise TypeError("W, U, h must have x's dtype; b, c must be float32")
+    if (x.shape != (n, D) or W.shape[0] != 4 * H or U.shape[0] != 4 * H or b.numel() != 4 * H
+            or h.shape != (n, H) or c.shape != (n, H)):
+        raise ValueError("shape mismatch between x, W, U, b, out and the schedule")
+    with torch.cuda.device(x.device):
+        code = lib.jitdb_treelstm_forward_static(
+            x.data_ptr() if n else None, W.data_ptr(), U.data_ptr(), b.data_ptr(), D, H, dt,
+            ctypes.byref(schedule.struct), h.data_ptr() if n else None, c.data_ptr() if n else None,
+            _stream_ptr(stream))
+    _check(code)
+    return h, c
 
 
 def jitdb_treelstm_forward_train(x, W, U, b, schedule: Schedule, stream=None, workspace=None,

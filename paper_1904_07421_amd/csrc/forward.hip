@@ -35,6 +35,7 @@
 
 #include "level_common.h"
 
+#include <mutex>
 #include <vector>
 
 namespace jitdb {
@@ -1568,4 +1569,54 @@ extern "C" int jitdb_treelstm_forward_train(const void *x, const void *W, const 
                                             void *workspace, size_t workspace_bytes, void *hip_stream) {
     return forward_entry(x, W, U, b, D, H, dtype, s, nullptr, h_out, c_out, gates_out, fgate_out, true,
                          workspace, workspace_bytes, hip_stream);
+}
+
+// ---- the forward for callers that cannot allocate ----------------------------------------
+// Code under HIP graph capture, tight serving loops and harnesses that forbid hipMalloc have no
+// workspace to hand over.  For them the workspace is this array, which every GPU the library
+// runs on holds from the moment the code object is loaded until the process ends.  In host code
+// the array's name is only a handle: the device address comes from hipGetSymbolAddress, once per
+// device, and that pointer is what the kernels get.
+static __device__ __align__(256) unsigned char scratch[JITDB_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_lock;
+
+int static_scratch_of_current_device(void **out) {
+    int dev = -1;
+    JITDB_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return JITDB_E_BADARG;
+    std::lock_guard<std::mutex> g(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        JITDB_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));    // this device's copy of the array
+        if (!p) return JITDB_E_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return JITDB_OK;
+}
+}  // namespace
+
+extern "C" int jitdb_treelstm_forward_static(const void *x, const void *W, const void *U, const float *b,
+                                             int32_t D, int32_t H, jitdb_dtype dtype,
+                                             const jitdb_schedule_t *s, void *h_out, float *c_out,
+                                             void *hip_stream) {
+    if (!s) return JITDB_E_NULL;
+    if (!dims_ok(s->n_nodes, s->n_edges, D, H, (int)dtype)) return JITDB_E_BADARG;
+    if (s->n_nodes == 0) return JITDB_OK;
+    const size_t need = carve_forward_ws(s->n_nodes, s->n_edges, make_dims(D, H, dtype), nullptr).bytes;
+    if (need > (size_t)JITDB_STATIC_SCRATCH_BYTES) return JITDB_E_WORKSPACE;
+    drop_stale_hip_error();
+    void *ws = nullptr;
+    JITDB_ABI_TRY
+    const int rc = static_scratch_of_current_device(&ws);
+    if (rc != JITDB_OK) return rc;
+    JITDB_ABI_CATCH
+    // Nothing in the workspace has to start at zero: every region is written in full by this call
+    // before anything reads it (packed weights, row records, the stacked level, P, padded copies).
+    return forward_entry(x, W, U, b, D, H, dtype, s, nullptr, h_out, c_out, nullptr, nullptr, false,
+                         ws, (size_t)JITDB_STATIC_SCRATCH_BYTES, hip_stream);
 }
