@@ -629,11 +629,13 @@ level_kernel(const LevelArgs a_in) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][g][v] = 0.0f;
 
+    CellBias bias = {};
     if constexpr (MODE == MODE_PROJ) {
         publish_rows();
         __syncthreads();
         dma_gemm<T, MODE>(a, lds, row_node, tile_row0, col_tile, acc, sink, []() {});
     } else {
+        bias = load_cell_bias<MODE>(a, col_tile * 2 + wn, lane);     // on its way while the GEMM runs
         dma_gemm<T, MODE>(a, lds, row_node, tile_row0, col_tile, acc, sink, publish_rows);
     }
 
@@ -650,7 +652,7 @@ level_kernel(const LevelArgs a_in) {
         for (int p = 0; p < 2; ++p) {
             const int r0 = wm * 64 + p * 32;
             cell_pass<T, MODE, SAVE>(a, acc[p], region, row_node + r0, row_ar + r0, row_cb + r0, row_kid + r0,
-                               col_tile * 2 + wn, lane);
+                               col_tile * 2 + wn, lane, bias);
         }
     }
 }
@@ -881,6 +883,10 @@ __device__ __forceinline__ void thin_body(const LevelArgs &a, int tile) {
     for (int g = 0; g < 4; ++g)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[g][v] = 0.0f;
+    CellBias bias = {};
+    if constexpr (MODE != MODE_PROJ) {
+        if (wave == 0) bias = load_cell_bias<MODE>(a, col, lane);     // on its way while the K loop runs
+    }
 
     u32x4 fa[kThinAhead], fb[kThinAhead];
     auto request = [&](int g, int slot) __attribute__((always_inline)) {
@@ -925,7 +931,7 @@ __device__ __forceinline__ void thin_body(const LevelArgs &a, int tile) {
         for (int g = 1; g < (MODE == MODE_LEAF ? 3 : 4); ++g)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[g][v] = exchange[g - 1][v][lane];
-        cell_pass<T, MODE, SAVE>(a, acc, region, s_node, s_ar, s_cb, s_kid, col, lane);
+        cell_pass<T, MODE, SAVE>(a, acc, region, s_node, s_ar, s_cb, s_kid, col, lane, bias);
     }
 }
 

@@ -196,6 +196,8 @@ tile256_kernel(const LevelArgs a) {
         for (int k = 0; k < kPF; ++k)
 #pragma unroll
             for (int j = 0; j < (MODE == MODE_LEAF ? 3 : 4); ++j) load_b_frag(Bs[k][j], cur_t, k, j);
+        CellBias bias = {};
+        if constexpr (MODE != MODE_PROJ) bias = load_cell_bias<MODE>(a, cur_t.col_tile * 2 + wn, lane);
         __syncthreads();
         {
             const int r = cur_t.row0 + t;
@@ -342,7 +344,7 @@ tile256_kernel(const LevelArgs a) {
             else
                 cell_pass<bf16_t, MODE, false>(a, pa4, region, row_node + r0, row_ar + (MODE == MODE_INTERNAL ? r0 : 0),
                                                row_cb + (MODE == MODE_INTERNAL ? r0 : 0),
-                                               row_kid + (MODE == MODE_INTERNAL ? r0 : 0), cur_t.col_tile * 2 + wn, lane);
+                                               row_kid + (MODE == MODE_INTERNAL ? r0 : 0), cur_t.col_tile * 2 + wn, lane, bias);
         }
     }
     wait_barrier256<0>();      // nothing is on its way to LDS when the block ends

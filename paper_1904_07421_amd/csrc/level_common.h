@@ -132,15 +132,24 @@ __device__ __forceinline__ void mfma_step(const u32x4 &a, const u32x4 &b, floatx
 // (P_k and c_k) are then fetched in 8- and 16-byte pieces, 64 / 128 contiguous bytes per
 // row, with four rows in flight per lane.  rn / rar / rcb / rkid describe the 32 rows
 // (node id or -1, arity, CSR start, first four child ids).  No block barrier inside.
+// The packed bias of the wave's unit tile: gate g of unit l32 (lane & 31).  Loaded by the caller
+// before its K loop, so that the cell update does not start with a trip to memory.
+struct CellBias { float i, o, u, f; };
+template <int MODE>
+__device__ __forceinline__ CellBias load_cell_bias(const LevelArgs &a, int unit_tile, int lane) {
+    const int pcol = unit_tile * kGateTile + (lane & 31);
+    CellBias b;
+    b.i = a.bp[pcol]; b.o = a.bp[pcol + kUnit]; b.u = a.bp[pcol + 2 * kUnit];
+    b.f = (MODE == MODE_INTERNAL) ? a.bp[pcol + 3 * kUnit] : 0.0f;
+    return b;
+}
+
 template <typename T, int MODE, bool SAVE = false>
 __device__ __forceinline__ void cell_pass(const LevelArgs &a, const floatx16 (&acc)[4], float *region,
                                           const int *rn, const int *rar, const int *rcb,
-                                          const int4 *rkid, int unit_tile, int lane) {
+                                          const int4 *rkid, int unit_tile, int lane, const CellBias &bias) {
     const int hf = lane >> 5, l32 = lane & 31;
-    const int pcol = unit_tile * kGateTile + l32;   // packed row of gate i for this unit
-    const float bi = a.bp[pcol], bo = a.bp[pcol + kUnit], bu = a.bp[pcol + 2 * kUnit];
-    float bf = 0.0f;
-    if constexpr (MODE == MODE_INTERNAL) bf = a.bp[pcol + 3 * kUnit];
+    const float bi = bias.i, bo = bias.o, bu = bias.u, bf = bias.f;
     float *s_iu = region;
     float *s_o = s_iu + 32 * kEpiStride;
     float *s_fx = s_o + 32 * kEpiStride;
