@@ -31,13 +31,13 @@ PEAK_F32_MFMA_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
 
-def measured_traffic(cfg, kernel_class):
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
-    (FETCH_SIZE + WRITE_SIZE scaled by a copy kernel of known size), or None."""
+def measured_traffic(cfg, key):
+    """A figure from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE scaled by a copy kernel
+    of known size), or None: key = "traffic_bytes_per_launch[<kernel class>]" or "traffic_bytes_per_forward"."""
     path = os.path.join(ROOT, "profiles", f"level_kernel_{cfg.dtype}_config{cfg.index}_pmc.txt")
     try:
         for line in open(path):
-            if line.startswith(f"traffic_bytes_per_launch[{kernel_class}]:"):
+            if line.startswith(key + ":"):
                 return float(line.split(":", 1)[1].split()[0])
     except OSError:
         pass
@@ -387,8 +387,21 @@ def main():
     flops_row = {"leaf": 2.0 * D * 3 * H, "internal": 2.0 * D * 4 * H + 2.0 * H * 3 * H, "proj": 2.0 * H * H}
     flops_total = {"leaf": n_leaf * flops_row["leaf"], "internal": n_int * flops_row["internal"],
                    "proj": E * flops_row["proj"]}
-    # stack step: reads every x row and every child's h row once, writes the stacked rows
-    bytes_stack = (2 * N * D + E * H + n_int * H) * esz
+    # Algorithmic bytes per row of each kernel class as this design moves them (padding does not count):
+    #   leaf      reads its stacked x row, writes h and c (fp32)
+    #   internal  reads its stacked [x | sum h] row, per child P_k and c_k (fp32), writes h and c
+    #   proj      reads h, writes P
+    bytes_row = {"leaf": D * esz + H * esz + 4.0 * H,
+                 "internal": (D + H) * esz + H * esz + 4.0 * H,
+                 "proj": 2.0 * H * esz}
+    bytes_edge_internal = H * esz + 4.0 * H
+    # the gather ("stack" step): the child sum reads every child's h row once and writes one row per
+    # internal node; the copy of x into the stacked matrix (read + written) is overhead of this design
+    bytes_gather = (E * H + n_int * H) * esz
+    bytes_xcopy = 2.0 * N * D * esz
+    # the fully fused minimum of the whole forward: x, h, c once, h_k and c_k once per edge, weights once
+    bytes_min = N * (D * esz + H * esz + 4.0 * H) + E * (H * esz + 4.0 * H) + (D + H) * 4.0 * H * esz
+    ridge = peak_tflops * 1e12 / (PEAK_HBM_GBS * 1e9)      # flop per byte at which the two roofs meet
     kernels = {}
     roof = None
     if prof is not None:
@@ -402,26 +415,53 @@ def main():
             if job == "proj" and proj_rows > 0:
                 fl *= E / proj_rows
             if ms > 0:
+                by = rows * bytes_row[job]
+                if job == "internal":      # its share of the edges, by rows (exact when one class holds all of them)
+                    by += E * bytes_edge_internal * rows / max(n_int, 1)
+                gbs = by / (ms * 1e-3) / 1e9
                 kernels[name] = {"ms_per_step": ms, "launches_per_step": n_l, "rows_per_step": rows,
                                  "flops_per_step": fl, "tflops": fl / (ms * 1e-3) / 1e12,
-                                 "frac_mfma_peak": fl / (ms * 1e-3) / 1e12 / peak_tflops}
+                                 "frac_mfma_peak": fl / (ms * 1e-3) / 1e12 / peak_tflops,
+                                 "bytes_per_step": by, "gbs": gbs, "frac_hbm_peak": gbs / PEAK_HBM_GBS,
+                                 "flop_per_byte": fl / by,
+                                 # the roof that binds a kernel of this intensity
+                                 "bound": "mfma" if fl / by >= ridge else "hbm"}
         ms = prof["stack"]["ms"] / args.steps
         if ms > 0:
             kernels["stack"] = {"ms_per_step": ms,
                                 "launches_per_step": prof["stack"]["launches"] / args.steps,
-                                "gbs": bytes_stack / (ms * 1e-3) / 1e9,
-                                "frac_hbm_peak": bytes_stack / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
+                                "bound": "hbm",
+                                # the gather proper (child sums): what the metric's "HBM GB/s of the gather" means
+                                "gather_bytes_per_step": bytes_gather,
+                                "gbs": bytes_gather / (ms * 1e-3) / 1e9,
+                                "frac_hbm_peak": bytes_gather / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                                # with the copy of x (this design's overhead) counted as moved bytes too
+                                "xcopy_bytes_per_step": bytes_xcopy,
+                                "gbs_with_xcopy": (bytes_gather + bytes_xcopy) / (ms * 1e-3) / 1e9}
         kernels["pack"] = {"ms_per_step": prof["pack"]["ms"] / args.steps}
         mfma_names = [n for n in ("leaf", "internal", "proj", "thin_leaf", "thin_internal", "thin_proj") if n in kernels]
         dom = max(mfma_names, key=lambda k: kernels[k]["ms_per_step"])
         k = kernels[dom]
         kname = (f"thin_kernel<{cfg.dtype},{dom[5:]}>" if dom.startswith("thin_") else f"level_kernel<{cfg.dtype},{dom}>")
-        roof = {"kernel": kname, "bound": "mfma",
-                "achieved": k["tflops"], "peak": peak_tflops, "unit": "TFLOP/s",
-                "frac": k["frac_mfma_peak"], "traffic": measured_traffic(cfg, dom),
-                "avg_launch_ms": k["ms_per_step"] / max(k["launches_per_step"], 1),
-                "flops_per_launch": k["flops_per_step"] / max(k["launches_per_step"], 1),
-                "flops_per_step": k["flops_per_step"], "dropped_events": prof["dropped"]}
+        # the dominant kernel against the roof that binds a kernel of its own intensity; the other
+        # roof's fraction is given beside it
+        launches = max(k["launches_per_step"], 1)
+        if k["bound"] == "mfma":
+            roof = {"kernel": kname, "bound": "mfma", "achieved": k["tflops"], "peak": peak_tflops,
+                    "unit": "TFLOP/s", "frac": k["frac_mfma_peak"]}
+        else:
+            roof = {"kernel": kname, "bound": "hbm", "achieved": k["gbs"], "peak": PEAK_HBM_GBS,
+                    "unit": "GB/s", "frac": k["frac_hbm_peak"]}
+        roof.update({"traffic": measured_traffic(cfg, f"traffic_bytes_per_launch[{dom}]"),
+                     "avg_launch_ms": k["ms_per_step"] / launches,
+                     "flop_per_byte": k["flop_per_byte"], "ridge_flop_per_byte": ridge,
+                     "frac_mfma_peak": k["frac_mfma_peak"], "frac_hbm_peak": k["frac_hbm_peak"],
+                     "tflops": k["tflops"], "gbs": k["gbs"],
+                     "flops_per_launch": k["flops_per_step"] / launches, "bytes_per_launch": k["bytes_per_step"] / launches,
+                     "flops_per_step": k["flops_per_step"], "dropped_events": prof["dropped"]})
+        tt = measured_traffic(cfg, "traffic_bytes_per_forward")
+        roof["traffic_total"] = tt
+        roof["traffic_total_over_bytes_min"] = None if tt is None else tt / bytes_min
         mfma_ms = sum(kernels[n]["ms_per_step"] for n in mfma_names)
         roof["all_mfma_kernels_frac"] = sum(flops_total.values()) / (mfma_ms * 1e-3) / 1e12 / peak_tflops
 
@@ -435,12 +475,18 @@ def main():
         measured = {"copy_gbs": J.jitdb_probe_copy(src, dst, stream=stream),
                     "mfma_tflops": J.jitdb_probe_mfma(J.JITDB_BF16 if esz == 2 else J.JITDB_F32, sink, stream=stream),
                     "what": "plain 1 GiB device copy, read + written; loop of independent 32x32 MFMAs on all CUs"}
-        del src, dst
+        # other shapes of stream: the best of them is the ceiling the HBM-bound pieces are quoted against
+        for kind, name in ((1, "read_gbs"), (2, "write_gbs"), (3, "copy_nt_gbs"), (4, "copy_chunk_gbs")):
+            measured[name] = J.jitdb_probe_stream(kind, src, dst, stream=stream)
+        measured["best_copy_gbs"] = max(measured["copy_gbs"], measured["copy_nt_gbs"], measured["copy_chunk_gbs"])
+        measured["what"] += ("; read-only, write-only, non-temporal and per-block-chunk copies of the same 1 GiB "
+                             "(best_copy_gbs = the fastest copy)")
         if roof is not None:
-            roof["measured_peak"] = measured["mfma_tflops"]
-            roof["frac_of_measured_peak"] = roof["achieved"] / measured["mfma_tflops"]
+            roof["measured_peak"] = measured["mfma_tflops"] if roof["bound"] == "mfma" else measured["best_copy_gbs"]
+            roof["frac_of_measured_peak"] = roof["achieved"] / roof["measured_peak"]
         if "stack" in kernels:
-            kernels["stack"]["frac_of_measured_copy"] = kernels["stack"]["gbs"] / measured["copy_gbs"]
+            kernels["stack"]["frac_of_measured_copy"] = kernels["stack"]["gbs_with_xcopy"] / measured["best_copy_gbs"]
+        del src, dst
 
     out = {
         "metric": "Tree-LSTM forward nodes/sec on 1 MI355X; MFMA util % + HBM GB/s vs peak",
@@ -455,6 +501,12 @@ def main():
         "ms_schedule_cache_hit": ms_cache_hit, "ms_forward_packed_weights": ms_fwd_packed,
         "ms_per_step_with_kernel_events": ms_with_events,
         "forward_only_nodes_per_s": N / (ms_fwd * 1e-3),
+        # the whole forward against its own roofline: max(F_min / MFMA peak, bytes_min / HBM peak) / ms_forward
+        "forward_roofline": {"f_min_flops": sum(flops_total.values()), "bytes_min": bytes_min,
+                             "ms_at_mfma_peak": sum(flops_total.values()) / (peak_tflops * 1e12) * 1e3,
+                             "ms_at_hbm_peak": bytes_min / (PEAK_HBM_GBS * 1e9) * 1e3},
+        "forward_frac_of_roofline": max(sum(flops_total.values()) / (peak_tflops * 1e12),
+                                        bytes_min / (PEAK_HBM_GBS * 1e9)) * 1e3 / ms_fwd,
         "roofline": roof, "kernels": kernels, "measured_peaks": measured,
         # the metric's other two figures: useful flops of all MFMA kernels / their summed time, as % of the bf16
         # (fp32) MFMA peak; algorithmic bytes of the gather ("stack") kernels / their time, and as % of 8 TB/s
@@ -476,10 +528,25 @@ def main():
         else:
             xo, Wo, Uo = x[:hi], W, U
         forward_c(sub[:r[1]], xo[:r[1]], Wo, Uo, b)          # build + first-touch outside the clock
+        forward_c(sub[:r[1]], xo[:r[1]], Wo, Uo, b, precision="f32")
+        # the oracle as it is used for parity: fp64, every host core
         t1 = time.perf_counter()
-        _, _, used = forward_c(sub, xo, Wo, Uo, b)
+        ho, co, used = forward_c(sub, xo, Wo, Uo, b)
         dt = time.perf_counter() - t1
-        # the same oracle on one thread, on a sixteenth of the sample
+        # ... and what it just computed is compared with what the GPU computed in the timed steps
+        # (h, c of the last forward; the forest's first trees are the same nodes in both)
+        hg = h[:hi].float().cpu().numpy()
+        cg = c[:hi].cpu().numpy()
+        tol = 2e-2 if esz == 2 else 1e-4
+        parity = {"nodes": hi, "max_abs_dh": float(np.abs(hg - ho).max()), "max_abs_dc": float(np.abs(cg - co).max()),
+                  "tolerance": tol}
+        parity["ok"] = bool(parity["max_abs_dh"] <= tol and parity["max_abs_dc"] <= tol)
+        del ho, co, hg, cg
+        # the same source compiled with fp32 arithmetic: the timing build (never compared with anything)
+        t1 = time.perf_counter()
+        _, _, used32 = forward_c(sub, xo, Wo, Uo, b, precision="f32")
+        dt32 = time.perf_counter() - t1
+        # the fp64 oracle on one thread, on a sixteenth of the sample
         n1 = max(1, n_trees // 16)
         hi1 = int(r[n1])
         t1 = time.perf_counter()
@@ -487,10 +554,17 @@ def main():
         dt1 = time.perf_counter() - t1
         out["cpu_baseline"] = {"value": hi / dt, "unit": "nodes/s", "cores": int(used), "kind": "oracle",
                                "sample": f"first {n_trees} trees ({hi} nodes) of the same forest, "
-                                         f"fp64 C oracle with OpenMP over trees, {dt:.1f}s",
+                                         f"fp64 C oracle (-O3 -march=native) with OpenMP over trees, {dt:.1f}s",
+                               "fp32_build": {"value": hi / dt32, "unit": "nodes/s", "cores": int(used32),
+                                              "sample": f"same trees, the oracle's source compiled with float, {dt32:.1f}s"},
                                "one_thread": {"value": hi1 / dt1, "unit": "nodes/s", "cores": 1,
-                                              "sample": f"first {n1} trees ({hi1} nodes), {dt1:.1f}s"}}
+                                              "sample": f"first {n1} trees ({hi1} nodes), fp64, {dt1:.1f}s"}}
+        out["parity"] = parity
+        if not parity["ok"]:
+            log(f"PARITY FAILED against the oracle: {parity}")
     print(json.dumps(out), flush=True)
+    if out.get("parity") is not None and not out["parity"]["ok"]:
+        sys.exit(1)
 
 
 if __name__ == "__main__":

@@ -417,9 +417,18 @@ int jitdb_profile_stop(jitdb_profile_t *out);
  *   jitdb_probe_mfma   times a loop of independent 32x32 MFMAs of the dtype's kind on every
  *                      CU and returns TFLOP/s; `sink` is dev memory for one float (never
  *                      written in practice).
- * Both run on `hip_stream` and wait for it.
+ *   jitdb_probe_stream the same for other shapes of stream, to find the best the memory system gives:
+ *                      `kind` = JITDB_STREAM_COPY (as jitdb_probe_copy), _READ (src only is read;
+ *                      GB/s read), _WRITE (dst only is written; GB/s written), _COPY_NT (four
+ *                      non-temporal 16-byte loads and stores in flight per thread), _COPY_CHUNK (one
+ *                      contiguous chunk per block); copies return (read + written) GB/s.  dst must
+ *                      be valid device memory of `bytes` for every kind.
+ * All run on `hip_stream` and wait for it.
  */
+enum { JITDB_STREAM_COPY = 0, JITDB_STREAM_READ = 1, JITDB_STREAM_WRITE = 2, JITDB_STREAM_COPY_NT = 3,
+       JITDB_STREAM_COPY_CHUNK = 4 };
 int jitdb_probe_copy(const void *src, void *dst, size_t bytes, void *hip_stream, double *gb_per_s);
+int jitdb_probe_stream(int kind, const void *src, void *dst, size_t bytes, void *hip_stream, double *gb_per_s);
 int jitdb_probe_mfma(jitdb_dtype dtype, float *sink, void *hip_stream, double *tflop_per_s);
 
 /* Static, NUL-terminated description of a status code. */

@@ -121,6 +121,9 @@ def load_library():
     lib.jitdb_profile_start.argtypes = [ctypes.c_int32]
     lib.jitdb_profile_stop.restype = ctypes.c_int
     lib.jitdb_profile_stop.argtypes = [ctypes.POINTER(_ProfileStruct)]
+    lib.jitdb_probe_stream.restype = ctypes.c_int
+    lib.jitdb_probe_stream.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
+                                       ctypes.c_void_p, ctypes.POINTER(ctypes.c_double)]
     lib.jitdb_probe_copy.restype = ctypes.c_int
     lib.jitdb_probe_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
                                      ctypes.POINTER(ctypes.c_double)]
@@ -208,6 +211,18 @@ def jitdb_probe_copy(src, dst, stream=None) -> float:
     out = ctypes.c_double(0.0)
     _check(load_library().jitdb_probe_copy(src.data_ptr(), dst.data_ptr(), nbytes, _stream_ptr(stream),
                                            ctypes.byref(out)))
+    return float(out.value)
+
+
+def jitdb_probe_stream(kind: int, src, dst, stream=None) -> float:
+    """GB/s of one shape of memory stream over two equally sized CUDA tensors (kinds: 0 copy, 1 read,
+    2 write, 3 copy with non-temporal accesses, 4 copy in per-block chunks)."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("src and dst must have the same size")
+    out = ctypes.c_double(0.0)
+    _check(load_library().jitdb_probe_stream(int(kind), src.data_ptr(), dst.data_ptr(), nbytes, _stream_ptr(stream),
+                                             ctypes.byref(out)))
     return float(out.value)
 
 

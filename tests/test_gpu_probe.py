@@ -33,3 +33,19 @@ def test_probe_bad_arguments():
         J.jitdb_probe_copy(src[:3], src[4:7])          # 12 bytes: not a multiple of 16
     with pytest.raises(J.JitdbError):
         J.jitdb_probe_mfma(7, src)
+
+
+@pytest.mark.parametrize("kind,name", [(0, "copy"), (1, "read"), (2, "write"), (3, "copy-nt"), (4, "copy-chunk")])
+def test_stream_probe_kinds(kind, name):
+    src = torch.arange(1 << 22, dtype=torch.int32, device="cuda")
+    dst = torch.zeros_like(src)
+    print(f"probe stream {name} 16 MiB", flush=True)
+    gbs = J.jitdb_probe_stream(kind, src, dst)
+    torch.cuda.synchronize()
+    assert 10.0 < gbs < 16000.0
+    if kind in (0, 3, 4):
+        assert torch.equal(src, dst)
+    if kind == 1:
+        assert not bool(dst.any())          # a read-only stream writes nothing
+    with pytest.raises(J.JitdbError):
+        J.jitdb_probe_stream(9, src, dst)
