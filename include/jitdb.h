@@ -53,7 +53,8 @@ typedef enum {
     JITDB_E_HIP = -6,          /* a HIP runtime call failed */
     JITDB_E_SCHEDULE = -7,     /* forward was handed a schedule that is not complete */
     JITDB_E_SIGNATURE = -8,    /* a signature is outside [0, n_sig) */
-    JITDB_E_NOMEM = -9         /* a host-side allocation failed (launch list, cache table, profiling events) */
+    JITDB_E_NOMEM = -9,        /* a host-side allocation failed (launch list, cache table, profiling events) */
+    JITDB_E_ARITY = -10        /* a node has more children than its (N-ary) cell has child positions */
 } jitdb_status;
 
 typedef enum {
@@ -235,6 +236,49 @@ size_t jitdb_treelstm_typed_workspace_bytes(int64_t n_nodes, int64_t n_edges,
  * `s` and `slots` come from jitdb_schedule_typed (slot_ptr is read on the device).
  */
 int jitdb_treelstm_forward_typed(const void *x, const void *W, const void *U, const float *b,
+                                 int32_t D, int32_t H, jitdb_dtype dtype,
+                                 const jitdb_schedule_t *s, const jitdb_slots_t *slots,
+                                 void *h_out, float *c_out,
+                                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * A table whose signatures name cells of different operator TYPE (the paper's key holds the operator
+ * type and its settings next to the depth, sections 4.2 and 4.3: nodes of different type never share
+ * a slot).  Two types:
+ *
+ *   JITDB_CELL_CHILDSUM  the cell of jitdb_treelstm_forward: W [4H, D], U [4H, H], b [4H], gate rows
+ *                        i, o, u, f; any number of children.
+ *   JITDB_CELL_NARY      the N-ary Tree-LSTM cell of the model the paper cites, `arity` = N child positions,
+ *                        1 <= N <= JITDB_MAX_NARY.  Children are taken in ascending node id (position 1,
+ *                        2, ...); with hc = [h of child 1 ; ... ; h of child N] (zero blocks for missing ones)
+ *                            i, o = sigmoid(W x + U hc + b)   u = tanh(W x + U hc + b)
+ *                            f_l  = sigmoid(W_{f_l} x + U_{f_l} hc + b_{f_l})      l = 1..N
+ *                            c    = i*u + sum over present children l of f_l * c_l   h = o * tanh(c)
+ *                        W [(3+N)H, D], U [(3+N)H, N*H] (column block l multiplies the child in position l),
+ *                        b [(3+N)H], gate rows i, o, u, f_1, ..., f_N.
+ *
+ * All cells share D, H and the dtype.  Cells may differ freely along edges (a child-sum parent applies
+ * its own forget weights to the h of an N-ary child and vice versa).  `cells` is a HOST array of n_sig
+ * entries whose W, U, b are device pointers; `s`, `slots` come from jitdb_schedule_typed with the same
+ * n_sig.  Child-sum slots run as in jitdb_treelstm_forward_typed; an N-ary slot is one stack step, one
+ * contraction for all its 3 + N gates and one cell update.
+ *
+ * Asynchronous like jitdb_treelstm_forward_typed unless the table holds an N-ary cell: then the call
+ * waits for the stream once at its end and returns JITDB_E_ARITY if some node under an N-ary cell has more
+ * than N children (its surplus children were left out; h_out, c_out are then not to be used).
+ */
+typedef enum { JITDB_CELL_CHILDSUM = 0, JITDB_CELL_NARY = 1 } jitdb_cell_kind;
+#define JITDB_MAX_NARY 4
+typedef struct jitdb_cell {
+    int32_t kind;      /* jitdb_cell_kind */
+    int32_t arity;     /* JITDB_CELL_NARY: N; ignored for JITDB_CELL_CHILDSUM */
+    const void *W;     /* dev, dtype elements */
+    const void *U;     /* dev, dtype elements */
+    const float *b;    /* dev, fp32 */
+} jitdb_cell_t;
+size_t jitdb_treelstm_cells_workspace_bytes(int64_t n_nodes, int64_t n_edges, int32_t D, int32_t H,
+                                            jitdb_dtype dtype, const jitdb_cell_t *cells, int32_t n_sig);
+int jitdb_treelstm_forward_cells(const void *x, const jitdb_cell_t *cells, int32_t n_sig,
                                  int32_t D, int32_t H, jitdb_dtype dtype,
                                  const jitdb_schedule_t *s, const jitdb_slots_t *slots,
                                  void *h_out, float *c_out,

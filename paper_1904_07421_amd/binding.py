@@ -17,6 +17,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libjitdb.so")
 
 JITDB_F32 = 0
+JITDB_CELL_CHILDSUM = 0
+JITDB_CELL_NARY = 1
+JITDB_MAX_NARY = 4
 JITDB_BF16 = 1
 
 _c_i32p = ctypes.POINTER(ctypes.c_int32)
@@ -54,6 +57,11 @@ class _SlotsStruct(ctypes.Structure):
 
 
 K_CLASSES = ("pack", "stack", "leaf", "internal", "proj", "thin_leaf", "thin_internal", "thin_proj")
+
+
+class _CellStruct(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int32), ("arity", ctypes.c_int32),
+                ("W", ctypes.c_void_p), ("U", ctypes.c_void_p), ("b", ctypes.c_void_p)]
 
 
 class _ProfileStruct(ctypes.Structure):
@@ -146,6 +154,15 @@ def load_library():
         ctypes.POINTER(_ScheduleStruct), ctypes.POINTER(_SlotsStruct), ctypes.c_void_p, ctypes.c_void_p,
         ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     lib.jitdb_treelstm_packed_bytes.restype = ctypes.c_size_t
+    lib.jitdb_treelstm_cells_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
+                                                         ctypes.c_int32, ctypes.c_int, ctypes.POINTER(_CellStruct),
+                                                         ctypes.c_int32]
+    lib.jitdb_treelstm_cells_workspace_bytes.restype = ctypes.c_size_t
+    lib.jitdb_treelstm_forward_cells.argtypes = [
+        ctypes.c_void_p, ctypes.POINTER(_CellStruct), ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int,
+        ctypes.POINTER(_ScheduleStruct), ctypes.POINTER(_SlotsStruct), ctypes.c_void_p, ctypes.c_void_p,
+        ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.jitdb_treelstm_forward_cells.restype = ctypes.c_int
     lib.jitdb_treelstm_packed_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int, ctypes.c_int32]
     lib.jitdb_treelstm_pack.restype = ctypes.c_int
     lib.jitdb_treelstm_pack.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
@@ -682,6 +699,77 @@ def jitdb_treelstm_forward_typed(x, W, U, b, schedule: TypedSchedule, stream=Non
     with torch.cuda.device(x.device):
         code = lib.jitdb_treelstm_forward_typed(
             x.data_ptr() if n else None, W.data_ptr(), U.data_ptr(), b.data_ptr(), D, H, dt,
+            ctypes.byref(schedule.struct), ctypes.byref(schedule.slots),
+            h.data_ptr() if n else None, c.data_ptr() if n else None,
+            workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
+    _check(code)
+    return h, c
+
+
+def _cell_array(cells, x, D: int, H: int):
+    """cells: a sequence of (kind, arity, W, U, b).  Returns the ctypes array for the library."""
+    import torch
+    arr = (_CellStruct * len(cells))()
+    for t, (kind, arity, W, U, b) in enumerate(cells):
+        if kind not in (JITDB_CELL_CHILDSUM, JITDB_CELL_NARY):
+            raise ValueError(f"cell {t}: unknown kind {kind}")
+        rows = 4 * H if kind == JITDB_CELL_CHILDSUM else (3 + arity) * H
+        cols = H if kind == JITDB_CELL_CHILDSUM else arity * H
+        for v, name in ((W, "W"), (U, "U"), (b, "b")):
+            if not v.is_cuda or not v.is_contiguous():
+                raise TypeError(f"cell {t}: {name} must be a contiguous CUDA tensor")
+        if W.dtype != x.dtype or U.dtype != x.dtype or b.dtype != torch.float32:
+            raise TypeError(f"cell {t}: W, U must have x's dtype and b must be float32")
+        if tuple(W.shape) != (rows, D) or tuple(U.shape) != (rows, cols) or tuple(b.shape) != (rows,):
+            raise ValueError(f"cell {t}: W, U, b must be [{rows}, {D}], [{rows}, {cols}], [{rows}]")
+        arr[t].kind, arr[t].arity = kind, arity if kind == JITDB_CELL_NARY else 0
+        arr[t].W, arr[t].U, arr[t].b = W.data_ptr(), U.data_ptr(), b.data_ptr()
+    return arr
+
+
+def jitdb_treelstm_cells_workspace_bytes(n_nodes: int, n_edges: int, D: int, H: int, dtype: int, cells) -> int:
+    """cells: a sequence of (kind, arity) pairs (weights are not needed to size the workspace)."""
+    arr = (_CellStruct * len(cells))()
+    for t, c in enumerate(cells):
+        arr[t].kind, arr[t].arity = c[0], c[1]
+    return int(load_library().jitdb_treelstm_cells_workspace_bytes(n_nodes, n_edges, D, H, dtype, arr, len(cells)))
+
+
+def jitdb_treelstm_forward_cells(x, cells, schedule: TypedSchedule, stream=None, workspace=None,
+                                 out: Optional[Tuple] = None):
+    """x [N, D]; cells: one (kind, arity, W, U, b) per signature of the schedule, kind JITDB_CELL_CHILDSUM
+    (W [4H, D], U [4H, H], b [4H]) or JITDB_CELL_NARY (W [(3+N)H, D], U [(3+N)H, N*H], b [(3+N)H]).
+    H is taken from the first cell's U.  Returns (h, c) as jitdb_treelstm_forward."""
+    import torch
+    lib = load_library()
+    if x.dtype == torch.float32:
+        dt = JITDB_F32
+    elif x.dtype == torch.bfloat16:
+        dt = JITDB_BF16
+    else:
+        raise TypeError("x must be float32 or bfloat16")
+    if not x.is_cuda or not x.is_contiguous():
+        raise TypeError("x must be a contiguous CUDA tensor")
+    n, T = schedule.n_nodes, schedule.n_sig
+    if len(cells) != T:
+        raise ValueError("one cell per signature of the schedule")
+    kind0, arity0, _, U0, _ = cells[0]
+    H = U0.shape[0] // (4 if kind0 == JITDB_CELL_CHILDSUM else 3 + arity0)
+    D = cells[0][2].shape[1]
+    if x.shape != (n, D):
+        raise ValueError("shape mismatch between x and the schedule")
+    arr = _cell_array(cells, x, D, H)
+    if out is None:
+        h = _empty(stream, (n, H), dtype=x.dtype, device=x.device)
+        c = _empty(stream, (n, H), dtype=torch.float32, device=x.device)
+    else:
+        h, c = out
+    need = int(lib.jitdb_treelstm_cells_workspace_bytes(n, schedule.n_edges, D, H, dt, arr, T))
+    if workspace is None:
+        workspace = _empty(stream, max(need, 256), dtype=torch.uint8, device=x.device)
+    with torch.cuda.device(x.device):
+        code = lib.jitdb_treelstm_forward_cells(
+            x.data_ptr() if n else None, arr, T, D, H, dt,
             ctypes.byref(schedule.struct), ctypes.byref(schedule.slots),
             h.data_ptr() if n else None, c.data_ptr() if n else None,
             workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))

@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libjitdb.so")
-SOURCES = ["schedule.hip", "forward.hip", "level256.hip", "backward.hip", "cache.hip", "probe.hip", "api.hip"]
+SOURCES = ["schedule.hip", "forward.hip", "level256.hip", "cells.hip", "backward.hip", "cache.hip", "probe.hip", "api.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

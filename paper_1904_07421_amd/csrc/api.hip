@@ -15,6 +15,7 @@ extern "C" const char *jitdb_strerror(int code) {
         case JITDB_E_SCHEDULE: return "schedule is incomplete or does not match the call";
         case JITDB_E_SIGNATURE: return "a signature is outside [0, n_sig)";
         case JITDB_E_NOMEM: return "a host-side allocation failed";
+        case JITDB_E_ARITY: return "a node has more children than its cell has child positions";
         default: return "unknown jitdb status";
     }
 }

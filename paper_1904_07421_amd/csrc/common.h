@@ -98,7 +98,8 @@ enum KbEpilogue : int {
     KB_EPI_DX_DHS = 0,       // col < D: out0[node[row] * D + col] = v (fp32), else out1[node[row] * H + col - D] = v
                              // (in the operands' element type)
     KB_EPI_ATOMIC_ACC = 1,   // atomicAdd(out0[row * ldc + col], v), fp32
-    KB_EPI_STORE = 2         // out0[row * ldc + col] = v, in the operands' element type
+    KB_EPI_STORE = 2,        // out0[row * ldc + col] = v, in the operands' element type
+    KB_EPI_STORE_F32 = 3     // out0[row * ldc + col] = v, fp32 whatever the operands are
 };
 struct KbGemm {
     const void *A; int64_t a_rows_alloc; int M;

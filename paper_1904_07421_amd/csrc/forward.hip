@@ -740,7 +740,8 @@ gemm_kb_kernel(LevelArgs a, const KbEpiArgs e) {
     float *region = reinterpret_cast<float *>(lds) + wave * (32 * kStride);
     const int c4 = (lane & 31) * 4;
     const int col = col_tile * kBN + wn * 128 + c4;
-    const bool vec_ok = e.kind == KB_EPI_STORE ? (e.ldc & 3) == 0 : ((e.D & 3) == 0 && (e.H & 3) == 0);
+    const bool vec_ok = (e.kind == KB_EPI_STORE || e.kind == KB_EPI_STORE_F32) ? (e.ldc & 3) == 0
+                                                                               : ((e.D & 3) == 0 && (e.H & 3) == 0);
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
 #pragma unroll
@@ -758,7 +759,16 @@ gemm_kb_kernel(LevelArgs a, const KbEpiArgs e) {
             if (row >= e.M || col >= e.N) continue;
             const float4 q = *reinterpret_cast<const float4 *>(region + rl * kStride + c4);
             const float f[4] = {q.x, q.y, q.z, q.w};
-            if (e.kind == KB_EPI_STORE) {
+            if (e.kind == KB_EPI_STORE_F32) {
+                float *dst = static_cast<float *>(e.out0) + (int64_t)row * e.ldc + col;
+                if (vec_ok && col + 4 <= e.N) {
+                    *reinterpret_cast<float4 *>(dst) = q;
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (col + j < e.N) dst[j] = f[j];
+                }
+            } else if (e.kind == KB_EPI_STORE) {
                 T *dst = static_cast<T *>(e.out0) + (int64_t)row * e.ldc + col;
                 if (vec_ok && col + 4 <= e.N) {
                     if constexpr (sizeof(T) == 4) {
@@ -1037,6 +1047,12 @@ struct ForwardWs {
     float *cs;    // nullptr when c_out can serve (H == Hq)
     int4 *tiles;  // tile tables of one typed level: cell batches, then projection batches (nullptr with one cell)
     int64_t tiles_each;
+    // tables that hold N-ary cells (jitdb_treelstm_forward_cells): one slot's stacked input and
+    // pre-activations, each such cell's packed weights, the flag for nodes with too many children
+    void *nary_A;
+    float *nary_Z;
+    void *nary_B[JITDB_MAX_SIGNATURES];
+    int *nary_err;
     size_t bytes;
 };
 
@@ -1067,9 +1083,10 @@ size_t packed_w_bytes(const Dims &d) { return (size_t)d.NPU * (d.Dp + d.Hp) * d.
 // the 256 x 256 tile kernel (bf16, one cell) reads the weights in a second, fragment-major layout
 bool has_fragment_copy(const Dims &d, int n_sig) { return d.esz == 2 && n_sig == 1; }
 
-ForwardWs carve_forward_ws(int64_t n, int64_t e, const Dims &d, void *base, int n_sig = 1) {
+ForwardWs carve_forward_ws(int64_t n, int64_t e, const Dims &d, void *base, int n_sig = 1,
+                           const jitdb_cell_t *cells = nullptr) {
     Carver c(base);
-    ForwardWs w;
+    ForwardWs w = {};
     (void)e;
     w.Bp = c.take<char>(packed_w_bytes(d) * n_sig);
     w.bp = c.take<float>((size_t)d.NP * n_sig);
@@ -1082,6 +1099,17 @@ ForwardWs carve_forward_ws(int64_t n, int64_t e, const Dims &d, void *base, int 
     w.cs = (d.H == d.Hq) ? nullptr : c.take<float>((size_t)n * d.Hq);
     w.tiles_each = n / kDmaBM + (int64_t)n_sig * n_sig + 1;
     w.tiles = n_sig > 1 ? c.take<int4>((size_t)(2 * w.tiles_each)) : nullptr;
+    int n_max = 0;
+    for (int t = 0; cells && t < n_sig; ++t)
+        if (cells[t].kind == JITDB_CELL_NARY) {
+            n_max = cells[t].arity > n_max ? cells[t].arity : n_max;
+            w.nary_B[t] = c.take<char>(nary_packed_bytes(d.D, d.H, d.Dp, d.Hp, cells[t].arity, d.esz));
+        }
+    if (n_max > 0) {
+        w.nary_A = c.take<char>((size_t)(n + kRowPad) * (d.Dp + (size_t)n_max * d.Hp) * d.esz);
+        w.nary_Z = c.take<float>((size_t)n * (3 + n_max) * d.H);
+        w.nary_err = c.take<int>(1);
+    }
     w.bytes = c.off;
     return w;
 }
@@ -1097,9 +1125,12 @@ bool dims_ok(int64_t n, int64_t e, int32_t D, int32_t H, int dtype) {
 // One batched evaluation per slot of the table, levels in ascending order.  Without `slots` a
 // level is one slot and there is one cell; with it, slot (l, t) is evaluated by cell t (its
 // own packed weights), and the records keep every row inside its slot.
+// With `cells` (one per signature) every signature names a cell of its own TYPE: child-sum cells
+// take the path of this file, N-ary cells the three steps of cells.hip; W, U, b then come from the
+// cells.
 template <typename T, bool SAVE>
 int run_forward(const void *x, const void *W, const void *U, const float *b, const Dims &d,
-                const jitdb_schedule_t *s, const jitdb_slots_t *slots,
+                const jitdb_schedule_t *s, const jitdb_slots_t *slots, const jitdb_cell_t *cells,
                 void *h_out, float *c_out, void *gates, void *fgate,
                 const ForwardWs &w_in, const void *packed, hipStream_t st) {
     // weights packed by an earlier jitdb_treelstm_pack are used where they lie
@@ -1114,15 +1145,23 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
     const int L = s->n_levels;
     const int n_sig = slots ? slots->n_sig : 1;
     const int32_t *sp = slots ? slots->host_slot_ptr : s->host_level_ptr;
+    const jitdb_dtype dtype = std::is_same<T, float>::value ? JITDB_F32 : JITDB_BF16;
+    auto is_nary = [&](int t) { return cells != nullptr && t >= 0 && cells[t].kind == JITDB_CELL_NARY; };
+    bool any_nary = false;
+    for (int t = 0; t < n_sig; ++t) any_nary = any_nary || is_nary(t);
 
     {   // row records and packed weights (one launch; further cells' weights one launch each)
         const int64_t total = (int64_t)d.NPU * (d.Dp + d.Hp);
         const unsigned pack_grid = (unsigned)(ceil_div(total, kThreads) < 4096 ? ceil_div(total, kThreads) : 4096);
         auto pack_args = [&](int t) {
             PackArgs p;
-            p.W = static_cast<const T *>(W) + (size_t)t * 4 * d.H * d.D;
-            p.U = static_cast<const T *>(U) + (size_t)t * 4 * d.H * d.H;
-            p.b = b + (size_t)t * 4 * d.H;
+            if (cells) {
+                p.W = cells[t].W; p.U = cells[t].U; p.b = cells[t].b;
+            } else {
+                p.W = static_cast<const T *>(W) + (size_t)t * 4 * d.H * d.D;
+                p.U = static_cast<const T *>(U) + (size_t)t * 4 * d.H * d.H;
+                p.b = b + (size_t)t * 4 * d.H;
+            }
             p.D = d.D; p.H = d.H; p.Dp = d.Dp; p.Hp = d.Hp; p.NP = d.NP; p.NPU = d.NPU;
             p.Bp = static_cast<char *>(w.Bp) + packed_w_bytes(d) * t;
             p.bp = w.bp + (size_t)d.NP * t;
@@ -1132,15 +1171,24 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
         const int n_windows = (int)ceil_div(s->n_nodes, kRecWindow);
         {
             ScopedLaunchTimer tm(JITDB_K_PACK, 0, st);
-            prepare_kernel<T><<<(unsigned)n_windows + (packed ? 0u : pack_grid), kThreads, 0, st>>>(
+            prepare_kernel<T><<<(unsigned)n_windows + ((packed || is_nary(0)) ? 0u : pack_grid), kThreads, 0, st>>>(
                 s->perm, slots ? slots->key : s->height, s->child_ptr, s->child_idx, w.row_rec, (int)s->n_nodes,
                 n_windows, pack_args(0));
             JITDB_LAUNCH_CHECK();
         }
         for (int t = 1; t < n_sig && !packed; ++t) {
+            if (is_nary(t)) continue;
             ScopedLaunchTimer tm(JITDB_K_PACK, 0, st);
             pack_weights_kernel<T><<<pack_grid, kThreads, 0, st>>>(pack_args(t));
             JITDB_LAUNCH_CHECK();
+        }
+        for (int t = 0; t < n_sig; ++t) {
+            if (!is_nary(t)) continue;
+            ScopedLaunchTimer tm(JITDB_K_PACK, 0, st);
+            // (every such launch also clears the flag for nodes with too many children)
+            const int rc = nary_pack(dtype, cells[t].W, cells[t].U, d.D, d.H, d.Dp, d.Hp, cells[t].arity, w.nary_B[t],
+                                     w.nary_err, st);
+            if (rc != JITDB_OK) return rc;
         }
     }
 
@@ -1185,7 +1233,7 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
                 for (int p = 0; p < n_sig; ++p)
                     n_proj_tiles += (int)ceil_div(sub_begin(l, t, p + 1) - sub_begin(l, t, p), kDmaBM);
         }
-        if (used > 1 && lvl_rows > kThinMaxRows) {
+        if (used > 1 && lvl_rows > kThinMaxRows && !any_nary) {
             segs.push_back({l, -1, slot_begin(l, 0), lvl_rows, n_tiles, n_proj_tiles});
         } else {
             for (int t = 0; t < n_sig; ++t) {
@@ -1229,56 +1277,66 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
             JITDB_LAUNCH_CHECK();
             a.tiles = w.tiles;
         }
-        if (!stacked_ahead) {
-            const StackArgs sa = stack_args(segs[i]);
-            ScopedLaunchTimer tm(JITDB_K_STACK, n_rows, st);
-            if (l == 0)
-                stack_kernel<T, false><<<stack_blocks(segs[i]), kThreads, 0, st>>>(
-                    static_cast<const T *>(sa.x), sa.D, sa.Dp, static_cast<const T *>(sa.hs), sa.Hp, sa.row_rec,
-                    sa.child_idx, static_cast<T *>(sa.A), sa.n_rows, sa.n_rows_alloc);
-            else
-                stack_kernel<T, true><<<stack_blocks(segs[i]), kThreads, 0, st>>>(
-                    static_cast<const T *>(sa.x), sa.D, sa.Dp, static_cast<const T *>(sa.hs), sa.Hp, sa.row_rec,
-                    sa.child_idx, static_cast<T *>(sa.A), sa.n_rows, sa.n_rows_alloc);
+        if (is_nary(sig)) {
+            // a slot of N-ary nodes: stack, one contraction for all 3 + N gates, cell update (cells.hip)
+            NarySlot ns;
+            ns.x = x; ns.row_rec = a.row_rec; ns.A = w.nary_A; ns.Bn = w.nary_B[sig]; ns.b = cells[sig].b;
+            ns.Z = w.nary_Z; ns.err = w.nary_err; ns.n_rows = n_rows; ns.N = cells[sig].arity;
+            ScopedLaunchTimer tm(l == 0 ? JITDB_K_THIN_LEAF : JITDB_K_THIN_INTERNAL, n_rows, st);
+            const int rc = run_nary_slot(dtype, a, ns, st);
+            if (rc != JITDB_OK) return rc;
+        } else {
+            if (!stacked_ahead) {
+                const StackArgs sa = stack_args(segs[i]);
+                ScopedLaunchTimer tm(JITDB_K_STACK, n_rows, st);
+                if (l == 0)
+                    stack_kernel<T, false><<<stack_blocks(segs[i]), kThreads, 0, st>>>(
+                        static_cast<const T *>(sa.x), sa.D, sa.Dp, static_cast<const T *>(sa.hs), sa.Hp, sa.row_rec,
+                        sa.child_idx, static_cast<T *>(sa.A), sa.n_rows, sa.n_rows_alloc);
+                else
+                    stack_kernel<T, true><<<stack_blocks(segs[i]), kThreads, 0, st>>>(
+                        static_cast<const T *>(sa.x), sa.D, sa.Dp, static_cast<const T *>(sa.hs), sa.Hp, sa.row_rec,
+                        sa.child_idx, static_cast<T *>(sa.A), sa.n_rows, sa.n_rows_alloc);
+                JITDB_LAUNCH_CHECK();
+            }
+            stacked_ahead = false;
+            // Levels too small to give every CU a 256 x 256 tile go to the thin kernel.
+            const bool thin = n_rows <= kThinMaxRows;
+            if (thin) {
+                a.n_col_tiles = n_unit_tiles;
+                a.n_tiles = (int)ceil_div(n_rows, 32) * a.n_col_tiles;
+                a.n_blocks = a.n_tiles;
+            } else {
+                a.n_col_tiles = d.NP / kBN;
+                a.n_tiles = 0;
+                a.n_row_tiles = row_tiles;
+                a.n_blocks = 8 * (int)ceil_div(row_tiles, 8) * a.n_col_tiles;
+            }
+            {
+                ScopedLaunchTimer tm(thin ? (l == 0 ? JITDB_K_THIN_LEAF : JITDB_K_THIN_INTERNAL)
+                                          : (l == 0 ? JITDB_K_LEAF : JITDB_K_INTERNAL), n_rows, st);
+                if (thin) {
+                    if (l == 0)
+                        thin_kernel<T, MODE_LEAF, SAVE><<<a.n_blocks, kThinWaves * 64, 0, st>>>(a);
+                    else
+                        thin_kernel<T, MODE_INTERNAL, SAVE><<<a.n_blocks, kThinWaves * 64, 0, st>>>(a);
+                } else if (may256 && tile256_applies(l == 0 ? MODE_LEAF : MODE_INTERNAL, a)) {
+                    const int rc = launch_tile256(l == 0 ? MODE_LEAF : MODE_INTERNAL, a, st);
+                    if (rc != JITDB_OK) return rc;
+                } else if (grouped) {
+                    if (l == 0)
+                        level_kernel<T, MODE_LEAF, false, true><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
+                    else
+                        level_kernel<T, MODE_INTERNAL, false, true><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
+                } else {
+                    if (l == 0)
+                        level_kernel<T, MODE_LEAF, SAVE><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
+                    else
+                        level_kernel<T, MODE_INTERNAL, SAVE><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
+                }
+            }
             JITDB_LAUNCH_CHECK();
         }
-        stacked_ahead = false;
-        // Levels too small to give every CU a 256 x 256 tile go to the thin kernel.
-        const bool thin = n_rows <= kThinMaxRows;
-        if (thin) {
-            a.n_col_tiles = n_unit_tiles;
-            a.n_tiles = (int)ceil_div(n_rows, 32) * a.n_col_tiles;
-            a.n_blocks = a.n_tiles;
-        } else {
-            a.n_col_tiles = d.NP / kBN;
-            a.n_tiles = 0;
-            a.n_row_tiles = row_tiles;
-            a.n_blocks = 8 * (int)ceil_div(row_tiles, 8) * a.n_col_tiles;
-        }
-        {
-            ScopedLaunchTimer tm(thin ? (l == 0 ? JITDB_K_THIN_LEAF : JITDB_K_THIN_INTERNAL)
-                                      : (l == 0 ? JITDB_K_LEAF : JITDB_K_INTERNAL), n_rows, st);
-            if (thin) {
-                if (l == 0)
-                    thin_kernel<T, MODE_LEAF, SAVE><<<a.n_blocks, kThinWaves * 64, 0, st>>>(a);
-                else
-                    thin_kernel<T, MODE_INTERNAL, SAVE><<<a.n_blocks, kThinWaves * 64, 0, st>>>(a);
-            } else if (may256 && tile256_applies(l == 0 ? MODE_LEAF : MODE_INTERNAL, a)) {
-                const int rc = launch_tile256(l == 0 ? MODE_LEAF : MODE_INTERNAL, a, st);
-                if (rc != JITDB_OK) return rc;
-            } else if (grouped) {
-                if (l == 0)
-                    level_kernel<T, MODE_LEAF, false, true><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
-                else
-                    level_kernel<T, MODE_INTERNAL, false, true><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
-            } else {
-                if (l == 0)
-                    level_kernel<T, MODE_LEAF, SAVE><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
-                else
-                    level_kernel<T, MODE_INTERNAL, SAVE><<<a.n_blocks, kDmaThreads, 0, st>>>(a);
-            }
-        }
-        JITDB_LAUNCH_CHECK();
         if (l + 1 >= L) continue;     // the top level has no parents to project for
 
         // Forget projections of these nodes (roots' rows go unused), with the PARENT's weights.
@@ -1296,12 +1354,13 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
         // one launch per non-empty sub-slot (a single one without a typed table)
         const int n_sub = slots ? n_sig : 1;
         int last_sub = -1;
+        // (an N-ary parent needs no projection of its children: its forget gates are part of its own contraction)
         for (int p = 0; p < n_sub; ++p)
-            if (!slots || sub_begin(l, sig, p + 1) > sub_begin(l, sig, p)) last_sub = p;
+            if ((!slots || sub_begin(l, sig, p + 1) > sub_begin(l, sig, p)) && !is_nary(slots ? p : -1)) last_sub = p;
         for (int p = 0; p < n_sub; ++p) {
             const int begin = slots ? sub_begin(l, sig, p) : segs[i].begin;
             const int rows = slots ? sub_begin(l, sig, p + 1) - begin : n_rows;
-            if (rows <= 0) continue;
+            if (rows <= 0 || is_nary(slots ? p : -1)) continue;
             a.Bp = static_cast<char *>(w.Bp) + packed_w_bytes(d) * p;
             a.bp = w.bp + (size_t)d.NP * p;
             a.row_rec = w.row_rec + 2 * (int64_t)begin;
@@ -1315,7 +1374,8 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
                 // the stack step of the next slot, if that is thin too, rides along with the slot's
                 // last projection (the level kernel above was the stack buffer's only reader); its
                 // rows are counted with this launch's class
-                if (p == last_sub && i + 1 < segs.size() && segs[i + 1].l > 0 && segs[i + 1].rows <= kThinMaxRows) {
+                if (p == last_sub && i + 1 < segs.size() && segs[i + 1].l > 0 && segs[i + 1].rows <= kThinMaxRows &&
+                    !is_nary(segs[i + 1].sig)) {
                     thin_proj_stack_kernel<T><<<a.n_blocks + stack_blocks(segs[i + 1]), kThinWaves * 64, 0, st>>>(
                         a, stack_args(segs[i + 1]));
                     stacked_ahead = true;
@@ -1445,16 +1505,22 @@ namespace {
 int forward_entry(const void *x, const void *W, const void *U, const float *b, int32_t D, int32_t H,
                   jitdb_dtype dtype, const jitdb_schedule_t *s, const jitdb_slots_t *slots,
                   void *h_out, float *c_out, void *gates, void *fgate, bool save,
-                  void *workspace, size_t workspace_bytes, void *hip_stream, const void *packed = nullptr) {
+                  void *workspace, size_t workspace_bytes, void *hip_stream, const void *packed = nullptr,
+                  const jitdb_cell_t *cells = nullptr) {
     if (!s) return JITDB_E_NULL;
     const int n_sig = slots ? slots->n_sig : 1;
     if (n_sig < 1 || n_sig > JITDB_MAX_SIGNATURES) return JITDB_E_BADARG;
+    for (int t = 0; cells && t < n_sig; ++t) {
+        if (cells[t].kind != JITDB_CELL_CHILDSUM && cells[t].kind != JITDB_CELL_NARY) return JITDB_E_BADARG;
+        if (cells[t].kind == JITDB_CELL_NARY && (cells[t].arity < 1 || cells[t].arity > JITDB_MAX_NARY)) return JITDB_E_BADARG;
+        if (!cells[t].W || !cells[t].U || !cells[t].b) return JITDB_E_NULL;
+    }
     drop_stale_hip_error();
     const int64_t n = s->n_nodes;
     if (!dims_ok(n, s->n_edges, D, H, (int)dtype)) return JITDB_E_BADARG;
     if (n == 0) return JITDB_OK;
     if (!x || !h_out || !c_out || !workspace) return JITDB_E_NULL;
-    if (!packed && (!W || !U || !b)) return JITDB_E_NULL;
+    if (!packed && !cells && (!W || !U || !b)) return JITDB_E_NULL;
     if (packed && (reinterpret_cast<uintptr_t>(packed) & 255) != 0) return JITDB_E_BADARG;
     if (save && (!gates || !fgate)) return JITDB_E_NULL;
     if (!s->perm || !s->height || !s->child_ptr || !s->child_idx || !s->host_level_ptr) return JITDB_E_NULL;
@@ -1479,17 +1545,17 @@ int forward_entry(const void *x, const void *W, const void *U, const float *b, i
     }
 
     const Dims d = make_dims(D, H, dtype);
-    const ForwardWs w = carve_forward_ws(n, s->n_edges, d, workspace, n_sig);
+    const ForwardWs w = carve_forward_ws(n, s->n_edges, d, workspace, n_sig, cells);
     if (workspace_bytes < w.bytes) return JITDB_E_WORKSPACE;
     hipStream_t st = (hipStream_t)hip_stream;
     // run_forward keeps its list of launches in a std::vector: an allocation failure becomes a status
     JITDB_ABI_TRY
     if (dtype == JITDB_F32) {
-        if (save) return run_forward<float, true>(x, W, U, b, d, s, slots, h_out, c_out, gates, fgate, w, packed, st);
-        return run_forward<float, false>(x, W, U, b, d, s, slots, h_out, c_out, nullptr, nullptr, w, packed, st);
+        if (save) return run_forward<float, true>(x, W, U, b, d, s, slots, cells, h_out, c_out, gates, fgate, w, packed, st);
+        return run_forward<float, false>(x, W, U, b, d, s, slots, cells, h_out, c_out, nullptr, nullptr, w, packed, st);
     }
-    if (save) return run_forward<bf16_t, true>(x, W, U, b, d, s, slots, h_out, c_out, gates, fgate, w, packed, st);
-    return run_forward<bf16_t, false>(x, W, U, b, d, s, slots, h_out, c_out, nullptr, nullptr, w, packed, st);
+    if (save) return run_forward<bf16_t, true>(x, W, U, b, d, s, slots, cells, h_out, c_out, gates, fgate, w, packed, st);
+    return run_forward<bf16_t, false>(x, W, U, b, d, s, slots, cells, h_out, c_out, nullptr, nullptr, w, packed, st);
     JITDB_ABI_CATCH
 }
 
@@ -1566,6 +1632,38 @@ extern "C" int jitdb_treelstm_forward_typed(const void *x, const void *W, const 
     if (!slots) return JITDB_E_NULL;
     return forward_entry(x, W, U, b, D, H, dtype, s, slots, h_out, c_out, nullptr, nullptr, false,
                          workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" size_t jitdb_treelstm_cells_workspace_bytes(int64_t n_nodes, int64_t n_edges, int32_t D, int32_t H,
+                                                       jitdb_dtype dtype, const jitdb_cell_t *cells, int32_t n_sig) {
+    if (!cells || !dims_ok(n_nodes, n_edges, D, H, (int)dtype) || n_sig < 1 || n_sig > JITDB_MAX_SIGNATURES) return 0;
+    for (int t = 0; t < n_sig; ++t)
+        if (cells[t].kind == JITDB_CELL_NARY && (cells[t].arity < 1 || cells[t].arity > JITDB_MAX_NARY)) return 0;
+    const Dims d = make_dims(D, H, dtype);
+    return carve_forward_ws(n_nodes, n_edges, d, nullptr, n_sig, cells).bytes;
+}
+
+extern "C" int jitdb_treelstm_forward_cells(const void *x, const jitdb_cell_t *cells, int32_t n_sig,
+                                            int32_t D, int32_t H, jitdb_dtype dtype,
+                                            const jitdb_schedule_t *s, const jitdb_slots_t *slots,
+                                            void *h_out, float *c_out,
+                                            void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (!slots || !cells) return JITDB_E_NULL;
+    if (n_sig != slots->n_sig) return JITDB_E_BADARG;
+    const int rc = forward_entry(x, nullptr, nullptr, nullptr, D, H, dtype, s, slots, h_out, c_out, nullptr, nullptr,
+                                 false, workspace, workspace_bytes, hip_stream, nullptr, cells);
+    if (rc != JITDB_OK || !s || s->n_nodes == 0) return rc;
+    bool any_nary = false;
+    for (int t = 0; t < n_sig; ++t) any_nary = any_nary || cells[t].kind == JITDB_CELL_NARY;
+    if (!any_nary) return JITDB_OK;
+    // a node with more children than its cell has positions: reported after the work has run
+    const Dims d = make_dims(D, H, dtype);
+    const ForwardWs w = carve_forward_ws(s->n_nodes, s->n_edges, d, workspace, n_sig, cells);
+    int flag = 0;
+    hipStream_t st = (hipStream_t)hip_stream;
+    JITDB_HIP_CHECK(hipMemcpyAsync(&flag, w.nary_err, sizeof(int), hipMemcpyDeviceToHost, st));
+    JITDB_HIP_CHECK(hipStreamSynchronize(st));
+    return flag ? JITDB_E_ARITY : JITDB_OK;
 }
 
 extern "C" int jitdb_treelstm_forward_train(const void *x, const void *W, const void *U, const float *b,

@@ -375,6 +375,22 @@ __device__ __forceinline__ void proj_pass(const LevelArgs &a, const floatx16 (&a
 
 }  // namespace
 
+// cells.hip: the N-ary cell (second operator type of the table)
+struct NarySlot {
+    const void *x;          // [N, D] all nodes' inputs, rows by node id
+    const int4 *row_rec;    // the slot's row records (two int4 per row)
+    void *A;                // workspace: the slot's stacked input, K-blocked
+    const void *Bn;         // the cell's packed weights (nary_pack)
+    const float *b;         // the cell's bias [(3 + N) H]
+    float *Z;               // workspace: pre-activations [n_rows, (3 + N) H]
+    int *err;               // device flag: set when a node has more children than the cell has positions
+    int n_rows, N;
+};
+size_t nary_packed_bytes(int D, int H, int Dp, int Hp, int N, size_t esz);
+int nary_pack(jitdb_dtype dtype, const void *W, const void *U, int D, int H, int Dp, int Hp, int N, void *Bn,
+              int *err_to_clear, hipStream_t st);
+int run_nary_slot(jitdb_dtype dtype, const LevelArgs &a, const NarySlot &s, hipStream_t st);
+
 // level256.hip
 bool tile256_applies(int mode, const LevelArgs &a);
 int launch_tile256(int mode, LevelArgs a, hipStream_t st);

@@ -33,8 +33,8 @@ def test_every_declared_symbol_is_exported(lib):
 def test_strerror_and_version(lib):
     import paper_1904_07421_amd as J
     assert J.jitdb_strerror(0) == "ok"
-    seen = {J.jitdb_strerror(c) for c in range(-9, 1)}
-    assert len(seen) == 10
+    seen = {J.jitdb_strerror(c) for c in range(-10, 1)}
+    assert len(seen) == 11
     assert "unknown" in J.jitdb_strerror(-99)
     assert re.fullmatch(r"\d+\.\d+", J.jitdb_version())
 

@@ -1,0 +1,162 @@
+"""GPU parity of a table whose signatures name cells of different operator type
+(jitdb_treelstm_forward_cells): child-sum and N-ary Tree-LSTM cells mixed freely along edges, against
+oracle/treelstm_cells_oracle.py (pinned in tests/test_oracle_cells.py), within the forward's tolerances."""
+import numpy as np
+import pytest
+
+from oracle import treelstm_cells_oracle as C
+from workloads import (bounded_arity_forest, arity_signatures, make_cell_values, make_values, star_forest,
+                       chain_forest)
+from gpu_util import dev_parent, bf16_tensor
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def _to_dev(a, dtype):
+    """fp32 array -> (device tensor in the run's dtype, the values the device sees as fp32 numpy)."""
+    import torch
+    if dtype == "bf16":
+        return bf16_tensor(a)
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda(), a
+
+
+def _run(parent, sig, positions, x, values, dtype):
+    """Schedule + forward over cells on the GPU.  Returns h, c (fp32 numpy) and the oracle's cells built
+    from the values as the device sees them."""
+    import torch
+    import paper_1904_07421_amd as J
+    sched = J.jitdb_schedule_typed(dev_parent(parent), dev_parent(sig), len(positions))
+    xt, xo = _to_dev(x, dtype)
+    cells, ocells = [], []
+    for N, (W, U, b) in zip(positions, values):
+        Wt, Wo = _to_dev(W, dtype)
+        Ut, Uo = _to_dev(U, dtype)
+        bt = torch.from_numpy(np.ascontiguousarray(b, dtype=np.float32)).cuda()
+        cells.append((J.JITDB_CELL_CHILDSUM if N == 0 else J.JITDB_CELL_NARY, N, Wt, Ut, bt))
+        ocells.append(C.childsum_cell(Wo, Uo, b) if N == 0 else C.nary_cell(N, Wo, Uo, b))
+    h, c = J.jitdb_treelstm_forward_cells(xt, cells, sched)
+    torch.cuda.synchronize()
+    return h.float().cpu().numpy(), c.cpu().numpy(), xo, ocells
+
+
+def _check(parent, sig, positions, D, H, dtype, seed):
+    n = parent.shape[0]
+    x = make_values(1, n, "random", D=D, H=H)[0]
+    values = make_cell_values(positions, D, H, seed)
+    h, c, xo, ocells = _run(parent, sig, positions, x, values, dtype)
+    h0, c0 = C.forward_cells(parent, sig, xo, ocells)
+    dh, dc = np.abs(h - h0).max(), np.abs(c - c0).max()
+    print(f"  N={n} cells={positions} D={D} H={H} {dtype}: max|dh| {dh:.3e} max|dc| {dc:.3e}", flush=True)
+    assert dh <= TOL[dtype] and dc <= TOL[dtype] * max(1.0, np.abs(c0).max())
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_mixed_table_paper_widths(dtype):
+    """Child-sum, binary and ternary cells drawn per node (D = 300, H = 150: padded K and gate widths)."""
+    p = bounded_arity_forest(300, 1, 25, 3, 11)
+    positions = [0, 2, 3]
+    sig = arity_signatures(p, positions, 12)
+    print(f"cells mixed {dtype} N={p.shape[0]}", flush=True)
+    _check(p, sig, positions, 300, 150, dtype, 13)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_binary_cell_alone_many_tiles(dtype):
+    """Binarised trees under one N = 2 cell; the leaf slot spans many row tiles and a ragged tail."""
+    p = bounded_arity_forest(3000, 1, 31, 2, 21)
+    sig = np.zeros(p.shape[0], np.int32)
+    print(f"cells binary {dtype} N={p.shape[0]}", flush=True)
+    _check(p, sig, [2], 48, 40, dtype, 22)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_nary_children_of_childsum_parents_and_back(dtype):
+    """Large slots of both types on every level: the child-sum parents' forget projections of N-ary
+    children and N-ary parents' reads of child-sum children run on the tiled kernels."""
+    p = bounded_arity_forest(2500, 8, 40, 4, 31)
+    positions = [0, 4]
+    sig = arity_signatures(p, positions, 32)
+    print(f"cells both ways {dtype} N={p.shape[0]}", flush=True)
+    _check(p, sig, positions, 64, 64, dtype, 33)
+
+
+def test_all_childsum_cells_equal_the_typed_forward():
+    import torch
+    import paper_1904_07421_amd as J
+    p = bounded_arity_forest(400, 1, 30, 5, 41)
+    from workloads import node_signatures, make_values_typed
+    sig = node_signatures(p, 3, 42)
+    x, W, U, b = make_values_typed(1, p.shape[0], 3, D=40, H=24)
+    sched = J.jitdb_schedule_typed(dev_parent(p), dev_parent(sig), 3)
+    xt, Wt, Ut, bt = (torch.from_numpy(v).cuda() for v in (x, W, U, b))
+    h0, c0 = J.jitdb_treelstm_forward_typed(xt, Wt, Ut, bt, sched)
+    cells = [(J.JITDB_CELL_CHILDSUM, 0, Wt[t].contiguous(), Ut[t].contiguous(), bt[t].contiguous()) for t in range(3)]
+    h1, c1 = J.jitdb_treelstm_forward_cells(xt, cells, sched)
+    torch.cuda.synchronize()
+    assert torch.equal(h0, h1) and torch.equal(c0, c1)
+
+
+def test_tied_nary_weights_give_the_childsum_forward():
+    """Position weights all equal and forget gate l seeing only child l: the N-ary cell computes what
+    the child-sum cell does (the pin of the oracle, here across the two GPU paths)."""
+    import torch
+    import paper_1904_07421_amd as J
+    N, D, H = 3, 36, 20
+    p = bounded_arity_forest(500, 1, 30, N, 51)
+    x, W, U, b = make_values(1, p.shape[0], "random", D=D, H=H)
+    Wn = np.concatenate([W[:3 * H]] + [W[3 * H:]] * N)
+    bn = np.concatenate([b[:3 * H]] + [b[3 * H:]] * N)
+    Un = np.zeros(((3 + N) * H, N * H), np.float32)
+    for l in range(N):
+        Un[:3 * H, l * H:(l + 1) * H] = U[:3 * H]
+        Un[(3 + l) * H:(4 + l) * H, l * H:(l + 1) * H] = U[3 * H:]
+    dp = dev_parent(p)
+    xt = torch.from_numpy(x).cuda()
+    h0, c0 = J.jitdb_treelstm_forward(xt, torch.from_numpy(W).cuda(), torch.from_numpy(U).cuda(),
+                                      torch.from_numpy(b).cuda(), J.jitdb_schedule(dp))
+    sched = J.jitdb_schedule_typed(dp, dev_parent(np.zeros_like(p)), 1)
+    cells = [(J.JITDB_CELL_NARY, N, torch.from_numpy(Wn).cuda(), torch.from_numpy(Un).cuda(), torch.from_numpy(bn).cuda())]
+    h1, c1 = J.jitdb_treelstm_forward_cells(xt, cells, sched)
+    torch.cuda.synchronize()
+    assert (h0 - h1).abs().max().item() <= 2e-4 and (c0 - c1).abs().max().item() <= 2e-4
+
+
+def test_more_children_than_positions_is_reported():
+    import torch
+    import paper_1904_07421_amd as J
+    p = np.concatenate([chain_forest(4, 1), star_forest(5, 1) + 4]).astype(np.int32)
+    p[4] = -1                                                  # the star's root; it has 4 children
+    positions = [2]
+    values = make_cell_values(positions, 16, 8, 61)
+    x = make_values(1, p.shape[0], "random", D=16, H=8)[0]
+    with pytest.raises(J.JitdbError) as e:
+        _run(p, np.zeros_like(p), positions, x, values, "f32")
+    assert e.value.code == -10
+    # the same forest under a cell with enough positions, right after the failed call
+    values = make_cell_values([4], 16, 8, 62)
+    h, c, xo, ocells = _run(p, np.zeros_like(p), [4], x, values, "f32")
+    h0, c0 = C.forward_cells(p, np.zeros_like(p), xo, ocells)
+    assert np.abs(h - h0).max() <= 1e-4 and np.abs(c - c0).max() <= 1e-4
+
+
+def test_argument_checks_and_empty_forest():
+    import torch
+    import paper_1904_07421_amd as J
+    assert J.jitdb_treelstm_cells_workspace_bytes(10, 9, 8, 8, J.JITDB_F32, [(J.JITDB_CELL_NARY, 5)]) == 0
+    assert J.jitdb_treelstm_cells_workspace_bytes(10, 9, 8, 8, J.JITDB_F32, [(J.JITDB_CELL_NARY, 0)]) == 0
+    assert J.jitdb_treelstm_cells_workspace_bytes(10, 9, 8, 8, J.JITDB_F32, [(J.JITDB_CELL_NARY, 2)]) > \
+        J.jitdb_treelstm_cells_workspace_bytes(10, 9, 8, 8, J.JITDB_F32, [(J.JITDB_CELL_CHILDSUM, 0)]) > 0
+    # a forest without nodes
+    p = np.zeros(0, np.int32)
+    sched = J.jitdb_schedule_typed(dev_parent(p), dev_parent(p), 1)
+    W, U, b = make_cell_values([2], 8, 8, 71)[0]
+    cells = [(J.JITDB_CELL_NARY, 2, torch.from_numpy(W).cuda(), torch.from_numpy(U).cuda(), torch.from_numpy(b).cuda())]
+    h, c = J.jitdb_treelstm_forward_cells(torch.zeros((0, 8), device="cuda"), cells, sched)
+    assert h.shape == (0, 8) and c.shape == (0, 8)
+    # the number of cells must be the schedule's number of signatures
+    p = chain_forest(3, 1)
+    sched = J.jitdb_schedule_typed(dev_parent(p), dev_parent(np.zeros_like(p)), 2)
+    with pytest.raises(ValueError):
+        J.jitdb_treelstm_forward_cells(torch.zeros((3, 8), device="cuda"), cells, sched)

@@ -19,6 +19,9 @@ from .forests import (  # noqa: F401
     perfect_kary_tree,
     tree_signatures,
     node_signatures,
+    bounded_arity_forest,
+    arity_signatures,
+    make_cell_values,
     mixed_forest,
     make_values_typed,
 )

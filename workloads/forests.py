@@ -302,3 +302,65 @@ def node_signatures(parent: np.ndarray, n_sig: int, seed: int) -> np.ndarray:
     k = int(has_child.sum())
     sig[has_child] = 1 + rng.integers(0, n_sig - 1, size=k).astype(np.int32)
     return sig
+
+
+# --------------------------------------------------------------------------
+# cells of different type in one table (child-sum next to N-ary cells)
+# --------------------------------------------------------------------------
+def bounded_arity_forest(n_trees: int, nodes_lo: int, nodes_hi: int, max_children: int, seed: int) -> np.ndarray:
+    """Trees of U[nodes_lo, nodes_hi] nodes in which no node has more than max_children children
+    (binarised constituency trees for max_children = 2): node v > 0 of a tree attaches to a uniformly
+    drawn earlier node that still has a free position.  Root first, trees one after another."""
+    rng = np.random.default_rng(seed)
+    parts = []
+    for _ in range(n_trees):
+        n = int(rng.integers(nodes_lo, nodes_hi + 1))
+        par = np.full(n, -1, dtype=np.int64)
+        free = [0]                               # nodes with a free position
+        deg = np.zeros(n, dtype=np.int64)
+        for v in range(1, n):
+            i = int(rng.integers(0, len(free)))
+            p = free[i]
+            par[v] = p
+            deg[p] += 1
+            if deg[p] == max_children:
+                free[i] = free[-1]
+                free.pop()
+            free.append(v)
+        parts.append(par.astype(np.int32))
+    return _concat(parts)
+
+
+def arity_signatures(parent: np.ndarray, positions, seed: int) -> np.ndarray:
+    """sig [N] int32 for a table of len(positions) cells; positions[t] = the number of child positions
+    of cell t (0: any number, a child-sum cell).  Every node draws uniformly among the cells that can
+    take its number of children, so parents and children differ freely."""
+    rng = np.random.default_rng(seed)
+    n = parent.shape[0]
+    arity = np.bincount(parent[parent >= 0], minlength=n)
+    positions = np.asarray(positions)
+    u = rng.random(n)
+    sig = np.empty(n, dtype=np.int32)
+    for a in np.unique(arity):
+        ok = np.flatnonzero((positions == 0) | (positions >= a))
+        if ok.size == 0:
+            raise ValueError(f"no cell can take a node with {a} children")
+        m = arity == a
+        sig[m] = ok[np.minimum((u[m] * ok.size).astype(np.int64), ok.size - 1)]
+    return sig
+
+
+def make_cell_values(positions, D: int, H: int, seed: int):
+    """One (W, U, b) per cell: [4H, D], [4H, H], [4H] for positions[t] = 0 (child-sum), else
+    [(3+N)H, D], [(3+N)H, N*H], [(3+N)H] with N = positions[t].  Uniform like make_values_typed; U of
+    an N-ary cell is scaled by its fan-in N*H."""
+    out = []
+    for t, N in enumerate(positions):
+        rng = np.random.default_rng(seed + 31 * t)
+        rows = 4 * H if N == 0 else (3 + N) * H
+        cols = H if N == 0 else N * H
+        kw, ku = 1.0 / np.sqrt(D), 1.0 / np.sqrt(cols)
+        out.append((rng.uniform(-kw, kw, size=(rows, D)).astype(np.float32),
+                    rng.uniform(-ku, ku, size=(rows, cols)).astype(np.float32),
+                    rng.uniform(-0.5, 0.5, size=rows).astype(np.float32)))
+    return out
