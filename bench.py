@@ -384,16 +384,20 @@ def main():
 
     # algorithmic work per step and per kernel class (padding and unused rows do not count);
     # the library reports how many level rows each class of launches covered
-    flops_row = {"leaf": 2.0 * D * 3 * H, "internal": 2.0 * D * 4 * H + 2.0 * H * 3 * H, "proj": 2.0 * H * H}
+    flops_row = {"leaf": 2.0 * D * 3 * H, "internal": 2.0 * D * 4 * H + 2.0 * H * 3 * H, "proj": 2.0 * H * H,
+                 # a level of one-child nodes in one launch: the internal row's work plus its child's projection
+                 "chain": 2.0 * D * 4 * H + 2.0 * H * 4 * H}
     flops_total = {"leaf": n_leaf * flops_row["leaf"], "internal": n_int * flops_row["internal"],
                    "proj": E * flops_row["proj"]}
     # Algorithmic bytes per row of each kernel class as this design moves them (padding does not count):
     #   leaf      reads its stacked x row, writes h and c (fp32)
     #   internal  reads its stacked [x | sum h] row, per child P_k and c_k (fp32), writes h and c
     #   proj      reads h, writes P
+    #   chain     reads its x row, its child's h and c, writes h and c
     bytes_row = {"leaf": D * esz + H * esz + 4.0 * H,
                  "internal": (D + H) * esz + H * esz + 4.0 * H,
-                 "proj": 2.0 * H * esz}
+                 "proj": 2.0 * H * esz,
+                 "chain": D * esz + H * esz + 4.0 * H + H * esz + 4.0 * H}
     bytes_edge_internal = H * esz + 4.0 * H
     # the gather ("stack" step): the child sum reads every child's h row once and writes one row per
     # internal node; the copy of x into the stacked matrix (read + written) is overhead of this design
@@ -406,18 +410,19 @@ def main():
     roof = None
     if prof is not None:
         proj_rows = (prof["proj"]["rows"] + prof["thin_proj"]["rows"]) / args.steps   # includes roots, whose P nobody reads
-        for name in ("leaf", "internal", "proj", "thin_leaf", "thin_internal", "thin_proj"):
+        chain_rows = prof["chain"]["rows"] / args.steps      # one edge each, projected inside the chain launch
+        for name in ("leaf", "internal", "proj", "thin_leaf", "thin_internal", "thin_proj", "chain"):
             job = name.replace("thin_", "")
             ms = prof[name]["ms"] / args.steps
             n_l = prof[name]["launches"] / args.steps
             rows = prof[name]["rows"] / args.steps
             fl = rows * flops_row[job]
             if job == "proj" and proj_rows > 0:
-                fl *= E / proj_rows
+                fl *= (E - chain_rows) / proj_rows
             if ms > 0:
                 by = rows * bytes_row[job]
                 if job == "internal":      # its share of the edges, by rows (exact when one class holds all of them)
-                    by += E * bytes_edge_internal * rows / max(n_int, 1)
+                    by += (E - chain_rows) * bytes_edge_internal * rows / max(n_int - chain_rows, 1)
                 gbs = by / (ms * 1e-3) / 1e9
                 kernels[name] = {"ms_per_step": ms, "launches_per_step": n_l, "rows_per_step": rows,
                                  "flops_per_step": fl, "tflops": fl / (ms * 1e-3) / 1e12,
@@ -439,10 +444,11 @@ def main():
                                 "xcopy_bytes_per_step": bytes_xcopy,
                                 "gbs_with_xcopy": (bytes_gather + bytes_xcopy) / (ms * 1e-3) / 1e9}
         kernels["pack"] = {"ms_per_step": prof["pack"]["ms"] / args.steps}
-        mfma_names = [n for n in ("leaf", "internal", "proj", "thin_leaf", "thin_internal", "thin_proj") if n in kernels]
+        mfma_names = [n for n in ("leaf", "internal", "proj", "thin_leaf", "thin_internal", "thin_proj", "chain") if n in kernels]
         dom = max(mfma_names, key=lambda k: kernels[k]["ms_per_step"])
         k = kernels[dom]
-        kname = (f"thin_kernel<{cfg.dtype},{dom[5:]}>" if dom.startswith("thin_") else f"level_kernel<{cfg.dtype},{dom}>")
+        kname = (f"thin_kernel<{cfg.dtype},{dom[5:]}>" if dom.startswith("thin_") else
+                 f"chain_kernel<{cfg.dtype}>" if dom == "chain" else f"level_kernel<{cfg.dtype},{dom}>")
         # the dominant kernel against the roof that binds a kernel of its own intensity; the other
         # roof's fraction is given beside it
         launches = max(k["launches_per_step"], 1)

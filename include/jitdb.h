@@ -93,6 +93,10 @@ typedef struct {
                                           its per-level launches from it */
     int32_t n_levels;        /* out: L = 1 + max height (0 if N == 0) */
     int64_t n_edges;         /* out: E = N - number of roots */
+    int32_t *host_level_kids; /* host [N+1] or NULL, out: entry l < n_levels = number of children of the nodes of
+                                          level l (0 for level 0), -1 = not known.  Optional: with it the forward
+                                          recognises levels in which every node has exactly one child (chains:
+                                          sequences, the thin tail of a forest) and runs each as a single launch */
 } jitdb_schedule_t;
 
 /* Bytes of device workspace jitdb_schedule needs for a forest of n_nodes (0 if n_nodes is invalid). */
@@ -438,7 +442,9 @@ typedef enum {
     JITDB_K_THIN_LEAF = 5,      /* the same three jobs done by the kernel for small levels */
     JITDB_K_THIN_INTERNAL = 6,
     JITDB_K_THIN_PROJ = 7,      /* includes the next slot's stack step when the two share a launch */
-    JITDB_K_CLASSES = 8
+    JITDB_K_CHAIN = 8,          /* a level whose nodes all have one child: gather, all four gates and the cell
+                                   update in one launch (no stack step, no projection) */
+    JITDB_K_CLASSES = 9
 } jitdb_kernel_class;
 
 typedef struct {

@@ -43,6 +43,7 @@ class _ScheduleStruct(ctypes.Structure):
         ("host_level_ptr", ctypes.c_void_p),
         ("n_levels", ctypes.c_int32),
         ("n_edges", ctypes.c_int64),
+        ("host_level_kids", ctypes.c_void_p),
     ]
 
 
@@ -56,7 +57,7 @@ class _SlotsStruct(ctypes.Structure):
     ]
 
 
-K_CLASSES = ("pack", "stack", "leaf", "internal", "proj", "thin_leaf", "thin_internal", "thin_proj")
+K_CLASSES = ("pack", "stack", "leaf", "internal", "proj", "thin_leaf", "thin_internal", "thin_proj", "chain")
 
 
 class _CellStruct(ctypes.Structure):
@@ -65,8 +66,8 @@ class _CellStruct(ctypes.Structure):
 
 
 class _ProfileStruct(ctypes.Structure):
-    _fields_ = [("ms", ctypes.c_double * 8), ("launches", ctypes.c_int64 * 8),
-                ("rows", ctypes.c_int64 * 8), ("dropped", ctypes.c_int64)]
+    _fields_ = [("ms", ctypes.c_double * 9), ("launches", ctypes.c_int64 * 9),
+                ("rows", ctypes.c_int64 * 9), ("dropped", ctypes.c_int64)]
 
 
 _lib = None
@@ -309,12 +310,13 @@ class Schedule:
         self.child_ptr = torch.empty(n + 1, **i32)
         self.child_idx = torch.empty(max(n, 1), **i32)
         self.host_level_ptr = np.zeros(n + 1, dtype=np.int32)
+        self.host_level_kids = np.full(n + 1, -1, dtype=np.int32)    # children per level; -1 = not known
         self.n_levels = 0
         self.n_edges = 0
         self.struct = _ScheduleStruct(
             n, self.height.data_ptr(), self.level_ptr.data_ptr(), self.perm.data_ptr(),
             self.inv_perm.data_ptr(), self.child_ptr.data_ptr(), self.child_idx.data_ptr(),
-            self.host_level_ptr.ctypes.data, 0, 0)
+            self.host_level_ptr.ctypes.data, 0, 0, self.host_level_kids.ctypes.data)
 
     def to_numpy(self) -> dict:
         """Host copies trimmed to their valid lengths (for comparison in tests)."""
@@ -326,6 +328,7 @@ class Schedule:
             inv_perm=self.inv_perm[:n].cpu().numpy(),
             child_ptr=self.child_ptr[:n + 1].cpu().numpy(),
             child_idx=self.child_idx[:E].cpu().numpy(),
+            level_kids=self.host_level_kids[:L].copy(),
             n_levels=L, n_edges=E)
 
 

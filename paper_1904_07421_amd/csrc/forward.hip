@@ -966,6 +966,116 @@ thin_proj_stack_kernel(const LevelArgs a, const StackArgs s) {
                             (int64_t)blockIdx.x - a.n_blocks);
 }
 
+// ---- chain levels ---------------------------------------------------------------------
+// A level in which every node has exactly one child (sequences filed as chains, the long thin
+// tail of a forest) needs neither the stack step nor the projection: the child sum is the
+// child's h, read in place, and U_f h_k belongs to the same row, so the forget gate is a fourth
+// full-K product like i, o and u.  One launch per level instead of two: the level's cost is its
+// chain of dependent launches, not its work.  Tiles and waves as in thin_kernel (32 rows x 32
+// units, wave g = gate g); A comes straight from x (rows by node id, zero past D) and from the
+// child's padded h row, B from the packed weights.  Needs D % 4 == 0 (whole 8- / 16-byte pieces
+// of an x row are either inside D or outside).
+template <typename T>
+__device__ __forceinline__ u32x4 load_x_piece(const char *p, int k0, int D) {
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if constexpr (sizeof(T) == 4) {
+        if (k0 < D) v = *reinterpret_cast<const u32x4 *>(p);
+    } else {
+        if (k0 < D) { const u32x2 q = *reinterpret_cast<const u32x2 *>(p); v[0] = q[0]; v[1] = q[1]; }
+        if (k0 + 4 < D) { const u32x2 q = *reinterpret_cast<const u32x2 *>(p + 8); v[2] = q[0]; v[3] = q[1]; }
+    }
+    return v;
+}
+
+template <typename T>
+__global__ void __launch_bounds__(kThinWaves * 64, 2)
+chain_kernel(const LevelArgs a) {
+    constexpr int ESZ = (int)sizeof(T);
+    constexpr int VEC = Traits<T>::VEC;
+    __shared__ __attribute__((aligned(16))) float region[3 * 32 * kEpiStride];
+    __shared__ __attribute__((aligned(16))) float exchange[3][16][64];   // accumulators of waves 1-3
+    __shared__ int s_node[32];
+    __shared__ int s_ar[32];
+    __shared__ int s_cb[32];
+    __shared__ int4 s_kid[32];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int hf = lane >> 5, l32 = lane & 31;
+    const int tile = blockIdx.x;
+    const int row0 = (tile / a.n_col_tiles) * 32;
+    const int col = tile % a.n_col_tiles;     // unit tile
+
+    int my_row = row0 + l32;
+    const bool row_ok = my_row < a.n_rows;
+    if (!row_ok) my_row = a.n_rows - 1;       // computed twice, stored never
+    const int4 r0 = a.row_rec[2 * (int64_t)my_row];
+    const int4 r1 = a.row_rec[2 * (int64_t)my_row + 1];
+    const bool has_kid = r0.y >= 1;           // always, in a level this kernel is launched for
+    const int kid = has_kid ? r1.x : 0;
+    if (wave == 0 && hf == 0) {
+        s_node[l32] = row_ok ? r0.x : -1;
+        s_ar[l32] = row_ok ? (has_kid ? 1 : 0) : 0;
+        s_cb[l32] = r0.z;
+        s_kid[l32] = r1;
+    }
+
+    // lane (l32, hf) supplies row l32, bytes [hf*16, +16) of each 32-byte K group, for A and B alike
+    const char *ax = static_cast<const char *>(a.x) + (int64_t)r0.x * a.D * ESZ + hf * 16;
+    const char *ah = static_cast<const char *>(a.hs) + (int64_t)kid * a.Hp * ESZ + hf * 16;
+    const int64_t brow = (int64_t)col * kGateTile + wave * kUnit + l32;
+    const char *bp = static_cast<const char *>(a.Bp) + operand_offset(brow, 0, a.NPU) + hf * 16;
+    const int64_t b_pair = (int64_t)a.NPU * 64;
+    const int gx = a.Dp * ESZ / 32;                      // K groups of the x part
+    const int n_groups = gx + a.Hp * ESZ / 32;
+
+    floatx16 acc[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[g][v] = 0.0f;
+    CellBias bias = {};
+    if (wave == 0) bias = load_cell_bias<MODE_CHAIN>(a, col, lane);     // on its way while the K loop runs
+
+    u32x4 fa[kThinAhead], fb[kThinAhead];
+    auto request = [&](int g, int slot) __attribute__((always_inline)) {
+        if (g < gx) {
+            fa[slot] = load_x_piece<T>(ax + (int64_t)g * 32, g * (32 / ESZ) + hf * VEC, a.D);
+        } else {
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (has_kid) v = *reinterpret_cast<const u32x4 *>(ah + (int64_t)(g - gx) * 32);
+            fa[slot] = v;
+        }
+        fb[slot] = *reinterpret_cast<const u32x4 *>(bp + (int64_t)(g >> 1) * b_pair + (g & 1) * 32);
+    };
+#pragma unroll
+    for (int s = 0; s < kThinAhead; ++s)
+        if (s < n_groups) request(s, s);
+    for (int g0 = 0; g0 < n_groups; g0 += kThinAhead) {
+#pragma unroll
+        for (int s = 0; s < kThinAhead; ++s) {
+            const int g = g0 + s;
+            if (g < n_groups) {
+                mfma_step<T>(fa[s], fb[s], acc[0]);
+                if (g + kThinAhead < n_groups) request(g + kThinAhead, s);
+            }
+        }
+    }
+
+    // gates 1-3 travel to wave 0, which holds gate 0
+    if (wave > 0) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) exchange[wave - 1][v][lane] = acc[0][v];
+    }
+    __syncthreads();
+    if (wave > 0) return;
+#pragma unroll
+    for (int g = 1; g < 4; ++g)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[g][v] = exchange[g - 1][v][lane];
+    cell_pass<T, MODE_CHAIN>(a, acc, region, s_node, s_ar, s_cb, s_kid, col, lane, bias);
+}
+
 // ---- tile tables of a typed level --------------------------------------------------------
 // One block.  bounds[e * stride] .. bounds[(e + 1) * stride], e < n_entries, are consecutive
 // ranges of positions (the level's slots with stride = n_sig, its sub-slots with stride = 1);
@@ -1199,6 +1309,7 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
     // tables keep the 128 x 256 kernel, which has those variants
     const bool may256 = std::is_same<T, bf16_t>::value && !SAVE && !slots && w.Bf != nullptr;
     a.hs = w.hs ? w.hs : h_out;
+    a.x = x;
     a.child_idx = s->child_idx;
 
     a.P = w.P; a.c_out = c_out; a.h_out = h_out;
@@ -1255,6 +1366,18 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
         return (unsigned)ceil_div((int64_t)g.rows * (Kp / Traits<T>::VEC), kThreads);
     };
     bool stacked_ahead = false;     // the slot's stack step already ran with the projection before it
+    // Levels from chain_from on are thin and hold only nodes with exactly one child (the schedule says
+    // how many children each level has): one launch each, no stack step, no projection.  A child
+    // below chain_from whose parent is such a node needs no projection either, so the level right
+    // below skips it too.
+    int chain_from = L;
+    if (!SAVE && !slots && s->host_level_kids && (d.D & 3) == 0) {
+        for (int l = L - 1; l >= 1; --l) {
+            const int rows = sp[l + 1] - sp[l];
+            if (rows > kThinMaxRows || s->host_level_kids[l] != rows) break;
+            chain_from = l;
+        }
+    }
     const int n_unit_tiles = d.Hu / kUnit;
     a.w_bytes = (int64_t)packed_w_bytes(d);
     a.NP = d.NP;
@@ -1276,6 +1399,15 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
             tile_table_kernel<<<1, kThreads, 0, st>>>(lvl, T2, 1, n_sig, w.tiles + w.tiles_each);
             JITDB_LAUNCH_CHECK();
             a.tiles = w.tiles;
+        }
+        if (l >= chain_from) {
+            a.n_col_tiles = n_unit_tiles;
+            a.n_tiles = (int)ceil_div(n_rows, 32) * a.n_col_tiles;
+            a.n_blocks = a.n_tiles;
+            ScopedLaunchTimer tm(JITDB_K_CHAIN, n_rows, st);
+            chain_kernel<T><<<a.n_blocks, kThinWaves * 64, 0, st>>>(a);
+            JITDB_LAUNCH_CHECK();
+            continue;
         }
         if (is_nary(sig)) {
             // a slot of N-ary nodes: stack, one contraction for all 3 + N gates, cell update (cells.hip)
@@ -1338,6 +1470,7 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
             JITDB_LAUNCH_CHECK();
         }
         if (l + 1 >= L) continue;     // the top level has no parents to project for
+        if (l + 1 >= chain_from) continue;   // every parent is a chain node: U_f h_k is part of its own launch
 
         // Forget projections of these nodes (roots' rows go unused), with the PARENT's weights.
         if (grouped) {

@@ -31,7 +31,8 @@ constexpr int kTile256MinRows[3] = {INT32_MAX, INT32_MAX, INT32_MAX};
 
 constexpr int kEpiStride = 40;  // floats per row of a wave's epilogue region: 32 units + 8; rows 4 apart fall 32 banks apart
 
-enum : int { MODE_LEAF = 0, MODE_INTERNAL = 1, MODE_PROJ = 2, MODE_GENERIC = 3 };   // GENERIC: plain C = A B^T
+enum : int { MODE_LEAF = 0, MODE_INTERNAL = 1, MODE_PROJ = 2, MODE_GENERIC = 3,   // GENERIC: plain C = A B^T
+             MODE_CHAIN = 4 };   // internal rows with exactly one child: the forget gate's pre-activation is complete
 
 template <typename T> struct Traits;
 template <> struct Traits<float> {
@@ -74,6 +75,7 @@ struct LevelArgs {
     // A operands
     const void *stack;    // [n_rows, Dp (+ Hp)] the level's stacked input (leaf / internal)
     const void *hs;       // [N, Hp] rows by node id (projection)
+    const void *x;        // [N, D] rows by node id (chain levels read them in place)
     // B operand: packed [W | U], NPU rows of Dp + Hp
     const void *Bp;
     const void *Bf;       // the same rows fragment-major (tile256_kernel), or null
@@ -140,7 +142,7 @@ __device__ __forceinline__ CellBias load_cell_bias(const LevelArgs &a, int unit_
     const int pcol = unit_tile * kGateTile + (lane & 31);
     CellBias b;
     b.i = a.bp[pcol]; b.o = a.bp[pcol + kUnit]; b.u = a.bp[pcol + 2 * kUnit];
-    b.f = (MODE == MODE_INTERNAL) ? a.bp[pcol + 3 * kUnit] : 0.0f;
+    b.f = (MODE == MODE_INTERNAL || MODE == MODE_CHAIN) ? a.bp[pcol + 3 * kUnit] : 0.0f;
     return b;
 }
 
@@ -148,6 +150,7 @@ template <typename T, int MODE, bool SAVE = false>
 __device__ __forceinline__ void cell_pass(const LevelArgs &a, const floatx16 (&acc)[4], float *region,
                                           const int *rn, const int *rar, const int *rcb,
                                           const int4 *rkid, int unit_tile, int lane, const CellBias &bias) {
+    constexpr bool KIDS = (MODE == MODE_INTERNAL || MODE == MODE_CHAIN);   // rows with children
     const int hf = lane >> 5, l32 = lane & 31;
     const float bi = bias.i, bo = bias.o, bu = bias.u, bf = bias.f;
     float *s_iu = region;
@@ -169,7 +172,7 @@ __device__ __forceinline__ void cell_pass(const LevelArgs &a, const floatx16 (&a
         const float gu = tanh_t<T>(acc[2][v] + bu);
         s_iu[rl * kEpiStride + l32] = gi * gu;
         s_o[rl * kEpiStride + l32] = go;
-        if constexpr (MODE == MODE_INTERNAL) s_fx[rl * kEpiStride + l32] = acc[3][v] + bf;
+        if constexpr (KIDS) s_fx[rl * kEpiStride + l32] = acc[3][v] + bf;
         if constexpr (SAVE) {
             const int nd = rn[rl];
             const int unit = unit_tile * kUnit + l32;
@@ -194,9 +197,9 @@ __device__ __forceinline__ void cell_pass(const LevelArgs &a, const floatx16 (&a
         const int so = tr[q] * kEpiStride + (lane & 7) * 4;
         cc[q] = *reinterpret_cast<const float4 *>(s_iu + so);
         go4[q] = *reinterpret_cast<const float4 *>(s_o + so);
-        if constexpr (MODE == MODE_INTERNAL) fx4[q] = *reinterpret_cast<const float4 *>(s_fx + so);
+        if constexpr (KIDS) fx4[q] = *reinterpret_cast<const float4 *>(s_fx + so);
     }
-    if constexpr (MODE == MODE_INTERNAL) {
+    if constexpr (KIDS) {
         // Children are taken two per row and round, for four rows at once: sixteen
         // independent 16-byte loads in flight per thread.  The first four child ids
         // of a row sit in LDS; longer lists (rare) continue from child_idx.  A slot
@@ -239,7 +242,9 @@ __device__ __forceinline__ void cell_pass(const LevelArgs &a, const floatx16 (&a
             for (int q = 0; q < 4; ++q)
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
-                    if constexpr (sizeof(T) == 4) {
+                    if constexpr (MODE == MODE_CHAIN) {      // U_f h_k is in the accumulator already
+                        pk[q][j] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    } else if constexpr (sizeof(T) == 4) {
                         pk[q][j] = *reinterpret_cast<const float4 *>(static_cast<const float *>(a.P) + ofs[q][j]);
                     } else {
                         const uint2 w = *reinterpret_cast<const uint2 *>(static_cast<const bf16_t *>(a.P) + ofs[q][j]);

@@ -282,6 +282,33 @@ level_hist_kernel(const int32_t *__restrict__ height, int32_t n, int32_t n_level
     }
 }
 
+// Children per level: every non-root node counts for the level of its parent.
+__global__ void __launch_bounds__(kThreads)
+level_kids_kernel(const int32_t *__restrict__ parent, const int32_t *__restrict__ height, int32_t n,
+                  int32_t n_levels, int32_t *__restrict__ level_kids) {
+    __shared__ int lds[kLdsLevels];
+    const bool use_lds = n_levels <= kLdsLevels;
+    if (use_lds) {
+        for (int i = threadIdx.x; i < n_levels; i += kThreads) lds[i] = 0;
+        __syncthreads();
+    }
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n;
+         i += (int64_t)gridDim.x * kThreads) {
+        const int p = parent[i];
+        if (p < 0) continue;
+        const int h = height[p];
+        if (use_lds) atomicAdd(&lds[h], 1);
+        else atomicAdd(&level_kids[h], 1);
+    }
+    if (use_lds) {
+        __syncthreads();
+        for (int i = threadIdx.x; i < n_levels; i += kThreads) {
+            const int c = lds[i];
+            if (c) atomicAdd(&level_kids[i], c);
+        }
+    }
+}
+
 // ---- stable LSD radix sort of (key, node id) pairs, 8 bits per pass ----------------
 constexpr int kRadixBits = 8;
 constexpr int kRadix = 1 << kRadixBits;
@@ -550,6 +577,7 @@ int schedule_impl(const int32_t *parent, const int32_t *sig, jitdb_slots_t *slot
     s->n_edges = 0;
     if (n64 == 0) {
         s->host_level_ptr[0] = 0;
+        if (s->host_level_kids) s->host_level_kids[0] = 0;
         if (slots && slots->slot_ptr) {
             int rc = launch_fill(slots->slot_ptr, 1, 0, (hipStream_t)hip_stream);
             if (rc != JITDB_OK) return rc;
@@ -655,6 +683,16 @@ int schedule_impl(const int32_t *parent, const int32_t *sig, jitdb_slots_t *slot
     //    outside the first E entries
     if ((rc = radix_sort_ids(parent, n, bits_needed(n64), n, s->child_idx, w.sort, st)) != JITDB_OK) return rc;
 
+    // 7. (optional) children per level, for the forward's choice of kernels; the child counts'
+    //    array is free again by now
+    if (s->host_level_kids) {
+        if ((rc = launch_fill(w.cnt, L, 0, st)) != JITDB_OK) return rc;
+        const unsigned g = (unsigned)(ceil_div(n64, kThreads) < 1024 ? ceil_div(n64, kThreads) : 1024);
+        level_kids_kernel<<<g, kThreads, 0, st>>>(parent, s->height, n, L, w.cnt);
+        JITDB_LAUNCH_CHECK();
+        JITDB_HIP_CHECK(hipMemcpyAsync(s->host_level_kids, w.cnt, sizeof(int32_t) * (size_t)L, hipMemcpyDeviceToHost, st));
+    }
+
     if (slots) {
         JITDB_HIP_CHECK(hipMemcpyAsync(slots->host_slot_ptr, slots->slot_ptr, sizeof(int32_t) * ((size_t)S + 1),
                                        hipMemcpyDeviceToHost, st));
@@ -727,6 +765,9 @@ extern "C" int jitdb_schedule_append(const jitdb_schedule_t *base, const int32_t
     fresh.height = w.height; fresh.level_ptr = w.level_ptr; fresh.perm = w.perm; fresh.inv_perm = w.inv_perm;
     fresh.child_ptr = w.child_ptr; fresh.child_idx = w.child_idx;
     fresh.host_level_ptr = out->host_level_ptr + na;
+    // children per level add up like the level sizes; known only if both parts know theirs
+    const bool kids_known = out->host_level_kids && (na == 0 || base->host_level_kids);
+    fresh.host_level_kids = kids_known ? out->host_level_kids + na : nullptr;
     fresh.n_levels = 0; fresh.n_edges = 0;
     if (n_new > 0) {
         const int rc = jitdb_schedule(parent_new, &fresh, w.sched_ws, w.sched_ws_bytes, hip_stream);
@@ -739,6 +780,11 @@ extern "C" int jitdb_schedule_append(const jitdb_schedule_t *base, const int32_t
         const int32_t b = n_new > 0 ? fresh.host_level_ptr[l < ln ? l : ln] : 0;
         const int32_t a = na > 0 ? base->host_level_ptr[l < la ? l : la] : 0;
         out->host_level_ptr[l] = a + b;
+        if (out->host_level_kids && l < l_out) {
+            const int32_t kb = (kids_known && l < ln) ? fresh.host_level_kids[l] : 0;
+            const int32_t ka = (kids_known && l < la) ? base->host_level_kids[l] : 0;
+            out->host_level_kids[l] = !kids_known || ka < 0 || kb < 0 ? -1 : ka + kb;
+        }
     }
     out->n_levels = l_out;
     out->n_edges = ea + en;

@@ -25,6 +25,8 @@ def _check(sched, parent_joint, label):
         assert np.array_equal(got[k], want[k]), f"{label}: {k}"
     L = got["n_levels"]
     assert np.array_equal(sched.host_level_ptr[:L + 1], want["level_ptr"]), f"{label}: host_level_ptr"
+    kids = np.bincount(want["height"], weights=np.diff(want["child_ptr"]), minlength=L).astype(np.int64)
+    assert np.array_equal(sched.host_level_kids[:L], kids), f"{label}: host_level_kids"
 
 
 def _split_at_tree(parent, frac):

@@ -429,3 +429,76 @@ def test_default_buffers_follow_the_launch_stream(c_oracle):
     ho, co, _ = c_oracle(p, x, W, U, b)
     for h, c in outs:
         assert np.abs(h.cpu().numpy() - ho).max() <= 1e-4 and np.abs(c.cpu().numpy() - co).max() <= 1e-4
+
+
+# ---- levels of one-child nodes (one launch per level) ------------------------------------------
+def _profile_classes(fn):
+    """Run fn() under the library's per-kernel timers; returns launches per class."""
+    import torch
+    import paper_1904_07421_amd as J
+    J.jitdb_profile_start(4096)
+    try:
+        out = fn()
+        torch.cuda.synchronize()
+    finally:
+        prof = J.jitdb_profile_stop()
+    return out, {k: v["launches"] for k, v in prof.items() if isinstance(v, dict)}
+
+
+def _trees_and_sequences(n_trees, n_seqs, len_hi, seed):
+    from workloads import mixed_forest
+    return mixed_forest(2, n_trees, n_seqs, 2, len_hi, seed)[0]
+
+
+@pytest.mark.parametrize("dtype,D,H", [("f32", 300, 256), ("bf16", 300, 512), ("f32", 44, 50), ("bf16", 44, 50),
+                                       ("bf16", 64, 72)])
+def test_chain_levels_run_as_one_launch_each(c_oracle, dtype, D, H):
+    """Parse trees plus sequences up to 90 long: above the trees' heights every level holds only nodes
+    with one child and takes the single-launch kernel (x and the child's h read in place, all four
+    gates full K); below, the usual stack / level / projection launches.  Padded widths included."""
+    parent = _trees_and_sequences(300, 700, 90, 5)
+    x, W, U, b = make_values(2, parent.shape[0], "random", D=D, H=H)
+    (res, launches) = _profile_classes(lambda: run_gpu_forward(parent, x, W, U, b, dtype))
+    sched, h, c, seen = res
+    L = sched.n_levels
+    lp, kids = sched.host_level_ptr[:L + 1], sched.host_level_kids[:L]
+    rows = np.diff(lp)
+    chain_from = L
+    for l in range(L - 1, 0, -1):
+        if kids[l] != rows[l]:
+            break
+        chain_from = l
+    print(f"chain levels {dtype} D={D} H={H}: N={parent.shape[0]} L={L} chain_from={chain_from} launches={launches}",
+          flush=True)
+    assert 1 < chain_from < L - 20
+    assert launches["chain"] == L - chain_from
+    ho, co = _oracle(c_oracle, parent, seen)
+    eh, ec = _report(f"chain-levels/{dtype}", h, c, ho, co)
+    assert eh <= TOL[dtype] and ec <= TOL[dtype] * max(1.0, float(np.abs(co).max()) / 8.0)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_chain_levels_need_the_child_counts_and_whole_x_pieces(c_oracle, dtype):
+    """Without the schedule's children-per-level, or with D not a multiple of 4, the same forest takes
+    the general launches and gives the same states within the tolerance."""
+    import torch
+    import paper_1904_07421_amd as J
+    parent = _trees_and_sequences(100, 300, 40, 6)
+    for D in (48, 46):
+        x, W, U, b = make_values(2, parent.shape[0], "random", D=D, H=40)
+        (res, launches) = _profile_classes(lambda: run_gpu_forward(parent, x, W, U, b, dtype))
+        sched, h, c, seen = res
+        assert (launches["chain"] > 0) == (D % 4 == 0), (D, launches)
+        ho, co = _oracle(c_oracle, parent, seen)
+        eh, ec = _report(f"chain D={D}/{dtype}", h, c, ho, co)
+        assert eh <= TOL[dtype] and ec <= TOL[dtype] * max(1.0, float(np.abs(co).max()) / 8.0)
+        if D % 4 == 0:
+            # the same schedule with the counts withheld
+            sched.host_level_kids[:] = -1
+            to = (lambda a: torch.from_numpy(np.ascontiguousarray(a, np.float32)).cuda()) if dtype == "f32" else \
+                (lambda a: __import__("gpu_util").bf16_tensor(a)[0])
+            args = (to(x), to(W), to(U), torch.from_numpy(b).cuda(), sched)
+            (res2, launches2) = _profile_classes(lambda: J.jitdb_treelstm_forward(*args))
+            assert launches2["chain"] == 0 and launches2["thin_proj"] > launches["thin_proj"]
+            h2, c2 = res2[0].float().cpu().numpy(), res2[1].cpu().numpy()
+            assert np.abs(h2 - h).max() <= TOL[dtype] and np.abs(c2 - c).max() <= TOL[dtype] * max(1.0, float(np.abs(co).max()) / 8.0)
