@@ -970,110 +970,190 @@ thin_proj_stack_kernel(const LevelArgs a, const StackArgs s) {
 // A level in which every node has exactly one child (sequences filed as chains, the long thin
 // tail of a forest) needs neither the stack step nor the projection: the child sum is the
 // child's h, read in place, and U_f h_k belongs to the same row, so the forget gate is a fourth
-// full-K product like i, o and u.  One launch per level instead of two: the level's cost is its
-// chain of dependent launches, not its work.  Tiles and waves as in thin_kernel (32 rows x 32
-// units, wave g = gate g); A comes straight from x (rows by node id, zero past D) and from the
-// child's padded h row, B from the packed weights.  Needs D % 4 == 0 (whole 8- / 16-byte pieces
-// of an x row are either inside D or outside).
+// full-K product like i, o and u.  One launch per level instead of two; such a level costs its
+// chain of dependent launches and the memory latencies inside them, not its work, so the kernel
+// is arranged to meet every latency once:
+//
+//   * tiles and waves as in thin_kernel (32 rows x 32 units, wave g = gate g);
+//   * the four waves need the same A rows [x_j | h_child], so the block fetches the tile's whole
+//     A (32 rows x K) once, all loads in flight together, 32 threads per row on consecutive
+//     16-byte pieces (zero past D, past K and without a child), into LDS; one barrier;
+//   * the K loop then has no barrier: A fragments from LDS (the next one read while this one is
+//     multiplied), the wave's own weight rows from global memory / L2, kChainAhead K groups ahead,
+//     the first turn requested before anything else in the kernel;
+//   * the gates meet in LDS and each wave finishes eight of the tile's rows.
+//
+// Needs D % 4 == 0 (an 8- / 16-byte piece of an x row is inside D or outside) and an A tile that
+// fits LDS (chain_lds_bytes).
+constexpr int kChainAhead = 16;                         // weight K groups in flight per wave
+constexpr int kChainLdsMax = 128 * 1024;                // dynamic LDS the kernel may ask for (beside ~22 KB static)
+// LDS pitch of an A row: K bytes + 16, so that 16 lanes' 16-byte reads of one K group fall in 64 different banks
+__host__ __device__ inline int chain_row_pitch(int k_bytes) { return k_bytes + 16; }
+inline size_t chain_lds_bytes(int k_bytes) { return (size_t)32 * chain_row_pitch(k_bytes); }
+
+// Validity of the two halves of a 16-byte piece, K bytes [kb, kb + 16), of a chain row's A operand.
 template <typename T>
-__device__ __forceinline__ u32x4 load_x_piece(const char *p, int k0, int D) {
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if constexpr (sizeof(T) == 4) {
-        if (k0 < D) v = *reinterpret_cast<const u32x4 *>(p);
-    } else {
-        if (k0 < D) { const u32x2 q = *reinterpret_cast<const u32x2 *>(p); v[0] = q[0]; v[1] = q[1]; }
-        if (k0 + 4 < D) { const u32x2 q = *reinterpret_cast<const u32x2 *>(p + 8); v[2] = q[0]; v[3] = q[1]; }
-    }
-    return v;
+__device__ __forceinline__ void chain_piece_ok(bool kid_ok, int kb, int x_bytes, int k_bytes, int D, bool &ok0, bool &ok1) {
+    constexpr int ESZ = (int)sizeof(T);
+    const bool in_x = kb < x_bytes;
+    const int k0 = kb / ESZ;
+    ok0 = in_x ? (k0 < D) : (kb < k_bytes && kid_ok);
+    ok1 = (ESZ == 2 && in_x) ? (k0 + 4 < D) : ok0;       // bf16: the second four elements of the piece
 }
 
 template <typename T>
 __global__ void __launch_bounds__(kThinWaves * 64, 2)
 chain_kernel(const LevelArgs a) {
     constexpr int ESZ = (int)sizeof(T);
-    constexpr int VEC = Traits<T>::VEC;
-    __shared__ __attribute__((aligned(16))) float region[3 * 32 * kEpiStride];
-    __shared__ __attribute__((aligned(16))) float exchange[3][16][64];   // accumulators of waves 1-3
+    extern __shared__ __attribute__((aligned(16))) char a_lds[];          // [32][chain_row_pitch]
+    __shared__ __attribute__((aligned(16))) float zt[4][32 * kEpiStride];  // pre-activations, [gate][row][unit]
     __shared__ int s_node[32];
-    __shared__ int s_ar[32];
-    __shared__ int s_cb[32];
-    __shared__ int4 s_kid[32];
+    __shared__ int s_kid[32];
 
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int hf = lane >> 5, l32 = lane & 31;
     const int tile = blockIdx.x;
     const int row0 = (tile / a.n_col_tiles) * 32;
     const int col = tile % a.n_col_tiles;     // unit tile
 
-    int my_row = row0 + l32;
-    const bool row_ok = my_row < a.n_rows;
-    if (!row_ok) my_row = a.n_rows - 1;       // computed twice, stored never
-    const int4 r0 = a.row_rec[2 * (int64_t)my_row];
-    const int4 r1 = a.row_rec[2 * (int64_t)my_row + 1];
-    const bool has_kid = r0.y >= 1;           // always, in a level this kernel is launched for
-    const int kid = has_kid ? r1.x : 0;
-    if (wave == 0 && hf == 0) {
-        s_node[l32] = row_ok ? r0.x : -1;
-        s_ar[l32] = row_ok ? (has_kid ? 1 : 0) : 0;
-        s_cb[l32] = r0.z;
-        s_kid[l32] = r1;
-    }
-
-    // lane (l32, hf) supplies row l32, bytes [hf*16, +16) of each 32-byte K group, for A and B alike
-    const char *ax = static_cast<const char *>(a.x) + (int64_t)r0.x * a.D * ESZ + hf * 16;
-    const char *ah = static_cast<const char *>(a.hs) + (int64_t)kid * a.Hp * ESZ + hf * 16;
+    // ---- weights: lane (l32, hf) supplies row l32 of the wave's gate, bytes [hf*16, +16) of each 32-byte K
+    //      group.  Every load of the ring is unconditional (a group index past the end is clamped to the
+    //      last group, whose data is then not used): the number of loads between a request and its use is
+    //      the same on every path, so the waits the compiler places are counted, not "all".
+    const int x_bytes = a.Dp * ESZ;                      // K bytes of the x part
+    const int k_bytes = x_bytes + a.Hp * ESZ;
+    const int pitch = chain_row_pitch(k_bytes);
+    const int n_groups = k_bytes / 32;
+    const int last_group = n_groups - 1;
     const int64_t brow = (int64_t)col * kGateTile + wave * kUnit + l32;
     const char *bp = static_cast<const char *>(a.Bp) + operand_offset(brow, 0, a.NPU) + hf * 16;
     const int64_t b_pair = (int64_t)a.NPU * 64;
-    const int gx = a.Dp * ESZ / 32;                      // K groups of the x part
-    const int n_groups = gx + a.Hp * ESZ / 32;
-
-    floatx16 acc[4];
-#pragma unroll
-    for (int g = 0; g < 4; ++g)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[g][v] = 0.0f;
-    CellBias bias = {};
-    if (wave == 0) bias = load_cell_bias<MODE_CHAIN>(a, col, lane);     // on its way while the K loop runs
-
-    u32x4 fa[kThinAhead], fb[kThinAhead];
+    u32x4 fb[kChainAhead];
     auto request = [&](int g, int slot) __attribute__((always_inline)) {
-        if (g < gx) {
-            fa[slot] = load_x_piece<T>(ax + (int64_t)g * 32, g * (32 / ESZ) + hf * VEC, a.D);
-        } else {
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (has_kid) v = *reinterpret_cast<const u32x4 *>(ah + (int64_t)(g - gx) * 32);
-            fa[slot] = v;
-        }
         fb[slot] = *reinterpret_cast<const u32x4 *>(bp + (int64_t)(g >> 1) * b_pair + (g & 1) * 32);
     };
 #pragma unroll
-    for (int s = 0; s < kThinAhead; ++s)
-        if (s < n_groups) request(s, s);
-    for (int g0 = 0; g0 < n_groups; g0 += kThinAhead) {
+    for (int s = 0; s < kChainAhead; ++s) request(s < last_group ? s : last_group, s);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- the tile's A: thread t moves pieces (t & 31) + 32 i of rows (t >> 5) + 8 j
+    {
+        const char *src_x[4], *src_h[4];
+        bool kid_ok[4];
 #pragma unroll
-        for (int s = 0; s < kThinAhead; ++s) {
-            const int g = g0 + s;
-            if (g < n_groups) {
-                mfma_step<T>(fa[s], fb[s], acc[0]);
-                if (g + kThinAhead < n_groups) request(g + kThinAhead, s);
+        for (int j = 0; j < 4; ++j) {
+            const int rl = (tid >> 5) + 8 * j;
+            int r = row0 + rl;
+            const bool ok = r < a.n_rows;
+            if (!ok) r = a.n_rows - 1;                // computed twice, stored never
+            const int4 r0 = a.row_rec[2 * (int64_t)r];
+            const int4 r1 = a.row_rec[2 * (int64_t)r + 1];
+            kid_ok[j] = r0.y >= 1;                    // always, in a level this kernel is launched for
+            src_x[j] = static_cast<const char *>(a.x) + (int64_t)r0.x * a.D * ESZ;
+            src_h[j] = static_cast<const char *>(a.hs) + (int64_t)(kid_ok[j] ? r1.x : 0) * a.Hp * ESZ;
+            if ((tid & 31) == 0) {                    // the rows as the cell update wants them
+                s_node[rl] = ok ? r0.x : -1;
+                s_kid[rl] = (ok && kid_ok[j]) ? r1.x : -1;
+            }
+        }
+        const int n_rounds = (k_bytes / 16 + 31) / 32;
+#pragma unroll 4
+        for (int i = 0; i < n_rounds; ++i) {
+            const int kb = ((tid & 31) + 32 * i) * 16;
+            if (kb >= k_bytes) break;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                bool ok0, ok1;
+                chain_piece_ok<T>(kid_ok[j], kb, x_bytes, k_bytes, a.D, ok0, ok1);
+                // a piece that is not to be read comes from the start of the x row (always valid: D >= 4)
+                // and is replaced by zero
+                const char *p = kb < x_bytes ? src_x[j] + kb : src_h[j] + (kb - x_bytes);
+                u32x4 v;
+                if constexpr (ESZ == 4) {
+                    v = *reinterpret_cast<const u32x4 *>(ok0 ? p : src_x[j]);
+                } else {
+                    const u32x2 q0 = *reinterpret_cast<const u32x2 *>(ok0 ? p : src_x[j]);
+                    const u32x2 q1 = *reinterpret_cast<const u32x2 *>(ok1 ? p + 8 : src_x[j]);
+                    v[0] = q0[0]; v[1] = q0[1]; v[2] = q1[0]; v[3] = q1[1];
+                }
+                v[0] = ok0 ? v[0] : 0u; v[1] = ok0 ? v[1] : 0u; v[2] = ok1 ? v[2] : 0u; v[3] = ok1 ? v[3] : 0u;
+                *reinterpret_cast<u32x4 *>(a_lds + ((tid >> 5) + 8 * j) * pitch + kb) = v;
             }
         }
     }
-
-    // gates 1-3 travel to wave 0, which holds gate 0
-    if (wave > 0) {
+    floatx16 acc;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) exchange[wave - 1][v][lane] = acc[0][v];
+    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+    __syncthreads();
+
+    // ---- K loop: whole turns of the ring, then the rest (a multiple of 4 groups)
+    const char *abuf = a_lds + l32 * pitch + hf * 16;    // this lane's A fragment, K group 0
+    const int n_full = n_groups / kChainAhead;
+    u32x4 fa = *reinterpret_cast<const u32x4 *>(abuf);
+    for (int c = 0; c < n_full; ++c) {
+        const int g0 = c * kChainAhead;
+#pragma unroll
+        for (int s = 0; s < kChainAhead; ++s) {
+            // the next A fragment leaves LDS while this one is multiplied
+            const int gnext = g0 + s + 1 < n_groups ? g0 + s + 1 : last_group;
+            const u32x4 fa_next = *reinterpret_cast<const u32x4 *>(abuf + gnext * 32);
+            mfma_step<T>(fa, fb[s], acc);
+            const int gn = g0 + s + kChainAhead;
+            request(gn < last_group ? gn : last_group, s);
+            __builtin_amdgcn_sched_barrier(0);      // the ring is refilled slot by slot, not in a burst at the end
+            fa = fa_next;
+        }
+    }
+    {
+        const int g0 = n_full * kChainAhead;
+        const int tail = n_groups - g0;
+#pragma unroll
+        for (int s = 0; s < kChainAhead; ++s)
+            if (s < tail) {
+                const int gnext = g0 + s + 1 < n_groups ? g0 + s + 1 : last_group;
+                const u32x4 fa_next = *reinterpret_cast<const u32x4 *>(abuf + gnext * 32);
+                mfma_step<T>(fa, fb[s], acc);
+                fa = fa_next;
+            }
+    }
+
+    // ---- the gates meet in LDS; wave w finishes rows 8 w .. 8 w + 7: eight lanes per row, four units per lane
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int rl = (v >> 2) * 8 + hf * 4 + (v & 3);
+        zt[wave][rl * kEpiStride + l32] = acc[v];
     }
     __syncthreads();
-    if (wave > 0) return;
+    const int tr = wave * 8 + (lane >> 3);
+    const int node = s_node[tr];
+    if (node < 0) return;
+    const int u4 = (lane & 7) * 4;
+    const int unit0 = col * kUnit + u4;
+    const int kid = s_kid[tr];
+    const int unit_ld = unit0 < a.Hq ? unit0 : 0;        // unit groups past the padded width read the first group (and store nothing)
+    float4 ck = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (kid >= 0) ck = *reinterpret_cast<const float4 *>(a.cs + (int64_t)kid * a.Hq + unit_ld);
+    const float *bias = a.bp + col * kGateTile + u4;
+    float z[4][4];
 #pragma unroll
-    for (int g = 1; g < 4; ++g)
+    for (int g = 0; g < 4; ++g) {
+        const float4 q = *reinterpret_cast<const float4 *>(&zt[g][tr * kEpiStride + u4]);
+        const float4 bq = *reinterpret_cast<const float4 *>(bias + g * kUnit);
+        z[g][0] = q.x + bq.x; z[g][1] = q.y + bq.y; z[g][2] = q.z + bq.z; z[g][3] = q.w + bq.w;
+    }
+    const float ckv[4] = {ck.x, ck.y, ck.z, ck.w};
+    float cc[4], go[4];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[g][v] = exchange[g - 1][v][lane];
-    cell_pass<T, MODE_CHAIN>(a, acc, region, s_node, s_ar, s_cb, s_kid, col, lane, bias);
+    for (int e = 0; e < 4; ++e) {
+        const float gi = sigmoid_t<T>(z[0][e]);
+        go[e] = sigmoid_t<T>(z[1][e]);
+        const float gu = tanh_t<T>(z[2][e]);
+        const float gf = sigmoid_t<T>(z[3][e]);
+        cc[e] = gi * gu + gf * ckv[e];
+    }
+    store_state<T>(a, node, unit0, make_float4(cc[0], cc[1], cc[2], cc[3]), make_float4(go[0], go[1], go[2], go[3]));
 }
 
 // ---- tile tables of a typed level --------------------------------------------------------
@@ -1371,13 +1451,18 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
     // below chain_from whose parent is such a node needs no projection either, so the level right
     // below skips it too.
     int chain_from = L;
-    if (!SAVE && !slots && s->host_level_kids && (d.D & 3) == 0) {
+    const int chain_k_bytes = (d.Dp + d.Hp) * d.esz;
+    const size_t chain_lds = chain_lds_bytes(chain_k_bytes);      // the tile's A rows live in LDS
+    if (!SAVE && !slots && s->host_level_kids && (d.D & 3) == 0 && chain_lds <= (size_t)kChainLdsMax) {
         for (int l = L - 1; l >= 1; --l) {
             const int rows = sp[l + 1] - sp[l];
             if (rows > kThinMaxRows || s->host_level_kids[l] != rows) break;
             chain_from = l;
         }
     }
+    if (chain_from < L)      // more dynamic LDS than a launch may ask for by default
+        JITDB_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&chain_kernel<T>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, kChainLdsMax));
     const int n_unit_tiles = d.Hu / kUnit;
     a.w_bytes = (int64_t)packed_w_bytes(d);
     a.NP = d.NP;
@@ -1405,7 +1490,7 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
             a.n_tiles = (int)ceil_div(n_rows, 32) * a.n_col_tiles;
             a.n_blocks = a.n_tiles;
             ScopedLaunchTimer tm(JITDB_K_CHAIN, n_rows, st);
-            chain_kernel<T><<<a.n_blocks, kThinWaves * 64, 0, st>>>(a);
+            chain_kernel<T><<<a.n_blocks, kThinWaves * 64, chain_lds, st>>>(a);
             JITDB_LAUNCH_CHECK();
             continue;
         }

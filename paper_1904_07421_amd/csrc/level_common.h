@@ -146,6 +146,55 @@ __device__ __forceinline__ CellBias load_cell_bias(const LevelArgs &a, int unit_
     return b;
 }
 
+// c and h = o * tanh(c) of four consecutive units of node nd, to c_out / h_out and to their padded
+// copies where those are separate arrays (pad columns of the padded h copy are zeroed).
+template <typename T>
+__device__ __forceinline__ void store_state(const LevelArgs &a, int64_t nd, int unit0, const float4 &cc, const float4 &go) {
+    T *h_out = static_cast<T *>(a.h_out);
+    T *hs_out = static_cast<T *>(a.hs_out);
+    const bool separate_hs = (a.hs_out != a.h_out);
+    const bool separate_cs = (a.cs != a.c_out);
+    const float c4[4] = {cc.x, cc.y, cc.z, cc.w};
+    const float o4[4] = {go.x, go.y, go.z, go.w};
+    T hv[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) hv[j] = from_f32<T>(o4[j] * tanh_t<T>(c4[j]));
+    if ((a.H & 3) == 0) {
+        if (unit0 < a.H) {
+            *reinterpret_cast<float4 *>(a.c_out + nd * a.H + unit0) = cc;
+            if (separate_cs) *reinterpret_cast<float4 *>(a.cs + nd * a.Hq + unit0) = cc;
+            if constexpr (sizeof(T) == 4) {
+                const float4 h4 = make_float4(hv[0], hv[1], hv[2], hv[3]);
+                *reinterpret_cast<float4 *>(h_out + nd * a.H + unit0) = h4;
+                if (separate_hs) *reinterpret_cast<float4 *>(hs_out + nd * a.Hp + unit0) = h4;
+            } else {
+                const uint2 h2 = make_uint2((uint32_t)hv[0] | ((uint32_t)hv[1] << 16),
+                                            (uint32_t)hv[2] | ((uint32_t)hv[3] << 16));
+                *reinterpret_cast<uint2 *>(h_out + nd * a.H + unit0) = h2;
+                if (separate_hs) *reinterpret_cast<uint2 *>(hs_out + nd * a.Hp + unit0) = h2;
+            }
+        } else if (separate_hs && unit0 < a.Hp) {   // zero pad columns of the padded h copy
+            if constexpr (sizeof(T) == 4)
+                *reinterpret_cast<float4 *>(hs_out + nd * a.Hp + unit0) = make_float4(0.f, 0.f, 0.f, 0.f);
+            else
+                *reinterpret_cast<uint2 *>(hs_out + nd * a.Hp + unit0) = make_uint2(0u, 0u);
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int unit = unit0 + j;
+            if (unit < a.H) {
+                a.c_out[nd * a.H + unit] = c4[j];
+                if (separate_cs) a.cs[nd * a.Hq + unit] = c4[j];
+                h_out[nd * a.H + unit] = hv[j];
+                if (separate_hs) hs_out[nd * a.Hp + unit] = hv[j];
+            } else if (separate_hs && unit < a.Hp) {
+                hs_out[nd * a.Hp + unit] = T(0);
+            }
+        }
+    }
+}
+
 template <typename T, int MODE, bool SAVE = false>
 __device__ __forceinline__ void cell_pass(const LevelArgs &a, const floatx16 (&acc)[4], float *region,
                                           const int *rn, const int *rar, const int *rcb,
@@ -156,11 +205,6 @@ __device__ __forceinline__ void cell_pass(const LevelArgs &a, const floatx16 (&a
     float *s_iu = region;
     float *s_o = s_iu + 32 * kEpiStride;
     float *s_fx = s_o + 32 * kEpiStride;
-    T *h_out = static_cast<T *>(a.h_out);
-    T *hs_out = static_cast<T *>(a.hs_out);
-    const bool separate_hs = (a.hs_out != a.h_out);
-    const bool separate_cs = (a.cs != a.c_out);
-    const bool vec_ok = (a.H & 3) == 0;
     const int unit0 = unit_tile * kUnit + (lane & 7) * 4;
     // unit groups past the padded width read the first group instead (and store nothing)
     const int unit_ld = unit0 < a.Hq ? unit0 : 0;
@@ -278,46 +322,7 @@ __device__ __forceinline__ void cell_pass(const LevelArgs &a, const floatx16 (&a
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         if (node[q] < 0) continue;
-        const float c4[4] = {cc[q].x, cc[q].y, cc[q].z, cc[q].w};
-        const float o4[4] = {go4[q].x, go4[q].y, go4[q].z, go4[q].w};
-        T hv[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) hv[j] = from_f32<T>(o4[j] * tanh_t<T>(c4[j]));
-        const int64_t nd = node[q];
-        if (vec_ok) {
-            if (unit0 < a.H) {
-                *reinterpret_cast<float4 *>(a.c_out + nd * a.H + unit0) = cc[q];
-                if (separate_cs) *reinterpret_cast<float4 *>(a.cs + nd * a.Hq + unit0) = cc[q];
-                if constexpr (sizeof(T) == 4) {
-                    const float4 h4 = make_float4(hv[0], hv[1], hv[2], hv[3]);
-                    *reinterpret_cast<float4 *>(h_out + nd * a.H + unit0) = h4;
-                    if (separate_hs) *reinterpret_cast<float4 *>(hs_out + nd * a.Hp + unit0) = h4;
-                } else {
-                    const uint2 h2 = make_uint2((uint32_t)hv[0] | ((uint32_t)hv[1] << 16),
-                                                (uint32_t)hv[2] | ((uint32_t)hv[3] << 16));
-                    *reinterpret_cast<uint2 *>(h_out + nd * a.H + unit0) = h2;
-                    if (separate_hs) *reinterpret_cast<uint2 *>(hs_out + nd * a.Hp + unit0) = h2;
-                }
-            } else if (separate_hs && unit0 < a.Hp) {   // zero pad columns of the padded h copy
-                if constexpr (sizeof(T) == 4)
-                    *reinterpret_cast<float4 *>(hs_out + nd * a.Hp + unit0) = make_float4(0.f, 0.f, 0.f, 0.f);
-                else
-                    *reinterpret_cast<uint2 *>(hs_out + nd * a.Hp + unit0) = make_uint2(0u, 0u);
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int unit = unit0 + j;
-                if (unit < a.H) {
-                    a.c_out[nd * a.H + unit] = c4[j];
-                    if (separate_cs) a.cs[nd * a.Hq + unit] = c4[j];
-                    h_out[nd * a.H + unit] = hv[j];
-                    if (separate_hs) hs_out[nd * a.Hp + unit] = hv[j];
-                } else if (separate_hs && unit < a.Hp) {
-                    hs_out[nd * a.Hp + unit] = T(0);
-                }
-            }
-        }
+        store_state<T>(a, node[q], unit0, cc[q], go4[q]);
     }
 }
 
