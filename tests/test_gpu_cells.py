@@ -49,7 +49,8 @@ def _check(parent, sig, positions, D, H, dtype, seed):
     h0, c0 = C.forward_cells(parent, sig, xo, ocells)
     dh, dc = np.abs(h - h0).max(), np.abs(c - c0).max()
     print(f"  N={n} cells={positions} D={D} H={H} {dtype}: max|dh| {dh:.3e} max|dc| {dc:.3e}", flush=True)
-    assert dh <= TOL[dtype] and dc <= TOL[dtype] * max(1.0, np.abs(c0).max())
+    # c is not bounded by 1: the flat bound holds up to max|c| = 8 (bf16) / 50 (fp32) and grows in proportion beyond
+    assert dh <= TOL[dtype] and dc <= TOL[dtype] * max(1.0, np.abs(c0).max() / (8.0 if dtype == "bf16" else 50.0))
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
