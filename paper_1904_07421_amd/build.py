@@ -143,6 +143,60 @@ def check_lds_read_waits(asm_text: str, kernel_substr: str = "level_kernel") -> 
     return seen
 
 
+_VMEM = re.compile(r"(global|buffer|flat|scratch)_(load|store|atomic)")
+
+
+def check_stage_loads(asm_text: str, kernel_substr: str = "level_kernel") -> int:
+    """Static check of the K loops of the kernels that move pipeline stages with direct-to-LDS loads
+    and wait for them with hand-written `s_waitcnt vmcnt(N)`: N is a number of loads of a YOUNGER
+    stage that may stay in flight, so it is only right if every wave issues exactly the expected
+    loads per stage and nothing else joins the same counter in between.  For every innermost loop
+    that holds MFMAs, the only vector-memory instructions must be global_load_lds_dwordx4, and their
+    number must be (loads per wave and stage) x (barriers in the loop): 5 for the leaf level kernel
+    (its blocks skip the forget rows), 6 otherwise.  Returns the number of loops examined."""
+    kernels, cur, name = [], None, None
+    for raw in asm_text.splitlines():
+        line = raw.split(";")[0].strip()
+        if not line:
+            continue
+        if line.endswith(":") and not line.startswith("."):
+            cur = [] if kernel_substr in line else None
+            if cur is not None:
+                kernels.append((line[:-1], cur))
+            continue
+        if cur is None or (line.startswith(".") and not line.endswith(":")):
+            continue
+        cur.append(line)
+    examined = 0
+    for name, body in kernels:
+        m = re.search(r"level_kernelI[a-z]Li(\d)E", name)
+        per_stage = 5 if (m and m.group(1) == "0") else 6
+        labels = {l[:-1]: i for i, l in enumerate(body) if l.endswith(":")}
+        loops = {}
+        for i, l in enumerate(body):
+            p = l.split()
+            if len(p) >= 2 and (p[0].startswith("s_cbranch") or p[0] == "s_branch") and p[1] in labels and labels[p[1]] <= i:
+                head = labels[p[1]]
+                loops[head] = max(loops.get(head, head), i)
+        with_mfma = [(a, b) for a, b in loops.items() if any(l.startswith("v_mfma") for l in body[a:b + 1])]
+        for a, b in with_mfma:
+            if any(a < a2 and b2 <= b for a2, b2 in with_mfma):
+                continue                                   # not innermost
+            seg = body[a:b + 1]
+            other = [l for l in seg if _VMEM.match(l) and not l.startswith("global_load_lds_dwordx4")]
+            if other:
+                raise RuntimeError(f"{name}: a K loop holds a vector-memory instruction besides the stage loads: {other[0]}")
+            n_dma = sum(1 for l in seg if l.startswith("global_load_lds_dwordx4"))
+            n_bar = sum(1 for l in seg if l.startswith("s_barrier"))
+            if n_dma == 0 and n_bar == 0:
+                continue                                   # a loop of MFMAs on operands that do not come through stages
+            if n_bar == 0 or n_dma != per_stage * n_bar:
+                raise RuntimeError(f"{name}: a K loop issues {n_dma} stage loads for {n_bar} barrier(s); "
+                                   f"the hand-placed waits assume {per_stage} per stage")
+            examined += 1
+    return examined
+
+
 def build(verbose: bool = False) -> str:
     """Always recompiles every source; returns the path of the shared library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -171,6 +225,10 @@ def build(verbose: bool = False) -> str:
             raise RuntimeError(f"the device assembly of {stem}.hip was not produced; cannot check it")
         if check_lds_read_waits(asm_texts[stem], name) == 0:
             raise RuntimeError(f"no LDS reads found in the assembly of {name}: the check is not looking at it")
+    # the K loops whose waits for direct-to-LDS stage loads are hand-counted
+    for name in ("level_kernel", "gemm_kb_kernel"):
+        if check_stage_loads(asm_texts["forward"], name) == 0:
+            raise RuntimeError(f"no K loop with stage loads found in the assembly of {name}: the check is not looking at it")
     if verbose and out.strip():
         print(out)
     return LIB

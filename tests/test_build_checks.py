@@ -55,3 +55,34 @@ def test_spilling_kernel_is_refused():
     with pytest.raises(RuntimeError, match="scratch"):
         B._check_no_scratch(lines)
     B._check_no_scratch([l.replace(": 16 ", ": 0 ") for l in lines])
+
+
+# ---- stage loads per K loop ------------------------------------------------------------------
+def _k_loop(mode: int, n_loads: int, extra: str = "") -> str:
+    loads = "".join("\tglobal_load_lds_dwordx4 v[2:3], off\n\tv_mfma_f32_32x32x16_bf16 v[20:35], v[10:13], v[10:13], v[20:35]\n"
+                    for _ in range(n_loads))
+    return (f"_ZN5jitdb12_GLOBAL__N_112level_kernelItLi{mode}ELb0ELb0EEEvNS_9LevelArgsE:\n"
+            "\ts_load_dwordx2 s[0:1], s[4:5], 0x0\n"
+            ".LBB0_1:\n" + loads + extra +
+            "\ts_waitcnt vmcnt(6) lgkmcnt(0)\n\ts_barrier\n"
+            "\ts_cbranch_scc1 .LBB0_1\n"
+            "\tglobal_store_dwordx4 v[0:1], v[20:23], off\n"
+            "\ts_endpgm\n")
+
+
+def test_stage_load_count_per_k_loop():
+    assert B.check_stage_loads(_k_loop(1, 6)) == 1          # internal / projection / plain GEMM: 6 per stage
+    assert B.check_stage_loads(_k_loop(0, 5)) == 1          # leaf: 5
+    with pytest.raises(RuntimeError, match="assume 6 per stage"):
+        B.check_stage_loads(_k_loop(1, 5))
+    with pytest.raises(RuntimeError, match="assume 5 per stage"):
+        B.check_stage_loads(_k_loop(0, 6))
+
+
+def test_foreign_vector_memory_instruction_in_a_k_loop_is_refused():
+    with pytest.raises(RuntimeError, match="besides the stage loads"):
+        B.check_stage_loads(_k_loop(1, 6, extra="\tglobal_load_dwordx4 v[40:43], v[2:3], off\n"))
+    with pytest.raises(RuntimeError, match="besides the stage loads"):
+        B.check_stage_loads(_k_loop(1, 6, extra="\tglobal_store_dword v[2:3], v40, off\n"))
+    # the same instructions outside the loop are none of its business
+    assert B.check_stage_loads(_k_loop(1, 6)) == 1
