@@ -510,3 +510,50 @@ def test_chain_levels_need_the_child_counts_and_whole_x_pieces(c_oracle, dtype):
             assert launches2["chain"] == 0 and launches2["thin_proj"] > launches["thin_proj"]
             h2, c2 = res2[0].float().cpu().numpy(), res2[1].cpu().numpy()
             assert np.abs(h2 - h).max() <= TOL[dtype] and np.abs(c2 - c).max() <= TOL[dtype] * _c_scale(dtype, co)
+
+
+def test_chain_levels_inside_a_captured_graph(c_oracle):
+    """The single-launch kernel of chain levels asks for more dynamic LDS than the default; the attribute is
+    set outside the stream's work, so the forward still records into a HIP graph and every replay matches."""
+    import torch
+    import paper_1904_07421_amd as J
+    from gpu_util import dev_parent
+    parent = _trees_and_sequences(60, 200, 50, 8)
+    D, H = 300, 256
+    x, W, U, b = make_values(2, parent.shape[0], "random", D=D, H=H)
+    s = J.jitdb_schedule(dev_parent(parent))
+    n = parent.shape[0]
+    assert (s.host_level_kids[s.n_levels - 10:s.n_levels] == np.diff(s.host_level_ptr[s.n_levels - 10:s.n_levels + 1])).all()
+    Wt, Ut, bt = (torch.from_numpy(a).cuda() for a in (W, U, b))
+    xt = torch.from_numpy(x).cuda()
+    h = torch.empty((n, H), device="cuda"); c = torch.empty((n, H), device="cuda")
+    ws = torch.empty(J.jitdb_treelstm_workspace_bytes(n, s.n_edges, D, H, J.JITDB_F32), dtype=torch.uint8, device="cuda")
+    st = torch.cuda.Stream()
+    st.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(st):                      # warm-up on the capture stream
+        J.jitdb_treelstm_forward(xt, Wt, Ut, bt, s, stream=st, workspace=ws, out=(h, c))
+    st.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=st):
+        J.jitdb_treelstm_forward(xt, Wt, Ut, bt, s, stream=st, workspace=ws, out=(h, c))
+    for scale in (1.0, -0.5, 2.0):
+        xs = (x * scale).astype(np.float32)
+        xt.copy_(torch.from_numpy(xs).cuda())        # eager work between replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        ho, co, _ = c_oracle(parent, xs, W, U, b)
+        assert np.abs(h.cpu().numpy() - ho).max() <= 1e-4 and np.abs(c.cpu().numpy() - co).max() <= 1e-4
+
+
+def test_chain_levels_too_wide_for_lds_take_the_general_launches(c_oracle):
+    """K = D + H so large that 32 rows of A do not fit the LDS the kernel may use: same result, other launches."""
+    parent = chain_forest(12, 40)
+    D, H = 1024, 1280                                  # 32 x (9216 + 16) bytes > 128 KB
+    x, W, U, b = make_values(2, parent.shape[0], "random", D=D, H=H)
+    (res, launches) = _profile_classes(lambda: run_gpu_forward(parent, x, W, U, b, "f32"))
+    _, h, c, seen = res
+    assert launches["chain"] == 0 and launches["thin_internal"] == 11
+    ho, co = _oracle(c_oracle, parent, seen)
+    eh, ec = _report("wide chain/f32", h, c, ho, co)
+    assert eh <= 1e-4 and ec <= 1e-4 * _c_scale("f32", co)
