@@ -320,6 +320,13 @@ size_t jitdb_treelstm_workspace_bytes(int64_t n_nodes, int64_t n_edges,
  * Fully asynchronous on `hip_stream`: level sizes come from s->host_level_ptr,
  * no device-to-host copy or synchronisation happens.  Levels run in order on
  * that one stream.  N == 0 succeeds and launches nothing.
+ *
+ * If s->host_level_kids is set, the run of top levels in which every node has
+ * exactly one child (kids == nodes of the level; sequences, thin tails) takes
+ * one launch per level that reads x and the child's h, c in place; the results
+ * agree with the general launches within rounding (the forget gate's two
+ * products are then summed in one accumulator).  Without it every level takes
+ * the general launches.
  */
 int jitdb_treelstm_forward(const void *x, const void *W, const void *U, const float *b,
                            int32_t D, int32_t H, jitdb_dtype dtype,
