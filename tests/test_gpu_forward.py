@@ -81,12 +81,16 @@ def _sampled_tree_check(c_oracle, cfg, n_sample, dtype=None, bias="zero", D=None
 
 
 def _progress(line):
-    """Long tests say where they are: a line on stdout and one in a file the GPU runner watches."""
+    """Long tests say where they are: a line on stdout and, if JITDB_PROGRESS_DIR names a directory,
+    one in a file there (for a runner that watches files rather than captured output)."""
     import os
     print(line, flush=True)
+    d = os.environ.get("JITDB_PROGRESS_DIR")
+    if not d:
+        return
     try:
-        os.makedirs("gpurun_out", exist_ok=True)
-        with open(os.path.join("gpurun_out", "parity_progress.txt"), "a") as f:
+        os.makedirs(d, exist_ok=True)
+        with open(os.path.join(d, "parity_progress.txt"), "a") as f:
             f.write(line + "\n")
     except OSError:
         pass
