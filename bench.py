@@ -183,6 +183,92 @@ def typed_bench(args, J, torch, cfg, dev, N, D, H, esz, peak_tflops, xt, parent,
     print(json.dumps(out), flush=True)
 
 
+def nary_bench(args, J, torch, cfg, dev, D, H, esz, peak_tflops):
+    """A second operator type in the table: trees with at most --nary children per node (binarised parse
+    trees for 2), as many trees and nodes per tree as the config, every node under ONE N-ary Tree-LSTM
+    cell.  step = jitdb_schedule_typed + jitdb_treelstm_forward_cells, one stream; the states of a sample
+    of trees are checked against the cells oracle (fp64, numpy)."""
+    from workloads import bounded_arity_forest, make_cell_values, make_values, to_bf16_bits, bf16_bits_to_f32, tree_ranges
+    Nc = args.nary
+    t0 = time.time()
+    parent = bounded_arity_forest(cfg.n_trees, cfg.size_lo, cfg.size_hi, Nc, 700 + cfg.index)
+    N = int(parent.shape[0])
+    x = make_values(cfg.index, N, "zero", D=D, H=H)[0]
+    (W, U, b), = make_cell_values([Nc], D, H, 800 + cfg.index)
+    log(f"{cfg.n_trees} trees with at most {Nc} children per node: N={N} generated in {time.time() - t0:.1f}s")
+    if esz == 2:
+        def up(a):
+            bits = to_bf16_bits(a)
+            return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(dev), bf16_bits_to_f32(bits)
+    else:
+        def up(a):
+            return torch.from_numpy(a).to(dev), a
+    (xt, xs), (Wt, Ws), (Ut, Us) = up(x), up(W), up(U)
+    bt = torch.from_numpy(b).to(dev)
+    pt = torch.from_numpy(parent).to(dev)
+    st_ = torch.zeros(N, dtype=torch.int32, device=dev)
+    dt = J.JITDB_BF16 if esz == 2 else J.JITDB_F32
+    sched = J.jitdb_schedule_typed(pt, st_, 1)
+    E = sched.n_edges
+    cells = [(J.JITDB_CELL_NARY, Nc, Wt, Ut, bt)]
+    ws_s = torch.empty(J.jitdb_schedule_typed_workspace_bytes(N, 1), dtype=torch.uint8, device=dev)
+    ws_f = torch.empty(J.jitdb_treelstm_cells_workspace_bytes(N, E, D, H, dt, [(J.JITDB_CELL_NARY, Nc)]),
+                       dtype=torch.uint8, device=dev)
+    h = torch.empty((N, H), dtype=xt.dtype, device=dev)
+    c = torch.empty((N, H), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def sch():
+        J.jitdb_schedule_typed(pt, st_, 1, stream=stream, workspace=ws_s, out=sched)
+
+    def fwd():
+        J.jitdb_treelstm_forward_cells(xt, cells, sched, stream=stream, workspace=ws_f, out=(h, c))
+
+    for _ in range(args.warmup):
+        sch(); fwd()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        sch(); fwd()
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        fwd()
+    torch.cuda.synchronize()
+    ms_f = (time.perf_counter() - t0) * 1e3 / args.steps
+    # algorithmic work: a leaf needs i, o, u from x; an internal node all 3 + N gates from x and from each child's h
+    n_leaf = int(sched.host_level_ptr[1])
+    f_alg = n_leaf * 2.0 * D * 3 * H + (N - n_leaf) * 2.0 * D * (3 + Nc) * H + E * 2.0 * H * (3 + Nc) * H
+    # parity of the timed output on the first trees
+    from oracle import treelstm_cells_oracle as C
+    r = tree_ranges(parent)
+    k = int(np.searchsorted(r, 4000))
+    n_s = int(r[max(k, 1)])
+    ho, co = C.forward_cells(parent[:n_s], np.zeros(n_s, np.int32), xs[:n_s], [C.nary_cell(Nc, Ws, Us, b)])
+    hg, cg = h[:n_s].float().cpu().numpy(), c[:n_s].cpu().numpy()
+    tol = 2e-2 if esz == 2 else 1e-4
+    dh, dc = float(np.abs(hg - ho).max()), float(np.abs(cg - co).max())
+    ok = bool(dh <= tol and dc <= tol * max(1.0, float(np.abs(co).max()) / (8.0 if esz == 2 else 50.0)))
+    out = {
+        "metric": f"Tree-LSTM forward nodes/sec on 1 MI355X, {Nc}-ary cell", "value": N / (ms_step * 1e-3),
+        "unit": "nodes/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.n_trees} trees of {cfg.size_lo}-{cfg.size_hi} nodes, at most {Nc} children per node, "
+                               f"one {Nc}-ary Tree-LSTM cell", "n_nodes": N, "n_edges": E, "n_levels": sched.n_levels,
+                   "D": D, "H": H, "step": "jitdb_schedule_typed + jitdb_treelstm_forward_cells, one stream"},
+        "ms_forward": ms_f,
+        "roofline": {"kernel": "N-ary forward as a whole (nary_stack_kernel, gemm_kb_kernel, nary_cell_kernel per slot)",
+                     "bound": "mfma", "achieved": f_alg / (ms_f * 1e-3) / 1e12, "peak": peak_tflops, "unit": "TFLOP/s",
+                     "frac": f_alg / (ms_f * 1e-3) / 1e12 / peak_tflops, "traffic": None, "flops_per_step": f_alg},
+        "parity": {"nodes": n_s, "max_abs_dh": dh, "max_abs_dc": dc, "tolerance": tol, "ok": ok},
+    }
+    print(json.dumps(out), flush=True)
+    if not ok:
+        sys.exit(1)
+
+
 def log(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
@@ -208,6 +294,9 @@ def main():
                          "(jitdb_schedule_typed + jitdb_treelstm_forward_typed); not the headline metric")
     ap.add_argument("--signatures-per-node", action="store_true",
                     help="with --signatures >= 2: draw the signature per node (leaves cell 0, others 1..n-1) instead of per tree")
+    ap.add_argument("--nary", type=int, default=0,
+                    help="time a table with one N-ary Tree-LSTM cell (N = this, 1..4) over trees of bounded arity "
+                         "(jitdb_schedule_typed + jitdb_treelstm_forward_cells); not the headline metric")
     ap.add_argument("--serial", action="store_true",
                     help="schedule and forward of a batch strictly one after the other on one stream "
                          "(default: the schedule of the next batch overlaps the forward of this one)")
@@ -224,6 +313,10 @@ def main():
     cfg = CONFIGS[args.config]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.nary > 0:
+        bf = cfg.dtype == "bf16"
+        return nary_bench(args, J, torch, cfg, dev, cfg.D, cfg.H, 2 if bf else 4,
+                          PEAK_BF16_TFLOPS if bf else PEAK_F32_MFMA_TFLOPS)
 
     t0 = time.time()
     parent = make_forest(cfg.index)

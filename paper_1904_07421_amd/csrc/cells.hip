@@ -57,11 +57,12 @@ nary_pack_kernel(const T *__restrict__ W, const T *__restrict__ U, int D, int H,
 // has positions sets *err; the surplus children are left out.
 template <typename T>
 __global__ void __launch_bounds__(kThreads)
-nary_stack_kernel(const T *__restrict__ x, int D, int Dp, const T *__restrict__ hs, int Hp, int N,
+nary_stack_kernel(const T *__restrict__ x, int D, int Dp, const T *__restrict__ hs, int Hp, int N, int Nk,
                   const int4 *__restrict__ row_rec, T *__restrict__ A, int n_rows, int n_rows_alloc,
                   int *__restrict__ err) {
+    // N: the cell's child positions; Nk <= N: positions stacked for this slot (0 for a slot of leaves)
     constexpr int VEC = Traits<T>::VEC;
-    const int cpr = (Dp + N * Hp) / VEC;
+    const int cpr = (Dp + Nk * Hp) / VEC;
     const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     const int64_t row = gid / cpr;
     const int ch = (int)(gid % cpr);
@@ -167,23 +168,25 @@ int run_nary_slot(jitdb_dtype dtype, const LevelArgs &a, const NarySlot &s, hipS
     if (s.n_rows <= 0) return JITDB_OK;
     const size_t esz = dtype == JITDB_F32 ? 4 : 2;
     const int vec = dtype == JITDB_F32 ? 4 : 8;
-    const int Kn = a.Dp + s.N * a.Hp;
+    const int Nk = s.leaves ? 0 : s.N;                       // child positions this slot stacks and multiplies
+    const int Kn = a.Dp + Nk * a.Hp;
     const int rows_alloc = (int)round_up(s.n_rows, kRowPad);
     const unsigned sblocks = (unsigned)ceil_div((int64_t)s.n_rows * (Kn / vec), kThreads);
     if (dtype == JITDB_F32)
         nary_stack_kernel<float><<<sblocks, kThreads, 0, st>>>(static_cast<const float *>(s.x), a.D, a.Dp,
-                                                              static_cast<const float *>(a.hs), a.Hp, s.N, s.row_rec,
+                                                              static_cast<const float *>(a.hs), a.Hp, s.N, Nk, s.row_rec,
                                                               static_cast<float *>(s.A), s.n_rows, rows_alloc, s.err);
     else
         nary_stack_kernel<bf16_t><<<sblocks, kThreads, 0, st>>>(static_cast<const bf16_t *>(s.x), a.D, a.Dp,
-                                                               static_cast<const bf16_t *>(a.hs), a.Hp, s.N, s.row_rec,
+                                                               static_cast<const bf16_t *>(a.hs), a.Hp, s.N, Nk, s.row_rec,
                                                                static_cast<bf16_t *>(s.A), s.n_rows, rows_alloc, s.err);
     JITDB_LAUNCH_CHECK();
     KbGemm g = {};
     g.A = s.A; g.a_rows_alloc = rows_alloc; g.M = s.n_rows;
-    g.B = s.Bn; g.b_rows_alloc = round_up((int64_t)(3 + s.N) * a.H, 256); g.N = (3 + s.N) * a.H;
+    // leaves: the gates i, o, u only (the first 3 H packed rows), over the x part of K (the first slabs)
+    g.B = s.Bn; g.b_rows_alloc = round_up((int64_t)(3 + s.N) * a.H, 256); g.N = (3 + Nk) * a.H;
     g.k_bytes = (int64_t)Kn * (int64_t)esz; g.k_splits = 1;
-    g.epilogue = KB_EPI_STORE_F32; g.out0 = s.Z; g.ldc = g.N;
+    g.epilogue = KB_EPI_STORE_F32; g.out0 = s.Z; g.ldc = (3 + s.N) * a.H;
     const int rc = launch_kb_gemm(dtype, g, st);
     if (rc != JITDB_OK) return rc;
     NaryCellArgs c;

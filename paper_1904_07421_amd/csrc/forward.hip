@@ -1498,7 +1498,7 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
             // a slot of N-ary nodes: stack, one contraction for all 3 + N gates, cell update (cells.hip)
             NarySlot ns;
             ns.x = x; ns.row_rec = a.row_rec; ns.A = w.nary_A; ns.Bn = w.nary_B[sig]; ns.b = cells[sig].b;
-            ns.Z = w.nary_Z; ns.err = w.nary_err; ns.n_rows = n_rows; ns.N = cells[sig].arity;
+            ns.Z = w.nary_Z; ns.err = w.nary_err; ns.n_rows = n_rows; ns.N = cells[sig].arity; ns.leaves = l == 0;
             ScopedLaunchTimer tm(l == 0 ? JITDB_K_THIN_LEAF : JITDB_K_THIN_INTERNAL, n_rows, st);
             const int rc = run_nary_slot(dtype, a, ns, st);
             if (rc != JITDB_OK) return rc;

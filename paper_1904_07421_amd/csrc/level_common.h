@@ -395,6 +395,7 @@ struct NarySlot {
     float *Z;               // workspace: pre-activations [n_rows, (3 + N) H]
     int *err;               // device flag: set when a node has more children than the cell has positions
     int n_rows, N;
+    bool leaves;            // a slot of level 0: no children, so K is the x part alone and the forget gates are not needed
 };
 size_t nary_packed_bytes(int D, int H, int Dp, int Hp, int N, size_t esz);
 int nary_pack(jitdb_dtype dtype, const void *W, const void *U, int D, int H, int Dp, int Hp, int N, void *Bn,
