@@ -126,6 +126,21 @@ def schedule(parent) -> dict:
                 n_levels=L, n_edges=int(child_ptr[n]))
 
 
+def level_kids(parent) -> np.ndarray:
+    """kids[l] = number of children of the nodes of level l (0 for the leaves), l < L: every non-root
+    node counts once, for the level of its parent.  Derived data of the schedule (the sum of the
+    arities over a level); the forward only uses it to pick kernels."""
+    parent = np.asarray(parent)
+    validate(parent)
+    h = heights(parent)
+    L = int(h.max()) + 1 if parent.shape[0] else 0
+    kids = np.zeros(L, dtype=np.int64)
+    for v in range(parent.shape[0]):
+        if parent[v] >= 0:
+            kids[int(h[int(parent[v])])] += 1
+    return kids
+
+
 def schedule_fast(parent) -> dict:
     """Same outputs as `schedule` for large forests, using numpy routines
     (stable argsort, bincount) and a level-by-level height sweep.  Checked

@@ -45,7 +45,7 @@ def run_gpu_forward(parent, x, W, U, b, dtype: str):
 def assert_schedule_equal(got: dict, want: dict):
     assert got["n_levels"] == want["n_levels"], (got["n_levels"], want["n_levels"])
     assert got["n_edges"] == want["n_edges"]
-    if "level_kids" in got:     # children per level, from the oracle's heights and child lists
+    if "level_kids" in got:     # children per level: the sum of the oracle's arities over each level
         arity = np.diff(np.asarray(want["child_ptr"]))
         kids = np.bincount(np.asarray(want["height"]), weights=arity, minlength=want["n_levels"]).astype(np.int64)
         assert np.array_equal(np.asarray(got["level_kids"]), kids), ("level_kids", got["level_kids"][:8], kids[:8])

@@ -21,6 +21,8 @@ def test_configs_bit_exact(cfg):
     got = _run(p).to_numpy()
     want = S.schedule(p) if p.shape[0] < 6000 else S.schedule_fast(p)
     assert_schedule_equal(got, want)
+    if p.shape[0] < 6000:                   # children per level against the oracle's own count
+        assert np.array_equal(got["level_kids"], S.level_kids(p))
 
 
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4])

@@ -152,3 +152,22 @@ def test_concat_forests_keeps_each_forest_intact():
     assert sj["n_edges"] == sa["n_edges"] + sb["n_edges"]
     assert np.array_equal(sj["child_idx"][:sa["n_edges"]], sa["child_idx"])
     assert np.array_equal(sj["child_idx"][sa["n_edges"]:], sb["child_idx"] + len(a))
+
+
+def test_children_per_level_closed_forms_and_identities():
+    """chain: one child per level above the leaf; star: all n - 1 under level 1; perfect k-ary: k times
+    the level's size; in general the sum is E, level 0 has none, and a level's count is the sum of its
+    nodes' arities from the child lists."""
+    assert S.level_kids(chain_forest(9)).tolist() == [0] + [1] * 8
+    assert S.level_kids(star_forest(12)).tolist() == [0, 11]
+    k, d = 3, 3
+    assert S.level_kids(perfect_kary_tree(k, d)).tolist() == [0] + [k * k ** (d - l) for l in range(1, d + 1)]
+    assert S.level_kids(np.zeros(0, np.int32)).tolist() == []
+    for cfg in (1, 2):
+        p = make_forest(cfg)
+        s = S.schedule(p)
+        kids = S.level_kids(p)
+        assert kids[0] == 0 and kids.sum() == s["n_edges"] and len(kids) == s["n_levels"]
+        arity = np.diff(s["child_ptr"])
+        assert kids.tolist() == [int(arity[s["height"] == l].sum()) for l in range(s["n_levels"])]
+        assert (kids[1:] >= np.diff(s["level_ptr"])[1:]).all()      # every node above the leaves has a child
