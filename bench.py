@@ -503,7 +503,7 @@ def main():
     roof = None
     if prof is not None:
         proj_rows = (prof["proj"]["rows"] + prof["thin_proj"]["rows"]) / args.steps   # includes roots, whose P nobody reads
-        chain_rows = prof["chain"]["rows"] / args.steps      # one edge each, projected inside the chain launch
+        chain_rows = prof["chain"]["edges"] / args.steps     # edges projected inside the chain launches (one per row)
         for name in ("leaf", "internal", "proj", "thin_leaf", "thin_internal", "thin_proj", "chain"):
             job = name.replace("thin_", "")
             ms = prof[name]["ms"] / args.steps

@@ -458,6 +458,8 @@ typedef struct {
     double ms[JITDB_K_CLASSES];        /* summed event time per class, milliseconds */
     int64_t launches[JITDB_K_CLASSES]; /* recorded launches per class */
     int64_t rows[JITDB_K_CLASSES];     /* level rows (nodes) those launches covered; 0 for PACK */
+    int64_t edges[JITDB_K_CLASSES];    /* children whose forget projections those launches computed themselves
+                                          (CHAIN); 0 for the classes that read them from the projection step */
     int64_t dropped;                   /* launches that found no free event pair */
 } jitdb_profile_t;
 

@@ -67,7 +67,7 @@ class _CellStruct(ctypes.Structure):
 
 class _ProfileStruct(ctypes.Structure):
     _fields_ = [("ms", ctypes.c_double * 9), ("launches", ctypes.c_int64 * 9),
-                ("rows", ctypes.c_int64 * 9), ("dropped", ctypes.c_int64)]
+                ("rows", ctypes.c_int64 * 9), ("edges", ctypes.c_int64 * 9), ("dropped", ctypes.c_int64)]
 
 
 _lib = None
@@ -215,7 +215,7 @@ def jitdb_profile_stop() -> dict:
     """{class: {"ms": total milliseconds, "launches": count, "rows": level rows covered}} plus "dropped"."""
     p = _ProfileStruct()
     _check(load_library().jitdb_profile_stop(ctypes.byref(p)))
-    out = {name: {"ms": float(p.ms[i]), "launches": int(p.launches[i]), "rows": int(p.rows[i])}
+    out = {name: {"ms": float(p.ms[i]), "launches": int(p.launches[i]), "rows": int(p.rows[i]), "edges": int(p.edges[i])}
            for i, name in enumerate(K_CLASSES)}
     out["dropped"] = int(p.dropped)
     return out

@@ -1207,18 +1207,21 @@ struct Profiler {
     hipEvent_t *begin = nullptr, *end = nullptr;
     int *cls = nullptr;
     int64_t *rows = nullptr;
+    int64_t *edges = nullptr;
 };
 Profiler g_prof;
 
 struct ScopedLaunchTimer {
     int slot = -1;
     hipStream_t st;
-    ScopedLaunchTimer(int kernel_class, int64_t rows, hipStream_t s) : st(s) {
+    // edges: children whose forget gates the launch computes in full (chain levels); else 0
+    ScopedLaunchTimer(int kernel_class, int64_t rows, hipStream_t s, int64_t edges = 0) : st(s) {
         if (!g_prof.on) return;
         if (g_prof.used >= g_prof.capacity) { ++g_prof.dropped; return; }
         slot = g_prof.used++;
         g_prof.cls[slot] = kernel_class;
         g_prof.rows[slot] = rows;
+        g_prof.edges[slot] = edges;
         (void)hipEventRecord(g_prof.begin[slot], st);
     }
     ~ScopedLaunchTimer() {
@@ -1489,7 +1492,7 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
             a.n_col_tiles = n_unit_tiles;
             a.n_tiles = (int)ceil_div(n_rows, 32) * a.n_col_tiles;
             a.n_blocks = a.n_tiles;
-            ScopedLaunchTimer tm(JITDB_K_CHAIN, n_rows, st);
+            ScopedLaunchTimer tm(JITDB_K_CHAIN, n_rows, st, s->host_level_kids[l]);
             chain_kernel<T><<<a.n_blocks, kThinWaves * 64, chain_lds, st>>>(a);
             JITDB_LAUNCH_CHECK();
             continue;
@@ -1660,7 +1663,7 @@ void profiler_release() {
         if (g_prof.begin && g_prof.begin[i]) (void)hipEventDestroy(g_prof.begin[i]);
         if (g_prof.end && g_prof.end[i]) (void)hipEventDestroy(g_prof.end[i]);
     }
-    delete[] g_prof.begin; delete[] g_prof.end; delete[] g_prof.cls; delete[] g_prof.rows;
+    delete[] g_prof.begin; delete[] g_prof.end; delete[] g_prof.cls; delete[] g_prof.rows; delete[] g_prof.edges;
     g_prof = Profiler();
 }
 }  // namespace
@@ -1673,8 +1676,9 @@ extern "C" int jitdb_profile_start(int32_t capacity) {
     g_prof.end = new (std::nothrow) hipEvent_t[capacity]();
     g_prof.cls = new (std::nothrow) int[capacity]();
     g_prof.rows = new (std::nothrow) int64_t[capacity]();
+    g_prof.edges = new (std::nothrow) int64_t[capacity]();
     g_prof.capacity = capacity;
-    if (!g_prof.begin || !g_prof.end || !g_prof.cls || !g_prof.rows) {
+    if (!g_prof.begin || !g_prof.end || !g_prof.cls || !g_prof.rows || !g_prof.edges) {
         profiler_release();
         return JITDB_E_NOMEM;
     }
@@ -1695,7 +1699,7 @@ extern "C" int jitdb_profile_stop(jitdb_profile_t *out) {
     if (!g_prof.on) return JITDB_E_BADARG;
     g_prof.on = false;
     int rc = JITDB_OK;
-    for (int c = 0; c < JITDB_K_CLASSES; ++c) { out->ms[c] = 0.0; out->launches[c] = 0; out->rows[c] = 0; }
+    for (int c = 0; c < JITDB_K_CLASSES; ++c) { out->ms[c] = 0.0; out->launches[c] = 0; out->rows[c] = 0; out->edges[c] = 0; }
     out->dropped = g_prof.dropped;
     for (int i = 0; i < g_prof.used; ++i) {
         float ms = 0.0f;
@@ -1707,6 +1711,7 @@ extern "C" int jitdb_profile_stop(jitdb_profile_t *out) {
         out->ms[g_prof.cls[i]] += ms;
         out->launches[g_prof.cls[i]] += 1;
         out->rows[g_prof.cls[i]] += g_prof.rows[i];
+        out->edges[g_prof.cls[i]] += g_prof.edges[i];
     }
     profiler_release();
     return rc;
