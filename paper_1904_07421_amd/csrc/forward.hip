@@ -831,19 +831,27 @@ constexpr int kThinAhead = 8;      // K groups in flight per wave
 template <typename T, int MODE, bool SAVE = false>
 __device__ __forceinline__ void thin_body(const LevelArgs &a, int tile) {
     constexpr int ESZ = (int)sizeof(T);
-    __shared__ __attribute__((aligned(16))) float region[3 * 32 * kEpiStride];
-    __shared__ __attribute__((aligned(16))) float exchange[3][16][64];   // accumulators of waves 1-3
+    // one block of LDS, used as region + exchange (training: wave 0 runs cell_pass) or as the four
+    // gates' pre-activations (cell_rows)
+    constexpr int kRegionFloats = 3 * 32 * kEpiStride;
+    constexpr int kExchangeFloats = 3 * 16 * 64;
+    static_assert(kRegionFloats + kExchangeFloats >= 4 * 32 * kEpiStride, "the gates of a tile must fit");
+    __shared__ __attribute__((aligned(16))) float smem[kRegionFloats + kExchangeFloats];
+    float *region = smem;
+    float (*exchange)[16][64] = reinterpret_cast<float (*)[16][64]>(smem + kRegionFloats);   // accumulators of waves 1-3
     __shared__ int s_node[32];
     __shared__ int s_ar[32];
     __shared__ int s_cb[32];
     __shared__ int4 s_kid[32];
+    constexpr bool ROWS = (MODE != MODE_PROJ) && !SAVE;      // the cell update is shared out over the four waves
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int hf = lane >> 5, l32 = lane & 31;
     const int row0 = (tile / a.n_col_tiles) * 32;
     const int col = tile % a.n_col_tiles;     // unit tile (gates) or group of four unit tiles (projection)
-    if (MODE == MODE_LEAF && wave == 3) return;                                   // leaves have no forget gate
+    // leaves have no forget gate: its wave multiplies nothing (and, where wave 0 does the whole cell update, leaves)
+    if (MODE == MODE_LEAF && wave == 3 && !ROWS) return;
     if (MODE == MODE_PROJ && (col * 4 + wave) * kUnit >= a.Hu) return;            // past the last unit tile
 
     // ---- the tile's rows
@@ -885,6 +893,7 @@ __device__ __forceinline__ void thin_body(const LevelArgs &a, int tile) {
         bp = static_cast<const char *>(a.Bp) + operand_offset(row, 0, a.NPU) + hf * 16;
         // the forget rows take part in the x part only (U_f applies to each child's own h)
         n_groups = (a.Dp + (MODE == MODE_INTERNAL && wave != 3 ? a.Hp : 0)) * ESZ / 32;
+        if (MODE == MODE_LEAF && wave == 3) n_groups = 0;
     }
     b_pair = (int64_t)a.NPU * 64;
 
@@ -928,6 +937,15 @@ __device__ __forceinline__ void thin_body(const LevelArgs &a, int tile) {
             const int node = __shfl(my_node, rl, 64);      // lane rl holds the node of tile row rl (all lanes take part)
             if (unit < a.H && row0 + rl < a.n_rows) P[(int64_t)node * a.Hq + unit] = from_f32<T>(acc[0][v]);
         }
+    } else if constexpr (ROWS) {
+        // the gates meet in LDS; every wave finishes eight of the tile's rows
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int rl = (v >> 2) * 8 + hf * 4 + (v & 3);
+            smem[wave * (32 * kEpiStride) + rl * kEpiStride + l32] = acc[0][v];
+        }
+        __syncthreads();
+        cell_rows<T, MODE>(a, smem, s_node, s_ar, s_cb, s_kid, col, wave, lane);
     } else {
         // gates 1-3 travel to wave 0, which holds gate 0 (every wave that is still here
         // reaches this barrier; the forget wave of a leaf level left above)

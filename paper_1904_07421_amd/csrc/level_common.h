@@ -326,6 +326,75 @@ __device__ __forceinline__ void cell_pass(const LevelArgs &a, const floatx16 (&a
     }
 }
 
+// ---- the cell update of a 32 x 32 tile by four waves: wave w finishes rows 8 w .. 8 w + 7 -------------
+// For the kernels of small levels, where the tile's latency is what a level costs: zt holds the four
+// gates' pre-activations (without bias) as [gate][row][unit] (kEpiStride floats per row); eight lanes
+// share a row, four units each, and walk that row's own child list four children at a time (P_k and
+// c_k of four children in flight per lane), in ascending child order.  With one wave for all 32 rows
+// (cell_pass) every row waits for the tile's longest child list; here a wave waits for the longest
+// of its eight rows, and four waves' loads are in flight together.
+template <typename T, int MODE>
+__device__ __forceinline__ void cell_rows(const LevelArgs &a, const float *zt, const int *rn, const int *rar,
+                                          const int *rcb, const int4 *rkid, int unit_tile, int wave, int lane) {
+    const int tr = wave * 8 + (lane >> 3);
+    const int node = rn[tr];
+    if (node < 0) return;
+    const int u4 = (lane & 7) * 4;
+    const int unit0 = unit_tile * kUnit + u4;
+    const float *bias = a.bp + unit_tile * kGateTile + u4;
+    auto gate = [&](int g) __attribute__((always_inline)) {
+        const float4 q = *reinterpret_cast<const float4 *>(zt + g * (32 * kEpiStride) + tr * kEpiStride + u4);
+        const float4 bq = *reinterpret_cast<const float4 *>(bias + g * kUnit);
+        return make_float4(q.x + bq.x, q.y + bq.y, q.z + bq.z, q.w + bq.w);
+    };
+    const float4 zi = gate(0), zo = gate(1), zu = gate(2);
+    float4 cc = make_float4(sigmoid_t<T>(zi.x) * tanh_t<T>(zu.x), sigmoid_t<T>(zi.y) * tanh_t<T>(zu.y),
+                            sigmoid_t<T>(zi.z) * tanh_t<T>(zu.z), sigmoid_t<T>(zi.w) * tanh_t<T>(zu.w));
+    const float4 go = make_float4(sigmoid_t<T>(zo.x), sigmoid_t<T>(zo.y), sigmoid_t<T>(zo.z), sigmoid_t<T>(zo.w));
+    if constexpr (MODE == MODE_INTERNAL) {
+        const float4 fx = gate(3);
+        const int ar = rar[tr];
+        const int cb = rcb[tr];
+        const int4 k4 = rkid[tr];
+        const int first[4] = {k4.x, k4.y, k4.z, k4.w};
+        const int unit_ld = unit0 < a.Hq ? unit0 : 0;     // unit groups past the padded width read the first group (and store nothing)
+        for (int c0 = 0; c0 < ar; c0 += 4) {
+            bool has[4];
+            int64_t ofs[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int c = c0 + j;
+                has[j] = c < ar;
+                // a slot without a child re-reads the row's first child and is not added
+                const int kid = !has[j] ? k4.x : (c0 == 0 ? first[j] : a.child_idx[cb + c]);
+                ofs[j] = (int64_t)kid * a.Hq + unit_ld;
+            }
+            float4 pk[4], ck[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if constexpr (sizeof(T) == 4) {
+                    pk[j] = *reinterpret_cast<const float4 *>(static_cast<const float *>(a.P) + ofs[j]);
+                } else {
+                    const uint2 w = *reinterpret_cast<const uint2 *>(static_cast<const bf16_t *>(a.P) + ofs[j]);
+                    pk[j] = make_float4(__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xFFFF0000u),
+                                        __uint_as_float(w.y << 16), __uint_as_float(w.y & 0xFFFF0000u));
+                }
+                ck[j] = *reinterpret_cast<const float4 *>(a.cs + ofs[j]);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (has[j]) {
+                    cc.x += sigmoid_t<T>(fx.x + pk[j].x) * ck[j].x;
+                    cc.y += sigmoid_t<T>(fx.y + pk[j].y) * ck[j].y;
+                    cc.z += sigmoid_t<T>(fx.z + pk[j].z) * ck[j].z;
+                    cc.w += sigmoid_t<T>(fx.w + pk[j].w) * ck[j].w;
+                }
+            }
+        }
+    }
+    store_state<T>(a, node, unit0, cc, go);
+}
+
 // ---- the projection's store of one wave: 32 rows x 128 units ----------------------------
 // acc[g][v] holds P = U_f h for row (v/4)*8 + hf*4 + v%4 and unit unit_base + g*32 + l32.  The wave
 // turns the tile around in its private LDS region so that 16 lanes store one row's 128 units in
