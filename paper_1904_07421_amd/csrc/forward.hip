@@ -826,6 +826,10 @@ gemm_kb_kernel(LevelArgs a, const KbEpiArgs e) {
 // cell_pass.  One block barrier, none in the K loop.
 constexpr int kThinWaves = 4;
 constexpr int kThinMaxRows = 8192; // levels up to this many rows use the thin kernel
+// ... and larger ones too, up to this size, if their nodes average kThinLongLists children or more: the thin
+// kernel's cell update walks every row's own child list, the tiled kernel's makes 32 rows wait for the longest
+constexpr int kThinMaxRowsLongLists = 16384;
+constexpr int kThinLongLists = 5;
 constexpr int kThinAhead = 8;      // K groups in flight per wave
 
 template <typename T, int MODE, bool SAVE = false>
@@ -1539,7 +1543,10 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
             }
             stacked_ahead = false;
             // Levels too small to give every CU a 256 x 256 tile go to the thin kernel.
-            const bool thin = n_rows <= kThinMaxRows;
+            bool thin = n_rows <= kThinMaxRows;
+            if (!thin && !SAVE && !slots && l > 0 && s->host_level_kids && n_rows <= kThinMaxRowsLongLists &&
+                s->host_level_kids[l] >= (int64_t)kThinLongLists * n_rows)
+                thin = true;
             if (thin) {
                 a.n_col_tiles = n_unit_tiles;
                 a.n_tiles = (int)ceil_div(n_rows, 32) * a.n_col_tiles;
