@@ -221,13 +221,14 @@ def build(verbose: bool = False) -> str:
     _check_no_scratch(lines)
     # the kernels whose LDS reads (and, for the 256 x 256 tile kernel, weight loads) are inline asm
     # (names with their length prefix, as they are mangled: "level_kernel" alone would also match fused_level_kernel)
-    for stem, name in (("forward", "12level_kernel"), ("forward", "14gemm_kb_kernel"), ("level256", "14tile256_kernel")):
+    for stem, name in (("forward", "12level_kernel"), ("forward", "14gemm_kb_kernel"), ("forward", "17nary_level_kernel"),
+                       ("level256", "14tile256_kernel")):
         if asm_texts.get(stem) is None:
             raise RuntimeError(f"the device assembly of {stem}.hip was not produced; cannot check it")
         if check_lds_read_waits(asm_texts[stem], name) == 0:
             raise RuntimeError(f"no LDS reads found in the assembly of {name}: the check is not looking at it")
     # the K loops whose waits for direct-to-LDS stage loads are hand-counted
-    for name in ("12level_kernel", "14gemm_kb_kernel"):
+    for name in ("12level_kernel", "14gemm_kb_kernel", "17nary_level_kernel"):
         if check_stage_loads(asm_texts["forward"], name) == 0:
             raise RuntimeError(f"no K loop with stage loads found in the assembly of {name}: the check is not looking at it")
     if verbose and out.strip():

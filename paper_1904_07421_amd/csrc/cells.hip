@@ -12,42 +12,57 @@
 // followed by an elementwise cell update.  Per slot:
 //
 //   nary_stack_kernel   the slot's dense input rows [x_j | h of child 1 | ... | h of child N], K-blocked
-//                       (the "stack" of section 4.3; children by ascending id = position 1, 2, ...)
-//   launch_kb_gemm      Z on the tiled MFMA core shared with the backward pass (fp32 out)
-//   nary_cell_kernel    i, o, u, f_l, c = i u + sum_l f_l c_{k_l}, h = o tanh(c); rows written by node id
+//                       (the "stack" of section 4.3; children by ascending id = position 1, 2, ...);
+//                       a slot of leaves stacks x alone
+//   launch_kb_gemm      for N > 1, internal nodes: the forget gates of positions 2 .. N as a plain GEMM
+//                       (exactly (N - 1) H columns), pre-activations kept in fp32
+//   nary_level_kernel   (forward.hip) the gates i, o, u, f_1 on the tiled MFMA core with the cell update as
+//                       its epilogue: c = i u + sum_l f_l c_{k_l}, h = o tanh(c), rows written by node id
 //                       (the "slice")
-//
-// This first version keeps the pre-activations in memory between the last two steps (the child-sum
-// path fuses them); it is the slot's operator type that is new here, not its speed.
 #include "level_common.h"
 
 namespace jitdb {
 namespace {
 
 // ---- weights ---------------------------------------------------------------------------
-// Bn: (3 + N) H rows (row = gate block * H + unit, padded to a multiple of 256), K = Dp + N Hp,
-// K-blocked like every operand of the tiled GEMM: [ W row (D, zero padded to Dp) | U columns of
-// position 1 (H, padded to Hp) | ... | position N ].
+// Two packed matrices, both K-blocked like every operand of the tiled GEMM, K = Dp + N Hp:
+// [ W row (D, zero padded to Dp) | U columns of position 1 (H, padded to Hp) | ... | position N ].
+//   main   row = unit tile * 128 + slot * 32 + u, slots i, o, u, f_1: the waves of one block hold all four
+//          gates of a hidden unit (a slot of leaves multiplies the first slabs, the x part, of the same rows)
+//   extra  the rows of f_2 .. f_N, gate-major ((N - 1) H rows): a plain GEMM of their own
+__host__ __device__ inline int nary_rows_main(int H) { return ((((H + kUnit - 1) / kUnit) * 128 + 255) / 256) * 256; }
+__host__ __device__ inline int nary_rows_extra(int H, int N) { return (((N - 1) * H + 255) / 256) * 256; }
+
 template <typename T>
 __global__ void __launch_bounds__(kThreads)
 nary_pack_kernel(const T *__restrict__ W, const T *__restrict__ U, int D, int H, int Dp, int Hp, int N,
-                 int rows_alloc, T *__restrict__ Bn, int *__restrict__ err_to_clear) {
+                 T *__restrict__ Bm, T *__restrict__ Bx, int *__restrict__ err_to_clear) {
     if (blockIdx.x == 0 && threadIdx.x == 0 && err_to_clear) *err_to_clear = 0;
     const int Kn = Dp + N * Hp;
-    const int G = 3 + N;
-    const int64_t total = (int64_t)rows_alloc * Kn;
+    const int rows_m = nary_rows_main(H), rows_x = nary_rows_extra(H, N);
+    const int64_t total_m = (int64_t)rows_m * Kn, total = total_m + (int64_t)rows_x * Kn;
     for (int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * kThreads) {
-        const int r = (int)(idx / Kn), k = (int)(idx % Kn);
+        const bool extra = idx >= total_m;
+        const int64_t id = extra ? idx - total_m : idx;
+        const int r = (int)(id / Kn), k = (int)(id % Kn);
+        int64_t g = -1;                                          // row of W / U (gate-major), or none
+        if (extra) {
+            if (r < (N - 1) * H) g = (int64_t)4 * H + r;         // f_2 starts at gate row 4 H
+        } else {
+            const int slot = (r % 128) / kUnit, unit = (r / 128) * kUnit + r % kUnit;
+            if (unit < H) g = (int64_t)slot * H + unit;
+        }
         T v = T(0);
-        if (r < G * H) {
+        if (g >= 0) {
             if (k < D) {
-                v = W[(int64_t)r * D + k];
+                v = W[g * D + k];
             } else if (k >= Dp) {
                 const int l = (k - Dp) / Hp, j = (k - Dp) % Hp;
-                if (j < H) v = U[(int64_t)r * N * H + l * H + j];
+                if (j < H) v = U[g * N * H + l * H + j];
             }
         }
-        *reinterpret_cast<T *>(reinterpret_cast<char *>(Bn) + operand_offset(r, (int64_t)k * sizeof(T), rows_alloc)) = v;
+        T *dst = extra ? Bx : Bm;
+        *reinterpret_cast<T *>(reinterpret_cast<char *>(dst) + operand_offset(r, (int64_t)k * sizeof(T), extra ? rows_x : rows_m)) = v;
     }
 }
 
@@ -94,76 +109,37 @@ nary_stack_kernel(const T *__restrict__ x, int D, int Dp, const T *__restrict__ 
     *reinterpret_cast<uint4 *>(reinterpret_cast<char *>(A) + operand_offset(row, (int64_t)k0 * sizeof(T), n_rows_alloc)) = o;
 }
 
-// ---- cell update -----------------------------------------------------------------------
-// One thread per (row, unit) over the padded width Hp: units below H are computed, the pad
-// columns of the padded h copy are zeroed.  Z [n_rows, (3 + N) H] fp32 without bias.
-struct NaryCellArgs {
-    const float *Z; const float *b; const int4 *row_rec; const float *cs;
-    void *h_out; void *hs_out; float *c_out; float *cs_out;
-    int n_rows, H, Hp, Hq, N;
-};
-template <typename T>
-__global__ void __launch_bounds__(kThreads)
-nary_cell_kernel(const NaryCellArgs a) {
-    const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    const int64_t row = gid / a.Hp;
-    const int unit = (int)(gid % a.Hp);
-    if (row >= a.n_rows) return;
-    const int4 r0 = a.row_rec[2 * row];
-    const int64_t nd = r0.x;
-    T *h_out = static_cast<T *>(a.h_out), *hs_out = static_cast<T *>(a.hs_out);
-    const bool separate_hs = hs_out != h_out;
-    if (unit >= a.H) {
-        if (separate_hs) hs_out[nd * a.Hp + unit] = T(0);
-        return;
-    }
-    const int H = a.H, ldz = (3 + a.N) * H;
-    const float *z = a.Z + row * ldz;
-    const float gi = sigmoid_t<T>(z[unit] + a.b[unit]);
-    const float go = sigmoid_t<T>(z[H + unit] + a.b[H + unit]);
-    const float gu = tanh_t<T>(z[2 * H + unit] + a.b[2 * H + unit]);
-    float c = gi * gu;
-    const int m = r0.y < a.N ? r0.y : a.N;
-    if (m > 0) {
-        const int4 kids = a.row_rec[2 * row + 1];
-        const int kid[4] = {kids.x, kids.y, kids.z, kids.w};
-#pragma unroll
-        for (int l = 0; l < 4; ++l)
-            if (l < m) {
-                const float f = sigmoid_t<T>(z[(3 + l) * H + unit] + a.b[(3 + l) * H + unit]);
-                c += f * a.cs[(int64_t)kid[l] * a.Hq + unit];
-            }
-    }
-    const T hv = from_f32<T>(go * tanh_t<T>(c));
-    a.c_out[nd * H + unit] = c;
-    if (a.cs_out != a.c_out) a.cs_out[nd * a.Hq + unit] = c;
-    h_out[nd * H + unit] = hv;
-    if (separate_hs) hs_out[nd * a.Hp + unit] = hv;
-}
-
 }  // namespace
 
+static size_t nary_main_bytes(int H, int Dp, int Hp, int N, size_t esz) {
+    return round_up((int64_t)nary_rows_main(H) * (size_t)(Dp + N * Hp) * esz, 256);
+}
 size_t nary_packed_bytes(int D, int H, int Dp, int Hp, int N, size_t esz) {
-    return (size_t)round_up((int64_t)(3 + N) * H, 256) * (size_t)(Dp + N * Hp) * esz;
+    (void)D;
+    return nary_main_bytes(H, Dp, Hp, N, esz) + (size_t)nary_rows_extra(H, N) * (size_t)(Dp + N * Hp) * esz;
 }
 
 int nary_pack(jitdb_dtype dtype, const void *W, const void *U, int D, int H, int Dp, int Hp, int N, void *Bn,
               int *err_to_clear, hipStream_t st) {
-    const int rows_alloc = (int)round_up((int64_t)(3 + N) * H, 256);
-    const int64_t total = (int64_t)rows_alloc * (Dp + N * Hp);
+    const size_t esz = dtype == JITDB_F32 ? 4 : 2;
+    void *Bx = static_cast<char *>(Bn) + nary_main_bytes(H, Dp, Hp, N, esz);
+    const int64_t total = (int64_t)(nary_rows_main(H) + nary_rows_extra(H, N)) * (Dp + N * Hp);
     const unsigned grid = (unsigned)(ceil_div(total, kThreads) < 4096 ? ceil_div(total, kThreads) : 4096);
     if (dtype == JITDB_F32)
         nary_pack_kernel<float><<<grid, kThreads, 0, st>>>(static_cast<const float *>(W), static_cast<const float *>(U),
-                                                          D, H, Dp, Hp, N, rows_alloc, static_cast<float *>(Bn), err_to_clear);
+                                                          D, H, Dp, Hp, N, static_cast<float *>(Bn),
+                                                          static_cast<float *>(Bx), err_to_clear);
     else
         nary_pack_kernel<bf16_t><<<grid, kThreads, 0, st>>>(static_cast<const bf16_t *>(W), static_cast<const bf16_t *>(U),
-                                                           D, H, Dp, Hp, N, rows_alloc, static_cast<bf16_t *>(Bn), err_to_clear);
+                                                           D, H, Dp, Hp, N, static_cast<bf16_t *>(Bn),
+                                                           static_cast<bf16_t *>(Bx), err_to_clear);
     JITDB_LAUNCH_CHECK();
     return JITDB_OK;
 }
 
-// One slot of N-ary nodes: the three steps above.  a: the level arguments of the forward (x rows come
-// through NarySlot, h and c of the children through a.hs / a.cs); rec: the slot's row records.
+// One slot of N-ary nodes: stack, (for N > 1 and internal nodes) the GEMM of the further forget gates,
+// the level kernel.  a: the level arguments of the forward (x rows come through NarySlot, h and c of the
+// children through a.hs / a.cs).
 int run_nary_slot(jitdb_dtype dtype, const LevelArgs &a, const NarySlot &s, hipStream_t st) {
     if (s.n_rows <= 0) return JITDB_OK;
     const size_t esz = dtype == JITDB_F32 ? 4 : 2;
@@ -181,23 +157,25 @@ int run_nary_slot(jitdb_dtype dtype, const LevelArgs &a, const NarySlot &s, hipS
                                                                static_cast<const bf16_t *>(a.hs), a.Hp, s.N, Nk, s.row_rec,
                                                                static_cast<bf16_t *>(s.A), s.n_rows, rows_alloc, s.err);
     JITDB_LAUNCH_CHECK();
-    KbGemm g = {};
+    if (!s.leaves && s.N > 1) {       // f_2 .. f_N of every row, before the kernel that uses them
+        KbGemm x = {};
+        x.A = s.A; x.a_rows_alloc = rows_alloc; x.M = s.n_rows;
+        x.B = static_cast<const char *>(s.Bn) + nary_main_bytes(a.H, a.Dp, a.Hp, s.N, esz);
+        x.b_rows_alloc = nary_rows_extra(a.H, s.N); x.N = (s.N - 1) * a.H;
+        x.k_bytes = (int64_t)Kn * (int64_t)esz; x.k_splits = 1;
+        x.epilogue = KB_EPI_STORE_F32; x.out0 = s.F; x.ldc = x.N;
+        const int rc = launch_kb_gemm(dtype, x, st);
+        if (rc != JITDB_OK) return rc;
+    }
+    NaryLevel g = {};
     g.A = s.A; g.a_rows_alloc = rows_alloc; g.M = s.n_rows;
-    // leaves: the gates i, o, u only (the first 3 H packed rows), over the x part of K (the first slabs)
-    g.B = s.Bn; g.b_rows_alloc = round_up((int64_t)(3 + s.N) * a.H, 256); g.N = (3 + Nk) * a.H;
-    g.k_bytes = (int64_t)Kn * (int64_t)esz; g.k_splits = 1;
-    g.epilogue = KB_EPI_STORE_F32; g.out0 = s.Z; g.ldc = (3 + s.N) * a.H;
-    const int rc = launch_kb_gemm(dtype, g, st);
-    if (rc != JITDB_OK) return rc;
-    NaryCellArgs c;
-    c.Z = s.Z; c.b = s.b; c.row_rec = s.row_rec; c.cs = a.cs;
-    c.h_out = a.h_out; c.hs_out = a.hs_out; c.c_out = a.c_out; c.cs_out = a.cs;
-    c.n_rows = s.n_rows; c.H = a.H; c.Hp = a.Hp; c.Hq = a.Hq; c.N = s.N;
-    const unsigned cblocks = (unsigned)ceil_div((int64_t)s.n_rows * a.Hp, kThreads);
-    if (dtype == JITDB_F32) nary_cell_kernel<float><<<cblocks, kThreads, 0, st>>>(c);
-    else nary_cell_kernel<bf16_t><<<cblocks, kThreads, 0, st>>>(c);
-    JITDB_LAUNCH_CHECK();
-    return JITDB_OK;
+    g.B = s.Bn; g.b_rows_alloc = nary_rows_main(a.H);
+    g.n_col_tiles = (int)ceil_div(ceil_div(a.H, kUnit), 2);
+    g.k_bytes = (int64_t)Kn * (int64_t)esz;
+    g.row_rec = s.row_rec; g.bias = s.b; g.cs = a.cs; g.F = s.F;
+    g.c_out = a.c_out; g.h_out = a.h_out; g.hs_out = a.hs_out; g.cs_out = a.cs;
+    g.H = a.H; g.Hp = a.Hp; g.Hq = a.Hq; g.N = s.N; g.leaves = s.leaves;
+    return launch_nary_level(dtype, g, st);
 }
 
 }  // namespace jitdb

@@ -814,6 +814,132 @@ gemm_kb_kernel(LevelArgs a, const KbEpiArgs e) {
     }
 }
 
+// ---- a slot of N-ary Tree-LSTM nodes: contraction and cell update in one kernel -----------
+// The same GEMM core on the slot's stacked rows [x | h_1 | ... | h_N] and the cell's weights packed like
+// the child-sum cell's (nary_pack in cells.hip): row = unit tile * 128 + slot * 32 + u with the slots
+// i, o, u, f_1, so a block's 256 columns are two unit tiles and every wave holds the four gates of its
+// 64 rows x 32 units in its own accumulators.  The forget gates of the further child positions,
+// f_2 .. f_N, are a plain GEMM of their own that runs before this kernel (no padding to whole slots that
+// way) and leaves its pre-activations in F; the cell update reads them from there.  A slot of leaves
+// runs the same kernel over the x part of K (the first slabs of the same packed weights) and uses i, o, u.
+// Rows, child ids and arities come with the row records; outputs go out by node id, 32 lanes on 32
+// consecutive units of a row, the c values of eight rows' children requested together.
+struct NaryEpi {
+    const int4 *row_rec; const float *bias; const float *cs; const float *F;
+    float *c_out; void *h_out; void *hs_out; float *cs_out;
+    int M, H, Hp, Hq, N;
+};
+
+template <typename T, bool LEAF>
+__global__ void __launch_bounds__(kDmaThreads, 2)
+nary_level_kernel(LevelArgs a, const NaryEpi e) {
+    __shared__ __attribute__((aligned(1024))) char lds[kDmaBufs * kDmaBuf];
+    __shared__ __attribute__((aligned(256))) char sink[4 * 256];
+    __shared__ int s_node[kDmaBM];
+    __shared__ int s_ar[kDmaBM];
+    __shared__ int4 s_kid[kDmaBM];
+    const int t = threadIdx.x;
+    const int lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int hf = lane >> 5, l32 = lane & 31;
+    int row_tile, col_tile;
+    if (!block_to_tile(blockIdx.x, a.n_row_tiles, a.n_col_tiles, row_tile, col_tile)) return;
+    const int tile_row0 = row_tile * kDmaBM;
+
+    floatx16 acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][g][v] = 0.0f;
+    if (t < kDmaBM) {       // the tile's rows, fetched while the GEMM runs
+        const int row = tile_row0 + t;
+        const bool ok = row < e.M;
+        const int4 r0 = e.row_rec[2 * (int64_t)(ok ? row : e.M - 1)];
+        s_node[t] = ok ? r0.x : -1;
+        if constexpr (!LEAF) {
+            s_ar[t] = r0.y < e.N ? r0.y : e.N;
+            s_kid[t] = e.row_rec[2 * (int64_t)(ok ? row : e.M - 1) + 1];
+        }
+    }
+    dma_gemm<T, MODE_GENERIC>(a, lds, nullptr, tile_row0, col_tile, acc, sink, []() {});
+    __syncthreads();
+
+    const int unit = (col_tile * 2 + wn) * kUnit + l32;
+    T *h_out = static_cast<T *>(e.h_out);
+    T *hs_out = static_cast<T *>(e.hs_out);
+    const bool separate_hs = hs_out != h_out;
+    const bool separate_cs = e.cs_out != e.c_out;
+    const int H = e.H;
+    const bool live = unit < H;
+    const int unit_ld = live ? unit : 0;
+    const float bi = e.bias[unit_ld], bo = e.bias[H + unit_ld], bu = e.bias[2 * H + unit_ld];
+    float bf[4] = {0.f, 0.f, 0.f, 0.f};
+    if constexpr (!LEAF) {
+#pragma unroll
+        for (int l = 0; l < 4; ++l)
+            if (l < e.N) bf[l] = e.bias[(3 + l) * H + unit_ld];
+    }
+    const int ldf = (e.N - 1) * H;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+        for (int vh = 0; vh < 2; ++vh) {
+            int64_t node[8];
+            float ck[8][4], fx[8][3];
+            int m[8];
+#pragma unroll
+            for (int vv = 0; vv < 8; ++vv) {       // what eight rows need from memory first: loads in flight together
+                const int v = vh * 8 + vv;
+                const int lr = wm * 64 + i * 32 + (v >> 2) * 8 + hf * 4 + (v & 3);
+                node[vv] = s_node[lr];
+                m[vv] = 0;
+#pragma unroll
+                for (int l = 0; l < 4; ++l) ck[vv][l] = 0.0f;
+#pragma unroll
+                for (int l = 0; l < 3; ++l) fx[vv][l] = 0.0f;
+                if constexpr (!LEAF) {
+                    if (node[vv] >= 0) m[vv] = s_ar[lr];
+                    const int4 k4 = s_kid[lr];
+                    const int kid[4] = {k4.x, k4.y, k4.z, k4.w};
+#pragma unroll
+                    for (int l = 0; l < 4; ++l)
+                        if (l < m[vv]) {
+                            ck[vv][l] = e.cs[(int64_t)kid[l] * e.Hq + unit_ld];
+                            if (l > 0) fx[vv][l - 1] = e.F[(int64_t)(tile_row0 + lr) * ldf + (l - 1) * H + unit_ld];
+                        }
+                }
+            }
+#pragma unroll
+            for (int vv = 0; vv < 8; ++vv) {
+                const int v = vh * 8 + vv;
+                if (node[vv] < 0) continue;
+                const int64_t nd = node[vv];
+                if (!live) {                        // pad columns of the padded h copy
+                    if (separate_hs && unit < e.Hp) hs_out[nd * e.Hp + unit] = T(0);
+                    continue;
+                }
+                const float gi = sigmoid_t<T>(acc[i][0][v] + bi);
+                const float go = sigmoid_t<T>(acc[i][1][v] + bo);
+                const float gu = tanh_t<T>(acc[i][2][v] + bu);
+                float c = gi * gu;
+                if constexpr (!LEAF) {
+#pragma unroll
+                    for (int l = 0; l < 4; ++l)
+                        if (l < m[vv]) c += sigmoid_t<T>((l == 0 ? acc[i][3][v] : fx[vv][l > 0 ? l - 1 : 0]) + bf[l]) * ck[vv][l];
+                }
+                const T hv = from_f32<T>(go * tanh_t<T>(c));
+                e.c_out[nd * H + unit] = c;
+                if (separate_cs) e.cs_out[nd * e.Hq + unit] = c;
+                h_out[nd * H + unit] = hv;
+                if (separate_hs) hs_out[nd * e.Hp + unit] = hv;
+            }
+        }
+    }
+}
+
 // ---- thin levels ---------------------------------------------------------------------
 // A level with a few thousand rows gives the 128 x 256 tiles too few blocks to fill 256
 // CUs, and each block then runs a whole K loop back to back: the level costs that
@@ -822,8 +948,9 @@ gemm_kb_kernel(LevelArgs a, const KbEpiArgs e) {
 // projection: wave g one of four unit tiles of forget rows), taking its MFMA operands
 // straight from global memory / L2 in fragment layout (16 bytes per lane, no LDS staging,
 // kThinAhead K groups requested ahead), so the K loop of a tile is a quarter as long as
-// with one wave per tile.  The gates meet in LDS and wave 0 finishes with the same
-// cell_pass.  One block barrier, none in the K loop.
+// with one wave per tile.  The gates meet in LDS and every wave finishes eight of the tile's
+// rows (cell_rows; the training variant: wave 0 runs cell_pass).  One block barrier, none in
+// the K loop.
 constexpr int kThinWaves = 4;
 constexpr int kThinMaxRows = 8192; // levels up to this many rows use the thin kernel
 // ... and larger ones too, up to this size, if their nodes average kThinLongLists children or more: the thin
@@ -1265,7 +1392,7 @@ struct ForwardWs {
     // tables that hold N-ary cells (jitdb_treelstm_forward_cells): one slot's stacked input and
     // pre-activations, each such cell's packed weights, the flag for nodes with too many children
     void *nary_A;
-    float *nary_Z;
+    float *nary_F;   // pre-activations of the forget gates of child positions 2 .. N of one slot
     void *nary_B[JITDB_MAX_SIGNATURES];
     int *nary_err;
     size_t bytes;
@@ -1322,7 +1449,7 @@ ForwardWs carve_forward_ws(int64_t n, int64_t e, const Dims &d, void *base, int 
         }
     if (n_max > 0) {
         w.nary_A = c.take<char>((size_t)(n + kRowPad) * (d.Dp + (size_t)n_max * d.Hp) * d.esz);
-        w.nary_Z = c.take<float>((size_t)n * (3 + n_max) * d.H);
+        w.nary_F = n_max > 1 ? c.take<float>((size_t)n * (n_max - 1) * d.H) : nullptr;
         w.nary_err = c.take<int>(1);
     }
     w.bytes = c.off;
@@ -1523,7 +1650,7 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
             // a slot of N-ary nodes: stack, one contraction for all 3 + N gates, cell update (cells.hip)
             NarySlot ns;
             ns.x = x; ns.row_rec = a.row_rec; ns.A = w.nary_A; ns.Bn = w.nary_B[sig]; ns.b = cells[sig].b;
-            ns.Z = w.nary_Z; ns.err = w.nary_err; ns.n_rows = n_rows; ns.N = cells[sig].arity; ns.leaves = l == 0;
+            ns.F = w.nary_F; ns.err = w.nary_err; ns.n_rows = n_rows; ns.N = cells[sig].arity; ns.leaves = l == 0;
             ScopedLaunchTimer tm(l == 0 ? JITDB_K_THIN_LEAF : JITDB_K_THIN_INTERNAL, n_rows, st);
             const int rc = run_nary_slot(dtype, a, ns, st);
             if (rc != JITDB_OK) return rc;
@@ -1644,6 +1771,35 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
 }
 
 }  // namespace
+
+int launch_nary_level(jitdb_dtype dtype, const NaryLevel &g, hipStream_t st) {
+    if (g.M <= 0) return JITDB_OK;
+    if (g.k_bytes <= 0 || g.k_bytes % 128 != 0) return JITDB_E_BADARG;
+    LevelArgs a = {};
+    a.stack = g.A;
+    a.n_rows_alloc = (int)g.a_rows_alloc;
+    a.Bp = g.B;
+    a.NPU = (int)g.b_rows_alloc;
+    a.n_rows = g.M;
+    a.Dp = (int)(g.k_bytes / (dtype == JITDB_F32 ? 4 : 2));
+    a.Hp = 0;
+    a.n_row_tiles = (int)ceil_div(g.M, kDmaBM);
+    a.n_col_tiles = g.n_col_tiles;
+    a.n_blocks = 8 * (int)ceil_div(a.n_row_tiles, 8) * a.n_col_tiles;
+    NaryEpi e;
+    e.row_rec = g.row_rec; e.bias = g.bias; e.cs = g.cs; e.F = g.F; e.c_out = g.c_out; e.h_out = g.h_out; e.hs_out = g.hs_out;
+    e.cs_out = g.cs_out; e.M = g.M; e.H = g.H; e.Hp = g.Hp; e.Hq = g.Hq; e.N = g.N;
+    dim3 grid((unsigned)a.n_blocks);
+    if (dtype == JITDB_F32) {
+        if (g.leaves) nary_level_kernel<float, true><<<grid, kDmaThreads, 0, st>>>(a, e);
+        else nary_level_kernel<float, false><<<grid, kDmaThreads, 0, st>>>(a, e);
+    } else {
+        if (g.leaves) nary_level_kernel<bf16_t, true><<<grid, kDmaThreads, 0, st>>>(a, e);
+        else nary_level_kernel<bf16_t, false><<<grid, kDmaThreads, 0, st>>>(a, e);
+    }
+    JITDB_LAUNCH_CHECK();
+    return JITDB_OK;
+}
 
 int launch_kb_gemm(jitdb_dtype dtype, const KbGemm &g, hipStream_t st) {
     if (g.M <= 0 || g.N <= 0 || g.k_bytes <= 0) return JITDB_OK;

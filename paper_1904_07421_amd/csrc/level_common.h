@@ -459,13 +459,25 @@ struct NarySlot {
     const void *x;          // [N, D] all nodes' inputs, rows by node id
     const int4 *row_rec;    // the slot's row records (two int4 per row)
     void *A;                // workspace: the slot's stacked input, K-blocked
-    const void *Bn;         // the cell's packed weights (nary_pack)
+    const void *Bn;         // the cell's packed weights (nary_pack): slots i, o, u, f_1 by unit tile, then the rows of f_2 .. f_N
+    float *F;               // workspace: pre-activations of f_2 .. f_N, [n_rows, (N - 1) H]
     const float *b;         // the cell's bias [(3 + N) H]
-    float *Z;               // workspace: pre-activations [n_rows, (3 + N) H]
     int *err;               // device flag: set when a node has more children than the cell has positions
     int n_rows, N;
     bool leaves;            // a slot of level 0: no children, so K is the x part alone and the forget gates are not needed
 };
+// The tiled GEMM with the N-ary cell update behind it (forward.hip): A [M rows] K-blocked, B packed by gate
+// slot, outputs by node id.
+struct NaryLevel {
+    const void *A; int64_t a_rows_alloc; int M;
+    const void *B; int64_t b_rows_alloc; int n_col_tiles;
+    int64_t k_bytes;
+    const int4 *row_rec; const float *bias; const float *cs; const float *F;
+    float *c_out; void *h_out; void *hs_out; float *cs_out;
+    int H, Hp, Hq, N;
+    bool leaves;
+};
+int launch_nary_level(jitdb_dtype dtype, const NaryLevel &g, hipStream_t st);
 size_t nary_packed_bytes(int D, int H, int Dp, int Hp, int N, size_t esz);
 int nary_pack(jitdb_dtype dtype, const void *W, const void *U, int D, int H, int Dp, int Hp, int N, void *Bn,
               int *err_to_clear, hipStream_t st);
