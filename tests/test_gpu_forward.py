@@ -561,3 +561,28 @@ def test_chain_levels_too_wide_for_lds_take_the_general_launches(c_oracle):
     ho, co = _oracle(c_oracle, parent, seen)
     eh, ec = _report("wide chain/f32", h, c, ho, co)
     assert eh <= 1e-4 and ec <= 1e-4 * _c_scale("f32", co)
+
+
+def test_children_per_level_are_optional_in_the_c_struct(c_oracle):
+    """A caller of the C ABI that leaves host_level_kids NULL gets the same schedule and a forward over the
+    general launches; one that sets it gets the counts filled in by jitdb_schedule."""
+    import torch
+    import paper_1904_07421_amd as J
+    from gpu_util import dev_parent
+    parent = _trees_and_sequences(40, 120, 30, 9)
+    x, W, U, b = make_values(2, parent.shape[0], "random", D=32, H=32)
+    dp = dev_parent(parent)
+    with_counts = J.jitdb_schedule(dp)
+    without = J.Schedule(parent.shape[0], dp.device)
+    without.struct.host_level_kids = None                    # NULL in the C struct
+    J.jitdb_schedule(dp, out=without)
+    a, bb = with_counts.to_numpy(), without.to_numpy()
+    for k in ("height", "level_ptr", "perm", "inv_perm", "child_ptr", "child_idx"):
+        assert np.array_equal(a[k], bb[k]), k
+    assert (without.host_level_kids == -1).all() and (with_counts.host_level_kids[:with_counts.n_levels] >= 0).all()
+    dev = lambda v: torch.from_numpy(np.ascontiguousarray(v, np.float32)).cuda()
+    (res, launches) = _profile_classes(lambda: J.jitdb_treelstm_forward(dev(x), dev(W), dev(U), dev(b), without))
+    assert launches["chain"] == 0
+    h, c = res[0].cpu().numpy(), res[1].cpu().numpy()
+    ho, co = _oracle(c_oracle, parent, (x, W, U, b))
+    assert np.abs(h - ho).max() <= 1e-4 and np.abs(c - co).max() <= 1e-4
