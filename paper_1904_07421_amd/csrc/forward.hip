@@ -18,7 +18,13 @@
 //                      128 x 256 tiles: one 32 x 32-unit tile per wave, operands straight
 //                      from L2; a thin level's projection and the next level's stack
 //                      step share one launch (thin_proj_stack_kernel)
+//   chain_kernel       a thin level whose nodes all have exactly one child (sequences, the long
+//                      tail of a deep forest) as ONE launch: x and the child's h read in place,
+//                      all four gates over the full K, no stack step and no projection
+//   tile256_kernel     (level256.hip) the level kernel on 256 x 256 tiles, bf16; switched off
 //
+// With cells of different type in the table (jitdb_treelstm_forward_cells) a slot of N-ary cells
+// runs nary_level_kernel below: the same GEMM core with the N-ary cell update as its epilogue.
 // With a typed table (jitdb_treelstm_forward_typed) a slot is (level, signature): each
 // signature has its own packed weights, the projection of a sub-slot uses the parent
 // cell's, and the slots of a large level run in one grouped launch through a tile table.
