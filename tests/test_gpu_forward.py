@@ -586,3 +586,30 @@ def test_children_per_level_are_optional_in_the_c_struct(c_oracle):
     h, c = res[0].cpu().numpy(), res[1].cpu().numpy()
     ho, co = _oracle(c_oracle, parent, (x, W, U, b))
     assert np.abs(h - ho).max() <= 1e-4 and np.abs(c - co).max() <= 1e-4
+
+
+@pytest.mark.parametrize("seed", list(range(8)))
+def test_chain_levels_random_shapes(c_oracle, seed):
+    """Random widths (H from 1 up, D any multiple of 4), tree / sequence mixes and row counts around the
+    tile edges, both types: the single-launch levels against the oracle."""
+    rng = np.random.default_rng(100 + seed)
+    D = int(rng.choice([4, 8, 12, 36, 100, 132, 300]))
+    H = int(rng.integers(1, 200))
+    dtype = "bf16" if seed % 2 else "f32"
+    n_seqs = int(rng.choice([1, 31, 32, 33, 97, 260]))
+    parent = _trees_and_sequences(int(rng.integers(0, 20)), n_seqs, int(rng.integers(3, 40)), 200 + seed)
+    x, W, U, b = make_values(2, parent.shape[0], "random", D=D, H=H)
+    (res, launches) = _profile_classes(lambda: run_gpu_forward(parent, x, W, U, b, dtype))
+    sched, h, c, seen = res
+    L = sched.n_levels
+    rows, kids = np.diff(sched.host_level_ptr[:L + 1]), sched.host_level_kids[:L]
+    expect = 0
+    for l in range(L - 1, 0, -1):
+        if kids[l] != rows[l]:
+            break
+        expect += 1
+    print(f"chain random seed={seed} D={D} H={H} {dtype} N={parent.shape[0]} L={L} chain levels={expect}", flush=True)
+    assert launches["chain"] == expect
+    ho, co = _oracle(c_oracle, parent, seen)
+    eh, ec = _report(f"chain-random/{seed}", h, c, ho, co)
+    assert eh <= TOL[dtype] and ec <= TOL[dtype] * _c_scale(dtype, co)
