@@ -161,3 +161,19 @@ def test_argument_checks_and_empty_forest():
     sched = J.jitdb_schedule_typed(dev_parent(p), dev_parent(np.zeros_like(p)), 2)
     with pytest.raises(ValueError):
         J.jitdb_treelstm_forward_cells(torch.zeros((3, 8), device="cuda"), cells, sched)
+
+
+@pytest.mark.parametrize("seed", list(range(8)))
+def test_random_cells_and_widths(seed):
+    """Random N, widths (any D, H from 1 up) and mixes of cell types, both dtypes, against the cells oracle."""
+    rng = np.random.default_rng(300 + seed)
+    N = int(rng.integers(1, 5))
+    D = int(rng.choice([1, 5, 16, 33, 64, 100]))
+    H = int(rng.integers(1, 150))
+    dtype = "bf16" if seed % 2 else "f32"
+    positions = [N] if seed % 3 == 0 else ([0, N] if seed % 3 == 1 else [N, max(1, N - 1), 0])
+    p = bounded_arity_forest(int(rng.integers(1, 400)), 1, int(rng.integers(1, 40)), min(n for n in positions if n > 0) if 0 not in positions else 6,
+                             310 + seed)
+    sig = arity_signatures(p, positions, 320 + seed)
+    print(f"cells random seed={seed} N={N} cells={positions} D={D} H={H} {dtype} nodes={p.shape[0]}", flush=True)
+    _check(p, sig, positions, D, H, dtype, 330 + seed)
