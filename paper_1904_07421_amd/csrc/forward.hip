@@ -955,8 +955,7 @@ nary_level_kernel(LevelArgs a, const NaryEpi e) {
 // straight from global memory / L2 in fragment layout (16 bytes per lane, no LDS staging,
 // kThinAhead K groups requested ahead), so the K loop of a tile is a quarter as long as
 // with one wave per tile.  The gates meet in LDS and every wave finishes eight of the tile's
-// rows (cell_rows; the training variant: wave 0 runs cell_pass).  One block barrier, none in
-// the K loop.
+// rows (cell_rows).  One block barrier, none in the K loop.
 constexpr int kThinWaves = 4;
 constexpr int kThinMaxRows = 8192; // levels up to this many rows use the thin kernel
 // ... and larger ones too, up to this size, if their nodes average kThinLongLists children or more: the thin
@@ -968,27 +967,18 @@ constexpr int kThinAhead = 8;      // K groups in flight per wave
 template <typename T, int MODE, bool SAVE = false>
 __device__ __forceinline__ void thin_body(const LevelArgs &a, int tile) {
     constexpr int ESZ = (int)sizeof(T);
-    // one block of LDS, used as region + exchange (training: wave 0 runs cell_pass) or as the four
-    // gates' pre-activations (cell_rows)
-    constexpr int kRegionFloats = 3 * 32 * kEpiStride;
-    constexpr int kExchangeFloats = 3 * 16 * 64;
-    static_assert(kRegionFloats + kExchangeFloats >= 4 * 32 * kEpiStride, "the gates of a tile must fit");
-    __shared__ __attribute__((aligned(16))) float smem[kRegionFloats + kExchangeFloats];
-    float *region = smem;
-    float (*exchange)[16][64] = reinterpret_cast<float (*)[16][64]>(smem + kRegionFloats);   // accumulators of waves 1-3
+    __shared__ __attribute__((aligned(16))) float smem[4 * 32 * kEpiStride];    // the four gates' pre-activations
     __shared__ int s_node[32];
     __shared__ int s_ar[32];
     __shared__ int s_cb[32];
     __shared__ int4 s_kid[32];
-    constexpr bool ROWS = (MODE != MODE_PROJ) && !SAVE;      // the cell update is shared out over the four waves
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int hf = lane >> 5, l32 = lane & 31;
     const int row0 = (tile / a.n_col_tiles) * 32;
     const int col = tile % a.n_col_tiles;     // unit tile (gates) or group of four unit tiles (projection)
-    // leaves have no forget gate: its wave multiplies nothing (and, where wave 0 does the whole cell update, leaves)
-    if (MODE == MODE_LEAF && wave == 3 && !ROWS) return;
+    // (leaves have no forget gate: its wave multiplies nothing, but takes its share of the cell update)
     if (MODE == MODE_PROJ && (col * 4 + wave) * kUnit >= a.Hu) return;            // past the last unit tile
 
     // ---- the tile's rows
@@ -1034,15 +1024,9 @@ __device__ __forceinline__ void thin_body(const LevelArgs &a, int tile) {
     }
     b_pair = (int64_t)a.NPU * 64;
 
-    floatx16 acc[4];
+    floatx16 acc[1];
 #pragma unroll
-    for (int g = 0; g < 4; ++g)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[g][v] = 0.0f;
-    CellBias bias = {};
-    if constexpr (MODE != MODE_PROJ) {
-        if (wave == 0) bias = load_cell_bias<MODE>(a, col, lane);     // on its way while the K loop runs
-    }
+    for (int v = 0; v < 16; ++v) acc[0][v] = 0.0f;
 
     u32x4 fa[kThinAhead], fb[kThinAhead];
     auto request = [&](int g, int slot) __attribute__((always_inline)) {
@@ -1074,7 +1058,7 @@ __device__ __forceinline__ void thin_body(const LevelArgs &a, int tile) {
             const int node = __shfl(my_node, rl, 64);      // lane rl holds the node of tile row rl (all lanes take part)
             if (unit < a.H && row0 + rl < a.n_rows) P[(int64_t)node * a.Hq + unit] = from_f32<T>(acc[0][v]);
         }
-    } else if constexpr (ROWS) {
+    } else {
         // the gates meet in LDS; every wave finishes eight of the tile's rows
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
@@ -1082,21 +1066,7 @@ __device__ __forceinline__ void thin_body(const LevelArgs &a, int tile) {
             smem[wave * (32 * kEpiStride) + rl * kEpiStride + l32] = acc[0][v];
         }
         __syncthreads();
-        cell_rows<T, MODE>(a, smem, s_node, s_ar, s_cb, s_kid, col, wave, lane);
-    } else {
-        // gates 1-3 travel to wave 0, which holds gate 0 (every wave that is still here
-        // reaches this barrier; the forget wave of a leaf level left above)
-        if (wave > 0) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) exchange[wave - 1][v][lane] = acc[0][v];
-        }
-        __syncthreads();
-        if (wave > 0) return;
-#pragma unroll
-        for (int g = 1; g < (MODE == MODE_LEAF ? 3 : 4); ++g)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[g][v] = exchange[g - 1][v][lane];
-        cell_pass<T, MODE, SAVE>(a, acc, region, s_node, s_ar, s_cb, s_kid, col, lane, bias);
+        cell_rows<T, MODE, SAVE>(a, smem, s_node, s_ar, s_cb, s_kid, col, wave, lane);
     }
 }
 

@@ -332,8 +332,9 @@ __device__ __forceinline__ void cell_pass(const LevelArgs &a, const floatx16 (&a
 // share a row, four units each, and walk that row's own child list four children at a time (P_k and
 // c_k of four children in flight per lane), in ascending child order.  With one wave for all 32 rows
 // (cell_pass) every row waits for the tile's longest child list; here a wave waits for the longest
-// of its eight rows, and four waves' loads are in flight together.
-template <typename T, int MODE>
+// of its eight rows, and four waves' loads are in flight together.  SAVE (training): the gates after
+// their non-linearities and every child's forget gate are kept as well.
+template <typename T, int MODE, bool SAVE = false>
 __device__ __forceinline__ void cell_rows(const LevelArgs &a, const float *zt, const int *rn, const int *rar,
                                           const int *rcb, const int4 *rkid, int unit_tile, int wave, int lane) {
     const int tr = wave * 8 + (lane >> 3);
@@ -348,9 +349,21 @@ __device__ __forceinline__ void cell_rows(const LevelArgs &a, const float *zt, c
         return make_float4(q.x + bq.x, q.y + bq.y, q.z + bq.z, q.w + bq.w);
     };
     const float4 zi = gate(0), zo = gate(1), zu = gate(2);
-    float4 cc = make_float4(sigmoid_t<T>(zi.x) * tanh_t<T>(zu.x), sigmoid_t<T>(zi.y) * tanh_t<T>(zu.y),
-                            sigmoid_t<T>(zi.z) * tanh_t<T>(zu.z), sigmoid_t<T>(zi.w) * tanh_t<T>(zu.w));
+    const float gi[4] = {sigmoid_t<T>(zi.x), sigmoid_t<T>(zi.y), sigmoid_t<T>(zi.z), sigmoid_t<T>(zi.w)};
+    const float gu[4] = {tanh_t<T>(zu.x), tanh_t<T>(zu.y), tanh_t<T>(zu.z), tanh_t<T>(zu.w)};
+    float4 cc = make_float4(gi[0] * gu[0], gi[1] * gu[1], gi[2] * gu[2], gi[3] * gu[3]);
     const float4 go = make_float4(sigmoid_t<T>(zo.x), sigmoid_t<T>(zo.y), sigmoid_t<T>(zo.z), sigmoid_t<T>(zo.w));
+    if constexpr (SAVE) {      // training: the gates after their non-linearities, rows by node id
+        const float o4[4] = {go.x, go.y, go.z, go.w};
+        T *g = static_cast<T *>(a.gates) + (int64_t)node * 3 * a.H;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (unit0 + e < a.H) {
+                g[unit0 + e] = from_f32<T>(gi[e]);
+                g[a.H + unit0 + e] = from_f32<T>(o4[e]);
+                g[2 * a.H + unit0 + e] = from_f32<T>(gu[e]);
+            }
+    }
     if constexpr (MODE == MODE_INTERNAL) {
         const float4 fx = gate(3);
         const int ar = rar[tr];
@@ -361,12 +374,14 @@ __device__ __forceinline__ void cell_rows(const LevelArgs &a, const float *zt, c
         for (int c0 = 0; c0 < ar; c0 += 4) {
             bool has[4];
             int64_t ofs[4];
+            int kidv[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int c = c0 + j;
                 has[j] = c < ar;
                 // a slot without a child re-reads the row's first child and is not added
                 const int kid = !has[j] ? k4.x : (c0 == 0 ? first[j] : a.child_idx[cb + c]);
+                kidv[j] = kid;
                 ofs[j] = (int64_t)kid * a.Hq + unit_ld;
             }
             float4 pk[4], ck[4];
@@ -384,10 +399,18 @@ __device__ __forceinline__ void cell_rows(const LevelArgs &a, const float *zt, c
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 if (has[j]) {
-                    cc.x += sigmoid_t<T>(fx.x + pk[j].x) * ck[j].x;
-                    cc.y += sigmoid_t<T>(fx.y + pk[j].y) * ck[j].y;
-                    cc.z += sigmoid_t<T>(fx.z + pk[j].z) * ck[j].z;
-                    cc.w += sigmoid_t<T>(fx.w + pk[j].w) * ck[j].w;
+                    const float f[4] = {sigmoid_t<T>(fx.x + pk[j].x), sigmoid_t<T>(fx.y + pk[j].y),
+                                        sigmoid_t<T>(fx.z + pk[j].z), sigmoid_t<T>(fx.w + pk[j].w)};
+                    cc.x += f[0] * ck[j].x;
+                    cc.y += f[1] * ck[j].y;
+                    cc.z += f[2] * ck[j].z;
+                    cc.w += f[3] * ck[j].w;
+                    if constexpr (SAVE) {      // training: the forget gate this parent applied to child kidv[j]
+                        T *dst = static_cast<T *>(a.fgate) + (int64_t)kidv[j] * a.H + unit0;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (unit0 + e < a.H) dst[e] = from_f32<T>(f[e]);
+                    }
                 }
             }
         }
