@@ -1106,12 +1106,20 @@ thin_proj_stack_kernel(const LevelArgs a, const StackArgs s) {
 //   * the K loop then has no barrier: A fragments from LDS (the next one read while this one is
 //     multiplied), the wave's own weight rows from global memory / L2, kChainAhead K groups ahead,
 //     the first turn requested before anything else in the kernel;
-//   * the gates meet in LDS and each wave finishes eight of the tile's rows.
+//   * the gates meet in LDS and each of the first four waves finishes eight of the tile's rows;
+//   * KS > 1: 4 KS waves, wave w multiplies gate w % 4 over part w / 4 of K.  A level of a few hundred rows leaves
+//     most SIMDs idle, and one wave per gate spends the level's time on its own chain of MFMAs (fp32: four
+//     64-cycle MFMAs per 32 bytes of K); KS waves per gate cut that chain, and the weight loads and fragment
+//     reads in it, KS-fold.  The parts' sums are added in the order of the parts.
 //
 // Needs D % 4 == 0 (an 8- / 16-byte piece of an x row is inside D or outside) and an A tile that
-// fits LDS (chain_lds_bytes).
+// fits LDS (chain_lds_bytes) beside the KS sets of pre-activations.
 constexpr int kChainAhead = 16;                         // weight K groups in flight per wave
-constexpr int kChainLdsMax = 128 * 1024;                // dynamic LDS the kernel may ask for (beside ~22 KB static)
+constexpr int kChainLdsTotal = 156 * 1024;              // LDS one block may take in all (static + dynamic)
+constexpr int kChainStatic = 1024;                      // static LDS of chain_kernel beside its pre-activations (row ids), rounded up
+__host__ __device__ constexpr int chain_zt_bytes(int ks) { return 4 * ks * 32 * kEpiStride * 4; }
+// dynamic LDS chain_kernel<T, KS> may ask for
+constexpr int chain_lds_max(int ks) { return kChainLdsTotal - kChainStatic - chain_zt_bytes(ks); }
 // LDS pitch of an A row: K bytes + 16, so that 16 lanes' 16-byte reads of one K group fall in 64 different banks
 __host__ __device__ inline int chain_row_pitch(int k_bytes) { return k_bytes + 16; }
 inline size_t chain_lds_bytes(int k_bytes) { return (size_t)32 * chain_row_pitch(k_bytes); }
@@ -1126,18 +1134,20 @@ __device__ __forceinline__ void chain_piece_ok(bool kid_ok, int kb, int x_bytes,
     ok1 = (ESZ == 2 && in_x) ? (k0 + 4 < D) : ok0;       // bf16: the second four elements of the piece
 }
 
-template <typename T>
-__global__ void __launch_bounds__(kThinWaves * 64, 2)
+template <typename T, int KS>
+__global__ void __launch_bounds__(kThinWaves * 64 * KS, KS == 1 ? 2 : 1)
 chain_kernel(const LevelArgs a) {
     constexpr int ESZ = (int)sizeof(T);
     extern __shared__ __attribute__((aligned(16))) char a_lds[];          // [32][chain_row_pitch]
-    __shared__ __attribute__((aligned(16))) float zt[4][32 * kEpiStride];  // pre-activations, [gate][row][unit]
+    __shared__ __attribute__((aligned(16))) float zt[4 * KS][32 * kEpiStride];  // pre-activations, [part][gate][row][unit]
     __shared__ int s_node[32];
     __shared__ int s_kid[32];
+    static_assert(sizeof(zt) == chain_zt_bytes(KS) && 2 * 32 * 4 <= kChainStatic, "chain_lds_max counts these");
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int gate = wave & 3, part = wave >> 2;
     const int hf = lane >> 5, l32 = lane & 31;
     const int tile = blockIdx.x;
     const int row0 = (tile / a.n_col_tiles) * 32;
@@ -1150,9 +1160,13 @@ chain_kernel(const LevelArgs a) {
     const int x_bytes = a.Dp * ESZ;                      // K bytes of the x part
     const int k_bytes = x_bytes + a.Hp * ESZ;
     const int pitch = chain_row_pitch(k_bytes);
-    const int n_groups = k_bytes / 32;
-    const int last_group = n_groups - 1;
-    const int64_t brow = (int64_t)col * kGateTile + wave * kUnit + l32;
+    const int n_all = k_bytes / 32;                      // K groups of a row (a multiple of four)
+    // this wave's part of them, [g_begin, g_begin + n_groups): whole slabs (pairs of groups)
+    const int per_part = ((n_all + KS - 1) / KS + 1) & ~1;
+    const int g_begin = part * per_part < n_all ? part * per_part : n_all;
+    const int n_groups = n_all - g_begin < per_part ? n_all - g_begin : per_part;
+    const int last_group = n_groups > 0 ? g_begin + n_groups - 1 : n_all - 1;   // (a part without groups loads the row's last one, unused)
+    const int64_t brow = (int64_t)col * kGateTile + gate * kUnit + l32;
     const char *bp = static_cast<const char *>(a.Bp) + operand_offset(brow, 0, a.NPU) + hf * 16;
     const int64_t b_pair = (int64_t)a.NPU * 64;
     u32x4 fb[kChainAhead];
@@ -1160,16 +1174,18 @@ chain_kernel(const LevelArgs a) {
         fb[slot] = *reinterpret_cast<const u32x4 *>(bp + (int64_t)(g >> 1) * b_pair + (g & 1) * 32);
     };
 #pragma unroll
-    for (int s = 0; s < kChainAhead; ++s) request(s < last_group ? s : last_group, s);
+    for (int s = 0; s < kChainAhead; ++s) request(g_begin + s < last_group ? g_begin + s : last_group, s);
     __builtin_amdgcn_sched_barrier(0);
 
-    // ---- the tile's A: thread t moves pieces (t & 31) + 32 i of rows (t >> 5) + 8 j
+    // ---- the tile's A: thread t moves pieces (t & 31) + 32 i of rows (t >> 5) + RPP j
     {
-        const char *src_x[4], *src_h[4];
-        bool kid_ok[4];
+        constexpr int RPP = 8 * KS;           // rows per pass of the block's threads
+        constexpr int NJ = 32 / RPP;
+        const char *src_x[NJ], *src_h[NJ];
+        bool kid_ok[NJ];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int rl = (tid >> 5) + 8 * j;
+        for (int j = 0; j < NJ; ++j) {
+            const int rl = (tid >> 5) + RPP * j;
             int r = row0 + rl;
             const bool ok = r < a.n_rows;
             if (!ok) r = a.n_rows - 1;                // computed twice, stored never
@@ -1189,7 +1205,7 @@ chain_kernel(const LevelArgs a) {
             const int kb = ((tid & 31) + 32 * i) * 16;
             if (kb >= k_bytes) break;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < NJ; ++j) {
                 bool ok0, ok1;
                 chain_piece_ok<T>(kid_ok[j], kb, x_bytes, k_bytes, a.D, ok0, ok1);
                 // a piece that is not to be read comes from the start of the x row (always valid: D >= 4)
@@ -1204,7 +1220,7 @@ chain_kernel(const LevelArgs a) {
                     v[0] = q0[0]; v[1] = q0[1]; v[2] = q1[0]; v[3] = q1[1];
                 }
                 v[0] = ok0 ? v[0] : 0u; v[1] = ok0 ? v[1] : 0u; v[2] = ok1 ? v[2] : 0u; v[3] = ok1 ? v[3] : 0u;
-                *reinterpret_cast<u32x4 *>(a_lds + ((tid >> 5) + 8 * j) * pitch + kb) = v;
+                *reinterpret_cast<u32x4 *>(a_lds + ((tid >> 5) + RPP * j) * pitch + kb) = v;
             }
         }
     }
@@ -1216,13 +1232,14 @@ chain_kernel(const LevelArgs a) {
     // ---- K loop: whole turns of the ring, then the rest (a multiple of 4 groups)
     const char *abuf = a_lds + l32 * pitch + hf * 16;    // this lane's A fragment, K group 0
     const int n_full = n_groups / kChainAhead;
-    u32x4 fa = *reinterpret_cast<const u32x4 *>(abuf);
+    const int g_end = g_begin + n_groups;
+    u32x4 fa = *reinterpret_cast<const u32x4 *>(abuf + (g_begin < n_all ? g_begin : n_all - 1) * 32);
     for (int c = 0; c < n_full; ++c) {
-        const int g0 = c * kChainAhead;
+        const int g0 = g_begin + c * kChainAhead;
 #pragma unroll
         for (int s = 0; s < kChainAhead; ++s) {
             // the next A fragment leaves LDS while this one is multiplied
-            const int gnext = g0 + s + 1 < n_groups ? g0 + s + 1 : last_group;
+            const int gnext = g0 + s + 1 < g_end ? g0 + s + 1 : last_group;
             const u32x4 fa_next = *reinterpret_cast<const u32x4 *>(abuf + gnext * 32);
             mfma_step<T>(fa, fb[s], acc);
             const int gn = g0 + s + kChainAhead;
@@ -1232,25 +1249,26 @@ chain_kernel(const LevelArgs a) {
         }
     }
     {
-        const int g0 = n_full * kChainAhead;
-        const int tail = n_groups - g0;
+        const int g0 = g_begin + n_full * kChainAhead;
+        const int tail = g_end - g0;
 #pragma unroll
         for (int s = 0; s < kChainAhead; ++s)
             if (s < tail) {
-                const int gnext = g0 + s + 1 < n_groups ? g0 + s + 1 : last_group;
+                const int gnext = g0 + s + 1 < g_end ? g0 + s + 1 : last_group;
                 const u32x4 fa_next = *reinterpret_cast<const u32x4 *>(abuf + gnext * 32);
                 mfma_step<T>(fa, fb[s], acc);
                 fa = fa_next;
             }
     }
 
-    // ---- the gates meet in LDS; wave w finishes rows 8 w .. 8 w + 7: eight lanes per row, four units per lane
+    // ---- the gates meet in LDS; wave w < 4 finishes rows 8 w .. 8 w + 7: eight lanes per row, four units per lane
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
         const int rl = (v >> 2) * 8 + hf * 4 + (v & 3);
         zt[wave][rl * kEpiStride + l32] = acc[v];
     }
     __syncthreads();
+    if (wave >= 4) return;
     const int tr = wave * 8 + (lane >> 3);
     const int node = s_node[tr];
     if (node < 0) return;
@@ -1264,7 +1282,12 @@ chain_kernel(const LevelArgs a) {
     float z[4][4];
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-        const float4 q = *reinterpret_cast<const float4 *>(&zt[g][tr * kEpiStride + u4]);
+        float4 q = *reinterpret_cast<const float4 *>(&zt[g][tr * kEpiStride + u4]);
+#pragma unroll
+        for (int p = 1; p < KS; ++p) {
+            const float4 qp = *reinterpret_cast<const float4 *>(&zt[4 * p + g][tr * kEpiStride + u4]);
+            q.x += qp.x; q.y += qp.y; q.z += qp.z; q.w += qp.w;
+        }
         const float4 bq = *reinterpret_cast<const float4 *>(bias + g * kUnit);
         z[g][0] = q.x + bq.x; z[g][1] = q.y + bq.y; z[g][2] = q.z + bq.z; z[g][3] = q.w + bq.w;
     }
@@ -1581,16 +1604,21 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
     int chain_from = L;
     const int chain_k_bytes = (d.Dp + d.Hp) * d.esz;
     const size_t chain_lds = chain_lds_bytes(chain_k_bytes);      // the tile's A rows live in LDS
-    if (!SAVE && !slots && s->host_level_kids && (d.D & 3) == 0 && chain_lds <= (size_t)kChainLdsMax) {
+    // waves per gate: fp32 (long MFMA chains) two if the LDS beside the A tile allows, bf16 one.  (Four measured
+    // slower than two: blocks of 1024 threads start later than they finish earlier.)
+    const int chain_ks = (sizeof(T) == 4 && chain_lds <= (size_t)chain_lds_max(2)) ? 2 : 1;
+    if (!SAVE && !slots && s->host_level_kids && (d.D & 3) == 0 && chain_lds <= (size_t)chain_lds_max(chain_ks)) {
         for (int l = L - 1; l >= 1; --l) {
             const int rows = sp[l + 1] - sp[l];
             if (rows > kThinMaxRows || s->host_level_kids[l] != rows) break;
             chain_from = l;
         }
     }
-    if (chain_from < L)      // more dynamic LDS than a launch may ask for by default
-        JITDB_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&chain_kernel<T>),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, kChainLdsMax));
+    if (chain_from < L) {    // more dynamic LDS than a launch may ask for by default
+        const void *fn = chain_ks == 2 ? reinterpret_cast<const void *>(&chain_kernel<T, 2>)
+                                       : reinterpret_cast<const void *>(&chain_kernel<T, 1>);
+        JITDB_HIP_CHECK(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, chain_lds_max(chain_ks)));
+    }
     const int n_unit_tiles = d.Hu / kUnit;
     a.w_bytes = (int64_t)packed_w_bytes(d);
     a.NP = d.NP;
@@ -1618,7 +1646,8 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
             a.n_tiles = (int)ceil_div(n_rows, 32) * a.n_col_tiles;
             a.n_blocks = a.n_tiles;
             ScopedLaunchTimer tm(JITDB_K_CHAIN, n_rows, st, s->host_level_kids[l]);
-            chain_kernel<T><<<a.n_blocks, kThinWaves * 64, chain_lds, st>>>(a);
+            if (chain_ks == 2) chain_kernel<T, 2><<<a.n_blocks, kThinWaves * 64 * 2, chain_lds, st>>>(a);
+            else chain_kernel<T, 1><<<a.n_blocks, kThinWaves * 64, chain_lds, st>>>(a);
             JITDB_LAUNCH_CHECK();
             continue;
         }

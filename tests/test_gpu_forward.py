@@ -463,11 +463,13 @@ def _trees_and_sequences(n_trees, n_seqs, len_hi, seed):
 
 
 @pytest.mark.parametrize("dtype,D,H", [("f32", 300, 256), ("bf16", 300, 512), ("f32", 44, 50), ("bf16", 44, 50),
-                                       ("bf16", 64, 72)])
+                                       ("bf16", 64, 72), ("f32", 300, 512), ("f32", 512, 512), ("f32", 4, 1)])
 def test_chain_levels_run_as_one_launch_each(c_oracle, dtype, D, H):
     """Parse trees plus sequences up to 90 long: above the trees' heights every level holds only nodes
     with one child and takes the single-launch kernel (x and the child's h read in place, all four
-    gates full K); below, the usual stack / level / projection launches.  Padded widths included."""
+    gates full K); below, the usual stack / level / projection launches.  Padded widths included.
+    fp32 splits K over two waves per gate where the LDS beside the A tile allows: (300, 256), (300, 512) and the
+    small widths do, (512, 512) does not."""
     parent = _trees_and_sequences(300, 700, 90, 5)
     x, W, U, b = make_values(2, parent.shape[0], "random", D=D, H=H)
     (res, launches) = _profile_classes(lambda: run_gpu_forward(parent, x, W, U, b, dtype))
@@ -553,7 +555,7 @@ def test_chain_levels_inside_a_captured_graph(c_oracle):
 def test_chain_levels_too_wide_for_lds_take_the_general_launches(c_oracle):
     """K = D + H so large that 32 rows of A do not fit the LDS the kernel may use: same result, other launches."""
     parent = chain_forest(12, 40)
-    D, H = 1024, 1280                                  # 32 x (9216 + 16) bytes > 128 KB
+    D, H = 1024, 1280                                  # 32 x (9216 + 16) bytes: more than a compute unit's LDS
     x, W, U, b = make_values(2, parent.shape[0], "random", D=D, H=H)
     (res, launches) = _profile_classes(lambda: run_gpu_forward(parent, x, W, U, b, "f32"))
     _, h, c, seen = res
