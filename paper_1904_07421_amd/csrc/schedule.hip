@@ -125,10 +125,43 @@ scan_apply_kernel(const int32_t *in, int64_t n_in, int32_t *out, int64_t n_out,
     }
 }
 
+// The same scan by one block, chunk after chunk with a running carry: one launch instead of three where the
+// array is short (the schedule of a small forest costs its number of launches, not its work).
+constexpr int kScanOneBlockChunks = 4;
+__global__ void __launch_bounds__(kThreads)
+scan_one_block_kernel(const int32_t *in, int64_t n_in, int32_t *out, int64_t n_out) {
+    int carry = 0;
+    for (int64_t chunk = 0; chunk < n_out; chunk += kScanChunk) {
+        const int64_t base = chunk + (int64_t)threadIdx.x * kScanItems;
+        int v[kScanItems];
+        int s = 0;
+#pragma unroll
+        for (int i = 0; i < kScanItems; ++i) {
+            const int64_t idx = base + i;
+            v[i] = idx < n_in ? in[idx] : 0;
+            s += v[i];
+        }
+        int total;
+        int run = block_exclusive_scan(s, &total) + carry;
+#pragma unroll
+        for (int i = 0; i < kScanItems; ++i) {
+            const int64_t idx = base + i;
+            if (idx < n_out) out[idx] = run;
+            run += v[i];
+        }
+        carry += total;
+    }
+}
+
 int launch_exclusive_scan(const int32_t *in, int64_t n_in, int32_t *out, int64_t n_out,
                           int32_t *partial, hipStream_t st) {
     if (n_out <= 0) return JITDB_OK;
     const int nb = (int)ceil_div(n_out, kScanChunk);
+    if (nb <= kScanOneBlockChunks) {
+        scan_one_block_kernel<<<1, kThreads, 0, st>>>(in, n_in, out, n_out);
+        JITDB_LAUNCH_CHECK();
+        return JITDB_OK;
+    }
     scan_reduce_kernel<<<nb, kThreads, 0, st>>>(in, n_in, partial);
     JITDB_LAUNCH_CHECK();
     scan_partials_kernel<<<1, kThreads, 0, st>>>(partial, nb);
@@ -233,6 +266,35 @@ jump_kernel(const int32_t *__restrict__ anc_in, int32_t *__restrict__ anc_out,
     if (any && (threadIdx.x & (kWave - 1)) == 0 &&
         __atomic_load_n(&meta[META_LIVE + k], __ATOMIC_RELAXED) == 0)
         __atomic_store_n(&meta[META_LIVE + k], 1, __ATOMIC_RELAXED);
+}
+
+// Every round of the pointer jumping in one launch, by one block: for forests small enough that a round is a
+// few passes of the block over the nodes.  The rounds are jump_kernel's (same reads, same atomic maxima, same
+// flags in meta); a barrier stands where the next launch would, and the block stops after the first round in
+// which no pointer moved.
+constexpr int kJumpOneBlockThreads = 1024;
+constexpr int kJumpOneBlockNodes = 8 * kJumpOneBlockThreads;
+__global__ void __launch_bounds__(kJumpOneBlockThreads)
+jump_one_block_kernel(int32_t *anc0, int32_t *anc1, int32_t *height, int32_t n, int rounds, int32_t *meta) {
+    for (int k = 0; k < rounds; ++k) {
+        const int32_t *anc_in = (k & 1) ? anc1 : anc0;
+        int32_t *anc_out = (k & 1) ? anc0 : anc1;
+        int live = 0;
+        for (int v = threadIdx.x; v < n; v += kJumpOneBlockThreads) {
+            const int32_t a = anc_in[v];
+            int32_t next = -1;
+            if (a >= 0) {
+                const int32_t hv = __atomic_load_n(&height[v], __ATOMIC_RELAXED);
+                atomicMax(&height[a], hv + (1 << k));
+                next = anc_in[a];
+                live |= next >= 0;
+            }
+            anc_out[v] = next;
+        }
+        const int any = __syncthreads_or(live);      // also: this round's stores and maxima before the next round's reads
+        if (threadIdx.x == 0 && any) meta[META_LIVE + k] = 1;
+        if (!any) break;
+    }
 }
 
 __global__ void __launch_bounds__(kThreads)
@@ -606,8 +668,8 @@ int schedule_impl(const int32_t *parent, const int32_t *sig, jitdb_slots_t *slot
     int rc;
 
     // 1. child counts + validation
-    if ((rc = launch_fill(w.meta, META_WORDS, 0, st)) != JITDB_OK) return rc;
-    if ((rc = launch_fill(w.cnt, n64 + 1, 0, st)) != JITDB_OK) return rc;
+    //    (the bookkeeping words and the counts lie back to back in the workspace: one fill)
+    if ((rc = launch_fill(w.meta, (w.cnt - w.meta) + n64 + 1, 0, st)) != JITDB_OK) return rc;
     count_children_kernel<<<grid, kThreads, 0, st>>>(parent, n, w.cnt, w.anc[0], s->height, w.meta);
     JITDB_LAUNCH_CHECK();
     if (slots) {
@@ -626,9 +688,14 @@ int schedule_impl(const int32_t *parent, const int32_t *sig, jitdb_slots_t *slot
     // (a capped grid with a stride loop: the rounds after the last live one are launched all the
     //  same and should cost a few thousand blocks' worth of "return", not a block per 256 nodes)
     const unsigned jump_grid = grid < 4096 ? grid : 4096;
-    for (int k = 0; k < rounds; ++k) {
-        jump_kernel<<<jump_grid, kThreads, 0, st>>>(w.anc[k & 1], w.anc[(k + 1) & 1], s->height, n, k, w.meta);
+    if (n <= kJumpOneBlockNodes && rounds > 0) {      // a small forest: all rounds in one launch
+        jump_one_block_kernel<<<1, kJumpOneBlockThreads, 0, st>>>(w.anc[0], w.anc[1], s->height, n, rounds, w.meta);
         JITDB_LAUNCH_CHECK();
+    } else {
+        for (int k = 0; k < rounds; ++k) {
+            jump_kernel<<<jump_grid, kThreads, 0, st>>>(w.anc[k & 1], w.anc[(k + 1) & 1], s->height, n, k, w.meta);
+            JITDB_LAUNCH_CHECK();
+        }
     }
     {
         const unsigned g = (unsigned)(ceil_div(n64, kThreads) < 1024 ? ceil_div(n64, kThreads) : 1024);

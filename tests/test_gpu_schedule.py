@@ -49,6 +49,33 @@ def test_shapes_and_edges(name, parent):
     assert_schedule_equal(_run(parent).to_numpy(), S.schedule_fast(parent))
 
 
+@pytest.mark.parametrize("n", [8191, 8192, 8193, 16383, 16384, 16385])
+@pytest.mark.parametrize("kind", ["chain", "trees"])
+def test_sizes_around_the_one_launch_paths(kind, n):
+    """Forests of up to 8192 nodes run every pointer-jumping round in one launch, and scans of up to 16384
+    entries are one launch: one node below, at and above both limits, as one relabelled chain (as many rounds as
+    a forest of that size can need) and as a forest of small trees."""
+    if kind == "chain":
+        p, _ = relabel(chain_forest(n), n)
+    else:
+        from workloads import bounded_arity_forest
+        p = bounded_arity_forest(n // 8 + 8, 9, 15, 4, n)[:n].copy()      # the last tree may be cut short:
+        assert (p < np.arange(n)).all()                                    # parents precede their children
+    print(f"schedule one-launch paths {kind} N={p.shape[0]}", flush=True)
+    assert p.shape[0] == n
+    assert_schedule_equal(_run(p).to_numpy(), S.schedule_fast(p))
+
+
+def test_small_cycle_is_detected_by_the_one_launch_rounds():
+    import paper_1904_07421_amd as J
+    p = chain_forest(50, 100).copy()                 # 100 chains of 50, 5000 nodes
+    roots = np.flatnonzero(p < 0)
+    p[roots[3]] = roots[3] + 49                      # the root of chain 3 under its own leaf
+    with pytest.raises(J.JitdbError) as e:
+        _run(p)
+    assert e.value.code == -4
+
+
 def test_deep_relabelled_chain():
     p, _ = relabel(chain_forest(70000), 5)       # 70000 levels, three radix passes over heights
     print("schedule deep relabelled chain", flush=True)
