@@ -244,11 +244,11 @@ __device__ __forceinline__ void cell_pass(const LevelArgs &a, const floatx16 (&a
         if constexpr (KIDS) fx4[q] = *reinterpret_cast<const float4 *>(s_fx + so);
     }
     if constexpr (KIDS) {
-        // Children are taken two per row and round, for four rows at once: sixteen
-        // independent 16-byte loads in flight per thread.  The first four child ids
-        // of a row sit in LDS; longer lists (rare) continue from child_idx.  A slot
-        // without a child re-reads the row's last child with weight zero, which
-        // keeps every load unconditional.
+        // Children are taken one per row and round, for four rows at once: eight independent loads in
+        // flight per thread (two per row and round measured no faster: half of all parents have one
+        // child, and the rows come sorted by arity).  The first four child ids of a row sit in LDS;
+        // longer lists (rare) continue from child_idx.  A row without a further child re-reads its last
+        // child with weight zero, which keeps every load unconditional.
         int ar[4];
         int max_ar = 0;
 #pragma unroll
@@ -259,64 +259,58 @@ __device__ __forceinline__ void cell_pass(const LevelArgs &a, const floatx16 (&a
         int64_t last[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) last[q] = unit_ld;
-        for (int c0 = 0; c0 < max_ar; c0 += 2) {
-            int64_t ofs[4][2];
-            float wgt[4][2];
-            int kidv[4][2];
+        for (int c = 0; c < max_ar; ++c) {
+            int64_t ofs[4];
+            float wgt[4];
+            int kidv[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 int4 kids = make_int4(0, 0, 0, 0);
-                if (c0 < 4) kids = rkid[tr[q]];
+                if (c < 4) kids = rkid[tr[q]];
+                const bool has = c < ar[q];
+                int kid;
+                if (c == 0) kid = kids.x;
+                else if (c == 1) kid = kids.y;
+                else if (c == 2) kid = kids.z;
+                else if (c == 3) kid = kids.w;
+                else kid = has ? a.child_idx[rcb[tr[q]] + c] : 0;
+                if (has) last[q] = (int64_t)kid * a.Hq + unit_ld;
+                ofs[q] = last[q];
+                wgt[q] = has ? 1.0f : 0.0f;
+                kidv[q] = has ? kid : -1;
+            }
+            float4 pk[4], ck[4];
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    const int c = c0 + j;
-                    const bool has = c < ar[q];
-                    int kid;
-                    if (c0 == 0) kid = j ? kids.y : kids.x;
-                    else if (c0 == 2) kid = j ? kids.w : kids.z;
-                    else kid = has ? a.child_idx[rcb[tr[q]] + c] : 0;
-                    if (has) last[q] = (int64_t)kid * a.Hq + unit_ld;
-                    ofs[q][j] = last[q];
-                    wgt[q][j] = has ? 1.0f : 0.0f;
-                    kidv[q][j] = has ? kid : -1;
+            for (int q = 0; q < 4; ++q) {
+                if constexpr (MODE == MODE_CHAIN) {      // U_f h_k is in the accumulator already
+                    pk[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+                } else if constexpr (sizeof(T) == 4) {
+                    pk[q] = *reinterpret_cast<const float4 *>(static_cast<const float *>(a.P) + ofs[q]);
+                } else {
+                    const uint2 w = *reinterpret_cast<const uint2 *>(static_cast<const bf16_t *>(a.P) + ofs[q]);
+                    pk[q] = make_float4(__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xFFFF0000u),
+                                        __uint_as_float(w.y << 16), __uint_as_float(w.y & 0xFFFF0000u));
+                }
+                ck[q] = *reinterpret_cast<const float4 *>(a.cs + ofs[q]);
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float f0 = sigmoid_t<T>(fx4[q].x + pk[q].x), f1 = sigmoid_t<T>(fx4[q].y + pk[q].y);
+                const float f2 = sigmoid_t<T>(fx4[q].z + pk[q].z), f3 = sigmoid_t<T>(fx4[q].w + pk[q].w);
+                cc[q].x += wgt[q] * f0 * ck[q].x;
+                cc[q].y += wgt[q] * f1 * ck[q].y;
+                cc[q].z += wgt[q] * f2 * ck[q].z;
+                cc[q].w += wgt[q] * f3 * ck[q].w;
+                if constexpr (SAVE) {
+                    if (kidv[q] >= 0) {
+                        const float fv[4] = {f0, f1, f2, f3};
+                        T *dst = static_cast<T *>(a.fgate) + (int64_t)kidv[q] * a.H + unit0;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (unit0 + e < a.H) dst[e] = from_f32<T>(fv[e]);
+                    }
                 }
             }
-            float4 pk[4][2], ck[4][2];
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    if constexpr (MODE == MODE_CHAIN) {      // U_f h_k is in the accumulator already
-                        pk[q][j] = make_float4(0.f, 0.f, 0.f, 0.f);
-                    } else if constexpr (sizeof(T) == 4) {
-                        pk[q][j] = *reinterpret_cast<const float4 *>(static_cast<const float *>(a.P) + ofs[q][j]);
-                    } else {
-                        const uint2 w = *reinterpret_cast<const uint2 *>(static_cast<const bf16_t *>(a.P) + ofs[q][j]);
-                        pk[q][j] = make_float4(__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xFFFF0000u),
-                                               __uint_as_float(w.y << 16), __uint_as_float(w.y & 0xFFFF0000u));
-                    }
-                    ck[q][j] = *reinterpret_cast<const float4 *>(a.cs + ofs[q][j]);
-                }
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    const float f0 = sigmoid_t<T>(fx4[q].x + pk[q][j].x), f1 = sigmoid_t<T>(fx4[q].y + pk[q][j].y);
-                    const float f2 = sigmoid_t<T>(fx4[q].z + pk[q][j].z), f3 = sigmoid_t<T>(fx4[q].w + pk[q][j].w);
-                    cc[q].x += wgt[q][j] * f0 * ck[q][j].x;
-                    cc[q].y += wgt[q][j] * f1 * ck[q][j].y;
-                    cc[q].z += wgt[q][j] * f2 * ck[q][j].z;
-                    cc[q].w += wgt[q][j] * f3 * ck[q][j].w;
-                    if constexpr (SAVE) {
-                        if (kidv[q][j] >= 0) {
-                            const float fv[4] = {f0, f1, f2, f3};
-                            T *dst = static_cast<T *>(a.fgate) + (int64_t)kidv[q][j] * a.H + unit0;
-#pragma unroll
-                            for (int e = 0; e < 4; ++e)
-                                if (unit0 + e < a.H) dst[e] = from_f32<T>(fv[e]);
-                        }
-                    }
-                }
         }
     }
 #pragma unroll
