@@ -352,7 +352,7 @@ __device__ __forceinline__ void dma_wait_barrier() {
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
-template <typename T, int MODE, typename Hook>
+template <typename T, int MODE, int NBUF = kDmaBufs, typename Hook>
 __device__ __forceinline__ void dma_gemm(const LevelArgs &a, char *lds, const int *row_node,
                                          int tile_row0, int col_tile, floatx16 (&acc)[2][4],
                                          char *sink, Hook &&after_first_requests) {
@@ -498,11 +498,14 @@ __device__ __forceinline__ void dma_gemm(const LevelArgs &a, char *lds, const in
     // go out, K group 0 is multiplied; once those reads are back nobody needs buffer cur any
     // more, and after the barrier (which also publishes stage g+1) it takes the request for
     // stage g+3.  K group 0 of stage g+1 is then read while K group 1 of stage g is multiplied.
+    // With two buffers (NBUF == 2) a stage's request follows the barrier that frees its buffer by one stage
+    // instead of two: nothing younger is in flight at a barrier, and every wait is for all loads.
+    static_assert(NBUF == 2 || NBUF == 3, "two or three stage buffers");
     Frags P, Q;
     int cur = 0;
-    auto next_buf = [&]() __attribute__((always_inline)) { return cur == 2 ? 0 : cur + 1; };
+    auto next_buf = [&]() __attribute__((always_inline)) { return cur == NBUF - 1 ? 0 : cur + 1; };
     auto step = [&](int g, auto ng_cur, auto ng_next, auto wait_tag) __attribute__((always_inline)) {
-        constexpr int WAIT = decltype(wait_tag)::value;
+        constexpr int WAIT = NBUF == 2 ? 0 : decltype(wait_tag)::value;
         read_group(cur, 1, ng_cur, Q);
         __builtin_amdgcn_sched_barrier(0);
         multiply(ng_cur, P);
@@ -511,7 +514,7 @@ __device__ __forceinline__ void dma_gemm(const LevelArgs &a, char *lds, const in
         dma_wait_barrier<WAIT>();
         read_group(next_buf(), 0, ng_next, P);
         __builtin_amdgcn_sched_barrier(0);
-        multiply_and_issue(ng_cur, Q, g + 3, cur, g + 3 < n_stages);
+        multiply_and_issue(ng_cur, Q, g + NBUF, cur, g + NBUF < n_stages);
         __builtin_amdgcn_sched_barrier(0);
         reads_done(ng_next, P);
         cur = next_buf();
@@ -539,9 +542,9 @@ __device__ __forceinline__ void dma_gemm(const LevelArgs &a, char *lds, const in
     }
     issue(0, 0);
     issue(1, 1);
-    if (n_stages > 2) issue(2, 2);
+    if (NBUF > 2 && n_stages > 2) issue(2, 2);
     after_first_requests();
-    if (n_stages > 2) dma_wait_barrier<2 * NLOAD>(); else dma_wait_barrier<NLOAD>();   // stage 0 is there
+    if (NBUF > 2 && n_stages > 2) dma_wait_barrier<2 * NLOAD>(); else dma_wait_barrier<NLOAD>();   // stage 0 is there
     int g = 0;
     if constexpr (MODE == MODE_PROJ) {
         read_group(0, 0, ngh, P);
@@ -574,13 +577,23 @@ __device__ __forceinline__ void dma_gemm(const LevelArgs &a, char *lds, const in
     dma_wait_barrier<0>();       // every wave is done reading the stage buffers
 }
 
+// The bf16 leaf level's blocks spend more time getting started and in the cell update than in their short K loop
+// (K = D only): there a block keeps two stage buffers instead of three and three blocks share a CU instead of
+// two (its three gate tiles leave the registers for that).  (fp32 leaves, whose K loop is bound by the fp32
+// matrix rate, lose 3 % that way and keep three buffers.)
+template <typename T, int MODE> constexpr bool kLeafDense = MODE == MODE_LEAF && sizeof(T) == 2;
+template <typename T, int MODE> constexpr int kLevelBufs = kLeafDense<T, MODE> ? 2 : kDmaBufs;
+template <typename T, int MODE> constexpr int kLevelBlocksPerCu = kLeafDense<T, MODE> ? 3 : 2;
+template <int MODE> constexpr int kEpiArrays = MODE == MODE_LEAF ? 2 : 3;      // i u and o; with children also W_f x + b_f
+
 template <typename T, int MODE, bool SAVE = false, bool GROUPED = false>
-__global__ void __launch_bounds__(kDmaThreads, 2)
+__global__ void __launch_bounds__(kDmaThreads, (kLevelBlocksPerCu<T, MODE>))
 level_kernel(const LevelArgs a_in) {
     LevelArgs a = a_in;
-    __shared__ __attribute__((aligned(1024))) char lds[kDmaBufs * kDmaBuf];
-    static_assert(4 * 3 * 32 * kEpiStride * 4 <= kDmaBufs * kDmaBuf, "epilogue regions must fit the stage buffers");
-    static_assert(4 * 32 * kDmaProjStride * 4 <= kDmaBufs * kDmaBuf, "projection regions must fit the stage buffers");
+    constexpr int NBUF = kLevelBufs<T, MODE>;
+    __shared__ __attribute__((aligned(1024))) char lds[NBUF * kDmaBuf];
+    static_assert(4 * kEpiArrays<MODE> * 32 * kEpiStride * 4 <= NBUF * kDmaBuf, "epilogue regions must fit the stage buffers");
+    static_assert(MODE != MODE_PROJ || 4 * 32 * kDmaProjStride * 4 <= NBUF * kDmaBuf, "projection regions must fit the stage buffers");
     __shared__ int row_node[kDmaBM];
     __shared__ int row_ar[kDmaBM];
     __shared__ int row_cb[kDmaBM];
@@ -639,10 +652,10 @@ level_kernel(const LevelArgs a_in) {
     if constexpr (MODE == MODE_PROJ) {
         publish_rows();
         __syncthreads();
-        dma_gemm<T, MODE>(a, lds, row_node, tile_row0, col_tile, acc, sink, []() {});
+        dma_gemm<T, MODE, NBUF>(a, lds, row_node, tile_row0, col_tile, acc, sink, []() {});
     } else {
         bias = load_cell_bias<MODE>(a, col_tile * 2 + wn, lane);     // on its way while the GEMM runs
-        dma_gemm<T, MODE>(a, lds, row_node, tile_row0, col_tile, acc, sink, publish_rows);
+        dma_gemm<T, MODE, NBUF>(a, lds, row_node, tile_row0, col_tile, acc, sink, publish_rows);
     }
 
     if constexpr (MODE == MODE_PROJ) {
@@ -653,7 +666,7 @@ level_kernel(const LevelArgs a_in) {
         for (int p = 0; p < 2; ++p)
             proj_pass<T>(a, acc[p], region, row_node + wm * 64 + p * 32, col_tile * 256 + wn * 128, lane);
     } else {
-        float *region = reinterpret_cast<float *>(lds) + wave * (3 * 32 * kEpiStride);
+        float *region = reinterpret_cast<float *>(lds) + wave * (kEpiArrays<MODE> * 32 * kEpiStride);
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
             const int r0 = wm * 64 + p * 32;
