@@ -123,19 +123,32 @@ __device__ __forceinline__ void row_record_body(const int32_t *__restrict__ perm
     const bool sorted = (lvl1 - lvl0) < 16;
     s_count[t] = 0;
     __syncthreads();
+    // A thread's sixteen records are fetched side by side, not one after the other: every load of a step is
+    // unconditional (a position past the window reads the window's last one and is dropped afterwards), so the
+    // chain perm -> child_ptr / height costs its two trips to memory once per thread, not once per record.
     int node[kRecPerThread], ar[kRecPerThread], cb[kRecPerThread], key[kRecPerThread];
+    bool live[kRecPerThread];
 #pragma unroll
     for (int i = 0; i < kRecPerThread; ++i) {
         const int p = w0 + i * kThreads + t;
-        node[i] = -1; ar[i] = 0; cb[i] = 0; key[i] = 0;
-        if (p < w0 + wn) {
-            node[i] = perm[p];
-            cb[i] = child_ptr[node[i]];
-            ar[i] = child_ptr[node[i] + 1] - cb[i];
-            if (sorted) {
-                key[i] = (height[node[i]] - lvl0) * 16 + (15 - (ar[i] < 15 ? ar[i] : 15));
-                atomicAdd(&s_count[key[i]], 1);
-            }
+        live[i] = p < w0 + wn;
+        node[i] = perm[live[i] ? p : w0 + wn - 1];
+    }
+    int hgt[kRecPerThread];
+#pragma unroll
+    for (int i = 0; i < kRecPerThread; ++i) {
+        cb[i] = child_ptr[node[i]];
+        ar[i] = child_ptr[node[i] + 1] - cb[i];
+        hgt[i] = sorted ? height[node[i]] : 0;
+    }
+#pragma unroll
+    for (int i = 0; i < kRecPerThread; ++i) {
+        key[i] = 0;
+        if (!live[i]) {
+            node[i] = -1; ar[i] = 0; cb[i] = 0;
+        } else if (sorted) {
+            key[i] = (hgt[i] - lvl0) * 16 + (15 - (ar[i] < 15 ? ar[i] : 15));
+            atomicAdd(&s_count[key[i]], 1);
         }
     }
     __syncthreads();
@@ -151,15 +164,21 @@ __device__ __forceinline__ void row_record_body(const int32_t *__restrict__ perm
     }
     s_count[t] = s_scan[t] - v;
     __syncthreads();
+    // the first four child ids of every record, again all loads of the thread side by side (a child position the
+    // node does not have reads the node's first position, or, for a leaf, whatever stands at its CSR start, which
+    // lies inside the array: child_ptr <= E < N; the value is replaced by -1)
+    int kid[kRecPerThread][4];
+#pragma unroll
+    for (int i = 0; i < kRecPerThread; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) kid[i][j] = child_idx[cb[i] + (j < ar[i] ? j : 0)];
 #pragma unroll
     for (int i = 0; i < kRecPerThread; ++i) {
         if (node[i] < 0) continue;
         const int64_t q = sorted ? (int64_t)w0 + atomicAdd(&s_count[key[i]], 1) : (int64_t)w0 + i * kThreads + t;
-        int kid[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) kid[j] = j < ar[i] ? child_idx[cb[i] + j] : -1;
         row_rec[2 * q] = make_int4(node[i], ar[i], cb[i], 0);
-        row_rec[2 * q + 1] = make_int4(kid[0], kid[1], kid[2], kid[3]);
+        row_rec[2 * q + 1] = make_int4(0 < ar[i] ? kid[i][0] : -1, 1 < ar[i] ? kid[i][1] : -1,
+                                       2 < ar[i] ? kid[i][2] : -1, 3 < ar[i] ? kid[i][3] : -1);
     }
 }
 
