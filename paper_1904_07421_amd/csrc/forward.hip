@@ -105,23 +105,32 @@ pack_weights_kernel(const PackArgs p) {
 // positions (a counting sort in LDS; positions are already ordered by level, and the
 // level is the major key so every row stays inside its level).  A window that spans 16 or
 // more levels is left in position order: its levels are too small for the order to matter.
-constexpr int kRecWindow = 4096;
-constexpr int kRecPerThread = kRecWindow / kThreads;
+// The longer the runs of equal arity, the fewer passes of the cell update mix child lists of different length: a
+// large forest takes windows of 16384 positions (blocks of 1024 threads, a launch of their own); measured on
+// 2.36 M nodes, windows of 4096 -> 8192 -> 16384 rows take the internal levels from 5.26 to 5.17 to 5.10 ms
+// (32768: 5.13) for 0.04 / 0.085 ms more in this step.
+constexpr int kRecPerThread = 16;
+constexpr int kRecWindow = kRecPerThread * kThreads;          // 4096
+constexpr int kRecThreadsLarge = 1024;
+constexpr int kRecWindowLarge = kRecPerThread * kRecThreadsLarge;   // 16384
+constexpr int64_t kRecLargeMinNodes = 262144;      // forests of at least this many nodes take the large windows
 
-// window `window` of the records (kThreads threads)
+// window `window` of the records (NT threads, kRecPerThread records each)
+template <int NT>
 __device__ __forceinline__ void row_record_body(const int32_t *__restrict__ perm, const int32_t *__restrict__ height,
                                                 const int32_t *__restrict__ child_ptr,
                                                 const int32_t *__restrict__ child_idx,
                                                 int4 *__restrict__ row_rec, int n, int window) {
+    constexpr int kWin = kRecPerThread * NT;
     __shared__ int s_count[256];   // per key: count, then the next free slot
     __shared__ int s_scan[256];
     const int t = threadIdx.x;
-    const int w0 = window * kRecWindow;
-    const int wn = (n - w0) < kRecWindow ? (n - w0) : kRecWindow;
+    const int w0 = window * kWin;
+    const int wn = (n - w0) < kWin ? (n - w0) : kWin;
     const int lvl0 = height[perm[w0]];
     const int lvl1 = height[perm[w0 + wn - 1]];
     const bool sorted = (lvl1 - lvl0) < 16;
-    s_count[t] = 0;
+    if (t < 256) s_count[t] = 0;
     __syncthreads();
     // A thread's sixteen records are fetched side by side, not one after the other: every load of a step is
     // unconditional (a position past the window reads the window's last one and is dropped afterwards), so the
@@ -130,7 +139,7 @@ __device__ __forceinline__ void row_record_body(const int32_t *__restrict__ perm
     bool live[kRecPerThread];
 #pragma unroll
     for (int i = 0; i < kRecPerThread; ++i) {
-        const int p = w0 + i * kThreads + t;
+        const int p = w0 + i * NT + t;
         live[i] = p < w0 + wn;
         node[i] = perm[live[i] ? p : w0 + wn - 1];
     }
@@ -152,33 +161,39 @@ __device__ __forceinline__ void row_record_body(const int32_t *__restrict__ perm
         }
     }
     __syncthreads();
-    // exclusive scan of the 256 counts
-    int v = s_count[t];
-    s_scan[t] = v;
+    // exclusive scan of the 256 counts (by the first 256 threads; every thread meets the barriers)
+    const int v = t < 256 ? s_count[t] : 0;
+    if (t < 256) s_scan[t] = v;
     __syncthreads();
     for (int d = 1; d < 256; d <<= 1) {
-        const int add = t >= d ? s_scan[t - d] : 0;
+        const int add = (t < 256 && t >= d) ? s_scan[t - d] : 0;
         __syncthreads();
-        s_scan[t] += add;
+        if (t < 256) s_scan[t] += add;
         __syncthreads();
     }
-    s_count[t] = s_scan[t] - v;
+    if (t < 256) s_count[t] = s_scan[t] - v;
     __syncthreads();
     // the first four child ids of every record, again all loads of the thread side by side (a child position the
     // node does not have reads the node's first position, or, for a leaf, whatever stands at its CSR start, which
     // lies inside the array: child_ptr <= E < N; the value is replaced by -1)
-    int kid[kRecPerThread][4];
+    // (in two halves: eight records' ids are in flight at a time, which keeps the large-window form in its registers)
 #pragma unroll
-    for (int i = 0; i < kRecPerThread; ++i)
+    for (int half = 0; half < 2; ++half) {
+        constexpr int HB = kRecPerThread / 2;
+        int kid[HB][4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) kid[i][j] = child_idx[cb[i] + (j < ar[i] ? j : 0)];
+        for (int i = 0; i < HB; ++i)
 #pragma unroll
-    for (int i = 0; i < kRecPerThread; ++i) {
-        if (node[i] < 0) continue;
-        const int64_t q = sorted ? (int64_t)w0 + atomicAdd(&s_count[key[i]], 1) : (int64_t)w0 + i * kThreads + t;
-        row_rec[2 * q] = make_int4(node[i], ar[i], cb[i], 0);
-        row_rec[2 * q + 1] = make_int4(0 < ar[i] ? kid[i][0] : -1, 1 < ar[i] ? kid[i][1] : -1,
-                                       2 < ar[i] ? kid[i][2] : -1, 3 < ar[i] ? kid[i][3] : -1);
+            for (int j = 0; j < 4; ++j) kid[i][j] = child_idx[cb[half * HB + i] + (j < ar[half * HB + i] ? j : 0)];
+#pragma unroll
+        for (int k = 0; k < HB; ++k) {
+            const int i = half * HB + k;
+            if (node[i] < 0) continue;
+            const int64_t q = sorted ? (int64_t)w0 + atomicAdd(&s_count[key[i]], 1) : (int64_t)w0 + i * NT + t;
+            row_rec[2 * q] = make_int4(node[i], ar[i], cb[i], 0);
+            row_rec[2 * q + 1] = make_int4(0 < ar[i] ? kid[k][0] : -1, 1 < ar[i] ? kid[k][1] : -1,
+                                           2 < ar[i] ? kid[k][2] : -1, 3 < ar[i] ? kid[k][3] : -1);
+        }
     }
 }
 
@@ -191,11 +206,19 @@ prepare_kernel(const int32_t *__restrict__ perm, const int32_t *__restrict__ key
                const int32_t *__restrict__ child_ptr, const int32_t *__restrict__ child_idx,
                int4 *__restrict__ row_rec, int n, int n_windows, const PackArgs p) {
     if ((int)blockIdx.x < n_windows)
-        row_record_body(perm, key, child_ptr, child_idx, row_rec, n, blockIdx.x);
+        row_record_body<kThreads>(perm, key, child_ptr, child_idx, row_rec, n, blockIdx.x);
     else
         pack_weights_body<T>(static_cast<const T *>(p.W), static_cast<const T *>(p.U), p.b, p.D, p.H, p.Dp, p.Hp,
                              p.NP, p.NPU, static_cast<T *>(p.Bp), p.bp, static_cast<T *>(p.Bf),
                              (int64_t)blockIdx.x - n_windows, (int64_t)gridDim.x - n_windows);
+}
+
+// The row records alone, in windows of kRecWindowLarge positions (large forests; prepare_kernel then only packs).
+__global__ void __launch_bounds__(kRecThreadsLarge)
+row_records_large_kernel(const int32_t *__restrict__ perm, const int32_t *__restrict__ key,
+                         const int32_t *__restrict__ child_ptr, const int32_t *__restrict__ child_idx,
+                         int4 *__restrict__ row_rec, int n) {
+    row_record_body<kRecThreadsLarge>(perm, key, child_ptr, child_idx, row_rec, n, blockIdx.x);
 }
 
 // ---- stack -------------------------------------------------------------------------
@@ -1541,12 +1564,20 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
             p.Bf = t == 0 ? w.Bf : nullptr;
             return p;
         };
-        const int n_windows = (int)ceil_div(s->n_nodes, kRecWindow);
-        {
+        const bool large = s->n_nodes >= kRecLargeMinNodes;
+        const int n_windows = large ? 0 : (int)ceil_div(s->n_nodes, kRecWindow);
+        const unsigned prep_grid = (unsigned)n_windows + ((packed || is_nary(0)) ? 0u : pack_grid);
+        if (prep_grid > 0) {
             ScopedLaunchTimer tm(JITDB_K_PACK, 0, st);
-            prepare_kernel<T><<<(unsigned)n_windows + ((packed || is_nary(0)) ? 0u : pack_grid), kThreads, 0, st>>>(
+            prepare_kernel<T><<<prep_grid, kThreads, 0, st>>>(
                 s->perm, slots ? slots->key : s->height, s->child_ptr, s->child_idx, w.row_rec, (int)s->n_nodes,
                 n_windows, pack_args(0));
+            JITDB_LAUNCH_CHECK();
+        }
+        if (large) {
+            ScopedLaunchTimer tm(JITDB_K_PACK, 0, st);
+            row_records_large_kernel<<<(unsigned)ceil_div(s->n_nodes, kRecWindowLarge), kRecThreadsLarge, 0, st>>>(
+                s->perm, slots ? slots->key : s->height, s->child_ptr, s->child_idx, w.row_rec, (int)s->n_nodes);
             JITDB_LAUNCH_CHECK();
         }
         for (int t = 1; t < n_sig && !packed; ++t) {
