@@ -58,15 +58,15 @@ struct PackArgs {
     void *Bf;       // the same rows fragment-major for the 256 x 256 tile kernel (bf16, one cell), or null
 };
 
-// block `block` of `n_blocks` (kThreads threads each, stride loop)
-template <typename T>
+// block `block` of `n_blocks` (NT threads each, stride loop)
+template <typename T, int NT = kThreads>
 __device__ __forceinline__ void pack_weights_body(const T *__restrict__ W, const T *__restrict__ U,
                                                   const float *__restrict__ b, int D, int H, int Dp, int Hp,
                                                   int NP, int NPU, T *__restrict__ Bp, float *__restrict__ bp,
                                                   T *__restrict__ Bf, int64_t block, int64_t n_blocks) {
     const int Kp = Dp + Hp;
     const int64_t total = (int64_t)NPU * Kp;
-    for (int64_t idx = block * kThreads + threadIdx.x; idx < total; idx += n_blocks * kThreads) {
+    for (int64_t idx = block * NT + threadIdx.x; idx < total; idx += n_blocks * NT) {
         const int r = (int)(idx / Kp), k = (int)(idx % Kp);
         const int tile = r / kGateTile, gate = (r % kGateTile) / kUnit, uu = r % kUnit;
         const int unit = tile * kUnit + uu;
@@ -213,12 +213,19 @@ prepare_kernel(const int32_t *__restrict__ perm, const int32_t *__restrict__ key
                              (int64_t)blockIdx.x - n_windows, (int64_t)gridDim.x - n_windows);
 }
 
-// The row records alone, in windows of kRecWindowLarge positions (large forests; prepare_kernel then only packs).
+// The same launch for large forests: row records in windows of kRecWindowLarge positions, blocks of 1024 threads.
+template <typename T>
 __global__ void __launch_bounds__(kRecThreadsLarge)
-row_records_large_kernel(const int32_t *__restrict__ perm, const int32_t *__restrict__ key,
-                         const int32_t *__restrict__ child_ptr, const int32_t *__restrict__ child_idx,
-                         int4 *__restrict__ row_rec, int n) {
-    row_record_body<kRecThreadsLarge>(perm, key, child_ptr, child_idx, row_rec, n, blockIdx.x);
+prepare_large_kernel(const int32_t *__restrict__ perm, const int32_t *__restrict__ key,
+                     const int32_t *__restrict__ child_ptr, const int32_t *__restrict__ child_idx,
+                     int4 *__restrict__ row_rec, int n, int n_windows, const PackArgs p) {
+    if ((int)blockIdx.x < n_windows)
+        row_record_body<kRecThreadsLarge>(perm, key, child_ptr, child_idx, row_rec, n, blockIdx.x);
+    else
+        pack_weights_body<T, kRecThreadsLarge>(static_cast<const T *>(p.W), static_cast<const T *>(p.U), p.b, p.D, p.H,
+                                               p.Dp, p.Hp, p.NP, p.NPU, static_cast<T *>(p.Bp), p.bp,
+                                               static_cast<T *>(p.Bf), (int64_t)blockIdx.x - n_windows,
+                                               (int64_t)gridDim.x - n_windows);
 }
 
 // ---- stack -------------------------------------------------------------------------
@@ -1565,19 +1572,21 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
             return p;
         };
         const bool large = s->n_nodes >= kRecLargeMinNodes;
-        const int n_windows = large ? 0 : (int)ceil_div(s->n_nodes, kRecWindow);
-        const unsigned prep_grid = (unsigned)n_windows + ((packed || is_nary(0)) ? 0u : pack_grid);
-        if (prep_grid > 0) {
+        {
             ScopedLaunchTimer tm(JITDB_K_PACK, 0, st);
-            prepare_kernel<T><<<prep_grid, kThreads, 0, st>>>(
-                s->perm, slots ? slots->key : s->height, s->child_ptr, s->child_idx, w.row_rec, (int)s->n_nodes,
-                n_windows, pack_args(0));
-            JITDB_LAUNCH_CHECK();
-        }
-        if (large) {
-            ScopedLaunchTimer tm(JITDB_K_PACK, 0, st);
-            row_records_large_kernel<<<(unsigned)ceil_div(s->n_nodes, kRecWindowLarge), kRecThreadsLarge, 0, st>>>(
-                s->perm, slots ? slots->key : s->height, s->child_ptr, s->child_idx, w.row_rec, (int)s->n_nodes);
+            const bool pack_here = !(packed || is_nary(0));
+            if (large) {
+                const int n_windows = (int)ceil_div(s->n_nodes, kRecWindowLarge);
+                const unsigned pg = pack_here ? (unsigned)(ceil_div(total, kRecThreadsLarge) < 1024 ? ceil_div(total, kRecThreadsLarge) : 1024) : 0u;
+                prepare_large_kernel<T><<<(unsigned)n_windows + pg, kRecThreadsLarge, 0, st>>>(
+                    s->perm, slots ? slots->key : s->height, s->child_ptr, s->child_idx, w.row_rec, (int)s->n_nodes,
+                    n_windows, pack_args(0));
+            } else {
+                const int n_windows = (int)ceil_div(s->n_nodes, kRecWindow);
+                prepare_kernel<T><<<(unsigned)n_windows + (pack_here ? pack_grid : 0u), kThreads, 0, st>>>(
+                    s->perm, slots ? slots->key : s->height, s->child_ptr, s->child_idx, w.row_rec, (int)s->n_nodes,
+                    n_windows, pack_args(0));
+            }
             JITDB_LAUNCH_CHECK();
         }
         for (int t = 1; t < n_sig && !packed; ++t) {
