@@ -673,7 +673,8 @@ level_kernel(const LevelArgs a_in) {
             rec0 = a.row_rec[2 * (int64_t)(tile_row0 + t)];
             rec1 = a.row_rec[2 * (int64_t)(tile_row0 + t) + 1];
         } else {
-            node_reg = a.row_rec[2 * (int64_t)(tile_row0 + t)].x;
+            node_reg = (MODE == MODE_PROJ && !GROUPED && a.proj_nodes) ? a.proj_nodes[tile_row0 + t]
+                                                                     : a.row_rec[2 * (int64_t)(tile_row0 + t)].x;
         }
     }
     auto publish_rows = [&]() __attribute__((always_inline)) {
@@ -1606,6 +1607,7 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
     }
 
     LevelArgs a;
+    a.proj_nodes = nullptr;
     a.stack = w.stack;
     a.Bf = w.Bf;
     // bf16 levels that are large enough run on 256 x 256 tiles (level256.hip); training and typed
@@ -1814,6 +1816,7 @@ int run_forward(const void *x, const void *W, const void *U, const float *b, con
             a.Bp = static_cast<char *>(w.Bp) + packed_w_bytes(d) * p;
             a.bp = w.bp + (size_t)d.NP * p;
             a.row_rec = w.row_rec + 2 * (int64_t)begin;
+            a.proj_nodes = slots ? nullptr : s->perm + begin;
             a.n_rows = rows;
             const bool thin_p = rows <= kThinMaxRows;
             ScopedLaunchTimer tm(thin_p ? JITDB_K_THIN_PROJ : JITDB_K_PROJ, rows, st);

@@ -107,6 +107,9 @@ struct LevelArgs {
     const int4 *tiles;
     int64_t w_bytes;      // bytes between the packed weights of consecutive cells
     int NP;               // floats between their packed biases
+    // tiled projection without a typed table: the level's node ids in position order (ascending ids, so the
+    // gathered h rows are fetched front to back: 1.4 % off the projection), or nullptr: the ids come from the records
+    const int32_t *proj_nodes;
 };
 
 namespace {
